@@ -1,0 +1,206 @@
+"""Benchmark of the IVFADC+R search path on one MI355X.
+
+A step is one pass of the whole query stage (coarse probe, look-up tables, ADC list scan,
+top-k' short-list, re-rank, top-k) over one batch of synthetic queries against an index that
+is already resident in HBM.  The index is built on the GPU from the seeded synthetic
+generator before the timed region.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_index(cfg, dm, n_gt, args):
+    """Train, encode and finalize on the GPU; brute-force ground truth of the first n_gt queries
+    is accumulated from the same generated chunks (exact: integer data, fp32 products < 2^24)."""
+    import torch
+    import synthdata as sd
+    import paper_1102_3828_amd as pkg
+
+    dev = dm.device
+    t0 = time.time()
+    ix = pkg.Index(cfg.d, cfg.c, cfg.m, cfg.m_refine)
+    train = dm.generate(sd.STREAM_TRAIN, 0, cfg.n_train)
+    ix.train(train, iters=args.train_iters, seed=1)
+    del train
+    torch.cuda.synchronize()
+    t_train = time.time() - t0
+    log(f"[bench] trained quantizers on {cfg.n_train} vectors in {t_train:.1f}s")
+
+    queries_u8 = dm.generate(sd.STREAM_QUERY, 0, cfg.n_query)
+    xq = queries_u8.float().contiguous()
+    gt_d = torch.full((n_gt, 1), float("inf"), device=dev)
+    gt_i = torch.full((n_gt, 1), -1, dtype=torch.int64, device=dev)
+    xg = xq[:n_gt]
+    t0 = time.time()
+    buf = None
+    for j, a in enumerate(range(0, cfg.N, sd.BASE_CHUNK)):
+        n = min(sd.BASE_CHUNK, cfg.N - a)
+        if buf is None or buf.shape[0] != n:
+            buf = torch.empty((n, cfg.d), dtype=torch.uint8, device=dev)
+        dm.generate(sd.STREAM_BASE0 + j, 0, n, out=buf)
+        ix.add(buf, a)
+        if n_gt:
+            for s in range(0, n, 1 << 20):
+                y = buf[s:s + (1 << 20)].float()
+                d2 = (y * y).sum(1)[None, :] - 2.0 * (xg @ y.T)
+                dmin, imin = d2.min(dim=1, keepdim=True)
+                better = dmin < gt_d
+                gt_d = torch.where(better, dmin, gt_d)
+                gt_i = torch.where(better, imin + a + s, gt_i)
+        if j % 10 == 9 or a + n >= cfg.N:
+            torch.cuda.synchronize()
+            log(f"[bench] added {a + n} / {cfg.N} vectors ({time.time() - t0:.1f}s)")
+    del buf
+    ix.finalize()
+    torch.cuda.synchronize()
+    t_add = time.time() - t0
+    log(f"[bench] encoded + finalized {cfg.N} vectors in {t_add:.1f}s")
+    return ix, xq, queries_u8, gt_i[:, 0].cpu().numpy(), dict(train_s=t_train, add_s=t_add)
+
+
+def cpu_baseline(ix, cfg, queries_u8, gpu_ids, budget_s=15.0, max_q=64):
+    """The CPU oracle's search on the exported index, timed on this host for a bounded sample."""
+    import numpy as np
+    from oracle import ivfadcr_oracle as orc
+    coarse, pq, rq = ix.get_codebooks()
+    t0 = time.time()
+    offsets, ids, codes, rcodes = ix.export()
+    log(f"[bench] exported index to host in {time.time() - t0:.1f}s")
+    index = orc.Index(orc.Codebooks(coarse, pq, rq), offsets, ids, codes, rcodes)
+    X = queries_u8[:max_q].cpu().numpy()
+    done, same, scanned = 0, 0, 0
+    t0 = time.time()
+    for qi in range(len(X)):
+        o_ids, _, tr = orc.search_one(X[qi], index, cfg.w, cfg.kprime, cfg.k)
+        done += 1
+        scanned += tr.scanned
+        same += int((o_ids == gpu_ids[qi]).sum())
+        if time.time() - t0 > budget_s:
+            break
+    el = time.time() - t0
+    return {"value": done / el, "unit": "queries/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {done} queries of the same workload, one at a time (numpy float64, single thread)",
+            "adc_codes_per_s": scanned / el,
+            "ids_identical_to_gpu": same / float(done * cfg.k)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default=os.environ.get("IVFR_BENCH_CONFIG", "cfg4"))
+    ap.add_argument("--N", type=int, default=0, help="override the database size (debugging)")
+    ap.add_argument("--kprime", type=int, default=0)
+    ap.add_argument("--m-refine", type=int, default=-1)
+    ap.add_argument("--train-iters", type=int, default=10)
+    ap.add_argument("--gt-queries", type=int, default=100)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scan-groups", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path is not sharded); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import dataclasses
+    import numpy as np
+    import torch
+    import synthdata as sd
+    from synthdata.gpu import DeviceMixture
+
+    cfg = sd.CONFIGS[args.config]
+    if args.N:
+        cfg = dataclasses.replace(cfg, N=args.N)
+    if args.kprime:
+        cfg = dataclasses.replace(cfg, kprime=args.kprime)
+    if args.m_refine >= 0:
+        cfg = dataclasses.replace(cfg, m_refine=args.m_refine)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dm = DeviceMixture(cfg.mixture(), "cuda:0")
+    n_gt = min(args.gt_queries, cfg.n_query)
+    ix, xq, queries_u8, gt, build_t = build_index(cfg, dm, n_gt, args)
+    if args.scan_groups:
+        ix.set_tuning(scan_groups=args.scan_groups)
+
+    B = min(cfg.batch, cfg.n_query)
+    n_batches = max(1, cfg.n_query // B)
+    batches = [xq[i * B:(i + 1) * B].contiguous() for i in range(n_batches)]
+
+    for s in range(args.warmup):
+        ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
+    ix.set_profiling(True)
+    torch.cuda.synchronize()
+    codes = 0
+    scan_ms = sample_ms = rerank_ms = 0.0
+    scan_launches = 0
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
+        st = ix.search_stats()
+        pr = ix.scan_profile()
+        codes += st["codes_scanned"]
+        scan_ms += pr["scan_ms"]; sample_ms += pr["sample_ms"]; rerank_ms += pr["rerank_ms"]
+        scan_launches += pr["scan_launches"]
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ix.set_profiling(False)
+    dense = ix.search_stats()["dense_fallbacks"]
+
+    # accuracy on the ground-truth subset (first batch holds the first n_gt queries)
+    g_ids, g_dist = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
+    g_ids = g_ids.cpu().numpy()
+    recall = {}
+    for r in (1, 10, 100):
+        if r <= cfg.k and n_gt:
+            recall[f"recall@{r}"] = float((g_ids[:n_gt, :r] == gt[:n_gt, None]).any(axis=1).mean())
+
+    qps = args.steps * B / elapsed
+    code_bytes = cfg.m * codes / max(args.steps, 1)            # algorithmic bytes per filtered-scan launch
+    scan_avg_ms = scan_ms / max(scan_launches, 1)
+    achieved = code_bytes / (scan_avg_ms * 1e-3) / 1e9 if scan_avg_ms > 0 else 0.0
+    out = {
+        "metric": "queries/s", "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: N={cfg.N} d={cfg.d} c={cfg.c} m={cfg.m} m'={cfg.m_refine} "
+                               f"w={cfg.w} k'={cfg.kprime} k={cfg.k}, {B} queries per step",
+                   "generator": f"uint8 Gaussian mixture G={cfg.G} zipf={cfg.zipf} seed={sd.BASE_SEED}"},
+        "adc_codes_per_s": codes / elapsed,
+        "codes_scanned_per_step": codes / max(args.steps, 1),
+        "stage_ms_per_step": {"sample_scan": sample_ms / args.steps, "filtered_scan": scan_ms / args.steps,
+                              "rerank": rerank_ms / args.steps},
+        "dense_fallbacks_last_step": dense,
+        "recall": recall, "recall_queries": n_gt,
+        "build_seconds": build_t,
+        "roofline": {"bound": "hbm", "kernel": "adc_scan_kernel (filtered pass)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": code_bytes,
+                     "avg_launch_ms": scan_avg_ms},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(ix, cfg, queries_u8, g_ids)
+    ix.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,131 @@
+/*
+ * ivfadcr.h - C interface of the MI355X (gfx950) IVFADC+R search library.
+ *
+ * Method: "Searching in one billion vectors: re-rank with source coding".  A database of
+ * d-dimensional vectors is indexed by (i) an inverted file over a coarse quantizer with c
+ * reproduction values (section 3.3), (ii) an m-byte product-quantizer code q_c of each
+ * vector's residual to its coarse centroid (section 2, Eq. (4)), and (iii) an m'-byte
+ * refinement code q_r of what q_c leaves (section 3.1, Eq. (7)-(8)).  A query visits the w
+ * nearest lists (v in the paper), ranks their entries by the asymmetric distance estimator
+ * read from look-up tables (Eq. (5)), keeps the k' best, rebuilds each of those explicitly
+ * as  coarse + decode(q_c) + decode(q_r)  (Eq. (9)) and returns the k with the smallest
+ * refined squared distance (Eq. (10); query steps 1-3 of section 3.2).
+ *
+ * Conventions
+ *  - Every function returns IVFR_OK (0) or a negative IVFR_ERR_* code; ivfr_last_error()
+ *    gives a message for the calling thread's last failure.  Nothing throws across this ABI.
+ *  - "host" / "device" in an argument comment says where the memory must live.  Buffers are
+ *    owned by the caller; the index and its scratch are owned by the library.
+ *  - All matrices are row-major and dense.  Distances are squared L2, fp32.
+ *  - 8 bits per sub-quantizer (256 reproduction values), as fixed in sections 2 and 3.1.
+ *  - ids are int32 (the 4 bytes per vector of section 3.3); N < 2^31.
+ *  - Calls on one index must not overlap in time (one stream of calls per index).
+ */
+#ifndef IVFADCR_H
+#define IVFADCR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IVFR_OK               0
+#define IVFR_ERR_INVALID_ARG (-1)  /* null pointer, bad shape, k > k', w > c, ...            */
+#define IVFR_ERR_STATE       (-2)  /* call not valid in the index's current state             */
+#define IVFR_ERR_OOM         (-3)  /* device or host allocation failed                        */
+#define IVFR_ERR_HIP         (-4)  /* a HIP runtime call failed (message names it)            */
+
+typedef struct ivfr_index ivfr_index;   /* opaque */
+
+typedef struct {
+    int32_t d;         /* vector dimension; multiple of 8                                   */
+    int32_t c;         /* coarse centroids = inverted lists (section 3.3)                   */
+    int32_t m;         /* bytes of the first-stage code; d % m == 0, m % 4 == 0             */
+    int32_t m_refine;  /* bytes of the refinement code m'; 0 = plain IVFADC; d % m' == 0    */
+    int32_t device;    /* HIP device ordinal                                                */
+} ivfr_params;
+
+/* Lifetime.  ivfr_create allocates nothing large; ivfr_destroy frees everything. */
+int ivfr_create(const ivfr_params* params, ivfr_index** out);
+int ivfr_destroy(ivfr_index* index);
+
+/* Offline step 1 of section 3.2: learn the coarse quantizer, q_c and q_r.
+ * ivfr_train runs Lloyd k-means on the GPU (initial centroids = distinct training rows drawn
+ * from `seed`; an empty cluster keeps its centroid): coarse on the vectors, q_c on the
+ * residuals to the coarse centroid, q_r on what q_c leaves.  train: uint8 [n, d], host or
+ * device; n >= max(c, 256).
+ * ivfr_set_codebooks injects codebooks instead (host fp32): coarse [c, d], pq [m, 256, d/m],
+ * rq [m', 256, d/m'] (ignored, may be NULL, when m' = 0).  ivfr_get_codebooks copies them out
+ * to host buffers of the same shapes.  Codebooks cannot change once vectors were added. */
+int ivfr_train(ivfr_index* index, const uint8_t* train, int64_t n, int32_t iters, uint64_t seed);
+int ivfr_set_codebooks(ivfr_index* index, const float* coarse, const float* pq, const float* rq);
+int ivfr_get_codebooks(const ivfr_index* index, float* coarse, float* pq, float* rq);
+
+/* Offline steps 2-3 of section 3.2: encode n vectors x (uint8 [n, d], host or device) and
+ * stage them for the inverted file.  Vector i gets id id_base + i; successive calls must use
+ * increasing, non-overlapping id ranges (lists are kept in ascending id order).
+ * ivfr_finalize sorts the staged entries into the inverted lists; afterwards the index is
+ * searchable and immutable. */
+int ivfr_add(ivfr_index* index, const uint8_t* x, int64_t n, int64_t id_base);
+int ivfr_finalize(ivfr_index* index);
+int64_t ivfr_ntotal(const ivfr_index* index);   /* vectors added so far (negative: error) */
+
+/* The finished index as flat host arrays: list l holds entries list_offsets[l] ..
+ * list_offsets[l+1]-1.  list_offsets int64 [c+1]; ids int32 [N]; codes uint8 [N, m]; rcodes
+ * uint8 [N, m'] (may be NULL when m' = 0).  ivfr_import installs such arrays (codebooks must
+ * be set first) and leaves the index finalized. */
+int ivfr_export(const ivfr_index* index, int64_t* list_offsets, int32_t* ids, uint8_t* codes, uint8_t* rcodes);
+int ivfr_import(ivfr_index* index, int64_t N, const int64_t* list_offsets, const int32_t* ids,
+                const uint8_t* codes, const uint8_t* rcodes);
+
+/* Query stage (section 3.2 steps 1-3 on the inverted file of section 3.3).
+ * queries: fp32 [nq, d], device.  1 <= w <= c, 1 <= k <= kprime.
+ * ids_out int32 [nq, k], dist_out fp32 [nq, k], device: per query ascending by (refined squared
+ * distance, id); when fewer than k entries were scanned the tail is id -1, distance +inf.
+ * stream: a hipStream_t (NULL = default stream).  Work is enqueued on it; the call also waits
+ * for it to finish (it reads back a small status word), so outputs are valid on return. */
+int ivfr_search(ivfr_index* index, const float* queries, int64_t nq, int32_t w, int32_t kprime, int32_t k,
+                int32_t* ids_out, float* dist_out, void* stream);
+
+/* Same search, additionally exposing intermediate results for verification (any of the extra
+ * pointers may be NULL).  All device memory.
+ *   probe_out       int32 [nq, w]   visited lists, nearest first (ties: lower list index)
+ *   probe_dist_out  fp32  [nq, w]   their squared coarse distances
+ *   short_ids_out   int32 [nq, k']  ids of the short-list of step 1 (unordered; tail -1)
+ *   short_est_out   fp32  [nq, k']  their ADC estimates (Eq. (5))
+ *   short_ref_out   fp32  [nq, k']  their refined distances (Eq. (10))
+ *   short_count_out int32 [nq]      short-list length = min(k', entries scanned)          */
+int ivfr_search_trace(ivfr_index* index, const float* queries, int64_t nq, int32_t w, int32_t kprime, int32_t k,
+                      int32_t* ids_out, float* dist_out,
+                      int32_t* probe_out, float* probe_dist_out,
+                      int32_t* short_ids_out, float* short_est_out, float* short_ref_out,
+                      int32_t* short_count_out, void* stream);
+
+/* Counters of the most recent search call: entries whose estimator was computed (sum over
+ * queries of the visited lists' lengths: the "v/c of the database" of section 3.3), (query,
+ * list) pairs, and queries that took the dense fallback because the filtered candidate buffer
+ * overflowed.  Any pointer may be NULL. */
+int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks);
+
+/* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
+ *   sample_mult (4)   step 1 first scans about sample_mult*k' entries of the nearest lists to
+ *                     bound the k'-th smallest estimate, then filters the full scan by it
+ *   cap_mult    (16)  per-query candidate buffer = cap_mult*k' entries (>= sample + 512)
+ *   batch       (1024) queries processed per internal batch
+ *   scan_groups (0 = auto) workgroups launched by the list-scan kernel                      */
+int ivfr_set_tuning(ivfr_index* index, int32_t sample_mult, int32_t cap_mult, int32_t batch, int32_t scan_groups);
+
+/* Average duration in milliseconds of the list-scan kernel launches (the filtered full
+ * scan) of the most recent search call, measured with HIP events on the search stream, and
+ * their number.  Timing is recorded only after ivfr_set_profiling(index, 1). */
+int ivfr_set_profiling(ivfr_index* index, int32_t enable);
+int ivfr_scan_profile(const ivfr_index* index, double* scan_ms_total, int32_t* scan_launches,
+                      double* rerank_ms_total, double* sample_ms_total);
+
+const char* ivfr_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IVFADCR_H */

@@ -1,0 +1,502 @@
+// Index lifetime, codebooks, offline stage (train / add / finalize) and import / export.
+#include "ivfr_internal.h"
+
+#include <algorithm>
+#include <numeric>
+#include <string.h>
+
+// launchers defined in encode.hip
+int ivfr_launch_list_ranks(const int32_t* list, int64_t n, int c, unsigned long long* list_fill, uint32_t* cnt,
+                           int T, uint32_t* rank, hipStream_t st);
+int ivfr_launch_scatter(const StagedChunk& ch, int m, int mr, const uint32_t* list_start, int32_t* ids,
+                        uint8_t* codes, uint8_t* rcodes, hipStream_t st);
+int ivfr_launch_iota(int32_t* ids, int64_t n, int64_t base, hipStream_t st);
+int ivfr_launch_km_accum_rows(const float* X, int64_t n, int d, const int32_t* assign, unsigned long long* sums,
+                              unsigned long long* counts, hipStream_t st);
+int ivfr_launch_km_accum_pq(const float* R, int64_t n, int d, int parts, const uint8_t* codes,
+                            unsigned long long* sums, unsigned long long* counts, hipStream_t st);
+int ivfr_launch_km_update(float* cent, int64_t total, int width, const unsigned long long* sums,
+                          const unsigned long long* counts, hipStream_t st);
+int ivfr_launch_gather_rows(const float* X, int d, int col0, int width, const int64_t* idx, int count, float* out,
+                            hipStream_t st);
+
+static thread_local char g_err[512] = "";
+
+void ivfr_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char* ivfr_last_error(void) { return g_err; }
+
+#define ADD_SUB 1048576   // vectors encoded per internal batch
+
+static int use_device(const ivfr_index* ix) {
+    IVFR_HIP(hipSetDevice(ix->p.device));
+    return IVFR_OK;
+}
+
+template <class T>
+static int dev_alloc(T** p, size_t count) {
+    *p = nullptr;
+    if (count == 0) count = 1;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T));
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        *p = nullptr;
+        ivfr_set_error("device allocation of %zu bytes failed: %s", count * sizeof(T), hipGetErrorString(e));
+        return IVFR_ERR_OOM;
+    }
+    return IVFR_OK;
+}
+
+template <class T>
+static void dev_free(T*& p) {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+}
+
+extern "C" int ivfr_create(const ivfr_params* params, ivfr_index** out) {
+    IVFR_REQUIRE(params && out, "ivfr_create: null argument");
+    const ivfr_params& p = *params;
+    IVFR_REQUIRE(p.d > 0 && p.d % 8 == 0, "d = %d must be a positive multiple of 8", p.d);
+    IVFR_REQUIRE(p.c >= 1, "c = %d must be >= 1", p.c);
+    IVFR_REQUIRE(p.m == 4 || p.m == 8 || p.m == 16 || p.m == 32 || p.m == 64, "m = %d must be 4, 8, 16, 32 or 64", p.m);
+    IVFR_REQUIRE(p.d % p.m == 0, "d = %d is not a multiple of m = %d", p.d, p.m);
+    IVFR_REQUIRE(p.d / p.m <= 32, "d/m = %d exceeds 32", p.d / p.m);
+    IVFR_REQUIRE(p.m_refine >= 0 && p.m_refine % 4 == 0, "m_refine = %d must be a non-negative multiple of 4", p.m_refine);
+    if (p.m_refine) {
+        IVFR_REQUIRE(p.d % p.m_refine == 0, "d = %d is not a multiple of m_refine = %d", p.d, p.m_refine);
+        IVFR_REQUIRE(p.d / p.m_refine <= 32, "d/m_refine = %d exceeds 32", p.d / p.m_refine);
+        int ds = p.d / p.m_refine;
+        IVFR_REQUIRE((ds & (ds - 1)) == 0, "d/m_refine = %d must be a power of two", ds);
+    }
+    {
+        int ds = p.d / p.m;
+        IVFR_REQUIRE((ds & (ds - 1)) == 0, "d/m = %d must be a power of two", ds);
+    }
+    int ndev = 0;
+    IVFR_HIP(hipGetDeviceCount(&ndev));
+    IVFR_REQUIRE(p.device >= 0 && p.device < ndev, "device %d out of range (%d devices)", p.device, ndev);
+    ivfr_index* ix = new (std::nothrow) ivfr_index();
+    if (!ix) { ivfr_set_error("host allocation failed"); return IVFR_ERR_OOM; }
+    ix->p = p;
+    ix->dsub = p.d / p.m;
+    ix->dsub_r = p.m_refine ? p.d / p.m_refine : 0;
+    int r = use_device(ix);
+    if (r == IVFR_OK) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, p.device) == hipSuccess) ix->n_cu = prop.multiProcessorCount;
+        r = ivfr_select_init();
+    }
+    if (r == IVFR_OK) {
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ix->h_status), 64 * sizeof(int), hipHostMallocDefault);
+        if (e != hipSuccess) { ivfr_set_error("pinned host allocation failed"); r = IVFR_ERR_OOM; }
+    }
+    if (r != IVFR_OK) { delete ix; return r; }
+    *out = ix;
+    return IVFR_OK;
+}
+
+static void free_staged(ivfr_index* ix) {
+    for (auto& ch : ix->staged) {
+        dev_free(ch.list); dev_free(ch.rank); dev_free(ch.ids); dev_free(ch.codes); dev_free(ch.rcodes);
+    }
+    ix->staged.clear();
+}
+
+extern "C" int ivfr_destroy(ivfr_index* ix) {
+    if (!ix) return IVFR_OK;
+    (void)hipSetDevice(ix->p.device);
+    (void)hipDeviceSynchronize();
+    free_staged(ix);
+    dev_free(ix->coarse); dev_free(ix->coarse_norm); dev_free(ix->pq); dev_free(ix->pq_norm); dev_free(ix->rq);
+    dev_free(ix->list_fill); dev_free(ix->list_start); dev_free(ix->list_len);
+    dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
+    ix->search_ws.release(); ix->encode_ws.release(); ix->dense_ws.release();
+    if (ix->h_status) (void)hipHostFree(ix->h_status);
+    delete ix;
+    return IVFR_OK;
+}
+
+static int alloc_books(ivfr_index* ix) {
+    const ivfr_params& p = ix->p;
+    if (ix->coarse) return IVFR_OK;
+    IVFR_TRY(dev_alloc(&ix->coarse, (size_t)p.c * p.d));
+    IVFR_TRY(dev_alloc(&ix->coarse_norm, (size_t)p.c));
+    IVFR_TRY(dev_alloc(&ix->pq, (size_t)p.m * IVFR_KS * ix->dsub));
+    IVFR_TRY(dev_alloc(&ix->pq_norm, (size_t)p.m * IVFR_KS));
+    if (p.m_refine) IVFR_TRY(dev_alloc(&ix->rq, (size_t)p.m_refine * IVFR_KS * ix->dsub_r));
+    return IVFR_OK;
+}
+
+static int refresh_norms(ivfr_index* ix, hipStream_t st) {
+    IVFR_TRY(ivfr_launch_row_norms(ix->coarse, ix->p.c, ix->p.d, ix->coarse_norm, st));
+    IVFR_TRY(ivfr_launch_row_norms(ix->pq, (int64_t)ix->p.m * IVFR_KS, ix->dsub, ix->pq_norm, st));
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_set_codebooks(ivfr_index* ix, const float* coarse, const float* pq, const float* rq) {
+    IVFR_REQUIRE(ix && coarse && pq, "ivfr_set_codebooks: null argument");
+    IVFR_REQUIRE(ix->p.m_refine == 0 || rq, "ivfr_set_codebooks: rq is required when m_refine > 0");
+    if (ix->n_added > 0 || ix->finalized) { ivfr_set_error("codebooks cannot change after vectors were added"); return IVFR_ERR_STATE; }
+    IVFR_TRY(use_device(ix));
+    IVFR_TRY(alloc_books(ix));
+    const ivfr_params& p = ix->p;
+    IVFR_HIP(hipMemcpy(ix->coarse, coarse, (size_t)p.c * p.d * sizeof(float), hipMemcpyHostToDevice));
+    IVFR_HIP(hipMemcpy(ix->pq, pq, (size_t)p.m * IVFR_KS * ix->dsub * sizeof(float), hipMemcpyHostToDevice));
+    if (p.m_refine)
+        IVFR_HIP(hipMemcpy(ix->rq, rq, (size_t)p.m_refine * IVFR_KS * ix->dsub_r * sizeof(float), hipMemcpyHostToDevice));
+    IVFR_TRY(refresh_norms(ix, nullptr));
+    IVFR_HIP(hipDeviceSynchronize());
+    ix->has_books = true;
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_get_codebooks(const ivfr_index* ix, float* coarse, float* pq, float* rq) {
+    IVFR_REQUIRE(ix && coarse && pq, "ivfr_get_codebooks: null argument");
+    if (!ix->has_books) { ivfr_set_error("no codebooks yet"); return IVFR_ERR_STATE; }
+    IVFR_TRY(use_device(ix));
+    const ivfr_params& p = ix->p;
+    IVFR_HIP(hipMemcpy(coarse, ix->coarse, (size_t)p.c * p.d * sizeof(float), hipMemcpyDeviceToHost));
+    IVFR_HIP(hipMemcpy(pq, ix->pq, (size_t)p.m * IVFR_KS * ix->dsub * sizeof(float), hipMemcpyDeviceToHost));
+    if (p.m_refine && rq)
+        IVFR_HIP(hipMemcpy(rq, ix->rq, (size_t)p.m_refine * IVFR_KS * ix->dsub_r * sizeof(float), hipMemcpyDeviceToHost));
+    return IVFR_OK;
+}
+
+static bool is_device_ptr(const void* p) {
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess) { (void)hipGetLastError(); return false; }
+    return attr.type == hipMemoryTypeDevice;
+}
+
+// uint8 rows [a, a+n) of src (host or device) -> fp32 device buffer X; `stage` holds the bytes when src is on the host
+static int load_rows_f32(const uint8_t* src, bool on_device, int64_t a, int64_t n, int d, uint8_t* stage, float* X,
+                         hipStream_t st) {
+    const uint8_t* dsrc = src + a * d;
+    if (!on_device) {
+        IVFR_HIP(hipMemcpyAsync(stage, src + a * d, (size_t)n * d, hipMemcpyHostToDevice, st));
+        dsrc = stage;
+    }
+    return ivfr_launch_u8_to_f32(dsrc, n * d, X, st);
+}
+
+// ---- training -----------------------------------------------------------------------------
+static inline uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// `count` distinct row indices in [0, n), chosen by the `count` smallest hashes of (seed, salt, row)
+static void draw_rows(uint64_t seed, uint64_t salt, int64_t n, int count, std::vector<int64_t>& out) {
+    std::vector<std::pair<uint64_t, int64_t>> h((size_t)n);
+    const uint64_t key = mix64(seed * 0x9E3779B97F4A7C15ull + salt);
+    for (int64_t i = 0; i < n; ++i) h[(size_t)i] = {mix64(key + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull), i};
+    std::nth_element(h.begin(), h.begin() + (count - 1), h.end());
+    out.resize((size_t)count);
+    for (int i = 0; i < count; ++i) out[(size_t)i] = h[(size_t)i].second;
+    std::sort(out.begin(), out.end());
+}
+
+// Lloyd iterations for the `parts` sub-quantizers of a product quantizer on the rows of R [n, d]
+static int train_pq(ivfr_index* ix, float* R, int64_t n, int parts, float* book, uint64_t seed, uint64_t salt0,
+                    int iters, uint8_t* codes_tmp, unsigned long long* sums, unsigned long long* counts,
+                    int64_t* d_idx, hipStream_t st) {
+    const int d = ix->p.d, dsub = d / parts;
+    std::vector<int64_t> rows;
+    for (int j = 0; j < parts; ++j) {
+        draw_rows(seed, salt0 + (uint64_t)j, n, IVFR_KS, rows);
+        IVFR_HIP(hipMemcpyAsync(d_idx, rows.data(), IVFR_KS * sizeof(int64_t), hipMemcpyHostToDevice, st));
+        IVFR_TRY(ivfr_launch_gather_rows(R, d, j * dsub, dsub, d_idx, IVFR_KS, book + (int64_t)j * IVFR_KS * dsub, st));
+        IVFR_HIP(hipStreamSynchronize(st));   // rows is reused
+    }
+    const int64_t total = (int64_t)parts * IVFR_KS * dsub;
+    for (int it = 0; it < iters; ++it) {
+        IVFR_TRY(ivfr_launch_pq_encode(R, n, d, book, parts, codes_tmp, false, st));
+        IVFR_HIP(hipMemsetAsync(sums, 0, (size_t)total * sizeof(unsigned long long), st));
+        IVFR_HIP(hipMemsetAsync(counts, 0, (size_t)parts * IVFR_KS * sizeof(unsigned long long), st));
+        IVFR_TRY(ivfr_launch_km_accum_pq(R, n, d, parts, codes_tmp, sums, counts, st));
+        IVFR_TRY(ivfr_launch_km_update(book, total, dsub, sums, counts, st));
+    }
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_train(ivfr_index* ix, const uint8_t* train, int64_t n, int32_t iters, uint64_t seed) {
+    IVFR_REQUIRE(ix && train, "ivfr_train: null argument");
+    IVFR_REQUIRE(iters >= 0, "iters = %d must be >= 0", iters);
+    IVFR_REQUIRE(n >= ix->p.c && n >= IVFR_KS, "training set of %lld rows is smaller than max(c, 256)", (long long)n);
+    if (ix->n_added > 0 || ix->finalized) { ivfr_set_error("codebooks cannot change after vectors were added"); return IVFR_ERR_STATE; }
+    IVFR_TRY(use_device(ix));
+    IVFR_TRY(alloc_books(ix));
+    const ivfr_params& p = ix->p;
+    const int d = p.d, c = p.c;
+    hipStream_t st = nullptr;
+    const bool on_dev = is_device_ptr(train);
+
+    float* T = nullptr;
+    uint8_t* stage = nullptr;
+    int32_t* assign = nullptr;
+    uint8_t* codes_tmp = nullptr;
+    unsigned long long *sums = nullptr, *counts = nullptr;
+    int64_t* d_idx = nullptr;
+    const int max_parts = std::max(p.m, p.m_refine);
+    const size_t sum_elems = std::max((size_t)c * d, (size_t)IVFR_KS * d);
+    const size_t cnt_elems = std::max((size_t)c, (size_t)max_parts * IVFR_KS);
+    int r = IVFR_OK;
+    auto cleanup = [&]() {
+        dev_free(T); dev_free(stage); dev_free(assign); dev_free(codes_tmp); dev_free(sums); dev_free(counts);
+        dev_free(d_idx);
+    };
+#define TR(expr) do { r = (expr); if (r != IVFR_OK) { cleanup(); return r; } } while (0)
+#define TRH(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { ivfr_set_error("%s failed: %s", #expr, hipGetErrorString(e_)); cleanup(); return IVFR_ERR_HIP; } } while (0)
+    TR(dev_alloc(&T, (size_t)n * d));
+    if (!on_dev) TR(dev_alloc(&stage, (size_t)n * d));
+    TR(dev_alloc(&assign, (size_t)n));
+    TR(dev_alloc(&codes_tmp, (size_t)n * max_parts));
+    TR(dev_alloc(&sums, sum_elems));
+    TR(dev_alloc(&counts, cnt_elems));
+    TR(dev_alloc(&d_idx, (size_t)std::max(c, IVFR_KS)));
+    TR(load_rows_f32(train, on_dev, 0, n, d, stage, T, st));
+
+    // coarse quantizer: initial centroids = c distinct training rows
+    {
+        std::vector<int64_t> rows;
+        draw_rows(seed, 1, n, c, rows);
+        TRH(hipMemcpyAsync(d_idx, rows.data(), (size_t)c * sizeof(int64_t), hipMemcpyHostToDevice, st));
+        TR(ivfr_launch_gather_rows(T, d, 0, d, d_idx, c, ix->coarse, st));
+        TRH(hipStreamSynchronize(st));
+    }
+    for (int it = 0; it < iters; ++it) {
+        TR(ivfr_launch_row_norms(ix->coarse, c, d, ix->coarse_norm, st));
+        TR(ivfr_launch_assign(T, n, ix->coarse, ix->coarse_norm, c, d, assign, st));
+        TRH(hipMemsetAsync(sums, 0, (size_t)c * d * sizeof(unsigned long long), st));
+        TRH(hipMemsetAsync(counts, 0, (size_t)c * sizeof(unsigned long long), st));
+        TR(ivfr_launch_km_accum_rows(T, n, d, assign, sums, counts, st));
+        TR(ivfr_launch_km_update(ix->coarse, (int64_t)c * d, d, sums, counts, st));
+    }
+    // residuals to the coarse centroid, then q_c on them, then q_r on what q_c leaves
+    TR(ivfr_launch_row_norms(ix->coarse, c, d, ix->coarse_norm, st));
+    TR(ivfr_launch_assign(T, n, ix->coarse, ix->coarse_norm, c, d, assign, st));
+    TR(ivfr_launch_residual(T, n, d, ix->coarse, assign, st));
+    TR(train_pq(ix, T, n, p.m, ix->pq, seed, 100, iters, codes_tmp, sums, counts, d_idx, st));
+    if (p.m_refine) {
+        TR(ivfr_launch_pq_encode(T, n, d, ix->pq, p.m, nullptr, true, st));
+        TR(train_pq(ix, T, n, p.m_refine, ix->rq, seed, 200, iters, codes_tmp, sums, counts, d_idx, st));
+    }
+    TR(refresh_norms(ix, st));
+    TRH(hipStreamSynchronize(st));
+#undef TR
+#undef TRH
+    cleanup();
+    ix->has_books = true;
+    return IVFR_OK;
+}
+
+// ---- add / finalize ---------------------------------------------------------------------------
+extern "C" int64_t ivfr_ntotal(const ivfr_index* ix) {
+    if (!ix) { ivfr_set_error("ivfr_ntotal: null index"); return IVFR_ERR_INVALID_ARG; }
+    return ix->finalized ? ix->N : ix->n_added;
+}
+
+extern "C" int ivfr_add(ivfr_index* ix, const uint8_t* x, int64_t n, int64_t id_base) {
+    IVFR_REQUIRE(ix && (x || n == 0), "ivfr_add: null argument");
+    IVFR_REQUIRE(n >= 0, "n = %lld must be >= 0", (long long)n);
+    if (!ix->has_books) { ivfr_set_error("ivfr_add before codebooks were trained or set"); return IVFR_ERR_STATE; }
+    if (ix->finalized) { ivfr_set_error("ivfr_add after ivfr_finalize"); return IVFR_ERR_STATE; }
+    IVFR_REQUIRE(id_base >= 0 && id_base + n <= 2147483647LL, "ids %lld..%lld do not fit int32", (long long)id_base,
+                 (long long)(id_base + n));
+    IVFR_REQUIRE(ix->next_id == INT64_MIN || id_base >= ix->next_id, "id ranges must increase: id_base %lld < %lld",
+                 (long long)id_base, (long long)ix->next_id);
+    IVFR_REQUIRE(ix->n_added + n <= 4000000000LL, "index is limited to 4e9 entries");
+    if (n == 0) return IVFR_OK;
+    IVFR_TRY(use_device(ix));
+    const ivfr_params& p = ix->p;
+    const int d = p.d, c = p.c, m = p.m, mr = p.m_refine;
+    hipStream_t st = nullptr;
+    if (!ix->list_fill) {
+        IVFR_TRY(dev_alloc(&ix->list_fill, (size_t)c));
+        IVFR_HIP(hipMemset(ix->list_fill, 0, (size_t)c * sizeof(unsigned long long)));
+    }
+    const bool on_dev = is_device_ptr(x);
+    const int64_t sub = std::min<int64_t>(n, ADD_SUB);
+    int T = 4096;
+    while ((int64_t)T * c > (1ll << 27) && T > 64) T >>= 1;
+    // workspace: fp32 rows, staged bytes, rank counters
+    size_t off_x = 0, off_stage = off_x + (size_t)sub * d * sizeof(float);
+    size_t off_cnt = off_stage + (on_dev ? 0 : ((size_t)sub * d + 255) / 256 * 256);
+    size_t total = off_cnt + (size_t)T * c * sizeof(uint32_t);
+    IVFR_TRY(ix->encode_ws.reserve(total));
+    char* ws = ix->encode_ws.as<char>();
+    float* X = reinterpret_cast<float*>(ws + off_x);
+    uint8_t* stage = reinterpret_cast<uint8_t*>(ws + off_stage);
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + off_cnt);
+
+    StagedChunk ch;
+    ch.n = n;
+    int r = IVFR_OK;
+    auto fail = [&](int code) {
+        dev_free(ch.list); dev_free(ch.rank); dev_free(ch.ids); dev_free(ch.codes); dev_free(ch.rcodes);
+        return code;
+    };
+    if ((r = dev_alloc(&ch.list, (size_t)n)) != IVFR_OK) return fail(r);
+    if ((r = dev_alloc(&ch.rank, (size_t)n)) != IVFR_OK) return fail(r);
+    if ((r = dev_alloc(&ch.ids, (size_t)n)) != IVFR_OK) return fail(r);
+    if ((r = dev_alloc(&ch.codes, (size_t)n * m)) != IVFR_OK) return fail(r);
+    if ((r = dev_alloc(&ch.rcodes, (size_t)n * mr)) != IVFR_OK) return fail(r);
+#define AD(expr) do { r = (expr); if (r != IVFR_OK) { (void)hipDeviceSynchronize(); return fail(r); } } while (0)
+    AD(ivfr_launch_iota(ch.ids, n, id_base, st));
+    for (int64_t a = 0; a < n; a += sub) {
+        const int64_t nb = std::min(sub, n - a);
+        AD(load_rows_f32(x, on_dev, a, nb, d, stage, X, st));
+        AD(ivfr_launch_assign(X, nb, ix->coarse, ix->coarse_norm, c, d, ch.list + a, st));
+        AD(ivfr_launch_residual(X, nb, d, ix->coarse, ch.list + a, st));
+        AD(ivfr_launch_pq_encode(X, nb, d, ix->pq, m, ch.codes + a * m, mr > 0, st));
+        if (mr > 0) AD(ivfr_launch_pq_encode(X, nb, d, ix->rq, mr, ch.rcodes + a * mr, false, st));
+        AD(ivfr_launch_list_ranks(ch.list + a, nb, c, ix->list_fill, cnt, T, ch.rank + a, st));
+    }
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { ivfr_set_error("ivfr_add: %s", hipGetErrorString(e)); return fail(IVFR_ERR_HIP); }
+#undef AD
+    ix->staged.push_back(ch);
+    ix->n_added += n;
+    ix->next_id = id_base + n;
+    return IVFR_OK;
+}
+
+// logical offsets -> padded layout on the device
+static int install_layout(ivfr_index* ix, const std::vector<int64_t>& offsets) {
+    const int c = ix->p.c;
+    ix->h_offsets = offsets;
+    ix->h_start.assign((size_t)c + 1, 0);
+    std::vector<uint32_t> len((size_t)c);
+    uint64_t pos = 0;
+    for (int l = 0; l < c; ++l) {
+        ix->h_start[(size_t)l] = (uint32_t)pos;
+        uint64_t n = (uint64_t)(offsets[(size_t)l + 1] - offsets[(size_t)l]);
+        len[(size_t)l] = (uint32_t)n;
+        pos += (n + IVFR_LIST_ALIGN - 1) / IVFR_LIST_ALIGN * IVFR_LIST_ALIGN;
+    }
+    if (pos + IVFR_TAIL_PAD >= 0xFFFFFFFFull) { ivfr_set_error("index too large for 32-bit entry positions"); return IVFR_ERR_INVALID_ARG; }
+    ix->h_start[(size_t)c] = (uint32_t)pos;
+    ix->n_slots = pos + IVFR_TAIL_PAD;
+    ix->N = offsets[(size_t)c];
+    IVFR_TRY(dev_alloc(&ix->list_start, (size_t)c + 1));
+    IVFR_TRY(dev_alloc(&ix->list_len, (size_t)c));
+    IVFR_HIP(hipMemcpy(ix->list_start, ix->h_start.data(), ((size_t)c + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
+    IVFR_HIP(hipMemcpy(ix->list_len, len.data(), (size_t)c * sizeof(uint32_t), hipMemcpyHostToDevice));
+    IVFR_TRY(dev_alloc(&ix->codes, (size_t)ix->n_slots * ix->p.m));
+    IVFR_TRY(dev_alloc(&ix->rcodes, (size_t)ix->n_slots * ix->p.m_refine));
+    IVFR_TRY(dev_alloc(&ix->ids, (size_t)ix->n_slots));
+    IVFR_HIP(hipMemset(ix->codes, 0, (size_t)ix->n_slots * ix->p.m));
+    if (ix->p.m_refine) IVFR_HIP(hipMemset(ix->rcodes, 0, (size_t)ix->n_slots * ix->p.m_refine));
+    IVFR_HIP(hipMemset(ix->ids, 0xff, (size_t)ix->n_slots * sizeof(int32_t)));
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_finalize(ivfr_index* ix) {
+    IVFR_REQUIRE(ix, "ivfr_finalize: null index");
+    if (ix->finalized) { ivfr_set_error("index already finalized"); return IVFR_ERR_STATE; }
+    if (!ix->has_books) { ivfr_set_error("ivfr_finalize before codebooks were trained or set"); return IVFR_ERR_STATE; }
+    IVFR_TRY(use_device(ix));
+    const int c = ix->p.c;
+    std::vector<unsigned long long> fill((size_t)c, 0ull);
+    if (ix->list_fill)
+        IVFR_HIP(hipMemcpy(fill.data(), ix->list_fill, (size_t)c * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+    std::vector<int64_t> offsets((size_t)c + 1, 0);
+    for (int l = 0; l < c; ++l) offsets[(size_t)l + 1] = offsets[(size_t)l] + (int64_t)fill[(size_t)l];
+    if (offsets[(size_t)c] != ix->n_added) { ivfr_set_error("internal: list fill %lld != added %lld", (long long)offsets[(size_t)c], (long long)ix->n_added); return IVFR_ERR_STATE; }
+    IVFR_TRY(install_layout(ix, offsets));
+    for (auto& ch : ix->staged)
+        IVFR_TRY(ivfr_launch_scatter(ch, ix->p.m, ix->p.m_refine, ix->list_start, ix->ids, ix->codes, ix->rcodes, nullptr));
+    IVFR_HIP(hipDeviceSynchronize());
+    free_staged(ix);
+    ix->encode_ws.release();
+    ix->finalized = true;
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_export(const ivfr_index* ix, int64_t* list_offsets, int32_t* ids, uint8_t* codes, uint8_t* rcodes) {
+    IVFR_REQUIRE(ix && list_offsets && ids && codes, "ivfr_export: null argument");
+    IVFR_REQUIRE(ix->p.m_refine == 0 || rcodes, "ivfr_export: rcodes is required when m_refine > 0");
+    if (!ix->finalized) { ivfr_set_error("ivfr_export before ivfr_finalize"); return IVFR_ERR_STATE; }
+    IVFR_TRY(use_device(ix));
+    const int c = ix->p.c, m = ix->p.m, mr = ix->p.m_refine;
+    memcpy(list_offsets, ix->h_offsets.data(), ((size_t)c + 1) * sizeof(int64_t));
+    for (int l = 0; l < c; ++l) {
+        const int64_t a = ix->h_offsets[(size_t)l], n = ix->h_offsets[(size_t)l + 1] - a;
+        if (n == 0) continue;
+        const uint64_t s = ix->h_start[(size_t)l];
+        IVFR_HIP(hipMemcpy(ids + a, ix->ids + s, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost));
+        IVFR_HIP(hipMemcpy(codes + a * m, ix->codes + s * m, (size_t)n * m, hipMemcpyDeviceToHost));
+        if (mr) IVFR_HIP(hipMemcpy(rcodes + a * mr, ix->rcodes + s * mr, (size_t)n * mr, hipMemcpyDeviceToHost));
+    }
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_import(ivfr_index* ix, int64_t N, const int64_t* list_offsets, const int32_t* ids,
+                           const uint8_t* codes, const uint8_t* rcodes) {
+    IVFR_REQUIRE(ix && list_offsets && (N == 0 || (ids && codes)), "ivfr_import: null argument");
+    IVFR_REQUIRE(ix->p.m_refine == 0 || N == 0 || rcodes, "ivfr_import: rcodes is required when m_refine > 0");
+    if (!ix->has_books) { ivfr_set_error("ivfr_import before codebooks were set"); return IVFR_ERR_STATE; }
+    if (ix->finalized || ix->n_added > 0) { ivfr_set_error("ivfr_import into a non-empty index"); return IVFR_ERR_STATE; }
+    const int c = ix->p.c, m = ix->p.m, mr = ix->p.m_refine;
+    IVFR_REQUIRE(N >= 0 && N <= 2147483647LL, "N = %lld out of range", (long long)N);
+    IVFR_REQUIRE(list_offsets[0] == 0 && list_offsets[c] == N, "list_offsets must run from 0 to N");
+    for (int l = 0; l < c; ++l)
+        IVFR_REQUIRE(list_offsets[l + 1] >= list_offsets[l], "list_offsets must be non-decreasing (list %d)", l);
+    IVFR_TRY(use_device(ix));
+    std::vector<int64_t> offsets(list_offsets, list_offsets + c + 1);
+    IVFR_TRY(install_layout(ix, offsets));
+    for (int l = 0; l < c; ++l) {
+        const int64_t a = offsets[(size_t)l], n = offsets[(size_t)l + 1] - a;
+        if (n == 0) continue;
+        const uint64_t s = ix->h_start[(size_t)l];
+        IVFR_HIP(hipMemcpy(ix->ids + s, ids + a, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice));
+        IVFR_HIP(hipMemcpy(ix->codes + s * m, codes + a * m, (size_t)n * m, hipMemcpyHostToDevice));
+        if (mr) IVFR_HIP(hipMemcpy(ix->rcodes + s * mr, rcodes + a * mr, (size_t)n * mr, hipMemcpyHostToDevice));
+    }
+    IVFR_HIP(hipDeviceSynchronize());
+    ix->n_added = N;
+    ix->finalized = true;
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_set_tuning(ivfr_index* ix, int32_t sample_mult, int32_t cap_mult, int32_t batch, int32_t scan_groups) {
+    IVFR_REQUIRE(ix, "ivfr_set_tuning: null index");
+    IVFR_REQUIRE(sample_mult >= 0 && cap_mult >= 0 && batch >= 0 && scan_groups >= 0, "tuning values must be >= 0");
+    IVFR_REQUIRE(batch <= 65535, "batch = %d exceeds 65535", batch);
+    if (sample_mult) ix->sample_mult = sample_mult;
+    if (cap_mult) ix->cap_mult = cap_mult;
+    if (batch) ix->batch = batch;
+    ix->scan_groups = scan_groups;
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_set_profiling(ivfr_index* ix, int32_t enable) {
+    IVFR_REQUIRE(ix, "ivfr_set_profiling: null index");
+    ix->profiling = enable != 0;
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_scan_profile(const ivfr_index* ix, double* scan_ms_total, int32_t* scan_launches,
+                                 double* rerank_ms_total, double* sample_ms_total) {
+    IVFR_REQUIRE(ix, "ivfr_scan_profile: null index");
+    if (scan_ms_total) *scan_ms_total = ix->prof_scan_ms;
+    if (scan_launches) *scan_launches = ix->prof_scan_launches;
+    if (rerank_ms_total) *rerank_ms_total = ix->prof_rerank_ms;
+    if (sample_ms_total) *sample_ms_total = ix->prof_sample_ms;
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks) {
+    IVFR_REQUIRE(ix, "ivfr_search_stats: null index");
+    if (codes_scanned) *codes_scanned = ix->st_codes;
+    if (pairs) *pairs = ix->st_pairs;
+    if (dense_fallbacks) *dense_fallbacks = ix->st_dense;
+    return IVFR_OK;
+}

@@ -1,0 +1,182 @@
+// Internal declarations shared by the translation units of libivfadcr (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <vector>
+
+#include "ivfadcr.h"
+
+#define IVFR_KS 256            // reproduction values per sub-quantizer (8 bits)
+#define IVFR_LIST_ALIGN 32u    // every inverted list starts at a multiple of 32 entries
+#define IVFR_BLOCK 512u        // entries per scan block: one 16-byte load per thread of a 256-thread group
+#define IVFR_TAIL_PAD 1024u    // zero entries after the last list so vector loads never run off the end
+
+void ivfr_set_error(const char* fmt, ...);
+
+#define IVFR_HIP(expr)                                                                         \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) {                                                                \
+            ivfr_set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return (e_ == hipErrorOutOfMemory) ? IVFR_ERR_OOM : IVFR_ERR_HIP;                  \
+        }                                                                                      \
+    } while (0)
+
+#define IVFR_TRY(expr)                  \
+    do {                                \
+        int r_ = (expr);                \
+        if (r_ != IVFR_OK) return r_;   \
+    } while (0)
+
+#define IVFR_REQUIRE(cond, ...)              \
+    do {                                     \
+        if (!(cond)) {                       \
+            ivfr_set_error(__VA_ARGS__);     \
+            return IVFR_ERR_INVALID_ARG;     \
+        }                                    \
+    } while (0)
+
+// Grow-only device buffer.
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    int reserve(size_t need) {
+        if (need <= bytes) return IVFR_OK;
+        if (p) { IVFR_HIP(hipFree(p)); p = nullptr; bytes = 0; }
+        size_t want = need + need / 8 + 256;
+        hipError_t e = hipMalloc(&p, want);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            p = nullptr;
+            e = hipMalloc(&p, need);
+            want = need;
+        }
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            p = nullptr;
+            ivfr_set_error("device allocation of %zu bytes failed", need);
+            return IVFR_ERR_OOM;
+        }
+        bytes = want;
+        return IVFR_OK;
+    }
+    void release() { if (p) (void)hipFree(p); p = nullptr; bytes = 0; }
+    template <class T> T* as() const { return reinterpret_cast<T*>(p); }
+};
+
+// One staged (encoded, not yet list-sorted) batch of database vectors.
+struct StagedChunk {
+    int64_t n = 0;
+    int32_t* list = nullptr;   // coarse list of each vector
+    uint32_t* rank = nullptr;  // position inside that list (insertion order)
+    int32_t* ids = nullptr;
+    uint8_t* codes = nullptr;  // [n, m]
+    uint8_t* rcodes = nullptr; // [n, m']
+};
+
+struct ivfr_index {
+    ivfr_params p;
+    int dsub = 0, dsub_r = 0;
+
+    // codebooks (device) and their squared norms
+    float* coarse = nullptr;       // [c, d]
+    float* coarse_norm = nullptr;  // [c]
+    float* pq = nullptr;           // [m, 256, dsub]
+    float* pq_norm = nullptr;      // [m, 256]
+    float* rq = nullptr;           // [m', 256, dsub_r]
+    bool has_books = false;
+
+    // staging
+    std::vector<StagedChunk> staged;
+    unsigned long long* list_fill = nullptr;  // [c] entries per list so far (device)
+    int64_t n_added = 0;
+    int64_t next_id = INT64_MIN;
+
+    // finished inverted file (device, padded layout: list l occupies
+    // [list_start[l], list_start[l] + list_len[l]) and list_start[l] % IVFR_LIST_ALIGN == 0)
+    bool finalized = false;
+    int64_t N = 0;
+    uint64_t n_slots = 0;            // padded entry count incl. tail pad
+    uint32_t* list_start = nullptr;  // [c+1]
+    uint32_t* list_len = nullptr;    // [c]
+    uint8_t* codes = nullptr;        // [n_slots, m]
+    uint8_t* rcodes = nullptr;       // [n_slots, m']
+    int32_t* ids = nullptr;          // [n_slots]
+    std::vector<int64_t> h_offsets;  // logical CSR offsets [c+1] (host)
+    std::vector<uint32_t> h_start;   // padded starts [c+1] (host)
+
+    // tuning
+    int sample_mult = 4, cap_mult = 16, batch = 1024, scan_groups = 0;
+
+    // scratch
+    DevBuf search_ws, encode_ws, dense_ws;
+    int* h_status = nullptr;         // pinned host word(s) for status read-back
+
+    // stats of the last search
+    int64_t st_codes = 0, st_pairs = 0, st_dense = 0;
+    bool profiling = false;
+    double prof_scan_ms = 0, prof_rerank_ms = 0, prof_sample_ms = 0;
+    int prof_scan_launches = 0;
+    int n_cu = 256;
+};
+
+// ---- kernels' host launchers (each enqueues on `st` and returns a status) -------------------
+
+// squared norms of the rows of X [n, dim]
+int ivfr_launch_row_norms(const float* X, int64_t n, int dim, float* out, hipStream_t st);
+// uint8 [n, d] -> fp32
+int ivfr_launch_u8_to_f32(const uint8_t* x, int64_t count, float* out, hipStream_t st);
+
+// fp32 MFMA distance GEMM: rows X [n, d] against centroids C [c, d].
+//  keys[row * c + col] = (bits(max(0, ||x||^2 + ||c||^2 - 2 x.c)) << 32) | col
+int ivfr_launch_dist_keys(const float* X, const float* xnorm, int64_t n, const float* C, const float* cnorm,
+                          int c, int d, uint64_t* keys, hipStream_t st);
+//  assign[row] = argmin_col (||c||^2 - 2 x.c), ties to the lowest col
+int ivfr_launch_assign(const float* X, int64_t n, const float* C, const float* cnorm, int c, int d,
+                       int32_t* assign, hipStream_t st);
+
+// Segmented exact top-K by 64-bit key (ascending).  One workgroup per segment (select.hip).
+struct SelectArgs {
+    int nseg = 0;
+    int K = 0;
+    // source A: keys[seg * seg_stride + i], i < count
+    const uint64_t* keys = nullptr;
+    // source B: records (estimate bits, entry position) with key = (estimate bits << 32) | ids[position]
+    const uint2* recs = nullptr;
+    const int32_t* ids = nullptr;
+    int64_t seg_stride = 0;
+    // element count per segment: fixed_count, or min(counts[seg], cap) when counts != nullptr
+    int64_t fixed_count = 0;
+    const uint32_t* counts = nullptr;
+    uint32_t cap = 0;
+};
+// pivot only: tau[seg] = estimate of the K-th smallest record (+inf when fewer than K); skip[seg] != 0 leaves tau alone
+int ivfr_launch_select_tau(const SelectArgs& a, const uint8_t* skip, float* tau, hipStream_t st);
+int ivfr_select_init();   // one-time function attributes
+
+// Search plan, look-up tables, list scan (scan.hip)
+struct PlanBuffers {
+    uint32_t* pair_start;  // [P] first padded entry of the pair's list
+    uint32_t* len1;        // [P] entries of the pair scanned by the sample pass
+    uint32_t* len2;        // [P] entries scanned by the filtered pass (0 if the query was fully sampled)
+    uint32_t* blkpre1;     // [P+1] exclusive prefix of blocks, sample pass
+    uint32_t* blkpre2;     // [P+1] same, filtered pass
+    unsigned long long* sq;      // [nq] entries in the query's visited lists
+    uint8_t* fully;              // [nq] 1 = the sample pass covered every visited entry
+    unsigned long long* totals;  // [2]: [0] = sum of sq
+};
+int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t n_sample,
+                     const PlanBuffers& pb, hipStream_t st);
+int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
+                    float* lut, hipStream_t st);
+int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
+                     const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
+                     uint64_t cand_stride, uint32_t cap, int groups, hipStream_t st);
+
+// Encoding (encode.hip)
+int ivfr_launch_residual(float* X, int64_t n, int d, const float* C, const int32_t* assign, hipStream_t st);
+int ivfr_launch_pq_encode(float* R, int64_t n, int d, const float* book, int parts, uint8_t* codes,
+                          bool subtract, hipStream_t st);

@@ -1,0 +1,106 @@
+// Query step 2 of section 3.2 (gfx950): for each short-list entry, rebuild the refined
+// approximation  y^ = coarse[l] + decode(q_c code) + decode(q_r code)  of Eq. (9) explicitly and
+// compute the squared distance ||x - y^||^2 of Eq. (10).  No full database vector is read:
+// an entry costs m + m' + 4 gathered bytes; the codebooks and the coarse centroids are small
+// enough to be served from cache.
+//
+// Eight lanes share one entry, lane t taking dimensions [t d/8, (t+1) d/8); the partial sums
+// are combined with three xor-shuffles.  The entry's list is found by binary search of its
+// position in the list start offsets.  Output per entry: the 64-bit key (distance bits << 32
+// | id) consumed by the final top-k selection.
+#include "ivfr_internal.h"
+
+template <int VEC>
+__global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ queries, int d, int c, int m, int mr,
+                                                     int dsub, int dsub_r, const float* __restrict__ coarse,
+                                                     const float* __restrict__ pq, const float* __restrict__ rq,
+                                                     const uint32_t* __restrict__ list_start,
+                                                     const uint8_t* __restrict__ codes,
+                                                     const uint8_t* __restrict__ rcodes,
+                                                     const int32_t* __restrict__ ids, int kprime, int q_base,
+                                                     const uint32_t* __restrict__ short_pos,
+                                                     const int32_t* __restrict__ short_n, uint64_t* __restrict__ keys,
+                                                     float* __restrict__ refined_out, int32_t* __restrict__ ids_out) {
+    const int q = q_base + blockIdx.y;
+    const int n = short_n[q];
+    const int slot = blockIdx.x * 32 + (threadIdx.x >> 3);
+    const int t = threadIdx.x & 7;
+    const bool live = slot < n;   // uniform over the 8 lanes of an entry
+    float acc = 0.f;
+    int32_t id = -1;
+    if (live) {
+        const uint32_t pos = short_pos[(int64_t)q * kprime + slot];
+        int lo = 0, hi = c;   // last list with list_start <= pos
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (list_start[mid] <= pos) lo = mid; else hi = mid;
+        }
+        const int l = lo;
+        id = ids[pos];
+        const uint8_t* code = codes + (uint64_t)pos * m;
+        const uint8_t* rcode = rcodes + (uint64_t)pos * mr;
+        const float* x = queries + (int64_t)q * d;
+        const float* cl = coarse + (int64_t)l * d;
+        const int e0 = t * (d / 8), e1 = e0 + d / 8;
+        if (VEC == 4) {
+            for (int e = e0; e < e1; e += 4) {
+                const int j = e / dsub;
+                float4 y = *reinterpret_cast<const float4*>(cl + e);
+                float4 pv = *reinterpret_cast<const float4*>(pq + ((int64_t)j * IVFR_KS + code[j]) * dsub + (e - j * dsub));
+                y.x += pv.x; y.y += pv.y; y.z += pv.z; y.w += pv.w;
+                if (mr > 0) {
+                    const int jr = e / dsub_r;
+                    float4 rv = *reinterpret_cast<const float4*>(rq + ((int64_t)jr * IVFR_KS + rcode[jr]) * dsub_r +
+                                                                 (e - jr * dsub_r));
+                    y.x += rv.x; y.y += rv.y; y.z += rv.z; y.w += rv.w;
+                }
+                float4 xv = *reinterpret_cast<const float4*>(x + e);
+                float a = xv.x - y.x, b = xv.y - y.y, cc = xv.z - y.z, dd = xv.w - y.w;
+                acc = fmaf(a, a, acc); acc = fmaf(b, b, acc); acc = fmaf(cc, cc, acc); acc = fmaf(dd, dd, acc);
+            }
+        } else {
+            for (int e = e0; e < e1; ++e) {
+                const int j = e / dsub;
+                float y = cl[e] + pq[((int64_t)j * IVFR_KS + code[j]) * dsub + (e - j * dsub)];
+                if (mr > 0) {
+                    const int jr = e / dsub_r;
+                    y += rq[((int64_t)jr * IVFR_KS + rcode[jr]) * dsub_r + (e - jr * dsub_r)];
+                }
+                float a = x[e] - y;
+                acc = fmaf(a, a, acc);
+            }
+        }
+    }
+    acc += __shfl_xor(acc, 4, 64);
+    acc += __shfl_xor(acc, 2, 64);
+    acc += __shfl_xor(acc, 1, 64);
+    if (t == 0 && slot < kprime) {
+        const int64_t o = (int64_t)q * kprime + slot;
+        if (live) {
+            keys[o] = ((uint64_t)__float_as_uint(acc) << 32) | (uint32_t)id;
+            if (refined_out) refined_out[o] = acc;
+            if (ids_out) ids_out[o] = id;
+        } else {
+            keys[o] = ~0ull;
+            if (refined_out) refined_out[o] = INFINITY;
+            if (ids_out) ids_out[o] = -1;
+        }
+    }
+}
+
+int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, int nq, int kprime,
+                       const uint32_t* short_pos, const int32_t* short_n, uint64_t* keys, float* refined_out,
+                       int32_t* ids_out, hipStream_t st) {
+    if (nq <= 0) return IVFR_OK;
+    dim3 grid((kprime + 31) / 32, nq);
+    const bool vec = (ix->dsub % 4 == 0) && (ix->p.m_refine == 0 || ix->dsub_r % 4 == 0) && ((ix->p.d / 8) % 4 == 0);
+#define IVFR_RERANK_ARGS                                                                                       \
+    queries, ix->p.d, ix->p.c, ix->p.m, ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq,      \
+        ix->list_start, ix->codes, ix->rcodes, ix->ids, kprime, q_base, short_pos, short_n, keys, refined_out, \
+        ids_out
+    if (vec) hipLaunchKernelGGL(rerank_kernel<4>, grid, dim3(256), 0, st, IVFR_RERANK_ARGS);
+    else hipLaunchKernelGGL(rerank_kernel<1>, grid, dim3(256), 0, st, IVFR_RERANK_ARGS);
+#undef IVFR_RERANK_ARGS
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}

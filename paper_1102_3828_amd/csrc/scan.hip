@@ -1,0 +1,344 @@
+// Query step 1 of section 3.2 on the inverted file of section 3.3 (gfx950): plan of the
+// visited (query, list) pairs, per-pair look-up tables of Eq. (5), and the ADC list scan.
+#include "ivfr_internal.h"
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// ------------------------------------------------------------------------------------------
+// Plan.  Pair p = q * w + r is the r-th nearest list of query q.  The scan runs twice:
+//  pass 1 ("sample") covers the first ~n_sample entries of the query's nearest lists and keeps
+//         every estimate; the k'-th smallest of them bounds the k'-th smallest overall;
+//  pass 2 covers every visited entry and keeps only estimates <= that bound.
+// A query whose visited lists hold no more than n_sample entries is finished by pass 1.
+// ------------------------------------------------------------------------------------------
+__global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int w,
+                                  const uint32_t* __restrict__ list_start, const uint32_t* __restrict__ list_len,
+                                  uint32_t n_sample, PlanBuffers pb) {
+    int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nq) return;
+    unsigned long long total = 0;
+    for (int r = 0; r < w; ++r) total += list_len[probe[(int64_t)q * w + r]];
+    const bool fully = total <= n_sample;
+    pb.sq[q] = total;
+    pb.fully[q] = fully ? 1 : 0;
+    atomicAdd(pb.totals, total);
+    unsigned long long cum = 0;
+    for (int r = 0; r < w; ++r) {
+        int64_t p = (int64_t)q * w + r;
+        int l = probe[p];
+        uint32_t len = list_len[l];
+        uint32_t s;
+        if (fully) s = len;
+        else {
+            unsigned long long room = (cum < n_sample) ? (n_sample - cum) : 0ull;
+            s = (room < len) ? (uint32_t)room : len;
+        }
+        cum += s;
+        pb.pair_start[p] = list_start[l];
+        pb.len1[p] = s;
+        pb.len2[p] = fully ? 0u : len;
+    }
+}
+
+// Exclusive prefix sums of ceil(len / IVFR_BLOCK) over the P pairs, for both passes (one workgroup).
+__global__ __launch_bounds__(1024) void plan_scan_kernel(int P, PlanBuffers pb) {
+    __shared__ uint32_t wtot[2][16];
+    __shared__ uint32_t carry[2];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (tid < 2) carry[tid] = 0;
+    __syncthreads();
+    for (int base = 0; base < P; base += 1024) {
+        int p = base + tid;
+        uint32_t v[2] = {0, 0};
+        if (p < P) {
+            v[0] = (pb.len1[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
+            v[1] = (pb.len2[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
+        }
+        uint32_t inc[2] = {v[0], v[1]};
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                uint32_t o = __shfl_up(inc[a], off, 64);
+                if (lane >= off) inc[a] += o;
+            }
+            if (lane == 63) wtot[a][wv] = inc[a];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            uint32_t add = carry[a];
+            for (int x = 0; x < wv; ++x) add += wtot[a][x];
+            inc[a] += add;
+        }
+        if (p < P) {
+            pb.blkpre1[p] = inc[0] - v[0];
+            pb.blkpre2[p] = inc[1] - v[1];
+        }
+        __syncthreads();
+        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; }
+        __syncthreads();
+    }
+    if (tid == 0) { pb.blkpre1[P] = carry[0]; pb.blkpre2[P] = carry[1]; }
+}
+
+int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t n_sample,
+                     const PlanBuffers& pb, hipStream_t st) {
+    IVFR_HIP(hipMemsetAsync(pb.totals, 0, 2 * sizeof(unsigned long long), st));
+    hipLaunchKernelGGL(plan_pairs_kernel, dim3((nq + 127) / 128), dim3(128), 0, st, probe, nq, w, ix->list_start,
+                       ix->list_len, n_sample, pb);
+    IVFR_HIP(hipGetLastError());
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, nq * w, pb);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Look-up tables of Eq. (5), one per (query, visited list):
+//   T[p][j][k] = || (x_q - coarse[l])^j - pq[j][k] ||^2 = ||r^j||^2 + ||pq[j][k]||^2 - 2 r^j . pq[j][k]
+// The dot products are a [pairs x dsub] . [dsub x 256] contraction per sub-quantizer and run
+// on the matrix cores (v_mfma_f32_32x32x2_f32): a workgroup takes 32 pairs, keeps their
+// residuals in LDS, and each wavefront walks its share of the (j, 32-centroid tile) grid.
+// Negative round-off is clamped to zero (the quantity is a squared norm).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void lut_mfma_kernel(const float* __restrict__ queries,
+                                                       const int32_t* __restrict__ probe, int P, int w, int d, int m,
+                                                       int dsub, const float* __restrict__ coarse,
+                                                       const float* __restrict__ pq, const float* __restrict__ pq_norm,
+                                                       float* __restrict__ lut) {
+    extern __shared__ float smem[];
+    const int stride = d + 4;
+    float* R = smem;                   // [32][d + 4]
+    float* rn = smem + 32 * stride;    // [32][m]
+    const int p0 = blockIdx.x * 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < 32 * (d / 4); i += 256) {
+        int pr = i / (d / 4), e = (i % (d / 4)) * 4;
+        int p = p0 + pr;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (p < P) {
+            int q = p / w;
+            int l = probe[p];
+            float4 x = *reinterpret_cast<const float4*>(queries + (int64_t)q * d + e);
+            float4 cc = *reinterpret_cast<const float4*>(coarse + (int64_t)l * d + e);
+            v = make_float4(x.x - cc.x, x.y - cc.y, x.z - cc.z, x.w - cc.w);
+        }
+        *reinterpret_cast<float4*>(R + pr * stride + e) = v;
+    }
+    __syncthreads();
+    for (int i = tid; i < 32 * m; i += 256) {
+        int pr = i / m, j = i % m;
+        float s = 0.f;
+        for (int e = 0; e < dsub; ++e) { float v = R[pr * stride + j * dsub + e]; s = fmaf(v, v, s); }
+        rn[i] = s;
+    }
+    __syncthreads();
+    const int r = lane & 31, h = lane >> 5;
+    const int ntile = m * 8;   // (j, 32-centroid tile) units
+    for (int u = wave; u < ntile; u += 4) {
+        const int j = u >> 3, nt = u & 7;
+        floatx16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        const float* brow = pq + ((int64_t)j * IVFR_KS + nt * 32 + r) * dsub;
+        for (int kk = 0; kk < dsub; kk += 8) {
+            float4 a = *reinterpret_cast<const float4*>(R + r * stride + j * dsub + kk + 4 * h);
+            float4 b = *reinterpret_cast<const float4*>(brow + kk + 4 * h);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+        }
+        const float pn = pq_norm[j * IVFR_KS + nt * 32 + r];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int pr = 8 * (v >> 2) + 4 * h + (v & 3);
+            int p = p0 + pr;
+            if (p < P) {
+                float val = fmaxf(0.f, fmaf(-2.f, acc[v], rn[pr * m + j] + pn));
+                lut[((int64_t)p * m + j) * IVFR_KS + nt * 32 + r] = val;
+            }
+        }
+    }
+}
+
+// Direct-form tables for sub-vector widths the MFMA path does not cover (dsub % 8 != 0).
+__global__ __launch_bounds__(256) void lut_direct_kernel(const float* __restrict__ queries,
+                                                         const int32_t* __restrict__ probe, int P, int w, int d, int m,
+                                                         int dsub, const float* __restrict__ coarse,
+                                                         const float* __restrict__ pq, float* __restrict__ lut) {
+    extern __shared__ float smem[];   // residual [d]
+    const int p = blockIdx.x;
+    const int q = p / w, l = probe[p];
+    for (int e = threadIdx.x; e < d; e += 256) smem[e] = queries[(int64_t)q * d + e] - coarse[(int64_t)l * d + e];
+    __syncthreads();
+    for (int i = threadIdx.x; i < m * IVFR_KS; i += 256) {
+        int j = i / IVFR_KS;
+        const float* cb = pq + (int64_t)i * dsub;
+        float s = 0.f;
+        for (int e = 0; e < dsub; ++e) { float df = smem[j * dsub + e] - cb[e]; s = fmaf(df, df, s); }
+        lut[(int64_t)p * m * IVFR_KS + i] = s;
+    }
+}
+
+int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w, float* lut,
+                    hipStream_t st) {
+    const int P = nq * w, d = ix->p.d, m = ix->p.m;
+    if (P <= 0) return IVFR_OK;
+    if (ix->dsub % 8 == 0) {
+        size_t lds = (size_t)(32 * (d + 4) + 32 * m) * sizeof(float);
+        hipLaunchKernelGGL(lut_mfma_kernel, dim3((P + 31) / 32), dim3(256), lds, st, queries, probe, P, w, d, m,
+                           ix->dsub, ix->coarse, ix->pq, ix->pq_norm, lut);
+    } else {
+        hipLaunchKernelGGL(lut_direct_kernel, dim3(P), dim3(256), (size_t)d * sizeof(float), st, queries, probe, P, w,
+                           d, m, ix->dsub, ix->coarse, ix->pq, lut);
+    }
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// ADC list scan (Eq. (5)): estimate = sum over the m code bytes of T[j][byte_j].
+//
+// The visited (pair, block) work of a pass is one virtual stream of blocks of IVFR_BLOCK entries;
+// workgroup g of G takes the contiguous share [total*g/G, total*(g+1)/G) of it, so every
+// workgroup streams the same number of code bytes whatever the list-length skew, and reloads
+// the pair's table (m KB, LDS) only when its share crosses into the next pair.  A thread
+// loads 16 code bytes per block with one coalesced dwordx4 load.  Estimates <= tau[q] are
+// appended to query q's candidate buffer as (estimate bits, entry position) records through
+// one wavefront-aggregated atomic per 64 lanes; the counter keeps counting past the
+// buffer's capacity so the host can tell an overflow.
+// ------------------------------------------------------------------------------------------
+template <int M>
+__device__ __forceinline__ float adc_sum(const float* lut, const uint32_t* wds) {
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int t = 0; t < M / 4; ++t) {
+        uint32_t v = wds[t];
+        const float* L = lut + t * 4 * IVFR_KS;
+        s0 += L[v & 0xff];
+        s1 += L[IVFR_KS + ((v >> 8) & 0xff)];
+        s0 += L[2 * IVFR_KS + ((v >> 16) & 0xff)];
+        s1 += L[3 * IVFR_KS + (v >> 24)];
+    }
+    return s0 + s1;
+}
+
+__device__ __forceinline__ void append_records(bool keep0, float e0, uint32_t pos0, bool keep1, float e1,
+                                               uint32_t pos1, uint2* cand, uint32_t* cnt, uint32_t cap) {
+    const uint64_t m0 = __ballot(keep0), m1 = __ballot(keep1);
+    if ((m0 | m1) == 0) return;
+    const int lane = threadIdx.x & 63;
+    const uint32_t n0 = __popcll(m0), n1 = __popcll(m1);
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(cnt, n0 + n1);
+    base = __shfl(base, 0, 64);
+    const uint64_t below = (1ull << lane) - 1ull;
+    if (keep0) {
+        uint32_t s = base + __popcll(m0 & below);
+        if (s < cap) cand[s] = make_uint2(__float_as_uint(e0), pos0);
+    }
+    if (keep1) {
+        uint32_t s = base + n0 + __popcll(m1 & below);
+        if (s < cap) cand[s] = make_uint2(__float_as_uint(e1), pos1);
+    }
+}
+
+template <int M>
+__global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict__ codes,
+                                                       const float* __restrict__ lut,
+                                                       const uint32_t* __restrict__ pair_start,
+                                                       const uint32_t* __restrict__ pair_len,
+                                                       const uint32_t* __restrict__ blkpre, int P, int w,
+                                                       const float* __restrict__ tau, uint2* __restrict__ cand,
+                                                       uint32_t* __restrict__ cand_cnt, uint64_t cand_stride,
+                                                       uint32_t cap) {
+    extern __shared__ float s_lut[];   // M * 256 floats
+    const uint32_t total = blkpre[P];
+    const uint32_t G = gridDim.x, g = blockIdx.x;
+    uint32_t b = (uint32_t)(((uint64_t)total * g) / G);
+    const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / G);
+    if (b >= b_end) return;
+    // last pair p with blkpre[p] <= b
+    int lo = 0, hi = P;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (blkpre[mid] <= b) lo = mid; else hi = mid;
+    }
+    int p = lo;
+    const int tid = threadIdx.x;
+    while (b < b_end) {
+        while (blkpre[p + 1] <= b) ++p;   // skip pairs without blocks in this pass
+        const uint32_t pb0 = blkpre[p], pb1 = blkpre[p + 1];
+        const uint32_t stop = pb1 < b_end ? pb1 : b_end;
+        const int q = p / w;
+        const uint32_t start = pair_start[p], len = pair_len[p];
+        const float t = tau[q];
+        uint2* qc = cand + (uint64_t)q * cand_stride;
+        uint32_t* cnt = cand_cnt + q;
+        __syncthreads();   // previous pair's table no longer in use
+        {
+            const float4* src = reinterpret_cast<const float4*>(lut + (int64_t)p * M * IVFR_KS);
+            float4* dst = reinterpret_cast<float4*>(s_lut);
+            for (int i = tid; i < M * IVFR_KS / 4; i += 256) dst[i] = src[i];
+        }
+        __syncthreads();
+        for (; b < stop; ++b) {
+            const uint32_t e0 = (b - pb0) * IVFR_BLOCK + 2u * tid;   // entry inside the list
+            uint32_t wds[2][M / 4];
+            bool in0 = e0 < len, in1 = e0 + 1 < len;
+            float est0 = 0.f, est1 = 0.f;
+            if (in0) {
+                const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e0) * M);
+                if (M == 8) {
+                    uint4 v = *reinterpret_cast<const uint4*>(src);
+                    wds[0][0] = v.x; wds[0][1] = v.y; wds[1][0] = v.z; wds[1][1] = v.w;
+                } else {
+#pragma unroll
+                    for (int t2 = 0; t2 < M / 4; ++t2) { wds[0][t2] = src[t2]; wds[1][t2] = src[M / 4 + t2]; }
+                }
+                est0 = adc_sum<M>(s_lut, wds[0]);
+                est1 = adc_sum<M>(s_lut, wds[1]);
+            }
+            append_records(in0 && est0 <= t, est0, start + e0, in1 && est1 <= t, est1, start + e0 + 1, qc, cnt, cap);
+        }
+    }
+}
+
+template <int M>
+static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
+                         const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
+                         uint64_t cand_stride, uint32_t cap, int groups, hipStream_t st) {
+    size_t lds = (size_t)M * IVFR_KS * sizeof(float);
+    static bool attr_done = false;
+    if (!attr_done && lds > 48 * 1024) {
+        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_kernel<M>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start, pair_len,
+                       blkpre, P, w, tau, cand, cand_cnt, cand_stride, cap);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
+                     const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
+                     uint64_t cand_stride, uint32_t cap, int groups, hipStream_t st) {
+    if (P <= 0) return IVFR_OK;
+#define IVFR_SCAN_CASE(MM)                                                                                      \
+    case MM:                                                                                                    \
+        return launch_scan_m<MM>(ix, lut, pair_start, pair_len, blkpre, P, w, tau, cand, cand_cnt, cand_stride, \
+                                 cap, groups, st)
+    switch (ix->p.m) {
+        IVFR_SCAN_CASE(4);
+        IVFR_SCAN_CASE(8);
+        IVFR_SCAN_CASE(16);
+        IVFR_SCAN_CASE(32);
+        IVFR_SCAN_CASE(64);
+        default:
+            ivfr_set_error("list scan supports m in {4, 8, 16, 32, 64}; got %d", ix->p.m);
+            return IVFR_ERR_INVALID_ARG;
+    }
+#undef IVFR_SCAN_CASE
+}

@@ -1,0 +1,267 @@
+// Query stage (section 3.2 steps 1-3 on the inverted file of section 3.3): host orchestration.
+//
+// Per internal batch of queries, all on one stream and without host round trips until the end:
+//   coarse distances (MFMA) -> w nearest lists -> plan of (query, list) pairs -> look-up
+//   tables (MFMA) -> sample scan -> per-query bound tau on the k'-th smallest estimate ->
+//   filtered scan of every visited entry -> exact k' smallest -> re-rank -> k smallest.
+// The bound is the k'-th smallest estimate among the first entries of the nearest lists: the
+// k'-th smallest of any subset can only be larger than the k'-th smallest overall, so filtering
+// by it loses nothing.  If a query's survivors overflow its candidate buffer (reported by the
+// device counter, read back once per batch), that query is redone through a buffer that holds
+// every visited entry.
+#include "ivfr_internal.h"
+
+#include <algorithm>
+#include <string.h>
+
+int ivfr_launch_select_records(const SelectArgs& a, int out_base, uint32_t* out_pos, float* out_est, int32_t* out_n,
+                               int32_t* overflow, int32_t* overflow_total, hipStream_t st);
+int ivfr_launch_select_sorted(const SelectArgs& a, const int32_t* counts_i32, int out_base, int32_t* out_lo,
+                              float* out_hi, hipStream_t st);
+int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, int nq, int kprime,
+                       const uint32_t* short_pos, const int32_t* short_n, uint64_t* keys, float* refined_out,
+                       int32_t* ids_out, hipStream_t st);
+
+__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// reset the candidate counters of queries that the filtered pass will refill
+__global__ void reset_counts_kernel(uint32_t* cnt, const uint8_t* fully, int nq) {
+    int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < nq && !fully[q]) cnt[q] = 0;
+}
+
+struct Carver {
+    size_t off = 0;
+    template <class T> size_t take(size_t count) {
+        size_t a = (off + 255) / 256 * 256;
+        off = a + count * sizeof(T);
+        return a;
+    }
+};
+
+namespace {
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    int kind = 0;   // 0 sample scan, 1 filtered scan, 2 rerank
+};
+}
+
+extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t nq, int32_t w, int32_t kprime,
+                                 int32_t k, int32_t* ids_out, float* dist_out, int32_t* probe_out,
+                                 float* probe_dist_out, int32_t* short_ids_out, float* short_est_out,
+                                 float* short_ref_out, int32_t* short_count_out, void* stream) {
+    IVFR_REQUIRE(ix && (nq == 0 || (queries && ids_out && dist_out)), "ivfr_search: null argument");
+    if (!ix->finalized) { ivfr_set_error("ivfr_search before ivfr_finalize / ivfr_import"); return IVFR_ERR_STATE; }
+    const ivfr_params& p = ix->p;
+    IVFR_REQUIRE(nq >= 0, "nq = %lld must be >= 0", (long long)nq);
+    IVFR_REQUIRE(w >= 1 && w <= p.c, "w = %d must be in [1, c = %d]", w, p.c);
+    IVFR_REQUIRE(kprime >= 1, "kprime = %d must be >= 1", kprime);
+    IVFR_REQUIRE(k >= 1 && k <= kprime, "k = %d must be in [1, kprime = %d]", k, kprime);
+    IVFR_REQUIRE(k <= 16384 && w <= 16384, "k and w are limited to 16384");
+    IVFR_REQUIRE((int64_t)kprime * ix->cap_mult < (1ll << 31), "kprime * cap_mult too large");
+    IVFR_HIP(hipSetDevice(p.device));
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    ix->st_codes = ix->st_pairs = ix->st_dense = 0;
+    ix->prof_scan_ms = ix->prof_rerank_ms = ix->prof_sample_ms = 0;
+    ix->prof_scan_launches = 0;
+    if (nq == 0) return IVFR_OK;
+
+    const int d = p.d, c = p.c, m = p.m;
+    const int B = (int)std::min<int64_t>(nq, ix->batch);
+    const int P = B * w;
+    const uint32_t n_sample = (uint32_t)std::min<int64_t>((int64_t)ix->sample_mult * kprime, 1ll << 30);
+    const uint32_t cap = (uint32_t)std::max<int64_t>((int64_t)ix->cap_mult * kprime, (int64_t)n_sample + IVFR_BLOCK);
+    const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 8;
+
+    // carve the workspace
+    Carver cv;
+    const size_t o_xnorm = cv.take<float>(B);
+    const size_t o_ckeys = cv.take<uint64_t>((size_t)B * c);
+    const size_t o_probe = cv.take<int32_t>(P);
+    const size_t o_probed = cv.take<float>(P);
+    const size_t o_pstart = cv.take<uint32_t>(P);
+    const size_t o_len1 = cv.take<uint32_t>(P);
+    const size_t o_len2 = cv.take<uint32_t>(P);
+    const size_t o_pre1 = cv.take<uint32_t>((size_t)P + 1);
+    const size_t o_pre2 = cv.take<uint32_t>((size_t)P + 1);
+    const size_t o_sq = cv.take<unsigned long long>(B);
+    const size_t o_fully = cv.take<uint8_t>(B);
+    const size_t o_totals = cv.take<unsigned long long>(2);
+    const size_t o_lut = cv.take<float>((size_t)P * m * IVFR_KS);
+    const size_t o_cand = cv.take<uint2>((size_t)B * cap);
+    const size_t o_cnt = cv.take<uint32_t>(B);
+    const size_t o_tau = cv.take<float>(B);
+    const size_t o_spos = cv.take<uint32_t>((size_t)B * kprime);
+    const size_t o_sest = cv.take<float>((size_t)B * kprime);
+    const size_t o_sn = cv.take<int32_t>(B);
+    const size_t o_over = cv.take<int32_t>(B);
+    const size_t o_overtot = cv.take<int32_t>(4);
+    const size_t o_rkeys = cv.take<uint64_t>((size_t)B * kprime);
+    const size_t o_sref = cv.take<float>((size_t)B * kprime);
+    const size_t o_sids = cv.take<int32_t>((size_t)B * kprime);
+    IVFR_TRY(ix->search_ws.reserve(cv.off + 256));
+    char* ws = ix->search_ws.as<char>();
+    float* xnorm = reinterpret_cast<float*>(ws + o_xnorm);
+    uint64_t* ckeys = reinterpret_cast<uint64_t*>(ws + o_ckeys);
+    int32_t* probe = reinterpret_cast<int32_t*>(ws + o_probe);
+    float* probed = reinterpret_cast<float*>(ws + o_probed);
+    PlanBuffers pb;
+    pb.pair_start = reinterpret_cast<uint32_t*>(ws + o_pstart);
+    pb.len1 = reinterpret_cast<uint32_t*>(ws + o_len1);
+    pb.len2 = reinterpret_cast<uint32_t*>(ws + o_len2);
+    pb.blkpre1 = reinterpret_cast<uint32_t*>(ws + o_pre1);
+    pb.blkpre2 = reinterpret_cast<uint32_t*>(ws + o_pre2);
+    pb.sq = reinterpret_cast<unsigned long long*>(ws + o_sq);
+    pb.fully = reinterpret_cast<uint8_t*>(ws + o_fully);
+    pb.totals = reinterpret_cast<unsigned long long*>(ws + o_totals);
+    float* lut = reinterpret_cast<float*>(ws + o_lut);
+    uint2* cand = reinterpret_cast<uint2*>(ws + o_cand);
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + o_cnt);
+    float* tau = reinterpret_cast<float*>(ws + o_tau);
+    uint32_t* spos = reinterpret_cast<uint32_t*>(ws + o_spos);
+    float* sest = reinterpret_cast<float*>(ws + o_sest);
+    int32_t* sn = reinterpret_cast<int32_t*>(ws + o_sn);
+    int32_t* over = reinterpret_cast<int32_t*>(ws + o_over);
+    int32_t* overtot = reinterpret_cast<int32_t*>(ws + o_overtot);
+    uint64_t* rkeys = reinterpret_cast<uint64_t*>(ws + o_rkeys);
+    float* sref = reinterpret_cast<float*>(ws + o_sref);
+    int32_t* sids = reinterpret_cast<int32_t*>(ws + o_sids);
+
+    std::vector<EventPair> events;
+    auto mark = [&](int kind, bool begin) -> int {
+        if (!ix->profiling) return IVFR_OK;
+        if (begin) {
+            EventPair ep;
+            ep.kind = kind;
+            IVFR_HIP(hipEventCreate(&ep.a));
+            IVFR_HIP(hipEventCreate(&ep.b));
+            IVFR_HIP(hipEventRecord(ep.a, st));
+            events.push_back(ep);
+        } else {
+            IVFR_HIP(hipEventRecord(events.back().b, st));
+        }
+        return IVFR_OK;
+    };
+
+    for (int64_t q0 = 0; q0 < nq; q0 += B) {
+        const int nb = (int)std::min<int64_t>(B, nq - q0);
+        const int Pb = nb * w;
+        const float* X = queries + q0 * d;
+        // visited lists: the w nearest coarse centroids
+        IVFR_TRY(ivfr_launch_row_norms(X, nb, d, xnorm, st));
+        IVFR_TRY(ivfr_launch_dist_keys(X, xnorm, nb, ix->coarse, ix->coarse_norm, c, d, ckeys, st));
+        {
+            SelectArgs a;
+            a.nseg = nb; a.K = w; a.keys = ckeys; a.seg_stride = c; a.fixed_count = c;
+            IVFR_TRY(ivfr_launch_select_sorted(a, nullptr, 0, probe, probed, st));
+        }
+        IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, n_sample, pb, st));
+        IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, st));
+        // sample pass: keep everything
+        IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
+        IVFR_HIP(hipMemsetAsync(overtot, 0, 4 * sizeof(int32_t), st));
+        hipLaunchKernelGGL(fill_f32_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, tau, (int64_t)nb, INFINITY);
+        IVFR_TRY(mark(0, true));
+        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len1, pb.blkpre1, Pb, w, tau, cand, cnt, cap, cap, groups, st));
+        IVFR_TRY(mark(0, false));
+        {
+            SelectArgs a;
+            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.seg_stride = cap; a.counts = cnt; a.cap = cap;
+            IVFR_TRY(ivfr_launch_select_tau(a, pb.fully, tau, st));
+        }
+        hipLaunchKernelGGL(reset_counts_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, cnt, pb.fully, nb);
+        // filtered pass over every visited entry
+        IVFR_TRY(mark(1, true));
+        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len2, pb.blkpre2, Pb, w, tau, cand, cnt, cap, cap, groups, st));
+        IVFR_TRY(mark(1, false));
+        {
+            SelectArgs a;
+            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.seg_stride = cap; a.counts = cnt; a.cap = cap;
+            IVFR_TRY(ivfr_launch_select_records(a, 0, spos, sest, sn, over, overtot, st));
+        }
+        // status read-back: overflow count and scanned totals
+        IVFR_HIP(hipMemcpyAsync(ix->h_status, overtot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+        IVFR_HIP(hipStreamSynchronize(st));
+        const int n_over = ix->h_status[0];
+        unsigned long long tot;
+        memcpy(&tot, ix->h_status + 2, sizeof(tot));
+        ix->st_codes += (int64_t)tot;
+        ix->st_pairs += Pb;
+        if (n_over > 0) {
+            // dense fallback, one query at a time: a buffer for every visited entry, no filter
+            std::vector<int32_t> h_over((size_t)nb);
+            std::vector<unsigned long long> h_sq((size_t)nb);
+            IVFR_HIP(hipMemcpy(h_over.data(), over, (size_t)nb * sizeof(int32_t), hipMemcpyDeviceToHost));
+            IVFR_HIP(hipMemcpy(h_sq.data(), pb.sq, (size_t)nb * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+            for (int q = 0; q < nb; ++q) {
+                if (!h_over[(size_t)q]) continue;
+                ix->st_dense += 1;
+                const uint64_t sqv = h_sq[(size_t)q];
+                IVFR_REQUIRE(sqv < 0xFFFFFFF0ull, "a query visits more than 2^32 entries");
+                const size_t bytes = (size_t)(sqv + 64) * sizeof(uint2) + 1024;
+                IVFR_TRY(ix->dense_ws.reserve(bytes));
+                uint32_t* dcnt = ix->dense_ws.as<uint32_t>();
+                float* dtau = reinterpret_cast<float*>(ix->dense_ws.as<char>() + 256);
+                uint32_t* dpre = reinterpret_cast<uint32_t*>(ix->dense_ws.as<char>() + 512);
+                uint2* dcand = reinterpret_cast<uint2*>(ix->dense_ws.as<char>() + 1024);
+                (void)dpre;
+                IVFR_HIP(hipMemsetAsync(dcnt, 0, sizeof(uint32_t), st));
+                hipLaunchKernelGGL(fill_f32_kernel, dim3(1), dim3(64), 0, st, dtau, (int64_t)1, INFINITY);
+                // the query's w pairs with their full lengths; block prefix computed on the host
+                std::vector<uint32_t> h_len((size_t)w), h_pre((size_t)w + 1, 0u);
+                IVFR_HIP(hipMemcpy(h_len.data(), pb.len2 + (size_t)q * w, (size_t)w * sizeof(uint32_t), hipMemcpyDeviceToHost));
+                for (int r = 0; r < w; ++r)
+                    h_pre[(size_t)r + 1] = h_pre[(size_t)r] + (h_len[(size_t)r] + IVFR_BLOCK - 1) / IVFR_BLOCK;
+                IVFR_HIP(hipMemcpy(pb.blkpre1, h_pre.data(), ((size_t)w + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
+                // pair p of this launch is pair q*w + p of the batch; with w pairs and divisor w the
+                // kernel's query index is 0, so tau / counter / buffer pointers are the dense ones
+                IVFR_TRY(ivfr_launch_scan(ix, lut + (size_t)q * w * m * IVFR_KS, pb.pair_start + (size_t)q * w,
+                                          pb.len2 + (size_t)q * w, pb.blkpre1, w, w, dtau, dcand, dcnt, 0,
+                                          (uint32_t)(sqv + 1), groups, st));
+                SelectArgs a;
+                a.nseg = 1; a.K = kprime; a.recs = dcand; a.ids = ix->ids; a.seg_stride = 0; a.counts = dcnt;
+                a.cap = (uint32_t)(sqv + 1);
+                IVFR_TRY(ivfr_launch_select_records(a, q, spos, sest, sn, nullptr, nullptr, st));
+            }
+        }
+        // re-rank and final top-k
+        IVFR_TRY(mark(2, true));
+        IVFR_TRY(ivfr_launch_rerank(ix, X, 0, nb, kprime, spos, sn, rkeys, sref, sids, st));
+        IVFR_TRY(mark(2, false));
+        {
+            SelectArgs a;
+            a.nseg = nb; a.K = k; a.keys = rkeys; a.seg_stride = kprime;
+            IVFR_TRY(ivfr_launch_select_sorted(a, sn, 0, ids_out + q0 * k, dist_out + q0 * k, st));
+        }
+        // optional trace outputs
+        if (probe_out) IVFR_HIP(hipMemcpyAsync(probe_out + q0 * w, probe, (size_t)Pb * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        if (probe_dist_out) IVFR_HIP(hipMemcpyAsync(probe_dist_out + q0 * w, probed, (size_t)Pb * sizeof(float), hipMemcpyDeviceToDevice, st));
+        const size_t sk = (size_t)nb * kprime;
+        if (short_ids_out) IVFR_HIP(hipMemcpyAsync(short_ids_out + q0 * kprime, sids, sk * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        if (short_ref_out) IVFR_HIP(hipMemcpyAsync(short_ref_out + q0 * kprime, sref, sk * sizeof(float), hipMemcpyDeviceToDevice, st));
+        if (short_est_out) IVFR_HIP(hipMemcpyAsync(short_est_out + q0 * kprime, sest, sk * sizeof(float), hipMemcpyDeviceToDevice, st));
+        if (short_count_out) IVFR_HIP(hipMemcpyAsync(short_count_out + q0, sn, (size_t)nb * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+        IVFR_HIP(hipStreamSynchronize(st));
+    }
+    for (auto& ep : events) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ep.a, ep.b) == hipSuccess) {
+            if (ep.kind == 0) ix->prof_sample_ms += ms;
+            else if (ep.kind == 1) { ix->prof_scan_ms += ms; ix->prof_scan_launches += 1; }
+            else ix->prof_rerank_ms += ms;
+        }
+        (void)hipEventDestroy(ep.a);
+        (void)hipEventDestroy(ep.b);
+    }
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t w, int32_t kprime, int32_t k,
+                           int32_t* ids_out, float* dist_out, void* stream) {
+    return ivfr_search_trace(ix, queries, nq, w, kprime, k, ids_out, dist_out, nullptr, nullptr, nullptr, nullptr,
+                             nullptr, nullptr, stream);
+}

@@ -1,0 +1,368 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs, the same codebooks and the same inverted file."""
+import numpy as np
+import pytest
+
+import synthdata as sd
+from oracle import ivfadcr_oracle as orc
+from helpers import REL_TOL, compare_results, init_draws, tiny_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def gpu_index_from_oracle(index, d=None):
+    """An ivfadcr Index holding exactly the oracle's codebooks and inverted file."""
+    import paper_1102_3828_amd as pkg
+    b = index.books
+    c, dd = b.coarse.shape
+    ix = pkg.Index(dd, c, b.pq.shape[0], b.m_refine)
+    ix.set_codebooks(b.coarse, b.pq, b.rq)
+    ix.import_(index.list_offsets, index.ids, index.codes, index.rcodes)
+    return ix
+
+
+def queries_dev(X):
+    torch = _torch()
+    return torch.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).cuda()
+
+
+def log(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ generator
+
+def test_hip_generator_matches_numpy():
+    from synthdata.gpu import DeviceMixture
+    for G, d, zipf in ((16, 32, None), (256, 128, None), (1024, 128, 1.1)):
+        mix = sd.make_mixture(G, d, zipf)
+        dm = DeviceMixture(mix)
+        for stream, start, n in ((sd.STREAM_TRAIN, 0, 5000), (sd.STREAM_BASE0 + 3, 123457, 3001)):
+            log("generator", G, d, zipf, stream, start, n)
+            ref = sd.gen_vectors(mix, stream, start, n)
+            got = dm.generate(stream, start, n).cpu().numpy()
+            assert np.array_equal(ref, got)
+
+
+# ------------------------------------------------------------------ stage-level parity
+
+@pytest.mark.parametrize("kw", [dict(), dict(m_refine=0), dict(d=64, m=8, m_refine=16, c=24, N=5000, n_train=3000)])
+def test_stages_against_oracle_trace(kw):
+    """Visited lists, short-list (ids, ADC estimates) and refined distances of every query."""
+    wl = tiny_workload(**kw)
+    index, X = wl["index"], wl["X"]
+    ix = gpu_index_from_oracle(index)
+    c = len(index.books.coarse)
+    for w, kp, k in ((3, 50, 10), (c, 200, 20), (1, 10 ** 4, 5), (2, 7, 7)):
+        log("stages", kw, w, kp, k)
+        ids, dist, t = ix.search(queries_dev(X), w, kp, k, trace=True)
+        t = {a: b.cpu().numpy() for a, b in t.items()}
+        inv = orc.entry_of_id(index)
+        for qi, x in enumerate(X):
+            o_ids, o_dist, tr = orc.search_one(x, index, w, kp, k)
+            # visited lists: identical unless two coarse distances nearly tie
+            if not np.array_equal(t["probe"][qi], tr.probe):
+                Dc = orc.sqdist(x[None].astype(np.float64), index.books.coarse)[0]
+                assert np.allclose(np.sort(Dc[t["probe"][qi]]), np.sort(tr.probe_d), rtol=REL_TOL)
+            assert np.allclose(t["probe_dist"][qi], tr.probe_d, rtol=REL_TOL, atol=1e-2)
+            # short-list: same members (it is unordered on the GPU side)
+            n = int(t["short_count"][qi])
+            assert n == len(tr.short_entries) == min(kp, tr.scanned)
+            g_ids = t["short_ids"][qi, :n]
+            o_short = index.ids[tr.short_entries]
+            diff = set(g_ids.tolist()) ^ set(o_short.tolist())
+            for i in diff:   # only near-ties of the k'-th estimate may differ
+                est = orc.adc_distance(x, index, int(inv[i]))
+                assert abs(est - tr.short_est[-1]) <= REL_TOL * tr.short_est[-1]
+            est_of = dict(zip(o_short.tolist(), tr.short_est.tolist()))
+            ref_of = dict(zip(o_short.tolist(), tr.short_refined.tolist()))
+            for s in range(n):
+                i = int(g_ids[s])
+                if i in est_of:
+                    assert abs(t["short_est"][qi, s] - est_of[i]) <= REL_TOL * max(est_of[i], 1.0)
+                    assert abs(t["short_ref"][qi, s] - ref_of[i]) <= REL_TOL * max(ref_of[i], 1.0)
+            assert (t["short_ids"][qi, n:] == -1).all()
+        exact, excused = compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, index, w, kp, k)
+        log("  exact", exact, "excused", excused)
+        assert excused <= 2
+    ix.close()
+
+
+def test_all_lists_full_shortlist_is_exact_over_reconstructions():
+    """w = c and k' = N: the GPU result is the exact k-NN among the refined reconstructions."""
+    from helpers import dense_reconstructions
+    wl = tiny_workload()
+    index, X = wl["index"], wl["X"]
+    ix = gpu_index_from_oracle(index)
+    dense = dense_reconstructions(index, refine=True)
+    ids, dist = ix.search(queries_dev(X), len(index.books.coarse), index.N, 25)
+    ids, dist = ids.cpu().numpy(), dist.cpu().numpy()
+    for qi, x in enumerate(X):
+        D = ((dense - x.astype(np.float64)) ** 2).sum(axis=1)
+        order = np.lexsort((index.ids, D))[:25]
+        assert ids[qi].tolist() == index.ids[order].tolist()
+        assert np.allclose(dist[qi], D[order], rtol=REL_TOL)
+    assert ix.search_stats()["codes_scanned"] == index.N * len(X)
+    ix.close()
+
+
+def test_lattice_database_returns_exact_neighbours():
+    rng = np.random.default_rng(5)
+    d, c, m, mr, N = 32, 6, 4, 8, 900
+    coarse = (rng.normal(size=(c, d)) * 100).astype(np.float32)
+    pq = (rng.normal(size=(m, 256, d // m)) * 2.0).astype(np.float32)
+    rq = (rng.normal(size=(mr, 256, d // mr)) * 1e-3).astype(np.float32)
+    books = orc.Codebooks(coarse, pq, rq)
+    Y = (coarse[rng.integers(0, c, N)].astype(np.float64) + orc.pq_decode(rng.integers(0, 256, (N, m)).astype(np.uint8), pq)
+         + orc.pq_decode(rng.integers(0, 256, (N, mr)).astype(np.uint8), rq))
+    lists, codes, rcodes = orc.encode(Y, books)
+    index = orc.assemble_index(lists, np.arange(N), codes, rcodes, books)
+    X = (rng.normal(size=(6, d)) * 100).astype(np.float32)
+    true_i, true_d = orc.brute_force(X.astype(np.float64), Y, 5)
+    ix = gpu_index_from_oracle(index)
+    ids, dist = ix.search(queries_dev(X), c, N, 5)
+    assert np.array_equal(ids.cpu().numpy(), true_i)
+    assert np.allclose(dist.cpu().numpy(), true_d, rtol=REL_TOL)
+    ix.close()
+
+
+# ------------------------------------------------------------------ end to end on workload-shaped data
+
+def _cfg_workload(cfg, N, n_train, n_query, iters=10):
+    mix = cfg.mixture()
+    T = sd.gen_vectors(mix, sd.STREAM_TRAIN, 0, n_train)
+    Y = sd.gen_base(mix, N)
+    X = sd.gen_vectors(mix, sd.STREAM_QUERY, 0, n_query)
+    return mix, T, Y, X
+
+
+def test_config0_end_to_end_gpu_built_index():
+    """The first workload (100k x 128-d, c = 256, m = m' = 8, w = 8, k' = 100, k = 10): the GPU trains,
+    encodes and searches; the oracle searches the exported index; brute force gives recall."""
+    import paper_1102_3828_amd as pkg
+    torch = _torch()
+    cfg = sd.CONFIGS["cfg0"]
+    mix, T, Y, X = _cfg_workload(cfg, cfg.N, cfg.n_train, cfg.n_query)
+    ix = pkg.Index(cfg.d, cfg.c, cfg.m, cfg.m_refine)
+    log("train")
+    ix.train(T, iters=10, seed=1)
+    log("add")
+    ix.add(torch.from_numpy(Y[:60000]).cuda(), 0)       # device input
+    ix.add(Y[60000:], 60000)                              # host input
+    ix.finalize()
+    assert ix.ntotal == cfg.N
+    coarse, pq, rq = ix.get_codebooks()
+    offsets, ids, codes, rcodes = ix.export()
+    index = orc.Index(orc.Codebooks(coarse, pq, rq), offsets, ids, codes, rcodes)
+    assert sorted(ids.tolist()) == list(range(cfg.N))
+    for l in range(cfg.c):
+        assert np.all(np.diff(ids[offsets[l]:offsets[l + 1]]) > 0)
+    log("encode parity")
+    sub_n = 20000      # the oracle's encoders on the first 20000 vectors (ids 0..19999)
+    keep = ids < sub_n
+    sub_off = np.concatenate([[0], np.cumsum([int(keep[offsets[l]:offsets[l + 1]].sum()) for l in range(cfg.c)])])
+    subst = check_encoding(Y[:sub_n], index.books, sub_off, ids[keep], codes[keep], rcodes[keep])
+    log("near-tie substitutions", subst)
+    assert subst <= 0.002 * sub_n * (1 + cfg.m + cfg.m_refine)
+    log("search parity")
+    g_ids, g_dist = ix.search(queries_dev(X), cfg.w, cfg.kprime, cfg.k)
+    g_ids, g_dist = g_ids.cpu().numpy(), g_dist.cpu().numpy()
+    exact, excused = compare_results(g_ids, g_dist, X, index, cfg.w, cfg.kprime, cfg.k)
+    log("exact", exact, "excused", excused)
+    assert exact >= 0.99 * cfg.n_query * cfg.k
+    true_i, _ = orc.brute_force(X, Y, 1)
+    r1, r10 = (orc.recall_at(g_ids, true_i[:, 0], r) for r in (1, 10))
+    log("recall@1", r1, "recall@10", r10)
+    o_ids, _, _ = orc.search(X, index, cfg.w, cfg.kprime, cfg.k)
+    assert abs(r10 - orc.recall_at(o_ids, true_i[:, 0], 10)) <= 0.02
+    assert r10 > 0.5
+    st = ix.search_stats()
+    assert st["pairs"] == cfg.n_query * cfg.w and st["dense_fallbacks"] == 0
+    ix.close()
+
+
+def test_gpu_training_quality_matches_oracle():
+    """k-means is chaotic, so trained codebooks are compared by their quantization error."""
+    import paper_1102_3828_amd as pkg
+    wl = tiny_workload(d=32, G=16, N=3000, n_train=4000, c=16, m=4, m_refine=8, iters=8)
+    T, Y = wl["T"], wl["Y"]
+    ix = pkg.Index(32, 16, 4, 8)
+    ix.train(T, iters=8, seed=3)
+    coarse, pq, rq = ix.get_codebooks()
+    gb = orc.Codebooks(coarse, pq, rq)
+
+    def errors(books):
+        lists, codes, rcodes = orc.encode(Y, books)
+        r1 = Y.astype(np.float64) - books.coarse[lists]
+        r2 = r1 - orc.pq_decode(codes, books.pq)
+        r3 = r2 - orc.pq_decode(rcodes, books.rq)
+        return [(r ** 2).sum(axis=1).mean() for r in (r1, r2, r3)]
+    eg, eo = errors(gb), errors(wl["books"])
+    log("gpu", eg, "oracle", eo)
+    for a, b in zip(eg, eo):
+        assert a < 1.1 * b
+    assert eg[0] > eg[1] > eg[2]
+    ix.close()
+
+
+def check_encoding(Y, books, offsets, ids, codes, rcodes, rel=REL_TOL):
+    """GPU encoding of vectors Y (row i has id i) against the oracle's encoders: every choice must
+    be the oracle's argmin, or a near-tie of it under the oracle's float64 distances (Eq. (8):
+    the encoders are argmins).  Returns the number of near-tie substitutions."""
+    N = len(Y)
+    assert sorted(ids.tolist()) == list(range(N))
+    entry = np.empty(N, dtype=np.int64)
+    entry[ids] = np.arange(N)
+    g_list = np.searchsorted(offsets, entry, side="right") - 1
+    for l in range(len(offsets) - 1):
+        assert np.all(np.diff(ids[offsets[l]:offsets[l + 1]]) > 0)
+    Yf = Y.astype(np.float64)
+    o_list = orc.nearest(Yf, books.coarse)
+    subst = 0
+    bad = np.nonzero(g_list != o_list)[0]
+    for i in bad:
+        D = orc.sqdist(Yf[i:i + 1], books.coarse)[0]
+        assert D[g_list[i]] <= (1 + rel) * D[o_list[i]], ("list", i)
+    subst += len(bad)
+    # first-stage codes, given the GPU's own list choice
+    r1 = Yf - books.coarse[g_list].astype(np.float64)
+    g_codes = codes[entry]
+    o_codes = orc.pq_encode(r1, books.pq)
+    m, _, sub = books.pq.shape
+    for i, j in zip(*np.nonzero(g_codes != o_codes)):
+        dd = ((r1[i, j * sub:(j + 1) * sub][None] - books.pq[j].astype(np.float64)) ** 2).sum(axis=1)
+        assert dd[g_codes[i, j]] <= (1 + rel) * dd[o_codes[i, j]] + 1e-9, ("code", i, j)
+        subst += 1
+    if books.rq is not None:
+        r2 = r1 - orc.pq_decode(g_codes, books.pq)
+        g_r = rcodes[entry]
+        o_r = orc.pq_encode(r2, books.rq)
+        mr, _, subr = books.rq.shape
+        for i, j in zip(*np.nonzero(g_r != o_r)):
+            dd = ((r2[i, j * subr:(j + 1) * subr][None] - books.rq[j].astype(np.float64)) ** 2).sum(axis=1)
+            assert dd[g_r[i, j]] <= (1 + rel) * dd[o_r[i, j]] + 1e-9, ("rcode", i, j)
+            subst += 1
+    return subst
+
+
+def test_encode_parity_with_oracle_codebooks():
+    import paper_1102_3828_amd as pkg
+    wl = tiny_workload(d=64, m=8, m_refine=16, c=24, N=5000, n_train=3000)
+    b, Y = wl["books"], wl["Y"]
+    ix = pkg.Index(64, 24, 8, 16)
+    ix.set_codebooks(b.coarse, b.pq, b.rq)
+    ix.add(Y[:1234], 0)
+    ix.add(Y[1234:1234], 1234)      # empty add
+    ix.add(Y[1234:], 1234)
+    ix.finalize()
+    offsets, ids, codes, rcodes = ix.export()
+    subst = check_encoding(Y, b, offsets, ids, codes, rcodes)
+    log("near-tie substitutions", subst)
+    assert subst <= 0.002 * Y.shape[0] * (1 + 8 + 16)
+    ix.close()
+
+
+# ------------------------------------------------------------------ edge cases and host logic
+
+def test_edge_cases_and_internal_paths():
+    wl = tiny_workload(d=64, m=8, m_refine=16, c=24, N=5000, n_train=3000)
+    index, X = wl["index"], wl["X"]
+    torch = _torch()
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    base_ids, base_dist = (t.cpu().numpy() for t in ix.search(xq, 6, 300, 20))
+    compare_results(base_ids, base_dist, X, index, 6, 300, 20)
+    # run twice: identical bits
+    again = ix.search(xq, 6, 300, 20)
+    assert np.array_equal(base_ids, again[0].cpu().numpy()) and np.array_equal(base_dist, again[1].cpu().numpy())
+    # batches of 5 queries give the same answer
+    ix.set_tuning(batch=5)
+    b_ids, b_dist = ix.search(xq, 6, 300, 20)
+    assert np.array_equal(base_ids, b_ids.cpu().numpy()) and np.array_equal(base_dist, b_dist.cpu().numpy())
+    # a candidate buffer far too small forces the dense fallback; same answer
+    ix.set_tuning(sample_mult=1, cap_mult=1, batch=1024)
+    f_ids, f_dist = ix.search(xq, 6, 300, 20)
+    log("dense fallbacks", ix.search_stats())
+    assert ix.search_stats()["dense_fallbacks"] > 0
+    assert np.array_equal(base_ids, f_ids.cpu().numpy()) and np.array_equal(base_dist, f_dist.cpu().numpy())
+    # a large sample covers everything in the first pass
+    ix.set_tuning(sample_mult=1000, cap_mult=1000)
+    s_ids, s_dist = ix.search(xq, 6, 300, 20)
+    assert np.array_equal(base_ids, s_ids.cpu().numpy()) and np.array_equal(base_dist, s_dist.cpu().numpy())
+    ix.set_tuning(sample_mult=4, cap_mult=16, scan_groups=3)
+    g_ids, _ = ix.search(xq, 6, 300, 20)
+    assert np.array_equal(base_ids, g_ids.cpu().numpy())
+    # no queries
+    e_ids, e_dist = ix.search(xq[:0], 6, 300, 20)
+    assert e_ids.shape == (0, 20)
+    # non-default stream
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        t_ids, _ = ix.search(xq, 6, 300, 20)
+    assert np.array_equal(base_ids, t_ids.cpu().numpy())
+    ix.close()
+
+
+def test_empty_lists_and_short_results():
+    """More lists than vectors: most lists are empty; k exceeds what the visited lists hold."""
+    rng = np.random.default_rng(11)
+    d, c, m, mr, N = 32, 64, 4, 4, 40
+    books = orc.Codebooks((rng.normal(size=(c, d)) * 50).astype(np.float32),
+                          (rng.normal(size=(m, 256, d // m)) * 5).astype(np.float32),
+                          (rng.normal(size=(mr, 256, d // mr))).astype(np.float32))
+    Y = rng.normal(size=(N, d)) * 50
+    index = orc.build_index(Y, np.arange(N), books)
+    X = (rng.normal(size=(9, d)) * 50).astype(np.float32)
+    ix = gpu_index_from_oracle(index)
+    for w, kp, k in ((5, 30, 30), (64, 100, 50), (1, 1, 1)):
+        ids, dist = ix.search(queries_dev(X), w, kp, k)
+        compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, index, w, kp, k)
+    ix.close()
+    # an index with no vectors at all
+    import paper_1102_3828_amd as pkg
+    ix = pkg.Index(d, c, m, mr)
+    ix.set_codebooks(books.coarse, books.pq, books.rq)
+    ix.finalize()
+    ids, dist = ix.search(queries_dev(X), 3, 10, 5)
+    assert (ids.cpu().numpy() == -1).all() and np.isinf(dist.cpu().numpy()).all()
+    ix.close()
+
+
+def test_error_paths():
+    import paper_1102_3828_amd as pkg
+    torch = _torch()
+    wl = tiny_workload()
+    index, X = wl["index"], wl["X"]
+    b = index.books
+    ix = pkg.Index(32, 8, 4, 4)
+    xq = queries_dev(X)
+    with pytest.raises(pkg.IvfrError) as e:
+        ix.add(wl["Y"][:10], 0)
+    assert e.value.code == pkg.binding.ERR_STATE
+    ix.set_codebooks(b.coarse, b.pq, b.rq)
+    with pytest.raises(pkg.IvfrError) as e:
+        ix.search(xq, 2, 10, 5)
+    assert e.value.code == pkg.binding.ERR_STATE
+    ix.add(wl["Y"][:100], 0)
+    with pytest.raises(pkg.IvfrError) as e:
+        ix.add(wl["Y"][:100], 50)       # overlapping ids
+    assert e.value.code == pkg.binding.ERR_INVALID_ARG
+    with pytest.raises(pkg.IvfrError) as e:
+        ix.set_codebooks(b.coarse, b.pq, b.rq)
+    assert e.value.code == pkg.binding.ERR_STATE
+    ix.finalize()
+    with pytest.raises(pkg.IvfrError) as e:
+        ix.add(wl["Y"][:10], 1000)
+    assert e.value.code == pkg.binding.ERR_STATE
+    for w, kp, k in ((0, 10, 5), (9, 10, 5), (2, 0, 0), (2, 5, 6)):
+        with pytest.raises(pkg.IvfrError) as e:
+            ix.search(xq, w, kp, k)
+        assert e.value.code == pkg.binding.ERR_INVALID_ARG
+    ids, _ = ix.search(xq, 2, 10, 5)    # still usable after errors
+    assert ids.shape == (len(X), 5)
+    ix.close()
