@@ -111,7 +111,7 @@ int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* 
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
  *   sample_mult (4)   step 1 first scans about sample_mult*k' entries of the nearest lists to
  *                     bound the k'-th smallest estimate, then filters the full scan by it
- *   cap_mult    (16)  per-query candidate buffer = cap_mult*k' entries (>= sample + 512)
+ *   cap_mult    (16)  per-query candidate buffer = max(cap_mult, sample_mult)*k' entries
  *   batch       (1024) queries processed per internal batch
  *   scan_groups (0 = auto) workgroups launched by the list-scan kernel                      */
 int ivfr_set_tuning(ivfr_index* index, int32_t sample_mult, int32_t cap_mult, int32_t batch, int32_t scan_groups);

@@ -10,6 +10,8 @@ import ctypes
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- must be loaded first: the library binds to the HIP runtime that PyTorch ships, so
+#                              that device pointers of torch tensors are valid inside it (one runtime per process)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libivfadcr.so")

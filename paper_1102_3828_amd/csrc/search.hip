@@ -73,7 +73,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const int B = (int)std::min<int64_t>(nq, ix->batch);
     const int P = B * w;
     const uint32_t n_sample = (uint32_t)std::min<int64_t>((int64_t)ix->sample_mult * kprime, 1ll << 30);
-    const uint32_t cap = (uint32_t)std::max<int64_t>((int64_t)ix->cap_mult * kprime, (int64_t)n_sample + IVFR_BLOCK);
+    const uint32_t cap = (uint32_t)std::max<int64_t>((int64_t)ix->cap_mult * kprime, (int64_t)n_sample);
     const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 8;
 
     // carve the workspace

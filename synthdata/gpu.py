@@ -5,6 +5,7 @@ import ctypes
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- loaded before the HIP library so both share PyTorch's HIP runtime
 
 from . import gen
 
