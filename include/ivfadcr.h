@@ -109,19 +109,31 @@ int ivfr_search_trace(ivfr_index* index, const float* queries, int64_t nq, int32
 int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks);
 
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
- *   sample_mult (4)   step 1 first scans about sample_mult*k' entries of the nearest lists to
- *                     bound the k'-th smallest estimate, then filters the full scan by it
- *   cap_mult    (16)  per-query candidate buffer = max(cap_mult, sample_mult)*k' entries
+ *   full_mult   (8)    a query that visits at most full_mult*k' entries keeps every estimate; a
+ *                      larger one first scores a uniform sample of its entries to bound the k'-th
+ *                      smallest estimate and keeps only estimates below the bound
+ *   cap_mult    (16)   per-query candidate buffer = max(cap_mult*k', min_cap) entries
+ *   min_cap     (8192) see cap_mult
  *   batch       (1024) queries processed per internal batch
- *   scan_groups (0 = auto) workgroups launched by the list-scan kernel                      */
-int ivfr_set_tuning(ivfr_index* index, int32_t sample_mult, int32_t cap_mult, int32_t batch, int32_t scan_groups);
+ *   scan_groups (0 = 8 per compute unit) workgroups launched by the list-scan kernel          */
+int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int32_t min_cap, int32_t batch,
+                    int32_t scan_groups);
 
-/* Average duration in milliseconds of the list-scan kernel launches (the filtered full
- * scan) of the most recent search call, measured with HIP events on the search stream, and
- * their number.  Timing is recorded only after ivfr_set_profiling(index, 1). */
+/* Per-stage GPU time of the most recent search call, in milliseconds, measured with HIP events
+ * on the search stream (recorded only after ivfr_set_profiling(index, 1)).  ms: host double
+ * [IVFR_N_STAGES], indexed by IVFR_STAGE_*; scan_launches: launches of the list-scan kernel
+ * (stage IVFR_STAGE_SCAN is exactly those launches), may be NULL. */
+#define IVFR_STAGE_COARSE    0   /* query norms + coarse distance GEMM                        */
+#define IVFR_STAGE_PROBE     1   /* w nearest lists + plan of (query, list) pairs             */
+#define IVFR_STAGE_LUT       2   /* look-up tables of Eq. (5)                                 */
+#define IVFR_STAGE_SAMPLE    3   /* sample scoring + bound selection                          */
+#define IVFR_STAGE_SCAN      4   /* ADC list scan                                             */
+#define IVFR_STAGE_SHORTLIST 5   /* exact k' smallest of the survivors                        */
+#define IVFR_STAGE_RERANK    6   /* Eq. (9)-(10) over the short-list                          */
+#define IVFR_STAGE_FINAL     7   /* k smallest refined distances, sorted                      */
+#define IVFR_N_STAGES        8
 int ivfr_set_profiling(ivfr_index* index, int32_t enable);
-int ivfr_scan_profile(const ivfr_index* index, double* scan_ms_total, int32_t* scan_launches,
-                      double* rerank_ms_total, double* sample_ms_total);
+int ivfr_stage_times(const ivfr_index* index, double* ms, int32_t* scan_launches);
 
 const char* ivfr_last_error(void);
 

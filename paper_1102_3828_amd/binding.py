@@ -50,10 +50,9 @@ def _load():
         "ivfr_search": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp]),
         "ivfr_search_trace": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ivfr_search_stats": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]),
-        "ivfr_set_tuning": (ctypes.c_int, [vp, i32, i32, i32, i32]),
+        "ivfr_set_tuning": (ctypes.c_int, [vp, i32, i32, i32, i32, i32]),
         "ivfr_set_profiling": (ctypes.c_int, [vp, i32]),
-        "ivfr_scan_profile": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32),
-                                             ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]),
+        "ivfr_stage_times": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]),
         "ivfr_last_error": (ctypes.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -65,7 +64,7 @@ def _load():
 lib = _load()
 EXPORTED = ["ivfr_create", "ivfr_destroy", "ivfr_train", "ivfr_set_codebooks", "ivfr_get_codebooks", "ivfr_add",
             "ivfr_finalize", "ivfr_ntotal", "ivfr_export", "ivfr_import", "ivfr_search", "ivfr_search_trace",
-            "ivfr_search_stats", "ivfr_set_tuning", "ivfr_set_profiling", "ivfr_scan_profile", "ivfr_last_error"]
+            "ivfr_search_stats", "ivfr_set_tuning", "ivfr_set_profiling", "ivfr_stage_times", "ivfr_last_error"]
 
 
 def _check(rc):
@@ -198,14 +197,19 @@ class Index:
         _check(lib.ivfr_search_stats(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
         return dict(codes_scanned=a.value, pairs=b.value, dense_fallbacks=c.value)
 
-    def set_tuning(self, sample_mult=0, cap_mult=0, batch=0, scan_groups=0):
-        _check(lib.ivfr_set_tuning(self._h, sample_mult, cap_mult, batch, scan_groups))
+    def set_tuning(self, full_mult=0, cap_mult=0, min_cap=0, batch=0, scan_groups=0):
+        _check(lib.ivfr_set_tuning(self._h, full_mult, cap_mult, min_cap, batch, scan_groups))
 
     def set_profiling(self, enable=True):
         _check(lib.ivfr_set_profiling(self._h, 1 if enable else 0))
 
-    def scan_profile(self):
-        ms, n = ctypes.c_double(), ctypes.c_int32()
-        rr, sm = ctypes.c_double(), ctypes.c_double()
-        _check(lib.ivfr_scan_profile(self._h, ctypes.byref(ms), ctypes.byref(n), ctypes.byref(rr), ctypes.byref(sm)))
-        return dict(scan_ms=ms.value, scan_launches=n.value, rerank_ms=rr.value, sample_ms=sm.value)
+    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final")
+
+    def stage_times(self):
+        """Per-stage milliseconds of the last search (after set_profiling) and scan launch count."""
+        ms = (ctypes.c_double * len(self.STAGES))()
+        n = ctypes.c_int32()
+        _check(lib.ivfr_stage_times(self._h, ms, ctypes.byref(n)))
+        out = dict(zip(self.STAGES, [float(v) for v in ms]))
+        out["scan_launches"] = n.value
+        return out

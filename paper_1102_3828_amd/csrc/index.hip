@@ -466,12 +466,15 @@ extern "C" int ivfr_import(ivfr_index* ix, int64_t N, const int64_t* list_offset
     return IVFR_OK;
 }
 
-extern "C" int ivfr_set_tuning(ivfr_index* ix, int32_t sample_mult, int32_t cap_mult, int32_t batch, int32_t scan_groups) {
+extern "C" int ivfr_set_tuning(ivfr_index* ix, int32_t full_mult, int32_t cap_mult, int32_t min_cap, int32_t batch,
+                               int32_t scan_groups) {
     IVFR_REQUIRE(ix, "ivfr_set_tuning: null index");
-    IVFR_REQUIRE(sample_mult >= 0 && cap_mult >= 0 && batch >= 0 && scan_groups >= 0, "tuning values must be >= 0");
+    IVFR_REQUIRE(full_mult >= 0 && cap_mult >= 0 && min_cap >= 0 && batch >= 0 && scan_groups >= 0,
+                 "tuning values must be >= 0");
     IVFR_REQUIRE(batch <= 65535, "batch = %d exceeds 65535", batch);
-    if (sample_mult) ix->sample_mult = sample_mult;
+    if (full_mult) ix->full_mult = full_mult;
     if (cap_mult) ix->cap_mult = cap_mult;
+    if (min_cap) ix->min_cap = min_cap;
     if (batch) ix->batch = batch;
     ix->scan_groups = scan_groups;
     return IVFR_OK;
@@ -483,13 +486,10 @@ extern "C" int ivfr_set_profiling(ivfr_index* ix, int32_t enable) {
     return IVFR_OK;
 }
 
-extern "C" int ivfr_scan_profile(const ivfr_index* ix, double* scan_ms_total, int32_t* scan_launches,
-                                 double* rerank_ms_total, double* sample_ms_total) {
-    IVFR_REQUIRE(ix, "ivfr_scan_profile: null index");
-    if (scan_ms_total) *scan_ms_total = ix->prof_scan_ms;
+extern "C" int ivfr_stage_times(const ivfr_index* ix, double* ms, int32_t* scan_launches) {
+    IVFR_REQUIRE(ix && ms, "ivfr_stage_times: null argument");
+    for (int i = 0; i < IVFR_N_STAGES; ++i) ms[i] = ix->prof_ms[i];
     if (scan_launches) *scan_launches = ix->prof_scan_launches;
-    if (rerank_ms_total) *rerank_ms_total = ix->prof_rerank_ms;
-    if (sample_ms_total) *sample_ms_total = ix->prof_sample_ms;
     return IVFR_OK;
 }
 

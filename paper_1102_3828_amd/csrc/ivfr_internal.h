@@ -11,6 +11,7 @@
 
 #define IVFR_KS 256            // reproduction values per sub-quantizer (8 bits)
 #define IVFR_LIST_ALIGN 32u    // every inverted list starts at a multiple of 32 entries
+#define IVFR_GRANULE 8u        // entries per sample granule
 #define IVFR_BLOCK 512u        // entries per scan block: one 16-byte load per thread of a 256-thread group
 #define IVFR_TAIL_PAD 1024u    // zero entries after the last list so vector loads never run off the end
 
@@ -109,7 +110,8 @@ struct ivfr_index {
     std::vector<uint32_t> h_start;   // padded starts [c+1] (host)
 
     // tuning
-    int sample_mult = 4, cap_mult = 16, batch = 1024, scan_groups = 0;
+    int full_mult = 8, cap_mult = 16, batch = 1024, scan_groups = 0;
+    int min_cap = 8192;
 
     // scratch
     DevBuf search_ws, encode_ws, dense_ws;
@@ -118,7 +120,7 @@ struct ivfr_index {
     // stats of the last search
     int64_t st_codes = 0, st_pairs = 0, st_dense = 0;
     bool profiling = false;
-    double prof_scan_ms = 0, prof_rerank_ms = 0, prof_sample_ms = 0;
+    double prof_ms[IVFR_N_STAGES] = {0};
     int prof_scan_launches = 0;
     int n_cu = 256;
 };
@@ -153,25 +155,31 @@ struct SelectArgs {
     const uint32_t* counts = nullptr;
     uint32_t cap = 0;
 };
-// pivot only: tau[seg] = estimate of the K-th smallest record (+inf when fewer than K); skip[seg] != 0 leaves tau alone
-int ivfr_launch_select_tau(const SelectArgs& a, const uint8_t* skip, float* tau, hipStream_t st);
+// Bound on the k'-th smallest estimate of each query from its uniform sample (a.counts records of the
+// query's sq visited entries): tau = the r-th smallest sampled estimate, r = mu + 5 sqrt(mu) + 6 with
+// mu = k' * sampled / sq the expected number of the true k' best inside the sample (+inf when the
+// sample holds fewer than r).  skip[seg] != 0 leaves tau alone.
+int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, const uint8_t* skip,
+                           float* tau, hipStream_t st);
 int ivfr_select_init();   // one-time function attributes
 
-// Search plan, look-up tables, list scan (scan.hip)
+// Search plan, look-up tables, sample and list scan (scan.hip)
 struct PlanBuffers {
     uint32_t* pair_start;  // [P] first padded entry of the pair's list
-    uint32_t* len1;        // [P] entries of the pair scanned by the sample pass
-    uint32_t* len2;        // [P] entries scanned by the filtered pass (0 if the query was fully sampled)
-    uint32_t* blkpre1;     // [P+1] exclusive prefix of blocks, sample pass
-    uint32_t* blkpre2;     // [P+1] same, filtered pass
+    uint32_t* len;         // [P] entries of the pair's list
+    uint32_t* blkpre;      // [P+1] exclusive prefix of scan blocks over the pairs
+    uint32_t* gpre;        // [nq, w+1] per query: exclusive prefix of sample granules over its pairs
+    uint32_t* stride;      // [nq] every stride-th granule of the query is sampled
     unsigned long long* sq;      // [nq] entries in the query's visited lists
-    uint8_t* fully;              // [nq] 1 = the sample pass covered every visited entry
+    uint8_t* fully;              // [nq] 1 = few enough entries to keep them all (no sample, tau = +inf)
     unsigned long long* totals;  // [2]: [0] = sum of sq
 };
-int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t n_sample,
-                     const PlanBuffers& pb, hipStream_t st);
+int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
+                     uint32_t stride_k, uint32_t max_sample_granules, const PlanBuffers& pb, hipStream_t st);
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
                     float* lut, hipStream_t st);
+int ivfr_launch_sample(const ivfr_index* ix, const float* lut, const PlanBuffers& pb, int nq, int w, uint2* cand,
+                       uint32_t* cand_cnt, uint64_t cand_stride, uint32_t cap, int ychunks, hipStream_t st);
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
                      uint64_t cand_stride, uint32_t cap, int groups, hipStream_t st);

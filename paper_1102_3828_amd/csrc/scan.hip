@@ -5,88 +5,79 @@
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // ------------------------------------------------------------------------------------------
-// Plan.  Pair p = q * w + r is the r-th nearest list of query q.  The scan runs twice:
-//  pass 1 ("sample") covers the first ~n_sample entries of the query's nearest lists and keeps
-//         every estimate; the k'-th smallest of them bounds the k'-th smallest overall;
-//  pass 2 covers every visited entry and keeps only estimates <= that bound.
-// A query whose visited lists hold no more than n_sample entries is finished by pass 1.
+// Plan.  Pair p = q * w + r is the r-th nearest list of query q.  Per query the plan fixes how
+// the k'-th smallest estimate is bounded before the scan:
+//  - a query whose visited lists hold at most `full_limit` entries keeps every estimate
+//    (tau = +inf) and is selected from directly;
+//  - otherwise a uniform sample of the visited entries is scored first: the lists' entries
+//    form one virtual stream of 8-entry granules (64 code bytes at m = 8) and every stride-th
+//    granule is taken, stride = k' / mu so that about mu of the true k' best fall in the sample.
 // ------------------------------------------------------------------------------------------
 __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int w,
                                   const uint32_t* __restrict__ list_start, const uint32_t* __restrict__ list_len,
-                                  uint32_t n_sample, PlanBuffers pb) {
+                                  uint32_t full_limit, uint32_t stride_k, uint32_t max_sample_granules,
+                                  PlanBuffers pb) {
     int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nq) return;
-    unsigned long long total = 0;
-    for (int r = 0; r < w; ++r) total += list_len[probe[(int64_t)q * w + r]];
-    const bool fully = total <= n_sample;
-    pb.sq[q] = total;
-    pb.fully[q] = fully ? 1 : 0;
-    atomicAdd(pb.totals, total);
-    unsigned long long cum = 0;
+    unsigned long long total = 0, gran = 0;
+    uint32_t* gp = pb.gpre + (int64_t)q * (w + 1);
     for (int r = 0; r < w; ++r) {
         int64_t p = (int64_t)q * w + r;
         int l = probe[p];
         uint32_t len = list_len[l];
-        uint32_t s;
-        if (fully) s = len;
-        else {
-            unsigned long long room = (cum < n_sample) ? (n_sample - cum) : 0ull;
-            s = (room < len) ? (uint32_t)room : len;
-        }
-        cum += s;
         pb.pair_start[p] = list_start[l];
-        pb.len1[p] = s;
-        pb.len2[p] = fully ? 0u : len;
+        pb.len[p] = len;
+        gp[r] = (uint32_t)gran;
+        total += len;
+        gran += (len + IVFR_GRANULE - 1) / IVFR_GRANULE;
     }
+    gp[w] = (uint32_t)gran;
+    const bool fully = total <= full_limit;
+    pb.sq[q] = total;
+    pb.fully[q] = fully ? 1 : 0;
+    uint32_t stride = stride_k;
+    const unsigned long long need = (gran + max_sample_granules - 1) / max_sample_granules;   // keeps the sample inside the buffer
+    if (need > stride) stride = (uint32_t)need;
+    if (stride < 1) stride = 1;
+    pb.stride[q] = stride;
+    atomicAdd(pb.totals, total);
 }
 
-// Exclusive prefix sums of ceil(len / IVFR_BLOCK) over the P pairs, for both passes (one workgroup).
+// Exclusive prefix sum of ceil(len / IVFR_BLOCK) over the P pairs (one workgroup).
 __global__ __launch_bounds__(1024) void plan_scan_kernel(int P, PlanBuffers pb) {
-    __shared__ uint32_t wtot[2][16];
-    __shared__ uint32_t carry[2];
+    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t carry;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid < 2) carry[tid] = 0;
+    if (tid == 0) carry = 0;
     __syncthreads();
     for (int base = 0; base < P; base += 1024) {
         int p = base + tid;
-        uint32_t v[2] = {0, 0};
-        if (p < P) {
-            v[0] = (pb.len1[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
-            v[1] = (pb.len2[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
-        }
-        uint32_t inc[2] = {v[0], v[1]};
+        uint32_t v = 0;
+        if (p < P) v = (pb.len[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
+        uint32_t inc = v;
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                uint32_t o = __shfl_up(inc[a], off, 64);
-                if (lane >= off) inc[a] += o;
-            }
-            if (lane == 63) wtot[a][wv] = inc[a];
+        for (int off = 1; off < 64; off <<= 1) {
+            uint32_t o = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += o;
         }
+        if (lane == 63) wtot[wv] = inc;
         __syncthreads();
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            uint32_t add = carry[a];
-            for (int x = 0; x < wv; ++x) add += wtot[a][x];
-            inc[a] += add;
-        }
-        if (p < P) {
-            pb.blkpre1[p] = inc[0] - v[0];
-            pb.blkpre2[p] = inc[1] - v[1];
-        }
+        uint32_t add = carry;
+        for (int x = 0; x < wv; ++x) add += wtot[x];
+        inc += add;
+        if (p < P) pb.blkpre[p] = inc - v;
         __syncthreads();
-        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; }
+        if (tid == 1023) carry = inc;
         __syncthreads();
     }
-    if (tid == 0) { pb.blkpre1[P] = carry[0]; pb.blkpre2[P] = carry[1]; }
+    if (tid == 0) pb.blkpre[P] = carry;
 }
 
-int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t n_sample,
-                     const PlanBuffers& pb, hipStream_t st) {
+int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
+                     uint32_t stride_k, uint32_t max_sample_granules, const PlanBuffers& pb, hipStream_t st) {
     IVFR_HIP(hipMemsetAsync(pb.totals, 0, 2 * sizeof(unsigned long long), st));
     hipLaunchKernelGGL(plan_pairs_kernel, dim3((nq + 127) / 128), dim3(128), 0, st, probe, nq, w, ix->list_start,
-                       ix->list_len, n_sample, pb);
+                       ix->list_len, full_limit, stride_k, max_sample_granules, pb);
     IVFR_HIP(hipGetLastError());
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, nq * w, pb);
     IVFR_HIP(hipGetLastError());
@@ -302,6 +293,94 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
             }
             append_records(in0 && est0 <= t, est0, start + e0, in1 && est1 <= t, est1, start + e0 + 1, qc, cnt, cap);
         }
+    }
+}
+
+// Sample pass: one thread scores one sampled granule of IVFR_GRANULE consecutive entries, reading
+// the pair's table from global memory (the sample is a small fraction of the scan), and the
+// wavefront appends its valid records to the query's buffer with one atomic.
+template <int M>
+__global__ __launch_bounds__(256) void adc_sample_kernel(const uint8_t* __restrict__ codes,
+                                                         const float* __restrict__ lut,
+                                                         const uint32_t* __restrict__ pair_start,
+                                                         const uint32_t* __restrict__ pair_len,
+                                                         const uint32_t* __restrict__ gpre,
+                                                         const uint32_t* __restrict__ stride_q,
+                                                         const uint8_t* __restrict__ fully, int w,
+                                                         uint2* __restrict__ cand, uint32_t* __restrict__ cand_cnt,
+                                                         uint64_t cand_stride, uint32_t cap) {
+    const int q = blockIdx.x;
+    if (fully[q]) return;
+    const uint32_t* gp = gpre + (int64_t)q * (w + 1);
+    const uint32_t G = gp[w], st = stride_q[q], off = st >> 1;
+    const uint32_t nsg = G > off ? (G - off + st - 1) / st : 0u;
+    uint2* qc = cand + (uint64_t)q * cand_stride;
+    uint32_t* cnt = cand_cnt + q;
+    const int lane = threadIdx.x & 63;
+    for (uint32_t j0 = blockIdx.y * 256u; j0 < nsg; j0 += gridDim.y * 256u) {
+        const uint32_t j = j0 + threadIdx.x;
+        float est[IVFR_GRANULE];
+        uint32_t nvalid = 0, pos0 = 0;
+        if (j < nsg) {
+            const uint32_t g = off + j * st;
+            int lo = 0, hi = w;   // last r with gp[r] <= g
+            while (hi - lo > 1) {
+                int mid = (lo + hi) >> 1;
+                if (gp[mid] <= g) lo = mid; else hi = mid;
+            }
+            const int64_t p = (int64_t)q * w + lo;
+            const uint32_t e0 = (g - gp[lo]) * IVFR_GRANULE, len = pair_len[p], start = pair_start[p];
+            nvalid = len - e0 < IVFR_GRANULE ? len - e0 : IVFR_GRANULE;
+            pos0 = start + e0;
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + (uint64_t)pos0 * M);
+            const float* T = lut + p * M * IVFR_KS;
+#pragma unroll
+            for (int t = 0; t < IVFR_GRANULE; ++t) {
+                uint32_t wds[M / 4];
+#pragma unroll
+                for (int x = 0; x < M / 4; ++x) wds[x] = src[t * (M / 4) + x];
+                est[t] = adc_sum<M>(T, wds);
+            }
+        }
+        // wavefront-aggregated append
+        uint32_t inc = nvalid;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            uint32_t v = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += v;
+        }
+        const uint32_t total = __shfl(inc, 63, 64);
+        if (total == 0) continue;
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(cnt, total);
+        base = __shfl(base, 0, 64) + inc - nvalid;
+#pragma unroll
+        for (int t = 0; t < IVFR_GRANULE; ++t)
+            if ((uint32_t)t < nvalid && base + t < cap) qc[base + t] = make_uint2(__float_as_uint(est[t]), pos0 + t);
+    }
+}
+
+template <int M>
+static int launch_sample_m(const ivfr_index* ix, const float* lut, const PlanBuffers& pb, int nq, int w, uint2* cand,
+                           uint32_t* cand_cnt, uint64_t cand_stride, uint32_t cap, int ychunks, hipStream_t st) {
+    hipLaunchKernelGGL(adc_sample_kernel<M>, dim3(nq, ychunks), dim3(256), 0, st, ix->codes, lut, pb.pair_start,
+                       pb.len, pb.gpre, pb.stride, pb.fully, w, cand, cand_cnt, cand_stride, cap);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+int ivfr_launch_sample(const ivfr_index* ix, const float* lut, const PlanBuffers& pb, int nq, int w, uint2* cand,
+                       uint32_t* cand_cnt, uint64_t cand_stride, uint32_t cap, int ychunks, hipStream_t st) {
+    if (nq <= 0) return IVFR_OK;
+    switch (ix->p.m) {
+        case 4: return launch_sample_m<4>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
+        case 8: return launch_sample_m<8>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
+        case 16: return launch_sample_m<16>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
+        case 32: return launch_sample_m<32>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
+        case 64: return launch_sample_m<64>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
+        default:
+            ivfr_set_error("list scan supports m in {4, 8, 16, 32, 64}; got %d", ix->p.m);
+            return IVFR_ERR_INVALID_ARG;
     }
 }
 

@@ -2,20 +2,23 @@
 //
 // Per internal batch of queries, all on one stream and without host round trips until the end:
 //   coarse distances (MFMA) -> w nearest lists -> plan of (query, list) pairs -> look-up
-//   tables (MFMA) -> sample scan -> per-query bound tau on the k'-th smallest estimate ->
-//   filtered scan of every visited entry -> exact k' smallest -> re-rank -> k smallest.
-// The bound is the k'-th smallest estimate among the first entries of the nearest lists: the
-// k'-th smallest of any subset can only be larger than the k'-th smallest overall, so filtering
-// by it loses nothing.  If a query's survivors overflow its candidate buffer (reported by the
-// device counter, read back once per batch), that query is redone through a buffer that holds
-// every visited entry.
+//   tables (MFMA) -> uniform sample of the visited entries -> per-query bound tau on the k'-th
+//   smallest estimate -> scan of every visited entry keeping estimates <= tau -> exact k'
+//   smallest of the survivors -> re-rank -> k smallest.
+// tau is a statistical bound (the r-th smallest sampled estimate, r chosen five standard
+// deviations above the expected number of true k'-best entries in the sample), so the scan
+// verifies it: a query whose survivors number fewer than k' (bound too tight) or more than its
+// candidate buffer holds (bound too loose) - both reported by the device counter, read back
+// once per batch - is redone through a buffer that holds every visited entry.  Results are
+// therefore exact whatever the sample says; the bound only decides how much is written.
 #include "ivfr_internal.h"
 
 #include <algorithm>
 #include <string.h>
 
-int ivfr_launch_select_records(const SelectArgs& a, int out_base, uint32_t* out_pos, float* out_est, int32_t* out_n,
-                               int32_t* overflow, int32_t* overflow_total, hipStream_t st);
+int ivfr_launch_select_records(const SelectArgs& a, int out_base, const unsigned long long* sq, uint32_t* out_pos,
+                               float* out_est, int32_t* out_n, int32_t* overflow, int32_t* overflow_total,
+                               hipStream_t st);
 int ivfr_launch_select_sorted(const SelectArgs& a, const int32_t* counts_i32, int out_base, int32_t* out_lo,
                               float* out_hi, hipStream_t st);
 int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, int nq, int kprime,
@@ -25,12 +28,6 @@ int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, i
 __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
-}
-
-// reset the candidate counters of queries that the filtered pass will refill
-__global__ void reset_counts_kernel(uint32_t* cnt, const uint8_t* fully, int nq) {
-    int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q < nq && !fully[q]) cnt[q] = 0;
 }
 
 struct Carver {
@@ -45,9 +42,12 @@ struct Carver {
 namespace {
 struct EventPair {
     hipEvent_t a = nullptr, b = nullptr;
-    int kind = 0;   // 0 sample scan, 1 filtered scan, 2 rerank
+    int kind = 0;   // IVFR_STAGE_*
 };
 }
+
+// Poisson mean of true k'-best entries wanted inside the sample; the sample stride is k' / mu.
+#define IVFR_SAMPLE_MU 8
 
 extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t nq, int32_t w, int32_t kprime,
                                  int32_t k, int32_t* ids_out, float* dist_out, int32_t* probe_out,
@@ -65,15 +65,18 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     IVFR_HIP(hipSetDevice(p.device));
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     ix->st_codes = ix->st_pairs = ix->st_dense = 0;
-    ix->prof_scan_ms = ix->prof_rerank_ms = ix->prof_sample_ms = 0;
+    for (int i = 0; i < IVFR_N_STAGES; ++i) ix->prof_ms[i] = 0;
     ix->prof_scan_launches = 0;
     if (nq == 0) return IVFR_OK;
 
     const int d = p.d, c = p.c, m = p.m;
     const int B = (int)std::min<int64_t>(nq, ix->batch);
     const int P = B * w;
-    const uint32_t n_sample = (uint32_t)std::min<int64_t>((int64_t)ix->sample_mult * kprime, 1ll << 30);
-    const uint32_t cap = (uint32_t)std::max<int64_t>((int64_t)ix->cap_mult * kprime, (int64_t)n_sample);
+    // candidate buffer per query; queries visiting no more than full_limit entries keep them all
+    const uint32_t cap = (uint32_t)std::max<int64_t>((int64_t)ix->cap_mult * kprime, ix->min_cap);
+    const uint32_t full_limit = (uint32_t)std::min<int64_t>(cap, (int64_t)ix->full_mult * kprime);
+    const uint32_t stride_k = (uint32_t)std::max(1, kprime / IVFR_SAMPLE_MU);
+    const uint32_t max_sample_granules = std::max(1u, cap / (2 * IVFR_GRANULE));
     const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 8;
 
     // carve the workspace
@@ -83,10 +86,10 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_probe = cv.take<int32_t>(P);
     const size_t o_probed = cv.take<float>(P);
     const size_t o_pstart = cv.take<uint32_t>(P);
-    const size_t o_len1 = cv.take<uint32_t>(P);
-    const size_t o_len2 = cv.take<uint32_t>(P);
-    const size_t o_pre1 = cv.take<uint32_t>((size_t)P + 1);
-    const size_t o_pre2 = cv.take<uint32_t>((size_t)P + 1);
+    const size_t o_len = cv.take<uint32_t>(P);
+    const size_t o_pre = cv.take<uint32_t>((size_t)P + 1);
+    const size_t o_gpre = cv.take<uint32_t>((size_t)B * (w + 1));
+    const size_t o_stride = cv.take<uint32_t>(B);
     const size_t o_sq = cv.take<unsigned long long>(B);
     const size_t o_fully = cv.take<uint8_t>(B);
     const size_t o_totals = cv.take<unsigned long long>(2);
@@ -102,6 +105,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_rkeys = cv.take<uint64_t>((size_t)B * kprime);
     const size_t o_sref = cv.take<float>((size_t)B * kprime);
     const size_t o_sids = cv.take<int32_t>((size_t)B * kprime);
+    const size_t o_dpre = cv.take<uint32_t>((size_t)w + 1);
     IVFR_TRY(ix->search_ws.reserve(cv.off + 256));
     char* ws = ix->search_ws.as<char>();
     float* xnorm = reinterpret_cast<float*>(ws + o_xnorm);
@@ -110,10 +114,10 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     float* probed = reinterpret_cast<float*>(ws + o_probed);
     PlanBuffers pb;
     pb.pair_start = reinterpret_cast<uint32_t*>(ws + o_pstart);
-    pb.len1 = reinterpret_cast<uint32_t*>(ws + o_len1);
-    pb.len2 = reinterpret_cast<uint32_t*>(ws + o_len2);
-    pb.blkpre1 = reinterpret_cast<uint32_t*>(ws + o_pre1);
-    pb.blkpre2 = reinterpret_cast<uint32_t*>(ws + o_pre2);
+    pb.len = reinterpret_cast<uint32_t*>(ws + o_len);
+    pb.blkpre = reinterpret_cast<uint32_t*>(ws + o_pre);
+    pb.gpre = reinterpret_cast<uint32_t*>(ws + o_gpre);
+    pb.stride = reinterpret_cast<uint32_t*>(ws + o_stride);
     pb.sq = reinterpret_cast<unsigned long long*>(ws + o_sq);
     pb.fully = reinterpret_cast<uint8_t*>(ws + o_fully);
     pb.totals = reinterpret_cast<unsigned long long*>(ws + o_totals);
@@ -129,6 +133,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     uint64_t* rkeys = reinterpret_cast<uint64_t*>(ws + o_rkeys);
     float* sref = reinterpret_cast<float*>(ws + o_sref);
     int32_t* sids = reinterpret_cast<int32_t*>(ws + o_sids);
+    uint32_t* dpre = reinterpret_cast<uint32_t*>(ws + o_dpre);
 
     std::vector<EventPair> events;
     auto mark = [&](int kind, bool begin) -> int {
@@ -151,38 +156,46 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         const int Pb = nb * w;
         const float* X = queries + q0 * d;
         // visited lists: the w nearest coarse centroids
+        IVFR_TRY(mark(IVFR_STAGE_COARSE, true));
         IVFR_TRY(ivfr_launch_row_norms(X, nb, d, xnorm, st));
         IVFR_TRY(ivfr_launch_dist_keys(X, xnorm, nb, ix->coarse, ix->coarse_norm, c, d, ckeys, st));
+        IVFR_TRY(mark(IVFR_STAGE_COARSE, false));
+        IVFR_TRY(mark(IVFR_STAGE_PROBE, true));
         {
             SelectArgs a;
             a.nseg = nb; a.K = w; a.keys = ckeys; a.seg_stride = c; a.fixed_count = c;
             IVFR_TRY(ivfr_launch_select_sorted(a, nullptr, 0, probe, probed, st));
         }
-        IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, n_sample, pb, st));
+        IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, max_sample_granules, pb, st));
+        IVFR_TRY(mark(IVFR_STAGE_PROBE, false));
+        IVFR_TRY(mark(IVFR_STAGE_LUT, true));
         IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, st));
-        // sample pass: keep everything
+        IVFR_TRY(mark(IVFR_STAGE_LUT, false));
+        // uniform sample of the visited entries -> bound tau on the k'-th smallest estimate
+        IVFR_TRY(mark(IVFR_STAGE_SAMPLE, true));
         IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_HIP(hipMemsetAsync(overtot, 0, 4 * sizeof(int32_t), st));
         hipLaunchKernelGGL(fill_f32_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, tau, (int64_t)nb, INFINITY);
-        IVFR_TRY(mark(0, true));
-        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len1, pb.blkpre1, Pb, w, tau, cand, cnt, cap, cap, groups, st));
-        IVFR_TRY(mark(0, false));
+        IVFR_TRY(ivfr_launch_sample(ix, lut, pb, nb, w, cand, cnt, cap, cap, 16, st));
         {
             SelectArgs a;
             a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.seg_stride = cap; a.counts = cnt; a.cap = cap;
-            IVFR_TRY(ivfr_launch_select_tau(a, pb.fully, tau, st));
+            IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, pb.fully, tau, st));
         }
-        hipLaunchKernelGGL(reset_counts_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, cnt, pb.fully, nb);
-        // filtered pass over every visited entry
-        IVFR_TRY(mark(1, true));
-        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len2, pb.blkpre2, Pb, w, tau, cand, cnt, cap, cap, groups, st));
-        IVFR_TRY(mark(1, false));
+        IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
+        IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
+        // scan of every visited entry, keeping estimates <= tau
+        IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
+        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, pb.blkpre, Pb, w, tau, cand, cnt, cap, cap, groups, st));
+        IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
+        IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, true));
         {
             SelectArgs a;
             a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.seg_stride = cap; a.counts = cnt; a.cap = cap;
-            IVFR_TRY(ivfr_launch_select_records(a, 0, spos, sest, sn, over, overtot, st));
+            IVFR_TRY(ivfr_launch_select_records(a, 0, pb.sq, spos, sest, sn, over, overtot, st));
         }
-        // status read-back: overflow count and scanned totals
+        IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, false));
+        // status read-back: failed-filter count and scanned totals
         IVFR_HIP(hipMemcpyAsync(ix->h_status, overtot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
         IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         IVFR_HIP(hipStreamSynchronize(st));
@@ -206,37 +219,37 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
                 IVFR_TRY(ix->dense_ws.reserve(bytes));
                 uint32_t* dcnt = ix->dense_ws.as<uint32_t>();
                 float* dtau = reinterpret_cast<float*>(ix->dense_ws.as<char>() + 256);
-                uint32_t* dpre = reinterpret_cast<uint32_t*>(ix->dense_ws.as<char>() + 512);
                 uint2* dcand = reinterpret_cast<uint2*>(ix->dense_ws.as<char>() + 1024);
-                (void)dpre;
                 IVFR_HIP(hipMemsetAsync(dcnt, 0, sizeof(uint32_t), st));
                 hipLaunchKernelGGL(fill_f32_kernel, dim3(1), dim3(64), 0, st, dtau, (int64_t)1, INFINITY);
-                // the query's w pairs with their full lengths; block prefix computed on the host
+                // the query's w pairs; block prefix computed on the host
                 std::vector<uint32_t> h_len((size_t)w), h_pre((size_t)w + 1, 0u);
-                IVFR_HIP(hipMemcpy(h_len.data(), pb.len2 + (size_t)q * w, (size_t)w * sizeof(uint32_t), hipMemcpyDeviceToHost));
+                IVFR_HIP(hipMemcpy(h_len.data(), pb.len + (size_t)q * w, (size_t)w * sizeof(uint32_t), hipMemcpyDeviceToHost));
                 for (int r = 0; r < w; ++r)
                     h_pre[(size_t)r + 1] = h_pre[(size_t)r] + (h_len[(size_t)r] + IVFR_BLOCK - 1) / IVFR_BLOCK;
-                IVFR_HIP(hipMemcpy(pb.blkpre1, h_pre.data(), ((size_t)w + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
-                // pair p of this launch is pair q*w + p of the batch; with w pairs and divisor w the
-                // kernel's query index is 0, so tau / counter / buffer pointers are the dense ones
+                IVFR_HIP(hipMemcpy(dpre, h_pre.data(), ((size_t)w + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
+                // pair r of this launch is pair q*w + r of the batch; with w pairs and divisor w the
+                // kernel's query index is 0, so tau / counter / buffer are the dense ones
                 IVFR_TRY(ivfr_launch_scan(ix, lut + (size_t)q * w * m * IVFR_KS, pb.pair_start + (size_t)q * w,
-                                          pb.len2 + (size_t)q * w, pb.blkpre1, w, w, dtau, dcand, dcnt, 0,
+                                          pb.len + (size_t)q * w, dpre, w, w, dtau, dcand, dcnt, 0,
                                           (uint32_t)(sqv + 1), groups, st));
                 SelectArgs a;
                 a.nseg = 1; a.K = kprime; a.recs = dcand; a.ids = ix->ids; a.seg_stride = 0; a.counts = dcnt;
                 a.cap = (uint32_t)(sqv + 1);
-                IVFR_TRY(ivfr_launch_select_records(a, q, spos, sest, sn, nullptr, nullptr, st));
+                IVFR_TRY(ivfr_launch_select_records(a, q, nullptr, spos, sest, sn, nullptr, nullptr, st));
             }
         }
         // re-rank and final top-k
-        IVFR_TRY(mark(2, true));
+        IVFR_TRY(mark(IVFR_STAGE_RERANK, true));
         IVFR_TRY(ivfr_launch_rerank(ix, X, 0, nb, kprime, spos, sn, rkeys, sref, sids, st));
-        IVFR_TRY(mark(2, false));
+        IVFR_TRY(mark(IVFR_STAGE_RERANK, false));
+        IVFR_TRY(mark(IVFR_STAGE_FINAL, true));
         {
             SelectArgs a;
             a.nseg = nb; a.K = k; a.keys = rkeys; a.seg_stride = kprime;
             IVFR_TRY(ivfr_launch_select_sorted(a, sn, 0, ids_out + q0 * k, dist_out + q0 * k, st));
         }
+        IVFR_TRY(mark(IVFR_STAGE_FINAL, false));
         // optional trace outputs
         if (probe_out) IVFR_HIP(hipMemcpyAsync(probe_out + q0 * w, probe, (size_t)Pb * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
         if (probe_dist_out) IVFR_HIP(hipMemcpyAsync(probe_dist_out + q0 * w, probed, (size_t)Pb * sizeof(float), hipMemcpyDeviceToDevice, st));
@@ -250,9 +263,8 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     for (auto& ep : events) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, ep.a, ep.b) == hipSuccess) {
-            if (ep.kind == 0) ix->prof_sample_ms += ms;
-            else if (ep.kind == 1) { ix->prof_scan_ms += ms; ix->prof_scan_launches += 1; }
-            else ix->prof_rerank_ms += ms;
+            ix->prof_ms[ep.kind] += ms;
+            if (ep.kind == IVFR_STAGE_SCAN) ix->prof_scan_launches += 1;
         }
         (void)hipEventDestroy(ep.a);
         (void)hipEventDestroy(ep.b);

@@ -102,27 +102,35 @@ __device__ __forceinline__ int64_t seg_count(const uint32_t* counts, uint32_t ca
     return c;
 }
 
-// ---- pivot only: tau = estimate of the K-th smallest record ---------------------------------
+// ---- bound from a uniform sample --------------------------------------------------------------
+// The sample holds n of the query's sq visited entries, so about mu = k' n / sq of the true k'
+// best are in it (Poisson-like).  Taking the r-th smallest sampled estimate with r = mu + 5
+// sqrt(mu) + 6 makes it all but certain (beyond five standard deviations) that at least k'
+// visited entries lie at or below it; the filtered scan verifies that by counting.
 __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, const int32_t* ids, int64_t seg_stride,
-                                                           const uint32_t* counts, uint32_t cap, int K,
+                                                           const uint32_t* counts, uint32_t cap,
+                                                           const unsigned long long* sq, int kprime,
                                                            const uint8_t* skip, float* tau) {
     const int seg = blockIdx.x;
     if (skip && skip[seg]) return;
     bool over;
     int64_t n = seg_count(counts, cap, 0, seg, &over);
-    if (n < K) {
+    const double mu = (double)kprime * (double)n / (double)(sq[seg] ? sq[seg] : 1ull);
+    const int64_t r = (int64_t)ceil(mu + 5.0 * sqrt(mu) + 6.0);
+    if (n < r || n == 0) {
         if (threadIdx.x == 0) tau[seg] = INFINITY;
         return;
     }
     SegView s{nullptr, recs, ids, (int64_t)seg * seg_stride, n};
-    uint64_t pivot = radix_pivot(s, (uint32_t)K);
+    uint64_t pivot = radix_pivot(s, (uint32_t)r);
     if (threadIdx.x == 0) tau[seg] = __uint_as_float((uint32_t)(pivot >> 32));
 }
 
-int ivfr_launch_select_tau(const SelectArgs& a, const uint8_t* skip, float* tau, hipStream_t st) {
+int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, const uint8_t* skip,
+                           float* tau, hipStream_t st) {
     if (a.nseg <= 0) return IVFR_OK;
     hipLaunchKernelGGL(select_tau_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.seg_stride, a.counts,
-                       a.cap, a.K, skip, tau);
+                       a.cap, sq, kprime, skip, tau);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -131,13 +139,16 @@ int ivfr_launch_select_tau(const SelectArgs& a, const uint8_t* skip, float* tau,
 __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs, const int32_t* ids,
                                                                int64_t seg_stride, const uint32_t* counts,
                                                                uint32_t cap, int64_t fixed_count, int K, int out_base,
-                                                               uint32_t* out_pos, float* out_est, int32_t* out_n,
-                                                               int32_t* overflow, int32_t* overflow_total) {
+                                                               const unsigned long long* sq, uint32_t* out_pos,
+                                                               float* out_est, int32_t* out_n, int32_t* overflow,
+                                                               int32_t* overflow_total) {
     __shared__ uint32_t s_slot;
     const int seg = blockIdx.x;
     const int q = out_base + seg;
     bool over;
     int64_t n = seg_count(counts, cap, fixed_count, seg, &over);
+    // the filter was too tight if it kept fewer than k' although more entries were visited
+    if (sq && n < K && (unsigned long long)n < sq[seg]) over = true;
     if (threadIdx.x == 0) {
         s_slot = 0;
         if (overflow) overflow[q] = over ? 1 : 0;
@@ -173,11 +184,12 @@ __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs
     if (threadIdx.x == 0) out_n[q] = K;
 }
 
-int ivfr_launch_select_records(const SelectArgs& a, int out_base, uint32_t* out_pos, float* out_est, int32_t* out_n,
-                               int32_t* overflow, int32_t* overflow_total, hipStream_t st) {
+int ivfr_launch_select_records(const SelectArgs& a, int out_base, const unsigned long long* sq, uint32_t* out_pos,
+                               float* out_est, int32_t* out_n, int32_t* overflow, int32_t* overflow_total,
+                               hipStream_t st) {
     if (a.nseg <= 0) return IVFR_OK;
     hipLaunchKernelGGL(select_records_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.seg_stride,
-                       a.counts, a.cap, a.fixed_count, a.K, out_base, out_pos, out_est, out_n, overflow,
+                       a.counts, a.cap, a.fixed_count, a.K, out_base, sq, out_pos, out_est, out_n, overflow,
                        overflow_total);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;

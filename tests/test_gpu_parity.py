@@ -284,19 +284,28 @@ def test_edge_cases_and_internal_paths():
     ix.set_tuning(batch=5)
     b_ids, b_dist = ix.search(xq, 6, 300, 20)
     assert np.array_equal(base_ids, b_ids.cpu().numpy()) and np.array_equal(base_dist, b_dist.cpu().numpy())
-    # a candidate buffer far too small forces the dense fallback; same answer
-    ix.set_tuning(sample_mult=1, cap_mult=1, batch=1024)
+    # sampled bound + filtered scan (the path large workloads take), forced by a small full_mult
+    ix.set_tuning(full_mult=1, batch=1024)
+    p_ids, p_dist = ix.search(xq, 6, 300, 20)
+    assert ix.search_stats()["dense_fallbacks"] == 0
+    assert np.array_equal(base_ids, p_ids.cpu().numpy()) and np.array_equal(base_dist, p_dist.cpu().numpy())
+    # a candidate buffer far too small makes the filter overflow: dense fallback, same answer
+    ix.set_tuning(full_mult=1, cap_mult=1, min_cap=1)
     f_ids, f_dist = ix.search(xq, 6, 300, 20)
     log("dense fallbacks", ix.search_stats())
     assert ix.search_stats()["dense_fallbacks"] > 0
     assert np.array_equal(base_ids, f_ids.cpu().numpy()) and np.array_equal(base_dist, f_dist.cpu().numpy())
-    # a large sample covers everything in the first pass
-    ix.set_tuning(sample_mult=1000, cap_mult=1000)
+    # every estimate kept (no sample, no filter)
+    ix.set_tuning(full_mult=1000, cap_mult=1000, min_cap=8192)
     s_ids, s_dist = ix.search(xq, 6, 300, 20)
     assert np.array_equal(base_ids, s_ids.cpu().numpy()) and np.array_equal(base_dist, s_dist.cpu().numpy())
-    ix.set_tuning(sample_mult=4, cap_mult=16, scan_groups=3)
+    ix.set_tuning(full_mult=8, cap_mult=16, scan_groups=3)
     g_ids, _ = ix.search(xq, 6, 300, 20)
     assert np.array_equal(base_ids, g_ids.cpu().numpy())
+    ix.set_tuning(full_mult=1, scan_groups=5)
+    g_ids, _ = ix.search(xq, 6, 300, 20)
+    assert np.array_equal(base_ids, g_ids.cpu().numpy())
+    ix.set_tuning(full_mult=8)
     # no queries
     e_ids, e_dist = ix.search(xq[:0], 6, 300, 20)
     assert e_ids.shape == (0, 20)
