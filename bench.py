@@ -114,6 +114,9 @@ def main():
     ap.add_argument("--gt-queries", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scan-groups", type=int, default=0)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB) three times, as the "
+                         "known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path is not sharded); run with --gpus 1",
@@ -146,10 +149,13 @@ def main():
     batches = [xq[i * B:(i + 1) * B].contiguous() for i in range(n_batches)]
 
     for s in range(args.warmup):
+        t0 = time.perf_counter()
         ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
+        log(f"[bench] warmup step {s}: {1e3 * (time.perf_counter() - t0):.1f} ms, {ix.search_stats()}")
     ix.set_profiling(True)
     torch.cuda.synchronize()
     codes = 0
+    dense_total = 0
     stage_ms = {}
     scan_launches = 0
     t0 = time.perf_counter()
@@ -161,10 +167,19 @@ def main():
         scan_launches += pr.pop("scan_launches")
         for name, ms in pr.items():
             stage_ms[name] = stage_ms.get(name, 0.0) + ms
+        dense_total += st["dense_fallbacks"]
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ix.set_profiling(False)
-    dense = ix.search_stats()["dense_fallbacks"]
+    log(f"[bench] timed {args.steps} steps in {elapsed:.3f}s")
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # accuracy on the ground-truth subset (first batch holds the first n_gt queries)
     g_ids, g_dist = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
@@ -188,7 +203,7 @@ def main():
         "adc_codes_per_s": codes / elapsed,
         "codes_scanned_per_step": codes / max(args.steps, 1),
         "stage_ms_per_step": {name: ms / args.steps for name, ms in stage_ms.items()},
-        "dense_fallbacks_last_step": dense,
+        "dense_fallbacks_total": dense_total,
         "recall": recall, "recall_queries": n_gt,
         "build_seconds": build_t,
         "roofline": {"bound": "hbm", "kernel": "adc_scan_kernel", "achieved": achieved,

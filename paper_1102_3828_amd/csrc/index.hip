@@ -115,7 +115,7 @@ extern "C" int ivfr_destroy(ivfr_index* ix) {
     dev_free(ix->coarse); dev_free(ix->coarse_norm); dev_free(ix->pq); dev_free(ix->pq_norm); dev_free(ix->rq);
     dev_free(ix->list_fill); dev_free(ix->list_start); dev_free(ix->list_len);
     dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
-    ix->search_ws.release(); ix->encode_ws.release(); ix->dense_ws.release();
+    ix->search_ws.release(); ix->cand_ws.release(); ix->encode_ws.release(); ix->dense_ws.release();
     if (ix->h_status) (void)hipHostFree(ix->h_status);
     delete ix;
     return IVFR_OK;

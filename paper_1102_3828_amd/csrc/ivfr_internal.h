@@ -114,7 +114,7 @@ struct ivfr_index {
     int min_cap = 8192;
 
     // scratch
-    DevBuf search_ws, encode_ws, dense_ws;
+    DevBuf search_ws, cand_ws, encode_ws, dense_ws;
     int* h_status = nullptr;         // pinned host word(s) for status read-back
 
     // stats of the last search
@@ -140,20 +140,31 @@ int ivfr_launch_dist_keys(const float* X, const float* xnorm, int64_t n, const f
 int ivfr_launch_assign(const float* X, int64_t n, const float* C, const float* cnorm, int c, int d,
                        int32_t* assign, hipStream_t st);
 
+// Where each query's candidate records live: query q owns cap(q) records from base(q).  Either
+// per-query arrays (off, capq) or a uniform (stride, ucap) layout.
+struct CandLayout {
+    const unsigned long long* off = nullptr;
+    const uint32_t* capq = nullptr;
+    uint64_t stride = 0;
+    uint32_t ucap = 0;
+    __host__ __device__ uint64_t base(int q) const { return off ? off[q] : (uint64_t)q * stride; }
+    __host__ __device__ uint32_t cap(int q) const { return capq ? capq[q] : ucap; }
+};
+
 // Segmented exact top-K by 64-bit key (ascending).  One workgroup per segment (select.hip).
 struct SelectArgs {
     int nseg = 0;
     int K = 0;
     // source A: keys[seg * seg_stride + i], i < count
     const uint64_t* keys = nullptr;
-    // source B: records (estimate bits, entry position) with key = (estimate bits << 32) | ids[position]
+    int64_t seg_stride = 0;
+    int64_t fixed_count = 0;   // elements per segment (source A)
+    // source B: records (estimate bits, entry position) with key = (estimate bits << 32) | ids[position];
+    // segment q holds min(counts[q], lay.cap(q)) records from lay.base(q)
     const uint2* recs = nullptr;
     const int32_t* ids = nullptr;
-    int64_t seg_stride = 0;
-    // element count per segment: fixed_count, or min(counts[seg], cap) when counts != nullptr
-    int64_t fixed_count = 0;
     const uint32_t* counts = nullptr;
-    uint32_t cap = 0;
+    CandLayout lay;
 };
 // Bound on the k'-th smallest estimate of each query from its uniform sample (a.counts records of the
 // query's sq visited entries): tau = the r-th smallest sampled estimate, r = mu + 5 sqrt(mu) + 6 with
@@ -170,19 +181,21 @@ struct PlanBuffers {
     uint32_t* blkpre;      // [P+1] exclusive prefix of scan blocks over the pairs
     uint32_t* gpre;        // [nq, w+1] per query: exclusive prefix of sample granules over its pairs
     uint32_t* stride;      // [nq] every stride-th granule of the query is sampled
+    uint32_t* capq;        // [nq] records in the query's candidate buffer
+    unsigned long long* coff;    // [nq] first record of the query's candidate buffer in the pool
     unsigned long long* sq;      // [nq] entries in the query's visited lists
     uint8_t* fully;              // [nq] 1 = few enough entries to keep them all (no sample, tau = +inf)
-    unsigned long long* totals;  // [2]: [0] = sum of sq
+    unsigned long long* totals;  // [2]: [0] = sum of sq, [1] = records in the candidate pool
 };
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
-                     uint32_t stride_k, uint32_t max_sample_granules, const PlanBuffers& pb, hipStream_t st);
+                     uint32_t stride_k, uint32_t min_cap, const PlanBuffers& pb, hipStream_t st);
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
                     float* lut, hipStream_t st);
 int ivfr_launch_sample(const ivfr_index* ix, const float* lut, const PlanBuffers& pb, int nq, int w, uint2* cand,
-                       uint32_t* cand_cnt, uint64_t cand_stride, uint32_t cap, int ychunks, hipStream_t st);
+                       uint32_t* cand_cnt, CandLayout lay, int ychunks, hipStream_t st);
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
-                     uint64_t cand_stride, uint32_t cap, int groups, hipStream_t st);
+                     CandLayout lay, int groups, hipStream_t st);
 
 // Encoding (encode.hip)
 int ivfr_launch_residual(float* X, int64_t n, int d, const float* C, const int32_t* assign, hipStream_t st);

@@ -15,8 +15,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // ------------------------------------------------------------------------------------------
 __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int w,
                                   const uint32_t* __restrict__ list_start, const uint32_t* __restrict__ list_len,
-                                  uint32_t full_limit, uint32_t stride_k, uint32_t max_sample_granules,
-                                  PlanBuffers pb) {
+                                  uint32_t full_limit, uint32_t stride_k, uint32_t min_cap, PlanBuffers pb) {
     int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nq) return;
     unsigned long long total = 0, gran = 0;
@@ -35,21 +34,50 @@ __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int
     const bool fully = total <= full_limit;
     pb.sq[q] = total;
     pb.fully[q] = fully ? 1 : 0;
-    uint32_t stride = stride_k;
-    const unsigned long long need = (gran + max_sample_granules - 1) / max_sample_granules;   // keeps the sample inside the buffer
-    if (need > stride) stride = (uint32_t)need;
-    if (stride < 1) stride = 1;
+    const uint32_t stride = stride_k < 1 ? 1u : stride_k;
     pb.stride[q] = stride;
+    // buffer: everything (no filter), or the larger of the sample and the survivors' allowance
+    unsigned long long capv;
+    if (fully) capv = total;
+    else {
+        capv = (gran / stride + 2) * IVFR_GRANULE;
+        if (capv < min_cap) capv = min_cap;
+    }
+    if (capv > 0xFFFFFFF0ull) capv = 0xFFFFFFF0ull;
+    pb.capq[q] = (uint32_t)capv;
     atomicAdd(pb.totals, total);
 }
 
-// Exclusive prefix sum of ceil(len / IVFR_BLOCK) over the P pairs (one workgroup).
-__global__ __launch_bounds__(1024) void plan_scan_kernel(int P, PlanBuffers pb) {
+// Exclusive prefix sums (one workgroup): candidate-buffer offsets over the nq queries, then
+// ceil(len / IVFR_BLOCK) over the P pairs.
+__global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int P, PlanBuffers pb) {
     __shared__ uint32_t wtot[16];
     __shared__ uint32_t carry;
+    __shared__ unsigned long long wtot64[16];
+    __shared__ unsigned long long carry64;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid == 0) carry = 0;
+    if (tid == 0) { carry = 0; carry64 = 0; }
     __syncthreads();
+    for (int base = 0; base < nq; base += 1024) {
+        int q = base + tid;
+        unsigned long long v = q < nq ? (((unsigned long long)pb.capq[q] + 31ull) & ~31ull) : 0ull;
+        unsigned long long inc = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            unsigned long long o = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += o;
+        }
+        if (lane == 63) wtot64[wv] = inc;
+        __syncthreads();
+        unsigned long long add = carry64;
+        for (int x = 0; x < wv; ++x) add += wtot64[x];
+        inc += add;
+        if (q < nq) pb.coff[q] = inc - v;
+        __syncthreads();
+        if (tid == 1023) carry64 = inc;
+        __syncthreads();
+    }
+    if (tid == 0) pb.totals[1] = carry64;
     for (int base = 0; base < P; base += 1024) {
         int p = base + tid;
         uint32_t v = 0;
@@ -74,12 +102,12 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int P, PlanBuffers pb) 
 }
 
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
-                     uint32_t stride_k, uint32_t max_sample_granules, const PlanBuffers& pb, hipStream_t st) {
+                     uint32_t stride_k, uint32_t min_cap, const PlanBuffers& pb, hipStream_t st) {
     IVFR_HIP(hipMemsetAsync(pb.totals, 0, 2 * sizeof(unsigned long long), st));
     hipLaunchKernelGGL(plan_pairs_kernel, dim3((nq + 127) / 128), dim3(128), 0, st, probe, nq, w, ix->list_start,
-                       ix->list_len, full_limit, stride_k, max_sample_granules, pb);
+                       ix->list_len, full_limit, stride_k, min_cap, pb);
     IVFR_HIP(hipGetLastError());
-    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, nq * w, pb);
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, nq, nq * w, pb);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -242,8 +270,7 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                                                        const uint32_t* __restrict__ pair_len,
                                                        const uint32_t* __restrict__ blkpre, int P, int w,
                                                        const float* __restrict__ tau, uint2* __restrict__ cand,
-                                                       uint32_t* __restrict__ cand_cnt, uint64_t cand_stride,
-                                                       uint32_t cap) {
+                                                       uint32_t* __restrict__ cand_cnt, CandLayout lay) {
     extern __shared__ float s_lut[];   // M * 256 floats
     const uint32_t total = blkpre[P];
     const uint32_t G = gridDim.x, g = blockIdx.x;
@@ -265,7 +292,8 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
         const int q = p / w;
         const uint32_t start = pair_start[p], len = pair_len[p];
         const float t = tau[q];
-        uint2* qc = cand + (uint64_t)q * cand_stride;
+        uint2* qc = cand + lay.base(q);
+        const uint32_t cap = lay.cap(q);
         uint32_t* cnt = cand_cnt + q;
         __syncthreads();   // previous pair's table no longer in use
         {
@@ -308,13 +336,14 @@ __global__ __launch_bounds__(256) void adc_sample_kernel(const uint8_t* __restri
                                                          const uint32_t* __restrict__ stride_q,
                                                          const uint8_t* __restrict__ fully, int w,
                                                          uint2* __restrict__ cand, uint32_t* __restrict__ cand_cnt,
-                                                         uint64_t cand_stride, uint32_t cap) {
+                                                         CandLayout lay) {
     const int q = blockIdx.x;
     if (fully[q]) return;
     const uint32_t* gp = gpre + (int64_t)q * (w + 1);
     const uint32_t G = gp[w], st = stride_q[q], off = st >> 1;
     const uint32_t nsg = G > off ? (G - off + st - 1) / st : 0u;
-    uint2* qc = cand + (uint64_t)q * cand_stride;
+    uint2* qc = cand + lay.base(q);
+    const uint32_t cap = lay.cap(q);
     uint32_t* cnt = cand_cnt + q;
     const int lane = threadIdx.x & 63;
     for (uint32_t j0 = blockIdx.y * 256u; j0 < nsg; j0 += gridDim.y * 256u) {
@@ -362,22 +391,22 @@ __global__ __launch_bounds__(256) void adc_sample_kernel(const uint8_t* __restri
 
 template <int M>
 static int launch_sample_m(const ivfr_index* ix, const float* lut, const PlanBuffers& pb, int nq, int w, uint2* cand,
-                           uint32_t* cand_cnt, uint64_t cand_stride, uint32_t cap, int ychunks, hipStream_t st) {
+                           uint32_t* cand_cnt, CandLayout lay, int ychunks, hipStream_t st) {
     hipLaunchKernelGGL(adc_sample_kernel<M>, dim3(nq, ychunks), dim3(256), 0, st, ix->codes, lut, pb.pair_start,
-                       pb.len, pb.gpre, pb.stride, pb.fully, w, cand, cand_cnt, cand_stride, cap);
+                       pb.len, pb.gpre, pb.stride, pb.fully, w, cand, cand_cnt, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
 int ivfr_launch_sample(const ivfr_index* ix, const float* lut, const PlanBuffers& pb, int nq, int w, uint2* cand,
-                       uint32_t* cand_cnt, uint64_t cand_stride, uint32_t cap, int ychunks, hipStream_t st) {
+                       uint32_t* cand_cnt, CandLayout lay, int ychunks, hipStream_t st) {
     if (nq <= 0) return IVFR_OK;
     switch (ix->p.m) {
-        case 4: return launch_sample_m<4>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
-        case 8: return launch_sample_m<8>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
-        case 16: return launch_sample_m<16>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
-        case 32: return launch_sample_m<32>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
-        case 64: return launch_sample_m<64>(ix, lut, pb, nq, w, cand, cand_cnt, cand_stride, cap, ychunks, st);
+        case 4: return launch_sample_m<4>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
+        case 8: return launch_sample_m<8>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
+        case 16: return launch_sample_m<16>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
+        case 32: return launch_sample_m<32>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
+        case 64: return launch_sample_m<64>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
         default:
             ivfr_set_error("list scan supports m in {4, 8, 16, 32, 64}; got %d", ix->p.m);
             return IVFR_ERR_INVALID_ARG;
@@ -387,7 +416,7 @@ int ivfr_launch_sample(const ivfr_index* ix, const float* lut, const PlanBuffers
 template <int M>
 static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
                          const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
-                         uint64_t cand_stride, uint32_t cap, int groups, hipStream_t st) {
+                         CandLayout lay, int groups, hipStream_t st) {
     size_t lds = (size_t)M * IVFR_KS * sizeof(float);
     static bool attr_done = false;
     if (!attr_done && lds > 48 * 1024) {
@@ -396,19 +425,19 @@ static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t*
         attr_done = true;
     }
     hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start, pair_len,
-                       blkpre, P, w, tau, cand, cand_cnt, cand_stride, cap);
+                       blkpre, P, w, tau, cand, cand_cnt, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
-                     uint64_t cand_stride, uint32_t cap, int groups, hipStream_t st) {
+                     CandLayout lay, int groups, hipStream_t st) {
     if (P <= 0) return IVFR_OK;
 #define IVFR_SCAN_CASE(MM)                                                                                      \
     case MM:                                                                                                    \
-        return launch_scan_m<MM>(ix, lut, pair_start, pair_len, blkpre, P, w, tau, cand, cand_cnt, cand_stride, \
-                                 cap, groups, st)
+        return launch_scan_m<MM>(ix, lut, pair_start, pair_len, blkpre, P, w, tau, cand, cand_cnt, lay, groups, \
+                                 st)
     switch (ix->p.m) {
         IVFR_SCAN_CASE(4);
         IVFR_SCAN_CASE(8);

@@ -72,11 +72,11 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const int d = p.d, c = p.c, m = p.m;
     const int B = (int)std::min<int64_t>(nq, ix->batch);
     const int P = B * w;
-    // candidate buffer per query; queries visiting no more than full_limit entries keep them all
-    const uint32_t cap = (uint32_t)std::max<int64_t>((int64_t)ix->cap_mult * kprime, ix->min_cap);
-    const uint32_t full_limit = (uint32_t)std::min<int64_t>(cap, (int64_t)ix->full_mult * kprime);
+    // Queries visiting no more than full_limit entries keep them all; the others get a candidate
+    // buffer for the larger of their sample and min_cap survivors (sized per query by the plan).
+    const uint32_t min_cap = (uint32_t)std::max<int64_t>((int64_t)ix->cap_mult * kprime, ix->min_cap);
+    const uint32_t full_limit = (uint32_t)std::min<int64_t>((int64_t)ix->full_mult * kprime, 1ll << 30);
     const uint32_t stride_k = (uint32_t)std::max(1, kprime / IVFR_SAMPLE_MU);
-    const uint32_t max_sample_granules = std::max(1u, cap / (2 * IVFR_GRANULE));
     const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 8;
 
     // carve the workspace
@@ -93,8 +93,9 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_sq = cv.take<unsigned long long>(B);
     const size_t o_fully = cv.take<uint8_t>(B);
     const size_t o_totals = cv.take<unsigned long long>(2);
+    const size_t o_capq = cv.take<uint32_t>(B);
+    const size_t o_coff = cv.take<unsigned long long>(B);
     const size_t o_lut = cv.take<float>((size_t)P * m * IVFR_KS);
-    const size_t o_cand = cv.take<uint2>((size_t)B * cap);
     const size_t o_cnt = cv.take<uint32_t>(B);
     const size_t o_tau = cv.take<float>(B);
     const size_t o_spos = cv.take<uint32_t>((size_t)B * kprime);
@@ -121,8 +122,12 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     pb.sq = reinterpret_cast<unsigned long long*>(ws + o_sq);
     pb.fully = reinterpret_cast<uint8_t*>(ws + o_fully);
     pb.totals = reinterpret_cast<unsigned long long*>(ws + o_totals);
+    pb.capq = reinterpret_cast<uint32_t*>(ws + o_capq);
+    pb.coff = reinterpret_cast<unsigned long long*>(ws + o_coff);
     float* lut = reinterpret_cast<float*>(ws + o_lut);
-    uint2* cand = reinterpret_cast<uint2*>(ws + o_cand);
+    CandLayout lay;
+    lay.off = pb.coff;
+    lay.capq = pb.capq;
     uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + o_cnt);
     float* tau = reinterpret_cast<float*>(ws + o_tau);
     uint32_t* spos = reinterpret_cast<uint32_t*>(ws + o_spos);
@@ -166,44 +171,48 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
             a.nseg = nb; a.K = w; a.keys = ckeys; a.seg_stride = c; a.fixed_count = c;
             IVFR_TRY(ivfr_launch_select_sorted(a, nullptr, 0, probe, probed, st));
         }
-        IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, max_sample_granules, pb, st));
+        IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, min_cap, pb, st));
+        // the candidate pool is sized by the plan: one small read-back
+        IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         IVFR_TRY(mark(IVFR_STAGE_PROBE, false));
         IVFR_TRY(mark(IVFR_STAGE_LUT, true));
         IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, st));
         IVFR_TRY(mark(IVFR_STAGE_LUT, false));
+        IVFR_HIP(hipStreamSynchronize(st));
+        unsigned long long tot2[2];
+        memcpy(tot2, ix->h_status + 2, sizeof(tot2));
+        ix->st_codes += (int64_t)tot2[0];
+        ix->st_pairs += Pb;
+        IVFR_TRY(ix->cand_ws.reserve((size_t)(tot2[1] + 64) * sizeof(uint2)));
+        uint2* cand = ix->cand_ws.as<uint2>();
         // uniform sample of the visited entries -> bound tau on the k'-th smallest estimate
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, true));
         IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_HIP(hipMemsetAsync(overtot, 0, 4 * sizeof(int32_t), st));
         hipLaunchKernelGGL(fill_f32_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, tau, (int64_t)nb, INFINITY);
-        IVFR_TRY(ivfr_launch_sample(ix, lut, pb, nb, w, cand, cnt, cap, cap, 16, st));
+        IVFR_TRY(ivfr_launch_sample(ix, lut, pb, nb, w, cand, cnt, lay, 16, st));
         {
             SelectArgs a;
-            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.seg_stride = cap; a.counts = cnt; a.cap = cap;
+            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = cnt; a.lay = lay;
             IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, pb.fully, tau, st));
         }
         IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
         // scan of every visited entry, keeping estimates <= tau
         IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
-        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, pb.blkpre, Pb, w, tau, cand, cnt, cap, cap, groups, st));
+        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, pb.blkpre, Pb, w, tau, cand, cnt, lay, groups, st));
         IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
         IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, true));
         {
             SelectArgs a;
-            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.seg_stride = cap; a.counts = cnt; a.cap = cap;
+            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = cnt; a.lay = lay;
             IVFR_TRY(ivfr_launch_select_records(a, 0, pb.sq, spos, sest, sn, over, overtot, st));
         }
         IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, false));
         // status read-back: failed-filter count and scanned totals
         IVFR_HIP(hipMemcpyAsync(ix->h_status, overtot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-        IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         IVFR_HIP(hipStreamSynchronize(st));
         const int n_over = ix->h_status[0];
-        unsigned long long tot;
-        memcpy(&tot, ix->h_status + 2, sizeof(tot));
-        ix->st_codes += (int64_t)tot;
-        ix->st_pairs += Pb;
         if (n_over > 0) {
             // dense fallback, one query at a time: a buffer for every visited entry, no filter
             std::vector<int32_t> h_over((size_t)nb);
@@ -230,12 +239,13 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
                 IVFR_HIP(hipMemcpy(dpre, h_pre.data(), ((size_t)w + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
                 // pair r of this launch is pair q*w + r of the batch; with w pairs and divisor w the
                 // kernel's query index is 0, so tau / counter / buffer are the dense ones
+                CandLayout dlay;
+                dlay.stride = 0;
+                dlay.ucap = (uint32_t)(sqv + 1);
                 IVFR_TRY(ivfr_launch_scan(ix, lut + (size_t)q * w * m * IVFR_KS, pb.pair_start + (size_t)q * w,
-                                          pb.len + (size_t)q * w, dpre, w, w, dtau, dcand, dcnt, 0,
-                                          (uint32_t)(sqv + 1), groups, st));
+                                          pb.len + (size_t)q * w, dpre, w, w, dtau, dcand, dcnt, dlay, groups, st));
                 SelectArgs a;
-                a.nseg = 1; a.K = kprime; a.recs = dcand; a.ids = ix->ids; a.seg_stride = 0; a.counts = dcnt;
-                a.cap = (uint32_t)(sqv + 1);
+                a.nseg = 1; a.K = kprime; a.recs = dcand; a.ids = ix->ids; a.counts = dcnt; a.lay = dlay;
                 IVFR_TRY(ivfr_launch_select_records(a, q, nullptr, spos, sest, sn, nullptr, nullptr, st));
             }
         }

@@ -94,9 +94,8 @@ __device__ uint64_t radix_pivot(const SegView& s, uint32_t K) {
     return prefix;
 }
 
-__device__ __forceinline__ int64_t seg_count(const uint32_t* counts, uint32_t cap, int64_t fixed, int seg, bool* over) {
+__device__ __forceinline__ int64_t seg_count(const uint32_t* counts, uint32_t cap, int seg, bool* over) {
     *over = false;
-    if (!counts) return fixed;
     uint32_t c = counts[seg];
     if (c > cap) { *over = true; return cap; }
     return c;
@@ -107,21 +106,21 @@ __device__ __forceinline__ int64_t seg_count(const uint32_t* counts, uint32_t ca
 // best are in it (Poisson-like).  Taking the r-th smallest sampled estimate with r = mu + 5
 // sqrt(mu) + 6 makes it all but certain (beyond five standard deviations) that at least k'
 // visited entries lie at or below it; the filtered scan verifies that by counting.
-__global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, const int32_t* ids, int64_t seg_stride,
-                                                           const uint32_t* counts, uint32_t cap,
+__global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, const int32_t* ids, CandLayout lay,
+                                                           const uint32_t* counts,
                                                            const unsigned long long* sq, int kprime,
                                                            const uint8_t* skip, float* tau) {
     const int seg = blockIdx.x;
     if (skip && skip[seg]) return;
     bool over;
-    int64_t n = seg_count(counts, cap, 0, seg, &over);
+    int64_t n = seg_count(counts, lay.cap(seg), seg, &over);
     const double mu = (double)kprime * (double)n / (double)(sq[seg] ? sq[seg] : 1ull);
     const int64_t r = (int64_t)ceil(mu + 5.0 * sqrt(mu) + 6.0);
     if (n < r || n == 0) {
         if (threadIdx.x == 0) tau[seg] = INFINITY;
         return;
     }
-    SegView s{nullptr, recs, ids, (int64_t)seg * seg_stride, n};
+    SegView s{nullptr, recs, ids, (int64_t)lay.base(seg), n};
     uint64_t pivot = radix_pivot(s, (uint32_t)r);
     if (threadIdx.x == 0) tau[seg] = __uint_as_float((uint32_t)(pivot >> 32));
 }
@@ -129,16 +128,16 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
 int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, const uint8_t* skip,
                            float* tau, hipStream_t st) {
     if (a.nseg <= 0) return IVFR_OK;
-    hipLaunchKernelGGL(select_tau_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.seg_stride, a.counts,
-                       a.cap, sq, kprime, skip, tau);
+    hipLaunchKernelGGL(select_tau_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.lay, a.counts, sq,
+                       kprime, skip, tau);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
 // ---- unordered compaction of the K smallest records -----------------------------------------
 __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs, const int32_t* ids,
-                                                               int64_t seg_stride, const uint32_t* counts,
-                                                               uint32_t cap, int64_t fixed_count, int K, int out_base,
+                                                               CandLayout lay, const uint32_t* counts, int K,
+                                                               int out_base,
                                                                const unsigned long long* sq, uint32_t* out_pos,
                                                                float* out_est, int32_t* out_n, int32_t* overflow,
                                                                int32_t* overflow_total) {
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs
     const int seg = blockIdx.x;
     const int q = out_base + seg;
     bool over;
-    int64_t n = seg_count(counts, cap, fixed_count, seg, &over);
+    int64_t n = seg_count(counts, lay.cap(seg), seg, &over);
     // the filter was too tight if it kept fewer than k' although more entries were visited
     if (sq && n < K && (unsigned long long)n < sq[seg]) over = true;
     if (threadIdx.x == 0) {
@@ -159,7 +158,7 @@ __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs
         if (threadIdx.x == 0) out_n[q] = 0;
         return;
     }
-    SegView s{nullptr, recs, ids, (int64_t)seg * seg_stride, n};
+    SegView s{nullptr, recs, ids, (int64_t)lay.base(seg), n};
     uint32_t* op = out_pos + (int64_t)q * K;
     float* oe = out_est + (int64_t)q * K;
     if (n <= K) {
@@ -188,9 +187,8 @@ int ivfr_launch_select_records(const SelectArgs& a, int out_base, const unsigned
                                float* out_est, int32_t* out_n, int32_t* overflow, int32_t* overflow_total,
                                hipStream_t st) {
     if (a.nseg <= 0) return IVFR_OK;
-    hipLaunchKernelGGL(select_records_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.seg_stride,
-                       a.counts, a.cap, a.fixed_count, a.K, out_base, sq, out_pos, out_est, out_n, overflow,
-                       overflow_total);
+    hipLaunchKernelGGL(select_records_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.lay, a.counts, a.K,
+                       out_base, sq, out_pos, out_est, out_n, overflow, overflow_total);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
