@@ -21,6 +21,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 
+# HBM bytes moved per adc_scan_kernel launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by a
+# plain copy of known size (profiles/search_cfg4_hbm_traffic.txt): 101.10 GB read + 0.15 GB written for
+# 101.14 GB of code bytes.  Stored as a ratio to the algorithmic bytes of the launch; other workloads: null.
+MEASURED_TRAFFIC_RATIO = {"cfg4": 101.252 / 101.141}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -208,7 +213,9 @@ def main():
         "build_seconds": build_t,
         "roofline": {"bound": "hbm", "kernel": "adc_scan_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes_per_launch": code_bytes,
+                     "traffic": (code_bytes * MEASURED_TRAFFIC_RATIO[cfg.name]
+                                 if cfg.name in MEASURED_TRAFFIC_RATIO and not (args.N or args.kprime) else None),
+                     "algorithmic_bytes_per_launch": code_bytes,
                      "avg_launch_ms": scan_avg_ms},
     }
     if not args.no_cpu_baseline:
