@@ -110,13 +110,13 @@ int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* 
 
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
  *   full_mult   (8)    a query that visits at most full_mult*k' entries keeps every estimate; a
- *                      larger one first scores a uniform sample of its entries (about 8/k' of
- *                      them) to bound the k'-th smallest estimate, and the scan keeps only
+ *                      larger one first scores a sample of its entries (the first 8/k' of every
+ *                      visited list) to bound the k'-th smallest estimate, and the scan keeps only
  *                      estimates below the bound
  *   cap_mult    (16)   such a query's candidate buffer holds max(cap_mult*k', min_cap) records,
  *   min_cap     (8192) or its sample if that is larger; overflowing it triggers an exact redo
  *   batch       (1024) queries processed per internal batch
- *   scan_groups (0 = 8 per compute unit) workgroups launched by the list-scan kernel          */
+ *   scan_groups (0 = 16 per compute unit) workgroups launched by the list-scan kernel          */
 int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int32_t min_cap, int32_t batch,
                     int32_t scan_groups);
 

@@ -11,7 +11,6 @@
 
 #define IVFR_KS 256            // reproduction values per sub-quantizer (8 bits)
 #define IVFR_LIST_ALIGN 32u    // every inverted list starts at a multiple of 32 entries
-#define IVFR_GRANULE 8u        // entries per sample granule
 #define IVFR_BLOCK 512u        // entries per scan block: one 16-byte load per thread of a 256-thread group
 #define IVFR_TAIL_PAD 1024u    // zero entries after the last list so vector loads never run off the end
 
@@ -178,9 +177,10 @@ int ivfr_select_init();   // one-time function attributes
 struct PlanBuffers {
     uint32_t* pair_start;  // [P] first padded entry of the pair's list
     uint32_t* len;         // [P] entries of the pair's list
+    uint32_t* len_s;       // [P] leading entries of the pair's list that belong to the sample
     uint32_t* blkpre;      // [P+1] exclusive prefix of scan blocks over the pairs
-    uint32_t* gpre;        // [nq, w+1] per query: exclusive prefix of sample granules over its pairs
-    uint32_t* stride;      // [nq] every stride-th granule of the query is sampled
+    uint32_t* blkpre_s;    // [P+1] same for the sample
+    uint32_t* nsample;     // [nq] sampled entries of the query
     uint32_t* capq;        // [nq] records in the query's candidate buffer
     unsigned long long* coff;    // [nq] first record of the query's candidate buffer in the pool
     unsigned long long* sq;      // [nq] entries in the query's visited lists
@@ -191,8 +191,6 @@ int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, 
                      uint32_t stride_k, uint32_t min_cap, const PlanBuffers& pb, hipStream_t st);
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
                     float* lut, hipStream_t st);
-int ivfr_launch_sample(const ivfr_index* ix, const float* lut, const PlanBuffers& pb, int nq, int w, uint2* cand,
-                       uint32_t* cand_cnt, CandLayout lay, int ychunks, hipStream_t st);
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
                      CandLayout lay, int groups, hipStream_t st);

@@ -9,54 +9,51 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // the k'-th smallest estimate is bounded before the scan:
 //  - a query whose visited lists hold at most `full_limit` entries keeps every estimate
 //    (tau = +inf) and is selected from directly;
-//  - otherwise a uniform sample of the visited entries is scored first: the lists' entries
-//    form one virtual stream of 8-entry granules (64 code bytes at m = 8) and every stride-th
-//    granule is taken, stride = k' / mu so that about mu of the true k' best fall in the sample.
+//  - otherwise a sample is scored first: the first ceil(len / stride) entries of every visited
+//    list, stride = k' / mu, so that about mu of the true k' best fall in the sample.  Entries
+//    of a list are in id order, which carries no information about the distance to a query,
+//    so a prefix is as good as a random draw, and taking the same fraction of every visited
+//    list keeps the sample stratified over near and far lists.
 // ------------------------------------------------------------------------------------------
 __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int w,
                                   const uint32_t* __restrict__ list_start, const uint32_t* __restrict__ list_len,
                                   uint32_t full_limit, uint32_t stride_k, uint32_t min_cap, PlanBuffers pb) {
     int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nq) return;
-    unsigned long long total = 0, gran = 0;
-    uint32_t* gp = pb.gpre + (int64_t)q * (w + 1);
+    const uint32_t stride = stride_k < 1 ? 1u : stride_k;
+    unsigned long long total = 0;
+    for (int r = 0; r < w; ++r) total += list_len[probe[(int64_t)q * w + r]];
+    const bool fully = total <= full_limit;
+    unsigned long long sampled = 0;
     for (int r = 0; r < w; ++r) {
         int64_t p = (int64_t)q * w + r;
         int l = probe[p];
         uint32_t len = list_len[l];
         pb.pair_start[p] = list_start[l];
         pb.len[p] = len;
-        gp[r] = (uint32_t)gran;
-        total += len;
-        gran += (len + IVFR_GRANULE - 1) / IVFR_GRANULE;
+        uint32_t ls = fully ? 0u : (len + stride - 1) / stride;
+        pb.len_s[p] = ls;
+        sampled += ls;
     }
-    gp[w] = (uint32_t)gran;
-    const bool fully = total <= full_limit;
     pb.sq[q] = total;
+    pb.nsample[q] = (uint32_t)(sampled > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : sampled);
     pb.fully[q] = fully ? 1 : 0;
-    const uint32_t stride = stride_k < 1 ? 1u : stride_k;
-    pb.stride[q] = stride;
     // buffer: everything (no filter), or the larger of the sample and the survivors' allowance
-    unsigned long long capv;
-    if (fully) capv = total;
-    else {
-        capv = (gran / stride + 2) * IVFR_GRANULE;
-        if (capv < min_cap) capv = min_cap;
-    }
+    unsigned long long capv = fully ? total : (sampled > min_cap ? sampled : (unsigned long long)min_cap);
     if (capv > 0xFFFFFFF0ull) capv = 0xFFFFFFF0ull;
     pb.capq[q] = (uint32_t)capv;
     atomicAdd(pb.totals, total);
 }
 
 // Exclusive prefix sums (one workgroup): candidate-buffer offsets over the nq queries, then
-// ceil(len / IVFR_BLOCK) over the P pairs.
+// ceil(len / IVFR_BLOCK) over the P pairs for the scan and for the sample.
 __global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int P, PlanBuffers pb) {
-    __shared__ uint32_t wtot[16];
-    __shared__ uint32_t carry;
+    __shared__ uint32_t wtot[2][16];
+    __shared__ uint32_t carry[2];
     __shared__ unsigned long long wtot64[16];
     __shared__ unsigned long long carry64;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid == 0) { carry = 0; carry64 = 0; }
+    if (tid == 0) { carry[0] = carry[1] = 0; carry64 = 0; }
     __syncthreads();
     for (int base = 0; base < nq; base += 1024) {
         int q = base + tid;
@@ -80,25 +77,34 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int P, PlanBuff
     if (tid == 0) pb.totals[1] = carry64;
     for (int base = 0; base < P; base += 1024) {
         int p = base + tid;
-        uint32_t v = 0;
-        if (p < P) v = (pb.len[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
-        uint32_t inc = v;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            uint32_t o = __shfl_up(inc, off, 64);
-            if (lane >= off) inc += o;
+        uint32_t v[2] = {0, 0};
+        if (p < P) {
+            v[0] = (pb.len[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
+            v[1] = (pb.len_s[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
         }
-        if (lane == 63) wtot[wv] = inc;
+        uint32_t inc[2] = {v[0], v[1]};
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                uint32_t o = __shfl_up(inc[a], off, 64);
+                if (lane >= off) inc[a] += o;
+            }
+            if (lane == 63) wtot[a][wv] = inc[a];
+        }
         __syncthreads();
-        uint32_t add = carry;
-        for (int x = 0; x < wv; ++x) add += wtot[x];
-        inc += add;
-        if (p < P) pb.blkpre[p] = inc - v;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            uint32_t add = carry[a];
+            for (int x = 0; x < wv; ++x) add += wtot[a][x];
+            inc[a] += add;
+        }
+        if (p < P) { pb.blkpre[p] = inc[0] - v[0]; pb.blkpre_s[p] = inc[1] - v[1]; }
         __syncthreads();
-        if (tid == 1023) carry = inc;
+        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; }
         __syncthreads();
     }
-    if (tid == 0) pb.blkpre[P] = carry;
+    if (tid == 0) { pb.blkpre[P] = carry[0]; pb.blkpre_s[P] = carry[1]; }
 }
 
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
@@ -302,114 +308,39 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
             for (int i = tid; i < M * IVFR_KS / 4; i += 256) dst[i] = src[i];
         }
         __syncthreads();
-        for (; b < stop; ++b) {
-            const uint32_t e0 = (b - pb0) * IVFR_BLOCK + 2u * tid;   // entry inside the list
-            uint32_t wds[2][M / 4];
-            bool in0 = e0 < len, in1 = e0 + 1 < len;
-            float est0 = 0.f, est1 = 0.f;
-            if (in0) {
-                const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e0) * M);
-                if (M == 8) {
-                    uint4 v = *reinterpret_cast<const uint4*>(src);
-                    wds[0][0] = v.x; wds[0][1] = v.y; wds[1][0] = v.z; wds[1][1] = v.w;
+        // two blocks per iteration: both loads are issued before the first table look-up
+        for (uint32_t bb = b; bb < stop; bb += 2) {
+            uint32_t wds[2][2][M / 4];
+            uint32_t e0[2];
+            bool in0[2], in1[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                e0[u] = (bb + u - pb0) * IVFR_BLOCK + 2u * tid;   // entry inside the list
+                in0[u] = bb + u < stop && e0[u] < len;
+                in1[u] = bb + u < stop && e0[u] + 1 < len;
+                if (in0[u]) {
+                    const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e0[u]) * M);
+                    if (M == 8) {
+                        uint4 v = *reinterpret_cast<const uint4*>(src);
+                        wds[u][0][0] = v.x; wds[u][0][1] = v.y; wds[u][1][0] = v.z; wds[u][1][1] = v.w;
+                    } else {
+#pragma unroll
+                        for (int t2 = 0; t2 < M / 4; ++t2) { wds[u][0][t2] = src[t2]; wds[u][1][t2] = src[M / 4 + t2]; }
+                    }
                 } else {
 #pragma unroll
-                    for (int t2 = 0; t2 < M / 4; ++t2) { wds[0][t2] = src[t2]; wds[1][t2] = src[M / 4 + t2]; }
+                    for (int t2 = 0; t2 < M / 4; ++t2) { wds[u][0][t2] = 0; wds[u][1][t2] = 0; }
                 }
-                est0 = adc_sum<M>(s_lut, wds[0]);
-                est1 = adc_sum<M>(s_lut, wds[1]);
             }
-            append_records(in0 && est0 <= t, est0, start + e0, in1 && est1 <= t, est1, start + e0 + 1, qc, cnt, cap);
-        }
-    }
-}
-
-// Sample pass: one thread scores one sampled granule of IVFR_GRANULE consecutive entries, reading
-// the pair's table from global memory (the sample is a small fraction of the scan), and the
-// wavefront appends its valid records to the query's buffer with one atomic.
-template <int M>
-__global__ __launch_bounds__(256) void adc_sample_kernel(const uint8_t* __restrict__ codes,
-                                                         const float* __restrict__ lut,
-                                                         const uint32_t* __restrict__ pair_start,
-                                                         const uint32_t* __restrict__ pair_len,
-                                                         const uint32_t* __restrict__ gpre,
-                                                         const uint32_t* __restrict__ stride_q,
-                                                         const uint8_t* __restrict__ fully, int w,
-                                                         uint2* __restrict__ cand, uint32_t* __restrict__ cand_cnt,
-                                                         CandLayout lay) {
-    const int q = blockIdx.x;
-    if (fully[q]) return;
-    const uint32_t* gp = gpre + (int64_t)q * (w + 1);
-    const uint32_t G = gp[w], st = stride_q[q], off = st >> 1;
-    const uint32_t nsg = G > off ? (G - off + st - 1) / st : 0u;
-    uint2* qc = cand + lay.base(q);
-    const uint32_t cap = lay.cap(q);
-    uint32_t* cnt = cand_cnt + q;
-    const int lane = threadIdx.x & 63;
-    for (uint32_t j0 = blockIdx.y * 256u; j0 < nsg; j0 += gridDim.y * 256u) {
-        const uint32_t j = j0 + threadIdx.x;
-        float est[IVFR_GRANULE];
-        uint32_t nvalid = 0, pos0 = 0;
-        if (j < nsg) {
-            const uint32_t g = off + j * st;
-            int lo = 0, hi = w;   // last r with gp[r] <= g
-            while (hi - lo > 1) {
-                int mid = (lo + hi) >> 1;
-                if (gp[mid] <= g) lo = mid; else hi = mid;
-            }
-            const int64_t p = (int64_t)q * w + lo;
-            const uint32_t e0 = (g - gp[lo]) * IVFR_GRANULE, len = pair_len[p], start = pair_start[p];
-            nvalid = len - e0 < IVFR_GRANULE ? len - e0 : IVFR_GRANULE;
-            pos0 = start + e0;
-            const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + (uint64_t)pos0 * M);
-            const float* T = lut + p * M * IVFR_KS;
 #pragma unroll
-            for (int t = 0; t < IVFR_GRANULE; ++t) {
-                uint32_t wds[M / 4];
-#pragma unroll
-                for (int x = 0; x < M / 4; ++x) wds[x] = src[t * (M / 4) + x];
-                est[t] = adc_sum<M>(T, wds);
+            for (int u = 0; u < 2; ++u) {
+                const float est0 = adc_sum<M>(s_lut, wds[u][0]);
+                const float est1 = adc_sum<M>(s_lut, wds[u][1]);
+                append_records(in0[u] && est0 <= t, est0, start + e0[u], in1[u] && est1 <= t, est1, start + e0[u] + 1,
+                               qc, cnt, cap);
             }
         }
-        // wavefront-aggregated append
-        uint32_t inc = nvalid;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            uint32_t v = __shfl_up(inc, o, 64);
-            if (lane >= o) inc += v;
-        }
-        const uint32_t total = __shfl(inc, 63, 64);
-        if (total == 0) continue;
-        uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(cnt, total);
-        base = __shfl(base, 0, 64) + inc - nvalid;
-#pragma unroll
-        for (int t = 0; t < IVFR_GRANULE; ++t)
-            if ((uint32_t)t < nvalid && base + t < cap) qc[base + t] = make_uint2(__float_as_uint(est[t]), pos0 + t);
-    }
-}
-
-template <int M>
-static int launch_sample_m(const ivfr_index* ix, const float* lut, const PlanBuffers& pb, int nq, int w, uint2* cand,
-                           uint32_t* cand_cnt, CandLayout lay, int ychunks, hipStream_t st) {
-    hipLaunchKernelGGL(adc_sample_kernel<M>, dim3(nq, ychunks), dim3(256), 0, st, ix->codes, lut, pb.pair_start,
-                       pb.len, pb.gpre, pb.stride, pb.fully, w, cand, cand_cnt, lay);
-    IVFR_HIP(hipGetLastError());
-    return IVFR_OK;
-}
-
-int ivfr_launch_sample(const ivfr_index* ix, const float* lut, const PlanBuffers& pb, int nq, int w, uint2* cand,
-                       uint32_t* cand_cnt, CandLayout lay, int ychunks, hipStream_t st) {
-    if (nq <= 0) return IVFR_OK;
-    switch (ix->p.m) {
-        case 4: return launch_sample_m<4>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
-        case 8: return launch_sample_m<8>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
-        case 16: return launch_sample_m<16>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
-        case 32: return launch_sample_m<32>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
-        case 64: return launch_sample_m<64>(ix, lut, pb, nq, w, cand, cand_cnt, lay, ychunks, st);
-        default:
-            ivfr_set_error("list scan supports m in {4, 8, 16, 32, 64}; got %d", ix->p.m);
-            return IVFR_ERR_INVALID_ARG;
+        b = stop;
     }
 }
 

@@ -77,7 +77,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const uint32_t min_cap = (uint32_t)std::max<int64_t>((int64_t)ix->cap_mult * kprime, ix->min_cap);
     const uint32_t full_limit = (uint32_t)std::min<int64_t>((int64_t)ix->full_mult * kprime, 1ll << 30);
     const uint32_t stride_k = (uint32_t)std::max(1, kprime / IVFR_SAMPLE_MU);
-    const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 8;
+    const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 16;
 
     // carve the workspace
     Carver cv;
@@ -88,8 +88,9 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_pstart = cv.take<uint32_t>(P);
     const size_t o_len = cv.take<uint32_t>(P);
     const size_t o_pre = cv.take<uint32_t>((size_t)P + 1);
-    const size_t o_gpre = cv.take<uint32_t>((size_t)B * (w + 1));
-    const size_t o_stride = cv.take<uint32_t>(B);
+    const size_t o_lens = cv.take<uint32_t>(P);
+    const size_t o_pres = cv.take<uint32_t>((size_t)P + 1);
+    const size_t o_nsample = cv.take<uint32_t>(B);
     const size_t o_sq = cv.take<unsigned long long>(B);
     const size_t o_fully = cv.take<uint8_t>(B);
     const size_t o_totals = cv.take<unsigned long long>(2);
@@ -117,8 +118,9 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     pb.pair_start = reinterpret_cast<uint32_t*>(ws + o_pstart);
     pb.len = reinterpret_cast<uint32_t*>(ws + o_len);
     pb.blkpre = reinterpret_cast<uint32_t*>(ws + o_pre);
-    pb.gpre = reinterpret_cast<uint32_t*>(ws + o_gpre);
-    pb.stride = reinterpret_cast<uint32_t*>(ws + o_stride);
+    pb.len_s = reinterpret_cast<uint32_t*>(ws + o_lens);
+    pb.blkpre_s = reinterpret_cast<uint32_t*>(ws + o_pres);
+    pb.nsample = reinterpret_cast<uint32_t*>(ws + o_nsample);
     pb.sq = reinterpret_cast<unsigned long long*>(ws + o_sq);
     pb.fully = reinterpret_cast<uint8_t*>(ws + o_fully);
     pb.totals = reinterpret_cast<unsigned long long*>(ws + o_totals);
@@ -190,7 +192,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_HIP(hipMemsetAsync(overtot, 0, 4 * sizeof(int32_t), st));
         hipLaunchKernelGGL(fill_f32_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, tau, (int64_t)nb, INFINITY);
-        IVFR_TRY(ivfr_launch_sample(ix, lut, pb, nb, w, cand, cnt, lay, 16, st));
+        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len_s, pb.blkpre_s, Pb, w, tau, cand, cnt, lay, groups, st));
         {
             SelectArgs a;
             a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = cnt; a.lay = lay;

@@ -11,11 +11,13 @@
 // digit of the keys that still match the prefix found so far (LDS atomics), a workgroup scan
 // finds the digit bucket that holds the K-th smallest, and the prefix grows by one byte.
 // After 8 passes the prefix is the K-th smallest key itself (the pivot); a last sweep emits
-// every key <= pivot.  For short-list records the low half (the vector id) is fetched from
+// every key <= pivot.  (As soon as few keys still match the prefix they are sorted in LDS
+// instead, which ends the passes early.)  For short-list records the low half (the vector id) is fetched from
 // the id array only in passes 4-7 and only for records whose estimate equals the pivot's.
 #include "ivfr_internal.h"
 
 #define SEL_T 512
+#define SEL_LCAP 2048
 #define SORT_MAX 16384
 
 struct SegView {
@@ -42,14 +44,19 @@ __device__ __forceinline__ uint32_t seg_lo(const SegView& s, uint32_t pos) {
 }
 
 // Returns the K-th smallest key of the segment (1 <= K <= n).  All threads must call.
+// Radix passes run only while more than SEL_LCAP keys still match the prefix; the remaining
+// candidates are then gathered into LDS, sorted there, and the pivot is read off directly.
 __device__ uint64_t radix_pivot(const SegView& s, uint32_t K) {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wsum[SEL_T / 64];
-    __shared__ uint32_t s_bin, s_need;
+    __shared__ uint32_t s_bin, s_need, s_match, s_fill;
+    __shared__ uint64_t lbuf[SEL_LCAP];
     const int tid = threadIdx.x;
     uint64_t prefix = 0;
     uint32_t need = K;
-    for (int pass = 0; pass < 8; ++pass) {
+    uint64_t nmatch = (uint64_t)s.n;
+    int pass = 0;
+    for (; pass < 8 && nmatch > SEL_LCAP; ++pass) {
         const int shift = 56 - 8 * pass;
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
@@ -84,14 +91,54 @@ __device__ uint64_t radix_pivot(const SegView& s, uint32_t K) {
             for (int wv = 0; wv < (tid >> 6); ++wv) add += wsum[wv];
             inc += add;
             uint32_t exc = inc - h;
-            if (exc < need && need <= inc) { s_bin = (uint32_t)tid; s_need = need - exc; }
+            if (exc < need && need <= inc) { s_bin = (uint32_t)tid; s_need = need - exc; s_match = h; }
         }
         __syncthreads();
         prefix = (prefix << 8) | s_bin;
         need = s_need;
+        nmatch = s_match;
         __syncthreads();
     }
-    return prefix;
+    if (pass == 8) return prefix;
+    // gather the keys whose top `pass` bytes equal the prefix
+    if (tid == 0) s_fill = 0;
+    __syncthreads();
+    for (int64_t i = tid; i < s.n; i += SEL_T) {
+        uint32_t pos;
+        uint32_t hi = seg_hi(s, i, &pos);
+        bool match;
+        if (pass == 0) match = true;
+        else if (pass <= 4) match = (hi >> (32 - 8 * pass)) == (uint32_t)prefix;
+        else match = hi == (uint32_t)(prefix >> (8 * (pass - 4)));
+        if (match) {
+            uint64_t key = ((uint64_t)hi << 32) | seg_lo(s, pos);
+            if (pass > 4 && (key >> (64 - 8 * pass)) != prefix) continue;
+            uint32_t slot = atomicAdd(&s_fill, 1u);
+            if (slot < SEL_LCAP) lbuf[slot] = key;
+        }
+    }
+    __syncthreads();
+    const uint32_t mcount = s_fill < SEL_LCAP ? s_fill : SEL_LCAP;
+    uint32_t n2 = 2;
+    while (n2 < mcount) n2 <<= 1;
+    for (uint32_t i = mcount + tid; i < n2; i += SEL_T) lbuf[i] = ~0ull;
+    __syncthreads();
+    for (uint32_t k = 2; k <= n2; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            for (uint32_t i = tid; i < n2; i += SEL_T) {
+                uint32_t ixj = i ^ j;
+                if (ixj > i) {
+                    uint64_t a = lbuf[i], b = lbuf[ixj];
+                    bool asc = (i & k) == 0;
+                    if ((a > b) == asc) { lbuf[i] = b; lbuf[ixj] = a; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    const uint64_t pivot = lbuf[need - 1];
+    __syncthreads();
+    return pivot;
 }
 
 __device__ __forceinline__ int64_t seg_count(const uint32_t* counts, uint32_t cap, int seg, bool* over) {
