@@ -110,7 +110,7 @@ int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* 
 
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
  *   full_mult   (8)    a query that visits at most full_mult*k' entries keeps every estimate; a
- *                      larger one first scores a sample of its entries (the first 8/k' of every
+ *                      larger one first scores a sample of its entries (the first 4/k' of every
  *                      visited list) to bound the k'-th smallest estimate, and the scan keeps only
  *                      estimates below the bound
  *   cap_mult    (16)   such a query's candidate buffer holds max(cap_mult*k', min_cap) records,

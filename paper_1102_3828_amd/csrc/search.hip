@@ -47,7 +47,7 @@ struct EventPair {
 }
 
 // Poisson mean of true k'-best entries wanted inside the sample; the sample stride is k' / mu.
-#define IVFR_SAMPLE_MU 8
+#define IVFR_SAMPLE_MU 4
 
 extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t nq, int32_t w, int32_t kprime,
                                  int32_t k, int32_t* ids_out, float* dist_out, int32_t* probe_out,

@@ -55,6 +55,66 @@ __device__ uint64_t radix_pivot(const SegView& s, uint32_t K) {
     uint64_t prefix = 0;
     uint32_t need = K;
     uint64_t nmatch = (uint64_t)s.n;
+    if (K <= SEL_T / 2 && s.n > SEL_LCAP) {
+        // Small K: every thread takes the minimum distance word of its strided share; the K-th
+        // smallest of those SEL_T minima bounds the K-th smallest key from above, and at least K
+        // keys lie at or below it.  Those few keys are gathered and sorted in LDS: two sweeps.
+        uint32_t mn = 0xFFFFFFFFu;
+        for (int64_t i = tid; i < s.n; i += SEL_T) {
+            uint32_t pos;
+            uint32_t hi = seg_hi(s, i, &pos);
+            mn = hi < mn ? hi : mn;
+        }
+        lbuf[tid] = mn;
+        __syncthreads();
+        for (uint32_t k = 2; k <= SEL_T; k <<= 1)
+            for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+                uint32_t i = tid, ixj = i ^ j;
+                if (ixj > i) {
+                    uint64_t a = lbuf[i], b = lbuf[ixj];
+                    bool asc = (i & k) == 0;
+                    if ((a > b) == asc) { lbuf[i] = b; lbuf[ixj] = a; }
+                }
+                __syncthreads();
+            }
+        const uint32_t bound = (uint32_t)lbuf[K - 1];
+        __syncthreads();
+        if (tid == 0) s_fill = 0;
+        __syncthreads();
+        for (int64_t i = tid; i < s.n; i += SEL_T) {
+            uint32_t pos;
+            uint32_t hi = seg_hi(s, i, &pos);
+            if (hi <= bound) {
+                uint32_t slot = atomicAdd(&s_fill, 1u);
+                if (slot < SEL_LCAP) lbuf[slot] = ((uint64_t)hi << 32) | seg_lo(s, pos);
+            }
+        }
+        __syncthreads();
+        const uint32_t got = s_fill;
+        __syncthreads();
+        if (got <= SEL_LCAP) {
+            uint32_t n2 = 2;
+            while (n2 < got) n2 <<= 1;
+            for (uint32_t i = got + tid; i < n2; i += SEL_T) lbuf[i] = ~0ull;
+            __syncthreads();
+            for (uint32_t k = 2; k <= n2; k <<= 1)
+                for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+                    for (uint32_t i = tid; i < n2; i += SEL_T) {
+                        uint32_t ixj = i ^ j;
+                        if (ixj > i) {
+                            uint64_t a = lbuf[i], b = lbuf[ixj];
+                            bool asc = (i & k) == 0;
+                            if ((a > b) == asc) { lbuf[i] = b; lbuf[ixj] = a; }
+                        }
+                    }
+                    __syncthreads();
+                }
+            const uint64_t pivot = lbuf[K - 1];
+            __syncthreads();
+            return pivot;
+        }
+        // too many equal distance words: fall through to the radix passes
+    }
     int pass = 0;
     for (; pass < 8 && nmatch > SEL_LCAP; ++pass) {
         const int shift = 56 - 8 * pass;

@@ -70,7 +70,13 @@ def compare_results(gpu_ids, gpu_dist, X, index, w, kprime, k, rel=REL_TOL, abs_
     abs_floor keeps the relative test meaningful for near-zero distances.
     """
     exact = excused = 0
-    inv = orc.entry_of_id(index)
+    if index.N <= 50_000_000:
+        inv = orc.entry_of_id(index)
+    else:
+        class _Lazy:   # a handful of look-ups in a huge index: search instead of an N-long inverse
+            def __getitem__(self, i):
+                return int(np.flatnonzero(index.ids == np.int32(i))[0])
+        inv = _Lazy()
     offs = index.list_offsets
     for qi, x in enumerate(X):
         o_ids, o_dist, tr = orc.search_one(x, index, w, kprime, k)

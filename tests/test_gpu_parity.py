@@ -186,6 +186,76 @@ def test_config0_end_to_end_gpu_built_index():
     ix.close()
 
 
+def _full_size_case(name, n_check, **override):
+    """A benchmark workload at its full size, in the launch configuration the benchmark times
+    (index built on the GPU from the HIP generator, first batch of 1000 queries searched in one
+    call); n_check of those queries are verified one by one against the oracle on the exported index."""
+    import dataclasses
+    import paper_1102_3828_amd as pkg
+    from synthdata.gpu import DeviceMixture
+    torch = _torch()
+    cfg = dataclasses.replace(sd.CONFIGS[name], **override)
+    dm = DeviceMixture(cfg.mixture())
+    ix = pkg.Index(cfg.d, cfg.c, cfg.m, cfg.m_refine)
+    log(name, "train")
+    ix.train(dm.generate(sd.STREAM_TRAIN, 0, cfg.n_train), iters=10, seed=1)
+    buf = None
+    for j, a in enumerate(range(0, cfg.N, sd.BASE_CHUNK)):
+        n = min(sd.BASE_CHUNK, cfg.N - a)
+        if buf is None or buf.shape[0] != n:
+            buf = torch.empty((n, cfg.d), dtype=torch.uint8, device="cuda")
+        dm.generate(sd.STREAM_BASE0 + j, 0, n, out=buf)
+        ix.add(buf, a)
+        if j % 20 == 19:
+            log(name, "added", a + n)
+    del buf
+    ix.finalize()
+    B = min(cfg.batch, cfg.n_query)
+    q_u8 = dm.generate(sd.STREAM_QUERY, 0, B)
+    log(name, "search")
+    g_ids, g_dist = ix.search(q_u8.float().contiguous(), cfg.w, cfg.kprime, cfg.k)
+    st = ix.search_stats()
+    log(name, st)
+    # closed form of section 3.3: a fraction of the order of w/c of the database is visited
+    frac = st["codes_scanned"] / float(B) / cfg.N
+    assert 0.3 * cfg.w / cfg.c < frac < (30.0 if cfg.zipf else 4.0) * cfg.w / cfg.c
+    # properties that hold at any size: ascending distances, distinct valid ids
+    gi, gd = g_ids.cpu().numpy(), g_dist.cpu().numpy()
+    assert (np.diff(gd, axis=1) >= 0).all() and (gi >= 0).all() and (gi < cfg.N).all()
+    assert all(len(set(r.tolist())) == cfg.k for r in gi[:50])
+    log(name, "export")
+    coarse, pq, rq = ix.get_codebooks()
+    offsets, ids, codes, rcodes = ix.export()
+    ix.close()
+    index = orc.Index(orc.Codebooks(coarse, pq, rq), offsets, ids, codes, rcodes)
+    assert index.bytes_per_vector() == cfg.m + cfg.m_refine + 4
+    X = q_u8[:n_check].cpu().numpy()
+    log(name, "oracle on", n_check, "queries")
+    exact, excused = compare_results(gi[:n_check], gd[:n_check], X, index, cfg.w, cfg.kprime, cfg.k)
+    log(name, "exact", exact, "excused", excused)
+    assert exact >= 0.98 * n_check * cfg.k
+
+
+@pytest.mark.timeout(300)
+def test_full_size_config1():
+    _full_size_case("cfg1", 24)
+
+
+@pytest.mark.timeout(300)
+def test_full_size_config2():
+    _full_size_case("cfg2", 16)
+
+
+@pytest.mark.timeout(600)
+def test_full_size_config3():
+    _full_size_case("cfg3", 4)
+
+
+@pytest.mark.timeout(900)
+def test_full_size_config4_one_billion():
+    _full_size_case("cfg4", 3)
+
+
 def test_gpu_training_quality_matches_oracle():
     """k-means is chaotic, so trained codebooks are compared by their quantization error."""
     import paper_1102_3828_amd as pkg
