@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 # HBM bytes moved per adc_scan_kernel launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by a
 # plain copy of known size (profiles/search_cfg4_hbm_traffic.txt): 101.10 GB read + 0.15 GB written for
 # 101.14 GB of code bytes.  Stored as a ratio to the algorithmic bytes of the launch; other workloads: null.
-MEASURED_TRAFFIC_RATIO = {"cfg4": 101.252 / 101.141}
+MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 101.252 / 101.141}
 
 
 def log(*a):
@@ -119,6 +119,8 @@ def main():
     ap.add_argument("--gt-queries", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scan-groups", type=int, default=0)
+    ap.add_argument("--per-pair", action="store_true",
+                    help="scan every (query, list) pair on its own (no sharing of a list between queries)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB) three times, as the "
                          "known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -148,6 +150,8 @@ def main():
     ix, xq, queries_u8, gt, build_t = build_index(cfg, dm, n_gt, args)
     if args.scan_groups:
         ix.set_tuning(scan_groups=args.scan_groups)
+    if args.per_pair:
+        ix.set_list_sharing(False)
 
     B = min(cfg.batch, cfg.n_query)
     n_batches = max(1, cfg.n_query // B)
@@ -160,6 +164,8 @@ def main():
     ix.set_profiling(True)
     torch.cuda.synchronize()
     codes = 0
+    codes_shared = 0
+    codes_streamed = 0
     dense_total = 0
     stage_ms = {}
     scan_launches = 0
@@ -169,6 +175,8 @@ def main():
         st = ix.search_stats()
         pr = ix.stage_times()
         codes += st["codes_scanned"]
+        codes_shared += st["codes_scanned_shared"]
+        codes_streamed += st["codes_streamed"]
         scan_launches += pr.pop("scan_launches")
         for name, ms in pr.items():
             stage_ms[name] = stage_ms.get(name, 0.0) + ms
@@ -195,28 +203,40 @@ def main():
             recall[f"recall@{r}"] = float((g_ids[:n_gt, :r] == gt[:n_gt, None]).any(axis=1).mean())
 
     qps = args.steps * B / elapsed
-    code_bytes = cfg.m * codes / max(args.steps, 1)            # algorithmic bytes per filtered-scan launch
-    scan_avg_ms = stage_ms.get("scan", 0.0) / max(scan_launches, 1)
-    achieved = code_bytes / (scan_avg_ms * 1e-3) / 1e9 if scan_avg_ms > 0 else 0.0
+    steps = max(args.steps, 1)
+    # Dominant kernel: the shared-list scan when it does most of the work, else the per-pair scan.
+    # Algorithmic bytes = m bytes per (query, visited entry) estimate the kernel computes.
+    ms_pair, ms_shared = stage_ms.get("scan", 0.0) / steps, stage_ms.get("scan_shared", 0.0) / steps
+    if ms_shared > ms_pair:
+        kname, k_ms, k_codes = "adc_scan_shared_kernel", ms_shared, codes_shared / steps
+    else:
+        kname, k_ms, k_codes = "adc_scan_kernel", ms_pair, (codes - codes_shared) / steps
+    code_bytes = cfg.m * k_codes
+    achieved = code_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
+    traffic_key = (cfg.name, kname)
+    plain = not (args.N or args.kprime or args.m_refine >= 0)
     out = {
         "metric": "queries/s", "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N} d={cfg.d} c={cfg.c} m={cfg.m} m'={cfg.m_refine} "
                                f"w={cfg.w} k'={cfg.kprime} k={cfg.k}, {B} queries per step",
-                   "generator": f"uint8 Gaussian mixture G={cfg.G} zipf={cfg.zipf} seed={sd.BASE_SEED}"},
+                   "generator": f"uint8 Gaussian mixture G={cfg.G} zipf={cfg.zipf} seed={sd.BASE_SEED}",
+                   "list_sharing": not args.per_pair},
         "adc_codes_per_s": codes / elapsed,
-        "codes_scanned_per_step": codes / max(args.steps, 1),
+        "codes_scanned_per_step": codes / steps,
+        "codes_streamed_per_step": codes_streamed / steps,
+        "codes_scanned_shared_per_step": codes_shared / steps,
         "stage_ms_per_step": {name: ms / args.steps for name, ms in stage_ms.items()},
         "dense_fallbacks_total": dense_total,
         "recall": recall, "recall_queries": n_gt,
         "build_seconds": build_t,
-        "roofline": {"bound": "hbm", "kernel": "adc_scan_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": kname, "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (code_bytes * MEASURED_TRAFFIC_RATIO[cfg.name]
-                                 if cfg.name in MEASURED_TRAFFIC_RATIO and not (args.N or args.kprime) else None),
+                     "traffic": (code_bytes * MEASURED_TRAFFIC_RATIO[traffic_key]
+                                 if traffic_key in MEASURED_TRAFFIC_RATIO and plain else None),
                      "algorithmic_bytes_per_launch": code_bytes,
-                     "avg_launch_ms": scan_avg_ms},
+                     "avg_launch_ms": k_ms},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ix, cfg, queries_u8, g_ids)

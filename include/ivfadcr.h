@@ -102,11 +102,22 @@ int ivfr_search_trace(ivfr_index* index, const float* queries, int64_t nq, int32
                       int32_t* short_ids_out, float* short_est_out, float* short_ref_out,
                       int32_t* short_count_out, void* stream);
 
-/* Counters of the most recent search call: entries whose estimator was computed (sum over
- * queries of the visited lists' lengths: the "v/c of the database" of section 3.3), (query,
- * list) pairs, and queries that took the dense fallback because the filtered candidate buffer
- * overflowed.  Any pointer may be NULL. */
-int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks);
+/* Counters of the most recent search call (any pointer may be NULL):
+ *   codes_scanned        (query, entry) estimates computed = sum over queries of the visited lists'
+ *                        lengths (the "v/c of the database" of section 3.3)
+ *   pairs                (query, list) pairs
+ *   dense_fallbacks      queries redone exactly because the sampled bound failed its check
+ *   codes_streamed       list entries read from memory by the scan (< codes_scanned when lists are
+ *                        shared between queries)
+ *   codes_scanned_shared part of codes_scanned computed by the shared-list scan                   */
+int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
+                      int64_t* codes_streamed, int64_t* codes_scanned_shared);
+
+/* List sharing (default on; needs m <= 16).  Queries of one internal batch that visit the same
+ * list are scanned four at a time: the list's codes are read once and each code byte fetches the
+ * four queries' table entries with one 16-byte LDS read.  Estimates, and therefore results, are
+ * bit-identical with sharing on or off; 0 scans every (query, list) pair on its own. */
+int ivfr_set_list_sharing(ivfr_index* index, int32_t enable);
 
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
  *   full_mult   (8)    a query that visits at most full_mult*k' entries keeps every estimate; a
@@ -122,17 +133,18 @@ int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int3
 
 /* Per-stage GPU time of the most recent search call, in milliseconds, measured with HIP events
  * on the search stream (recorded only after ivfr_set_profiling(index, 1)).  ms: host double
- * [IVFR_N_STAGES], indexed by IVFR_STAGE_*; scan_launches: launches of the list-scan kernel
- * (stage IVFR_STAGE_SCAN is exactly those launches), may be NULL. */
+ * [IVFR_N_STAGES], indexed by IVFR_STAGE_*; scan_launches: launches of the list-scan kernels
+ * (stages IVFR_STAGE_SCAN and IVFR_STAGE_SCAN_SHARED are exactly those launches), may be NULL. */
 #define IVFR_STAGE_COARSE    0   /* query norms + coarse distance GEMM                        */
 #define IVFR_STAGE_PROBE     1   /* w nearest lists + plan of (query, list) pairs             */
 #define IVFR_STAGE_LUT       2   /* look-up tables of Eq. (5)                                 */
 #define IVFR_STAGE_SAMPLE    3   /* sample scoring + bound selection                          */
-#define IVFR_STAGE_SCAN      4   /* ADC list scan                                             */
+#define IVFR_STAGE_SCAN      4   /* ADC list scan, one (query, list) pair at a time           */
 #define IVFR_STAGE_SHORTLIST 5   /* exact k' smallest of the survivors                        */
 #define IVFR_STAGE_RERANK    6   /* Eq. (9)-(10) over the short-list                          */
 #define IVFR_STAGE_FINAL     7   /* k smallest refined distances, sorted                      */
-#define IVFR_N_STAGES        8
+#define IVFR_STAGE_SCAN_SHARED 8 /* ADC list scan, four queries per pass over a shared list   */
+#define IVFR_N_STAGES        9
 int ivfr_set_profiling(ivfr_index* index, int32_t enable);
 int ivfr_stage_times(const ivfr_index* index, double* ms, int32_t* scan_launches);
 

@@ -49,7 +49,8 @@ def _load():
         "ivfr_import": (ctypes.c_int, [vp, i64, vp, vp, vp, vp]),
         "ivfr_search": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp]),
         "ivfr_search_trace": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
-        "ivfr_search_stats": (ctypes.c_int, [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]),
+        "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 5),
+        "ivfr_set_list_sharing": (ctypes.c_int, [vp, i32]),
         "ivfr_set_tuning": (ctypes.c_int, [vp, i32, i32, i32, i32, i32]),
         "ivfr_set_profiling": (ctypes.c_int, [vp, i32]),
         "ivfr_stage_times": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]),
@@ -64,7 +65,7 @@ def _load():
 lib = _load()
 EXPORTED = ["ivfr_create", "ivfr_destroy", "ivfr_train", "ivfr_set_codebooks", "ivfr_get_codebooks", "ivfr_add",
             "ivfr_finalize", "ivfr_ntotal", "ivfr_export", "ivfr_import", "ivfr_search", "ivfr_search_trace",
-            "ivfr_search_stats", "ivfr_set_tuning", "ivfr_set_profiling", "ivfr_stage_times", "ivfr_last_error"]
+            "ivfr_search_stats", "ivfr_set_list_sharing", "ivfr_set_tuning", "ivfr_set_profiling", "ivfr_stage_times", "ivfr_last_error"]
 
 
 def _check(rc):
@@ -193,9 +194,13 @@ class Index:
         return ids, dist, t
 
     def search_stats(self):
-        a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
-        _check(lib.ivfr_search_stats(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
-        return dict(codes_scanned=a.value, pairs=b.value, dense_fallbacks=c.value)
+        v = [ctypes.c_int64() for _ in range(5)]
+        _check(lib.ivfr_search_stats(self._h, *[ctypes.byref(x) for x in v]))
+        names = ("codes_scanned", "pairs", "dense_fallbacks", "codes_streamed", "codes_scanned_shared")
+        return dict(zip(names, [x.value for x in v]))
+
+    def set_list_sharing(self, enable=True):
+        _check(lib.ivfr_set_list_sharing(self._h, 1 if enable else 0))
 
     def set_tuning(self, full_mult=0, cap_mult=0, min_cap=0, batch=0, scan_groups=0):
         _check(lib.ivfr_set_tuning(self._h, full_mult, cap_mult, min_cap, batch, scan_groups))
@@ -203,7 +208,7 @@ class Index:
     def set_profiling(self, enable=True):
         _check(lib.ivfr_set_profiling(self._h, 1 if enable else 0))
 
-    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final")
+    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared")
 
     def stage_times(self):
         """Per-stage milliseconds of the last search (after set_profiling) and scan launch count."""

@@ -493,10 +493,19 @@ extern "C" int ivfr_stage_times(const ivfr_index* ix, double* ms, int32_t* scan_
     return IVFR_OK;
 }
 
-extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks) {
+extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
+                                 int64_t* codes_streamed, int64_t* codes_scanned_shared) {
     IVFR_REQUIRE(ix, "ivfr_search_stats: null index");
     if (codes_scanned) *codes_scanned = ix->st_codes;
     if (pairs) *pairs = ix->st_pairs;
     if (dense_fallbacks) *dense_fallbacks = ix->st_dense;
+    if (codes_streamed) *codes_streamed = ix->st_streamed;
+    if (codes_scanned_shared) *codes_scanned_shared = ix->st_shared_codes;
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_set_list_sharing(ivfr_index* ix, int32_t enable) {
+    IVFR_REQUIRE(ix, "ivfr_set_list_sharing: null index");
+    ix->share_lists = enable ? 1 : 0;
     return IVFR_OK;
 }

@@ -110,6 +110,7 @@ struct ivfr_index {
 
     // tuning
     int full_mult = 8, cap_mult = 16, batch = 1024, scan_groups = 0;
+    int share_lists = 1;             // 1 = scan lists visited by several queries of a batch once for four of them
     int min_cap = 8192;
 
     // scratch
@@ -117,7 +118,7 @@ struct ivfr_index {
     int* h_status = nullptr;         // pinned host word(s) for status read-back
 
     // stats of the last search
-    int64_t st_codes = 0, st_pairs = 0, st_dense = 0;
+    int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0;
     bool profiling = false;
     double prof_ms[IVFR_N_STAGES] = {0};
     int prof_scan_launches = 0;
@@ -191,9 +192,31 @@ int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, 
                      uint32_t stride_k, uint32_t min_cap, const PlanBuffers& pb, hipStream_t st);
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
                     float* lut, hipStream_t st);
+// unit_pairs == nullptr: unit u of the launch is pair u; otherwise pair unit_pairs[u]
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
-                     const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
-                     CandLayout lay, int groups, hipStream_t st);
+                     const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau, uint2* cand,
+                     uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st);
+
+// Shared scan: pairs of one batch grouped by list into units of four plus left-over pairs
+struct GroupBuffers {
+    uint32_t* list_np;      // [c] pairs visiting each list
+    uint32_t* g4;           // [c] exclusive prefix of units of four
+    uint32_t* lo;           // [c] exclusive prefix of left-over pairs
+    uint32_t* cur;          // [c] fill cursors
+    uint32_t* counts;       // [2] number of units of four, number of left-over pairs
+    uint32_t* unit4_pairs;  // [P] pair ids, four per unit
+    uint32_t* lo_pairs;     // [P] left-over pair ids
+    uint32_t* blk4;         // [P/4 + 1] block prefix over units of four
+    uint32_t* blklo;        // [P + 1] block prefix over left-over pairs
+    unsigned long long* work;  // [2] list entries streamed by the shared scan, by the per-pair scan
+};
+int ivfr_launch_group_plan(const int32_t* probe, int P, int c, const uint32_t* pair_len, const GroupBuffers& gb,
+                           hipStream_t st);
+bool ivfr_shared_scan_supported(const ivfr_index* ix);
+int ivfr_launch_scan_shared(const ivfr_index* ix, const float* lut, const uint32_t* pair_start,
+                            const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
+                            int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
+                            hipStream_t st);
 
 // Encoding (encode.hip)
 int ivfr_launch_residual(float* X, int64_t n, int d, const float* C, const int32_t* assign, hipStream_t st);

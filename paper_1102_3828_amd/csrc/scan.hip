@@ -274,7 +274,8 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                                                        const float* __restrict__ lut,
                                                        const uint32_t* __restrict__ pair_start,
                                                        const uint32_t* __restrict__ pair_len,
-                                                       const uint32_t* __restrict__ blkpre, int P, int w,
+                                                       const uint32_t* __restrict__ blkpre,
+                                                       const uint32_t* __restrict__ unit_pairs, int P, int w,
                                                        const float* __restrict__ tau, uint2* __restrict__ cand,
                                                        uint32_t* __restrict__ cand_cnt, CandLayout lay) {
     extern __shared__ float s_lut[];   // M * 256 floats
@@ -295,15 +296,16 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
         while (blkpre[p + 1] <= b) ++p;   // skip pairs without blocks in this pass
         const uint32_t pb0 = blkpre[p], pb1 = blkpre[p + 1];
         const uint32_t stop = pb1 < b_end ? pb1 : b_end;
-        const int q = p / w;
-        const uint32_t start = pair_start[p], len = pair_len[p];
+        const int64_t pid = unit_pairs ? (int64_t)unit_pairs[p] : (int64_t)p;   // unit p of this launch is pair pid
+        const int q = (int)(pid / w);
+        const uint32_t start = pair_start[pid], len = pair_len[pid];
         const float t = tau[q];
         uint2* qc = cand + lay.base(q);
         const uint32_t cap = lay.cap(q);
         uint32_t* cnt = cand_cnt + q;
         __syncthreads();   // previous pair's table no longer in use
         {
-            const float4* src = reinterpret_cast<const float4*>(lut + (int64_t)p * M * IVFR_KS);
+            const float4* src = reinterpret_cast<const float4*>(lut + pid * M * IVFR_KS);
             float4* dst = reinterpret_cast<float4*>(s_lut);
             for (int i = tid; i < M * IVFR_KS / 4; i += 256) dst[i] = src[i];
         }
@@ -346,8 +348,8 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
 
 template <int M>
 static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
-                         const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
-                         CandLayout lay, int groups, hipStream_t st) {
+                         const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau,
+                         uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
     size_t lds = (size_t)M * IVFR_KS * sizeof(float);
     static bool attr_done = false;
     if (!attr_done && lds > 48 * 1024) {
@@ -356,19 +358,19 @@ static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t*
         attr_done = true;
     }
     hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start, pair_len,
-                       blkpre, P, w, tau, cand, cand_cnt, lay);
+                       blkpre, unit_pairs, P, w, tau, cand, cand_cnt, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
-                     const uint32_t* blkpre, int P, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
-                     CandLayout lay, int groups, hipStream_t st) {
+                     const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau, uint2* cand,
+                     uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
     if (P <= 0) return IVFR_OK;
-#define IVFR_SCAN_CASE(MM)                                                                                      \
-    case MM:                                                                                                    \
-        return launch_scan_m<MM>(ix, lut, pair_start, pair_len, blkpre, P, w, tau, cand, cand_cnt, lay, groups, \
-                                 st)
+#define IVFR_SCAN_CASE(MM)                                                                                     \
+    case MM:                                                                                                   \
+        return launch_scan_m<MM>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, P, w, tau, cand, cand_cnt, \
+                                 lay, groups, st)
     switch (ix->p.m) {
         IVFR_SCAN_CASE(4);
         IVFR_SCAN_CASE(8);
@@ -380,4 +382,267 @@ int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pai
             return IVFR_ERR_INVALID_ARG;
     }
 #undef IVFR_SCAN_CASE
+}
+
+// ------------------------------------------------------------------------------------------
+// Shared scan: queries of one batch that visit the same list are scanned together.
+//
+// Four (query, list) pairs with the same list form a unit: the list's codes are loaded once
+// and every code byte indexes a table of float4 whose lanes are the four queries' entries
+// (LDS layout [j][k][4]), so one 16-byte LDS read serves four queries.  On this chip a random
+// 64-lane ds_read_b128 costs ~10 LDS cycles for 256 values against ~7 cycles for the 64
+// values of a random ds_read_b32, and the list is read from HBM once instead of four times.
+// Each query keeps its own bound tau, counter and candidate buffer, and its estimate is the
+// same sum of the same eight fp32 terms in the same order as in the per-pair kernel.
+// Pairs that do not fill a unit of four are left to the per-pair kernel.
+// ------------------------------------------------------------------------------------------
+__global__ void group_count_kernel(const int32_t* __restrict__ probe, int P, uint32_t* __restrict__ list_np) {
+    int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < P) atomicAdd(&list_np[probe[p]], 1u);
+}
+
+// per list: exclusive prefixes of units of four (g4) and of left-over pairs (lo); one workgroup
+__global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, const uint32_t* __restrict__ list_np,
+                                                                uint32_t* __restrict__ g4, uint32_t* __restrict__ lo,
+                                                                uint32_t* __restrict__ cur, uint32_t* __restrict__ counts) {
+    __shared__ uint32_t wtot[2][16];
+    __shared__ uint32_t carry[2];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    if (tid < 2) carry[tid] = 0;
+    __syncthreads();
+    for (int base = 0; base < c; base += 1024) {
+        int l = base + tid;
+        uint32_t n = l < c ? list_np[l] : 0u;
+        uint32_t v[2] = {n / 4, n % 4};
+        uint32_t inc[2] = {v[0], v[1]};
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                uint32_t o = __shfl_up(inc[a], off, 64);
+                if (lane >= off) inc[a] += o;
+            }
+            if (lane == 63) wtot[a][wv] = inc[a];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            uint32_t add = carry[a];
+            for (int x = 0; x < wv; ++x) add += wtot[a][x];
+            inc[a] += add;
+        }
+        if (l < c) { g4[l] = inc[0] - v[0]; lo[l] = inc[1] - v[1]; cur[l] = 0; }
+        __syncthreads();
+        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; }
+        __syncthreads();
+    }
+    if (tid == 0) { counts[0] = carry[0]; counts[1] = carry[1]; }
+}
+
+__global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, const uint32_t* __restrict__ list_np,
+                                  const uint32_t* __restrict__ g4, const uint32_t* __restrict__ lo,
+                                  uint32_t* __restrict__ cur, uint32_t* __restrict__ unit4_pairs,
+                                  uint32_t* __restrict__ lo_pairs) {
+    int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    const int l = probe[p];
+    const uint32_t n = list_np[l], full = (n / 4) * 4;
+    const uint32_t i = atomicAdd(&cur[l], 1u);
+    if (i < full) unit4_pairs[(g4[l] + i / 4) * 4 + (i & 3)] = (uint32_t)p;
+    else lo_pairs[lo[l] + (i - full)] = (uint32_t)p;
+}
+
+// block prefixes over the units of four and over the left-over pairs; work totals; one workgroup
+__global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* __restrict__ counts,
+                                                                const uint32_t* __restrict__ unit4_pairs,
+                                                                const uint32_t* __restrict__ lo_pairs,
+                                                                const uint32_t* __restrict__ pair_len,
+                                                                uint32_t* __restrict__ blk4, uint32_t* __restrict__ blklo,
+                                                                unsigned long long* __restrict__ work) {
+    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t carry;
+    __shared__ unsigned long long s_work;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    for (int which = 0; which < 2; ++which) {
+        const int n = (int)counts[which];
+        const uint32_t* ids = which == 0 ? unit4_pairs : lo_pairs;
+        uint32_t* out = which == 0 ? blk4 : blklo;
+        const int step = which == 0 ? 4 : 1;
+        if (tid == 0) { carry = 0; s_work = 0; }
+        __syncthreads();
+        unsigned long long mywork = 0;
+        for (int base = 0; base < n; base += 1024) {
+            int u = base + tid;
+            uint32_t len = u < n ? pair_len[ids[(int64_t)u * step]] : 0u;
+            mywork += len;
+            uint32_t v = (len + IVFR_BLOCK - 1) / IVFR_BLOCK;
+            uint32_t inc = v;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                uint32_t o = __shfl_up(inc, off, 64);
+                if (lane >= off) inc += o;
+            }
+            if (lane == 63) wtot[wv] = inc;
+            __syncthreads();
+            uint32_t add = carry;
+            for (int x = 0; x < wv; ++x) add += wtot[x];
+            inc += add;
+            if (u < n) out[u] = inc - v;
+            __syncthreads();
+            if (tid == 1023) carry = inc;
+            __syncthreads();
+        }
+        atomicAdd(&s_work, mywork);
+        __syncthreads();
+        if (tid == 0) { out[n] = carry; work[which] = s_work; }
+        __syncthreads();
+    }
+}
+
+int ivfr_launch_group_plan(const int32_t* probe, int P, int c, const uint32_t* pair_len, const GroupBuffers& gb,
+                           hipStream_t st) {
+    IVFR_HIP(hipMemsetAsync(gb.list_np, 0, (size_t)c * sizeof(uint32_t), st));
+    hipLaunchKernelGGL(group_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, gb.list_np);
+    hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, gb.list_np, gb.g4, gb.lo, gb.cur,
+                       gb.counts);
+    hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, gb.list_np, gb.g4, gb.lo,
+                       gb.cur, gb.unit4_pairs, gb.lo_pairs);
+    hipLaunchKernelGGL(group_scan_units_kernel, dim3(1), dim3(1024), 0, st, gb.counts, gb.unit4_pairs, gb.lo_pairs,
+                       pair_len, gb.blk4, gb.blklo, gb.work);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+template <int M>
+__global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __restrict__ codes,
+                                                              const float* __restrict__ lut,
+                                                              const uint32_t* __restrict__ pair_start,
+                                                              const uint32_t* __restrict__ pair_len,
+                                                              const uint32_t* __restrict__ blkpre,
+                                                              const uint32_t* __restrict__ unit_pairs, int nunits,
+                                                              int w, const float* __restrict__ tau,
+                                                              uint2* __restrict__ cand,
+                                                              uint32_t* __restrict__ cand_cnt, CandLayout lay) {
+    extern __shared__ float4 s_lut4[];   // [M * 256] float4: lane x = query x of the unit
+    const uint32_t total = blkpre[nunits];
+    const uint32_t G = gridDim.x, g = blockIdx.x;
+    uint32_t b = (uint32_t)(((uint64_t)total * g) / G);
+    const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / G);
+    if (b >= b_end) return;
+    int lo = 0, hi = nunits;   // last unit u with blkpre[u] <= b
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (blkpre[mid] <= b) lo = mid; else hi = mid;
+    }
+    int u = lo;
+    const int tid = threadIdx.x;
+    while (b < b_end) {
+        while (blkpre[u + 1] <= b) ++u;
+        const uint32_t pb0 = blkpre[u], pb1 = blkpre[u + 1];
+        const uint32_t stop = pb1 < b_end ? pb1 : b_end;
+        int64_t pid[4];
+        float t[4];
+        uint2* qc[4];
+        uint32_t* cnt[4];
+        uint32_t cap[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            pid[x] = (int64_t)unit_pairs[(int64_t)u * 4 + x];
+            const int q = (int)(pid[x] / w);
+            t[x] = tau[q];
+            qc[x] = cand + lay.base(q);
+            cap[x] = lay.cap(q);
+            cnt[x] = cand_cnt + q;
+        }
+        const uint32_t start = pair_start[pid[0]], len = pair_len[pid[0]];   // the four pairs share the list
+        __syncthreads();   // previous unit's tables no longer in use
+        for (int e = tid; e < M * IVFR_KS; e += 256)
+            s_lut4[e] = make_float4(lut[pid[0] * M * IVFR_KS + e], lut[pid[1] * M * IVFR_KS + e],
+                                    lut[pid[2] * M * IVFR_KS + e], lut[pid[3] * M * IVFR_KS + e]);
+        __syncthreads();
+        for (uint32_t bb = b; bb < stop; bb += 2) {
+            uint32_t wds[2][2][M / 4];
+            uint32_t e0[2];
+            bool in0[2], in1[2];
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                e0[v] = (bb + v - pb0) * IVFR_BLOCK + 2u * tid;
+                in0[v] = bb + v < stop && e0[v] < len;
+                in1[v] = bb + v < stop && e0[v] + 1 < len;
+                if (in0[v]) {
+                    const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e0[v]) * M);
+                    if (M == 8) {
+                        uint4 c4 = *reinterpret_cast<const uint4*>(src);
+                        wds[v][0][0] = c4.x; wds[v][0][1] = c4.y; wds[v][1][0] = c4.z; wds[v][1][1] = c4.w;
+                    } else {
+#pragma unroll
+                        for (int t2 = 0; t2 < M / 4; ++t2) { wds[v][0][t2] = src[t2]; wds[v][1][t2] = src[M / 4 + t2]; }
+                    }
+                } else {
+#pragma unroll
+                    for (int t2 = 0; t2 < M / 4; ++t2) { wds[v][0][t2] = 0; wds[v][1][t2] = 0; }
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                // per query the same two partial sums as adc_sum<M>: even and odd sub-quantizers
+                float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0, b0 = a0, b1 = a0;
+#pragma unroll
+                for (int t2 = 0; t2 < M / 4; ++t2) {
+                    const uint32_t wa = wds[v][0][t2], wb = wds[v][1][t2];
+                    const float4* L = s_lut4 + t2 * 4 * IVFR_KS;
+                    float4 x;
+                    x = L[wa & 0xff];                          a0.x += x.x; a0.y += x.y; a0.z += x.z; a0.w += x.w;
+                    x = L[IVFR_KS + ((wa >> 8) & 0xff)];        a1.x += x.x; a1.y += x.y; a1.z += x.z; a1.w += x.w;
+                    x = L[2 * IVFR_KS + ((wa >> 16) & 0xff)];   a0.x += x.x; a0.y += x.y; a0.z += x.z; a0.w += x.w;
+                    x = L[3 * IVFR_KS + (wa >> 24)];            a1.x += x.x; a1.y += x.y; a1.z += x.z; a1.w += x.w;
+                    x = L[wb & 0xff];                          b0.x += x.x; b0.y += x.y; b0.z += x.z; b0.w += x.w;
+                    x = L[IVFR_KS + ((wb >> 8) & 0xff)];        b1.x += x.x; b1.y += x.y; b1.z += x.z; b1.w += x.w;
+                    x = L[2 * IVFR_KS + ((wb >> 16) & 0xff)];   b0.x += x.x; b0.y += x.y; b0.z += x.z; b0.w += x.w;
+                    x = L[3 * IVFR_KS + (wb >> 24)];            b1.x += x.x; b1.y += x.y; b1.z += x.z; b1.w += x.w;
+                }
+                const float ea[4] = {a0.x + a1.x, a0.y + a1.y, a0.z + a1.z, a0.w + a1.w};
+                const float eb[4] = {b0.x + b1.x, b0.y + b1.y, b0.z + b1.z, b0.w + b1.w};
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    append_records(in0[v] && ea[x] <= t[x], ea[x], start + e0[v], in1[v] && eb[x] <= t[x], eb[x],
+                                   start + e0[v] + 1, qc[x], cnt[x], cap[x]);
+            }
+        }
+        b = stop;
+    }
+}
+
+template <int M>
+static int launch_shared_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
+                           const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits, int w, const float* tau,
+                           uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
+    size_t lds = (size_t)M * IVFR_KS * sizeof(float4);
+    static bool attr_done = false;
+    if (!attr_done && lds > 48 * 1024) {
+        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared_kernel<M>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(adc_scan_shared_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start, pair_len,
+                       blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+bool ivfr_shared_scan_supported(const ivfr_index* ix) { return ix->p.m <= 16; }
+
+int ivfr_launch_scan_shared(const ivfr_index* ix, const float* lut, const uint32_t* pair_start,
+                            const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
+                            int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
+                            hipStream_t st) {
+    if (nunits <= 0) return IVFR_OK;
+    switch (ix->p.m) {
+        case 4: return launch_shared_m<4>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
+        case 8: return launch_shared_m<8>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
+        case 16: return launch_shared_m<16>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
+        default:
+            ivfr_set_error("shared scan supports m <= 16; got %d", ix->p.m);
+            return IVFR_ERR_INVALID_ARG;
+    }
 }

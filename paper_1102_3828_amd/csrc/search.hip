@@ -64,7 +64,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     IVFR_REQUIRE((int64_t)kprime * ix->cap_mult < (1ll << 31), "kprime * cap_mult too large");
     IVFR_HIP(hipSetDevice(p.device));
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    ix->st_codes = ix->st_pairs = ix->st_dense = 0;
+    ix->st_codes = ix->st_pairs = ix->st_dense = ix->st_streamed = ix->st_shared_codes = 0;
     for (int i = 0; i < IVFR_N_STAGES; ++i) ix->prof_ms[i] = 0;
     ix->prof_scan_launches = 0;
     if (nq == 0) return IVFR_OK;
@@ -108,6 +108,16 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_sref = cv.take<float>((size_t)B * kprime);
     const size_t o_sids = cv.take<int32_t>((size_t)B * kprime);
     const size_t o_dpre = cv.take<uint32_t>((size_t)w + 1);
+    const size_t o_gnp = cv.take<uint32_t>(c);
+    const size_t o_gg4 = cv.take<uint32_t>(c);
+    const size_t o_glo = cv.take<uint32_t>(c);
+    const size_t o_gcur = cv.take<uint32_t>(c);
+    const size_t o_gcounts = cv.take<uint32_t>(4);
+    const size_t o_gu4 = cv.take<uint32_t>((size_t)P + 4);
+    const size_t o_glop = cv.take<uint32_t>((size_t)P + 4);
+    const size_t o_gblk4 = cv.take<uint32_t>((size_t)P / 4 + 2);
+    const size_t o_gblklo = cv.take<uint32_t>((size_t)P + 2);
+    const size_t o_gwork = cv.take<unsigned long long>(2);
     IVFR_TRY(ix->search_ws.reserve(cv.off + 256));
     char* ws = ix->search_ws.as<char>();
     float* xnorm = reinterpret_cast<float*>(ws + o_xnorm);
@@ -141,6 +151,18 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     float* sref = reinterpret_cast<float*>(ws + o_sref);
     int32_t* sids = reinterpret_cast<int32_t*>(ws + o_sids);
     uint32_t* dpre = reinterpret_cast<uint32_t*>(ws + o_dpre);
+    GroupBuffers gb;
+    gb.list_np = reinterpret_cast<uint32_t*>(ws + o_gnp);
+    gb.g4 = reinterpret_cast<uint32_t*>(ws + o_gg4);
+    gb.lo = reinterpret_cast<uint32_t*>(ws + o_glo);
+    gb.cur = reinterpret_cast<uint32_t*>(ws + o_gcur);
+    gb.counts = reinterpret_cast<uint32_t*>(ws + o_gcounts);
+    gb.unit4_pairs = reinterpret_cast<uint32_t*>(ws + o_gu4);
+    gb.lo_pairs = reinterpret_cast<uint32_t*>(ws + o_glop);
+    gb.blk4 = reinterpret_cast<uint32_t*>(ws + o_gblk4);
+    gb.blklo = reinterpret_cast<uint32_t*>(ws + o_gblklo);
+    gb.work = reinterpret_cast<unsigned long long*>(ws + o_gwork);
+    const bool share = ix->share_lists && ivfr_shared_scan_supported(ix);
 
     std::vector<EventPair> events;
     auto mark = [&](int kind, bool begin) -> int {
@@ -174,6 +196,11 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
             IVFR_TRY(ivfr_launch_select_sorted(a, nullptr, 0, probe, probed, st));
         }
         IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, min_cap, pb, st));
+        if (share) {
+            IVFR_TRY(ivfr_launch_group_plan(probe, Pb, c, pb.len, gb, st));
+            IVFR_HIP(hipMemcpyAsync(ix->h_status + 8, gb.counts, 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+            IVFR_HIP(hipMemcpyAsync(ix->h_status + 10, gb.work, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+        }
         // the candidate pool is sized by the plan: one small read-back
         IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         IVFR_TRY(mark(IVFR_STAGE_PROBE, false));
@@ -185,6 +212,17 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         memcpy(tot2, ix->h_status + 2, sizeof(tot2));
         ix->st_codes += (int64_t)tot2[0];
         ix->st_pairs += Pb;
+        int n_unit4 = 0, n_lo = 0;
+        if (share) {
+            unsigned long long gw[2];
+            memcpy(gw, ix->h_status + 10, sizeof(gw));
+            n_unit4 = ix->h_status[8];
+            n_lo = ix->h_status[9];
+            ix->st_streamed += (int64_t)(gw[0] + gw[1]);
+            ix->st_shared_codes += (int64_t)(4 * gw[0]);
+        } else {
+            ix->st_streamed += (int64_t)tot2[0];
+        }
         IVFR_TRY(ix->cand_ws.reserve((size_t)(tot2[1] + 64) * sizeof(uint2)));
         uint2* cand = ix->cand_ws.as<uint2>();
         // uniform sample of the visited entries -> bound tau on the k'-th smallest estimate
@@ -192,7 +230,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_HIP(hipMemsetAsync(overtot, 0, 4 * sizeof(int32_t), st));
         hipLaunchKernelGGL(fill_f32_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, tau, (int64_t)nb, INFINITY);
-        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len_s, pb.blkpre_s, Pb, w, tau, cand, cnt, lay, groups, st));
+        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len_s, pb.blkpre_s, nullptr, Pb, w, tau, cand, cnt, lay, groups, st));
         {
             SelectArgs a;
             a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = cnt; a.lay = lay;
@@ -201,9 +239,22 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
         // scan of every visited entry, keeping estimates <= tau
-        IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
-        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, pb.blkpre, Pb, w, tau, cand, cnt, lay, groups, st));
-        IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
+        if (share) {
+            // lists visited by several queries: four queries per pass over the list; the rest pair by pair
+            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED, true));
+            IVFR_TRY(ivfr_launch_scan_shared(ix, lut, pb.pair_start, pb.len, gb.blk4, gb.unit4_pairs, n_unit4, w, tau,
+                                             cand, cnt, lay, groups, st));
+            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED, false));
+            IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
+            IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, gb.blklo, gb.lo_pairs, n_lo, w, tau, cand, cnt,
+                                      lay, groups, st));
+            IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
+        } else {
+            IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
+            IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, pb.blkpre, nullptr, Pb, w, tau, cand, cnt, lay,
+                                      groups, st));
+            IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
+        }
         IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, true));
         {
             SelectArgs a;
@@ -245,7 +296,8 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
                 dlay.stride = 0;
                 dlay.ucap = (uint32_t)(sqv + 1);
                 IVFR_TRY(ivfr_launch_scan(ix, lut + (size_t)q * w * m * IVFR_KS, pb.pair_start + (size_t)q * w,
-                                          pb.len + (size_t)q * w, dpre, w, w, dtau, dcand, dcnt, dlay, groups, st));
+                                          pb.len + (size_t)q * w, dpre, nullptr, w, w, dtau, dcand, dcnt, dlay, groups,
+                                          st));
                 SelectArgs a;
                 a.nseg = 1; a.K = kprime; a.recs = dcand; a.ids = ix->ids; a.counts = dcnt; a.lay = dlay;
                 IVFR_TRY(ivfr_launch_select_records(a, q, nullptr, spos, sest, sn, nullptr, nullptr, st));
@@ -276,7 +328,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, ep.a, ep.b) == hipSuccess) {
             ix->prof_ms[ep.kind] += ms;
-            if (ep.kind == IVFR_STAGE_SCAN) ix->prof_scan_launches += 1;
+            if (ep.kind == IVFR_STAGE_SCAN || ep.kind == IVFR_STAGE_SCAN_SHARED) ix->prof_scan_launches += 1;
         }
         (void)hipEventDestroy(ep.a);
         (void)hipEventDestroy(ep.b);

@@ -350,6 +350,19 @@ def test_edge_cases_and_internal_paths():
     # run twice: identical bits
     again = ix.search(xq, 6, 300, 20)
     assert np.array_equal(base_ids, again[0].cpu().numpy()) and np.array_equal(base_dist, again[1].cpu().numpy())
+    # lists shared between queries are scanned four queries at a time by default; pair by pair gives the same bits
+    st = ix.search_stats()
+    assert st["codes_scanned_shared"] > 0 and st["codes_streamed"] < st["codes_scanned"]
+    ix.set_list_sharing(False)
+    pp = ix.search(xq, 6, 300, 20)
+    st = ix.search_stats()
+    assert st["codes_scanned_shared"] == 0 and st["codes_streamed"] == st["codes_scanned"]
+    assert np.array_equal(base_ids, pp[0].cpu().numpy()) and np.array_equal(base_dist, pp[1].cpu().numpy())
+    ix.set_tuning(full_mult=1)
+    pp = ix.search(xq, 6, 300, 20)
+    assert np.array_equal(base_ids, pp[0].cpu().numpy()) and np.array_equal(base_dist, pp[1].cpu().numpy())
+    ix.set_tuning(full_mult=8)
+    ix.set_list_sharing(True)
     # batches of 5 queries give the same answer
     ix.set_tuning(batch=5)
     b_ids, b_dist = ix.search(xq, 6, 300, 20)
