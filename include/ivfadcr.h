@@ -109,13 +109,14 @@ int ivfr_search_trace(ivfr_index* index, const float* queries, int64_t nq, int32
  *   dense_fallbacks      queries redone exactly because the sampled bound failed its check
  *   codes_streamed       list entries read from memory by the scan (< codes_scanned when lists are
  *                        shared between queries)
- *   codes_scanned_shared part of codes_scanned computed by the shared-list scan                   */
+ *   codes_scanned_shared / _shared2  parts of codes_scanned computed by the shared-list scans of
+ *                        four and of two queries per pass                                           */
 int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
-                      int64_t* codes_streamed, int64_t* codes_scanned_shared);
+                      int64_t* codes_streamed, int64_t* codes_scanned_shared, int64_t* codes_scanned_shared2);
 
 /* List sharing (default on; needs m <= 16).  Queries of one internal batch that visit the same
- * list are scanned four at a time: the list's codes are read once and each code byte fetches the
- * four queries' table entries with one 16-byte LDS read.  Estimates, and therefore results, are
+ * list are scanned four (or two) at a time: the list's codes are read once and each code byte
+ * fetches the queries' table entries with one 16-byte (8-byte) LDS read.  Estimates, and therefore results, are
  * bit-identical with sharing on or off; 0 scans every (query, list) pair on its own. */
 int ivfr_set_list_sharing(ivfr_index* index, int32_t enable);
 
@@ -134,7 +135,7 @@ int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int3
 /* Per-stage GPU time of the most recent search call, in milliseconds, measured with HIP events
  * on the search stream (recorded only after ivfr_set_profiling(index, 1)).  ms: host double
  * [IVFR_N_STAGES], indexed by IVFR_STAGE_*; scan_launches: launches of the list-scan kernels
- * (stages IVFR_STAGE_SCAN and IVFR_STAGE_SCAN_SHARED are exactly those launches), may be NULL. */
+ * (stages IVFR_STAGE_SCAN, _SCAN_SHARED and _SCAN_SHARED2 are exactly those launches), may be NULL. */
 #define IVFR_STAGE_COARSE    0   /* query norms + coarse distance GEMM                        */
 #define IVFR_STAGE_PROBE     1   /* w nearest lists + plan of (query, list) pairs             */
 #define IVFR_STAGE_LUT       2   /* look-up tables of Eq. (5)                                 */
@@ -144,7 +145,8 @@ int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int3
 #define IVFR_STAGE_RERANK    6   /* Eq. (9)-(10) over the short-list                          */
 #define IVFR_STAGE_FINAL     7   /* k smallest refined distances, sorted                      */
 #define IVFR_STAGE_SCAN_SHARED 8 /* ADC list scan, four queries per pass over a shared list   */
-#define IVFR_N_STAGES        9
+#define IVFR_STAGE_SCAN_SHARED2 9 /* ADC list scan, two queries per pass over a shared list   */
+#define IVFR_N_STAGES        10
 int ivfr_set_profiling(ivfr_index* index, int32_t enable);
 int ivfr_stage_times(const ivfr_index* index, double* ms, int32_t* scan_launches);
 

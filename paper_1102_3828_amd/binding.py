@@ -49,7 +49,7 @@ def _load():
         "ivfr_import": (ctypes.c_int, [vp, i64, vp, vp, vp, vp]),
         "ivfr_search": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp]),
         "ivfr_search_trace": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
-        "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 5),
+        "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 6),
         "ivfr_set_list_sharing": (ctypes.c_int, [vp, i32]),
         "ivfr_set_tuning": (ctypes.c_int, [vp, i32, i32, i32, i32, i32]),
         "ivfr_set_profiling": (ctypes.c_int, [vp, i32]),
@@ -194,9 +194,10 @@ class Index:
         return ids, dist, t
 
     def search_stats(self):
-        v = [ctypes.c_int64() for _ in range(5)]
+        v = [ctypes.c_int64() for _ in range(6)]
         _check(lib.ivfr_search_stats(self._h, *[ctypes.byref(x) for x in v]))
-        names = ("codes_scanned", "pairs", "dense_fallbacks", "codes_streamed", "codes_scanned_shared")
+        names = ("codes_scanned", "pairs", "dense_fallbacks", "codes_streamed", "codes_scanned_shared",
+                 "codes_scanned_shared2")
         return dict(zip(names, [x.value for x in v]))
 
     def set_list_sharing(self, enable=True):
@@ -208,7 +209,7 @@ class Index:
     def set_profiling(self, enable=True):
         _check(lib.ivfr_set_profiling(self._h, 1 if enable else 0))
 
-    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared")
+    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared", "scan_shared2")
 
     def stage_times(self):
         """Per-stage milliseconds of the last search (after set_profiling) and scan launch count."""

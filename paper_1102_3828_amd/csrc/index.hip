@@ -494,13 +494,15 @@ extern "C" int ivfr_stage_times(const ivfr_index* ix, double* ms, int32_t* scan_
 }
 
 extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
-                                 int64_t* codes_streamed, int64_t* codes_scanned_shared) {
+                                 int64_t* codes_streamed, int64_t* codes_scanned_shared,
+                                 int64_t* codes_scanned_shared2) {
     IVFR_REQUIRE(ix, "ivfr_search_stats: null index");
     if (codes_scanned) *codes_scanned = ix->st_codes;
     if (pairs) *pairs = ix->st_pairs;
     if (dense_fallbacks) *dense_fallbacks = ix->st_dense;
     if (codes_streamed) *codes_streamed = ix->st_streamed;
     if (codes_scanned_shared) *codes_scanned_shared = ix->st_shared_codes;
+    if (codes_scanned_shared2) *codes_scanned_shared2 = ix->st_shared2_codes;
     return IVFR_OK;
 }
 

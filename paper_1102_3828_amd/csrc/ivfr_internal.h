@@ -118,7 +118,7 @@ struct ivfr_index {
     int* h_status = nullptr;         // pinned host word(s) for status read-back
 
     // stats of the last search
-    int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0;
+    int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0;
     bool profiling = false;
     double prof_ms[IVFR_N_STAGES] = {0};
     int prof_scan_launches = 0;
@@ -197,23 +197,26 @@ int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pai
                      const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau, uint2* cand,
                      uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st);
 
-// Shared scan: pairs of one batch grouped by list into units of four plus left-over pairs
+// Shared scan: pairs of one batch grouped by list into units of four, units of two and single pairs
 struct GroupBuffers {
     uint32_t* list_np;      // [c] pairs visiting each list
     uint32_t* g4;           // [c] exclusive prefix of units of four
-    uint32_t* lo;           // [c] exclusive prefix of left-over pairs
+    uint32_t* g2;           // [c] exclusive prefix of units of two
+    uint32_t* lo;           // [c] exclusive prefix of single pairs
     uint32_t* cur;          // [c] fill cursors
-    uint32_t* counts;       // [2] number of units of four, number of left-over pairs
-    uint32_t* unit4_pairs;  // [P] pair ids, four per unit
-    uint32_t* lo_pairs;     // [P] left-over pair ids
-    uint32_t* blk4;         // [P/4 + 1] block prefix over units of four
-    uint32_t* blklo;        // [P + 1] block prefix over left-over pairs
-    unsigned long long* work;  // [2] list entries streamed by the shared scan, by the per-pair scan
+    uint32_t* counts;       // [3] units of four, units of two, single pairs
+    uint32_t* unit4_pairs;  // [P + 4c + 4] pair ids, four per unit (0xFFFFFFFF = empty slot)
+    uint32_t* unit2_pairs;  // [2c] pair ids, two per unit
+    uint32_t* lo_pairs;     // [c] single pair ids
+    uint32_t* blk4;         // [P/4 + c + 2] block prefix over units of four
+    uint32_t* blk2;         // [c + 2] block prefix over units of two
+    uint32_t* blklo;        // [c + 2] block prefix over single pairs
+    unsigned long long* work;  // [3] list entries streamed by all scans; estimates computed by the scans of four, of two
 };
 int ivfr_launch_group_plan(const int32_t* probe, int P, int c, const uint32_t* pair_len, const GroupBuffers& gb,
                            hipStream_t st);
 bool ivfr_shared_scan_supported(const ivfr_index* ix);
-int ivfr_launch_scan_shared(const ivfr_index* ix, const float* lut, const uint32_t* pair_start,
+int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
                             int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
                             hipStream_t st);

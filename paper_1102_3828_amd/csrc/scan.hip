@@ -394,29 +394,42 @@ int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pai
 // values of a random ds_read_b32, and the list is read from HBM once instead of four times.
 // Each query keeps its own bound tau, counter and candidate buffer, and its estimate is the
 // same sum of the same eight fp32 terms in the same order as in the per-pair kernel.
-// Pairs that do not fill a unit of four are left to the per-pair kernel.
+// A list visited by 4n+3 queries gets one unit with an empty slot, 4n+2 a unit of two (8-byte
+// LDS reads), 4n+1 leaves a single pair to the per-pair kernel.
 // ------------------------------------------------------------------------------------------
 __global__ void group_count_kernel(const int32_t* __restrict__ probe, int P, uint32_t* __restrict__ list_np) {
     int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p < P) atomicAdd(&list_np[probe[p]], 1u);
 }
 
-// per list: exclusive prefixes of units of four (g4) and of left-over pairs (lo); one workgroup
+#define IVFR_NO_PAIR 0xFFFFFFFFu   // empty slot of a unit of four (a list visited by 4n+3 queries)
+
+// A list visited by n queries yields n/4 units of four; a remainder of 3 becomes one more unit of
+// four with an empty slot, a remainder of 2 a unit of two, a remainder of 1 a single pair.
+__device__ __forceinline__ void split_units(uint32_t n, uint32_t* n4, uint32_t* n2, uint32_t* n1) {
+    const uint32_t r = n & 3u;
+    *n4 = n / 4 + (r == 3 ? 1u : 0u);
+    *n2 = r == 2 ? 1u : 0u;
+    *n1 = r == 1 ? 1u : 0u;
+}
+
+// per list: exclusive prefixes of units of four, units of two and single pairs; one workgroup
 __global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, const uint32_t* __restrict__ list_np,
-                                                                uint32_t* __restrict__ g4, uint32_t* __restrict__ lo,
-                                                                uint32_t* __restrict__ cur, uint32_t* __restrict__ counts) {
-    __shared__ uint32_t wtot[2][16];
-    __shared__ uint32_t carry[2];
+                                                                uint32_t* __restrict__ g4, uint32_t* __restrict__ g2,
+                                                                uint32_t* __restrict__ lo, uint32_t* __restrict__ cur,
+                                                                uint32_t* __restrict__ counts) {
+    __shared__ uint32_t wtot[3][16];
+    __shared__ uint32_t carry[3];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid < 2) carry[tid] = 0;
+    if (tid < 3) carry[tid] = 0;
     __syncthreads();
     for (int base = 0; base < c; base += 1024) {
         int l = base + tid;
-        uint32_t n = l < c ? list_np[l] : 0u;
-        uint32_t v[2] = {n / 4, n % 4};
-        uint32_t inc[2] = {v[0], v[1]};
+        uint32_t v[3] = {0, 0, 0};
+        if (l < c) split_units(list_np[l], &v[0], &v[1], &v[2]);
+        uint32_t inc[3] = {v[0], v[1], v[2]};
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
+        for (int a = 0; a < 3; ++a) {
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 uint32_t o = __shfl_up(inc[a], off, 64);
@@ -426,55 +439,67 @@ __global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, const uin
         }
         __syncthreads();
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
+        for (int a = 0; a < 3; ++a) {
             uint32_t add = carry[a];
             for (int x = 0; x < wv; ++x) add += wtot[a][x];
             inc[a] += add;
         }
-        if (l < c) { g4[l] = inc[0] - v[0]; lo[l] = inc[1] - v[1]; cur[l] = 0; }
+        if (l < c) { g4[l] = inc[0] - v[0]; g2[l] = inc[1] - v[1]; lo[l] = inc[2] - v[2]; cur[l] = 0; }
         __syncthreads();
-        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; }
+        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; carry[2] = inc[2]; }
         __syncthreads();
     }
-    if (tid == 0) { counts[0] = carry[0]; counts[1] = carry[1]; }
+    if (tid < 3) counts[tid] = carry[tid];
 }
 
 __global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, const uint32_t* __restrict__ list_np,
-                                  const uint32_t* __restrict__ g4, const uint32_t* __restrict__ lo,
-                                  uint32_t* __restrict__ cur, uint32_t* __restrict__ unit4_pairs,
+                                  const uint32_t* __restrict__ g4, const uint32_t* __restrict__ g2,
+                                  const uint32_t* __restrict__ lo, uint32_t* __restrict__ cur,
+                                  uint32_t* __restrict__ unit4_pairs, uint32_t* __restrict__ unit2_pairs,
                                   uint32_t* __restrict__ lo_pairs) {
     int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= P) return;
     const int l = probe[p];
-    const uint32_t n = list_np[l], full = (n / 4) * 4;
+    const uint32_t n = list_np[l], r = n & 3u;
+    const uint32_t in4 = (r == 3) ? n : n - r;   // pairs of this list that go into units of four
     const uint32_t i = atomicAdd(&cur[l], 1u);
-    if (i < full) unit4_pairs[(g4[l] + i / 4) * 4 + (i & 3)] = (uint32_t)p;
-    else lo_pairs[lo[l] + (i - full)] = (uint32_t)p;
+    if (i < in4) unit4_pairs[(g4[l] + i / 4) * 4 + (i & 3)] = (uint32_t)p;
+    else if (r == 2) unit2_pairs[g2[l] * 2 + (i - in4)] = (uint32_t)p;
+    else lo_pairs[lo[l]] = (uint32_t)p;
 }
 
-// block prefixes over the units of four and over the left-over pairs; work totals; one workgroup
+// block prefixes over the units of four, the units of two and the single pairs; work totals; one workgroup
 __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* __restrict__ counts,
                                                                 const uint32_t* __restrict__ unit4_pairs,
+                                                                const uint32_t* __restrict__ unit2_pairs,
                                                                 const uint32_t* __restrict__ lo_pairs,
                                                                 const uint32_t* __restrict__ pair_len,
-                                                                uint32_t* __restrict__ blk4, uint32_t* __restrict__ blklo,
+                                                                uint32_t* __restrict__ blk4, uint32_t* __restrict__ blk2,
+                                                                uint32_t* __restrict__ blklo,
                                                                 unsigned long long* __restrict__ work) {
     __shared__ uint32_t wtot[16];
     __shared__ uint32_t carry;
-    __shared__ unsigned long long s_work;
+    __shared__ unsigned long long s_read, s_est[2];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    for (int which = 0; which < 2; ++which) {
+    if (tid == 0) { s_read = 0; s_est[0] = 0; s_est[1] = 0; }
+    for (int which = 0; which < 3; ++which) {
         const int n = (int)counts[which];
-        const uint32_t* ids = which == 0 ? unit4_pairs : lo_pairs;
-        uint32_t* out = which == 0 ? blk4 : blklo;
-        const int step = which == 0 ? 4 : 1;
-        if (tid == 0) { carry = 0; s_work = 0; }
+        const uint32_t* ids = which == 0 ? unit4_pairs : (which == 1 ? unit2_pairs : lo_pairs);
+        uint32_t* out = which == 0 ? blk4 : (which == 1 ? blk2 : blklo);
+        const int step = which == 0 ? 4 : (which == 1 ? 2 : 1);
+        if (tid == 0) carry = 0;
         __syncthreads();
-        unsigned long long mywork = 0;
+        unsigned long long my_read = 0, my_est = 0;
         for (int base = 0; base < n; base += 1024) {
             int u = base + tid;
-            uint32_t len = u < n ? pair_len[ids[(int64_t)u * step]] : 0u;
-            mywork += len;
+            uint32_t len = 0;
+            if (u < n) {
+                len = pair_len[ids[(int64_t)u * step]];
+                uint32_t members = step;
+                if (which == 0 && ids[(int64_t)u * 4 + 3] == IVFR_NO_PAIR) members = 3;
+                my_read += len;
+                if (which < 2) my_est += (unsigned long long)len * members;
+            }
             uint32_t v = (len + IVFR_BLOCK - 1) / IVFR_BLOCK;
             uint32_t inc = v;
 #pragma unroll
@@ -492,28 +517,44 @@ __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* 
             if (tid == 1023) carry = inc;
             __syncthreads();
         }
-        atomicAdd(&s_work, mywork);
+        atomicAdd(&s_read, my_read);
+        if (which < 2) atomicAdd(&s_est[which], my_est);
         __syncthreads();
-        if (tid == 0) { out[n] = carry; work[which] = s_work; }
+        if (tid == 0) out[n] = carry;
         __syncthreads();
     }
+    if (tid == 0) { work[0] = s_read; work[1] = s_est[0]; work[2] = s_est[1]; }
 }
 
 int ivfr_launch_group_plan(const int32_t* probe, int P, int c, const uint32_t* pair_len, const GroupBuffers& gb,
                            hipStream_t st) {
     IVFR_HIP(hipMemsetAsync(gb.list_np, 0, (size_t)c * sizeof(uint32_t), st));
+    IVFR_HIP(hipMemsetAsync(gb.unit4_pairs, 0xff, ((size_t)P + 4 * (size_t)c + 4) * sizeof(uint32_t), st));
     hipLaunchKernelGGL(group_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, gb.list_np);
-    hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, gb.list_np, gb.g4, gb.lo, gb.cur,
+    hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, gb.list_np, gb.g4, gb.g2, gb.lo, gb.cur,
                        gb.counts);
-    hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, gb.list_np, gb.g4, gb.lo,
-                       gb.cur, gb.unit4_pairs, gb.lo_pairs);
-    hipLaunchKernelGGL(group_scan_units_kernel, dim3(1), dim3(1024), 0, st, gb.counts, gb.unit4_pairs, gb.lo_pairs,
-                       pair_len, gb.blk4, gb.blklo, gb.work);
+    hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, gb.list_np, gb.g4, gb.g2,
+                       gb.lo, gb.cur, gb.unit4_pairs, gb.unit2_pairs, gb.lo_pairs);
+    hipLaunchKernelGGL(group_scan_units_kernel, dim3(1), dim3(1024), 0, st, gb.counts, gb.unit4_pairs, gb.unit2_pairs,
+                       gb.lo_pairs, pair_len, gb.blk4, gb.blk2, gb.blklo, gb.work);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
-template <int M>
+template <int G> struct LutVec;
+template <> struct LutVec<4> { typedef float4 type; };
+template <> struct LutVec<2> { typedef float2 type; };
+
+__device__ __forceinline__ void vadd(float4& a, const float4& x) { a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w; }
+__device__ __forceinline__ void vadd(float2& a, const float2& x) { a.x += x.x; a.y += x.y; }
+__device__ __forceinline__ float vget(const float4& a, int i) { return i == 0 ? a.x : (i == 1 ? a.y : (i == 2 ? a.z : a.w)); }
+__device__ __forceinline__ float vget(const float2& a, int i) { return i == 0 ? a.x : a.y; }
+__device__ __forceinline__ void vzero(float4& a) { a = make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ void vzero(float2& a) { a = make_float2(0.f, 0.f); }
+__device__ __forceinline__ void vload(float4& a, const float* v) { a = make_float4(v[0], v[1], v[2], v[3]); }
+__device__ __forceinline__ void vload(float2& a, const float* v) { a = make_float2(v[0], v[1]); }
+
+template <int M, int G>
 __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __restrict__ codes,
                                                               const float* __restrict__ lut,
                                                               const uint32_t* __restrict__ pair_start,
@@ -523,11 +564,13 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
                                                               int w, const float* __restrict__ tau,
                                                               uint2* __restrict__ cand,
                                                               uint32_t* __restrict__ cand_cnt, CandLayout lay) {
-    extern __shared__ float4 s_lut4[];   // [M * 256] float4: lane x = query x of the unit
+    typedef typename LutVec<G>::type vec_t;
+    extern __shared__ float s_raw[];
+    vec_t* s_lutv = reinterpret_cast<vec_t*>(s_raw);   // [M * 256] vectors: component x = query x of the unit
     const uint32_t total = blkpre[nunits];
-    const uint32_t G = gridDim.x, g = blockIdx.x;
-    uint32_t b = (uint32_t)(((uint64_t)total * g) / G);
-    const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / G);
+    const uint32_t NG = gridDim.x, g = blockIdx.x;
+    uint32_t b = (uint32_t)(((uint64_t)total * g) / NG);
+    const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / NG);
     if (b >= b_end) return;
     int lo = 0, hi = nunits;   // last unit u with blkpre[u] <= b
     while (hi - lo > 1) {
@@ -540,25 +583,32 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
         while (blkpre[u + 1] <= b) ++u;
         const uint32_t pb0 = blkpre[u], pb1 = blkpre[u + 1];
         const uint32_t stop = pb1 < b_end ? pb1 : b_end;
-        int64_t pid[4];
-        float t[4];
-        uint2* qc[4];
-        uint32_t* cnt[4];
-        uint32_t cap[4];
+        int64_t pid[G];
+        float t[G];
+        uint2* qc[G];
+        uint32_t* cnt[G];
+        uint32_t cap[G];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            pid[x] = (int64_t)unit_pairs[(int64_t)u * 4 + x];
+        for (int x = 0; x < G; ++x) {
+            const uint32_t raw = unit_pairs[(int64_t)u * G + x];
+            const bool real = raw != IVFR_NO_PAIR;
+            pid[x] = real ? (int64_t)raw : (int64_t)unit_pairs[(int64_t)u * G];   // an empty slot reads slot 0's table
             const int q = (int)(pid[x] / w);
-            t[x] = tau[q];
+            t[x] = real ? tau[q] : -1.f;                                         // ... and never keeps anything
             qc[x] = cand + lay.base(q);
             cap[x] = lay.cap(q);
             cnt[x] = cand_cnt + q;
         }
-        const uint32_t start = pair_start[pid[0]], len = pair_len[pid[0]];   // the four pairs share the list
+        const uint32_t start = pair_start[pid[0]], len = pair_len[pid[0]];   // the unit's pairs share the list
         __syncthreads();   // previous unit's tables no longer in use
-        for (int e = tid; e < M * IVFR_KS; e += 256)
-            s_lut4[e] = make_float4(lut[pid[0] * M * IVFR_KS + e], lut[pid[1] * M * IVFR_KS + e],
-                                    lut[pid[2] * M * IVFR_KS + e], lut[pid[3] * M * IVFR_KS + e]);
+        for (int e = tid; e < M * IVFR_KS; e += 256) {
+            float v[G];
+#pragma unroll
+            for (int x = 0; x < G; ++x) v[x] = lut[pid[x] * M * IVFR_KS + e];
+            vec_t packed;
+            vload(packed, v);
+            s_lutv[e] = packed;
+        }
         __syncthreads();
         for (uint32_t bb = b; bb < stop; bb += 2) {
             uint32_t wds[2][2][M / 4];
@@ -586,63 +636,73 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
 #pragma unroll
             for (int v = 0; v < 2; ++v) {
                 // per query the same two partial sums as adc_sum<M>: even and odd sub-quantizers
-                float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0, b0 = a0, b1 = a0;
+                vec_t a0, a1, b0, b1;
+                vzero(a0); vzero(a1); vzero(b0); vzero(b1);
 #pragma unroll
                 for (int t2 = 0; t2 < M / 4; ++t2) {
                     const uint32_t wa = wds[v][0][t2], wb = wds[v][1][t2];
-                    const float4* L = s_lut4 + t2 * 4 * IVFR_KS;
-                    float4 x;
-                    x = L[wa & 0xff];                          a0.x += x.x; a0.y += x.y; a0.z += x.z; a0.w += x.w;
-                    x = L[IVFR_KS + ((wa >> 8) & 0xff)];        a1.x += x.x; a1.y += x.y; a1.z += x.z; a1.w += x.w;
-                    x = L[2 * IVFR_KS + ((wa >> 16) & 0xff)];   a0.x += x.x; a0.y += x.y; a0.z += x.z; a0.w += x.w;
-                    x = L[3 * IVFR_KS + (wa >> 24)];            a1.x += x.x; a1.y += x.y; a1.z += x.z; a1.w += x.w;
-                    x = L[wb & 0xff];                          b0.x += x.x; b0.y += x.y; b0.z += x.z; b0.w += x.w;
-                    x = L[IVFR_KS + ((wb >> 8) & 0xff)];        b1.x += x.x; b1.y += x.y; b1.z += x.z; b1.w += x.w;
-                    x = L[2 * IVFR_KS + ((wb >> 16) & 0xff)];   b0.x += x.x; b0.y += x.y; b0.z += x.z; b0.w += x.w;
-                    x = L[3 * IVFR_KS + (wb >> 24)];            b1.x += x.x; b1.y += x.y; b1.z += x.z; b1.w += x.w;
+                    const vec_t* L = s_lutv + t2 * 4 * IVFR_KS;
+                    vadd(a0, L[wa & 0xff]);
+                    vadd(a1, L[IVFR_KS + ((wa >> 8) & 0xff)]);
+                    vadd(a0, L[2 * IVFR_KS + ((wa >> 16) & 0xff)]);
+                    vadd(a1, L[3 * IVFR_KS + (wa >> 24)]);
+                    vadd(b0, L[wb & 0xff]);
+                    vadd(b1, L[IVFR_KS + ((wb >> 8) & 0xff)]);
+                    vadd(b0, L[2 * IVFR_KS + ((wb >> 16) & 0xff)]);
+                    vadd(b1, L[3 * IVFR_KS + (wb >> 24)]);
                 }
-                const float ea[4] = {a0.x + a1.x, a0.y + a1.y, a0.z + a1.z, a0.w + a1.w};
-                const float eb[4] = {b0.x + b1.x, b0.y + b1.y, b0.z + b1.z, b0.w + b1.w};
 #pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    append_records(in0[v] && ea[x] <= t[x], ea[x], start + e0[v], in1[v] && eb[x] <= t[x], eb[x],
-                                   start + e0[v] + 1, qc[x], cnt[x], cap[x]);
+                for (int x = 0; x < G; ++x) {
+                    const float ea = vget(a0, x) + vget(a1, x), eb = vget(b0, x) + vget(b1, x);
+                    append_records(in0[v] && ea <= t[x], ea, start + e0[v], in1[v] && eb <= t[x], eb, start + e0[v] + 1,
+                                   qc[x], cnt[x], cap[x]);
+                }
             }
         }
         b = stop;
     }
 }
 
-template <int M>
-static int launch_shared_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
-                           const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits, int w, const float* tau,
-                           uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
-    size_t lds = (size_t)M * IVFR_KS * sizeof(float4);
+template <int M, int G>
+static int launch_shared_mg(const ivfr_index* ix, const float* lut, const uint32_t* pair_start,
+                            const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
+                            int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
+                            hipStream_t st) {
+    size_t lds = (size_t)M * IVFR_KS * sizeof(float) * G;
     static bool attr_done = false;
     if (!attr_done && lds > 48 * 1024) {
-        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared_kernel<M>),
+        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared_kernel<M, G>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_done = true;
     }
-    hipLaunchKernelGGL(adc_scan_shared_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start, pair_len,
-                       blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay);
+    hipLaunchKernelGGL((adc_scan_shared_kernel<M, G>), dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start,
+                       pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
 bool ivfr_shared_scan_supported(const ivfr_index* ix) { return ix->p.m <= 16; }
 
-int ivfr_launch_scan_shared(const ivfr_index* ix, const float* lut, const uint32_t* pair_start,
+int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
                             int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
                             hipStream_t st) {
     if (nunits <= 0) return IVFR_OK;
-    switch (ix->p.m) {
-        case 4: return launch_shared_m<4>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
-        case 8: return launch_shared_m<8>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
-        case 16: return launch_shared_m<16>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
-        default:
-            ivfr_set_error("shared scan supports m <= 16; got %d", ix->p.m);
-            return IVFR_ERR_INVALID_ARG;
+#define IVFR_SH_ARGS ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st
+    if (G == 4) {
+        switch (ix->p.m) {
+            case 4: return launch_shared_mg<4, 4>(IVFR_SH_ARGS);
+            case 8: return launch_shared_mg<8, 4>(IVFR_SH_ARGS);
+            case 16: return launch_shared_mg<16, 4>(IVFR_SH_ARGS);
+        }
+    } else if (G == 2) {
+        switch (ix->p.m) {
+            case 4: return launch_shared_mg<4, 2>(IVFR_SH_ARGS);
+            case 8: return launch_shared_mg<8, 2>(IVFR_SH_ARGS);
+            case 16: return launch_shared_mg<16, 2>(IVFR_SH_ARGS);
+        }
     }
+#undef IVFR_SH_ARGS
+    ivfr_set_error("shared scan supports m <= 16 and units of 2 or 4; got m = %d, unit %d", ix->p.m, G);
+    return IVFR_ERR_INVALID_ARG;
 }

@@ -64,7 +64,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     IVFR_REQUIRE((int64_t)kprime * ix->cap_mult < (1ll << 31), "kprime * cap_mult too large");
     IVFR_HIP(hipSetDevice(p.device));
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    ix->st_codes = ix->st_pairs = ix->st_dense = ix->st_streamed = ix->st_shared_codes = 0;
+    ix->st_codes = ix->st_pairs = ix->st_dense = ix->st_streamed = ix->st_shared_codes = ix->st_shared2_codes = 0;
     for (int i = 0; i < IVFR_N_STAGES; ++i) ix->prof_ms[i] = 0;
     ix->prof_scan_launches = 0;
     if (nq == 0) return IVFR_OK;
@@ -110,14 +110,17 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_dpre = cv.take<uint32_t>((size_t)w + 1);
     const size_t o_gnp = cv.take<uint32_t>(c);
     const size_t o_gg4 = cv.take<uint32_t>(c);
+    const size_t o_gg2 = cv.take<uint32_t>(c);
     const size_t o_glo = cv.take<uint32_t>(c);
     const size_t o_gcur = cv.take<uint32_t>(c);
     const size_t o_gcounts = cv.take<uint32_t>(4);
-    const size_t o_gu4 = cv.take<uint32_t>((size_t)P + 4);
-    const size_t o_glop = cv.take<uint32_t>((size_t)P + 4);
-    const size_t o_gblk4 = cv.take<uint32_t>((size_t)P / 4 + 2);
-    const size_t o_gblklo = cv.take<uint32_t>((size_t)P + 2);
-    const size_t o_gwork = cv.take<unsigned long long>(2);
+    const size_t o_gu4 = cv.take<uint32_t>((size_t)P + 4 * (size_t)c + 4);
+    const size_t o_gu2 = cv.take<uint32_t>(2 * (size_t)c + 4);
+    const size_t o_glop = cv.take<uint32_t>((size_t)c + 4);
+    const size_t o_gblk4 = cv.take<uint32_t>((size_t)P / 4 + c + 2);
+    const size_t o_gblk2 = cv.take<uint32_t>((size_t)c + 2);
+    const size_t o_gblklo = cv.take<uint32_t>((size_t)c + 2);
+    const size_t o_gwork = cv.take<unsigned long long>(4);
     IVFR_TRY(ix->search_ws.reserve(cv.off + 256));
     char* ws = ix->search_ws.as<char>();
     float* xnorm = reinterpret_cast<float*>(ws + o_xnorm);
@@ -154,12 +157,15 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     GroupBuffers gb;
     gb.list_np = reinterpret_cast<uint32_t*>(ws + o_gnp);
     gb.g4 = reinterpret_cast<uint32_t*>(ws + o_gg4);
+    gb.g2 = reinterpret_cast<uint32_t*>(ws + o_gg2);
     gb.lo = reinterpret_cast<uint32_t*>(ws + o_glo);
     gb.cur = reinterpret_cast<uint32_t*>(ws + o_gcur);
     gb.counts = reinterpret_cast<uint32_t*>(ws + o_gcounts);
     gb.unit4_pairs = reinterpret_cast<uint32_t*>(ws + o_gu4);
+    gb.unit2_pairs = reinterpret_cast<uint32_t*>(ws + o_gu2);
     gb.lo_pairs = reinterpret_cast<uint32_t*>(ws + o_glop);
     gb.blk4 = reinterpret_cast<uint32_t*>(ws + o_gblk4);
+    gb.blk2 = reinterpret_cast<uint32_t*>(ws + o_gblk2);
     gb.blklo = reinterpret_cast<uint32_t*>(ws + o_gblklo);
     gb.work = reinterpret_cast<unsigned long long*>(ws + o_gwork);
     const bool share = ix->share_lists && ivfr_shared_scan_supported(ix);
@@ -198,8 +204,8 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, min_cap, pb, st));
         if (share) {
             IVFR_TRY(ivfr_launch_group_plan(probe, Pb, c, pb.len, gb, st));
-            IVFR_HIP(hipMemcpyAsync(ix->h_status + 8, gb.counts, 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-            IVFR_HIP(hipMemcpyAsync(ix->h_status + 10, gb.work, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+            IVFR_HIP(hipMemcpyAsync(ix->h_status + 8, gb.counts, 3 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+            IVFR_HIP(hipMemcpyAsync(ix->h_status + 12, gb.work, 3 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         }
         // the candidate pool is sized by the plan: one small read-back
         IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
@@ -212,14 +218,16 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         memcpy(tot2, ix->h_status + 2, sizeof(tot2));
         ix->st_codes += (int64_t)tot2[0];
         ix->st_pairs += Pb;
-        int n_unit4 = 0, n_lo = 0;
+        int n_unit4 = 0, n_unit2 = 0, n_lo = 0;
         if (share) {
-            unsigned long long gw[2];
-            memcpy(gw, ix->h_status + 10, sizeof(gw));
+            unsigned long long gw[3];
+            memcpy(gw, ix->h_status + 12, sizeof(gw));
             n_unit4 = ix->h_status[8];
-            n_lo = ix->h_status[9];
-            ix->st_streamed += (int64_t)(gw[0] + gw[1]);
-            ix->st_shared_codes += (int64_t)(4 * gw[0]);
+            n_unit2 = ix->h_status[9];
+            n_lo = ix->h_status[10];
+            ix->st_streamed += (int64_t)gw[0];
+            ix->st_shared_codes += (int64_t)gw[1];
+            ix->st_shared2_codes += (int64_t)gw[2];
         } else {
             ix->st_streamed += (int64_t)tot2[0];
         }
@@ -242,9 +250,13 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         if (share) {
             // lists visited by several queries: four queries per pass over the list; the rest pair by pair
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED, true));
-            IVFR_TRY(ivfr_launch_scan_shared(ix, lut, pb.pair_start, pb.len, gb.blk4, gb.unit4_pairs, n_unit4, w, tau,
-                                             cand, cnt, lay, groups, st));
+            IVFR_TRY(ivfr_launch_scan_shared(ix, 4, lut, pb.pair_start, pb.len, gb.blk4, gb.unit4_pairs, n_unit4, w,
+                                             tau, cand, cnt, lay, groups, st));
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED, false));
+            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED2, true));
+            IVFR_TRY(ivfr_launch_scan_shared(ix, 2, lut, pb.pair_start, pb.len, gb.blk2, gb.unit2_pairs, n_unit2, w,
+                                             tau, cand, cnt, lay, groups, st));
+            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED2, false));
             IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
             IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, gb.blklo, gb.lo_pairs, n_lo, w, tau, cand, cnt,
                                       lay, groups, st));
@@ -328,7 +340,8 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, ep.a, ep.b) == hipSuccess) {
             ix->prof_ms[ep.kind] += ms;
-            if (ep.kind == IVFR_STAGE_SCAN || ep.kind == IVFR_STAGE_SCAN_SHARED) ix->prof_scan_launches += 1;
+            if (ep.kind == IVFR_STAGE_SCAN || ep.kind == IVFR_STAGE_SCAN_SHARED || ep.kind == IVFR_STAGE_SCAN_SHARED2)
+                ix->prof_scan_launches += 1;
         }
         (void)hipEventDestroy(ep.a);
         (void)hipEventDestroy(ep.b);
