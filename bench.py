@@ -21,10 +21,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 
-# HBM bytes moved per adc_scan_kernel launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by a
-# plain copy of known size (profiles/search_cfg4_hbm_traffic.txt): 101.10 GB read + 0.15 GB written for
-# 101.14 GB of code bytes.  Stored as a ratio to the algorithmic bytes of the launch; other workloads: null.
-MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 101.252 / 101.141}
+# HBM bytes moved per scan launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy
+# of known size (profiles/search_cfg4_hbm_traffic.txt), stored as a ratio to the algorithmic bytes of the
+# launch (m bytes per (query, entry) estimate); other workloads: null.
+#   per-pair scan (--per-pair):  101.10 GB read + 0.15 GB written for 101.14 GB of code bytes
+#   shared scan of four:          24.89 GB read + 0.16 GB written for  96.14 GB (one read serves four queries)
+MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 101.252 / 101.141,
+                          ("cfg4", "adc_scan_shared_kernel"): 25.051 / 96.142}
+LDS_PEAK_GBS = 256 * 128 * 2.4    # 256 CUs x 128 B/clk x 2.4 GHz
 
 
 def log(*a):
@@ -239,7 +243,11 @@ def main():
                      "traffic": (code_bytes * MEASURED_TRAFFIC_RATIO[traffic_key]
                                  if traffic_key in MEASURED_TRAFFIC_RATIO and plain else None),
                      "algorithmic_bytes_per_launch": code_bytes,
-                     "avg_launch_ms": k_ms},
+                     "avg_launch_ms": k_ms,
+                     # every estimate is m random 4-byte LDS reads: the scan's other limiter
+                     "lds": {"achieved": 4.0 * code_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0,
+                             "peak": LDS_PEAK_GBS, "unit": "GB/s",
+                             "frac": (4.0 * code_bytes / (k_ms * 1e-3) / 1e9 / LDS_PEAK_GBS) if k_ms > 0 else 0.0}},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ix, cfg, queries_u8, g_ids)

@@ -10,20 +10,26 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 //  - a query whose visited lists hold at most `full_limit` entries keeps every estimate
 //    (tau = +inf) and is selected from directly;
 //  - otherwise a sample is scored first: the first ceil(len / stride) entries of every visited
-//    list, stride = k' / mu, so that about mu of the true k' best fall in the sample.  Entries
+//    list, stride = k' / mu, so that about mu of the true k' best fall in the sample (a query
+//    that visits very many entries gets a wider stride so its sample stays below max_sample).  Entries
 //    of a list are in id order, which carries no information about the distance to a query,
 //    so a prefix is as good as a random draw, and taking the same fraction of every visited
 //    list keeps the sample stratified over near and far lists.
 // ------------------------------------------------------------------------------------------
 __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int w,
                                   const uint32_t* __restrict__ list_start, const uint32_t* __restrict__ list_len,
-                                  uint32_t full_limit, uint32_t stride_k, uint32_t min_cap, PlanBuffers pb) {
+                                  uint32_t full_limit, uint32_t stride_k, uint32_t min_cap, uint32_t max_sample,
+                                  int kprime, PlanBuffers pb) {
     int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nq) return;
-    const uint32_t stride = stride_k < 1 ? 1u : stride_k;
     unsigned long long total = 0;
     for (int r = 0; r < w; ++r) total += list_len[probe[(int64_t)q * w + r]];
     const bool fully = total <= full_limit;
+    // stride k'/mu, widened when the query visits so much that its sample would exceed max_sample
+    unsigned long long stride64 = stride_k < 1 ? 1ull : stride_k;
+    const unsigned long long widen = (total + max_sample - 1) / max_sample;
+    if (widen > stride64) stride64 = widen;
+    const uint32_t stride = (uint32_t)(stride64 > 0xFFFFFFFFull ? 0xFFFFFFFFull : stride64);
     unsigned long long sampled = 0;
     for (int r = 0; r < w; ++r) {
         int64_t p = (int64_t)q * w + r;
@@ -38,8 +44,15 @@ __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int
     pb.sq[q] = total;
     pb.nsample[q] = (uint32_t)(sampled > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : sampled);
     pb.fully[q] = fully ? 1 : 0;
-    // buffer: everything (no filter), or the larger of the sample and the survivors' allowance
-    unsigned long long capv = fully ? total : (sampled > min_cap ? sampled : (unsigned long long)min_cap);
+    // buffer: everything (no filter), or the largest of the sample, min_cap and twice the survivors
+    // expected from the bound (rank r of the sample, one sampled entry standing for `stride`)
+    unsigned long long capv = total;
+    if (!fully) {
+        const double mu = (double)kprime / (double)stride;
+        const double expect = (mu + 5.0 * sqrt(mu) + 6.0) * (double)stride;
+        capv = sampled > min_cap ? sampled : (unsigned long long)min_cap;
+        if ((double)capv < 2.0 * expect) capv = (unsigned long long)(2.0 * expect);
+    }
     if (capv > 0xFFFFFFF0ull) capv = 0xFFFFFFF0ull;
     pb.capq[q] = (uint32_t)capv;
     atomicAdd(pb.totals, total);
@@ -108,10 +121,11 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int P, PlanBuff
 }
 
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
-                     uint32_t stride_k, uint32_t min_cap, const PlanBuffers& pb, hipStream_t st) {
+                     uint32_t stride_k, uint32_t min_cap, uint32_t max_sample, int kprime, const PlanBuffers& pb,
+                     hipStream_t st) {
     IVFR_HIP(hipMemsetAsync(pb.totals, 0, 2 * sizeof(unsigned long long), st));
     hipLaunchKernelGGL(plan_pairs_kernel, dim3((nq + 127) / 128), dim3(128), 0, st, probe, nq, w, ix->list_start,
-                       ix->list_len, full_limit, stride_k, min_cap, pb);
+                       ix->list_len, full_limit, stride_k, min_cap, max_sample, kprime, pb);
     IVFR_HIP(hipGetLastError());
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, nq, nq * w, pb);
     IVFR_HIP(hipGetLastError());

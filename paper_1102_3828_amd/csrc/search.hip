@@ -48,6 +48,8 @@ struct EventPair {
 
 // Poisson mean of true k'-best entries wanted inside the sample; the sample stride is k' / mu.
 #define IVFR_SAMPLE_MU 4
+// Upper limit of a query's sample (entries); beyond it the stride widens and the bound loosens.
+#define IVFR_MAX_SAMPLE 131072u
 
 extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t nq, int32_t w, int32_t kprime,
                                  int32_t k, int32_t* ids_out, float* dist_out, int32_t* probe_out,
@@ -201,7 +203,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
             a.nseg = nb; a.K = w; a.keys = ckeys; a.seg_stride = c; a.fixed_count = c;
             IVFR_TRY(ivfr_launch_select_sorted(a, nullptr, 0, probe, probed, st));
         }
-        IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, min_cap, pb, st));
+        IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, min_cap, IVFR_MAX_SAMPLE, kprime, pb, st));
         if (share) {
             IVFR_TRY(ivfr_launch_group_plan(probe, Pb, c, pb.len, gb, st));
             IVFR_HIP(hipMemcpyAsync(ix->h_status + 8, gb.counts, 3 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));

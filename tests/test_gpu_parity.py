@@ -93,6 +93,49 @@ def test_stages_against_oracle_trace(kw):
     ix.close()
 
 
+@pytest.mark.parametrize("m,m_refine", [(4, 0), (4, 64), (16, 8), (32, 32), (64, 4)])
+def test_other_code_sizes(m, m_refine):
+    """Code sizes other than the workloads' m = 8 (the paper's Table 2 varies m and m'): every
+    sub-vector width from 16 down to 1 dimension, with and without list sharing."""
+    wl = tiny_workload(d=64, G=16, N=4000, n_train=2500, n_query=16, c=12, m=m, m_refine=m_refine, iters=3)
+    index, X = wl["index"], wl["X"]
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    for share in (True, False):
+        ix.set_list_sharing(share)
+        for full_mult in (8, 1):
+            ix.set_tuning(full_mult=full_mult)
+            log("code sizes", m, m_refine, "share", share, "full_mult", full_mult)
+            ids, dist = ix.search(xq, 5, 150, 12)
+            exact, excused = compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, index, 5, 150, 12)
+            assert excused <= 2
+    ix.close()
+
+
+def test_single_list_is_exhaustive_adc_plus_r():
+    """c = 1: no inverted file, every query scans every code (the ADC+R rows of Table 1)."""
+    import paper_1102_3828_amd as pkg
+    wl = tiny_workload(d=32, G=16, N=6000, n_train=2000, n_query=12, c=1, m=4, m_refine=8, iters=4)
+    index, X, Y = wl["index"], wl["X"], wl["Y"]
+    ix = gpu_index_from_oracle(index)
+    for kp, k, full_mult in ((100, 10, 8), (600, 50, 1), (6000, 20, 8)):
+        ix.set_tuning(full_mult=full_mult)
+        ids, dist = ix.search(queries_dev(X), 1, kp, k)
+        assert ix.search_stats()["codes_scanned"] == len(X) * index.N
+        compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, index, 1, kp, k)
+    ix.close()
+    # the GPU builds the same single-list index from the vectors
+    ix = pkg.Index(32, 1, 4, 8)
+    b = index.books
+    ix.set_codebooks(b.coarse, b.pq, b.rq)
+    ix.add(Y, 0)
+    ix.finalize()
+    offsets, ids, codes, rcodes = ix.export()
+    assert offsets.tolist() == [0, index.N] and np.array_equal(ids, np.arange(index.N))
+    assert check_encoding(Y, b, offsets, ids, codes, rcodes) <= 20
+    ix.close()
+
+
 def test_all_lists_full_shortlist_is_exact_over_reconstructions():
     """w = c and k' = N: the GPU result is the exact k-NN among the refined reconstructions."""
     from helpers import dense_reconstructions
@@ -372,11 +415,10 @@ def test_edge_cases_and_internal_paths():
     p_ids, p_dist = ix.search(xq, 6, 300, 20)
     assert ix.search_stats()["dense_fallbacks"] == 0
     assert np.array_equal(base_ids, p_ids.cpu().numpy()) and np.array_equal(base_dist, p_dist.cpu().numpy())
-    # a candidate buffer far too small makes the filter overflow: dense fallback, same answer
+    # the smallest candidate buffers the plan allows
     ix.set_tuning(full_mult=1, cap_mult=1, min_cap=1)
     f_ids, f_dist = ix.search(xq, 6, 300, 20)
-    log("dense fallbacks", ix.search_stats())
-    assert ix.search_stats()["dense_fallbacks"] > 0
+    log("smallest buffers", ix.search_stats())
     assert np.array_equal(base_ids, f_ids.cpu().numpy()) and np.array_equal(base_dist, f_dist.cpu().numpy())
     # every estimate kept (no sample, no filter)
     ix.set_tuning(full_mult=1000, cap_mult=1000, min_cap=8192)
@@ -397,6 +439,29 @@ def test_edge_cases_and_internal_paths():
     with torch.cuda.stream(s):
         t_ids, _ = ix.search(xq, 6, 300, 20)
     assert np.array_equal(base_ids, t_ids.cpu().numpy())
+    ix.close()
+
+
+def test_duplicate_vectors_take_the_exact_redo():
+    """Degenerate input: a database of a few vectors repeated a thousand times.  Estimates tie in
+    huge groups, so the entries at or below the sampled bound overflow the candidate buffer and the
+    query is redone through the buffer that holds everything; ties are then broken by id, exactly."""
+    wl = tiny_workload(d=32, G=16, N=3000, n_train=2000, n_query=12, c=8, m=4, m_refine=4, iters=4)
+    books, X = wl["books"], wl["X"]
+    distinct = wl["Y"][:6]
+    Y = np.repeat(distinct, 1000, axis=0)
+    rng = np.random.default_rng(3)
+    Y = Y[rng.permutation(len(Y))]
+    index = orc.build_index(Y, np.arange(len(Y)), books)
+    ix = gpu_index_from_oracle(index)
+    ix.set_tuning(full_mult=1, cap_mult=1, min_cap=1)
+    ids, dist = ix.search(queries_dev(X), 8, 50, 20)
+    st = ix.search_stats()
+    log("duplicates", st)
+    assert st["dense_fallbacks"] > 0
+    o_ids, o_dist, _ = orc.search(X, index, 8, 50, 20)
+    assert np.array_equal(ids.cpu().numpy(), o_ids)
+    assert np.allclose(dist.cpu().numpy(), o_dist, rtol=REL_TOL)
     ix.close()
 
 
