@@ -125,6 +125,10 @@ def main():
     ap.add_argument("--scan-groups", type=int, default=0)
     ap.add_argument("--per-pair", action="store_true",
                     help="scan every (query, list) pair on its own (no sharing of a list between queries)")
+    ap.add_argument("--sharing", type=int, default=2, choices=(0, 1, 2),
+                    help="list sharing mode: 0 per pair, 1 fp32 units of four/two, 2 also fp16 units of eight")
+    ap.add_argument("--sweep-groups", default="",
+                    help="comma-separated scan workgroup counts: time a few steps with each (to stderr) before the run")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB) three times, as the "
                          "known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -155,12 +159,26 @@ def main():
     if args.scan_groups:
         ix.set_tuning(scan_groups=args.scan_groups)
     if args.per_pair:
-        ix.set_list_sharing(False)
+        args.sharing = 0
+    ix.set_list_sharing(args.sharing)
 
     B = min(cfg.batch, cfg.n_query)
     n_batches = max(1, cfg.n_query // B)
     batches = [xq[i * B:(i + 1) * B].contiguous() for i in range(n_batches)]
 
+    if args.sweep_groups:
+        ix.set_profiling(True)
+        for gcount in [int(x) for x in args.sweep_groups.split(",")]:
+            ix.set_tuning(scan_groups=gcount)
+            acc = {}
+            for s in range(4):
+                ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
+                if s:
+                    for name, ms in ix.stage_times().items():
+                        acc[name] = acc.get(name, 0.0) + ms / 3.0
+            log(f"[bench] scan_groups={gcount}: " + ", ".join(f"{k} {v:.3f}" for k, v in acc.items() if k.startswith("scan") or k == "sample"))
+        ix.set_profiling(False)
+        ix.set_tuning(scan_groups=args.scan_groups)
     for s in range(args.warmup):
         t0 = time.perf_counter()
         ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
@@ -170,6 +188,7 @@ def main():
     codes = 0
     codes_shared = 0
     codes_shared2 = 0
+    codes_shared8 = 0
     codes_streamed = 0
     dense_total = 0
     stage_ms = {}
@@ -182,6 +201,7 @@ def main():
         codes += st["codes_scanned"]
         codes_shared += st["codes_scanned_shared"]
         codes_shared2 += st["codes_scanned_shared2"]
+        codes_shared8 += st["codes_scanned_shared8"]
         codes_streamed += st["codes_streamed"]
         scan_launches += pr.pop("scan_launches")
         for name, ms in pr.items():
@@ -212,12 +232,13 @@ def main():
     steps = max(args.steps, 1)
     # Dominant kernel: the shared-list scan when it does most of the work, else the per-pair scan.
     # Algorithmic bytes = m bytes per (query, visited entry) estimate the kernel computes.
-    ms_pair, ms_shared = stage_ms.get("scan", 0.0) / steps, stage_ms.get("scan_shared", 0.0) / steps
-    if ms_shared > ms_pair:
-        kname, k_ms, k_codes = "adc_scan_shared_kernel", ms_shared, codes_shared / steps
-    else:
-        kname, k_ms, k_codes = "adc_scan_kernel", ms_pair, (codes - codes_shared - codes_shared2) / steps
+    kernels = [("adc_scan_kernel", stage_ms.get("scan", 0.0) / steps,
+                (codes - codes_shared - codes_shared2 - codes_shared8) / steps),
+               ("adc_scan_shared_kernel", stage_ms.get("scan_shared", 0.0) / steps, codes_shared / steps),
+               ("adc_scan_shared8h_kernel", stage_ms.get("scan_shared8", 0.0) / steps, codes_shared8 / steps)]
+    kname, k_ms, k_codes = max(kernels, key=lambda k: k[1])
     code_bytes = cfg.m * k_codes
+    lds_b = 2.0 if kname == "adc_scan_shared8h_kernel" else 4.0
     achieved = code_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
     traffic_key = (cfg.name, kname)
     plain = not (args.N or args.kprime or args.m_refine >= 0)
@@ -228,12 +249,13 @@ def main():
         "config": {"workload": f"{cfg.name}: N={cfg.N} d={cfg.d} c={cfg.c} m={cfg.m} m'={cfg.m_refine} "
                                f"w={cfg.w} k'={cfg.kprime} k={cfg.k}, {B} queries per step",
                    "generator": f"uint8 Gaussian mixture G={cfg.G} zipf={cfg.zipf} seed={sd.BASE_SEED}",
-                   "list_sharing": not args.per_pair},
+                   "list_sharing_mode": args.sharing},
         "adc_codes_per_s": codes / elapsed,
         "codes_scanned_per_step": codes / steps,
         "codes_streamed_per_step": codes_streamed / steps,
         "codes_scanned_shared_per_step": codes_shared / steps,
         "codes_scanned_shared2_per_step": codes_shared2 / steps,
+        "codes_scanned_shared8_per_step": codes_shared8 / steps,
         "stage_ms_per_step": {name: ms / args.steps for name, ms in stage_ms.items()},
         "dense_fallbacks_total": dense_total,
         "recall": recall, "recall_queries": n_gt,
@@ -244,10 +266,10 @@ def main():
                                  if traffic_key in MEASURED_TRAFFIC_RATIO and plain else None),
                      "algorithmic_bytes_per_launch": code_bytes,
                      "avg_launch_ms": k_ms,
-                     # every estimate is m random 4-byte LDS reads: the scan's other limiter
-                     "lds": {"achieved": 4.0 * code_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0,
+                     # every estimate is m random LDS reads of 4 bytes (2 with fp16 tables): the scan's other limiter
+                     "lds": {"achieved": lds_b * code_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0,
                              "peak": LDS_PEAK_GBS, "unit": "GB/s",
-                             "frac": (4.0 * code_bytes / (k_ms * 1e-3) / 1e9 / LDS_PEAK_GBS) if k_ms > 0 else 0.0}},
+                             "frac": (lds_b * code_bytes / (k_ms * 1e-3) / 1e9 / LDS_PEAK_GBS) if k_ms > 0 else 0.0}},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ix, cfg, queries_u8, g_ids)

@@ -109,16 +109,20 @@ int ivfr_search_trace(ivfr_index* index, const float* queries, int64_t nq, int32
  *   dense_fallbacks      queries redone exactly because the sampled bound failed its check
  *   codes_streamed       list entries read from memory by the scan (< codes_scanned when lists are
  *                        shared between queries)
- *   codes_scanned_shared / _shared2  parts of codes_scanned computed by the shared-list scans of
- *                        four and of two queries per pass                                           */
+ *   codes_scanned_shared / _shared2 / _shared8  parts of codes_scanned computed by the shared-list
+ *                        scans of four, two and eight queries per pass                              */
 int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
-                      int64_t* codes_streamed, int64_t* codes_scanned_shared, int64_t* codes_scanned_shared2);
+                      int64_t* codes_streamed, int64_t* codes_scanned_shared, int64_t* codes_scanned_shared2,
+                      int64_t* codes_scanned_shared8);
 
-/* List sharing (default on; needs m <= 16).  Queries of one internal batch that visit the same
- * list are scanned four (or two) at a time: the list's codes are read once and each code byte
- * fetches the queries' table entries with one 16-byte (8-byte) LDS read.  Estimates, and therefore results, are
- * bit-identical with sharing on or off; 0 scans every (query, list) pair on its own. */
-int ivfr_set_list_sharing(ivfr_index* index, int32_t enable);
+/* List sharing.  Queries of one internal batch that visit the same list are scanned together: the
+ * list's codes are read once and each code byte fetches all the queries' table entries with one
+ * LDS read.  mode 0: every (query, list) pair is scanned on its own.  mode 1 (needs m <= 16): units
+ * of four and of two queries with fp32 tables (16- and 8-byte LDS reads).  mode 2 (default; m <= 8):
+ * in addition units of eight queries with half-precision tables; an entry whose half-precision
+ * estimate could be within the bound is re-evaluated in fp32 before it is kept, so the recorded
+ * estimates, and therefore the results, are bit-identical in all three modes. */
+int ivfr_set_list_sharing(ivfr_index* index, int32_t mode);
 
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
  *   full_mult   (8)    a query that visits at most full_mult*k' entries keeps every estimate; a
@@ -128,14 +132,14 @@ int ivfr_set_list_sharing(ivfr_index* index, int32_t enable);
  *   cap_mult    (16)   such a query's candidate buffer holds max(cap_mult*k', min_cap) records,
  *   min_cap     (8192) or its sample if that is larger; overflowing it triggers an exact redo
  *   batch       (1024) queries processed per internal batch
- *   scan_groups (0 = 16 per compute unit) workgroups launched by the list-scan kernel          */
+ *   scan_groups (0 = chosen from the amount of work) workgroups launched by the list-scan kernels          */
 int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int32_t min_cap, int32_t batch,
                     int32_t scan_groups);
 
 /* Per-stage GPU time of the most recent search call, in milliseconds, measured with HIP events
  * on the search stream (recorded only after ivfr_set_profiling(index, 1)).  ms: host double
  * [IVFR_N_STAGES], indexed by IVFR_STAGE_*; scan_launches: launches of the list-scan kernels
- * (stages IVFR_STAGE_SCAN, _SCAN_SHARED and _SCAN_SHARED2 are exactly those launches), may be NULL. */
+ * (the IVFR_STAGE_SCAN* stages are exactly those launches), may be NULL. */
 #define IVFR_STAGE_COARSE    0   /* query norms + coarse distance GEMM                        */
 #define IVFR_STAGE_PROBE     1   /* w nearest lists + plan of (query, list) pairs             */
 #define IVFR_STAGE_LUT       2   /* look-up tables of Eq. (5)                                 */
@@ -146,7 +150,8 @@ int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int3
 #define IVFR_STAGE_FINAL     7   /* k smallest refined distances, sorted                      */
 #define IVFR_STAGE_SCAN_SHARED 8 /* ADC list scan, four queries per pass over a shared list   */
 #define IVFR_STAGE_SCAN_SHARED2 9 /* ADC list scan, two queries per pass over a shared list   */
-#define IVFR_N_STAGES        10
+#define IVFR_STAGE_SCAN_SHARED8 10 /* ADC list scan, eight queries per pass, fp16 tables      */
+#define IVFR_N_STAGES        11
 int ivfr_set_profiling(ivfr_index* index, int32_t enable);
 int ivfr_stage_times(const ivfr_index* index, double* ms, int32_t* scan_launches);
 

@@ -49,7 +49,7 @@ def _load():
         "ivfr_import": (ctypes.c_int, [vp, i64, vp, vp, vp, vp]),
         "ivfr_search": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp]),
         "ivfr_search_trace": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
-        "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 6),
+        "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 7),
         "ivfr_set_list_sharing": (ctypes.c_int, [vp, i32]),
         "ivfr_set_tuning": (ctypes.c_int, [vp, i32, i32, i32, i32, i32]),
         "ivfr_set_profiling": (ctypes.c_int, [vp, i32]),
@@ -194,14 +194,15 @@ class Index:
         return ids, dist, t
 
     def search_stats(self):
-        v = [ctypes.c_int64() for _ in range(6)]
+        v = [ctypes.c_int64() for _ in range(7)]
         _check(lib.ivfr_search_stats(self._h, *[ctypes.byref(x) for x in v]))
         names = ("codes_scanned", "pairs", "dense_fallbacks", "codes_streamed", "codes_scanned_shared",
-                 "codes_scanned_shared2")
+                 "codes_scanned_shared2", "codes_scanned_shared8")
         return dict(zip(names, [x.value for x in v]))
 
-    def set_list_sharing(self, enable=True):
-        _check(lib.ivfr_set_list_sharing(self._h, 1 if enable else 0))
+    def set_list_sharing(self, mode=2):
+        """0 = per pair; 1 = fp32 units of four / two; 2 = also fp16 units of eight (default)."""
+        _check(lib.ivfr_set_list_sharing(self._h, int(mode)))
 
     def set_tuning(self, full_mult=0, cap_mult=0, min_cap=0, batch=0, scan_groups=0):
         _check(lib.ivfr_set_tuning(self._h, full_mult, cap_mult, min_cap, batch, scan_groups))
@@ -209,7 +210,7 @@ class Index:
     def set_profiling(self, enable=True):
         _check(lib.ivfr_set_profiling(self._h, 1 if enable else 0))
 
-    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared", "scan_shared2")
+    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared", "scan_shared2", "scan_shared8")
 
     def stage_times(self):
         """Per-stage milliseconds of the last search (after set_profiling) and scan launch count."""

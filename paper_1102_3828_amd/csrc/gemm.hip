@@ -32,6 +32,27 @@ __global__ __launch_bounds__(256) void row_norms_kernel(const float* __restrict_
     out[row] = s;
 }
 
+// out[j] = max over the `per` rows of group j of sqrt(norm2[j * per + k])
+__global__ __launch_bounds__(256) void group_max_norm_kernel(const float* __restrict__ norm2, int per,
+                                                             float* __restrict__ out) {
+    __shared__ float red[256];
+    float m = 0.f;
+    for (int k = threadIdx.x; k < per; k += 256) m = fmaxf(m, norm2[(int64_t)blockIdx.x * per + k]);
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[blockIdx.x] = sqrtf(red[0]);
+}
+
+int ivfr_launch_group_max_norm(const float* norm2, int groups, int per, float* out, hipStream_t st) {
+    hipLaunchKernelGGL(group_max_norm_kernel, dim3(groups), dim3(256), 0, st, norm2, per, out);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
 int ivfr_launch_row_norms(const float* X, int64_t n, int dim, float* out, hipStream_t st) {
     if (n <= 0) return IVFR_OK;
     hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, X, n, dim, out);

@@ -112,7 +112,7 @@ extern "C" int ivfr_destroy(ivfr_index* ix) {
     (void)hipSetDevice(ix->p.device);
     (void)hipDeviceSynchronize();
     free_staged(ix);
-    dev_free(ix->coarse); dev_free(ix->coarse_norm); dev_free(ix->pq); dev_free(ix->pq_norm); dev_free(ix->rq);
+    dev_free(ix->coarse); dev_free(ix->coarse_norm); dev_free(ix->pq); dev_free(ix->pq_norm); dev_free(ix->pq_maxnorm); dev_free(ix->rq);
     dev_free(ix->list_fill); dev_free(ix->list_start); dev_free(ix->list_len);
     dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
     ix->search_ws.release(); ix->cand_ws.release(); ix->encode_ws.release(); ix->dense_ws.release();
@@ -128,6 +128,7 @@ static int alloc_books(ivfr_index* ix) {
     IVFR_TRY(dev_alloc(&ix->coarse_norm, (size_t)p.c));
     IVFR_TRY(dev_alloc(&ix->pq, (size_t)p.m * IVFR_KS * ix->dsub));
     IVFR_TRY(dev_alloc(&ix->pq_norm, (size_t)p.m * IVFR_KS));
+    IVFR_TRY(dev_alloc(&ix->pq_maxnorm, (size_t)p.m));
     if (p.m_refine) IVFR_TRY(dev_alloc(&ix->rq, (size_t)p.m_refine * IVFR_KS * ix->dsub_r));
     return IVFR_OK;
 }
@@ -135,6 +136,7 @@ static int alloc_books(ivfr_index* ix) {
 static int refresh_norms(ivfr_index* ix, hipStream_t st) {
     IVFR_TRY(ivfr_launch_row_norms(ix->coarse, ix->p.c, ix->p.d, ix->coarse_norm, st));
     IVFR_TRY(ivfr_launch_row_norms(ix->pq, (int64_t)ix->p.m * IVFR_KS, ix->dsub, ix->pq_norm, st));
+    IVFR_TRY(ivfr_launch_group_max_norm(ix->pq_norm, ix->p.m, IVFR_KS, ix->pq_maxnorm, st));
     return IVFR_OK;
 }
 
@@ -495,7 +497,7 @@ extern "C" int ivfr_stage_times(const ivfr_index* ix, double* ms, int32_t* scan_
 
 extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
                                  int64_t* codes_streamed, int64_t* codes_scanned_shared,
-                                 int64_t* codes_scanned_shared2) {
+                                 int64_t* codes_scanned_shared2, int64_t* codes_scanned_shared8) {
     IVFR_REQUIRE(ix, "ivfr_search_stats: null index");
     if (codes_scanned) *codes_scanned = ix->st_codes;
     if (pairs) *pairs = ix->st_pairs;
@@ -503,11 +505,13 @@ extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, i
     if (codes_streamed) *codes_streamed = ix->st_streamed;
     if (codes_scanned_shared) *codes_scanned_shared = ix->st_shared_codes;
     if (codes_scanned_shared2) *codes_scanned_shared2 = ix->st_shared2_codes;
+    if (codes_scanned_shared8) *codes_scanned_shared8 = ix->st_shared8_codes;
     return IVFR_OK;
 }
 
-extern "C" int ivfr_set_list_sharing(ivfr_index* ix, int32_t enable) {
+extern "C" int ivfr_set_list_sharing(ivfr_index* ix, int32_t mode) {
     IVFR_REQUIRE(ix, "ivfr_set_list_sharing: null index");
-    ix->share_lists = enable ? 1 : 0;
+    IVFR_REQUIRE(mode >= 0 && mode <= 2, "list sharing mode %d must be 0, 1 or 2", mode);
+    ix->share_lists = mode;
     return IVFR_OK;
 }

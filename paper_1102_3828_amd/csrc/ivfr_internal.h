@@ -86,6 +86,7 @@ struct ivfr_index {
     float* coarse_norm = nullptr;  // [c]
     float* pq = nullptr;           // [m, 256, dsub]
     float* pq_norm = nullptr;      // [m, 256]
+    float* pq_maxnorm = nullptr;   // [m] largest centroid norm of each sub-quantizer
     float* rq = nullptr;           // [m', 256, dsub_r]
     bool has_books = false;
 
@@ -110,7 +111,7 @@ struct ivfr_index {
 
     // tuning
     int full_mult = 8, cap_mult = 16, batch = 1024, scan_groups = 0;
-    int share_lists = 1;             // 1 = scan lists visited by several queries of a batch once for four of them
+    int share_lists = 2;             // 0 = every pair on its own; 1 = fp32 units of four / two; 2 = also fp16 units of eight
     int min_cap = 8192;
 
     // scratch
@@ -118,7 +119,7 @@ struct ivfr_index {
     int* h_status = nullptr;         // pinned host word(s) for status read-back
 
     // stats of the last search
-    int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0;
+    int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0, st_shared8_codes = 0;
     bool profiling = false;
     double prof_ms[IVFR_N_STAGES] = {0};
     int prof_scan_launches = 0;
@@ -129,6 +130,7 @@ struct ivfr_index {
 
 // squared norms of the rows of X [n, dim]
 int ivfr_launch_row_norms(const float* X, int64_t n, int dim, float* out, hipStream_t st);
+int ivfr_launch_group_max_norm(const float* norm2, int groups, int per, float* out, hipStream_t st);
 // uint8 [n, d] -> fp32
 int ivfr_launch_u8_to_f32(const uint8_t* x, int64_t count, float* out, hipStream_t st);
 
@@ -192,35 +194,41 @@ int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, 
                      uint32_t stride_k, uint32_t min_cap, uint32_t max_sample, int kprime, const PlanBuffers& pb,
                      hipStream_t st);
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
-                    float* lut, hipStream_t st);
+                    float* lut, float* lut_scale, hipStream_t st);
 // unit_pairs == nullptr: unit u of the launch is pair u; otherwise pair unit_pairs[u]
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau, uint2* cand,
                      uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st);
 
-// Shared scan: pairs of one batch grouped by list into units of four, units of two and single pairs
+// Shared scan: pairs of one batch grouped by list into units of eight, four, two and single pairs
 struct GroupBuffers {
-    uint32_t* list_np;      // [c] pairs visiting each list
-    uint32_t* g4;           // [c] exclusive prefix of units of four
-    uint32_t* g2;           // [c] exclusive prefix of units of two
-    uint32_t* lo;           // [c] exclusive prefix of single pairs
-    uint32_t* cur;          // [c] fill cursors
-    uint32_t* counts;       // [3] units of four, units of two, single pairs
-    uint32_t* unit4_pairs;  // [P + 4c + 4] pair ids, four per unit (0xFFFFFFFF = empty slot)
+    uint32_t* list_np;      // [2c] pairs visiting each list, by class (0 = filtered query, 1 = keeps everything)
+    uint32_t* gpre;         // [4][c] exclusive prefixes of units of eight / four / two / single pairs
+    uint32_t* cur;          // [2c] fill cursors
+    uint32_t* counts;       // [4] units of eight, four, two, single pairs
+    uint32_t* unit8_pairs;  // pair ids, eight per unit (0xFFFFFFFF = empty slot); unit4_pairs follows contiguously
+    uint32_t* unit4_pairs;  // pair ids, four per unit
+    size_t unit_bytes;      // bytes of unit8_pairs + unit4_pairs (cleared to empty before every fill)
     uint32_t* unit2_pairs;  // [2c] pair ids, two per unit
     uint32_t* lo_pairs;     // [c] single pair ids
-    uint32_t* blk4;         // [P/4 + c + 2] block prefix over units of four
-    uint32_t* blk2;         // [c + 2] block prefix over units of two
-    uint32_t* blklo;        // [c + 2] block prefix over single pairs
-    unsigned long long* work;  // [3] list entries streamed by all scans; estimates computed by the scans of four, of two
+    uint32_t* blk8;         // block prefix over units of eight
+    uint32_t* blk4;         // ... of four
+    uint32_t* blk2;         // ... of two
+    uint32_t* blklo;        // ... over single pairs
+    unsigned long long* work;  // [5] list entries streamed; estimates computed by units of eight, four, two, singles
 };
-int ivfr_launch_group_plan(const int32_t* probe, int P, int c, const uint32_t* pair_len, const GroupBuffers& gb,
-                           hipStream_t st);
+int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* fully, bool use8,
+                           const uint32_t* pair_len, const GroupBuffers& gb, hipStream_t st);
 bool ivfr_shared_scan_supported(const ivfr_index* ix);
+bool ivfr_shared8h_supported(const ivfr_index* ix);
 int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
                             int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
                             hipStream_t st);
+int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const float* lut_scale,
+                              const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
+                              const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,
+                              uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st);
 
 // Encoding (encode.hip)
 int ivfr_launch_residual(float* X, int64_t n, int d, const float* C, const int32_t* assign, hipStream_t st);

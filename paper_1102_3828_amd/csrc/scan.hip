@@ -144,7 +144,8 @@ __global__ __launch_bounds__(256) void lut_mfma_kernel(const float* __restrict__
                                                        const int32_t* __restrict__ probe, int P, int w, int d, int m,
                                                        int dsub, const float* __restrict__ coarse,
                                                        const float* __restrict__ pq, const float* __restrict__ pq_norm,
-                                                       float* __restrict__ lut) {
+                                                       const float* __restrict__ pq_maxnorm,
+                                                       float* __restrict__ lut, float* __restrict__ lut_scale) {
     extern __shared__ float smem[];
     const int stride = d + 4;
     float* R = smem;                   // [32][d + 4]
@@ -172,6 +173,13 @@ __global__ __launch_bounds__(256) void lut_mfma_kernel(const float* __restrict__
         rn[i] = s;
     }
     __syncthreads();
+    // fp16 scale of the pair's table: every entry is at most (||r^j|| + max_k ||pq[j][k]||)^2, so with
+    // s = 60000 / sum_j of those bounds no sum of m scaled entries overflows half precision
+    if (tid < 32 && p0 + tid < P) {
+        float ub = 0.f;
+        for (int j = 0; j < m; ++j) { float a = sqrtf(rn[tid * m + j]) + pq_maxnorm[j]; ub = fmaf(a, a, ub); }
+        lut_scale[p0 + tid] = ub > 0.f ? 60000.f / ub : 1.f;
+    }
     const int r = lane & 31, h = lane >> 5;
     const int ntile = m * 8;   // (j, 32-centroid tile) units
     for (int u = wave; u < ntile; u += 4) {
@@ -205,12 +213,24 @@ __global__ __launch_bounds__(256) void lut_mfma_kernel(const float* __restrict__
 __global__ __launch_bounds__(256) void lut_direct_kernel(const float* __restrict__ queries,
                                                          const int32_t* __restrict__ probe, int P, int w, int d, int m,
                                                          int dsub, const float* __restrict__ coarse,
-                                                         const float* __restrict__ pq, float* __restrict__ lut) {
+                                                         const float* __restrict__ pq,
+                                                         const float* __restrict__ pq_maxnorm,
+                                                         float* __restrict__ lut, float* __restrict__ lut_scale) {
     extern __shared__ float smem[];   // residual [d]
     const int p = blockIdx.x;
     const int q = p / w, l = probe[p];
     for (int e = threadIdx.x; e < d; e += 256) smem[e] = queries[(int64_t)q * d + e] - coarse[(int64_t)l * d + e];
     __syncthreads();
+    if (threadIdx.x == 0) {
+        float ub = 0.f;
+        for (int j = 0; j < m; ++j) {
+            float s2 = 0.f;
+            for (int e = 0; e < dsub; ++e) s2 = fmaf(smem[j * dsub + e], smem[j * dsub + e], s2);
+            float a = sqrtf(s2) + pq_maxnorm[j];
+            ub = fmaf(a, a, ub);
+        }
+        lut_scale[p] = ub > 0.f ? 60000.f / ub : 1.f;
+    }
     for (int i = threadIdx.x; i < m * IVFR_KS; i += 256) {
         int j = i / IVFR_KS;
         const float* cb = pq + (int64_t)i * dsub;
@@ -221,16 +241,16 @@ __global__ __launch_bounds__(256) void lut_direct_kernel(const float* __restrict
 }
 
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w, float* lut,
-                    hipStream_t st) {
+                    float* lut_scale, hipStream_t st) {
     const int P = nq * w, d = ix->p.d, m = ix->p.m;
     if (P <= 0) return IVFR_OK;
     if (ix->dsub % 8 == 0) {
         size_t lds = (size_t)(32 * (d + 4) + 32 * m) * sizeof(float);
         hipLaunchKernelGGL(lut_mfma_kernel, dim3((P + 31) / 32), dim3(256), lds, st, queries, probe, P, w, d, m,
-                           ix->dsub, ix->coarse, ix->pq, ix->pq_norm, lut);
+                           ix->dsub, ix->coarse, ix->pq, ix->pq_norm, ix->pq_maxnorm, lut, lut_scale);
     } else {
         hipLaunchKernelGGL(lut_direct_kernel, dim3(P), dim3(256), (size_t)d * sizeof(float), st, queries, probe, P, w,
-                           d, m, ix->dsub, ix->coarse, ix->pq, lut);
+                           d, m, ix->dsub, ix->coarse, ix->pq, ix->pq_maxnorm, lut, lut_scale);
     }
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
@@ -411,39 +431,57 @@ int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pai
 // A list visited by 4n+3 queries gets one unit with an empty slot, 4n+2 a unit of two (8-byte
 // LDS reads), 4n+1 leaves a single pair to the per-pair kernel.
 // ------------------------------------------------------------------------------------------
-__global__ void group_count_kernel(const int32_t* __restrict__ probe, int P, uint32_t* __restrict__ list_np) {
+#define IVFR_NO_PAIR 0xFFFFFFFFu   // empty slot of a unit
+
+// Pairs of a query that is bounded by a sample ("filtered", class 0) may go into units of eight;
+// pairs of a query that keeps every estimate (class 1) only into the exact fp32 units.
+__global__ void group_count_kernel(const int32_t* __restrict__ probe, int P, int w, const uint8_t* __restrict__ fully,
+                                   int use8, uint32_t* __restrict__ list_np) {
     int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < P) atomicAdd(&list_np[probe[p]], 1u);
+    if (p >= P) return;
+    const int cls = (use8 && !fully[p / w]) ? 0 : 1;
+    atomicAdd(&list_np[2 * probe[p] + cls], 1u);
 }
 
-#define IVFR_NO_PAIR 0xFFFFFFFFu   // empty slot of a unit of four (a list visited by 4n+3 queries)
-
-// A list visited by n queries yields n/4 units of four; a remainder of 3 becomes one more unit of
-// four with an empty slot, a remainder of 2 a unit of two, a remainder of 1 a single pair.
-__device__ __forceinline__ void split_units(uint32_t n, uint32_t* n4, uint32_t* n2, uint32_t* n1) {
-    const uint32_t r = n & 3u;
-    *n4 = n / 4 + (r == 3 ? 1u : 0u);
-    *n2 = r == 2 ? 1u : 0u;
-    *n1 = r == 1 ? 1u : 0u;
+// A list visited by nA class-0 and nB class-1 pairs yields: units of eight from the class-0 pairs
+// (a remainder of 5..7 becomes one more unit with empty slots); the other class-0 pairs join the
+// class-1 pairs in a pool of n that gives n/4 units of four (a remainder of 3 becomes one more
+// unit with an empty slot), a remainder of 2 a unit of two, a remainder of 1 a single pair.
+struct ListSplit { uint32_t n8, in8, restA, n4, in4, n2, n1; };
+__device__ __forceinline__ ListSplit split_units(uint32_t nA, uint32_t nB) {
+    ListSplit s;
+    const uint32_t rA = nA & 7u;
+    s.n8 = nA / 8 + (rA >= 5 ? 1u : 0u);
+    s.in8 = rA >= 5 ? nA : nA - rA;
+    s.restA = nA - s.in8;
+    const uint32_t n = s.restA + nB, r = n & 3u;
+    s.n4 = n / 4 + (r == 3 ? 1u : 0u);
+    s.in4 = r == 3 ? n : n - r;
+    s.n2 = r == 2 ? 1u : 0u;
+    s.n1 = r == 1 ? 1u : 0u;
+    return s;
 }
 
-// per list: exclusive prefixes of units of four, units of two and single pairs; one workgroup
+// per list: exclusive prefixes of the four kinds of unit; one workgroup
 __global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, const uint32_t* __restrict__ list_np,
-                                                                uint32_t* __restrict__ g4, uint32_t* __restrict__ g2,
-                                                                uint32_t* __restrict__ lo, uint32_t* __restrict__ cur,
-                                                                uint32_t* __restrict__ counts) {
-    __shared__ uint32_t wtot[3][16];
-    __shared__ uint32_t carry[3];
+                                                                uint32_t* __restrict__ gpre /*[4][c]*/,
+                                                                uint32_t* __restrict__ cur /*[2c]*/,
+                                                                uint32_t* __restrict__ counts /*[4]*/) {
+    __shared__ uint32_t wtot[4][16];
+    __shared__ uint32_t carry[4];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid < 3) carry[tid] = 0;
+    if (tid < 4) carry[tid] = 0;
     __syncthreads();
     for (int base = 0; base < c; base += 1024) {
         int l = base + tid;
-        uint32_t v[3] = {0, 0, 0};
-        if (l < c) split_units(list_np[l], &v[0], &v[1], &v[2]);
-        uint32_t inc[3] = {v[0], v[1], v[2]};
+        uint32_t v[4] = {0, 0, 0, 0};
+        if (l < c) {
+            ListSplit sp = split_units(list_np[2 * l], list_np[2 * l + 1]);
+            v[0] = sp.n8; v[1] = sp.n4; v[2] = sp.n2; v[3] = sp.n1;
+        }
+        uint32_t inc[4] = {v[0], v[1], v[2], v[3]};
 #pragma unroll
-        for (int a = 0; a < 3; ++a) {
+        for (int a = 0; a < 4; ++a) {
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 uint32_t o = __shfl_up(inc[a], off, 64);
@@ -453,54 +491,58 @@ __global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, const uin
         }
         __syncthreads();
 #pragma unroll
-        for (int a = 0; a < 3; ++a) {
+        for (int a = 0; a < 4; ++a) {
             uint32_t add = carry[a];
             for (int x = 0; x < wv; ++x) add += wtot[a][x];
             inc[a] += add;
         }
-        if (l < c) { g4[l] = inc[0] - v[0]; g2[l] = inc[1] - v[1]; lo[l] = inc[2] - v[2]; cur[l] = 0; }
+        if (l < c) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) gpre[(int64_t)a * c + l] = inc[a] - v[a];
+            cur[2 * l] = 0;
+            cur[2 * l + 1] = 0;
+        }
         __syncthreads();
-        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; carry[2] = inc[2]; }
+        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; carry[2] = inc[2]; carry[3] = inc[3]; }
         __syncthreads();
     }
-    if (tid < 3) counts[tid] = carry[tid];
+    if (tid < 4) counts[tid] = carry[tid];
 }
 
-__global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, const uint32_t* __restrict__ list_np,
-                                  const uint32_t* __restrict__ g4, const uint32_t* __restrict__ g2,
-                                  const uint32_t* __restrict__ lo, uint32_t* __restrict__ cur,
-                                  uint32_t* __restrict__ unit4_pairs, uint32_t* __restrict__ unit2_pairs,
-                                  uint32_t* __restrict__ lo_pairs) {
+__global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, int w, const uint8_t* __restrict__ fully,
+                                  int use8, int c, const uint32_t* __restrict__ list_np,
+                                  const uint32_t* __restrict__ gpre, uint32_t* __restrict__ cur,
+                                  uint32_t* __restrict__ unit8_pairs, uint32_t* __restrict__ unit4_pairs,
+                                  uint32_t* __restrict__ unit2_pairs, uint32_t* __restrict__ lo_pairs) {
     int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= P) return;
     const int l = probe[p];
-    const uint32_t n = list_np[l], r = n & 3u;
-    const uint32_t in4 = (r == 3) ? n : n - r;   // pairs of this list that go into units of four
-    const uint32_t i = atomicAdd(&cur[l], 1u);
-    if (i < in4) unit4_pairs[(g4[l] + i / 4) * 4 + (i & 3)] = (uint32_t)p;
-    else if (r == 2) unit2_pairs[g2[l] * 2 + (i - in4)] = (uint32_t)p;
-    else lo_pairs[lo[l]] = (uint32_t)p;
+    const int cls = (use8 && !fully[p / w]) ? 0 : 1;
+    const ListSplit sp = split_units(list_np[2 * l], list_np[2 * l + 1]);
+    const uint32_t i = atomicAdd(&cur[2 * l + cls], 1u);
+    if (cls == 0 && i < sp.in8) {
+        unit8_pairs[((int64_t)gpre[l] + i / 8) * 8 + (i & 7)] = (uint32_t)p;
+        return;
+    }
+    const uint32_t k = cls == 0 ? i - sp.in8 : sp.restA + i;   // index in the list's pool
+    if (k < sp.in4) unit4_pairs[((int64_t)gpre[(int64_t)c + l] + k / 4) * 4 + (k & 3)] = (uint32_t)p;
+    else if (sp.n2) unit2_pairs[(int64_t)gpre[2 * (int64_t)c + l] * 2 + (k - sp.in4)] = (uint32_t)p;
+    else lo_pairs[gpre[3 * (int64_t)c + l]] = (uint32_t)p;
 }
 
-// block prefixes over the units of four, the units of two and the single pairs; work totals; one workgroup
-__global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* __restrict__ counts,
-                                                                const uint32_t* __restrict__ unit4_pairs,
-                                                                const uint32_t* __restrict__ unit2_pairs,
-                                                                const uint32_t* __restrict__ lo_pairs,
-                                                                const uint32_t* __restrict__ pair_len,
-                                                                uint32_t* __restrict__ blk4, uint32_t* __restrict__ blk2,
-                                                                uint32_t* __restrict__ blklo,
-                                                                unsigned long long* __restrict__ work) {
+// block prefixes over the four kinds of unit; work totals; one workgroup
+__global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* __restrict__ counts, GroupBuffers gb,
+                                                                const uint32_t* __restrict__ pair_len) {
     __shared__ uint32_t wtot[16];
     __shared__ uint32_t carry;
-    __shared__ unsigned long long s_read, s_est[2];
+    __shared__ unsigned long long s_read, s_est[4];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid == 0) { s_read = 0; s_est[0] = 0; s_est[1] = 0; }
-    for (int which = 0; which < 3; ++which) {
+    if (tid == 0) { s_read = 0; s_est[0] = s_est[1] = s_est[2] = s_est[3] = 0; }
+    for (int which = 0; which < 4; ++which) {
         const int n = (int)counts[which];
-        const uint32_t* ids = which == 0 ? unit4_pairs : (which == 1 ? unit2_pairs : lo_pairs);
-        uint32_t* out = which == 0 ? blk4 : (which == 1 ? blk2 : blklo);
-        const int step = which == 0 ? 4 : (which == 1 ? 2 : 1);
+        const uint32_t* ids = which == 0 ? gb.unit8_pairs : (which == 1 ? gb.unit4_pairs : (which == 2 ? gb.unit2_pairs : gb.lo_pairs));
+        uint32_t* out = which == 0 ? gb.blk8 : (which == 1 ? gb.blk4 : (which == 2 ? gb.blk2 : gb.blklo));
+        const int step = which == 0 ? 8 : (which == 1 ? 4 : (which == 2 ? 2 : 1));
         if (tid == 0) carry = 0;
         __syncthreads();
         unsigned long long my_read = 0, my_est = 0;
@@ -509,10 +551,10 @@ __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* 
             uint32_t len = 0;
             if (u < n) {
                 len = pair_len[ids[(int64_t)u * step]];
-                uint32_t members = step;
-                if (which == 0 && ids[(int64_t)u * 4 + 3] == IVFR_NO_PAIR) members = 3;
+                uint32_t members = 0;
+                for (int x = 0; x < step; ++x) members += ids[(int64_t)u * step + x] != IVFR_NO_PAIR ? 1u : 0u;
                 my_read += len;
-                if (which < 2) my_est += (unsigned long long)len * members;
+                my_est += (unsigned long long)len * members;
             }
             uint32_t v = (len + IVFR_BLOCK - 1) / IVFR_BLOCK;
             uint32_t inc = v;
@@ -532,25 +574,27 @@ __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* 
             __syncthreads();
         }
         atomicAdd(&s_read, my_read);
-        if (which < 2) atomicAdd(&s_est[which], my_est);
+        atomicAdd(&s_est[which], my_est);
         __syncthreads();
         if (tid == 0) out[n] = carry;
         __syncthreads();
     }
-    if (tid == 0) { work[0] = s_read; work[1] = s_est[0]; work[2] = s_est[1]; }
+    if (tid == 0) {
+        gb.work[0] = s_read;
+        gb.work[1] = s_est[0]; gb.work[2] = s_est[1]; gb.work[3] = s_est[2]; gb.work[4] = s_est[3];
+    }
 }
 
-int ivfr_launch_group_plan(const int32_t* probe, int P, int c, const uint32_t* pair_len, const GroupBuffers& gb,
-                           hipStream_t st) {
-    IVFR_HIP(hipMemsetAsync(gb.list_np, 0, (size_t)c * sizeof(uint32_t), st));
-    IVFR_HIP(hipMemsetAsync(gb.unit4_pairs, 0xff, ((size_t)P + 4 * (size_t)c + 4) * sizeof(uint32_t), st));
-    hipLaunchKernelGGL(group_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, gb.list_np);
-    hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, gb.list_np, gb.g4, gb.g2, gb.lo, gb.cur,
-                       gb.counts);
-    hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, gb.list_np, gb.g4, gb.g2,
-                       gb.lo, gb.cur, gb.unit4_pairs, gb.unit2_pairs, gb.lo_pairs);
-    hipLaunchKernelGGL(group_scan_units_kernel, dim3(1), dim3(1024), 0, st, gb.counts, gb.unit4_pairs, gb.unit2_pairs,
-                       gb.lo_pairs, pair_len, gb.blk4, gb.blk2, gb.blklo, gb.work);
+int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* fully, bool use8,
+                           const uint32_t* pair_len, const GroupBuffers& gb, hipStream_t st) {
+    IVFR_HIP(hipMemsetAsync(gb.list_np, 0, 2 * (size_t)c * sizeof(uint32_t), st));
+    IVFR_HIP(hipMemsetAsync(gb.unit8_pairs, 0xff, gb.unit_bytes, st));   // unit8 and unit4 arrays are contiguous
+    hipLaunchKernelGGL(group_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, fully, use8 ? 1 : 0,
+                       gb.list_np);
+    hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, gb.list_np, gb.gpre, gb.cur, gb.counts);
+    hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, fully, use8 ? 1 : 0, c,
+                       gb.list_np, gb.gpre, gb.cur, gb.unit8_pairs, gb.unit4_pairs, gb.unit2_pairs, gb.lo_pairs);
+    hipLaunchKernelGGL(group_scan_units_kernel, dim3(1), dim3(1024), 0, st, gb.counts, gb, pair_len);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -719,4 +763,181 @@ int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const
 #undef IVFR_SH_ARGS
     ivfr_set_error("shared scan supports m <= 16 and units of 2 or 4; got m = %d, unit %d", ix->p.m, G);
     return IVFR_ERR_INVALID_ARG;
+}
+
+// ------------------------------------------------------------------------------------------
+// Shared scan of eight queries with half-precision tables and an exact re-evaluation.
+//
+// LDS read bandwidth bounds the shared scan, so the tables of a unit of eight are kept as fp16:
+// one 16-byte LDS read then serves eight queries.  Table x is scaled by s_x (chosen so that no
+// sum of m entries can overflow fp16) and the m entries are added in packed fp16.  All terms
+// are non-negative, so the result H satisfies |H - s_x E| <= (2^-11 (m+1)) s_x E + m 2^-24 for
+// the fp32 estimate E (one rounding per table entry, one per add, subnormal spacing 2^-24).
+// An entry can only belong to the short-list if E <= tau, hence only if
+//     H <= s_x tau (1 + 4.5e-3) + 4e-3          (m <= 8: 9 * 2^-11 = 4.4e-3; the constant also
+//                                                covers fp16 subnormals flushed to zero),
+// and exactly those few (a fraction of a percent of the scanned entries) are re-evaluated in
+// fp32 from the query's table in global memory, with the same summation order as everywhere
+// else; only that exact value is compared with tau and recorded.  The records, and therefore
+// the search results, are bit-identical to the fp32 kernels' (tested).
+// ------------------------------------------------------------------------------------------
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+
+template <int M>
+__global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* __restrict__ codes,
+                                                                const float* __restrict__ lut,
+                                                                const float* __restrict__ lut_scale,
+                                                                const uint32_t* __restrict__ pair_start,
+                                                                const uint32_t* __restrict__ pair_len,
+                                                                const uint32_t* __restrict__ blkpre,
+                                                                const uint32_t* __restrict__ unit_pairs, int nunits,
+                                                                int w, const float* __restrict__ tau,
+                                                                uint2* __restrict__ cand,
+                                                                uint32_t* __restrict__ cand_cnt, CandLayout lay) {
+    extern __shared__ float s_raw[];
+    half8* s_lut8 = reinterpret_cast<half8*>(s_raw);   // [M * 256] x 8 halves: component x = query x of the unit
+    const uint32_t total = blkpre[nunits];
+    const uint32_t NG = gridDim.x, g = blockIdx.x;
+    uint32_t b = (uint32_t)(((uint64_t)total * g) / NG);
+    const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / NG);
+    if (b >= b_end) return;
+    int lo = 0, hi = nunits;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (blkpre[mid] <= b) lo = mid; else hi = mid;
+    }
+    int u = lo;
+    const int tid = threadIdx.x;
+    while (b < b_end) {
+        while (blkpre[u + 1] <= b) ++u;
+        const uint32_t pb0 = blkpre[u], pb1 = blkpre[u + 1];
+        const uint32_t stop = pb1 < b_end ? pb1 : b_end;
+        int64_t pid[8];
+        float t[8], ts[8], sc[8];
+        half8 tsh;   // the thresholds in half precision, rounded up
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const uint32_t raw = unit_pairs[(int64_t)u * 8 + x];
+            const bool real = raw != IVFR_NO_PAIR;
+            pid[x] = real ? (int64_t)raw : (int64_t)unit_pairs[(int64_t)u * 8];
+            sc[x] = lut_scale[pid[x]];
+            t[x] = real ? tau[(int)(pid[x] / w)] : -1.f;
+            ts[x] = real ? t[x] * sc[x] * 1.0045f + 4e-3f : -1.f;
+            tsh[x] = (_Float16)(real ? ts[x] * 1.001f + 1e-4f : -1.f);   // 2^-10 > the 2^-11 of the conversion
+        }
+        const uint32_t start = pair_start[pid[0]], len = pair_len[pid[0]];
+        __syncthreads();
+        for (int e = tid; e < M * IVFR_KS; e += 256) {
+            half8 h;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) h[x] = (_Float16)(lut[pid[x] * M * IVFR_KS + e] * sc[x]);
+            s_lut8[e] = h;
+        }
+        __syncthreads();
+        for (uint32_t bb = b; bb < stop; bb += 2) {
+            uint32_t wds[2][2][M / 4];
+            uint32_t e0[2];
+            bool in0[2], in1[2];
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                e0[v] = (bb + v - pb0) * IVFR_BLOCK + 2u * tid;
+                in0[v] = bb + v < stop && e0[v] < len;
+                in1[v] = bb + v < stop && e0[v] + 1 < len;
+                if (in0[v]) {
+                    const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e0[v]) * M);
+                    if (M == 8) {
+                        uint4 c4 = *reinterpret_cast<const uint4*>(src);
+                        wds[v][0][0] = c4.x; wds[v][0][1] = c4.y; wds[v][1][0] = c4.z; wds[v][1][1] = c4.w;
+                    } else {
+#pragma unroll
+                        for (int t2 = 0; t2 < M / 4; ++t2) { wds[v][0][t2] = src[t2]; wds[v][1][t2] = src[M / 4 + t2]; }
+                    }
+                } else {
+#pragma unroll
+                    for (int t2 = 0; t2 < M / 4; ++t2) { wds[v][0][t2] = 0; wds[v][1][t2] = 0; }
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                half8 ha, hb;
+#pragma unroll
+                for (int t2 = 0; t2 < M / 4; ++t2) {
+                    const uint32_t wa = wds[v][0][t2], wb = wds[v][1][t2];
+                    const half8* L = s_lut8 + t2 * 4 * IVFR_KS;
+                    if (t2 == 0) { ha = L[wa & 0xff]; hb = L[wb & 0xff]; }
+                    else { ha += L[wa & 0xff]; hb += L[wb & 0xff]; }
+                    ha += L[IVFR_KS + ((wa >> 8) & 0xff)];
+                    hb += L[IVFR_KS + ((wb >> 8) & 0xff)];
+                    ha += L[2 * IVFR_KS + ((wa >> 16) & 0xff)];
+                    hb += L[2 * IVFR_KS + ((wb >> 16) & 0xff)];
+                    ha += L[3 * IVFR_KS + (wa >> 24)];
+                    hb += L[3 * IVFR_KS + (wb >> 24)];
+                }
+                // fast reject: thresholds minus sums in packed fp16; a negative sign in all eight lanes of
+                // both codes means no query can keep either entry (the sign of an fp16 difference is exact)
+                const half8 da = tsh - ha, db = tsh - hb;
+                const uint4 ua = __builtin_bit_cast(uint4, da), ub = __builtin_bit_cast(uint4, db);
+                const bool none0 = !in0[v] || ((ua.x & ua.y & ua.z & ua.w & 0x80008000u) == 0x80008000u);
+                const bool none1 = !in1[v] || ((ub.x & ub.y & ub.z & ub.w & 0x80008000u) == 0x80008000u);
+                if (__ballot(!(none0 && none1)) == 0) continue;
+                uint32_t maybe0 = 0, maybe1 = 0;   // bit x: query x may keep this entry
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    maybe0 |= ((float)ha[x] <= ts[x] ? 1u : 0u) << x;
+                    maybe1 |= ((float)hb[x] <= ts[x] ? 1u : 0u) << x;
+                }
+                if (!in0[v]) maybe0 = 0;
+                if (!in1[v]) maybe1 = 0;
+                if (__ballot((maybe0 | maybe1) != 0) == 0) continue;
+                // exact fp32 re-evaluation of the few candidates, query by query
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    const bool c0 = (maybe0 >> x) & 1u, c1 = (maybe1 >> x) & 1u;
+                    if (__ballot(c0 || c1) == 0) continue;
+                    const float* T = lut + pid[x] * M * IVFR_KS;
+                    float x0 = 0.f, x1 = 0.f;
+                    if (c0) x0 = adc_sum<M>(T, wds[v][0]);
+                    if (c1) x1 = adc_sum<M>(T, wds[v][1]);
+                    const int q = (int)(pid[x] / w);
+                    append_records(c0 && x0 <= t[x], x0, start + e0[v], c1 && x1 <= t[x], x1, start + e0[v] + 1,
+                                   cand + lay.base(q), cand_cnt + q, lay.cap(q));
+                }
+            }
+        }
+        b = stop;
+    }
+}
+
+template <int M>
+static int launch_shared8h_m(const ivfr_index* ix, const float* lut, const float* lut_scale,
+                             const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
+                             const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,
+                             uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
+    size_t lds = (size_t)M * IVFR_KS * 16;
+    static bool attr_done = false;
+    if (!attr_done && lds > 48 * 1024) {
+        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(adc_scan_shared8h_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, lut_scale,
+                       pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+bool ivfr_shared8h_supported(const ivfr_index* ix) { return ix->p.m <= 8; }
+
+int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const float* lut_scale,
+                              const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
+                              const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,
+                              uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
+    if (nunits <= 0) return IVFR_OK;
+    switch (ix->p.m) {
+        case 4: return launch_shared8h_m<4>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
+        case 8: return launch_shared8h_m<8>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
+        default:
+            ivfr_set_error("half-precision shared scan supports m <= 8; got %d", ix->p.m);
+            return IVFR_ERR_INVALID_ARG;
+    }
 }

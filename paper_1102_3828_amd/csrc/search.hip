@@ -66,7 +66,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     IVFR_REQUIRE((int64_t)kprime * ix->cap_mult < (1ll << 31), "kprime * cap_mult too large");
     IVFR_HIP(hipSetDevice(p.device));
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    ix->st_codes = ix->st_pairs = ix->st_dense = ix->st_streamed = ix->st_shared_codes = ix->st_shared2_codes = 0;
+    ix->st_codes = ix->st_pairs = ix->st_dense = ix->st_streamed = ix->st_shared_codes = ix->st_shared2_codes = ix->st_shared8_codes = 0;
     for (int i = 0; i < IVFR_N_STAGES; ++i) ix->prof_ms[i] = 0;
     ix->prof_scan_launches = 0;
     if (nq == 0) return IVFR_OK;
@@ -79,7 +79,15 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const uint32_t min_cap = (uint32_t)std::max<int64_t>((int64_t)ix->cap_mult * kprime, ix->min_cap);
     const uint32_t full_limit = (uint32_t)std::min<int64_t>((int64_t)ix->full_mult * kprime, 1ll << 30);
     const uint32_t stride_k = (uint32_t)std::max(1, kprime / IVFR_SAMPLE_MU);
-    const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 16;
+    // Workgroups per scan launch: every group takes an equal share of the launch's 512-entry blocks.  About
+    // 128 blocks per group (64 for the narrower kernels) balances the tail against the per-group set-up.
+    auto pick_groups = [&](double entries, int blocks_per_group) -> int {
+        if (ix->scan_groups > 0) return ix->scan_groups;
+        double g = entries / (double)IVFR_BLOCK / blocks_per_group;
+        const double lo = ix->n_cu * 8.0, hi = 32768.0;
+        return (int)(g < lo ? lo : (g > hi ? hi : g));
+    };
+    const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 8;   // sample pass, dense fallback
 
     // carve the workspace
     Carver cv;
@@ -110,19 +118,21 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_sref = cv.take<float>((size_t)B * kprime);
     const size_t o_sids = cv.take<int32_t>((size_t)B * kprime);
     const size_t o_dpre = cv.take<uint32_t>((size_t)w + 1);
-    const size_t o_gnp = cv.take<uint32_t>(c);
-    const size_t o_gg4 = cv.take<uint32_t>(c);
-    const size_t o_gg2 = cv.take<uint32_t>(c);
-    const size_t o_glo = cv.take<uint32_t>(c);
-    const size_t o_gcur = cv.take<uint32_t>(c);
+    const size_t o_lscale = cv.take<float>(P);
+    const size_t o_gnp = cv.take<uint32_t>(2 * (size_t)c);
+    const size_t o_gpre = cv.take<uint32_t>(4 * (size_t)c);
+    const size_t o_gcur = cv.take<uint32_t>(2 * (size_t)c);
     const size_t o_gcounts = cv.take<uint32_t>(4);
-    const size_t o_gu4 = cv.take<uint32_t>((size_t)P + 4 * (size_t)c + 4);
+    // units of eight: at most P/8 + c (one more per list for a remainder of 5..7); units of four likewise
+    const size_t n_u8 = ((size_t)P / 8 + c + 1) * 8, n_u4 = ((size_t)P / 4 + c + 1) * 4;
+    const size_t o_gu8 = cv.take<uint32_t>(n_u8 + n_u4);
     const size_t o_gu2 = cv.take<uint32_t>(2 * (size_t)c + 4);
     const size_t o_glop = cv.take<uint32_t>((size_t)c + 4);
+    const size_t o_gblk8 = cv.take<uint32_t>((size_t)P / 8 + c + 2);
     const size_t o_gblk4 = cv.take<uint32_t>((size_t)P / 4 + c + 2);
     const size_t o_gblk2 = cv.take<uint32_t>((size_t)c + 2);
     const size_t o_gblklo = cv.take<uint32_t>((size_t)c + 2);
-    const size_t o_gwork = cv.take<unsigned long long>(4);
+    const size_t o_gwork = cv.take<unsigned long long>(6);
     IVFR_TRY(ix->search_ws.reserve(cv.off + 256));
     char* ws = ix->search_ws.as<char>();
     float* xnorm = reinterpret_cast<float*>(ws + o_xnorm);
@@ -156,21 +166,24 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     float* sref = reinterpret_cast<float*>(ws + o_sref);
     int32_t* sids = reinterpret_cast<int32_t*>(ws + o_sids);
     uint32_t* dpre = reinterpret_cast<uint32_t*>(ws + o_dpre);
+    float* lut_scale = reinterpret_cast<float*>(ws + o_lscale);
     GroupBuffers gb;
     gb.list_np = reinterpret_cast<uint32_t*>(ws + o_gnp);
-    gb.g4 = reinterpret_cast<uint32_t*>(ws + o_gg4);
-    gb.g2 = reinterpret_cast<uint32_t*>(ws + o_gg2);
-    gb.lo = reinterpret_cast<uint32_t*>(ws + o_glo);
+    gb.gpre = reinterpret_cast<uint32_t*>(ws + o_gpre);
     gb.cur = reinterpret_cast<uint32_t*>(ws + o_gcur);
     gb.counts = reinterpret_cast<uint32_t*>(ws + o_gcounts);
-    gb.unit4_pairs = reinterpret_cast<uint32_t*>(ws + o_gu4);
+    gb.unit8_pairs = reinterpret_cast<uint32_t*>(ws + o_gu8);
+    gb.unit4_pairs = gb.unit8_pairs + n_u8;
+    gb.unit_bytes = (n_u8 + n_u4) * sizeof(uint32_t);
     gb.unit2_pairs = reinterpret_cast<uint32_t*>(ws + o_gu2);
     gb.lo_pairs = reinterpret_cast<uint32_t*>(ws + o_glop);
+    gb.blk8 = reinterpret_cast<uint32_t*>(ws + o_gblk8);
     gb.blk4 = reinterpret_cast<uint32_t*>(ws + o_gblk4);
     gb.blk2 = reinterpret_cast<uint32_t*>(ws + o_gblk2);
     gb.blklo = reinterpret_cast<uint32_t*>(ws + o_gblklo);
     gb.work = reinterpret_cast<unsigned long long*>(ws + o_gwork);
-    const bool share = ix->share_lists && ivfr_shared_scan_supported(ix);
+    const bool share = ix->share_lists >= 1 && ivfr_shared_scan_supported(ix);
+    const bool share8 = share && ix->share_lists >= 2 && ivfr_shared8h_supported(ix);
 
     std::vector<EventPair> events;
     auto mark = [&](int kind, bool begin) -> int {
@@ -205,31 +218,38 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         }
         IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, min_cap, IVFR_MAX_SAMPLE, kprime, pb, st));
         if (share) {
-            IVFR_TRY(ivfr_launch_group_plan(probe, Pb, c, pb.len, gb, st));
-            IVFR_HIP(hipMemcpyAsync(ix->h_status + 8, gb.counts, 3 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-            IVFR_HIP(hipMemcpyAsync(ix->h_status + 12, gb.work, 3 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+            IVFR_TRY(ivfr_launch_group_plan(probe, Pb, w, c, pb.fully, share8, pb.len, gb, st));
+            IVFR_HIP(hipMemcpyAsync(ix->h_status + 8, gb.counts, 4 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+            IVFR_HIP(hipMemcpyAsync(ix->h_status + 12, gb.work, 5 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         }
         // the candidate pool is sized by the plan: one small read-back
         IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         IVFR_TRY(mark(IVFR_STAGE_PROBE, false));
         IVFR_TRY(mark(IVFR_STAGE_LUT, true));
-        IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, st));
+        IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, lut_scale, st));
         IVFR_TRY(mark(IVFR_STAGE_LUT, false));
         IVFR_HIP(hipStreamSynchronize(st));
         unsigned long long tot2[2];
         memcpy(tot2, ix->h_status + 2, sizeof(tot2));
         ix->st_codes += (int64_t)tot2[0];
         ix->st_pairs += Pb;
-        int n_unit4 = 0, n_unit2 = 0, n_lo = 0;
+        int n_unit8 = 0, n_unit4 = 0, n_unit2 = 0, n_lo = 0;
+        int g8 = groups, g4 = groups, g2 = groups, g1 = pick_groups((double)tot2[0], 64);
         if (share) {
-            unsigned long long gw[3];
+            unsigned long long gw[5];
             memcpy(gw, ix->h_status + 12, sizeof(gw));
-            n_unit4 = ix->h_status[8];
-            n_unit2 = ix->h_status[9];
-            n_lo = ix->h_status[10];
+            n_unit8 = ix->h_status[8];
+            n_unit4 = ix->h_status[9];
+            n_unit2 = ix->h_status[10];
+            n_lo = ix->h_status[11];
+            g8 = pick_groups((double)gw[1] / 8.0, 128);
+            g4 = pick_groups((double)gw[2] / 4.0, 128);
+            g2 = pick_groups((double)gw[3] / 2.0, 64);
+            g1 = pick_groups((double)gw[4], 64);
             ix->st_streamed += (int64_t)gw[0];
-            ix->st_shared_codes += (int64_t)gw[1];
-            ix->st_shared2_codes += (int64_t)gw[2];
+            ix->st_shared8_codes += (int64_t)gw[1];
+            ix->st_shared_codes += (int64_t)gw[2];
+            ix->st_shared2_codes += (int64_t)gw[3];
         } else {
             ix->st_streamed += (int64_t)tot2[0];
         }
@@ -250,23 +270,27 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
         // scan of every visited entry, keeping estimates <= tau
         if (share) {
-            // lists visited by several queries: four queries per pass over the list; the rest pair by pair
+            // lists visited by several queries: eight, four or two queries per pass over the list; the rest pair by pair
+            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED8, true));
+            IVFR_TRY(ivfr_launch_scan_shared8h(ix, lut, lut_scale, pb.pair_start, pb.len, gb.blk8, gb.unit8_pairs, n_unit8,
+                                               w, tau, cand, cnt, lay, g8, st));
+            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED8, false));
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED, true));
             IVFR_TRY(ivfr_launch_scan_shared(ix, 4, lut, pb.pair_start, pb.len, gb.blk4, gb.unit4_pairs, n_unit4, w,
-                                             tau, cand, cnt, lay, groups, st));
+                                             tau, cand, cnt, lay, g4, st));
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED, false));
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED2, true));
             IVFR_TRY(ivfr_launch_scan_shared(ix, 2, lut, pb.pair_start, pb.len, gb.blk2, gb.unit2_pairs, n_unit2, w,
-                                             tau, cand, cnt, lay, groups, st));
+                                             tau, cand, cnt, lay, g2, st));
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED2, false));
             IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
             IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, gb.blklo, gb.lo_pairs, n_lo, w, tau, cand, cnt,
-                                      lay, groups, st));
+                                      lay, g1, st));
             IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
         } else {
             IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
             IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, pb.blkpre, nullptr, Pb, w, tau, cand, cnt, lay,
-                                      groups, st));
+                                      g1, st));
             IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
         }
         IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, true));
@@ -342,7 +366,8 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, ep.a, ep.b) == hipSuccess) {
             ix->prof_ms[ep.kind] += ms;
-            if (ep.kind == IVFR_STAGE_SCAN || ep.kind == IVFR_STAGE_SCAN_SHARED || ep.kind == IVFR_STAGE_SCAN_SHARED2)
+            if (ep.kind == IVFR_STAGE_SCAN || ep.kind == IVFR_STAGE_SCAN_SHARED || ep.kind == IVFR_STAGE_SCAN_SHARED2 ||
+                ep.kind == IVFR_STAGE_SCAN_SHARED8)
                 ix->prof_scan_launches += 1;
         }
         (void)hipEventDestroy(ep.a);

@@ -101,7 +101,7 @@ def test_other_code_sizes(m, m_refine):
     index, X = wl["index"], wl["X"]
     ix = gpu_index_from_oracle(index)
     xq = queries_dev(X)
-    for share in (True, False):
+    for share in (2, 1, 0):
         ix.set_list_sharing(share)
         for full_mult in (8, 1):
             ix.set_tuning(full_mult=full_mult)
@@ -393,10 +393,10 @@ def test_edge_cases_and_internal_paths():
     # run twice: identical bits
     again = ix.search(xq, 6, 300, 20)
     assert np.array_equal(base_ids, again[0].cpu().numpy()) and np.array_equal(base_dist, again[1].cpu().numpy())
-    # lists shared between queries are scanned four queries at a time by default; pair by pair gives the same bits
+    # lists shared between queries are scanned several queries at a time by default; pair by pair gives the same bits
     st = ix.search_stats()
     assert st["codes_scanned_shared"] > 0 and st["codes_streamed"] < st["codes_scanned"]
-    ix.set_list_sharing(False)
+    ix.set_list_sharing(0)
     pp = ix.search(xq, 6, 300, 20)
     st = ix.search_stats()
     assert st["codes_scanned_shared"] == 0 and st["codes_streamed"] == st["codes_scanned"]
@@ -405,7 +405,7 @@ def test_edge_cases_and_internal_paths():
     pp = ix.search(xq, 6, 300, 20)
     assert np.array_equal(base_ids, pp[0].cpu().numpy()) and np.array_equal(base_dist, pp[1].cpu().numpy())
     ix.set_tuning(full_mult=8)
-    ix.set_list_sharing(True)
+    ix.set_list_sharing(2)
     # batches of 5 queries give the same answer
     ix.set_tuning(batch=5)
     b_ids, b_dist = ix.search(xq, 6, 300, 20)
@@ -439,6 +439,35 @@ def test_edge_cases_and_internal_paths():
     with torch.cuda.stream(s):
         t_ids, _ = ix.search(xq, 6, 300, 20)
     assert np.array_equal(base_ids, t_ids.cpu().numpy())
+    ix.close()
+
+
+def test_list_sharing_modes_give_identical_bits():
+    """Many queries on few lists: units of eight (half-precision tables + exact re-evaluation), of
+    four and of two (fp32 tables) and single pairs must all record the same fp32 estimates, so the
+    three sharing modes return identical bits; the trace is checked against the oracle as well."""
+    wl = tiny_workload(d=64, G=16, N=20000, n_train=3000, n_query=75, c=16, m=8, m_refine=16, iters=4)
+    index, X = wl["index"], wl["X"]
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    ix.set_tuning(full_mult=1)     # sampled bound + filter, as the large workloads run
+    outs = {}
+    for mode in (2, 1, 0):
+        ix.set_list_sharing(mode)
+        ids, dist, t = ix.search(xq, 5, 120, 25, trace=True)
+        st = ix.search_stats()
+        log("sharing mode", mode, st)
+        outs[mode] = (ids.cpu().numpy(), dist.cpu().numpy(),
+                      np.sort(t["short_ids"].cpu().numpy(), axis=1), np.sort(t["short_est"].cpu().numpy(), axis=1))
+        assert st["dense_fallbacks"] == 0
+        assert (st["codes_scanned_shared8"] > 0) == (mode == 2)
+        assert (st["codes_scanned_shared"] > 0) == (mode >= 1)
+        assert (st["codes_streamed"] == st["codes_scanned"]) == (mode == 0)
+    for mode in (1, 0):
+        for a, b in zip(outs[2], outs[mode]):
+            assert np.array_equal(a, b)
+    exact, excused = compare_results(outs[2][0], outs[2][1], X, index, 5, 120, 25)
+    assert excused <= 3
     ix.close()
 
 
