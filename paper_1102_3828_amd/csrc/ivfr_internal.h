@@ -188,6 +188,7 @@ struct PlanBuffers {
     unsigned long long* coff;    // [nq] first record of the query's candidate buffer in the pool
     unsigned long long* sq;      // [nq] entries in the query's visited lists
     uint8_t* fully;              // [nq] 1 = few enough entries to keep them all (no sample, tau = +inf)
+    uint8_t* exact_only;         // [nq] 1 = too large a share of the estimates will pass the bound for fp16 units
     unsigned long long* totals;  // [2]: [0] = sum of sq, [1] = records in the candidate pool
 };
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
@@ -217,7 +218,7 @@ struct GroupBuffers {
     uint32_t* blklo;        // ... over single pairs
     unsigned long long* work;  // [5] list entries streamed; estimates computed by units of eight, four, two, singles
 };
-int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* fully, bool use8,
+int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* exact_only, bool use8,
                            const uint32_t* pair_len, const GroupBuffers& gb, hipStream_t st);
 bool ivfr_shared_scan_supported(const ivfr_index* ix);
 bool ivfr_shared8h_supported(const ivfr_index* ix);

@@ -47,12 +47,15 @@ __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int
     // buffer: everything (no filter), or the largest of the sample, min_cap and twice the survivors
     // expected from the bound (rank r of the sample, one sampled entry standing for `stride`)
     unsigned long long capv = total;
+    bool exact_only = true;   // the half-precision units of eight pay off only when very few estimates pass the bound
     if (!fully) {
         const double mu = (double)kprime / (double)stride;
         const double expect = (mu + 5.0 * sqrt(mu) + 6.0) * (double)stride;
         capv = sampled > min_cap ? sampled : (unsigned long long)min_cap;
         if ((double)capv < 2.0 * expect) capv = (unsigned long long)(2.0 * expect);
+        exact_only = expect > 0.002 * (double)total;
     }
+    pb.exact_only[q] = exact_only ? 1 : 0;
     if (capv > 0xFFFFFFF0ull) capv = 0xFFFFFFF0ull;
     pb.capq[q] = (uint32_t)capv;
     atomicAdd(pb.totals, total);
@@ -433,13 +436,13 @@ int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pai
 // ------------------------------------------------------------------------------------------
 #define IVFR_NO_PAIR 0xFFFFFFFFu   // empty slot of a unit
 
-// Pairs of a query that is bounded by a sample ("filtered", class 0) may go into units of eight;
-// pairs of a query that keeps every estimate (class 1) only into the exact fp32 units.
-__global__ void group_count_kernel(const int32_t* __restrict__ probe, int P, int w, const uint8_t* __restrict__ fully,
+// Pairs of a query whose bound lets only a tiny share of its estimates pass (class 0) may go into the
+// half-precision units of eight; pairs of the other queries (class 1) only into the fp32 units.
+__global__ void group_count_kernel(const int32_t* __restrict__ probe, int P, int w, const uint8_t* __restrict__ exact_only,
                                    int use8, uint32_t* __restrict__ list_np) {
     int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= P) return;
-    const int cls = (use8 && !fully[p / w]) ? 0 : 1;
+    const int cls = (use8 && !exact_only[p / w]) ? 0 : 1;
     atomicAdd(&list_np[2 * probe[p] + cls], 1u);
 }
 
@@ -509,7 +512,8 @@ __global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, const uin
     if (tid < 4) counts[tid] = carry[tid];
 }
 
-__global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, int w, const uint8_t* __restrict__ fully,
+__global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, int w,
+                                  const uint8_t* __restrict__ exact_only,
                                   int use8, int c, const uint32_t* __restrict__ list_np,
                                   const uint32_t* __restrict__ gpre, uint32_t* __restrict__ cur,
                                   uint32_t* __restrict__ unit8_pairs, uint32_t* __restrict__ unit4_pairs,
@@ -517,7 +521,7 @@ __global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, int 
     int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= P) return;
     const int l = probe[p];
-    const int cls = (use8 && !fully[p / w]) ? 0 : 1;
+    const int cls = (use8 && !exact_only[p / w]) ? 0 : 1;
     const ListSplit sp = split_units(list_np[2 * l], list_np[2 * l + 1]);
     const uint32_t i = atomicAdd(&cur[2 * l + cls], 1u);
     if (cls == 0 && i < sp.in8) {
@@ -585,14 +589,14 @@ __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* 
     }
 }
 
-int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* fully, bool use8,
+int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* exact_only, bool use8,
                            const uint32_t* pair_len, const GroupBuffers& gb, hipStream_t st) {
     IVFR_HIP(hipMemsetAsync(gb.list_np, 0, 2 * (size_t)c * sizeof(uint32_t), st));
     IVFR_HIP(hipMemsetAsync(gb.unit8_pairs, 0xff, gb.unit_bytes, st));   // unit8 and unit4 arrays are contiguous
-    hipLaunchKernelGGL(group_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, fully, use8 ? 1 : 0,
+    hipLaunchKernelGGL(group_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0,
                        gb.list_np);
     hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, gb.list_np, gb.gpre, gb.cur, gb.counts);
-    hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, fully, use8 ? 1 : 0, c,
+    hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0, c,
                        gb.list_np, gb.gpre, gb.cur, gb.unit8_pairs, gb.unit4_pairs, gb.unit2_pairs, gb.lo_pairs);
     hipLaunchKernelGGL(group_scan_units_kernel, dim3(1), dim3(1024), 0, st, gb.counts, gb, pair_len);
     IVFR_HIP(hipGetLastError());

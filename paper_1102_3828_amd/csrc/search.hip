@@ -103,6 +103,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_nsample = cv.take<uint32_t>(B);
     const size_t o_sq = cv.take<unsigned long long>(B);
     const size_t o_fully = cv.take<uint8_t>(B);
+    const size_t o_exonly = cv.take<uint8_t>(B);
     const size_t o_totals = cv.take<unsigned long long>(2);
     const size_t o_capq = cv.take<uint32_t>(B);
     const size_t o_coff = cv.take<unsigned long long>(B);
@@ -148,6 +149,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     pb.nsample = reinterpret_cast<uint32_t*>(ws + o_nsample);
     pb.sq = reinterpret_cast<unsigned long long*>(ws + o_sq);
     pb.fully = reinterpret_cast<uint8_t*>(ws + o_fully);
+    pb.exact_only = reinterpret_cast<uint8_t*>(ws + o_exonly);
     pb.totals = reinterpret_cast<unsigned long long*>(ws + o_totals);
     pb.capq = reinterpret_cast<uint32_t*>(ws + o_capq);
     pb.coff = reinterpret_cast<unsigned long long*>(ws + o_coff);
@@ -218,7 +220,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         }
         IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, min_cap, IVFR_MAX_SAMPLE, kprime, pb, st));
         if (share) {
-            IVFR_TRY(ivfr_launch_group_plan(probe, Pb, w, c, pb.fully, share8, pb.len, gb, st));
+            IVFR_TRY(ivfr_launch_group_plan(probe, Pb, w, c, pb.exact_only, share8, pb.len, gb, st));
             IVFR_HIP(hipMemcpyAsync(ix->h_status + 8, gb.counts, 4 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
             IVFR_HIP(hipMemcpyAsync(ix->h_status + 12, gb.work, 5 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         }
