@@ -95,7 +95,18 @@ extern "C" int ivfr_create(const ivfr_params* params, ivfr_index** out) {
         hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ix->h_status), 64 * sizeof(int), hipHostMallocDefault);
         if (e != hipSuccess) { ivfr_set_error("pinned host allocation failed"); r = IVFR_ERR_OOM; }
     }
-    if (r != IVFR_OK) { delete ix; return r; }
+    for (int i = 0; i < 3 && r == IVFR_OK; ++i) {
+        if (hipStreamCreateWithFlags(&ix->side[i], hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&ix->ev_join[i], hipEventDisableTiming) != hipSuccess) {
+            ivfr_set_error("stream / event creation failed");
+            r = IVFR_ERR_HIP;
+        }
+    }
+    if (r == IVFR_OK && hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming) != hipSuccess) {
+        ivfr_set_error("event creation failed");
+        r = IVFR_ERR_HIP;
+    }
+    if (r != IVFR_OK) { ivfr_destroy(ix); return r; }
     *out = ix;
     return IVFR_OK;
 }
@@ -117,6 +128,11 @@ extern "C" int ivfr_destroy(ivfr_index* ix) {
     dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
     ix->search_ws.release(); ix->cand_ws.release(); ix->encode_ws.release(); ix->dense_ws.release();
     if (ix->h_status) (void)hipHostFree(ix->h_status);
+    for (int i = 0; i < 3; ++i) {
+        if (ix->side[i]) (void)hipStreamDestroy(ix->side[i]);
+        if (ix->ev_join[i]) (void)hipEventDestroy(ix->ev_join[i]);
+    }
+    if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
     delete ix;
     return IVFR_OK;
 }

@@ -117,6 +117,8 @@ struct ivfr_index {
     // scratch
     DevBuf search_ws, cand_ws, encode_ws, dense_ws;
     int* h_status = nullptr;         // pinned host word(s) for status read-back
+    hipStream_t side[3] = {nullptr, nullptr, nullptr};   // the small scan launches overlap the large one
+    hipEvent_t ev_fork = nullptr, ev_join[3] = {nullptr, nullptr, nullptr};
 
     // stats of the last search
     int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0, st_shared8_codes = 0;

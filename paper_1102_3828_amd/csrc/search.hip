@@ -188,20 +188,21 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const bool share8 = share && ix->share_lists >= 2 && ivfr_shared8h_supported(ix);
 
     std::vector<EventPair> events;
-    auto mark = [&](int kind, bool begin) -> int {
+    auto mark_on = [&](int kind, bool begin, hipStream_t s) -> int {
         if (!ix->profiling) return IVFR_OK;
         if (begin) {
             EventPair ep;
             ep.kind = kind;
             IVFR_HIP(hipEventCreate(&ep.a));
             IVFR_HIP(hipEventCreate(&ep.b));
-            IVFR_HIP(hipEventRecord(ep.a, st));
+            IVFR_HIP(hipEventRecord(ep.a, s));
             events.push_back(ep);
         } else {
-            IVFR_HIP(hipEventRecord(events.back().b, st));
+            IVFR_HIP(hipEventRecord(events.back().b, s));
         }
         return IVFR_OK;
     };
+    auto mark = [&](int kind, bool begin) -> int { return mark_on(kind, begin, st); };
 
     for (int64_t q0 = 0; q0 < nq; q0 += B) {
         const int nb = (int)std::min<int64_t>(B, nq - q0);
@@ -272,23 +273,31 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
         // scan of every visited entry, keeping estimates <= tau
         if (share) {
-            // lists visited by several queries: eight, four or two queries per pass over the list; the rest pair by pair
+            // lists visited by several queries: eight, four or two queries per pass over the list; the rest pair
+            // by pair.  The four launches are independent (they append to the same buffers through atomics), so
+            // the three small ones go to side streams and fill the large one's tail.
+            IVFR_HIP(hipEventRecord(ix->ev_fork, st));
+            for (int i = 0; i < 3; ++i) IVFR_HIP(hipStreamWaitEvent(ix->side[i], ix->ev_fork, 0));
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED8, true));
             IVFR_TRY(ivfr_launch_scan_shared8h(ix, lut, lut_scale, pb.pair_start, pb.len, gb.blk8, gb.unit8_pairs, n_unit8,
                                                w, tau, cand, cnt, lay, g8, st));
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED8, false));
-            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED, true));
+            IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED, true, ix->side[0]));
             IVFR_TRY(ivfr_launch_scan_shared(ix, 4, lut, pb.pair_start, pb.len, gb.blk4, gb.unit4_pairs, n_unit4, w,
-                                             tau, cand, cnt, lay, g4, st));
-            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED, false));
-            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED2, true));
+                                             tau, cand, cnt, lay, g4, ix->side[0]));
+            IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED, false, ix->side[0]));
+            IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED2, true, ix->side[1]));
             IVFR_TRY(ivfr_launch_scan_shared(ix, 2, lut, pb.pair_start, pb.len, gb.blk2, gb.unit2_pairs, n_unit2, w,
-                                             tau, cand, cnt, lay, g2, st));
-            IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED2, false));
-            IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
+                                             tau, cand, cnt, lay, g2, ix->side[1]));
+            IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED2, false, ix->side[1]));
+            IVFR_TRY(mark_on(IVFR_STAGE_SCAN, true, ix->side[2]));
             IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, gb.blklo, gb.lo_pairs, n_lo, w, tau, cand, cnt,
-                                      lay, g1, st));
-            IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
+                                      lay, g1, ix->side[2]));
+            IVFR_TRY(mark_on(IVFR_STAGE_SCAN, false, ix->side[2]));
+            for (int i = 0; i < 3; ++i) {
+                IVFR_HIP(hipEventRecord(ix->ev_join[i], ix->side[i]));
+                IVFR_HIP(hipStreamWaitEvent(st, ix->ev_join[i], 0));
+            }
         } else {
             IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
             IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, pb.blkpre, nullptr, Pb, w, tau, cand, cnt, lay,
