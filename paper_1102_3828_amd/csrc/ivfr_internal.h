@@ -194,8 +194,8 @@ struct PlanBuffers {
     unsigned long long* totals;  // [2]: [0] = sum of sq, [1] = records in the candidate pool
 };
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
-                     uint32_t stride_k, uint32_t min_cap, uint32_t max_sample, int kprime, const PlanBuffers& pb,
-                     hipStream_t st);
+                     uint32_t stride_k, uint32_t min_cap, uint32_t max_sample, int kprime, float half_frac,
+                     const PlanBuffers& pb, hipStream_t st);
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
                     float* lut, float* lut_scale, hipStream_t st);
 // unit_pairs == nullptr: unit u of the launch is pair u; otherwise pair unit_pairs[u]

@@ -19,7 +19,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int w,
                                   const uint32_t* __restrict__ list_start, const uint32_t* __restrict__ list_len,
                                   uint32_t full_limit, uint32_t stride_k, uint32_t min_cap, uint32_t max_sample,
-                                  int kprime, PlanBuffers pb) {
+                                  int kprime, float half_frac, PlanBuffers pb) {
     int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nq) return;
     unsigned long long total = 0;
@@ -53,7 +53,7 @@ __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int
         const double expect = (mu + 5.0 * sqrt(mu) + 6.0) * (double)stride;
         capv = sampled > min_cap ? sampled : (unsigned long long)min_cap;
         if ((double)capv < 2.0 * expect) capv = (unsigned long long)(2.0 * expect);
-        exact_only = expect > 0.002 * (double)total;
+        exact_only = expect > (double)half_frac * (double)total;
     }
     pb.exact_only[q] = exact_only ? 1 : 0;
     if (capv > 0xFFFFFFF0ull) capv = 0xFFFFFFF0ull;
@@ -124,11 +124,11 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int P, PlanBuff
 }
 
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
-                     uint32_t stride_k, uint32_t min_cap, uint32_t max_sample, int kprime, const PlanBuffers& pb,
-                     hipStream_t st) {
+                     uint32_t stride_k, uint32_t min_cap, uint32_t max_sample, int kprime, float half_frac,
+                     const PlanBuffers& pb, hipStream_t st) {
     IVFR_HIP(hipMemsetAsync(pb.totals, 0, 2 * sizeof(unsigned long long), st));
     hipLaunchKernelGGL(plan_pairs_kernel, dim3((nq + 127) / 128), dim3(128), 0, st, probe, nq, w, ix->list_start,
-                       ix->list_len, full_limit, stride_k, min_cap, max_sample, kprime, pb);
+                       ix->list_len, full_limit, stride_k, min_cap, max_sample, kprime, half_frac, pb);
     IVFR_HIP(hipGetLastError());
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, nq, nq * w, pb);
     IVFR_HIP(hipGetLastError());

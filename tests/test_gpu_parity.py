@@ -230,7 +230,7 @@ def test_config0_end_to_end_gpu_built_index():
 
 
 def _full_size_case(name, n_check, **override):
-    """A benchmark workload at its full size, in the launch configuration the benchmark times
+    """One of the five benchmark workloads at its full size, in the launch configuration the benchmark times
     (index built on the GPU from the HIP generator, first batch of 1000 queries searched in one
     call); n_check of those queries are verified one by one against the oracle on the exported index."""
     import dataclasses
