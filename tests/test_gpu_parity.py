@@ -482,6 +482,23 @@ def test_list_sharing_modes_give_identical_bits():
     ix.close()
 
 
+def test_papers_own_shortlist_setting():
+    """Section 4.3 runs k = 10000 with k' = 20000 (k'/k = 2): the largest result lists the library sorts."""
+    wl = tiny_workload(d=32, G=16, N=60000, n_train=2000, n_query=3, c=8, m=4, m_refine=8, iters=4)
+    index, X = wl["index"], wl["X"]
+    ix = gpu_index_from_oracle(index)
+    for full_mult in (8, 1):
+        ix.set_tuning(full_mult=full_mult)
+        ids, dist = ix.search(queries_dev(X), 6, 20000, 10000)
+        exact, excused = compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, index, 6, 20000, 10000)
+        log("k = 10000, k' = 20000: exact", exact, "excused", excused)
+        assert excused <= 20
+    import paper_1102_3828_amd as pkg
+    with pytest.raises(pkg.IvfrError):
+        ix.search(queries_dev(X), 6, 40000, 20000)     # beyond the sortable result length
+    ix.close()
+
+
 def test_duplicate_vectors_take_the_exact_redo():
     """Degenerate input: a database of a few vectors repeated a thousand times.  Estimates tie in
     huge groups, so the entries at or below the sampled bound overflow the candidate buffer and the
