@@ -25,9 +25,11 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 # of known size (profiles/search_cfg4_hbm_traffic.txt), stored as a ratio to the algorithmic bytes of the
 # launch (m bytes per (query, entry) estimate); other workloads: null.
 #   per-pair scan (--per-pair):  101.10 GB read + 0.15 GB written for 101.14 GB of code bytes
-#   shared scan of four:          24.89 GB read + 0.16 GB written for  96.14 GB (one read serves four queries)
+#   fp32 units of four (--sharing 1): 24.89 GB read + 0.16 GB written for 96.14 GB (one read serves four queries)
+#   fp16 units of eight (default):    15.38 GB read + 0.15 GB written for 92.97 GB (one read serves eight queries)
 MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 101.252 / 101.141,
-                          ("cfg4", "adc_scan_shared_kernel"): 25.051 / 96.142}
+                          ("cfg4", "adc_scan_shared_kernel"): 25.051 / 96.142,
+                          ("cfg4", "adc_scan_shared8h_kernel"): 15.526 / 92.966}
 LDS_PEAK_GBS = 256 * 128 * 2.4    # 256 CUs x 128 B/clk x 2.4 GHz
 
 
@@ -119,6 +121,8 @@ def main():
     ap.add_argument("--N", type=int, default=0, help="override the database size (debugging)")
     ap.add_argument("--kprime", type=int, default=0)
     ap.add_argument("--m-refine", type=int, default=-1)
+    ap.add_argument("--c", type=int, default=0, help="override the number of coarse centroids (1 = exhaustive ADC+R)")
+    ap.add_argument("--w", type=int, default=0, help="override the number of lists visited")
     ap.add_argument("--train-iters", type=int, default=10)
     ap.add_argument("--gt-queries", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -151,6 +155,10 @@ def main():
         cfg = dataclasses.replace(cfg, kprime=args.kprime)
     if args.m_refine >= 0:
         cfg = dataclasses.replace(cfg, m_refine=args.m_refine)
+    if args.c:
+        cfg = dataclasses.replace(cfg, c=args.c)
+    if args.w:
+        cfg = dataclasses.replace(cfg, w=args.w)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dm = DeviceMixture(cfg.mixture(), "cuda:0")
@@ -241,7 +249,7 @@ def main():
     lds_b = 2.0 if kname == "adc_scan_shared8h_kernel" else 4.0
     achieved = code_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
     traffic_key = (cfg.name, kname)
-    plain = not (args.N or args.kprime or args.m_refine >= 0)
+    plain = not (args.N or args.kprime or args.m_refine >= 0 or args.c or args.w)
     out = {
         "metric": "queries/s", "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
