@@ -199,6 +199,7 @@ def main():
     codes_shared8 = 0
     codes_streamed = 0
     dense_total = 0
+    retries_total = 0
     stage_ms = {}
     scan_launches = 0
     t0 = time.perf_counter()
@@ -215,6 +216,7 @@ def main():
         for name, ms in pr.items():
             stage_ms[name] = stage_ms.get(name, 0.0) + ms
         dense_total += st["dense_fallbacks"]
+        retries_total += st["bound_retries"]
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ix.set_profiling(False)
@@ -266,6 +268,7 @@ def main():
         "codes_scanned_shared8_per_step": codes_shared8 / steps,
         "stage_ms_per_step": {name: ms / args.steps for name, ms in stage_ms.items()},
         "dense_fallbacks_total": dense_total,
+        "bound_retries_total": retries_total,
         "recall": recall, "recall_queries": n_gt,
         "build_seconds": build_t,
         "roofline": {"bound": "hbm", "kernel": kname, "achieved": achieved,

@@ -106,14 +106,17 @@ int ivfr_search_trace(ivfr_index* index, const float* queries, int64_t nq, int32
  *   codes_scanned        (query, entry) estimates computed = sum over queries of the visited lists'
  *                        lengths (the "v/c of the database" of section 3.3)
  *   pairs                (query, list) pairs
- *   dense_fallbacks      queries redone exactly because the sampled bound failed its check
+ *   dense_fallbacks      queries redone without any filter (a buffer for every visited entry): the
+ *                        sampled bound kept fewer than k' entries, or ties made tightening it useless
+ *   bound_retries        rescans of one query with a tightened bound after its survivors overflowed
+ *                        the candidate buffer
  *   codes_streamed       list entries read from memory by the scan (< codes_scanned when lists are
  *                        shared between queries)
  *   codes_scanned_shared / _shared2 / _shared8  parts of codes_scanned computed by the shared-list
  *                        scans of four, two and eight queries per pass                              */
 int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
                       int64_t* codes_streamed, int64_t* codes_scanned_shared, int64_t* codes_scanned_shared2,
-                      int64_t* codes_scanned_shared8);
+                      int64_t* codes_scanned_shared8, int64_t* bound_retries);
 
 /* List sharing.  Queries of one internal batch that visit the same list are scanned together: the
  * list's codes are read once and each code byte fetches all the queries' table entries with one
@@ -129,8 +132,9 @@ int ivfr_set_list_sharing(ivfr_index* index, int32_t mode);
  *                      larger one first scores a sample of its entries (the first 4/k' of every
  *                      visited list) to bound the k'-th smallest estimate, and the scan keeps only
  *                      estimates below the bound
- *   cap_mult    (16)   such a query's candidate buffer holds max(cap_mult*k', min_cap) records,
- *   min_cap     (8192) or its sample if that is larger; overflowing it triggers an exact redo
+ *   cap_mult    (16)   such a query's candidate buffer holds max(cap_mult*k', min_cap) records, or its
+ *   min_cap     (8192) sample, or the survivors expected from the bound plus six deviations, whichever
+ *                      is largest; overflowing it triggers a rescan of that query with a tighter bound
  *   batch       (1024) queries processed per internal batch
  *   scan_groups (0 = chosen from the amount of work) workgroups launched by the list-scan kernels          */
 int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int32_t min_cap, int32_t batch,

@@ -49,7 +49,7 @@ def _load():
         "ivfr_import": (ctypes.c_int, [vp, i64, vp, vp, vp, vp]),
         "ivfr_search": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp]),
         "ivfr_search_trace": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
-        "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 7),
+        "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 8),
         "ivfr_set_list_sharing": (ctypes.c_int, [vp, i32]),
         "ivfr_set_tuning": (ctypes.c_int, [vp, i32, i32, i32, i32, i32]),
         "ivfr_set_profiling": (ctypes.c_int, [vp, i32]),
@@ -194,10 +194,10 @@ class Index:
         return ids, dist, t
 
     def search_stats(self):
-        v = [ctypes.c_int64() for _ in range(7)]
+        v = [ctypes.c_int64() for _ in range(8)]
         _check(lib.ivfr_search_stats(self._h, *[ctypes.byref(x) for x in v]))
         names = ("codes_scanned", "pairs", "dense_fallbacks", "codes_streamed", "codes_scanned_shared",
-                 "codes_scanned_shared2", "codes_scanned_shared8")
+                 "codes_scanned_shared2", "codes_scanned_shared8", "bound_retries")
         return dict(zip(names, [x.value for x in v]))
 
     def set_list_sharing(self, mode=2):

@@ -513,7 +513,8 @@ extern "C" int ivfr_stage_times(const ivfr_index* ix, double* ms, int32_t* scan_
 
 extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
                                  int64_t* codes_streamed, int64_t* codes_scanned_shared,
-                                 int64_t* codes_scanned_shared2, int64_t* codes_scanned_shared8) {
+                                 int64_t* codes_scanned_shared2, int64_t* codes_scanned_shared8,
+                                 int64_t* bound_retries) {
     IVFR_REQUIRE(ix, "ivfr_search_stats: null index");
     if (codes_scanned) *codes_scanned = ix->st_codes;
     if (pairs) *pairs = ix->st_pairs;
@@ -522,6 +523,7 @@ extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, i
     if (codes_scanned_shared) *codes_scanned_shared = ix->st_shared_codes;
     if (codes_scanned_shared2) *codes_scanned_shared2 = ix->st_shared2_codes;
     if (codes_scanned_shared8) *codes_scanned_shared8 = ix->st_shared8_codes;
+    if (bound_retries) *bound_retries = ix->st_retries;
     return IVFR_OK;
 }
 

@@ -121,7 +121,7 @@ struct ivfr_index {
     hipEvent_t ev_fork = nullptr, ev_join[3] = {nullptr, nullptr, nullptr};
 
     // stats of the last search
-    int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0, st_shared8_codes = 0;
+    int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0, st_shared8_codes = 0, st_retries = 0;
     bool profiling = false;
     double prof_ms[IVFR_N_STAGES] = {0};
     int prof_scan_launches = 0;
@@ -173,9 +173,10 @@ struct SelectArgs {
 // Bound on the k'-th smallest estimate of each query from its uniform sample (a.counts records of the
 // query's sq visited entries): tau = the r-th smallest sampled estimate, r = mu + 5 sqrt(mu) + 6 with
 // mu = k' * sampled / sq the expected number of the true k' best inside the sample (+inf when the
-// sample holds fewer than r).  skip[seg] != 0 leaves tau alone.
-int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, const uint8_t* skip,
-                           float* tau, hipStream_t st);
+// sample holds fewer than r).  fixed_rank > 0 takes that rank instead.  skip[seg] != 0 leaves tau alone.
+// tau_id (optional) receives the id of the record taken, i.e. the low half of its key.
+int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, int fixed_rank,
+                           const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st);
 int ivfr_select_init();   // one-time function attributes
 
 // Search plan, look-up tables, sample and list scan (scan.hip)
@@ -198,10 +199,12 @@ int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, 
                      const PlanBuffers& pb, hipStream_t st);
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
                     float* lut, float* lut_scale, hipStream_t st);
-// unit_pairs == nullptr: unit u of the launch is pair u; otherwise pair unit_pairs[u]
+// unit_pairs == nullptr: unit u of the launch is pair u; otherwise pair unit_pairs[u].  An entry is kept
+// when its estimate is <= tau[q]; with tau_id, when its key (estimate, id) is <= (tau[q], tau_id[q]).
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau, uint2* cand,
-                     uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st);
+                     uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st,
+                     const uint32_t* tau_id = nullptr);
 
 // Shared scan: pairs of one batch grouped by list into units of eight, four, two and single pairs
 struct GroupBuffers {

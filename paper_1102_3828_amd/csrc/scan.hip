@@ -44,15 +44,18 @@ __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int
     pb.sq[q] = total;
     pb.nsample[q] = (uint32_t)(sampled > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : sampled);
     pb.fully[q] = fully ? 1 : 0;
-    // buffer: everything (no filter), or the largest of the sample, min_cap and twice the survivors
-    // expected from the bound (rank r of the sample, one sampled entry standing for `stride`)
+    // buffer: everything (no filter), or the largest of the sample, min_cap and the survivors expected
+    // from the bound (rank r of the sample, one sampled entry standing for `stride`) plus six deviations
     unsigned long long capv = total;
     bool exact_only = true;   // the half-precision units of eight pay off only when very few estimates pass the bound
     if (!fully) {
         const double mu = (double)kprime / (double)stride;
-        const double expect = (mu + 5.0 * sqrt(mu) + 6.0) * (double)stride;
+        const double rank = mu + 5.0 * sqrt(mu) + 6.0;
+        const double expect = rank * (double)stride;
         capv = sampled > min_cap ? sampled : (unsigned long long)min_cap;
-        if ((double)capv < 2.0 * expect) capv = (unsigned long long)(2.0 * expect);
+        // the number of visited entries below the rank-th sampled one scatters by ~1/sqrt(rank): six deviations
+        const double roomy = expect * (1.0 + 6.0 / sqrt(rank));
+        if ((double)capv < roomy) capv = (unsigned long long)roomy;
         exact_only = expect > (double)half_frac * (double)total;
     }
     pb.exact_only[q] = exact_only ? 1 : 0;
@@ -314,7 +317,9 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                                                        const uint32_t* __restrict__ blkpre,
                                                        const uint32_t* __restrict__ unit_pairs, int P, int w,
                                                        const float* __restrict__ tau, uint2* __restrict__ cand,
-                                                       uint32_t* __restrict__ cand_cnt, CandLayout lay) {
+                                                       uint32_t* __restrict__ cand_cnt, CandLayout lay,
+                                                       const uint32_t* __restrict__ tau_id,
+                                                       const int32_t* __restrict__ ids) {
     extern __shared__ float s_lut[];   // M * 256 floats
     const uint32_t total = blkpre[P];
     const uint32_t G = gridDim.x, g = blockIdx.x;
@@ -337,6 +342,8 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
         const int q = (int)(pid / w);
         const uint32_t start = pair_start[pid], len = pair_len[pid];
         const float t = tau[q];
+        // with tau_id the bound is the 64-bit key (estimate, id): an estimate equal to tau passes only up to that id
+        const uint32_t t_id = tau_id ? tau_id[q] : 0xFFFFFFFFu;
         uint2* qc = cand + lay.base(q);
         const uint32_t cap = lay.cap(q);
         uint32_t* cnt = cand_cnt + q;
@@ -375,8 +382,12 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
             for (int u = 0; u < 2; ++u) {
                 const float est0 = adc_sum<M>(s_lut, wds[u][0]);
                 const float est1 = adc_sum<M>(s_lut, wds[u][1]);
-                append_records(in0[u] && est0 <= t, est0, start + e0[u], in1[u] && est1 <= t, est1, start + e0[u] + 1,
-                               qc, cnt, cap);
+                bool k0 = in0[u] && est0 <= t, k1 = in1[u] && est1 <= t;
+                if (tau_id) {
+                    if (k0 && est0 == t) k0 = (uint32_t)ids[start + e0[u]] <= t_id;
+                    if (k1 && est1 == t) k1 = (uint32_t)ids[start + e0[u] + 1] <= t_id;
+                }
+                append_records(k0, est0, start + e0[u], k1, est1, start + e0[u] + 1, qc, cnt, cap);
             }
         }
         b = stop;
@@ -386,7 +397,8 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
 template <int M>
 static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
                          const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau,
-                         uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
+                         uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st,
+                         const uint32_t* tau_id) {
     size_t lds = (size_t)M * IVFR_KS * sizeof(float);
     static bool attr_done = false;
     if (!attr_done && lds > 48 * 1024) {
@@ -395,19 +407,19 @@ static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t*
         attr_done = true;
     }
     hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start, pair_len,
-                       blkpre, unit_pairs, P, w, tau, cand, cand_cnt, lay);
+                       blkpre, unit_pairs, P, w, tau, cand, cand_cnt, lay, tau_id, ix->ids);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau, uint2* cand,
-                     uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
+                     uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st, const uint32_t* tau_id) {
     if (P <= 0) return IVFR_OK;
 #define IVFR_SCAN_CASE(MM)                                                                                     \
     case MM:                                                                                                   \
         return launch_scan_m<MM>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, P, w, tau, cand, cand_cnt, \
-                                 lay, groups, st)
+                                 lay, groups, st, tau_id)
     switch (ix->p.m) {
         IVFR_SCAN_CASE(4);
         IVFR_SCAN_CASE(8);

@@ -70,7 +70,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     IVFR_REQUIRE((int64_t)kprime * ix->cap_mult < (1ll << 31), "kprime * cap_mult too large");
     IVFR_HIP(hipSetDevice(p.device));
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    ix->st_codes = ix->st_pairs = ix->st_dense = ix->st_streamed = ix->st_shared_codes = ix->st_shared2_codes = ix->st_shared8_codes = 0;
+    ix->st_codes = ix->st_pairs = ix->st_dense = ix->st_streamed = ix->st_shared_codes = ix->st_shared2_codes = ix->st_shared8_codes = ix->st_retries = 0;
     for (int i = 0; i < IVFR_N_STAGES; ++i) ix->prof_ms[i] = 0;
     ix->prof_scan_launches = 0;
     if (nq == 0) return IVFR_OK;
@@ -114,6 +114,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_lut = cv.take<float>((size_t)P * m * IVFR_KS);
     const size_t o_cnt = cv.take<uint32_t>(B);
     const size_t o_tau = cv.take<float>(B);
+    const size_t o_tauid = cv.take<uint32_t>(B);
     const size_t o_spos = cv.take<uint32_t>((size_t)B * kprime);
     const size_t o_sest = cv.take<float>((size_t)B * kprime);
     const size_t o_sn = cv.take<int32_t>(B);
@@ -163,6 +164,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     lay.capq = pb.capq;
     uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + o_cnt);
     float* tau = reinterpret_cast<float*>(ws + o_tau);
+    uint32_t* tau_id = reinterpret_cast<uint32_t*>(ws + o_tauid);
     uint32_t* spos = reinterpret_cast<uint32_t*>(ws + o_spos);
     float* sest = reinterpret_cast<float*>(ws + o_sest);
     int32_t* sn = reinterpret_cast<int32_t*>(ws + o_sn);
@@ -272,7 +274,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         {
             SelectArgs a;
             a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = cnt; a.lay = lay;
-            IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, pb.fully, tau, st));
+            IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, 0, pb.fully, tau, nullptr, st));
         }
         IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
@@ -321,13 +323,50 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_HIP(hipStreamSynchronize(st));
         const int n_over = ix->h_status[0];
         if (n_over > 0) {
-            // dense fallback, one query at a time: a buffer for every visited entry, no filter
+            // queries whose filter failed its check are redone one at a time
             std::vector<int32_t> h_over((size_t)nb);
             std::vector<unsigned long long> h_sq((size_t)nb);
             IVFR_HIP(hipMemcpy(h_over.data(), over, (size_t)nb * sizeof(int32_t), hipMemcpyDeviceToHost));
             IVFR_HIP(hipMemcpy(h_sq.data(), pb.sq, (size_t)nb * sizeof(unsigned long long), hipMemcpyDeviceToHost));
             for (int q = 0; q < nb; ++q) {
                 if (!h_over[(size_t)q]) continue;
+                // the query's w pairs; block prefix computed on the host
+                std::vector<uint32_t> h_len((size_t)w), h_pre((size_t)w + 1, 0u);
+                IVFR_HIP(hipMemcpy(h_len.data(), pb.len + (size_t)q * w, (size_t)w * sizeof(uint32_t), hipMemcpyDeviceToHost));
+                for (int r = 0; r < w; ++r)
+                    h_pre[(size_t)r + 1] = h_pre[(size_t)r] + (h_len[(size_t)r] + IVFR_BLOCK - 1) / IVFR_BLOCK;
+                IVFR_HIP(hipMemcpy(dpre, h_pre.data(), ((size_t)w + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
+                const int gq = pick_groups((double)h_sq[(size_t)q], 64);
+                // Too many survivors: the k'-th smallest key (estimate, id) of the records that were kept (a subset
+                // of the visited entries with at least k' members) is a valid and tighter bound; rescan this query
+                // with it.  The id in the bound lets it cut through any number of equal estimates.
+                uint32_t h_cnt = 0, h_cap = 0;
+                IVFR_HIP(hipMemcpy(&h_cnt, cnt + q, sizeof(uint32_t), hipMemcpyDeviceToHost));
+                IVFR_HIP(hipMemcpy(&h_cap, pb.capq + q, sizeof(uint32_t), hipMemcpyDeviceToHost));
+                CandLayout qlay;
+                qlay.off = pb.coff + q;
+                qlay.capq = pb.capq + q;
+                bool settled = false;
+                for (int tries = 0; tries < 8 && h_cnt > h_cap && h_cap >= (uint32_t)kprime; ++tries) {
+                    ix->st_retries += 1;
+                    SelectArgs a;
+                    a.nseg = 1; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = cnt + q; a.lay = qlay;
+                    IVFR_TRY(ivfr_launch_select_tau(a, pb.sq + q, kprime, kprime, nullptr, tau + q, tau_id + q, st));
+                    IVFR_HIP(hipMemsetAsync(cnt + q, 0, sizeof(uint32_t), st));
+                    IVFR_TRY(ivfr_launch_scan(ix, lut + (size_t)q * w * m * IVFR_KS, pb.pair_start + (size_t)q * w,
+                                              pb.len + (size_t)q * w, dpre, nullptr, w, w, tau + q, cand, cnt + q, qlay,
+                                              gq, st, tau_id + q));
+                    IVFR_TRY(ivfr_launch_select_records(a, q, pb.sq + q, spos, sest, sn, over, nullptr, st));
+                    const uint32_t before = h_cnt;
+                    int32_t still = 0;
+                    IVFR_HIP(hipMemcpyAsync(&h_cnt, cnt + q, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+                    IVFR_HIP(hipMemcpyAsync(&still, over + q, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                    IVFR_HIP(hipStreamSynchronize(st));
+                    if (!still) { settled = true; break; }
+                    if (h_cnt >= before) break;   // no progress
+                }
+                if (settled) continue;
+                // last resort: a buffer for every visited entry, no filter
                 ix->st_dense += 1;
                 const uint64_t sqv = h_sq[(size_t)q];
                 IVFR_REQUIRE(sqv < 0xFFFFFFF0ull, "a query visits more than 2^32 entries");
@@ -338,20 +377,13 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
                 uint2* dcand = reinterpret_cast<uint2*>(ix->dense_ws.as<char>() + 1024);
                 IVFR_HIP(hipMemsetAsync(dcnt, 0, sizeof(uint32_t), st));
                 hipLaunchKernelGGL(fill_f32_kernel, dim3(1), dim3(64), 0, st, dtau, (int64_t)1, INFINITY);
-                // the query's w pairs; block prefix computed on the host
-                std::vector<uint32_t> h_len((size_t)w), h_pre((size_t)w + 1, 0u);
-                IVFR_HIP(hipMemcpy(h_len.data(), pb.len + (size_t)q * w, (size_t)w * sizeof(uint32_t), hipMemcpyDeviceToHost));
-                for (int r = 0; r < w; ++r)
-                    h_pre[(size_t)r + 1] = h_pre[(size_t)r] + (h_len[(size_t)r] + IVFR_BLOCK - 1) / IVFR_BLOCK;
-                IVFR_HIP(hipMemcpy(dpre, h_pre.data(), ((size_t)w + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
                 // pair r of this launch is pair q*w + r of the batch; with w pairs and divisor w the
                 // kernel's query index is 0, so tau / counter / buffer are the dense ones
                 CandLayout dlay;
                 dlay.stride = 0;
                 dlay.ucap = (uint32_t)(sqv + 1);
                 IVFR_TRY(ivfr_launch_scan(ix, lut + (size_t)q * w * m * IVFR_KS, pb.pair_start + (size_t)q * w,
-                                          pb.len + (size_t)q * w, dpre, nullptr, w, w, dtau, dcand, dcnt, dlay, groups,
-                                          st));
+                                          pb.len + (size_t)q * w, dpre, nullptr, w, w, dtau, dcand, dcnt, dlay, gq, st));
                 SelectArgs a;
                 a.nseg = 1; a.K = kprime; a.recs = dcand; a.ids = ix->ids; a.counts = dcnt; a.lay = dlay;
                 IVFR_TRY(ivfr_launch_select_records(a, q, nullptr, spos, sest, sn, nullptr, nullptr, st));

@@ -216,27 +216,35 @@ __device__ __forceinline__ int64_t seg_count(const uint32_t* counts, uint32_t ca
 __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, const int32_t* ids, CandLayout lay,
                                                            const uint32_t* counts,
                                                            const unsigned long long* sq, int kprime,
-                                                           const uint8_t* skip, float* tau) {
+                                                           int fixed_rank, const uint8_t* skip, float* tau,
+                                                           uint32_t* tau_id) {
     const int seg = blockIdx.x;
     if (skip && skip[seg]) return;
     bool over;
     int64_t n = seg_count(counts, lay.cap(seg), seg, &over);
     const double mu = (double)kprime * (double)n / (double)(sq[seg] ? sq[seg] : 1ull);
-    const int64_t r = (int64_t)ceil(mu + 5.0 * sqrt(mu) + 6.0);
+    // fixed_rank > 0: the records are a subset of the visited entries and their fixed_rank-th smallest is wanted
+    const int64_t r = fixed_rank > 0 ? (int64_t)fixed_rank : (int64_t)ceil(mu + 5.0 * sqrt(mu) + 6.0);
     if (n < r || n == 0) {
-        if (threadIdx.x == 0) tau[seg] = INFINITY;
+        if (threadIdx.x == 0) {
+            tau[seg] = INFINITY;
+            if (tau_id) tau_id[seg] = 0xFFFFFFFFu;
+        }
         return;
     }
     SegView s{nullptr, recs, ids, (int64_t)lay.base(seg), n};
     uint64_t pivot = radix_pivot(s, (uint32_t)r);
-    if (threadIdx.x == 0) tau[seg] = __uint_as_float((uint32_t)(pivot >> 32));
+    if (threadIdx.x == 0) {
+        tau[seg] = __uint_as_float((uint32_t)(pivot >> 32));
+        if (tau_id) tau_id[seg] = (uint32_t)pivot;
+    }
 }
 
-int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, const uint8_t* skip,
-                           float* tau, hipStream_t st) {
+int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, int fixed_rank,
+                           const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st) {
     if (a.nseg <= 0) return IVFR_OK;
     hipLaunchKernelGGL(select_tau_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.lay, a.counts, sq,
-                       kprime, skip, tau);
+                       kprime, fixed_rank, skip, tau, tau_id);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }

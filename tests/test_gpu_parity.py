@@ -499,10 +499,10 @@ def test_papers_own_shortlist_setting():
     ix.close()
 
 
-def test_duplicate_vectors_take_the_exact_redo():
+def test_duplicate_vectors_are_cut_by_id():
     """Degenerate input: a database of a few vectors repeated a thousand times.  Estimates tie in
-    huge groups, so the entries at or below the sampled bound overflow the candidate buffer and the
-    query is redone through the buffer that holds everything; ties are then broken by id, exactly."""
+    huge groups, so the entries at or below the sampled bound overflow the candidate buffer; the
+    rescan's bound is a key (estimate, id), which cuts through the ties, lowest ids first."""
     wl = tiny_workload(d=32, G=16, N=3000, n_train=2000, n_query=12, c=8, m=4, m_refine=4, iters=4)
     books, X = wl["books"], wl["X"]
     distinct = wl["Y"][:6]
@@ -515,10 +515,40 @@ def test_duplicate_vectors_take_the_exact_redo():
     ids, dist = ix.search(queries_dev(X), 8, 50, 20)
     st = ix.search_stats()
     log("duplicates", st)
-    assert st["dense_fallbacks"] > 0
+    assert st["bound_retries"] > 0
     o_ids, o_dist, _ = orc.search(X, index, 8, 50, 20)
     assert np.array_equal(ids.cpu().numpy(), o_ids)
     assert np.allclose(dist.cpu().numpy(), o_dist, rtol=REL_TOL)
+    ix.close()
+
+
+@pytest.mark.parametrize("order", ["far_first", "near_first"])
+def test_unrepresentative_sample(order):
+    """One list whose sampled prefix misrepresents it.  Far entries first: the bound drawn from the
+    prefix lets every near entry through, the candidate buffer overflows, and the query is rescanned
+    with the k'-th smallest key of the records that were kept.  The few nearest entries first: the
+    bound falls among them, fewer than k' entries pass, and the query is redone without a filter."""
+    rng = np.random.default_rng(17)
+    d, c, m, mr = 32, 1, 4, 4
+    if order == "far_first":
+        parts = [rng.normal(60, 12, size=(60000, d)), rng.normal(180, 12, size=(60000, d))]
+    else:
+        parts = [rng.normal(180, 4, size=(4000, d)), rng.normal(60, 12, size=(116000, d))]
+    Y = np.clip(np.concatenate(parts), 0, 255).round()
+    T = Y[rng.permutation(len(Y))[:4000]]
+    ic, ip, ir = init_draws(len(T), c, m, mr)
+    books = orc.train(T, c, m, mr, 4, ic, ip, ir)
+    index = orc.build_index(Y, np.arange(len(Y)), books)
+    X = np.concatenate([rng.normal(180, 12, size=(6, d)), rng.normal(60, 12, size=(3, d))]).astype(np.float32)
+    ix = gpu_index_from_oracle(index)
+    ids, dist = ix.search(queries_dev(X), 1, 100, 20)
+    st = ix.search_stats()
+    log("ordered list", order, st)
+    if order == "far_first":
+        assert st["bound_retries"] >= 6 and st["dense_fallbacks"] == 0
+    else:
+        assert st["dense_fallbacks"] >= 6
+    compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, index, 1, 100, 20)
     ix.close()
 
 
