@@ -798,6 +798,51 @@ int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const
 // the search results, are bit-identical to the fp32 kernels' (tested).
 // ------------------------------------------------------------------------------------------
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef short short8 __attribute__((ext_vector_type(8)));
+
+// 16 * (byte B of w): the byte offset of a 16-byte table entry, in one VALU operation (a shift whose
+// operand is selected by sub-dword addressing instead of an extract followed by a shift)
+template <int B>
+__device__ __forceinline__ uint32_t byte_x16(uint32_t w) {
+    uint32_t r;
+    const uint32_t four = 4u;
+    if (B == 0)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(four), "v"(w));
+    else if (B == 1)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(four), "v"(w));
+    else if (B == 2)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(four), "v"(w));
+    else
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(four), "v"(w));
+    return r;
+}
+// 16-byte LDS read at an absolute LDS byte address (the kernel's dynamic LDS starts at address 0 when it
+// has no static LDS, which the launcher checks): the address register is used as it is, and the
+// compile-time part goes into the instruction's offset field.
+typedef __attribute__((address_space(3))) const half8 lds_half8;
+__device__ __forceinline__ half8 lds_h8(uint32_t byte_addr, uint32_t const_off) {
+    return *reinterpret_cast<lds_half8*>((uintptr_t)(byte_addr + const_off));
+}
+
+// Codes of entries e and e+1 of the list that starts at `start` (two M-byte codes = one 16-byte load at
+// M = 8), zeros when the block is not part of the pass or the entry lies beyond the list.
+template <int M>
+__device__ __forceinline__ void load_code_pair(const uint8_t* __restrict__ codes, uint32_t start, uint32_t e, bool live,
+                                               uint32_t len, uint32_t (&w0)[M / 4], uint32_t (&w1)[M / 4]) {
+    if (live && e < len) {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e) * M);
+        if (M == 8) {
+            const uint4 c4 = *reinterpret_cast<const uint4*>(src);
+            w0[0] = c4.x; w0[1] = c4.y; w1[0] = c4.z; w1[1] = c4.w;
+        } else {
+#pragma unroll
+            for (int t2 = 0; t2 < M / 4; ++t2) { w0[t2] = src[t2]; w1[t2] = src[M / 4 + t2]; }
+        }
+    } else {
+#pragma unroll
+        for (int t2 = 0; t2 < M / 4; ++t2) { w0[t2] = 0; w1[t2] = 0; }
+    }
+}
 
 template <int M>
 __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* __restrict__ codes,
@@ -830,7 +875,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
         const uint32_t stop = pb1 < b_end ? pb1 : b_end;
         int64_t pid[8];
         float t[8], ts[8], sc[8];
-        half8 tsh;   // the thresholds in half precision, rounded up
+        half8 tsh;   // the thresholds in half precision, rounded up (bit pattern 0xFFFF for an empty slot)
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
             const uint32_t raw = unit_pairs[(int64_t)u * 8 + x];
@@ -839,8 +884,12 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
             sc[x] = lut_scale[pid[x]];
             t[x] = real ? tau[(int)(pid[x] / w)] : -1.f;
             ts[x] = real ? t[x] * sc[x] * 1.0045f + 4e-3f : -1.f;
-            tsh[x] = (_Float16)(real ? ts[x] * 1.001f + 1e-4f : -1.f);   // 2^-10 > the 2^-11 of the conversion
+            tsh[x] = (_Float16)(real ? ts[x] * 1.001f + 1e-4f : 0.f);   // 2^-10 > the 2^-11 of the conversion
         }
+        short8 tshi = __builtin_bit_cast(short8, tsh);
+#pragma unroll
+        for (int x = 0; x < 8; ++x)
+            if (unit_pairs[(int64_t)u * 8 + x] == IVFR_NO_PAIR) tshi[x] = (short)-1;
         const uint32_t start = pair_start[pid[0]], len = pair_len[pid[0]];
         __syncthreads();
         for (int e = tid; e < M * IVFR_KS; e += 256) {
@@ -859,19 +908,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
                 e0[v] = (bb + v - pb0) * IVFR_BLOCK + 2u * tid;
                 in0[v] = bb + v < stop && e0[v] < len;
                 in1[v] = bb + v < stop && e0[v] + 1 < len;
-                if (in0[v]) {
-                    const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e0[v]) * M);
-                    if (M == 8) {
-                        uint4 c4 = *reinterpret_cast<const uint4*>(src);
-                        wds[v][0][0] = c4.x; wds[v][0][1] = c4.y; wds[v][1][0] = c4.z; wds[v][1][1] = c4.w;
-                    } else {
-#pragma unroll
-                        for (int t2 = 0; t2 < M / 4; ++t2) { wds[v][0][t2] = src[t2]; wds[v][1][t2] = src[M / 4 + t2]; }
-                    }
-                } else {
-#pragma unroll
-                    for (int t2 = 0; t2 < M / 4; ++t2) { wds[v][0][t2] = 0; wds[v][1][t2] = 0; }
-                }
+                load_code_pair<M>(codes, start, e0[v], bb + v < stop, len, wds[v][0], wds[v][1]);
             }
 #pragma unroll
             for (int v = 0; v < 2; ++v) {
@@ -889,9 +926,10 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
                     ha += L[3 * IVFR_KS + (wa >> 24)];
                     hb += L[3 * IVFR_KS + (wb >> 24)];
                 }
-                // fast reject: thresholds minus sums in packed fp16; a negative sign in all eight lanes of
-                // both codes means no query can keep either entry (the sign of an fp16 difference is exact)
-                const half8 da = tsh - ha, db = tsh - hb;
+                // fast reject: sums and thresholds are non-negative, so their fp16 bit patterns order like
+                // 16-bit integers; threshold minus sum in packed int16 is negative in all eight lanes of both
+                // codes when no query can keep either entry (an empty slot's -1 minus a sum is always negative)
+                const short8 da = tshi - __builtin_bit_cast(short8, ha), db = tshi - __builtin_bit_cast(short8, hb);
                 const uint4 ua = __builtin_bit_cast(uint4, da), ub = __builtin_bit_cast(uint4, db);
                 const bool none0 = !in0[v] || ((ua.x & ua.y & ua.z & ua.w & 0x80008000u) == 0x80008000u);
                 const bool none1 = !in1[v] || ((ub.x & ub.y & ub.z & ub.w & 0x80008000u) == 0x80008000u);
@@ -931,9 +969,15 @@ static int launch_shared8h_m(const ivfr_index* ix, const float* lut, const float
                              uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
     size_t lds = (size_t)M * IVFR_KS * 16;
     static bool attr_done = false;
-    if (!attr_done && lds > 48 * 1024) {
-        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    if (!attr_done) {
+        // the kernel addresses its tables by absolute LDS address: they must start at 0 (no static LDS)
+        hipFuncAttributes fa;
+        IVFR_HIP(hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>)));
+        IVFR_REQUIRE(fa.sharedSizeBytes == 0, "half-precision shared scan: unexpected static LDS (%zu bytes)",
+                     (size_t)fa.sharedSizeBytes);
+        if (lds > 48 * 1024)
+            IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_done = true;
     }
     hipLaunchKernelGGL(adc_scan_shared8h_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, lut_scale,
