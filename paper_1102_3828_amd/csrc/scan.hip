@@ -800,30 +800,6 @@ int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef short short8 __attribute__((ext_vector_type(8)));
 
-// 16 * (byte B of w): the byte offset of a 16-byte table entry, in one VALU operation (a shift whose
-// operand is selected by sub-dword addressing instead of an extract followed by a shift)
-template <int B>
-__device__ __forceinline__ uint32_t byte_x16(uint32_t w) {
-    uint32_t r;
-    const uint32_t four = 4u;
-    if (B == 0)
-        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(four), "v"(w));
-    else if (B == 1)
-        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(four), "v"(w));
-    else if (B == 2)
-        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(four), "v"(w));
-    else
-        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(four), "v"(w));
-    return r;
-}
-// 16-byte LDS read at an absolute LDS byte address (the kernel's dynamic LDS starts at address 0 when it
-// has no static LDS, which the launcher checks): the address register is used as it is, and the
-// compile-time part goes into the instruction's offset field.
-typedef __attribute__((address_space(3))) const half8 lds_half8;
-__device__ __forceinline__ half8 lds_h8(uint32_t byte_addr, uint32_t const_off) {
-    return *reinterpret_cast<lds_half8*>((uintptr_t)(byte_addr + const_off));
-}
-
 // Codes of entries e and e+1 of the list that starts at `start` (two M-byte codes = one 16-byte load at
 // M = 8), zeros when the block is not part of the pass or the entry lies beyond the list.
 template <int M>
@@ -969,15 +945,9 @@ static int launch_shared8h_m(const ivfr_index* ix, const float* lut, const float
                              uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
     size_t lds = (size_t)M * IVFR_KS * 16;
     static bool attr_done = false;
-    if (!attr_done) {
-        // the kernel addresses its tables by absolute LDS address: they must start at 0 (no static LDS)
-        hipFuncAttributes fa;
-        IVFR_HIP(hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>)));
-        IVFR_REQUIRE(fa.sharedSizeBytes == 0, "half-precision shared scan: unexpected static LDS (%zu bytes)",
-                     (size_t)fa.sharedSizeBytes);
-        if (lds > 48 * 1024)
-            IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    if (!attr_done && lds > 48 * 1024) {
+        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_done = true;
     }
     hipLaunchKernelGGL(adc_scan_shared8h_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, lut_scale,
