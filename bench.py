@@ -112,6 +112,69 @@ def cpu_baseline(ix, cfg, queries_u8, gpu_ids, budget_s=15.0, max_q=64):
             "ids_identical_to_gpu": same / float(done * cfg.k)}
 
 
+def sweep(args):
+    """Parameter sweeps in the shape of the paper's tables, on the synthetic generator (section 4; the
+    absolute recall values belong to this data, not to BIGANN).  One JSON line per setting on stdout.
+      table1: ADC / ADC+R (no inverted file) and IVFADC / IVFADC+R, m = 8, m' in {0, 8, 16, 32}
+      table2: equal-memory pairs (m, m') without inverted file
+      fig3:   recall@10 against the database size, IVFADC+R, m' in {0, 8, 32}"""
+    import dataclasses
+    import numpy as np
+    import torch
+    import synthdata as sd
+    from synthdata.gpu import DeviceMixture
+
+    base = sd.CONFIGS[args.config]
+    if args.N:
+        base = dataclasses.replace(base, N=args.N)
+    if args.kprime:
+        base = dataclasses.replace(base, kprime=args.kprime)
+    torch.cuda.set_device(0)
+    dm = DeviceMixture(base.mixture(), "cuda:0")
+    if args.sweep == "table1":
+        settings = [dict(c=c, w=w, m_refine=mr) for c, w in ((1, 1), (base.c, base.w)) for mr in (0, 8, 16, 32)]
+    elif args.sweep == "table2":
+        settings = [dict(c=1, w=1, m=m, m_refine=mr)
+                    for m, mr in ((8, 0), (4, 4), (16, 0), (8, 8), (32, 0), (16, 16), (64, 0), (32, 32))]
+    else:
+        settings = [dict(N=n, m_refine=mr) for n in (10 ** 6, 10 ** 7, 10 ** 8, 10 ** 9) if n <= base.N
+                    for mr in (0, 8, 32)]
+    gt_cache = {}
+    for st in settings:
+        cfg = dataclasses.replace(base, **st)
+        n_gt = min(args.gt_queries, cfg.n_query)
+        have = gt_cache.get(cfg.N)
+        ix, xq, _, gt, build_t = build_index(cfg, dm, 0 if have is not None else n_gt, args)
+        if have is None:
+            gt_cache[cfg.N] = gt
+        gt = gt_cache[cfg.N]
+        B = min(cfg.batch, cfg.n_query)
+        batches = [xq[i * B:(i + 1) * B].contiguous() for i in range(max(1, cfg.n_query // B))]
+        ix.search(batches[-1], cfg.w, cfg.kprime, cfg.k)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        retries = dense = 0
+        for s in range(args.steps):
+            ix.search(batches[s % len(batches)], cfg.w, cfg.kprime, cfg.k)
+            stats = ix.search_stats()
+            retries += stats["bound_retries"]
+            dense += stats["dense_fallbacks"]
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        ids, _ = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
+        ids = ids.cpu().numpy()
+        rec = {f"recall@{r}": float((ids[:n_gt, :r] == gt[:n_gt, None]).any(axis=1).mean())
+               for r in (1, 10, 100) if r <= cfg.k}
+        row = {"sweep": args.sweep, "N": cfg.N, "c": cfg.c, "w": cfg.w, "m": cfg.m, "m_refine": cfg.m_refine,
+               "kprime": cfg.kprime, "k": cfg.k, "bytes_per_vector": cfg.m + cfg.m_refine + 4,
+               "ms_per_query": 1e3 * el / (args.steps * B), "queries_per_s": args.steps * B / el,
+               "bound_retries": retries, "dense_fallbacks": dense, **rec, "build_s": build_t["add_s"]}
+        print(json.dumps(row), flush=True)
+        ix.close()
+        del ix
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,6 +196,9 @@ def main():
                     help="list sharing mode: 0 per pair, 1 fp32 units of four/two, 2 also fp16 units of eight")
     ap.add_argument("--sweep-groups", default="",
                     help="comma-separated scan workgroup counts: time a few steps with each (to stderr) before the run")
+    ap.add_argument("--sweep", default="", choices=("", "table1", "table2", "fig3"),
+                    help="run a parameter sweep in the shape of the paper's Table 1, Table 2 or Figure 3 on the "
+                         "synthetic generator (one JSON line per setting) instead of the benchmark")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB) three times, as the "
                          "known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -141,6 +207,10 @@ def main():
         print("bench.py: this build measures one GPU only (the path is not sharded); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.sweep:
+        sweep(args)
+        return
 
     import dataclasses
     import numpy as np

@@ -787,11 +787,11 @@ int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const
 // LDS read bandwidth bounds the shared scan, so the tables of a unit of eight are kept as fp16:
 // one 16-byte LDS read then serves eight queries.  Table x is scaled by s_x (chosen so that no
 // sum of m entries can overflow fp16) and the m entries are added in packed fp16.  All terms
-// are non-negative, so the result H satisfies |H - s_x E| <= (2^-11 (m+1)) s_x E + m 2^-24 for
-// the fp32 estimate E (one rounding per table entry, one per add, subnormal spacing 2^-24).
+// are non-negative, so the result H satisfies H <= s_x E (1 + 2^-11)^m + m 2^-14 for the fp32
+// estimate E (one rounding per table entry, one per add; an entry below the smallest normal
+// 2^-14 may round up to it or be flushed to zero).
 // An entry can only belong to the short-list if E <= tau, hence only if
-//     H <= s_x tau (1 + 4.5e-3) + 4e-3          (m <= 8: 9 * 2^-11 = 4.4e-3; the constant also
-//                                                covers fp16 subnormals flushed to zero),
+//     H <= s_x tau (1 + (m + 1.2) 2^-11) + 4e-3     (1.0045 at m = 8, 1.0084 at m = 16),
 // and exactly those few (a fraction of a percent of the scanned entries) are re-evaluated in
 // fp32 from the query's table in global memory, with the same summation order as everywhere
 // else; only that exact value is compared with tau and recorded.  The records, and therefore
@@ -859,7 +859,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
             pid[x] = real ? (int64_t)raw : (int64_t)unit_pairs[(int64_t)u * 8];
             sc[x] = lut_scale[pid[x]];
             t[x] = real ? tau[(int)(pid[x] / w)] : -1.f;
-            ts[x] = real ? t[x] * sc[x] * 1.0045f + 4e-3f : -1.f;
+            ts[x] = real ? t[x] * sc[x] * (1.f + (M + 1.2f) * 4.8828125e-4f) + 4e-3f : -1.f;
             tsh[x] = (_Float16)(real ? ts[x] * 1.001f + 1e-4f : 0.f);   // 2^-10 > the 2^-11 of the conversion
         }
         short8 tshi = __builtin_bit_cast(short8, tsh);
@@ -956,7 +956,7 @@ static int launch_shared8h_m(const ivfr_index* ix, const float* lut, const float
     return IVFR_OK;
 }
 
-bool ivfr_shared8h_supported(const ivfr_index* ix) { return ix->p.m <= 8; }
+bool ivfr_shared8h_supported(const ivfr_index* ix) { return ix->p.m <= 16; }
 
 int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const float* lut_scale,
                               const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
@@ -966,8 +966,9 @@ int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const floa
     switch (ix->p.m) {
         case 4: return launch_shared8h_m<4>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
         case 8: return launch_shared8h_m<8>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
+        case 16: return launch_shared8h_m<16>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
         default:
-            ivfr_set_error("half-precision shared scan supports m <= 8; got %d", ix->p.m);
+            ivfr_set_error("half-precision shared scan supports m <= 16; got %d", ix->p.m);
             return IVFR_ERR_INVALID_ARG;
     }
 }

@@ -442,11 +442,12 @@ def test_edge_cases_and_internal_paths():
     ix.close()
 
 
-def test_list_sharing_modes_give_identical_bits():
+@pytest.mark.parametrize("m", [8, 16, 4])
+def test_list_sharing_modes_give_identical_bits(m):
     """Many queries on few lists: units of eight (half-precision tables + exact re-evaluation), of
     four and of two (fp32 tables) and single pairs must all record the same fp32 estimates, so the
     three sharing modes return identical bits; the trace is checked against the oracle as well."""
-    wl = tiny_workload(d=64, G=16, N=60000, n_train=3000, n_query=75, c=4, m=8, m_refine=16, iters=4)
+    wl = tiny_workload(d=64, G=16, N=60000, n_train=3000, n_query=75, c=4, m=m, m_refine=16, iters=4)
     index, X = wl["index"], wl["X"]
     ix = gpu_index_from_oracle(index)
     xq = queries_dev(X)
