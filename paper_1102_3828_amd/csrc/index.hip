@@ -124,7 +124,7 @@ extern "C" int ivfr_destroy(ivfr_index* ix) {
     (void)hipDeviceSynchronize();
     free_staged(ix);
     dev_free(ix->coarse); dev_free(ix->coarse_norm); dev_free(ix->pq); dev_free(ix->pq_norm); dev_free(ix->pq_maxnorm); dev_free(ix->rq);
-    dev_free(ix->list_fill); dev_free(ix->list_start); dev_free(ix->list_len);
+    dev_free(ix->list_fill); dev_free(ix->list_start); dev_free(ix->list_len); dev_free(ix->chunk_list);
     dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
     ix->search_ws.release(); ix->cand_ws.release(); ix->encode_ws.release(); ix->dense_ws.release();
     if (ix->h_status) (void)hipHostFree(ix->h_status);
@@ -407,6 +407,23 @@ static int install_layout(ivfr_index* ix, const std::vector<int64_t>& offsets) {
     IVFR_TRY(dev_alloc(&ix->list_len, (size_t)c));
     IVFR_HIP(hipMemcpy(ix->list_start, ix->h_start.data(), ((size_t)c + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
     IVFR_HIP(hipMemcpy(ix->list_len, len.data(), (size_t)c * sizeof(uint32_t), hipMemcpyHostToDevice));
+    // position -> list directory: for every 2^shift slots the last list that starts at or before the
+    // chunk's first slot (about 2^18 chunks); an entry's list is then found between two neighbours
+    int shift = 6;
+    while ((ix->n_slots >> shift) > (1ull << 18)) ++shift;
+    const size_t n_chunks = (size_t)(ix->n_slots >> shift) + 2;
+    std::vector<uint32_t> dir(n_chunks);
+    {
+        int l = 0;
+        for (size_t i = 0; i < n_chunks; ++i) {
+            const uint64_t first = (uint64_t)i << shift;
+            while (l + 1 < c && (uint64_t)ix->h_start[(size_t)l + 1] <= first) ++l;
+            dir[i] = (uint32_t)l;
+        }
+    }
+    ix->chunk_shift = shift;
+    IVFR_TRY(dev_alloc(&ix->chunk_list, n_chunks));
+    IVFR_HIP(hipMemcpy(ix->chunk_list, dir.data(), n_chunks * sizeof(uint32_t), hipMemcpyHostToDevice));
     IVFR_TRY(dev_alloc(&ix->codes, (size_t)ix->n_slots * ix->p.m));
     IVFR_TRY(dev_alloc(&ix->rcodes, (size_t)ix->n_slots * ix->p.m_refine));
     IVFR_TRY(dev_alloc(&ix->ids, (size_t)ix->n_slots));

@@ -103,6 +103,8 @@ struct ivfr_index {
     uint64_t n_slots = 0;            // padded entry count incl. tail pad
     uint32_t* list_start = nullptr;  // [c+1]
     uint32_t* list_len = nullptr;    // [c]
+    uint32_t* chunk_list = nullptr;  // [(n_slots >> chunk_shift) + 2]: last list starting at or before slot i << chunk_shift
+    int chunk_shift = 0;
     uint8_t* codes = nullptr;        // [n_slots, m]
     uint8_t* rcodes = nullptr;       // [n_slots, m']
     int32_t* ids = nullptr;          // [n_slots]

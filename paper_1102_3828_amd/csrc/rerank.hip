@@ -4,10 +4,13 @@
 // an entry costs m + m' + 4 gathered bytes; the codebooks and the coarse centroids are small
 // enough to be served from cache.
 //
-// Eight lanes share one entry, lane t taking dimensions [t d/8, (t+1) d/8); the partial sums
-// are combined with three xor-shuffles.  The entry's list is found by binary search of its
-// position in the list start offsets.  Output per entry: the 64-bit key (distance bits << 32
-// | id) consumed by the final top-k selection.
+// Eight lanes share one entry and interleave its dimensions in 16-byte pieces (lane t takes
+// dimensions 4t..4t+3 of every group of 32), so that one load instruction of the eight lanes
+// covers 128 contiguous bytes of the query and the coarse centroid and whole codebook rows (few
+// cache lines per instruction); the partial sums are combined with three xor-shuffles.  The entry's list is found from its position through a
+// directory (one list index per 2^shift slots) followed by a binary search between two
+// neighbouring directory entries, usually zero to two steps.  Output per entry: the 64-bit key
+// (distance bits << 32 | id) consumed by the final top-k selection.
 #include "ivfr_internal.h"
 
 template <int VEC>
@@ -15,6 +18,7 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
                                                      int dsub, int dsub_r, const float* __restrict__ coarse,
                                                      const float* __restrict__ pq, const float* __restrict__ rq,
                                                      const uint32_t* __restrict__ list_start,
+                                                     const uint32_t* __restrict__ chunk_list, int chunk_shift,
                                                      const uint8_t* __restrict__ codes,
                                                      const uint8_t* __restrict__ rcodes,
                                                      const int32_t* __restrict__ ids, int kprime, int q_base,
@@ -30,7 +34,8 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
     int32_t id = -1;
     if (live) {
         const uint32_t pos = short_pos[(int64_t)q * kprime + slot];
-        int lo = 0, hi = c;   // last list with list_start <= pos
+        // last list with list_start <= pos
+        int lo = (int)chunk_list[pos >> chunk_shift], hi = (int)chunk_list[(pos >> chunk_shift) + 1] + 1;
         while (hi - lo > 1) {
             int mid = (lo + hi) >> 1;
             if (list_start[mid] <= pos) lo = mid; else hi = mid;
@@ -41,9 +46,8 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
         const uint8_t* rcode = rcodes + (uint64_t)pos * mr;
         const float* x = queries + (int64_t)q * d;
         const float* cl = coarse + (int64_t)l * d;
-        const int e0 = t * (d / 8), e1 = e0 + d / 8;
         if (VEC == 4) {
-            for (int e = e0; e < e1; e += 4) {
+            for (int e = 4 * t; e < d; e += 32) {
                 const int j = e / dsub;
                 float4 y = *reinterpret_cast<const float4*>(cl + e);
                 float4 pv = *reinterpret_cast<const float4*>(pq + ((int64_t)j * IVFR_KS + code[j]) * dsub + (e - j * dsub));
@@ -59,7 +63,7 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
                 acc = fmaf(a, a, acc); acc = fmaf(b, b, acc); acc = fmaf(cc, cc, acc); acc = fmaf(dd, dd, acc);
             }
         } else {
-            for (int e = e0; e < e1; ++e) {
+            for (int e = t; e < d; e += 8) {
                 const int j = e / dsub;
                 float y = cl[e] + pq[((int64_t)j * IVFR_KS + code[j]) * dsub + (e - j * dsub)];
                 if (mr > 0) {
@@ -96,8 +100,8 @@ int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, i
     const bool vec = (ix->dsub % 4 == 0) && (ix->p.m_refine == 0 || ix->dsub_r % 4 == 0) && ((ix->p.d / 8) % 4 == 0);
 #define IVFR_RERANK_ARGS                                                                                       \
     queries, ix->p.d, ix->p.c, ix->p.m, ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq,      \
-        ix->list_start, ix->codes, ix->rcodes, ix->ids, kprime, q_base, short_pos, short_n, keys, refined_out, \
-        ids_out
+        ix->list_start, ix->chunk_list, ix->chunk_shift, ix->codes, ix->rcodes, ix->ids, kprime, q_base,       \
+        short_pos, short_n, keys, refined_out, ids_out
     if (vec) hipLaunchKernelGGL(rerank_kernel<4>, grid, dim3(256), 0, st, IVFR_RERANK_ARGS);
     else hipLaunchKernelGGL(rerank_kernel<1>, grid, dim3(256), 0, st, IVFR_RERANK_ARGS);
 #undef IVFR_RERANK_ARGS
