@@ -12,6 +12,7 @@
 #define IVFR_KS 256            // reproduction values per sub-quantizer (8 bits)
 #define IVFR_LIST_ALIGN 32u    // every inverted list starts at a multiple of 32 entries
 #define IVFR_BLOCK 512u        // entries per scan block: one 16-byte load per thread of a 256-thread group
+#define IVFR_SAMPLE_CHUNK 2048u   // entries of a sample prefix scored by one wavefront
 #define IVFR_TAIL_PAD 1024u    // zero entries after the last list so vector loads never run off the end
 
 void ivfr_set_error(const char* fmt, ...);
@@ -187,7 +188,11 @@ struct PlanBuffers {
     uint32_t* len;         // [P] entries of the pair's list
     uint32_t* len_s;       // [P] leading entries of the pair's list that belong to the sample
     uint32_t* blkpre;      // [P+1] exclusive prefix of scan blocks over the pairs
-    uint32_t* blkpre_s;    // [P+1] same for the sample
+    uint32_t* blkpre_s;    // [P+1] exclusive prefix of the sample's chunks (IVFR_SAMPLE_CHUNK entries) over the pairs
+    uint32_t* items_s;     // [blkpre_s[P]] pair of every sample chunk
+    uint32_t* soff;        // [P] first record of the pair's sample inside the query's candidate buffer
+    uint32_t* qblk;        // [nq] scan blocks of the query, then (after the plan's scan) its first block
+    uint32_t* qblk_s;      // [nq] same for the sample
     uint32_t* nsample;     // [nq] sampled entries of the query
     uint32_t* capq;        // [nq] records in the query's candidate buffer
     unsigned long long* coff;    // [nq] first record of the query's candidate buffer in the pool
@@ -207,6 +212,13 @@ int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pai
                      const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau, uint2* cand,
                      uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st,
                      const uint32_t* tau_id = nullptr);
+
+// Sample pass: the estimate of entry e < len_s[p] of pair p is recorded at slot soff[p] + e of the query's
+// buffer (no counters involved).  One wavefront per chunk of IVFR_SAMPLE_CHUNK entries; items[i] is the
+// pair of chunk i, chunk_pre the pairs' chunk prefix.
+int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
+                            const uint32_t* chunk_pre, const uint32_t* items, uint32_t n_items, const uint32_t* soff,
+                            int w, uint2* cand, CandLayout lay, hipStream_t st);
 
 // Shared scan: pairs of one batch grouped by list into units of eight, four, two and single pairs
 struct GroupBuffers {

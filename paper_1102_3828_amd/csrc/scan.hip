@@ -16,14 +16,31 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 //    so a prefix is as good as a random draw, and taking the same fraction of every visited
 //    list keeps the sample stratified over near and far lists.
 // ------------------------------------------------------------------------------------------
-__global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int w,
-                                  const uint32_t* __restrict__ list_start, const uint32_t* __restrict__ list_len,
-                                  uint32_t full_limit, uint32_t stride_k, uint32_t min_cap, uint32_t max_sample,
-                                  int kprime, float half_frac, PlanBuffers pb) {
-    int q = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        uint32_t o = __shfl_up(v, off, 64);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+// One wavefront per query: the lanes take the query's w pairs in turn.  Block counts are prefix-summed
+// inside the query here (blkpre, blkpre_s hold query-relative values, qblk / qblk_s the query totals;
+// blkpre counts scan blocks of IVFR_BLOCK entries, blkpre_s sample chunks of IVFR_SAMPLE_CHUNK entries);
+// plan_scan_kernel turns them into batch-wide prefixes.
+__global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int w,
+                                                         const uint32_t* __restrict__ list_start,
+                                                         const uint32_t* __restrict__ list_len, uint32_t full_limit,
+                                                         uint32_t stride_k, uint32_t min_cap, uint32_t max_sample,
+                                                         int kprime, float half_frac, PlanBuffers pb) {
+    const int lane = threadIdx.x & 63;
+    const int q = blockIdx.x * 4 + (threadIdx.x >> 6);   // uniform over the wavefront
     if (q >= nq) return;
     unsigned long long total = 0;
-    for (int r = 0; r < w; ++r) total += list_len[probe[(int64_t)q * w + r]];
+    for (int r = lane; r < w; r += 64) total += list_len[probe[(int64_t)q * w + r]];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) total += __shfl_xor(total, off, 64);
     const bool fully = total <= full_limit;
     // stride k'/mu, widened when the query visits so much that its sample would exceed max_sample
     unsigned long long stride64 = stride_k < 1 ? 1ull : stride_k;
@@ -31,16 +48,38 @@ __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int
     if (widen > stride64) stride64 = widen;
     const uint32_t stride = (uint32_t)(stride64 > 0xFFFFFFFFull ? 0xFFFFFFFFull : stride64);
     unsigned long long sampled = 0;
-    for (int r = 0; r < w; ++r) {
-        int64_t p = (int64_t)q * w + r;
-        int l = probe[p];
-        uint32_t len = list_len[l];
-        pb.pair_start[p] = list_start[l];
-        pb.len[p] = len;
-        uint32_t ls = fully ? 0u : (len + stride - 1) / stride;
-        pb.len_s[p] = ls;
+    uint32_t carry = 0, carry_s = 0, carry_e = 0;
+    for (int r0 = 0; r0 < w; r0 += 64) {
+        const int r = r0 + lane;
+        uint32_t len = 0, ls = 0;
+        if (r < w) {
+            const int64_t p = (int64_t)q * w + r;
+            const int l = probe[p];
+            len = list_len[l];
+            ls = fully ? 0u : (len + stride - 1) / stride;
+            pb.pair_start[p] = list_start[l];
+            pb.len[p] = len;
+            pb.len_s[p] = ls;
+        }
+        const uint32_t nb = (len + IVFR_BLOCK - 1) / IVFR_BLOCK, nbs = (ls + IVFR_SAMPLE_CHUNK - 1) / IVFR_SAMPLE_CHUNK;
+        const uint32_t inc = wave_incl_scan(nb, lane), inc_s = wave_incl_scan(nbs, lane);
+        const uint32_t inc_e = wave_incl_scan(ls, lane);   // a query's sample stays below 2^32 entries (max_sample + w)
+        if (r < w) {
+            const int64_t p = (int64_t)q * w + r;
+            pb.blkpre[p] = carry + inc - nb;
+            pb.blkpre_s[p] = carry_s + inc_s - nbs;
+            pb.soff[p] = carry_e + inc_e - ls;
+        }
+        carry += __shfl(inc, 63, 64);
+        carry_s += __shfl(inc_s, 63, 64);
+        carry_e += __shfl(inc_e, 63, 64);
         sampled += ls;
     }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sampled += __shfl_xor(sampled, off, 64);
+    if (lane != 0) return;
+    pb.qblk[q] = carry;
+    pb.qblk_s[q] = carry_s;
     pb.sq[q] = total;
     pb.nsample[q] = (uint32_t)(sampled > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : sampled);
     pb.fully[q] = fully ? 1 : 0;
@@ -64,9 +103,9 @@ __global__ void plan_pairs_kernel(const int32_t* __restrict__ probe, int nq, int
     atomicAdd(pb.totals, total);
 }
 
-// Exclusive prefix sums (one workgroup): candidate-buffer offsets over the nq queries, then
-// ceil(len / IVFR_BLOCK) over the P pairs for the scan and for the sample.
-__global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int P, PlanBuffers pb) {
+// One workgroup: exclusive prefix sums over the nq queries (candidate-buffer offsets; scan and sample
+// blocks), then the per-query block offsets are added to the query-relative prefixes of the P pairs.
+__global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int w, PlanBuffers pb) {
     __shared__ uint32_t wtot[2][16];
     __shared__ uint32_t carry[2];
     __shared__ unsigned long long wtot64[16];
@@ -75,65 +114,52 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int P, PlanBuff
     if (tid == 0) { carry[0] = carry[1] = 0; carry64 = 0; }
     __syncthreads();
     for (int base = 0; base < nq; base += 1024) {
-        int q = base + tid;
-        unsigned long long v = q < nq ? (((unsigned long long)pb.capq[q] + 31ull) & ~31ull) : 0ull;
-        unsigned long long inc = v;
+        const int q = base + tid;
+        const unsigned long long v64 = q < nq ? (((unsigned long long)pb.capq[q] + 31ull) & ~31ull) : 0ull;
+        unsigned long long inc64 = v64;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            unsigned long long o = __shfl_up(inc, off, 64);
-            if (lane >= off) inc += o;
+            unsigned long long o = __shfl_up(inc64, off, 64);
+            if (lane >= off) inc64 += o;
         }
-        if (lane == 63) wtot64[wv] = inc;
+        const uint32_t v[2] = {q < nq ? pb.qblk[q] : 0u, q < nq ? pb.qblk_s[q] : 0u};
+        uint32_t inc[2] = {wave_incl_scan(v[0], lane), wave_incl_scan(v[1], lane)};
+        if (lane == 63) { wtot64[wv] = inc64; wtot[0][wv] = inc[0]; wtot[1][wv] = inc[1]; }
         __syncthreads();
-        unsigned long long add = carry64;
-        for (int x = 0; x < wv; ++x) add += wtot64[x];
-        inc += add;
-        if (q < nq) pb.coff[q] = inc - v;
+        unsigned long long add64 = carry64;
+        uint32_t add[2] = {carry[0], carry[1]};
+        for (int x = 0; x < wv; ++x) { add64 += wtot64[x]; add[0] += wtot[0][x]; add[1] += wtot[1][x]; }
+        inc64 += add64; inc[0] += add[0]; inc[1] += add[1];
+        if (q < nq) {
+            pb.coff[q] = inc64 - v64;
+            pb.qblk[q] = inc[0] - v[0];     // now the query's first block in the batch-wide stream
+            pb.qblk_s[q] = inc[1] - v[1];
+        }
         __syncthreads();
-        if (tid == 1023) carry64 = inc;
+        if (tid == 1023) { carry64 = inc64; carry[0] = inc[0]; carry[1] = inc[1]; }
         __syncthreads();
     }
-    if (tid == 0) pb.totals[1] = carry64;
-    for (int base = 0; base < P; base += 1024) {
-        int p = base + tid;
-        uint32_t v[2] = {0, 0};
-        if (p < P) {
-            v[0] = (pb.len[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
-            v[1] = (pb.len_s[p] + IVFR_BLOCK - 1) / IVFR_BLOCK;
-        }
-        uint32_t inc[2] = {v[0], v[1]};
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                uint32_t o = __shfl_up(inc[a], off, 64);
-                if (lane >= off) inc[a] += o;
-            }
-            if (lane == 63) wtot[a][wv] = inc[a];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            uint32_t add = carry[a];
-            for (int x = 0; x < wv; ++x) add += wtot[a][x];
-            inc[a] += add;
-        }
-        if (p < P) { pb.blkpre[p] = inc[0] - v[0]; pb.blkpre_s[p] = inc[1] - v[1]; }
-        __syncthreads();
-        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; }
-        __syncthreads();
+    // the workgroup's own global writes above are visible to all its threads after the barrier
+    const int P = nq * w;
+    for (int p = tid; p < P; p += 1024) {
+        const int q = p / w;
+        pb.blkpre[p] += pb.qblk[q];
+        const uint32_t first = pb.blkpre_s[p] + pb.qblk_s[q];
+        pb.blkpre_s[p] = first;
+        const uint32_t nchunk = (pb.len_s[p] + IVFR_SAMPLE_CHUNK - 1) / IVFR_SAMPLE_CHUNK;
+        for (uint32_t i = 0; i < nchunk; ++i) pb.items_s[first + i] = (uint32_t)p;
     }
-    if (tid == 0) { pb.blkpre[P] = carry[0]; pb.blkpre_s[P] = carry[1]; }
+    if (tid == 0) { pb.totals[1] = carry64; pb.blkpre[P] = carry[0]; pb.blkpre_s[P] = carry[1]; }
 }
 
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
                      uint32_t stride_k, uint32_t min_cap, uint32_t max_sample, int kprime, float half_frac,
                      const PlanBuffers& pb, hipStream_t st) {
     IVFR_HIP(hipMemsetAsync(pb.totals, 0, 2 * sizeof(unsigned long long), st));
-    hipLaunchKernelGGL(plan_pairs_kernel, dim3((nq + 127) / 128), dim3(128), 0, st, probe, nq, w, ix->list_start,
+    hipLaunchKernelGGL(plan_pairs_kernel, dim3((nq + 3) / 4), dim3(256), 0, st, probe, nq, w, ix->list_start,
                        ix->list_len, full_limit, stride_k, min_cap, max_sample, kprime, half_frac, pb);
     IVFR_HIP(hipGetLastError());
-    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, nq, nq * w, pb);
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, nq, w, pb);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -546,58 +572,51 @@ __global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, int 
     else lo_pairs[gpre[3 * (int64_t)c + l]] = (uint32_t)p;
 }
 
-// block prefixes over the four kinds of unit; work totals; one workgroup
+// block prefixes over the units of one kind and its work total; one workgroup per kind (blockIdx.x:
+// 0 = units of eight, 1 = of four, 2 = of two, 3 = single pairs); work[0] must be zero on entry
 __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* __restrict__ counts, GroupBuffers gb,
                                                                 const uint32_t* __restrict__ pair_len) {
     __shared__ uint32_t wtot[16];
     __shared__ uint32_t carry;
-    __shared__ unsigned long long s_read, s_est[4];
+    __shared__ unsigned long long s_read, s_est;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid == 0) { s_read = 0; s_est[0] = s_est[1] = s_est[2] = s_est[3] = 0; }
-    for (int which = 0; which < 4; ++which) {
-        const int n = (int)counts[which];
-        const uint32_t* ids = which == 0 ? gb.unit8_pairs : (which == 1 ? gb.unit4_pairs : (which == 2 ? gb.unit2_pairs : gb.lo_pairs));
-        uint32_t* out = which == 0 ? gb.blk8 : (which == 1 ? gb.blk4 : (which == 2 ? gb.blk2 : gb.blklo));
-        const int step = which == 0 ? 8 : (which == 1 ? 4 : (which == 2 ? 2 : 1));
-        if (tid == 0) carry = 0;
-        __syncthreads();
-        unsigned long long my_read = 0, my_est = 0;
-        for (int base = 0; base < n; base += 1024) {
-            int u = base + tid;
-            uint32_t len = 0;
-            if (u < n) {
-                len = pair_len[ids[(int64_t)u * step]];
-                uint32_t members = 0;
-                for (int x = 0; x < step; ++x) members += ids[(int64_t)u * step + x] != IVFR_NO_PAIR ? 1u : 0u;
-                my_read += len;
-                my_est += (unsigned long long)len * members;
-            }
-            uint32_t v = (len + IVFR_BLOCK - 1) / IVFR_BLOCK;
-            uint32_t inc = v;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                uint32_t o = __shfl_up(inc, off, 64);
-                if (lane >= off) inc += o;
-            }
-            if (lane == 63) wtot[wv] = inc;
-            __syncthreads();
-            uint32_t add = carry;
-            for (int x = 0; x < wv; ++x) add += wtot[x];
-            inc += add;
-            if (u < n) out[u] = inc - v;
-            __syncthreads();
-            if (tid == 1023) carry = inc;
-            __syncthreads();
+    const int which = blockIdx.x;
+    const int n = (int)counts[which];
+    const uint32_t* ids = which == 0 ? gb.unit8_pairs : (which == 1 ? gb.unit4_pairs : (which == 2 ? gb.unit2_pairs : gb.lo_pairs));
+    uint32_t* out = which == 0 ? gb.blk8 : (which == 1 ? gb.blk4 : (which == 2 ? gb.blk2 : gb.blklo));
+    const int step = which == 0 ? 8 : (which == 1 ? 4 : (which == 2 ? 2 : 1));
+    if (tid == 0) { s_read = 0; s_est = 0; carry = 0; }
+    __syncthreads();
+    unsigned long long my_read = 0, my_est = 0;
+    for (int base = 0; base < n; base += 1024) {
+        int u = base + tid;
+        uint32_t len = 0;
+        if (u < n) {
+            len = pair_len[ids[(int64_t)u * step]];
+            uint32_t members = 0;
+            for (int x = 0; x < step; ++x) members += ids[(int64_t)u * step + x] != IVFR_NO_PAIR ? 1u : 0u;
+            my_read += len;
+            my_est += (unsigned long long)len * members;
         }
-        atomicAdd(&s_read, my_read);
-        atomicAdd(&s_est[which], my_est);
+        const uint32_t v = (len + IVFR_BLOCK - 1) / IVFR_BLOCK;
+        uint32_t inc = wave_incl_scan(v, lane);
+        if (lane == 63) wtot[wv] = inc;
         __syncthreads();
-        if (tid == 0) out[n] = carry;
+        uint32_t add = carry;
+        for (int x = 0; x < wv; ++x) add += wtot[x];
+        inc += add;
+        if (u < n) out[u] = inc - v;
+        __syncthreads();
+        if (tid == 1023) carry = inc;
         __syncthreads();
     }
+    atomicAdd(&s_read, my_read);
+    atomicAdd(&s_est, my_est);
+    __syncthreads();
     if (tid == 0) {
-        gb.work[0] = s_read;
-        gb.work[1] = s_est[0]; gb.work[2] = s_est[1]; gb.work[3] = s_est[2]; gb.work[4] = s_est[3];
+        out[n] = carry;
+        atomicAdd(&gb.work[0], s_read);
+        gb.work[1 + which] = s_est;
     }
 }
 
@@ -610,7 +629,8 @@ int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint
     hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, gb.list_np, gb.gpre, gb.cur, gb.counts);
     hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0, c,
                        gb.list_np, gb.gpre, gb.cur, gb.unit8_pairs, gb.unit4_pairs, gb.unit2_pairs, gb.lo_pairs);
-    hipLaunchKernelGGL(group_scan_units_kernel, dim3(1), dim3(1024), 0, st, gb.counts, gb, pair_len);
+    IVFR_HIP(hipMemsetAsync(gb.work, 0, sizeof(unsigned long long), st));
+    hipLaunchKernelGGL(group_scan_units_kernel, dim3(4), dim3(1024), 0, st, gb.counts, gb, pair_len);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -818,6 +838,85 @@ __device__ __forceinline__ void load_code_pair(const uint8_t* __restrict__ codes
 #pragma unroll
         for (int t2 = 0; t2 < M / 4; ++t2) { w0[t2] = 0; w1[t2] = 0; }
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// Sample pass: the first len_s[p] entries of every pair, all estimates kept, each at its own slot
+// of the query's buffer (the plan's prefix sums give the place, no counter is touched).  The prefixes are
+// short (a few hundred entries, a few chunks of IVFR_SAMPLE_CHUNK for the longest lists) and there
+// are tens of thousands of pairs, so the work is table loads and latency: one wavefront per chunk,
+// each with its own LDS slice for the table and no workgroup barrier, keeps many independent
+// chunks in flight per compute unit.
+// ------------------------------------------------------------------------------------------
+template <int M, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void adc_sample_kernel(const uint8_t* __restrict__ codes,
+                                                                const float* __restrict__ lut,
+                                                                const uint32_t* __restrict__ pair_start,
+                                                                const uint32_t* __restrict__ len_s,
+                                                                const uint32_t* __restrict__ chunk_pre,
+                                                                const uint32_t* __restrict__ items, uint32_t n_items,
+                                                                const uint32_t* __restrict__ soff, int w,
+                                                                uint2* __restrict__ cand, CandLayout lay) {
+    extern __shared__ float s_lut[];   // WAVES wavefronts x M * 256 floats
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t item = blockIdx.x * WAVES + wave;   // uniform over the wavefront
+    if (item >= n_items) return;
+    const uint32_t p = items[item];
+    const uint32_t first = (item - chunk_pre[p]) * IVFR_SAMPLE_CHUNK;
+    const uint32_t n = len_s[p];
+    const uint32_t last = n - first < IVFR_SAMPLE_CHUNK ? n : first + IVFR_SAMPLE_CHUNK;   // exclusive
+    float* T = s_lut + wave * M * IVFR_KS;
+    {
+        const float4* src = reinterpret_cast<const float4*>(lut + (int64_t)p * M * IVFR_KS);
+        float4* dst = reinterpret_cast<float4*>(T);
+#pragma unroll
+        for (int i = 0; i < M; ++i) dst[i * 64 + lane] = src[i * 64 + lane];
+    }
+    // the wavefront's own writes are visible to its later reads: LDS operations of one wavefront complete in order
+    const uint32_t start = pair_start[p];
+    const int q = (int)(p / (uint32_t)w);
+    uint2* out = cand + lay.base(q) + soff[p];   // the buffer holds at least the query's whole sample
+    for (uint32_t e = first + 2u * lane; e < last; e += 128u) {
+        uint32_t w0[M / 4], w1[M / 4];
+        load_code_pair<M>(codes, start, e, true, last, w0, w1);
+        out[e] = make_uint2(__float_as_uint(adc_sum<M>(T, w0)), start + e);
+        if (e + 1 < last) out[e + 1] = make_uint2(__float_as_uint(adc_sum<M>(T, w1)), start + e + 1);
+    }
+}
+
+template <int M, int WAVES>
+static int launch_sample_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
+                           const uint32_t* chunk_pre, const uint32_t* items, uint32_t n_items, const uint32_t* soff,
+                           int w, uint2* cand, CandLayout lay, hipStream_t st) {
+    size_t lds = (size_t)WAVES * M * IVFR_KS * sizeof(float);
+    static bool attr_done = false;
+    if (!attr_done && lds > 48 * 1024) {
+        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_sample_kernel<M, WAVES>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((adc_sample_kernel<M, WAVES>), dim3((n_items + WAVES - 1) / WAVES), dim3(64 * WAVES), lds, st,
+                       ix->codes, lut, pair_start, len_s, chunk_pre, items, n_items, soff, w, cand, lay);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
+                            const uint32_t* chunk_pre, const uint32_t* items, uint32_t n_items, const uint32_t* soff,
+                            int w, uint2* cand, CandLayout lay, hipStream_t st) {
+    if (n_items == 0) return IVFR_OK;
+#define IVFR_SAMPLE_ARGS ix, lut, pair_start, len_s, chunk_pre, items, n_items, soff, w, cand, lay, st
+    switch (ix->p.m) {
+        case 4: return launch_sample_m<4, 4>(IVFR_SAMPLE_ARGS);
+        case 8: return launch_sample_m<8, 4>(IVFR_SAMPLE_ARGS);
+        case 16: return launch_sample_m<16, 4>(IVFR_SAMPLE_ARGS);
+        case 32: return launch_sample_m<32, 4>(IVFR_SAMPLE_ARGS);
+        case 64: return launch_sample_m<64, 2>(IVFR_SAMPLE_ARGS);
+        default:
+            ivfr_set_error("list scan supports m in {4, 8, 16, 32, 64}; got %d", ix->p.m);
+            return IVFR_ERR_INVALID_ARG;
+    }
+#undef IVFR_SAMPLE_ARGS
 }
 
 template <int M>

@@ -104,7 +104,12 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_pre = cv.take<uint32_t>((size_t)P + 1);
     const size_t o_lens = cv.take<uint32_t>(P);
     const size_t o_pres = cv.take<uint32_t>((size_t)P + 1);
+    // chunks of the sample: at most one partial chunk per pair plus the full ones of IVFR_MAX_SAMPLE + w entries
+    const size_t n_items_max = (size_t)P + (size_t)B * ((IVFR_MAX_SAMPLE + (size_t)w) / IVFR_SAMPLE_CHUNK + 1);
+    const size_t o_items = cv.take<uint32_t>(n_items_max);
+    const size_t o_soff = cv.take<uint32_t>(P);
     const size_t o_nsample = cv.take<uint32_t>(B);
+    const size_t o_qblk = cv.take<uint32_t>(2 * (size_t)B);
     const size_t o_sq = cv.take<unsigned long long>(B);
     const size_t o_fully = cv.take<uint8_t>(B);
     const size_t o_exonly = cv.take<uint8_t>(B);
@@ -151,7 +156,11 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     pb.blkpre = reinterpret_cast<uint32_t*>(ws + o_pre);
     pb.len_s = reinterpret_cast<uint32_t*>(ws + o_lens);
     pb.blkpre_s = reinterpret_cast<uint32_t*>(ws + o_pres);
+    pb.items_s = reinterpret_cast<uint32_t*>(ws + o_items);
+    pb.soff = reinterpret_cast<uint32_t*>(ws + o_soff);
     pb.nsample = reinterpret_cast<uint32_t*>(ws + o_nsample);
+    pb.qblk = reinterpret_cast<uint32_t*>(ws + o_qblk);
+    pb.qblk_s = pb.qblk + B;
     pb.sq = reinterpret_cast<unsigned long long*>(ws + o_sq);
     pb.fully = reinterpret_cast<uint8_t*>(ws + o_fully);
     pb.exact_only = reinterpret_cast<uint8_t*>(ws + o_exonly);
@@ -234,6 +243,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         }
         // the candidate pool is sized by the plan: one small read-back
         IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+        IVFR_HIP(hipMemcpyAsync(ix->h_status + 24, pb.blkpre_s + Pb, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
         IVFR_TRY(mark(IVFR_STAGE_PROBE, false));
         IVFR_TRY(mark(IVFR_STAGE_LUT, true));
         IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, lut_scale, st));
@@ -241,6 +251,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_HIP(hipStreamSynchronize(st));
         unsigned long long tot2[2];
         memcpy(tot2, ix->h_status + 2, sizeof(tot2));
+        const uint32_t n_sample_chunks = (uint32_t)ix->h_status[24];
         ix->st_codes += (int64_t)tot2[0];
         ix->st_pairs += Pb;
         int n_unit8 = 0, n_unit4 = 0, n_unit2 = 0, n_lo = 0;
@@ -267,13 +278,14 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         uint2* cand = ix->cand_ws.as<uint2>();
         // uniform sample of the visited entries -> bound tau on the k'-th smallest estimate
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, true));
-        IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_HIP(hipMemsetAsync(overtot, 0, 4 * sizeof(int32_t), st));
         hipLaunchKernelGGL(fill_f32_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, tau, (int64_t)nb, INFINITY);
-        IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len_s, pb.blkpre_s, nullptr, Pb, w, tau, cand, cnt, lay, groups, st));
+        IVFR_TRY(ivfr_launch_sample_scan(ix, lut, pb.pair_start, pb.len_s, pb.blkpre_s, pb.items_s, n_sample_chunks,
+                                         pb.soff, w, cand, lay, st));
         {
+            // the sample of query q fills the first nsample[q] records of its buffer
             SelectArgs a;
-            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = cnt; a.lay = lay;
+            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = pb.nsample; a.lay = lay;
             IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, 0, pb.fully, tau, nullptr, st));
         }
         IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
