@@ -919,6 +919,15 @@ int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32
 #undef IVFR_SAMPLE_ARGS
 }
 
+#define Q8H_CAP 192   // queued candidates per wavefront (two LDS words each)
+
+// bit x set when 16-bit lane x of the four words is not negative (lane 0 = low half of u.x)
+__device__ __forceinline__ uint32_t sign_free_mask(uint4 u) {
+    const uint32_t neg = ((u.x >> 15) & 1u) | ((u.x >> 30) & 2u) | ((u.y >> 13) & 4u) | ((u.y >> 28) & 8u) |
+                         ((u.z >> 11) & 16u) | ((u.z >> 26) & 32u) | ((u.w >> 9) & 64u) | ((u.w >> 24) & 128u);
+    return ~neg & 0xffu;
+}
+
 template <int M>
 __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* __restrict__ codes,
                                                                 const float* __restrict__ lut,
@@ -932,6 +941,11 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
                                                                 uint32_t* __restrict__ cand_cnt, CandLayout lay) {
     extern __shared__ float s_raw[];
     half8* s_lut8 = reinterpret_cast<half8*>(s_raw);   // [M * 256] x 8 halves: component x = query x of the unit
+    // behind the tables: per wavefront a queue of Q8H_CAP (entry, query mask) candidates, then the unit's pairs and bounds
+    uint32_t* q_entry = reinterpret_cast<uint32_t*>(s_raw) + M * IVFR_KS * 4 + (threadIdx.x >> 6) * (2 * Q8H_CAP);
+    uint32_t* q_mask = q_entry + Q8H_CAP;
+    uint32_t* s_pid = reinterpret_cast<uint32_t*>(s_raw) + M * IVFR_KS * 4 + 4 * (2 * Q8H_CAP);
+    float* s_tau = reinterpret_cast<float*>(s_pid + 8);
     const uint32_t total = blkpre[nunits];
     const uint32_t NG = gridDim.x, g = blockIdx.x;
     uint32_t b = (uint32_t)(((uint64_t)total * g) / NG);
@@ -943,7 +957,36 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
         if (blkpre[mid] <= b) lo = mid; else hi = mid;
     }
     int u = lo;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    uint32_t qn = 0;   // candidates queued by this wavefront (uniform over its lanes)
+    uint32_t start = 0;
+    // Exact fp32 re-evaluation of the queued candidates, one per lane: every lane works on its own
+    // (entry, query) combinations, so the table reads and the appends of a whole queue overlap.
+    auto drain = [&]() {
+        for (uint32_t base = 0; base < qn; base += 64) {
+            const uint32_t i = base + lane;
+            if (i < qn) {
+                const uint32_t e = q_entry[i];
+                uint32_t mask = q_mask[i];
+                uint32_t wd[M / 4];
+                const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e) * M);
+#pragma unroll
+                for (int t2 = 0; t2 < M / 4; ++t2) wd[t2] = src[t2];
+                while (mask) {
+                    const int x = __ffs(mask) - 1;
+                    mask &= mask - 1;
+                    const uint32_t pidx = s_pid[x];
+                    const float est = adc_sum<M>(lut + (int64_t)pidx * M * IVFR_KS, wd);
+                    if (est <= s_tau[x]) {
+                        const int q = (int)(pidx / (uint32_t)w);
+                        const uint32_t slot = atomicAdd(cand_cnt + q, 1u);
+                        if (slot < lay.cap(q)) cand[lay.base(q) + slot] = make_uint2(__float_as_uint(est), start + e);
+                    }
+                }
+            }
+        }
+        qn = 0;
+    };
     while (b < b_end) {
         while (blkpre[u + 1] <= b) ++u;
         const uint32_t pb0 = blkpre[u], pb1 = blkpre[u + 1];
@@ -965,8 +1008,14 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
 #pragma unroll
         for (int x = 0; x < 8; ++x)
             if (unit_pairs[(int64_t)u * 8 + x] == IVFR_NO_PAIR) tshi[x] = (short)-1;
-        const uint32_t start = pair_start[pid[0]], len = pair_len[pid[0]];
-        __syncthreads();
+        start = pair_start[pid[0]];
+        const uint32_t len = pair_len[pid[0]];
+        __syncthreads();   // every wavefront has drained its queue and left the previous unit's tables
+        if (tid < 8) {
+            const uint32_t raw = unit_pairs[(int64_t)u * 8 + tid];
+            s_pid[tid] = raw != IVFR_NO_PAIR ? raw : unit_pairs[(int64_t)u * 8];
+            s_tau[tid] = raw != IVFR_NO_PAIR ? tau[(int)(raw / (uint32_t)w)] : -1.f;
+        }
         for (int e = tid; e < M * IVFR_KS; e += 256) {
             half8 h;
 #pragma unroll
@@ -1009,30 +1058,26 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
                 const bool none0 = !in0[v] || ((ua.x & ua.y & ua.z & ua.w & 0x80008000u) == 0x80008000u);
                 const bool none1 = !in1[v] || ((ub.x & ub.y & ub.z & ub.w & 0x80008000u) == 0x80008000u);
                 if (__ballot(!(none0 && none1)) == 0) continue;
-                uint32_t maybe0 = 0, maybe1 = 0;   // bit x: query x may keep this entry
-#pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    maybe0 |= ((float)ha[x] <= ts[x] ? 1u : 0u) << x;
-                    maybe1 |= ((float)hb[x] <= ts[x] ? 1u : 0u) << x;
+                // bit x of the mask: query x may keep the entry (its difference is not negative)
+                const uint32_t m0 = none0 ? 0u : sign_free_mask(ua), m1 = none1 ? 0u : sign_free_mask(ub);
+                const uint64_t b0 = __ballot(m0 != 0), b1 = __ballot(m1 != 0);
+                const uint64_t below = (1ull << lane) - 1ull;
+                const uint32_t n0 = __popcll(b0);
+                if (m0) {
+                    const uint32_t slot = qn + __popcll(b0 & below);
+                    q_entry[slot] = e0[v];
+                    q_mask[slot] = m0;
                 }
-                if (!in0[v]) maybe0 = 0;
-                if (!in1[v]) maybe1 = 0;
-                if (__ballot((maybe0 | maybe1) != 0) == 0) continue;
-                // exact fp32 re-evaluation of the few candidates, query by query
-#pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    const bool c0 = (maybe0 >> x) & 1u, c1 = (maybe1 >> x) & 1u;
-                    if (__ballot(c0 || c1) == 0) continue;
-                    const float* T = lut + pid[x] * M * IVFR_KS;
-                    float x0 = 0.f, x1 = 0.f;
-                    if (c0) x0 = adc_sum<M>(T, wds[v][0]);
-                    if (c1) x1 = adc_sum<M>(T, wds[v][1]);
-                    const int q = (int)(pid[x] / w);
-                    append_records(c0 && x0 <= t[x], x0, start + e0[v], c1 && x1 <= t[x], x1, start + e0[v] + 1,
-                                   cand + lay.base(q), cand_cnt + q, lay.cap(q));
+                if (m1) {
+                    const uint32_t slot = qn + n0 + __popcll(b1 & below);
+                    q_entry[slot] = e0[v] + 1;
+                    q_mask[slot] = m1;
                 }
+                qn += n0 + __popcll(b1);
+                if (qn > Q8H_CAP - 128) drain();   // room for the next 64 x 2 entries
             }
         }
+        drain();   // the queue refers to this unit's pairs
         b = stop;
     }
 }
@@ -1042,7 +1087,7 @@ static int launch_shared8h_m(const ivfr_index* ix, const float* lut, const float
                              const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
                              const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,
                              uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
-    size_t lds = (size_t)M * IVFR_KS * 16;
+    size_t lds = (size_t)M * IVFR_KS * 16 + 4 * 2 * Q8H_CAP * sizeof(uint32_t) + 16 * sizeof(uint32_t);
     static bool attr_done = false;
     if (!attr_done && lds > 48 * 1024) {
         IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>),
