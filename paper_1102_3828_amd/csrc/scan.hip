@@ -10,7 +10,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 //  - a query whose visited lists hold at most `full_limit` entries keeps every estimate
 //    (tau = +inf) and is selected from directly;
 //  - otherwise a sample is scored first: the first ceil(len / stride) entries of every visited
-//    list, stride = k' / mu, so that about mu of the true k' best fall in the sample (a query
+//    list; about mu = k' / stride of the true k' best fall in the sample (mu >= 4; a query
 //    that visits very many entries gets a wider stride so its sample stays below max_sample).  Entries
 //    of a list are in id order, which carries no information about the distance to a query,
 //    so a prefix is as good as a random draw, and taking the same fraction of every visited
@@ -41,11 +41,23 @@ __global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restri
     for (int r = lane; r < w; r += 64) total += list_len[probe[(int64_t)q * w + r]];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) total += __shfl_xor(total, off, 64);
-    const bool fully = total <= full_limit;
-    // stride k'/mu, widened when the query visits so much that its sample would exceed max_sample
-    unsigned long long stride64 = stride_k < 1 ? 1ull : stride_k;
+    bool fully = total <= full_limit;
+    // Sample size: scoring a sampled entry and handling a surviving one cost about the same order, and the
+    // survivors fall as k' (1 + 5/sqrt(mu) + 6/mu) with mu = k' n_s / total, so the cheapest sample grows as
+    // the cube root of k' * total (the factor 16 is measured).  Stride = total / n_s, at most k' / mu_min
+    // (stride_k), at least what keeps the sample below max_sample; a sample of half the entries or more is
+    // pointless: such a query keeps everything instead.
+    unsigned long long stride64 = 1;
+    {
+        const double ns = 16.0 * cbrt((double)kprime * (double)total);
+        const double st_d = (double)total / (ns > 1.0 ? ns : 1.0);
+        stride64 = st_d > 4.0e9 ? 4000000000ull : (unsigned long long)st_d;
+    }
+    if (stride64 > (stride_k < 1 ? 1ull : stride_k)) stride64 = stride_k < 1 ? 1ull : stride_k;
     const unsigned long long widen = (total + max_sample - 1) / max_sample;
     if (widen > stride64) stride64 = widen;
+    if (stride64 < 1) stride64 = 1;
+    if (stride64 <= 2) fully = true;
     const uint32_t stride = (uint32_t)(stride64 > 0xFFFFFFFFull ? 0xFFFFFFFFull : stride64);
     unsigned long long sampled = 0;
     uint32_t carry = 0, carry_s = 0, carry_e = 0;

@@ -447,14 +447,13 @@ def test_list_sharing_modes_give_identical_bits(m):
     """Many queries on few lists: units of eight (half-precision tables + exact re-evaluation), of
     four and of two (fp32 tables) and single pairs must all record the same fp32 estimates, so the
     three sharing modes return identical bits; the trace is checked against the oracle as well."""
-    wl = tiny_workload(d=64, G=16, N=60000, n_train=3000, n_query=75, c=4, m=m, m_refine=16, iters=4)
+    wl = tiny_workload(d=32, G=16, N=600000, n_train=3000, n_query=75, c=4, m=m, m_refine=16, iters=4)
     index, X = wl["index"], wl["X"]
     ix = gpu_index_from_oracle(index)
     xq = queries_dev(X)
-    # sampled bound + filter, as the large workloads run; k' is tiny against the ~30000 visited entries, so
+    # sampled bound + filter, as the large workloads run; k' is small against the ~300000 visited entries, so
     # the bound passes well under 0.2 % of the estimates and the half-precision units are used
-    ix.set_tuning(full_mult=1)
-    w, kp, k = 2, 8, 5
+    w, kp, k = 2, 64, 5
     outs = {}
     for mode in (2, 1, 0):
         ix.set_list_sharing(mode)
@@ -501,13 +500,13 @@ def test_papers_own_shortlist_setting():
 
 
 def test_duplicate_vectors_are_cut_by_id():
-    """Degenerate input: a database of a few vectors repeated a thousand times.  Estimates tie in
+    """Degenerate input: a database of three vectors repeated two thousand times each.  Estimates tie in
     huge groups, so the entries at or below the sampled bound overflow the candidate buffer; the
     rescan's bound is a key (estimate, id), which cuts through the ties, lowest ids first."""
     wl = tiny_workload(d=32, G=16, N=3000, n_train=2000, n_query=12, c=8, m=4, m_refine=4, iters=4)
     books, X = wl["books"], wl["X"]
-    distinct = wl["Y"][:6]
-    Y = np.repeat(distinct, 1000, axis=0)
+    distinct = wl["Y"][:3]
+    Y = np.repeat(distinct, 2000, axis=0)
     rng = np.random.default_rng(3)
     Y = Y[rng.permutation(len(Y))]
     index = orc.build_index(Y, np.arange(len(Y)), books)
