@@ -828,6 +828,10 @@ int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const
 // fp32 from the query's table in global memory, with the same summation order as everywhere
 // else; only that exact value is compared with tau and recorded.  The records, and therefore
 // the search results, are bit-identical to the fp32 kernels' (tested).
+// The candidates are not re-evaluated where they are found (every second or third pass of the
+// scan loop has one somewhere in the wavefront, and its global reads and atomic would stall
+// all 64 lanes): a wavefront queues them in LDS as (entry, query mask) and works the queue off
+// when it is full or the unit ends, one candidate per lane, so the latencies overlap.
 // ------------------------------------------------------------------------------------------
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef short short8 __attribute__((ext_vector_type(8)));
