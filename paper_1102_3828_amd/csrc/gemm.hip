@@ -256,10 +256,164 @@ __global__ __launch_bounds__(256) void assign_kernel(const float* __restrict__ X
     }
 }
 
+// The same assignment with the 128 rows of X resident in LDS for the whole walk over the columns
+// (d <= 128): a 512-thread workgroup (8 wavefronts, 2x4) takes 128 rows x 256 columns per step, only
+// the centroid slabs are staged, double-buffered, and the global loads of the next slab are issued
+// before the matrix instructions of the current one, so one barrier per slab remains.  Same slab
+// order and accumulation as assign_kernel: the results are identical.
+#define RN 256
+__device__ __forceinline__ void mma_slab_rs(const float* As, int a_stride, const float* Bs, int wm, int wn,
+                                            floatx16 acc[2][2]) {
+    const int lane = threadIdx.x & 63;
+    const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int kk = 0; kk < KT / 8; ++kk) {
+        float4 a[2], b[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            a[t] = *reinterpret_cast<const float4*>(As + (64 * wm + 32 * t + r) * a_stride + kk * 8 + 4 * h);
+            b[t] = *reinterpret_cast<const float4*>(Bs + (64 * wn + 32 * t + r) * LDS_STRIDE + kk * 8 + 4 * h);
+        }
+#pragma unroll
+        for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta].x, b[tb].x, acc[ta][tb], 0, 0, 0);
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta].y, b[tb].y, acc[ta][tb], 0, 0, 0);
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta].z, b[tb].z, acc[ta][tb], 0, 0, 0);
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta].w, b[tb].w, acc[ta][tb], 0, 0, 0);
+            }
+    }
+}
+
+__global__ __launch_bounds__(512) void assign_resident_kernel(const float* __restrict__ X, int64_t n,
+                                                              const float* __restrict__ C,
+                                                              const float* __restrict__ cnorm, int c, int d, int dpad,
+                                                              int32_t* __restrict__ assign) {
+    extern __shared__ float smem[];
+    __shared__ float red_v[4][TM];
+    __shared__ int red_i[4][TM];
+    const int DP = dpad + 4;
+    float* As = smem;             // [TM][DP]
+    float* Bs = As + TM * DP;     // 2 x [RN][LDS_STRIDE]
+    const int64_t row0 = (int64_t)blockIdx.x * TM;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int kc = (tid & 7) * 4, sr = tid >> 3;   // staging: 64 rows x 8 float4 per pass
+    for (int k0 = 0; k0 < dpad; k0 += KT)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = sr + 64 * i;
+            const int64_t gr = row0 + r;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gr < n && k0 + kc < d) v = *reinterpret_cast<const float4*>(X + gr * d + k0 + kc);
+            *reinterpret_cast<float4*>(As + r * DP + k0 + kc) = v;
+        }
+    const int ks = dpad / KT, ntile = (c + RN - 1) / RN, S = ntile * ks;
+    float4 pre[4];
+    auto load_b = [&](int s) {
+        const int col0 = (s / ks) * RN, k0 = (s % ks) * KT;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int gc = col0 + sr + 64 * i;
+            pre[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gc < c && k0 + kc < d) pre[i] = *reinterpret_cast<const float4*>(C + (int64_t)gc * d + k0 + kc);
+        }
+    };
+    auto store_b = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<float4*>(Bs + buf * RN * LDS_STRIDE + (sr + 64 * i) * LDS_STRIDE + kc) = pre[i];
+    };
+    float best_v[2][16];
+    int best_i[2][16];
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            best_v[a][v] = INFINITY; best_i[a][v] = 0x7fffffff;
+            acc[a][0][v] = 0.f; acc[a][1][v] = 0.f;
+        }
+    load_b(0);
+    store_b(0);
+    __syncthreads();
+    for (int s = 0; s < S; ++s) {
+        if (s + 1 < S) load_b(s + 1);
+        mma_slab_rs(As + (s % ks) * KT, DP, Bs + (s & 1) * RN * LDS_STRIDE, wm, wn, acc);
+        if (s % ks == ks - 1) {
+            const int col0 = (s / ks) * RN;
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const int col = col0 + 64 * wn + 32 * tb + (lane & 31);
+                const bool ok = col < c;
+                const float cn = ok ? cnorm[col] : 0.f;
+#pragma unroll
+                for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float val = fmaf(-2.f, acc[ta][tb][v], cn);
+                        if (ok && val < best_v[ta][v]) { best_v[ta][v] = val; best_i[ta][v] = col; }
+                        acc[ta][tb][v] = 0.f;
+                    }
+            }
+        }
+        if (s + 1 < S) store_b((s + 1) & 1);
+        __syncthreads();
+    }
+    // reduce over the 32 lanes that share a row, then over the four column wavefronts
+#pragma unroll
+    for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float bv = best_v[ta][v];
+            int bi = best_i[ta][v];
+#pragma unroll
+            for (int off = 16; off >= 1; off >>= 1) {
+                float ov = __shfl_xor(bv, off, 64);
+                int oi = __shfl_xor(bi, off, 64);
+                if (ov < bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            if ((lane & 31) == 0) {
+                int r = 64 * wm + 32 * ta + acc_row(v, lane);
+                red_v[wn][r] = bv;
+                red_i[wn][r] = bi;
+            }
+        }
+    __syncthreads();
+    if (tid < TM) {
+        const int64_t row = row0 + tid;
+        if (row < n) {
+            float bv = red_v[0][tid];
+            int bi = red_i[0][tid];
+#pragma unroll
+            for (int x = 1; x < 4; ++x) {
+                const float ov = red_v[x][tid];
+                const int oi = red_i[x][tid];
+                if (ov < bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            assign[row] = bi;
+        }
+    }
+}
+
 int ivfr_launch_assign(const float* X, int64_t n, const float* C, const float* cnorm, int c, int d,
                        int32_t* assign, hipStream_t st) {
     if (n <= 0) return IVFR_OK;
     dim3 grid((unsigned)((n + TM - 1) / TM));
+    const int dpad = (d + KT - 1) / KT * KT;
+    if (dpad <= 128) {
+        const size_t lds = ((size_t)TM * (dpad + 4) + 2 * (size_t)RN * LDS_STRIDE) * sizeof(float);
+        static bool attr_done = false;
+        if (!attr_done) {
+            IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(assign_resident_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
+            attr_done = true;
+        }
+        hipLaunchKernelGGL(assign_resident_kernel, grid, dim3(512), lds, st, X, n, C, cnorm, c, d, dpad, assign);
+        IVFR_HIP(hipGetLastError());
+        return IVFR_OK;
+    }
     hipLaunchKernelGGL(assign_kernel, grid, dim3(256), 0, st, X, n, C, cnorm, c, d, assign);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
