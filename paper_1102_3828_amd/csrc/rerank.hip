@@ -12,6 +12,7 @@
 // neighbouring directory entries, usually zero to two steps.  Output per entry: the 64-bit key
 // (distance bits << 32 | id) consumed by the final top-k selection.
 #include "ivfr_internal.h"
+#include <algorithm>
 
 template <int VEC>
 __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ queries, int d, int c, int m, int mr,
@@ -92,11 +93,102 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
     }
 }
 
+// Variant for many short-list entries: the refinement codebook (256 d floats, 128 KB at d = 128) is
+// copied into LDS once per workgroup and the workgroups (one per compute unit, 1024 threads) walk over
+// blocks of 128 entries.  The codebook rows are short (d/m' floats), so gathering them through the
+// vector cache fetches whole 128-byte lines for 32 or 64 useful bytes, and that fill traffic from L2 is
+// what bounds the plain kernel when k' is large.  Arithmetic and summation order are the same.
+__global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restrict__ queries, int d, int c, int m, int mr,
+                                                          int dsub, int dsub_r, const float* __restrict__ coarse,
+                                                          const float* __restrict__ pq, const float* __restrict__ rq,
+                                                          const uint32_t* __restrict__ list_start,
+                                                          const uint32_t* __restrict__ chunk_list, int chunk_shift,
+                                                          const uint8_t* __restrict__ codes,
+                                                          const uint8_t* __restrict__ rcodes,
+                                                          const int32_t* __restrict__ ids, int kprime, int q_base,
+                                                          int nq, const uint32_t* __restrict__ short_pos,
+                                                          const int32_t* __restrict__ short_n,
+                                                          uint64_t* __restrict__ keys, float* __restrict__ refined_out,
+                                                          int32_t* __restrict__ ids_out) {
+    extern __shared__ float s_rq[];   // [m'][256][d/m'] = 256 d floats
+    for (int i = threadIdx.x; i < 64 * d; i += 1024)
+        reinterpret_cast<float4*>(s_rq)[i] = reinterpret_cast<const float4*>(rq)[i];
+    __syncthreads();
+    const int t = threadIdx.x & 7, g = threadIdx.x >> 3;
+    const int per_q = (kprime + 127) / 128;
+    const int64_t n_items = (int64_t)nq * per_q;
+    for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int q = q_base + (int)(item / per_q);
+        const int slot = (int)(item % per_q) * 128 + g;
+        const int n = short_n[q];
+        const bool live = slot < n;   // uniform over the 8 lanes of an entry
+        float acc = 0.f;
+        int32_t id = -1;
+        if (live) {
+            const uint32_t pos = short_pos[(int64_t)q * kprime + slot];
+            int lo = (int)chunk_list[pos >> chunk_shift], hi = (int)chunk_list[(pos >> chunk_shift) + 1] + 1;
+            while (hi - lo > 1) {
+                int mid = (lo + hi) >> 1;
+                if (list_start[mid] <= pos) lo = mid; else hi = mid;
+            }
+            id = ids[pos];
+            const uint8_t* code = codes + (uint64_t)pos * m;
+            const uint8_t* rcode = rcodes + (uint64_t)pos * mr;
+            const float* x = queries + (int64_t)q * d;
+            const float* cl = coarse + (int64_t)lo * d;
+            for (int e = 4 * t; e < d; e += 32) {
+                const int j = e / dsub, jr = e / dsub_r;
+                float4 y = *reinterpret_cast<const float4*>(cl + e);
+                const float4 pv = *reinterpret_cast<const float4*>(pq + ((int64_t)j * IVFR_KS + code[j]) * dsub + (e - j * dsub));
+                y.x += pv.x; y.y += pv.y; y.z += pv.z; y.w += pv.w;
+                const float4 rv = *reinterpret_cast<const float4*>(s_rq + (jr * IVFR_KS + rcode[jr]) * dsub_r + (e - jr * dsub_r));
+                y.x += rv.x; y.y += rv.y; y.z += rv.z; y.w += rv.w;
+                const float4 xv = *reinterpret_cast<const float4*>(x + e);
+                const float a = xv.x - y.x, b = xv.y - y.y, cc = xv.z - y.z, dd = xv.w - y.w;
+                acc = fmaf(a, a, acc); acc = fmaf(b, b, acc); acc = fmaf(cc, cc, acc); acc = fmaf(dd, dd, acc);
+            }
+        }
+        acc += __shfl_xor(acc, 4, 64);
+        acc += __shfl_xor(acc, 2, 64);
+        acc += __shfl_xor(acc, 1, 64);
+        if (t == 0 && slot < kprime) {
+            const int64_t o = (int64_t)q * kprime + slot;
+            if (live) {
+                keys[o] = ((uint64_t)__float_as_uint(acc) << 32) | (uint32_t)id;
+                if (refined_out) refined_out[o] = acc;
+                if (ids_out) ids_out[o] = id;
+            } else {
+                keys[o] = ~0ull;
+                if (refined_out) refined_out[o] = INFINITY;
+                if (ids_out) ids_out[o] = -1;
+            }
+        }
+    }
+}
+
 int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, int nq, int kprime,
                        const uint32_t* short_pos, const int32_t* short_n, uint64_t* keys, float* refined_out,
                        int32_t* ids_out, hipStream_t st) {
     if (nq <= 0) return IVFR_OK;
     dim3 grid((kprime + 31) / 32, nq);
+    const bool vec0 = (ix->dsub % 4 == 0) && (ix->p.m_refine == 0 || ix->dsub_r % 4 == 0) && ((ix->p.d / 8) % 4 == 0);
+    const size_t rq_bytes = (size_t)IVFR_KS * ix->p.d * sizeof(float);
+    if (vec0 && ix->p.m_refine > 0 && rq_bytes <= 128 * 1024 && (int64_t)nq * kprime >= (int64_t)ix->n_cu * 1024) {
+        static bool attr_done = false;
+        if (!attr_done) {
+            IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+            attr_done = true;
+        }
+        const int64_t n_items = (int64_t)nq * ((kprime + 127) / 128);
+        const int groups = (int)std::min<int64_t>(n_items, ix->n_cu);
+        hipLaunchKernelGGL(rerank_lds_kernel, dim3(groups), dim3(1024), rq_bytes, st, queries, ix->p.d, ix->p.c, ix->p.m,
+                           ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq, ix->list_start,
+                           ix->chunk_list, ix->chunk_shift, ix->codes, ix->rcodes, ix->ids, kprime, q_base, nq, short_pos,
+                           short_n, keys, refined_out, ids_out);
+        IVFR_HIP(hipGetLastError());
+        return IVFR_OK;
+    }
     const bool vec = (ix->dsub % 4 == 0) && (ix->p.m_refine == 0 || ix->dsub_r % 4 == 0) && ((ix->p.d / 8) % 4 == 0);
 #define IVFR_RERANK_ARGS                                                                                       \
     queries, ix->p.d, ix->p.c, ix->p.m, ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq,      \
