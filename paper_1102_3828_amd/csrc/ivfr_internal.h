@@ -177,9 +177,11 @@ struct SelectArgs {
 // query's sq visited entries): tau = the r-th smallest sampled estimate, r = mu + 5 sqrt(mu) + 6 with
 // mu = k' * sampled / sq the expected number of the true k' best inside the sample (+inf when the
 // sample holds fewer than r).  fixed_rank > 0 takes that rank instead.  skip[seg] != 0 leaves tau alone.
-// tau_id (optional) receives the id of the record taken, i.e. the low half of its key.
+// tau_id (optional) receives the id of the record taken, i.e. the low half of its key.  values_only: segment
+// q holds counts[q] bare estimates (4 bytes each) from the start of its record buffer instead of records.
 int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, int fixed_rank,
-                           const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st);
+                           const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st,
+                           bool values_only = false);
 int ivfr_select_init();   // one-time function attributes
 
 // Search plan, look-up tables, sample and list scan (scan.hip)
@@ -213,8 +215,8 @@ int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pai
                      uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st,
                      const uint32_t* tau_id = nullptr);
 
-// Sample pass: the estimate of entry e < len_s[p] of pair p is recorded at slot soff[p] + e of the query's
-// buffer (no counters involved).  One wavefront per chunk of IVFR_SAMPLE_CHUNK entries; items[i] is the
+// Sample pass: the estimate of entry e < len_s[p] of pair p is written as a bare float at index soff[p] + e of
+// the query's buffer (no counters involved; only the values are needed to bound the k'-th smallest).  One wavefront per chunk of IVFR_SAMPLE_CHUNK entries; items[i] is the
 // pair of chunk i, chunk_pre the pairs' chunk prefix.
 int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
                             const uint32_t* chunk_pre, const uint32_t* items, uint32_t n_items, const uint32_t* soff,

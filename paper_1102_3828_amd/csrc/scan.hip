@@ -857,8 +857,8 @@ __device__ __forceinline__ void load_code_pair(const uint8_t* __restrict__ codes
 }
 
 // ------------------------------------------------------------------------------------------
-// Sample pass: the first len_s[p] entries of every pair, all estimates kept, each at its own slot
-// of the query's buffer (the plan's prefix sums give the place, no counter is touched).  The prefixes are
+// Sample pass: the first len_s[p] entries of every pair, all estimates kept (the values only), each at its own place
+// in the query's buffer (the plan's prefix sums give the place, no counter is touched).  The prefixes are
 // short (a few hundred entries, a few chunks of IVFR_SAMPLE_CHUNK for the longest lists) and there
 // are tens of thousands of pairs, so the work is table loads and latency: one wavefront per chunk,
 // each with its own LDS slice for the table and no workgroup barrier, keeps many independent
@@ -891,12 +891,13 @@ __global__ __launch_bounds__(64 * WAVES) void adc_sample_kernel(const uint8_t* _
     // the wavefront's own writes are visible to its later reads: LDS operations of one wavefront complete in order
     const uint32_t start = pair_start[p];
     const int q = (int)(p / (uint32_t)w);
-    uint2* out = cand + lay.base(q) + soff[p];   // the buffer holds at least the query's whole sample
+    // bare estimates: the buffer (records of 8 bytes) holds at least the query's whole sample
+    float* out = reinterpret_cast<float*>(cand + lay.base(q)) + soff[p];
     for (uint32_t e = first + 2u * lane; e < last; e += 128u) {
         uint32_t w0[M / 4], w1[M / 4];
         load_code_pair<M>(codes, start, e, true, last, w0, w1);
-        out[e] = make_uint2(__float_as_uint(adc_sum<M>(T, w0)), start + e);
-        if (e + 1 < last) out[e + 1] = make_uint2(__float_as_uint(adc_sum<M>(T, w1)), start + e + 1);
+        out[e] = adc_sum<M>(T, w0);
+        if (e + 1 < last) out[e + 1] = adc_sum<M>(T, w1);
     }
 }
 

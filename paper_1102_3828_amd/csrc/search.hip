@@ -283,10 +283,10 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_TRY(ivfr_launch_sample_scan(ix, lut, pb.pair_start, pb.len_s, pb.blkpre_s, pb.items_s, n_sample_chunks,
                                          pb.soff, w, cand, lay, st));
         {
-            // the sample of query q fills the first nsample[q] records of its buffer
+            // the sample of query q is nsample[q] bare estimates at the start of its buffer
             SelectArgs a;
             a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = pb.nsample; a.lay = lay;
-            IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, 0, pb.fully, tau, nullptr, st));
+            IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, 0, pb.fully, tau, nullptr, st, true));
         }
         IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));

@@ -26,9 +26,14 @@ struct SegView {
     const int32_t* ids;
     int64_t base;
     int64_t n;
+    const uint32_t* vals = nullptr;   // source C: bare distance words; the element index is the low half of the key
 };
 
 __device__ __forceinline__ uint32_t seg_hi(const SegView& s, int64_t i, uint32_t* pos) {
+    if (s.vals) {
+        *pos = (uint32_t)i;
+        return s.vals[s.base + i];
+    }
     if (s.keys) {
         uint64_t k = s.keys[s.base + i];
         *pos = (uint32_t)k;
@@ -40,7 +45,7 @@ __device__ __forceinline__ uint32_t seg_hi(const SegView& s, int64_t i, uint32_t
 }
 
 __device__ __forceinline__ uint32_t seg_lo(const SegView& s, uint32_t pos) {
-    return s.keys ? pos : (uint32_t)s.ids[pos];
+    return (s.keys || s.vals) ? pos : (uint32_t)s.ids[pos];
 }
 
 // Returns the K-th smallest key of the segment (1 <= K <= n).  All threads must call.
@@ -217,11 +222,11 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
                                                            const uint32_t* counts,
                                                            const unsigned long long* sq, int kprime,
                                                            int fixed_rank, const uint8_t* skip, float* tau,
-                                                           uint32_t* tau_id) {
+                                                           uint32_t* tau_id, int values_only) {
     const int seg = blockIdx.x;
     if (skip && skip[seg]) return;
     bool over;
-    int64_t n = seg_count(counts, lay.cap(seg), seg, &over);
+    int64_t n = seg_count(counts, values_only ? 0xFFFFFFFFu : lay.cap(seg), seg, &over);
     const double mu = (double)kprime * (double)n / (double)(sq[seg] ? sq[seg] : 1ull);
     // fixed_rank > 0: the records are a subset of the visited entries and their fixed_rank-th smallest is wanted
     const int64_t r = fixed_rank > 0 ? (int64_t)fixed_rank : (int64_t)ceil(mu + 5.0 * sqrt(mu) + 6.0);
@@ -233,6 +238,11 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
         return;
     }
     SegView s{nullptr, recs, ids, (int64_t)lay.base(seg), n};
+    if (values_only) {   // the segment holds n bare estimates (4 bytes each) at the start of its record buffer
+        s.recs = nullptr;
+        s.vals = reinterpret_cast<const uint32_t*>(recs);
+        s.base = 2 * (int64_t)lay.base(seg);
+    }
     uint64_t pivot = radix_pivot(s, (uint32_t)r);
     if (threadIdx.x == 0) {
         tau[seg] = __uint_as_float((uint32_t)(pivot >> 32));
@@ -241,10 +251,10 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
 }
 
 int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, int fixed_rank,
-                           const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st) {
+                           const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st, bool values_only) {
     if (a.nseg <= 0) return IVFR_OK;
     hipLaunchKernelGGL(select_tau_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.lay, a.counts, sq,
-                       kprime, fixed_rank, skip, tau, tau_id);
+                       kprime, fixed_rank, skip, tau, tau_id, values_only ? 1 : 0);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
