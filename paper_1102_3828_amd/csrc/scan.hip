@@ -115,8 +115,7 @@ __global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restri
     atomicAdd(pb.totals, total);
 }
 
-// One workgroup: exclusive prefix sums over the nq queries (candidate-buffer offsets; scan and sample
-// blocks), then the per-query block offsets are added to the query-relative prefixes of the P pairs.
+// One workgroup: exclusive prefix sums over the nq queries (candidate-buffer offsets; scan and sample blocks).
 __global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int w, PlanBuffers pb) {
     __shared__ uint32_t wtot[2][16];
     __shared__ uint32_t carry[2];
@@ -151,17 +150,20 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int w, PlanBuff
         if (tid == 1023) { carry64 = inc64; carry[0] = inc[0]; carry[1] = inc[1]; }
         __syncthreads();
     }
-    // the workgroup's own global writes above are visible to all its threads after the barrier
-    const int P = nq * w;
-    for (int p = tid; p < P; p += 1024) {
-        const int q = p / w;
-        pb.blkpre[p] += pb.qblk[q];
-        const uint32_t first = pb.blkpre_s[p] + pb.qblk_s[q];
-        pb.blkpre_s[p] = first;
-        const uint32_t nchunk = (pb.len_s[p] + IVFR_SAMPLE_CHUNK - 1) / IVFR_SAMPLE_CHUNK;
-        for (uint32_t i = 0; i < nchunk; ++i) pb.items_s[first + i] = (uint32_t)p;
-    }
-    if (tid == 0) { pb.totals[1] = carry64; pb.blkpre[P] = carry[0]; pb.blkpre_s[P] = carry[1]; }
+    if (tid == 0) { pb.totals[1] = carry64; pb.blkpre[nq * w] = carry[0]; pb.blkpre_s[nq * w] = carry[1]; }
+}
+
+// The per-query block offsets are added to the query-relative prefixes of the P pairs, and the pair of
+// every sample chunk is written out.
+__global__ __launch_bounds__(256) void plan_expand_kernel(int P, int w, PlanBuffers pb) {
+    const int p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= P) return;
+    const int q = p / w;
+    pb.blkpre[p] += pb.qblk[q];
+    const uint32_t first = pb.blkpre_s[p] + pb.qblk_s[q];
+    pb.blkpre_s[p] = first;
+    const uint32_t nchunk = (pb.len_s[p] + IVFR_SAMPLE_CHUNK - 1) / IVFR_SAMPLE_CHUNK;
+    for (uint32_t i = 0; i < nchunk; ++i) pb.items_s[first + i] = (uint32_t)p;
 }
 
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
@@ -172,6 +174,7 @@ int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, 
                        ix->list_len, full_limit, stride_k, min_cap, max_sample, kprime, half_frac, pb);
     IVFR_HIP(hipGetLastError());
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, st, nq, w, pb);
+    hipLaunchKernelGGL(plan_expand_kernel, dim3((nq * w + 255) / 256), dim3(256), 0, st, nq * w, w, pb);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }

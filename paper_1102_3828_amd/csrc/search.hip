@@ -330,8 +330,33 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
             IVFR_TRY(ivfr_launch_select_records(a, 0, pb.sq, spos, sest, sn, over, overtot, st));
         }
         IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, false));
-        // status read-back: failed-filter count and scanned totals
+        // Re-rank, final top-k and the optional trace outputs.  Enqueued before the filter's check is read
+        // back (one host round trip less); if a query failed the check it is redone below and this runs again.
+        auto finish = [&]() -> int {
+            // re-rank and final top-k
+            IVFR_TRY(mark(IVFR_STAGE_RERANK, true));
+            IVFR_TRY(ivfr_launch_rerank(ix, X, 0, nb, kprime, spos, sn, rkeys, sref, sids, st));
+            IVFR_TRY(mark(IVFR_STAGE_RERANK, false));
+            IVFR_TRY(mark(IVFR_STAGE_FINAL, true));
+            {
+                SelectArgs a;
+                a.nseg = nb; a.K = k; a.keys = rkeys; a.seg_stride = kprime;
+                IVFR_TRY(ivfr_launch_select_sorted(a, sn, 0, ids_out + q0 * k, dist_out + q0 * k, st));
+            }
+            IVFR_TRY(mark(IVFR_STAGE_FINAL, false));
+            // optional trace outputs
+            if (probe_out) IVFR_HIP(hipMemcpyAsync(probe_out + q0 * w, probe, (size_t)Pb * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+            if (probe_dist_out) IVFR_HIP(hipMemcpyAsync(probe_dist_out + q0 * w, probed, (size_t)Pb * sizeof(float), hipMemcpyDeviceToDevice, st));
+            const size_t sk = (size_t)nb * kprime;
+            if (short_ids_out) IVFR_HIP(hipMemcpyAsync(short_ids_out + q0 * kprime, sids, sk * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+            if (short_ref_out) IVFR_HIP(hipMemcpyAsync(short_ref_out + q0 * kprime, sref, sk * sizeof(float), hipMemcpyDeviceToDevice, st));
+            if (short_est_out) IVFR_HIP(hipMemcpyAsync(short_est_out + q0 * kprime, sest, sk * sizeof(float), hipMemcpyDeviceToDevice, st));
+            if (short_count_out) IVFR_HIP(hipMemcpyAsync(short_count_out + q0, sn, (size_t)nb * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+            return IVFR_OK;
+        };
+        // status read-back: failed-filter count
         IVFR_HIP(hipMemcpyAsync(ix->h_status, overtot, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        IVFR_TRY(finish());
         IVFR_HIP(hipStreamSynchronize(st));
         const int n_over = ix->h_status[0];
         if (n_over > 0) {
@@ -400,27 +425,9 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
                 a.nseg = 1; a.K = kprime; a.recs = dcand; a.ids = ix->ids; a.counts = dcnt; a.lay = dlay;
                 IVFR_TRY(ivfr_launch_select_records(a, q, nullptr, spos, sest, sn, nullptr, nullptr, st));
             }
+            IVFR_TRY(finish());
+            IVFR_HIP(hipStreamSynchronize(st));
         }
-        // re-rank and final top-k
-        IVFR_TRY(mark(IVFR_STAGE_RERANK, true));
-        IVFR_TRY(ivfr_launch_rerank(ix, X, 0, nb, kprime, spos, sn, rkeys, sref, sids, st));
-        IVFR_TRY(mark(IVFR_STAGE_RERANK, false));
-        IVFR_TRY(mark(IVFR_STAGE_FINAL, true));
-        {
-            SelectArgs a;
-            a.nseg = nb; a.K = k; a.keys = rkeys; a.seg_stride = kprime;
-            IVFR_TRY(ivfr_launch_select_sorted(a, sn, 0, ids_out + q0 * k, dist_out + q0 * k, st));
-        }
-        IVFR_TRY(mark(IVFR_STAGE_FINAL, false));
-        // optional trace outputs
-        if (probe_out) IVFR_HIP(hipMemcpyAsync(probe_out + q0 * w, probe, (size_t)Pb * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
-        if (probe_dist_out) IVFR_HIP(hipMemcpyAsync(probe_dist_out + q0 * w, probed, (size_t)Pb * sizeof(float), hipMemcpyDeviceToDevice, st));
-        const size_t sk = (size_t)nb * kprime;
-        if (short_ids_out) IVFR_HIP(hipMemcpyAsync(short_ids_out + q0 * kprime, sids, sk * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
-        if (short_ref_out) IVFR_HIP(hipMemcpyAsync(short_ref_out + q0 * kprime, sref, sk * sizeof(float), hipMemcpyDeviceToDevice, st));
-        if (short_est_out) IVFR_HIP(hipMemcpyAsync(short_est_out + q0 * kprime, sest, sk * sizeof(float), hipMemcpyDeviceToDevice, st));
-        if (short_count_out) IVFR_HIP(hipMemcpyAsync(short_count_out + q0, sn, (size_t)nb * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
-        IVFR_HIP(hipStreamSynchronize(st));
     }
     for (auto& ep : events) {
         float ms = 0.f;
