@@ -350,6 +350,72 @@ __device__ __forceinline__ void append_records(bool keep0, float e0, uint32_t po
     }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Appending through a wavefront queue.  When a noticeable share of the estimates passes the bound,
+// an atomic (with its round trip) in most passes of the scan loop stalls all 64 lanes.  The fp32
+// scans therefore collect what they keep in a small LDS queue per wavefront, (estimate, position,
+// query slot of the unit), and write it out when the queue is nearly full or the unit ends: one
+// atomic per query slot and 64 queued records, issued together.
+// ------------------------------------------------------------------------------------------
+#define WQ_CAP 160   // records per wavefront queue; a push adds at most 128
+struct WaveQueue {
+    uint32_t* est;   // [WQ_CAP] LDS
+    uint32_t* pos;   // [WQ_CAP]
+    uint32_t* tag;   // [WQ_CAP] query slot inside the unit
+    uint32_t n;      // uniform over the wavefront
+};
+#define WQ_WORDS (3 * WQ_CAP)   // LDS words per wavefront
+
+__device__ __forceinline__ void wq_push(WaveQueue& wq, bool k0, float e0, uint32_t p0, bool k1, float e1, uint32_t p1,
+                                        uint32_t tag) {
+    const uint64_t m0 = __ballot(k0), m1 = __ballot(k1);
+    if ((m0 | m1) == 0) return;
+    const uint64_t below = (1ull << (threadIdx.x & 63)) - 1ull;
+    const uint32_t n0 = __popcll(m0);
+    if (k0) {
+        const uint32_t s = wq.n + __popcll(m0 & below);
+        wq.est[s] = __float_as_uint(e0); wq.pos[s] = p0; wq.tag[s] = tag;
+    }
+    if (k1) {
+        const uint32_t s = wq.n + n0 + __popcll(m1 & below);
+        wq.est[s] = __float_as_uint(e1); wq.pos[s] = p1; wq.tag[s] = tag;
+    }
+    wq.n += n0 + __popcll(m1);
+}
+
+// qc[x], cnt[x], cap[x]: buffer, counter and capacity of query slot x of the current unit
+template <int G>
+__device__ __forceinline__ void wq_flush(WaveQueue& wq, uint2* const (&qc)[G], uint32_t* const (&cnt)[G],
+                                         const uint32_t (&cap)[G]) {
+    const int lane = threadIdx.x & 63;
+    const uint64_t below = (1ull << lane) - 1ull;
+    for (uint32_t base = 0; base < wq.n; base += 64) {
+        const uint32_t i = base + lane;
+        const bool valid = i < wq.n;
+        const uint32_t tag = valid ? wq.tag[i] : 0xFFFFFFFFu;
+        uint32_t rank = 0, mine = 0;
+        uint32_t* my_cnt = cnt[0];
+#pragma unroll
+        for (int x = 0; x < G; ++x) {
+            const uint64_t bx = __ballot(tag == (uint32_t)x);
+            if (tag == (uint32_t)x) rank = __popcll(bx & below);
+            if (lane == x) { mine = __popcll(bx); my_cnt = cnt[x]; }
+        }
+        uint32_t got = 0;
+        if (lane < G && mine) got = atomicAdd(my_cnt, mine);   // the G atomics are in flight together
+#pragma unroll
+        for (int x = 0; x < G; ++x) {
+            const uint32_t gx = __shfl(got, x, 64);
+            if (tag == (uint32_t)x) {
+                const uint32_t slot = gx + rank;
+                if (slot < cap[x]) qc[x][slot] = make_uint2(wq.est[i], wq.pos[i]);
+            }
+        }
+    }
+    wq.n = 0;
+}
+
 template <int M>
 __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict__ codes,
                                                        const float* __restrict__ lut,
@@ -361,7 +427,12 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                                                        uint32_t* __restrict__ cand_cnt, CandLayout lay,
                                                        const uint32_t* __restrict__ tau_id,
                                                        const int32_t* __restrict__ ids) {
-    extern __shared__ float s_lut[];   // M * 256 floats
+    extern __shared__ float s_lut[];   // M * 256 floats, then the wavefronts' append queues
+    WaveQueue wq;
+    wq.est = reinterpret_cast<uint32_t*>(s_lut) + M * IVFR_KS + (threadIdx.x >> 6) * WQ_WORDS;
+    wq.pos = wq.est + WQ_CAP;
+    wq.tag = wq.pos + WQ_CAP;
+    wq.n = 0;
     const uint32_t total = blkpre[P];
     const uint32_t G = gridDim.x, g = blockIdx.x;
     uint32_t b = (uint32_t)(((uint64_t)total * g) / G);
@@ -385,9 +456,10 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
         const float t = tau[q];
         // with tau_id the bound is the 64-bit key (estimate, id): an estimate equal to tau passes only up to that id
         const uint32_t t_id = tau_id ? tau_id[q] : 0xFFFFFFFFu;
-        uint2* qc = cand + lay.base(q);
-        const uint32_t cap = lay.cap(q);
-        uint32_t* cnt = cand_cnt + q;
+        const bool keep_all = t == INFINITY;
+        uint2* const qc[1] = {cand + lay.base(q)};
+        const uint32_t cap[1] = {lay.cap(q)};
+        uint32_t* const cnt[1] = {cand_cnt + q};
         __syncthreads();   // previous pair's table no longer in use
         {
             const float4* src = reinterpret_cast<const float4*>(lut + pid * M * IVFR_KS);
@@ -428,9 +500,15 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                     if (k0 && est0 == t) k0 = (uint32_t)ids[start + e0[u]] <= t_id;
                     if (k1 && est1 == t) k1 = (uint32_t)ids[start + e0[u] + 1] <= t_id;
                 }
-                append_records(k0, est0, start + e0[u], k1, est1, start + e0[u] + 1, qc, cnt, cap);
+                if (keep_all) {   // nothing is filtered: a full wavefront of records per pass, one atomic for all of them
+                    append_records(k0, est0, start + e0[u], k1, est1, start + e0[u] + 1, qc[0], cnt[0], cap[0]);
+                } else {
+                    if (wq.n > WQ_CAP - 128) wq_flush<1>(wq, qc, cnt, cap);
+                    wq_push(wq, k0, est0, start + e0[u], k1, est1, start + e0[u] + 1, 0u);
+                }
             }
         }
+        wq_flush<1>(wq, qc, cnt, cap);   // the queue belongs to this pair's query
         b = stop;
     }
 }
@@ -440,7 +518,7 @@ static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t*
                          const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau,
                          uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st,
                          const uint32_t* tau_id) {
-    size_t lds = (size_t)M * IVFR_KS * sizeof(float);
+    size_t lds = (size_t)(M * IVFR_KS + 4 * WQ_WORDS) * sizeof(float);
     static bool attr_done = false;
     if (!attr_done && lds > 48 * 1024) {
         IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_kernel<M>),
@@ -676,6 +754,11 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
     typedef typename LutVec<G>::type vec_t;
     extern __shared__ float s_raw[];
     vec_t* s_lutv = reinterpret_cast<vec_t*>(s_raw);   // [M * 256] vectors: component x = query x of the unit
+    WaveQueue wq;                                      // behind the tables: the wavefronts' append queues
+    wq.est = reinterpret_cast<uint32_t*>(s_raw) + M * IVFR_KS * G + (threadIdx.x >> 6) * WQ_WORDS;
+    wq.pos = wq.est + WQ_CAP;
+    wq.tag = wq.pos + WQ_CAP;
+    wq.n = 0;
     const uint32_t total = blkpre[nunits];
     const uint32_t NG = gridDim.x, g = blockIdx.x;
     uint32_t b = (uint32_t)(((uint64_t)total * g) / NG);
@@ -763,11 +846,17 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
 #pragma unroll
                 for (int x = 0; x < G; ++x) {
                     const float ea = vget(a0, x) + vget(a1, x), eb = vget(b0, x) + vget(b1, x);
-                    append_records(in0[v] && ea <= t[x], ea, start + e0[v], in1[v] && eb <= t[x], eb, start + e0[v] + 1,
-                                   qc[x], cnt[x], cap[x]);
+                    if (t[x] == INFINITY) {   // nothing is filtered for this query: direct, one atomic per pass
+                        append_records(in0[v], ea, start + e0[v], in1[v], eb, start + e0[v] + 1, qc[x], cnt[x], cap[x]);
+                    } else {
+                        if (wq.n > WQ_CAP - 128) wq_flush<G>(wq, qc, cnt, cap);
+                        wq_push(wq, in0[v] && ea <= t[x], ea, start + e0[v], in1[v] && eb <= t[x], eb,
+                                start + e0[v] + 1, (uint32_t)x);
+                    }
                 }
             }
         }
+        wq_flush<G>(wq, qc, cnt, cap);   // the queue refers to this unit's queries
         b = stop;
     }
 }
@@ -777,7 +866,7 @@ static int launch_shared_mg(const ivfr_index* ix, const float* lut, const uint32
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
                             int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
                             hipStream_t st) {
-    size_t lds = (size_t)M * IVFR_KS * sizeof(float) * G;
+    size_t lds = (size_t)(M * IVFR_KS * G + 4 * WQ_WORDS) * sizeof(float);
     static bool attr_done = false;
     if (!attr_done && lds > 48 * 1024) {
         IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared_kernel<M, G>),
