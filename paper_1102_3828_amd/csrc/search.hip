@@ -76,7 +76,16 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     if (nq == 0) return IVFR_OK;
 
     const int d = p.d, c = p.c, m = p.m;
-    const int B = (int)std::min<int64_t>(nq, ix->batch);
+    // queries per internal batch: the tuning value, lowered so that the per-batch tables (w m KB per query),
+    // the coarse keys (8 c bytes) and the short-list arrays (24 k' bytes) stay below 4 GiB each
+    int64_t B64 = std::min<int64_t>(nq, ix->batch);
+    {
+        const int64_t budget = 4ll << 30;
+        B64 = std::min<int64_t>(B64, std::max<int64_t>(1, budget / ((int64_t)w * p.m * IVFR_KS * 4)));
+        B64 = std::min<int64_t>(B64, std::max<int64_t>(1, budget / ((int64_t)kprime * 24)));
+        B64 = std::min<int64_t>(B64, std::max<int64_t>(1, budget / ((int64_t)p.c * 8)));
+    }
+    const int B = (int)B64;
     const int P = B * w;
     // Queries visiting no more than full_limit entries keep them all; the others get a candidate
     // buffer for the larger of their sample and min_cap survivors (sized per query by the plan).
