@@ -577,6 +577,25 @@ def test_empty_lists_and_short_results():
     ix.close()
 
 
+def test_visiting_thousands_of_lists_splits_the_batch():
+    """w = c = 8192: the look-up tables of one query take 32 MB, so the 150 queries cannot share one internal
+    batch (the library keeps a batch's tables under 4 GiB); results must not depend on the split."""
+    rng = np.random.default_rng(23)
+    d, c, m, mr, N = 32, 8192, 4, 4, 6000
+    books = orc.Codebooks((rng.normal(size=(c, d)) * 40 + 128).astype(np.float32),
+                          (rng.normal(size=(m, 256, d // m)) * 6).astype(np.float32),
+                          (rng.normal(size=(mr, 256, d // mr))).astype(np.float32))
+    Y = np.clip(rng.normal(128, 40, size=(N, d)), 0, 255).round()
+    index = orc.build_index(Y, np.arange(N), books)
+    X = np.clip(rng.normal(128, 40, size=(150, d)), 0, 255).astype(np.float32)
+    ix = gpu_index_from_oracle(index)
+    ids, dist = ix.search(queries_dev(X), c, 300, 10)
+    assert ix.search_stats()["pairs"] == 150 * c
+    sel = [0, 1, 2, 127, 128, 129, 148, 149]   # both sides of the split (the oracle builds 8192 tables per query)
+    compare_results(ids.cpu().numpy()[sel], dist.cpu().numpy()[sel], X[sel], index, c, 300, 10)
+    ix.close()
+
+
 def test_error_paths():
     import paper_1102_3828_amd as pkg
     torch = _torch()
