@@ -1,16 +1,19 @@
 // Query stage (section 3.2 steps 1-3 on the inverted file of section 3.3): host orchestration.
 //
-// Per internal batch of queries, all on one stream and without host round trips until the end:
-//   coarse distances (MFMA) -> w nearest lists -> plan of (query, list) pairs -> look-up
-//   tables (MFMA) -> uniform sample of the visited entries -> per-query bound tau on the k'-th
-//   smallest estimate -> scan of every visited entry keeping estimates <= tau -> exact k'
-//   smallest of the survivors -> re-rank -> k smallest.
+// Per internal batch of queries:
+//   coarse distances (MFMA) -> w nearest lists -> plan of (query, list) pairs, grouped by list into
+//   units of queries that share a pass -> look-up tables (MFMA) -> sample of the visited entries
+//   (the same leading fraction of every visited list) -> per-query bound tau on the k'-th smallest
+//   estimate -> scan of every visited entry keeping estimates <= tau (four launches side by side:
+//   units of eight, four, two queries and single pairs) -> exact k' smallest of the survivors ->
+//   re-rank -> k smallest.
+// The host waits twice per batch: for the plan's sizes (candidate pool, launch shapes) and at the end.
 // tau is a statistical bound (the r-th smallest sampled estimate, r chosen five standard
 // deviations above the expected number of true k'-best entries in the sample), so the scan
-// verifies it: a query whose survivors number fewer than k' (bound too tight) or more than its
-// candidate buffer holds (bound too loose) - both reported by the device counter, read back
-// once per batch - is redone through a buffer that holds every visited entry.  Results are
-// therefore exact whatever the sample says; the bound only decides how much is written.
+// verifies it by counting: a query whose survivors overflow its candidate buffer is rescanned
+// with a tightened key bound, one that kept fewer than k' is redone through a buffer that holds
+// every visited entry.  Results are therefore exact whatever the sample says; the bound only
+// decides how much is written.
 #include "ivfr_internal.h"
 
 #include <algorithm>
@@ -46,7 +49,8 @@ struct EventPair {
 };
 }
 
-// Poisson mean of true k'-best entries wanted inside the sample; the sample stride is k' / mu.
+// Smallest Poisson mean of true k'-best entries wanted inside the sample: the sample stride (one entry in
+// `stride` is sampled) never exceeds k' / mu; the plan narrows it when a larger sample pays off.
 #define IVFR_SAMPLE_MU 4
 // Upper limit of a query's sample (entries); beyond it the stride widens and the bound loosens.
 #define IVFR_MAX_SAMPLE 131072u
@@ -100,7 +104,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         const double lo = ix->n_cu * 8.0, hi = 32768.0;
         return (int)(g < lo ? lo : (g > hi ? hi : g));
     };
-    const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 8;   // sample pass, dense fallback
+    const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 8;   // launches whose work is not known yet
 
     // carve the workspace
     Carver cv;
