@@ -311,9 +311,10 @@ int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* p
 // workgroup streams the same number of code bytes whatever the list-length skew, and reloads
 // the pair's table (m KB, LDS) only when its share crosses into the next pair.  A thread
 // loads 16 code bytes per block with one coalesced dwordx4 load.  Estimates <= tau[q] are
-// appended to query q's candidate buffer as (estimate bits, entry position) records through
-// one wavefront-aggregated atomic per 64 lanes; the counter keeps counting past the
-// buffer's capacity so the host can tell an overflow.
+// appended to query q's candidate buffer as (estimate bits, entry position) records, slots
+// reserved by wavefront-aggregated atomics (collected in a small LDS queue first when a
+// filter is active, see below); the counter keeps counting past the buffer's capacity so
+// the host can tell an overflow.
 // ------------------------------------------------------------------------------------------
 template <int M>
 __device__ __forceinline__ float adc_sum(const float* lut, const uint32_t* wds) {
