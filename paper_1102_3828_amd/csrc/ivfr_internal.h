@@ -241,12 +241,14 @@ struct GroupBuffers {
 };
 int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* exact_only, bool use8,
                            const uint32_t* pair_len, const GroupBuffers& gb, hipStream_t st);
+// With lut_scale and exact_only (per query: 1 = keep to fp32), units of four whose queries all allow it run on
+// half-precision tables with an exact re-evaluation, like the units of eight.
 bool ivfr_shared_scan_supported(const ivfr_index* ix);
 bool ivfr_shared8h_supported(const ivfr_index* ix);
 int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
                             int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
-                            hipStream_t st);
+                            hipStream_t st, const float* lut_scale = nullptr, const uint8_t* exact_only = nullptr);
 int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const float* lut_scale,
                               const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
                               const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,

@@ -729,6 +729,29 @@ int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint
     return IVFR_OK;
 }
 
+// Codes of entries e and e+1 of the list that starts at `start` (two M-byte codes = one 16-byte load at
+// M = 8), zeros when the block is not part of the pass or the entry lies beyond the list.
+template <int M>
+__device__ __forceinline__ void load_code_pair(const uint8_t* __restrict__ codes, uint32_t start, uint32_t e, bool live,
+                                               uint32_t len, uint32_t (&w0)[M / 4], uint32_t (&w1)[M / 4]) {
+    if (live && e < len) {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e) * M);
+        if (M == 8) {
+            const uint4 c4 = *reinterpret_cast<const uint4*>(src);
+            w0[0] = c4.x; w0[1] = c4.y; w1[0] = c4.z; w1[1] = c4.w;
+        } else {
+#pragma unroll
+            for (int t2 = 0; t2 < M / 4; ++t2) { w0[t2] = src[t2]; w1[t2] = src[M / 4 + t2]; }
+        }
+    } else {
+#pragma unroll
+        for (int t2 = 0; t2 < M / 4; ++t2) { w0[t2] = 0; w1[t2] = 0; }
+    }
+}
+
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+
 template <int G> struct LutVec;
 template <> struct LutVec<4> { typedef float4 type; };
 template <> struct LutVec<2> { typedef float2 type; };
@@ -742,6 +765,119 @@ __device__ __forceinline__ void vzero(float2& a) { a = make_float2(0.f, 0.f); }
 __device__ __forceinline__ void vload(float4& a, const float* v) { a = make_float4(v[0], v[1], v[2], v[3]); }
 __device__ __forceinline__ void vload(float2& a, const float* v) { a = make_float2(v[0], v[1]); }
 
+
+// One unit of four queries on half-precision tables (the scheme of the units of eight, documented at
+// adc_scan_shared8h_kernel: scaled fp16 tables, packed fp16 sums, an int16 sign test against the rounded-up
+// bounds, and an exact fp32 re-evaluation of the queued candidates, which alone is compared and recorded).
+// Called by all 256 threads after the barrier that retires the previous unit's tables; blocks [b, stop)
+// of the unit whose first block is pb0.  wq's arrays serve as the candidate queue (entry, query mask).
+template <int M>
+__device__ __forceinline__ void half_unit_pass(const uint8_t* __restrict__ codes, const float* __restrict__ lut,
+                                               const float* __restrict__ lut_scale,
+                                               const uint32_t* __restrict__ unit, const int64_t (&pid)[4],
+                                               const float (&t)[4], uint2* const (&qc)[4], uint32_t* const (&cnt)[4],
+                                               const uint32_t (&cap)[4], uint32_t start, uint32_t len, uint32_t b,
+                                               uint32_t stop, uint32_t pb0, float* s_raw, WaveQueue& wq) {
+    half4* s_lut4 = reinterpret_cast<half4*>(s_raw);   // [M * 256] x 4 halves
+    const int tid = threadIdx.x, lane = tid & 63;
+    float sc[4];
+    half4 tsh;
+    short4v tshi;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const bool real = unit[x] != IVFR_NO_PAIR;
+        sc[x] = lut_scale[pid[x]];
+        const float ts = real ? t[x] * sc[x] * (1.f + (M + 1.2f) * 4.8828125e-4f) + 4e-3f : 0.f;
+        tsh[x] = (_Float16)(real ? ts * 1.001f + 1e-4f : 0.f);
+    }
+    tshi = __builtin_bit_cast(short4v, tsh);
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+        if (unit[x] == IVFR_NO_PAIR) tshi[x] = (short)-1;
+    for (int e = tid; e < M * IVFR_KS; e += 256) {
+        half4 h;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) h[x] = (_Float16)(lut[pid[x] * M * IVFR_KS + e] * sc[x]);
+        s_lut4[e] = h;
+    }
+    __syncthreads();
+    auto drain = [&]() {
+        for (uint32_t base = 0; base < wq.n; base += 64) {
+            const uint32_t i = base + lane;
+            if (i < wq.n) {
+                const uint32_t e = wq.est[i], mask = wq.pos[i];
+                uint32_t wd[M / 4];
+                const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e) * M);
+#pragma unroll
+                for (int t2 = 0; t2 < M / 4; ++t2) wd[t2] = src[t2];
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    if ((mask >> x) & 1u) {
+                        const float est = adc_sum<M>(lut + pid[x] * M * IVFR_KS, wd);
+                        if (est <= t[x]) {
+                            const uint32_t slot = atomicAdd(cnt[x], 1u);
+                            if (slot < cap[x]) qc[x][slot] = make_uint2(__float_as_uint(est), start + e);
+                        }
+                    }
+            }
+        }
+        wq.n = 0;
+    };
+    for (uint32_t bb = b; bb < stop; bb += 2) {
+        uint32_t wds[2][2][M / 4];
+        uint32_t e0[2];
+        bool in0[2], in1[2];
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            e0[v] = (bb + v - pb0) * IVFR_BLOCK + 2u * tid;
+            in0[v] = bb + v < stop && e0[v] < len;
+            in1[v] = bb + v < stop && e0[v] + 1 < len;
+            load_code_pair<M>(codes, start, e0[v], bb + v < stop, len, wds[v][0], wds[v][1]);
+        }
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            half4 ha, hb;
+#pragma unroll
+            for (int t2 = 0; t2 < M / 4; ++t2) {
+                const uint32_t wa = wds[v][0][t2], wb = wds[v][1][t2];
+                const half4* L = s_lut4 + t2 * 4 * IVFR_KS;
+                if (t2 == 0) { ha = L[wa & 0xff]; hb = L[wb & 0xff]; }
+                else { ha += L[wa & 0xff]; hb += L[wb & 0xff]; }
+                ha += L[IVFR_KS + ((wa >> 8) & 0xff)];
+                hb += L[IVFR_KS + ((wb >> 8) & 0xff)];
+                ha += L[2 * IVFR_KS + ((wa >> 16) & 0xff)];
+                hb += L[2 * IVFR_KS + ((wb >> 16) & 0xff)];
+                ha += L[3 * IVFR_KS + (wa >> 24)];
+                hb += L[3 * IVFR_KS + (wb >> 24)];
+            }
+            const short4v da = tshi - __builtin_bit_cast(short4v, ha), db = tshi - __builtin_bit_cast(short4v, hb);
+            const uint2 ua = __builtin_bit_cast(uint2, da), ub = __builtin_bit_cast(uint2, db);
+            const bool none0 = !in0[v] || ((ua.x & ua.y & 0x80008000u) == 0x80008000u);
+            const bool none1 = !in1[v] || ((ub.x & ub.y & 0x80008000u) == 0x80008000u);
+            if (__ballot(!(none0 && none1)) == 0) continue;
+            // bit x: the difference of query x is not negative
+            const uint32_t m0 = none0 ? 0u : (~(((ua.x >> 15) & 1u) | ((ua.x >> 30) & 2u) | ((ua.y >> 13) & 4u) | ((ua.y >> 28) & 8u)) & 0xfu);
+            const uint32_t m1 = none1 ? 0u : (~(((ub.x >> 15) & 1u) | ((ub.x >> 30) & 2u) | ((ub.y >> 13) & 4u) | ((ub.y >> 28) & 8u)) & 0xfu);
+            const uint64_t b0 = __ballot(m0 != 0), b1 = __ballot(m1 != 0);
+            const uint64_t below = (1ull << lane) - 1ull;
+            const uint32_t n0 = __popcll(b0);
+            if (m0) {
+                const uint32_t slot = wq.n + __popcll(b0 & below);
+                wq.est[slot] = e0[v];
+                wq.pos[slot] = m0;
+            }
+            if (m1) {
+                const uint32_t slot = wq.n + n0 + __popcll(b1 & below);
+                wq.est[slot] = e0[v] + 1;
+                wq.pos[slot] = m1;
+            }
+            wq.n += n0 + __popcll(b1);
+            if (wq.n > WQ_CAP - 128) drain();
+        }
+    }
+    drain();
+}
+
 template <int M, int G>
 __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __restrict__ codes,
                                                               const float* __restrict__ lut,
@@ -751,7 +887,9 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
                                                               const uint32_t* __restrict__ unit_pairs, int nunits,
                                                               int w, const float* __restrict__ tau,
                                                               uint2* __restrict__ cand,
-                                                              uint32_t* __restrict__ cand_cnt, CandLayout lay) {
+                                                              uint32_t* __restrict__ cand_cnt, CandLayout lay,
+                                                              const float* __restrict__ lut_scale,
+                                                              const uint8_t* __restrict__ exact_only) {
     typedef typename LutVec<G>::type vec_t;
     extern __shared__ float s_raw[];
     vec_t* s_lutv = reinterpret_cast<vec_t*>(s_raw);   // [M * 256] vectors: component x = query x of the unit
@@ -793,7 +931,24 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
             cnt[x] = cand_cnt + q;
         }
         const uint32_t start = pair_start[pid[0]], len = pair_len[pid[0]];   // the unit's pairs share the list
+        // A unit of four whose queries all pass only a small share of their estimates runs on half-precision
+        // tables with an exact re-evaluation of the few candidates, like the units of eight (see below).
+        bool half_unit = false;
+        if (G == 4 && exact_only != nullptr) {
+            half_unit = true;
+#pragma unroll
+            for (int x = 0; x < G; ++x)
+                if (unit_pairs[(int64_t)u * G + x] != IVFR_NO_PAIR && exact_only[(int)(pid[x] / w)]) half_unit = false;
+        }
         __syncthreads();   // previous unit's tables no longer in use
+        if constexpr (G == 4) {
+            if (half_unit) {
+                half_unit_pass<M>(codes, lut, lut_scale, unit_pairs + (int64_t)u * G, pid, t, qc, cnt, cap, start, len, b,
+                                  stop, pb0, s_raw, wq);
+                b = stop;
+                continue;
+            }
+        }
         for (int e = tid; e < M * IVFR_KS; e += 256) {
             float v[G];
 #pragma unroll
@@ -866,7 +1021,7 @@ template <int M, int G>
 static int launch_shared_mg(const ivfr_index* ix, const float* lut, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
                             int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
-                            hipStream_t st) {
+                            hipStream_t st, const float* lut_scale, const uint8_t* exact_only) {
     size_t lds = (size_t)(M * IVFR_KS * G + 4 * WQ_WORDS) * sizeof(float);
     static bool attr_done = false;
     if (!attr_done && lds > 48 * 1024) {
@@ -875,7 +1030,7 @@ static int launch_shared_mg(const ivfr_index* ix, const float* lut, const uint32
         attr_done = true;
     }
     hipLaunchKernelGGL((adc_scan_shared_kernel<M, G>), dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start,
-                       pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay);
+                       pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, lut_scale, exact_only);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -885,9 +1040,10 @@ bool ivfr_shared_scan_supported(const ivfr_index* ix) { return ix->p.m <= 16; }
 int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
                             int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
-                            hipStream_t st) {
+                            hipStream_t st, const float* lut_scale, const uint8_t* exact_only) {
     if (nunits <= 0) return IVFR_OK;
-#define IVFR_SH_ARGS ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st
+#define IVFR_SH_ARGS \
+    ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st, lut_scale, exact_only
     if (G == 4) {
         switch (ix->p.m) {
             case 4: return launch_shared_mg<4, 4>(IVFR_SH_ARGS);
@@ -928,26 +1084,6 @@ int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const
 // ------------------------------------------------------------------------------------------
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef short short8 __attribute__((ext_vector_type(8)));
-
-// Codes of entries e and e+1 of the list that starts at `start` (two M-byte codes = one 16-byte load at
-// M = 8), zeros when the block is not part of the pass or the entry lies beyond the list.
-template <int M>
-__device__ __forceinline__ void load_code_pair(const uint8_t* __restrict__ codes, uint32_t start, uint32_t e, bool live,
-                                               uint32_t len, uint32_t (&w0)[M / 4], uint32_t (&w1)[M / 4]) {
-    if (live && e < len) {
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e) * M);
-        if (M == 8) {
-            const uint4 c4 = *reinterpret_cast<const uint4*>(src);
-            w0[0] = c4.x; w0[1] = c4.y; w1[0] = c4.z; w1[1] = c4.w;
-        } else {
-#pragma unroll
-            for (int t2 = 0; t2 < M / 4; ++t2) { w0[t2] = src[t2]; w1[t2] = src[M / 4 + t2]; }
-        }
-    } else {
-#pragma unroll
-        for (int t2 = 0; t2 < M / 4; ++t2) { w0[t2] = 0; w1[t2] = 0; }
-    }
-}
 
 // ------------------------------------------------------------------------------------------
 // Sample pass: the first len_s[p] entries of every pair, all estimates kept (the values only), each at its own place

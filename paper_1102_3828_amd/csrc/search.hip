@@ -316,7 +316,8 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED8, false));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED, true, ix->side[0]));
             IVFR_TRY(ivfr_launch_scan_shared(ix, 4, lut, pb.pair_start, pb.len, gb.blk4, gb.unit4_pairs, n_unit4, w,
-                                             tau, cand, cnt, lay, g4, ix->side[0]));
+                                             tau, cand, cnt, lay, g4, ix->side[0], share8 ? lut_scale : nullptr,
+                                             share8 ? pb.exact_only : nullptr));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED, false, ix->side[0]));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED2, true, ix->side[1]));
             IVFR_TRY(ivfr_launch_scan_shared(ix, 2, lut, pb.pair_start, pb.len, gb.blk2, gb.unit2_pairs, n_unit2, w,
