@@ -357,6 +357,32 @@ def main():
                              "peak": LDS_PEAK_GBS, "unit": "GB/s",
                              "frac": (lds_b * code_bytes / (k_ms * 1e-3) / 1e9 / LDS_PEAK_GBS) if k_ms > 0 else 0.0}},
     }
+    if args.sharing != 0:
+        # The same workload with every (query, list) pair scanned on its own (no reuse of a code read between
+        # queries): the HBM-bound form of the scan, three steps outside the timed region.
+        ix.set_list_sharing(0)
+        ix.set_profiling(True)
+        ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
+        pp_ms, pp_codes, pp_wall = 0.0, 0, 0.0
+        for s in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
+            torch.cuda.synchronize()
+            pp_wall += time.perf_counter() - t0
+            pp_ms += ix.stage_times()["scan"]
+            pp_codes += ix.search_stats()["codes_scanned"]
+        ix.set_profiling(False)
+        ix.set_list_sharing(args.sharing)
+        pp_bytes = cfg.m * pp_codes / 3.0
+        pp_gbs = pp_bytes / (pp_ms / 3.0 * 1e-3) / 1e9 if pp_ms > 0 else 0.0
+        key = (cfg.name, "adc_scan_kernel")
+        out["roofline_per_pair"] = {"bound": "hbm", "kernel": "adc_scan_kernel", "achieved": pp_gbs, "peak": HBM_PEAK_GBS,
+                                    "unit": "GB/s", "frac": pp_gbs / HBM_PEAK_GBS,
+                                    "traffic": (pp_bytes * MEASURED_TRAFFIC_RATIO[key]
+                                                if key in MEASURED_TRAFFIC_RATIO and plain else None),
+                                    "algorithmic_bytes_per_launch": pp_bytes, "avg_launch_ms": pp_ms / 3.0,
+                                    "ms_per_step": 1e3 * pp_wall / 3.0, "list_sharing_mode": 0}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ix, cfg, queries_u8, g_ids)
     ix.close()
