@@ -596,6 +596,47 @@ def test_visiting_thousands_of_lists_splits_the_batch():
     ix.close()
 
 
+def _random_case(seed):
+    """Seeded pick of a valid shape: d a multiple of 8; m, m' bytes with sub-vectors of 1..32 dimensions."""
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([8, 16, 32, 64, 128]))
+    ms = [m for m in (4, 8, 16, 32, 64) if d % m == 0 and d // m in (1, 2, 4, 8, 16, 32)]
+    mrs = [0] + ms
+    m, mr = int(rng.choice(ms)), int(rng.choice(mrs))
+    c = int(rng.choice([1, 2, 3, 7, 16, 33]))
+    N = int(rng.integers(1, 4000))
+    w = int(rng.integers(1, c + 1))
+    kp = int(rng.choice([1, 5, 40, 300, 5000]))
+    k = int(rng.integers(1, min(kp, 200) + 1))
+    nq = int(rng.integers(1, 20))
+    return dict(d=d, m=m, mr=mr, c=c, N=N, w=w, kp=kp, k=k, nq=nq)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shapes(seed):
+    """Seeded random shapes: odd dimensions and code sizes, more lists than vectors, k' above and below what is
+    visited, every list-sharing mode and both the filtered and the keep-everything paths."""
+    cs = _random_case(seed)
+    log("random case", seed, cs)
+    rng = np.random.default_rng(2000 + seed)
+    d, c, m, mr = cs["d"], cs["c"], cs["m"], cs["mr"]
+    books = orc.Codebooks((rng.normal(size=(c, d)) * 30 + 128).astype(np.float32),
+                          (rng.normal(size=(m, 256, d // m)) * 8).astype(np.float32),
+                          (rng.normal(size=(mr, 256, d // mr)) * 2).astype(np.float32) if mr else None)
+    Y = np.clip(rng.normal(128, 35, size=(cs["N"], d)), 0, 255).round()
+    index = orc.build_index(Y, np.arange(cs["N"]), books)
+    X = np.clip(rng.normal(128, 35, size=(cs["nq"], d)), 0, 255).astype(np.float32)
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    for mode, full_mult in ((2, 8), (1, 1), (0, 1)):
+        ix.set_list_sharing(mode)
+        ix.set_tuning(full_mult=full_mult)
+        ids, dist = ix.search(xq, cs["w"], cs["kp"], cs["k"])
+        exact, excused = compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, index, cs["w"], cs["kp"], cs["k"])
+        assert excused <= max(2, exact // 50)
+    ix.close()
+
+
 def test_error_paths():
     import paper_1102_3828_amd as pkg
     torch = _torch()
