@@ -41,8 +41,10 @@ typedef struct ivfr_index ivfr_index;   /* opaque */
 typedef struct {
     int32_t d;         /* vector dimension; multiple of 8                                   */
     int32_t c;         /* coarse centroids = inverted lists (section 3.3)                   */
-    int32_t m;         /* bytes of the first-stage code; d % m == 0, m % 4 == 0             */
-    int32_t m_refine;  /* bytes of the refinement code m'; 0 = plain IVFADC; d % m' == 0    */
+    int32_t m;         /* bytes of the first-stage code: 4, 8, 16, 32 or 64; d/m a power of
+                          two, at most 32                                                    */
+    int32_t m_refine;  /* bytes of the refinement code m'; 0 = plain IVFADC; else a multiple
+                          of 4 with d/m' a power of two, at most 32                          */
     int32_t device;    /* HIP device ordinal                                                */
 } ivfr_params;
 
