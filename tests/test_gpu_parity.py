@@ -266,6 +266,11 @@ def _full_size_case(name, n_check, **override):
     gi, gd = g_ids.cpu().numpy(), g_dist.cpu().numpy()
     assert (np.diff(gd, axis=1) >= 0).all() and (gi >= 0).all() and (gi < cfg.N).all()
     assert all(len(set(r.tolist())) == cfg.k for r in gi[:50])
+    # every (query, list) pair scanned on its own must give the same bits for the whole batch
+    ix.set_list_sharing(0)
+    p_ids, p_dist = ix.search(q_u8.float().contiguous(), cfg.w, cfg.kprime, cfg.k)
+    assert np.array_equal(p_ids.cpu().numpy(), gi) and np.array_equal(p_dist.cpu().numpy(), gd)
+    ix.set_list_sharing(2)
     log(name, "export")
     coarse, pq, rq = ix.get_codebooks()
     offsets, ids, codes, rcodes = ix.export()
