@@ -145,7 +145,9 @@ int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int3
                     int32_t scan_groups);
 
 /* Per-stage GPU time of the most recent search call, in milliseconds, measured with HIP events
- * on the search stream (recorded only after ivfr_set_profiling(index, 1)).  ms: host double
+ * on the streams the kernels run on.  ivfr_set_profiling(index, level): 0 = off (default), 1 = only the
+ * list-scan launches are timed (the IVFR_STAGE_SCAN* stages; about 0.03 ms of host time per batch), 2 = every
+ * stage (about 0.1 ms per batch).  ms: host double
  * [IVFR_N_STAGES], indexed by IVFR_STAGE_*; scan_launches: launches of the list-scan kernels
  * (the IVFR_STAGE_SCAN* stages are exactly those launches), may be NULL. */
 #define IVFR_STAGE_COARSE    0   /* query norms + coarse distance GEMM                        */

@@ -207,8 +207,10 @@ class Index:
     def set_tuning(self, full_mult=0, cap_mult=0, min_cap=0, batch=0, scan_groups=0):
         _check(lib.ivfr_set_tuning(self._h, full_mult, cap_mult, min_cap, batch, scan_groups))
 
-    def set_profiling(self, enable=True):
-        _check(lib.ivfr_set_profiling(self._h, 1 if enable else 0))
+    def set_profiling(self, level=2):
+        """0 / False = off, 1 = time the list-scan launches only, 2 / True = time every stage."""
+        level = 2 if level is True else (0 if level is False else int(level))
+        _check(lib.ivfr_set_profiling(self._h, level))
 
     STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared", "scan_shared2", "scan_shared8")
 

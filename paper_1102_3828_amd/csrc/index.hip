@@ -133,6 +133,8 @@ extern "C" int ivfr_destroy(ivfr_index* ix) {
         if (ix->ev_join[i]) (void)hipEventDestroy(ix->ev_join[i]);
     }
     if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
+    for (hipEvent_t e : ix->prof_events) (void)hipEventDestroy(e);
+    ix->prof_events.clear();
     delete ix;
     return IVFR_OK;
 }
@@ -517,7 +519,8 @@ extern "C" int ivfr_set_tuning(ivfr_index* ix, int32_t full_mult, int32_t cap_mu
 
 extern "C" int ivfr_set_profiling(ivfr_index* ix, int32_t enable) {
     IVFR_REQUIRE(ix, "ivfr_set_profiling: null index");
-    ix->profiling = enable != 0;
+    IVFR_REQUIRE(enable >= 0 && enable <= 2, "profiling level %d must be 0, 1 or 2", enable);
+    ix->profiling = enable;
     return IVFR_OK;
 }
 

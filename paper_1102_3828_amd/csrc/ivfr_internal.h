@@ -125,7 +125,8 @@ struct ivfr_index {
 
     // stats of the last search
     int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0, st_shared8_codes = 0, st_retries = 0;
-    bool profiling = false;
+    int profiling = 0;   // 0 off, 1 list-scan launches only, 2 every stage
+    std::vector<hipEvent_t> prof_events;   // timing events, created once and reused by every search call
     double prof_ms[IVFR_N_STAGES] = {0};
     int prof_scan_launches = 0;
     int n_cu = 256;

@@ -217,13 +217,22 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const bool share8 = share && ix->share_lists >= 2 && ivfr_shared8h_supported(ix);
 
     std::vector<EventPair> events;
+    size_t ev_used = 0;   // events of the index's pool taken by this call
     auto mark_on = [&](int kind, bool begin, hipStream_t s) -> int {
-        if (!ix->profiling) return IVFR_OK;
+        const bool is_scan = kind == IVFR_STAGE_SCAN || kind == IVFR_STAGE_SCAN_SHARED ||
+                             kind == IVFR_STAGE_SCAN_SHARED2 || kind == IVFR_STAGE_SCAN_SHARED8;
+        if (ix->profiling == 0 || (ix->profiling == 1 && !is_scan)) return IVFR_OK;
         if (begin) {
+            while (ix->prof_events.size() < ev_used + 2) {
+                hipEvent_t e = nullptr;
+                IVFR_HIP(hipEventCreate(&e));
+                ix->prof_events.push_back(e);
+            }
             EventPair ep;
             ep.kind = kind;
-            IVFR_HIP(hipEventCreate(&ep.a));
-            IVFR_HIP(hipEventCreate(&ep.b));
+            ep.a = ix->prof_events[ev_used];
+            ep.b = ix->prof_events[ev_used + 1];
+            ev_used += 2;
             IVFR_HIP(hipEventRecord(ep.a, s));
             events.push_back(ep);
         } else {
@@ -451,8 +460,6 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
                 ep.kind == IVFR_STAGE_SCAN_SHARED8)
                 ix->prof_scan_launches += 1;
         }
-        (void)hipEventDestroy(ep.a);
-        (void)hipEventDestroy(ep.b);
     }
     return IVFR_OK;
 }
