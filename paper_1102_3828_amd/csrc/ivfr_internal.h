@@ -204,6 +204,7 @@ struct PlanBuffers {
     uint8_t* exact_only;         // [nq] 1 = too large a share of the estimates will pass the bound for fp16 units
     unsigned long long* totals;  // [2]: [0] = sum of sq, [1] = records in the candidate pool
 };
+// pb.totals must be zero on entry.
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
                      uint32_t stride_k, uint32_t min_cap, uint32_t max_sample, int kprime, float half_frac,
                      const PlanBuffers& pb, hipStream_t st);
@@ -240,6 +241,7 @@ struct GroupBuffers {
     uint32_t* blklo;        // ... over single pairs
     unsigned long long* work;  // [5] list entries streamed; estimates computed by units of eight, four, two, singles
 };
+// On entry gb.list_np and gb.work must be zero and the unit8 / unit4 arrays filled with IVFR_NO_PAIR.
 int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* exact_only, bool use8,
                            const uint32_t* pair_len, const GroupBuffers& gb, hipStream_t st);
 // With lut_scale and exact_only (per query: 1 = keep to fp32), units of four whose queries all allow it run on

@@ -169,7 +169,6 @@ __global__ __launch_bounds__(256) void plan_expand_kernel(int P, int w, PlanBuff
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
                      uint32_t stride_k, uint32_t min_cap, uint32_t max_sample, int kprime, float half_frac,
                      const PlanBuffers& pb, hipStream_t st) {
-    IVFR_HIP(hipMemsetAsync(pb.totals, 0, 2 * sizeof(unsigned long long), st));
     hipLaunchKernelGGL(plan_pairs_kernel, dim3((nq + 3) / 4), dim3(256), 0, st, probe, nq, w, ix->list_start,
                        ix->list_len, full_limit, stride_k, min_cap, max_sample, kprime, half_frac, pb);
     IVFR_HIP(hipGetLastError());
@@ -716,14 +715,11 @@ __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* 
 
 int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* exact_only, bool use8,
                            const uint32_t* pair_len, const GroupBuffers& gb, hipStream_t st) {
-    IVFR_HIP(hipMemsetAsync(gb.list_np, 0, 2 * (size_t)c * sizeof(uint32_t), st));
-    IVFR_HIP(hipMemsetAsync(gb.unit8_pairs, 0xff, gb.unit_bytes, st));   // unit8 and unit4 arrays are contiguous
     hipLaunchKernelGGL(group_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0,
                        gb.list_np);
     hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, gb.list_np, gb.gpre, gb.cur, gb.counts);
     hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0, c,
                        gb.list_np, gb.gpre, gb.cur, gb.unit8_pairs, gb.unit4_pairs, gb.unit2_pairs, gb.lo_pairs);
-    IVFR_HIP(hipMemsetAsync(gb.work, 0, sizeof(unsigned long long), st));
     hipLaunchKernelGGL(group_scan_units_kernel, dim3(4), dim3(1024), 0, st, gb.counts, gb, pair_len);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;

@@ -28,6 +28,15 @@ int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, i
                        const uint32_t* short_pos, const int32_t* short_n, uint64_t* keys, float* refined_out,
                        int32_t* ids_out, hipStream_t st);
 
+// Start of a batch: clear the counters (one contiguous block), mark every unit slot empty, tau = +inf.
+__global__ __launch_bounds__(256) void batch_reset_kernel(uint32_t* zero, size_t zero_words, uint32_t* ones,
+                                                          size_t ones_words, float* tau, int nb) {
+    const size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x, stride = (size_t)gridDim.x * 256;
+    for (size_t i = i0; i < zero_words; i += stride) zero[i] = 0u;
+    for (size_t i = i0; i < ones_words; i += stride) ones[i] = 0xFFFFFFFFu;
+    for (size_t i = i0; i < (size_t)nb; i += stride) tau[i] = INFINITY;
+}
+
 __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -126,24 +135,20 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_sq = cv.take<unsigned long long>(B);
     const size_t o_fully = cv.take<uint8_t>(B);
     const size_t o_exonly = cv.take<uint8_t>(B);
-    const size_t o_totals = cv.take<unsigned long long>(2);
     const size_t o_capq = cv.take<uint32_t>(B);
     const size_t o_coff = cv.take<unsigned long long>(B);
     const size_t o_lut = cv.take<float>((size_t)P * m * IVFR_KS);
-    const size_t o_cnt = cv.take<uint32_t>(B);
     const size_t o_tau = cv.take<float>(B);
     const size_t o_tauid = cv.take<uint32_t>(B);
     const size_t o_spos = cv.take<uint32_t>((size_t)B * kprime);
     const size_t o_sest = cv.take<float>((size_t)B * kprime);
     const size_t o_sn = cv.take<int32_t>(B);
     const size_t o_over = cv.take<int32_t>(B);
-    const size_t o_overtot = cv.take<int32_t>(4);
     const size_t o_rkeys = cv.take<uint64_t>((size_t)B * kprime);
     const size_t o_sref = cv.take<float>((size_t)B * kprime);
     const size_t o_sids = cv.take<int32_t>((size_t)B * kprime);
     const size_t o_dpre = cv.take<uint32_t>((size_t)w + 1);
     const size_t o_lscale = cv.take<float>(P);
-    const size_t o_gnp = cv.take<uint32_t>(2 * (size_t)c);
     const size_t o_gpre = cv.take<uint32_t>(4 * (size_t)c);
     const size_t o_gcur = cv.take<uint32_t>(2 * (size_t)c);
     const size_t o_gcounts = cv.take<uint32_t>(4);
@@ -156,7 +161,14 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_gblk4 = cv.take<uint32_t>((size_t)P / 4 + c + 2);
     const size_t o_gblk2 = cv.take<uint32_t>((size_t)c + 2);
     const size_t o_gblklo = cv.take<uint32_t>((size_t)c + 2);
+    // cleared by one kernel at the start of every batch: plan totals, unit work totals, failed-filter count,
+    // candidate counters, pairs per list
+    const size_t o_totals = cv.take<unsigned long long>(2);
     const size_t o_gwork = cv.take<unsigned long long>(6);
+    const size_t o_overtot = cv.take<int32_t>(4);
+    const size_t o_cnt = cv.take<uint32_t>(B);
+    const size_t o_gnp = cv.take<uint32_t>(2 * (size_t)c);
+    const size_t zero_words = (cv.off - o_totals + 3) / 4;
     IVFR_TRY(ix->search_ws.reserve(cv.off + 256));
     char* ws = ix->search_ws.as<char>();
     float* xnorm = reinterpret_cast<float*>(ws + o_xnorm);
@@ -246,6 +258,8 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         const int nb = (int)std::min<int64_t>(B, nq - q0);
         const int Pb = nb * w;
         const float* X = queries + q0 * d;
+        hipLaunchKernelGGL(batch_reset_kernel, dim3(64), dim3(256), 0, st, reinterpret_cast<uint32_t*>(ws + o_totals),
+                           zero_words, gb.unit8_pairs, share ? gb.unit_bytes / 4 : (size_t)0, tau, nb);
         // visited lists: the w nearest coarse centroids
         IVFR_TRY(mark(IVFR_STAGE_COARSE, true));
         IVFR_TRY(ivfr_launch_row_norms(X, nb, d, xnorm, st));
@@ -300,17 +314,14 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         uint2* cand = ix->cand_ws.as<uint2>();
         // uniform sample of the visited entries -> bound tau on the k'-th smallest estimate
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, true));
-        IVFR_HIP(hipMemsetAsync(overtot, 0, 4 * sizeof(int32_t), st));
-        hipLaunchKernelGGL(fill_f32_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, tau, (int64_t)nb, INFINITY);
         IVFR_TRY(ivfr_launch_sample_scan(ix, lut, pb.pair_start, pb.len_s, pb.blkpre_s, pb.items_s, n_sample_chunks,
                                          pb.soff, w, cand, lay, st));
-        {
+        if (n_sample_chunks > 0) {   // else every query of the batch keeps everything: tau stays +inf
             // the sample of query q is nsample[q] bare estimates at the start of its buffer
             SelectArgs a;
             a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = pb.nsample; a.lay = lay;
             IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, 0, pb.fully, tau, nullptr, st, true));
         }
-        IVFR_HIP(hipMemsetAsync(cnt, 0, (size_t)nb * sizeof(uint32_t), st));
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
         // scan of every visited entry, keeping estimates <= tau
         if (share) {
