@@ -1161,6 +1161,9 @@ int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32
 #undef IVFR_SAMPLE_ARGS
 }
 
+// Threads per workgroup of the half-precision scan of eight: eight wavefronts share one 32 KB set of tables,
+// three workgroups (24 wavefronts) fit a compute unit; measured best against 256 and 1024.
+#define H8_T 512
 #define Q8H_CAP 192   // queued candidates per wavefront (two LDS words each)
 
 // bit x set when 16-bit lane x of the four words is not negative (lane 0 = low half of u.x)
@@ -1171,7 +1174,7 @@ __device__ __forceinline__ uint32_t sign_free_mask(uint4 u) {
 }
 
 template <int M>
-__global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* __restrict__ codes,
+__global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* __restrict__ codes,
                                                                 const float* __restrict__ lut,
                                                                 const float* __restrict__ lut_scale,
                                                                 const uint32_t* __restrict__ pair_start,
@@ -1186,7 +1189,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
     // behind the tables: per wavefront a queue of Q8H_CAP (entry, query mask) candidates, then the unit's pairs and bounds
     uint32_t* q_entry = reinterpret_cast<uint32_t*>(s_raw) + M * IVFR_KS * 4 + (threadIdx.x >> 6) * (2 * Q8H_CAP);
     uint32_t* q_mask = q_entry + Q8H_CAP;
-    uint32_t* s_pid = reinterpret_cast<uint32_t*>(s_raw) + M * IVFR_KS * 4 + 4 * (2 * Q8H_CAP);
+    uint32_t* s_pid = reinterpret_cast<uint32_t*>(s_raw) + M * IVFR_KS * 4 + (H8_T / 64) * (2 * Q8H_CAP);
     float* s_tau = reinterpret_cast<float*>(s_pid + 8);
     const uint32_t total = blkpre[nunits];
     const uint32_t NG = gridDim.x, g = blockIdx.x;
@@ -1258,23 +1261,25 @@ __global__ __launch_bounds__(256) void adc_scan_shared8h_kernel(const uint8_t* _
             s_pid[tid] = raw != IVFR_NO_PAIR ? raw : unit_pairs[(int64_t)u * 8];
             s_tau[tid] = raw != IVFR_NO_PAIR ? tau[(int)(raw / (uint32_t)w)] : -1.f;
         }
-        for (int e = tid; e < M * IVFR_KS; e += 256) {
+        for (int e = tid; e < M * IVFR_KS; e += H8_T) {
             half8 h;
 #pragma unroll
             for (int x = 0; x < 8; ++x) h[x] = (_Float16)(lut[pid[x] * M * IVFR_KS + e] * sc[x]);
             s_lut8[e] = h;
         }
         __syncthreads();
-        for (uint32_t bb = b; bb < stop; bb += 2) {
+        constexpr uint32_t BPV = H8_T / 256;   // blocks covered by the workgroup per v
+        for (uint32_t bb = b; bb < stop; bb += 2 * BPV) {
             uint32_t wds[2][2][M / 4];
             uint32_t e0[2];
             bool in0[2], in1[2];
 #pragma unroll
             for (int v = 0; v < 2; ++v) {
-                e0[v] = (bb + v - pb0) * IVFR_BLOCK + 2u * tid;
-                in0[v] = bb + v < stop && e0[v] < len;
-                in1[v] = bb + v < stop && e0[v] + 1 < len;
-                load_code_pair<M>(codes, start, e0[v], bb + v < stop, len, wds[v][0], wds[v][1]);
+                const uint32_t blk = bb + v * BPV + (uint32_t)(tid >> 8);
+                e0[v] = (blk - pb0) * IVFR_BLOCK + 2u * (uint32_t)(tid & 255);
+                in0[v] = blk < stop && e0[v] < len;
+                in1[v] = blk < stop && e0[v] + 1 < len;
+                load_code_pair<M>(codes, start, e0[v], blk < stop, len, wds[v][0], wds[v][1]);
             }
 #pragma unroll
             for (int v = 0; v < 2; ++v) {
@@ -1329,14 +1334,14 @@ static int launch_shared8h_m(const ivfr_index* ix, const float* lut, const float
                              const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
                              const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,
                              uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
-    size_t lds = (size_t)M * IVFR_KS * 16 + 4 * 2 * Q8H_CAP * sizeof(uint32_t) + 16 * sizeof(uint32_t);
+    size_t lds = (size_t)M * IVFR_KS * 16 + (H8_T / 64) * 2 * Q8H_CAP * sizeof(uint32_t) + 16 * sizeof(uint32_t);
     static bool attr_done = false;
     if (!attr_done && lds > 48 * 1024) {
         IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_done = true;
     }
-    hipLaunchKernelGGL(adc_scan_shared8h_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, lut_scale,
+    hipLaunchKernelGGL(adc_scan_shared8h_kernel<M>, dim3(groups), dim3(H8_T), lds, st, ix->codes, lut, lut_scale,
                        pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;

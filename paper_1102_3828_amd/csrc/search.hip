@@ -106,7 +106,8 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const uint32_t full_limit = (uint32_t)std::min<int64_t>((int64_t)ix->full_mult * kprime, 1ll << 30);
     const uint32_t stride_k = (uint32_t)std::max(1, kprime / IVFR_SAMPLE_MU);
     // Workgroups per scan launch: every group takes an equal share of the launch's 512-entry blocks.  About
-    // 128 blocks per group (64 for the narrower kernels) balances the tail against the per-group set-up.
+    // 128 blocks per group of 256 threads (256 for the 512-thread scan of eight, 64 for the narrower kernels)
+    // balances the tail against the per-group set-up.
     auto pick_groups = [&](double entries, int blocks_per_group) -> int {
         if (ix->scan_groups > 0) return ix->scan_groups;
         double g = entries / (double)IVFR_BLOCK / blocks_per_group;
@@ -299,7 +300,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
             n_unit4 = ix->h_status[9];
             n_unit2 = ix->h_status[10];
             n_lo = ix->h_status[11];
-            g8 = pick_groups((double)gw[1] / 8.0, 128);
+            g8 = pick_groups((double)gw[1] / 8.0, 256);
             g4 = pick_groups((double)gw[2] / 4.0, 128);
             g2 = pick_groups((double)gw[3] / 2.0, 64);
             g1 = pick_groups((double)gw[4], 64);
