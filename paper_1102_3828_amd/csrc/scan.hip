@@ -315,6 +315,14 @@ int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* p
 // filter is active, see below); the counter keeps counting past the buffer's capacity so
 // the host can tell an overflow.
 // ------------------------------------------------------------------------------------------
+
+// Workgroups are dealt to the eight XCDs (each with its own L2) round-robin by blockIdx.  Giving the
+// workgroups of one XCD a contiguous eighth of the block stream keeps neighbours in the stream - which
+// work on the same pair or unit and read the same tables - behind the same L2.
+__device__ __forceinline__ uint32_t xcd_share_index(uint32_t block, uint32_t groups) {
+    return (groups & 7u) ? block : (block & 7u) * (groups >> 3) + (block >> 3);
+}
+
 template <int M>
 __device__ __forceinline__ float adc_sum(const float* lut, const uint32_t* wds) {
     float s0 = 0.f, s1 = 0.f;
@@ -434,7 +442,7 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
     wq.tag = wq.pos + WQ_CAP;
     wq.n = 0;
     const uint32_t total = blkpre[P];
-    const uint32_t G = gridDim.x, g = blockIdx.x;
+    const uint32_t G = gridDim.x, g = xcd_share_index(blockIdx.x, gridDim.x);
     uint32_t b = (uint32_t)(((uint64_t)total * g) / G);
     const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / G);
     if (b >= b_end) return;
@@ -895,7 +903,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
     wq.tag = wq.pos + WQ_CAP;
     wq.n = 0;
     const uint32_t total = blkpre[nunits];
-    const uint32_t NG = gridDim.x, g = blockIdx.x;
+    const uint32_t NG = gridDim.x, g = xcd_share_index(blockIdx.x, gridDim.x);
     uint32_t b = (uint32_t)(((uint64_t)total * g) / NG);
     const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / NG);
     if (b >= b_end) return;
@@ -1192,7 +1200,7 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
     uint32_t* s_pid = reinterpret_cast<uint32_t*>(s_raw) + M * IVFR_KS * 4 + (H8_T / 64) * (2 * Q8H_CAP);
     float* s_tau = reinterpret_cast<float*>(s_pid + 8);
     const uint32_t total = blkpre[nunits];
-    const uint32_t NG = gridDim.x, g = blockIdx.x;
+    const uint32_t NG = gridDim.x, g = xcd_share_index(blockIdx.x, gridDim.x);
     uint32_t b = (uint32_t)(((uint64_t)total * g) / NG);
     const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / NG);
     if (b >= b_end) return;

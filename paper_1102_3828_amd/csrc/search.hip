@@ -112,7 +112,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         if (ix->scan_groups > 0) return ix->scan_groups;
         double g = entries / (double)IVFR_BLOCK / blocks_per_group;
         const double lo = ix->n_cu * 8.0, hi = 32768.0;
-        return (int)(g < lo ? lo : (g > hi ? hi : g));
+        return ((int)(g < lo ? lo : (g > hi ? hi : g)) + 7) & ~7;   // a multiple of the eight XCDs
     };
     const int groups = ix->scan_groups > 0 ? ix->scan_groups : ix->n_cu * 8;   // launches whose work is not known yet
 
