@@ -642,6 +642,25 @@ def test_random_shapes(seed):
     ix.close()
 
 
+def test_search_on_a_callers_stream():
+    """The library enqueues on the stream it is given (here a non-default torch stream) and returns when that
+    stream has drained: same bits as on the default stream."""
+    torch = _torch()
+    wl = tiny_workload(d=64, G=16, N=4000, n_train=2500, n_query=16, c=12, m=8, m_refine=8, iters=3)
+    index, X = wl["index"], wl["X"]
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    torch.cuda.synchronize()
+    ids0, dist0 = ix.search(xq, 5, 150, 12)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ids1, dist1 = ix.search(xq, 5, 150, 12)
+    assert torch.equal(ids0, ids1) and torch.equal(dist0, dist1)
+    ids2, dist2 = ix.search(xq, 5, 150, 12, stream=side.cuda_stream)
+    assert torch.equal(ids0, ids2) and torch.equal(dist0, dist2)
+    ix.close()
+
+
 def test_error_paths():
     import paper_1102_3828_amd as pkg
     torch = _torch()
