@@ -189,6 +189,8 @@ def main():
     ap.add_argument("--m-refine", type=int, default=-1)
     ap.add_argument("--c", type=int, default=0, help="override the number of coarse centroids (1 = exhaustive ADC+R)")
     ap.add_argument("--w", type=int, default=0, help="override the number of lists visited")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="queries per step (default: the workload's 1000); the library's internal batch follows it")
     ap.add_argument("--train-iters", type=int, default=10)
     ap.add_argument("--gt-queries", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -244,6 +246,9 @@ def main():
     if args.per_pair:
         args.sharing = 0
     ix.set_list_sharing(args.sharing)
+    if args.batch:
+        cfg = dataclasses.replace(cfg, batch=args.batch)
+        ix.set_tuning(batch=min(args.batch, 65535))
 
     B = min(cfg.batch, cfg.n_query)
     n_batches = max(1, cfg.n_query // B)

@@ -114,11 +114,11 @@ int ivfr_search_trace(ivfr_index* index, const float* queries, int64_t nq, int32
  *                        the candidate buffer
  *   codes_streamed       list entries read from memory by the scan (< codes_scanned when lists are
  *                        shared between queries)
- *   codes_scanned_shared / _shared2 / _shared8  parts of codes_scanned computed by the shared-list
- *                        scans of four, two and eight queries per pass                              */
+ *   codes_scanned_shared / _shared2 / _shared8 / _shared64  parts of codes_scanned computed by the
+ *                        shared-list scans of four, two, eight and 64 queries per pass              */
 int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
                       int64_t* codes_streamed, int64_t* codes_scanned_shared, int64_t* codes_scanned_shared2,
-                      int64_t* codes_scanned_shared8, int64_t* bound_retries);
+                      int64_t* codes_scanned_shared8, int64_t* bound_retries, int64_t* codes_scanned_shared64);
 
 /* List sharing.  Queries of one internal batch that visit the same list are scanned together: the
  * list's codes are read once and each code byte fetches all the queries' table entries with one
@@ -126,7 +126,11 @@ int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* 
  * of four and of two queries with fp32 tables (16- and 8-byte LDS reads).  mode 2 (default; m <= 16):
  * in addition units of eight queries with half-precision tables; an entry whose half-precision
  * estimate could be within the bound is re-evaluated in fp32 before it is kept, so the recorded
- * estimates, and therefore the results, are bit-identical in all three modes. */
+ * estimates, and therefore the results, are bit-identical in all modes.  mode 3 (m in {4, 8, 16},
+ * sub-vectors of 8, 16 or 32 dimensions, d <= 128; otherwise it acts as mode 2): lists visited by 64 or
+ * more queries of the batch are in addition scanned in units of 64 queries on the matrix cores: the
+ * estimate ||r||^2 - 2 r.y + ||y||^2 of Eq. (5) against the decoded entry y becomes an fp16 contraction
+ * that filters with a rigorous error margin, followed by the same exact fp32 re-evaluation. */
 int ivfr_set_list_sharing(ivfr_index* index, int32_t mode);
 
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
@@ -161,7 +165,8 @@ int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int3
 #define IVFR_STAGE_SCAN_SHARED 8 /* ADC list scan, four queries per pass over a shared list   */
 #define IVFR_STAGE_SCAN_SHARED2 9 /* ADC list scan, two queries per pass over a shared list   */
 #define IVFR_STAGE_SCAN_SHARED8 10 /* ADC list scan, eight queries per pass, fp16 tables      */
-#define IVFR_N_STAGES        11
+#define IVFR_STAGE_SCAN_SHARED64 11 /* ADC list scan, 64 queries per pass on the matrix cores */
+#define IVFR_N_STAGES        12
 int ivfr_set_profiling(ivfr_index* index, int32_t enable);
 int ivfr_stage_times(const ivfr_index* index, double* ms, int32_t* scan_launches);
 

@@ -49,7 +49,7 @@ def _load():
         "ivfr_import": (ctypes.c_int, [vp, i64, vp, vp, vp, vp]),
         "ivfr_search": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp]),
         "ivfr_search_trace": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
-        "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 8),
+        "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 9),
         "ivfr_set_list_sharing": (ctypes.c_int, [vp, i32]),
         "ivfr_set_tuning": (ctypes.c_int, [vp, i32, i32, i32, i32, i32]),
         "ivfr_set_profiling": (ctypes.c_int, [vp, i32]),
@@ -194,14 +194,15 @@ class Index:
         return ids, dist, t
 
     def search_stats(self):
-        v = [ctypes.c_int64() for _ in range(8)]
+        v = [ctypes.c_int64() for _ in range(9)]
         _check(lib.ivfr_search_stats(self._h, *[ctypes.byref(x) for x in v]))
         names = ("codes_scanned", "pairs", "dense_fallbacks", "codes_streamed", "codes_scanned_shared",
-                 "codes_scanned_shared2", "codes_scanned_shared8", "bound_retries")
+                 "codes_scanned_shared2", "codes_scanned_shared8", "bound_retries", "codes_scanned_shared64")
         return dict(zip(names, [x.value for x in v]))
 
     def set_list_sharing(self, mode=2):
-        """0 = per pair; 1 = fp32 units of four / two; 2 = also fp16 units of eight (default)."""
+        """0 = per pair; 1 = fp32 units of four / two; 2 = also fp16 units of eight (default); 3 = also
+        matrix-core units of 64."""
         _check(lib.ivfr_set_list_sharing(self._h, int(mode)))
 
     def set_tuning(self, full_mult=0, cap_mult=0, min_cap=0, batch=0, scan_groups=0):
@@ -212,7 +213,7 @@ class Index:
         level = 2 if level is True else (0 if level is False else int(level))
         _check(lib.ivfr_set_profiling(self._h, level))
 
-    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared", "scan_shared2", "scan_shared8")
+    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared", "scan_shared2", "scan_shared8", "scan_shared64")
 
     def stage_times(self):
         """Per-stage milliseconds of the last search (after set_profiling) and scan launch count."""

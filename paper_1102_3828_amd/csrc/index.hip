@@ -95,7 +95,7 @@ extern "C" int ivfr_create(const ivfr_params* params, ivfr_index** out) {
         hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ix->h_status), 64 * sizeof(int), hipHostMallocDefault);
         if (e != hipSuccess) { ivfr_set_error("pinned host allocation failed"); r = IVFR_ERR_OOM; }
     }
-    for (int i = 0; i < 3 && r == IVFR_OK; ++i) {
+    for (int i = 0; i < 4 && r == IVFR_OK; ++i) {
         if (hipStreamCreateWithFlags(&ix->side[i], hipStreamNonBlocking) != hipSuccess ||
             hipEventCreateWithFlags(&ix->ev_join[i], hipEventDisableTiming) != hipSuccess) {
             ivfr_set_error("stream / event creation failed");
@@ -128,7 +128,7 @@ extern "C" int ivfr_destroy(ivfr_index* ix) {
     dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
     ix->search_ws.release(); ix->cand_ws.release(); ix->encode_ws.release(); ix->dense_ws.release();
     if (ix->h_status) (void)hipHostFree(ix->h_status);
-    for (int i = 0; i < 3; ++i) {
+    for (int i = 0; i < 4; ++i) {
         if (ix->side[i]) (void)hipStreamDestroy(ix->side[i]);
         if (ix->ev_join[i]) (void)hipEventDestroy(ix->ev_join[i]);
     }
@@ -534,7 +534,7 @@ extern "C" int ivfr_stage_times(const ivfr_index* ix, double* ms, int32_t* scan_
 extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, int64_t* pairs, int64_t* dense_fallbacks,
                                  int64_t* codes_streamed, int64_t* codes_scanned_shared,
                                  int64_t* codes_scanned_shared2, int64_t* codes_scanned_shared8,
-                                 int64_t* bound_retries) {
+                                 int64_t* bound_retries, int64_t* codes_scanned_shared64) {
     IVFR_REQUIRE(ix, "ivfr_search_stats: null index");
     if (codes_scanned) *codes_scanned = ix->st_codes;
     if (pairs) *pairs = ix->st_pairs;
@@ -544,12 +544,13 @@ extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, i
     if (codes_scanned_shared2) *codes_scanned_shared2 = ix->st_shared2_codes;
     if (codes_scanned_shared8) *codes_scanned_shared8 = ix->st_shared8_codes;
     if (bound_retries) *bound_retries = ix->st_retries;
+    if (codes_scanned_shared64) *codes_scanned_shared64 = ix->st_shared64_codes;
     return IVFR_OK;
 }
 
 extern "C" int ivfr_set_list_sharing(ivfr_index* ix, int32_t mode) {
     IVFR_REQUIRE(ix, "ivfr_set_list_sharing: null index");
-    IVFR_REQUIRE(mode >= 0 && mode <= 2, "list sharing mode %d must be 0, 1 or 2", mode);
+    IVFR_REQUIRE(mode >= 0 && mode <= 3, "list sharing mode %d must be 0, 1, 2 or 3", mode);
     ix->share_lists = mode;
     return IVFR_OK;
 }

@@ -114,17 +114,17 @@ struct ivfr_index {
 
     // tuning
     int full_mult = 8, cap_mult = 16, batch = 1024, scan_groups = 0;
-    int share_lists = 2;             // 0 = every pair on its own; 1 = fp32 units of four / two; 2 = also fp16 units of eight
+    int share_lists = 2;             // 0 = every pair on its own; 1 = fp32 units of four / two; 2 = also fp16 units of eight; 3 = also matrix-core units of 64
     int min_cap = 8192;
 
     // scratch
     DevBuf search_ws, cand_ws, encode_ws, dense_ws;
     int* h_status = nullptr;         // pinned host word(s) for status read-back
-    hipStream_t side[3] = {nullptr, nullptr, nullptr};   // the small scan launches overlap the large one
-    hipEvent_t ev_fork = nullptr, ev_join[3] = {nullptr, nullptr, nullptr};
+    hipStream_t side[4] = {nullptr, nullptr, nullptr, nullptr};   // the smaller scan launches overlap the large one
+    hipEvent_t ev_fork = nullptr, ev_join[4] = {nullptr, nullptr, nullptr, nullptr};
 
     // stats of the last search
-    int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0, st_shared8_codes = 0, st_retries = 0;
+    int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0, st_shared8_codes = 0, st_retries = 0, st_shared64_codes = 0;
     int profiling = 0;   // 0 off, 1 list-scan launches only, 2 every stage
     std::vector<hipEvent_t> prof_events;   // timing events, created once and reused by every search call
     double prof_ms[IVFR_N_STAGES] = {0};
@@ -227,9 +227,9 @@ int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32
 // Shared scan: pairs of one batch grouped by list into units of eight, four, two and single pairs
 struct GroupBuffers {
     uint32_t* list_np;      // [2c] pairs visiting each list, by class (0 = filtered query, 1 = keeps everything)
-    uint32_t* gpre;         // [4][c] exclusive prefixes of units of eight / four / two / single pairs
+    uint32_t* gpre;         // [5][c] exclusive prefixes of units of eight / four / two / single pairs / units of 64
     uint32_t* cur;          // [2c] fill cursors
-    uint32_t* counts;       // [4] units of eight, four, two, single pairs
+    uint32_t* counts;       // [5] units of eight, four, two, single pairs, units of 64
     uint32_t* unit8_pairs;  // pair ids, eight per unit (0xFFFFFFFF = empty slot); unit4_pairs follows contiguously
     uint32_t* unit4_pairs;  // pair ids, four per unit
     size_t unit_bytes;      // bytes of unit8_pairs + unit4_pairs (cleared to empty before every fill)
@@ -239,10 +239,12 @@ struct GroupBuffers {
     uint32_t* blk4;         // ... of four
     uint32_t* blk2;         // ... of two
     uint32_t* blklo;        // ... over single pairs
-    unsigned long long* work;  // [5] list entries streamed; estimates computed by units of eight, four, two, singles
+    uint32_t* unit64_pairs; // pair ids, 64 per unit (always full)
+    uint32_t* blk64;        // block prefix over units of 64
+    unsigned long long* work;  // [6] list entries streamed; estimates computed by units of eight, four, two, singles, 64
 };
 // On entry gb.list_np and gb.work must be zero and the unit8 / unit4 arrays filled with IVFR_NO_PAIR.
-int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* exact_only, bool use8,
+int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* exact_only, bool use8, bool use64,
                            const uint32_t* pair_len, const GroupBuffers& gb, hipStream_t st);
 // With lut_scale and exact_only (per query: 1 = keep to fp32), units of four whose queries all allow it run on
 // half-precision tables with an exact re-evaluation, like the units of eight.
@@ -256,6 +258,13 @@ int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const floa
                               const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
                               const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,
                               uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st);
+// Units of 64 queries on the matrix cores (fp16 decode x query contraction as the filter, exact fp32 sums for
+// what passes).  queries: the batch's [nq][d] floats; probe: the list of every pair.
+bool ivfr_mfma_scan_supported(const ivfr_index* ix);
+int ivfr_launch_scan_mfma64(const ivfr_index* ix, const float* queries, const int32_t* probe, const float* lut,
+                            const float* lut_scale, const uint32_t* pair_start, const uint32_t* pair_len,
+                            const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits, int w, const float* tau,
+                            uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st);
 
 // Encoding (encode.hip)
 int ivfr_launch_residual(float* X, int64_t n, int d, const float* C, const int32_t* assign, hipStream_t st);

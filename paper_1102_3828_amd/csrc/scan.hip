@@ -585,13 +585,18 @@ __global__ void group_count_kernel(const int32_t* __restrict__ probe, int P, int
     atomicAdd(&list_np[2 * probe[p] + cls], 1u);
 }
 
-// A list visited by nA class-0 and nB class-1 pairs yields: units of eight from the class-0 pairs
+// A list visited by nA class-0 and nB class-1 pairs yields: with use64, units of 64 from every full 64 class-0
+// pairs; units of eight from the other class-0 pairs
 // (a remainder of 5..7 becomes one more unit with empty slots); the other class-0 pairs join the
 // class-1 pairs in a pool of n that gives n/4 units of four (a remainder of 3 becomes one more
 // unit with an empty slot), a remainder of 2 a unit of two, a remainder of 1 a single pair.
-struct ListSplit { uint32_t n8, in8, restA, n4, in4, n2, n1; };
-__device__ __forceinline__ ListSplit split_units(uint32_t nA, uint32_t nB) {
+struct ListSplit { uint32_t n64, in64, n8, in8, restA, n4, in4, n2, n1; };
+__device__ __forceinline__ ListSplit split_units(uint32_t nA, uint32_t nB, int use64) {
     ListSplit s;
+    // full units of 64 class-0 pairs first (matrix-core scan); the rest as below
+    s.n64 = use64 ? nA / 64u : 0u;
+    s.in64 = s.n64 * 64u;
+    nA -= s.in64;
     const uint32_t rA = nA & 7u;
     s.n8 = nA / 8 + (rA >= 5 ? 1u : 0u);
     s.in8 = rA >= 5 ? nA : nA - rA;
@@ -604,26 +609,26 @@ __device__ __forceinline__ ListSplit split_units(uint32_t nA, uint32_t nB) {
     return s;
 }
 
-// per list: exclusive prefixes of the four kinds of unit; one workgroup
-__global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, const uint32_t* __restrict__ list_np,
-                                                                uint32_t* __restrict__ gpre /*[4][c]*/,
+// per list: exclusive prefixes of the five kinds of unit (eight, four, two, single, 64); one workgroup
+__global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, int use64, const uint32_t* __restrict__ list_np,
+                                                                uint32_t* __restrict__ gpre /*[5][c]*/,
                                                                 uint32_t* __restrict__ cur /*[2c]*/,
-                                                                uint32_t* __restrict__ counts /*[4]*/) {
-    __shared__ uint32_t wtot[4][16];
-    __shared__ uint32_t carry[4];
+                                                                uint32_t* __restrict__ counts /*[5]*/) {
+    __shared__ uint32_t wtot[5][16];
+    __shared__ uint32_t carry[5];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid < 4) carry[tid] = 0;
+    if (tid < 5) carry[tid] = 0;
     __syncthreads();
     for (int base = 0; base < c; base += 1024) {
         int l = base + tid;
-        uint32_t v[4] = {0, 0, 0, 0};
+        uint32_t v[5] = {0, 0, 0, 0, 0};
         if (l < c) {
-            ListSplit sp = split_units(list_np[2 * l], list_np[2 * l + 1]);
-            v[0] = sp.n8; v[1] = sp.n4; v[2] = sp.n2; v[3] = sp.n1;
+            ListSplit sp = split_units(list_np[2 * l], list_np[2 * l + 1], use64);
+            v[0] = sp.n8; v[1] = sp.n4; v[2] = sp.n2; v[3] = sp.n1; v[4] = sp.n64;
         }
-        uint32_t inc[4] = {v[0], v[1], v[2], v[3]};
+        uint32_t inc[5] = {v[0], v[1], v[2], v[3], v[4]};
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
+        for (int a = 0; a < 5; ++a) {
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 uint32_t o = __shfl_up(inc[a], off, 64);
@@ -633,36 +638,47 @@ __global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, const uin
         }
         __syncthreads();
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
+        for (int a = 0; a < 5; ++a) {
             uint32_t add = carry[a];
             for (int x = 0; x < wv; ++x) add += wtot[a][x];
             inc[a] += add;
         }
         if (l < c) {
 #pragma unroll
-            for (int a = 0; a < 4; ++a) gpre[(int64_t)a * c + l] = inc[a] - v[a];
+            for (int a = 0; a < 5; ++a) gpre[(int64_t)a * c + l] = inc[a] - v[a];
             cur[2 * l] = 0;
             cur[2 * l + 1] = 0;
         }
         __syncthreads();
-        if (tid == 1023) { carry[0] = inc[0]; carry[1] = inc[1]; carry[2] = inc[2]; carry[3] = inc[3]; }
+        if (tid == 1023) {
+#pragma unroll
+            for (int a = 0; a < 5; ++a) carry[a] = inc[a];
+        }
         __syncthreads();
     }
-    if (tid < 4) counts[tid] = carry[tid];
+    if (tid < 5) counts[tid] = carry[tid];
 }
 
 __global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, int w,
                                   const uint8_t* __restrict__ exact_only,
-                                  int use8, int c, const uint32_t* __restrict__ list_np,
+                                  int use8, int use64, int c, const uint32_t* __restrict__ list_np,
                                   const uint32_t* __restrict__ gpre, uint32_t* __restrict__ cur,
                                   uint32_t* __restrict__ unit8_pairs, uint32_t* __restrict__ unit4_pairs,
-                                  uint32_t* __restrict__ unit2_pairs, uint32_t* __restrict__ lo_pairs) {
+                                  uint32_t* __restrict__ unit2_pairs, uint32_t* __restrict__ lo_pairs,
+                                  uint32_t* __restrict__ unit64_pairs) {
     int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= P) return;
     const int l = probe[p];
     const int cls = (use8 && !exact_only[p / w]) ? 0 : 1;
-    const ListSplit sp = split_units(list_np[2 * l], list_np[2 * l + 1]);
-    const uint32_t i = atomicAdd(&cur[2 * l + cls], 1u);
+    const ListSplit sp = split_units(list_np[2 * l], list_np[2 * l + 1], use64);
+    uint32_t i = atomicAdd(&cur[2 * l + cls], 1u);
+    if (cls == 0) {
+        if (i < sp.in64) {
+            unit64_pairs[((int64_t)gpre[4 * (int64_t)c + l] + i / 64) * 64 + (i & 63)] = (uint32_t)p;
+            return;
+        }
+        i -= sp.in64;
+    }
     if (cls == 0 && i < sp.in8) {
         unit8_pairs[((int64_t)gpre[l] + i / 8) * 8 + (i & 7)] = (uint32_t)p;
         return;
@@ -674,7 +690,7 @@ __global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, int 
 }
 
 // block prefixes over the units of one kind and its work total; one workgroup per kind (blockIdx.x:
-// 0 = units of eight, 1 = of four, 2 = of two, 3 = single pairs); work[0] must be zero on entry
+// 0 = units of eight, 1 = of four, 2 = of two, 3 = single pairs, 4 = units of 64); work[0] must be zero on entry
 __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* __restrict__ counts, GroupBuffers gb,
                                                                 const uint32_t* __restrict__ pair_len) {
     __shared__ uint32_t wtot[16];
@@ -683,9 +699,9 @@ __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int which = blockIdx.x;
     const int n = (int)counts[which];
-    const uint32_t* ids = which == 0 ? gb.unit8_pairs : (which == 1 ? gb.unit4_pairs : (which == 2 ? gb.unit2_pairs : gb.lo_pairs));
-    uint32_t* out = which == 0 ? gb.blk8 : (which == 1 ? gb.blk4 : (which == 2 ? gb.blk2 : gb.blklo));
-    const int step = which == 0 ? 8 : (which == 1 ? 4 : (which == 2 ? 2 : 1));
+    const uint32_t* ids = which == 0 ? gb.unit8_pairs : (which == 1 ? gb.unit4_pairs : (which == 2 ? gb.unit2_pairs : (which == 3 ? gb.lo_pairs : gb.unit64_pairs)));
+    uint32_t* out = which == 0 ? gb.blk8 : (which == 1 ? gb.blk4 : (which == 2 ? gb.blk2 : (which == 3 ? gb.blklo : gb.blk64)));
+    const int step = which == 0 ? 8 : (which == 1 ? 4 : (which == 2 ? 2 : (which == 3 ? 1 : 64)));
     if (tid == 0) { s_read = 0; s_est = 0; carry = 0; }
     __syncthreads();
     unsigned long long my_read = 0, my_est = 0;
@@ -721,14 +737,16 @@ __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* 
     }
 }
 
-int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* exact_only, bool use8,
+int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint8_t* exact_only, bool use8, bool use64,
                            const uint32_t* pair_len, const GroupBuffers& gb, hipStream_t st) {
+    const int u64 = (use8 && use64) ? 1 : 0;
     hipLaunchKernelGGL(group_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0,
                        gb.list_np);
-    hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, gb.list_np, gb.gpre, gb.cur, gb.counts);
-    hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0, c,
-                       gb.list_np, gb.gpre, gb.cur, gb.unit8_pairs, gb.unit4_pairs, gb.unit2_pairs, gb.lo_pairs);
-    hipLaunchKernelGGL(group_scan_units_kernel, dim3(4), dim3(1024), 0, st, gb.counts, gb, pair_len);
+    hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, u64, gb.list_np, gb.gpre, gb.cur, gb.counts);
+    hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0, u64,
+                       c, gb.list_np, gb.gpre, gb.cur, gb.unit8_pairs, gb.unit4_pairs, gb.unit2_pairs, gb.lo_pairs,
+                       gb.unit64_pairs);
+    hipLaunchKernelGGL(group_scan_units_kernel, dim3(5), dim3(1024), 0, st, gb.counts, gb, pair_len);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -1370,4 +1388,323 @@ int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const floa
             ivfr_set_error("half-precision shared scan supports m <= 16; got %d", ix->p.m);
             return IVFR_ERR_INVALID_ARG;
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// Matrix-core scan for lists that 64 queries of the batch visit together.
+//
+// With that many queries on one list the estimate of Eq. (5) is cheaper as a contraction than as table
+// look-ups: for query residual r and the entry's decoded vector y = (pq[0][b_0], ..., pq[m-1][b_{m-1}])
+//     estimate = ||r||^2 - 2 r . y + ||y||^2 ,
+// so a tile of 32 entries against 64 queries is a [64 x d] . [d x 32] product.  The decoded vectors are
+// gathered, 16 bytes per lane and 16-dimension step, from one fp16 copy of the PQ codebook that stays in LDS for
+// the whole launch (it depends on neither list nor query, so nothing is rebuilt between units); the queries'
+// -2 r, in fp16, stay in registers; v_mfma_f32_32x32x16_f16 accumulates in fp32 on top of a per-query constant
+//     c0 = S (||r||^2 - tau) - margin,
+// and an entry can be kept by query x only if c0[x] + (product) + S ||y||^2 <= 0 (S: the power-of-two scale
+// that brings both fp16 operands into range).  The margin bounds every rounding of this filter against the fp32
+// table sum, so nothing the exact test would keep is dropped: fp16 rounding of both operands changes
+// the product by at most 2^-10 sum_j 2 ||r^j|| max_k ||pq[j][k]||, the tables themselves and the fp32 sums are
+// accurate to a few 2^-22 of sum_j (||r^j|| + max_k ||pq[j][k]||)^2.  Whatever passes is queued per wavefront
+// and re-evaluated exactly like in the half-precision scan of eight: the same fp32 sum of the same table
+// entries, compared with tau, appended to the query's buffer.  Wavefronts work independently (no barrier after
+// the codebook is staged); each takes an equal share of the launch's block stream.
+// ------------------------------------------------------------------------------------------
+#define MF_T 512      // threads per workgroup: eight wavefronts share the LDS codebook, one workgroup per CU
+#define MF_ROWS 64    // queries per unit
+#define MFQ_CAP 128   // queued candidates per wavefront; a tile adds at most 64
+
+template <int M, int DSUB>
+__global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __restrict__ codes,
+                                                              const float* __restrict__ queries,
+                                                              const int32_t* __restrict__ probe,
+                                                              const float* __restrict__ coarse,
+                                                              const float* __restrict__ pq,
+                                                              const float* __restrict__ pq_norm,
+                                                              const float* __restrict__ pq_maxnorm,
+                                                              const float* __restrict__ lut,
+                                                              const float* __restrict__ lut_scale,
+                                                              const uint32_t* __restrict__ pair_start,
+                                                              const uint32_t* __restrict__ pair_len,
+                                                              const uint32_t* __restrict__ blkpre,
+                                                              const uint32_t* __restrict__ unit_pairs, int nunits,
+                                                              int w, const float* __restrict__ tau,
+                                                              uint2* __restrict__ cand,
+                                                              uint32_t* __restrict__ cand_cnt, CandLayout lay) {
+    constexpr int D = M * DSUB;          // dimensions
+    constexpr int KSTEPS = D / 16;       // matrix instructions per tile and 32 queries
+    constexpr int CENT_BYTES = IVFR_KS * D * 2;
+    constexpr int WAVE_WORDS = 2 * MFQ_CAP + 3 * MF_ROWS;
+    extern __shared__ float s_raw[];
+    char* s_cent = reinterpret_cast<char*>(s_raw);                                  // fp16 [M][256][DSUB], scaled
+    float* s_norm = reinterpret_cast<float*>(s_cent + CENT_BYTES);                  // [M][256] ||pq[j][k]||^2
+    uint32_t* s_wave = reinterpret_cast<uint32_t*>(s_norm + M * IVFR_KS) + (threadIdx.x >> 6) * WAVE_WORDS;
+    uint32_t* q_entry = s_wave;                  // entry | (lane half << 31)
+    uint32_t* q_mask = s_wave + MFQ_CAP;         // bit rb*16 + i: accumulator i of query block rb passed
+    uint32_t* s_pid = s_wave + 2 * MFQ_CAP;      // [64] pair of every row
+    float* s_tau = reinterpret_cast<float*>(s_pid + MF_ROWS);
+    float* s_c0 = s_tau + MF_ROWS;
+    const int tid = threadIdx.x, lane = tid & 63, row = lane & 31, h = lane >> 5;
+
+    // codebook scale: a power of two that brings the largest component below 128
+    float cmax = 0.f, nmax = 0.f;
+#pragma unroll
+    for (int j = 0; j < M; ++j) { const float v = pq_maxnorm[j]; cmax = fmaxf(cmax, v); nmax = fmaf(v, v, nmax); }
+    int ce = 0;
+    if (cmax > 0.f) (void)frexpf(cmax, &ce);
+    const float s_c = cmax > 0.f ? ldexpf(1.f, 7 - ce) : 1.f;
+    for (int i = tid; i < IVFR_KS * D / 8; i += MF_T) {
+        const float4 v0 = *reinterpret_cast<const float4*>(pq + (int64_t)i * 8);
+        const float4 v1 = *reinterpret_cast<const float4*>(pq + (int64_t)i * 8 + 4);
+        half8 hv;
+        hv[0] = (_Float16)(v0.x * s_c); hv[1] = (_Float16)(v0.y * s_c); hv[2] = (_Float16)(v0.z * s_c); hv[3] = (_Float16)(v0.w * s_c);
+        hv[4] = (_Float16)(v1.x * s_c); hv[5] = (_Float16)(v1.y * s_c); hv[6] = (_Float16)(v1.z * s_c); hv[7] = (_Float16)(v1.w * s_c);
+        reinterpret_cast<half8*>(s_cent)[i] = hv;
+    }
+    for (int i = tid; i < M * IVFR_KS; i += MF_T) s_norm[i] = pq_norm[i];
+    __syncthreads();   // the only barrier: from here on every wavefront works alone
+
+    const uint32_t total = blkpre[nunits];
+    const uint32_t NW = gridDim.x * (MF_T / 64);
+    const uint32_t gw = xcd_share_index(blockIdx.x, gridDim.x) * (MF_T / 64) + (uint32_t)(tid >> 6);
+    uint32_t b = (uint32_t)(((uint64_t)total * gw) / NW);
+    const uint32_t b_end = (uint32_t)(((uint64_t)total * (gw + 1)) / NW);
+    if (b >= b_end) return;
+    int lo = 0, hi = nunits;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (blkpre[mid] <= b) lo = mid; else hi = mid;
+    }
+    int u = lo;
+    uint32_t qn = 0, start = 0;
+    // per-lane parts of the LDS addresses
+    const uint32_t cent_lane = DSUB == 8 ? (uint32_t)h * (IVFR_KS * 16) : (uint32_t)h * 16;
+    const uint32_t norm_lane = (uint32_t)h * (M / 2) * (IVFR_KS * 4);
+
+    auto drain = [&]() {
+        for (uint32_t base = 0; base < qn; base += 64) {
+            const uint32_t i = base + lane;
+            if (i < qn) {
+                const uint32_t e = q_entry[i] & 0x7fffffffu, hh = q_entry[i] >> 31;
+                uint32_t mask = q_mask[i];
+                uint32_t wd[M / 4];
+                const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e) * M);
+#pragma unroll
+                for (int t2 = 0; t2 < M / 4; ++t2) wd[t2] = src[t2];
+                while (mask) {
+                    const int x = __ffs(mask) - 1;
+                    mask &= mask - 1;
+                    const int r64 = (x >> 4) * 32 + 8 * ((x & 15) >> 2) + 4 * (int)hh + (x & 3);
+                    const uint32_t pidx = s_pid[r64];
+                    const float est = adc_sum<M>(lut + (int64_t)pidx * M * IVFR_KS, wd);
+                    if (est <= s_tau[r64]) {
+                        const int q = (int)(pidx / (uint32_t)w);
+                        const uint32_t slot = atomicAdd(cand_cnt + q, 1u);
+                        if (slot < lay.cap(q)) cand[lay.base(q) + slot] = make_uint2(__float_as_uint(est), start + e);
+                    }
+                }
+            }
+        }
+        qn = 0;
+    };
+
+    while (b < b_end) {
+        while (blkpre[u + 1] <= b) ++u;
+        const uint32_t pb0 = blkpre[u], pb1 = blkpre[u + 1];
+        const uint32_t stop = pb1 < b_end ? pb1 : b_end;
+        // ---- the unit's 64 queries: residuals -> fp16 operand, per-row constants ----
+        uint32_t pidx[2];
+        bool real[2];
+        const float* xr[2];
+        const float* cr[2];
+        float rr[2] = {0.f, 0.f}, amax = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const uint32_t raw = unit_pairs[(int64_t)u * MF_ROWS + rb * 32 + row];
+            real[rb] = raw != IVFR_NO_PAIR;
+            pidx[rb] = real[rb] ? raw : unit_pairs[(int64_t)u * MF_ROWS];
+            xr[rb] = queries + (int64_t)(pidx[rb] / (uint32_t)w) * D + 8 * h;
+            cr[rb] = coarse + (int64_t)probe[pidx[rb]] * D + 8 * h;
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const float4 x0 = *reinterpret_cast<const float4*>(xr[rb] + 16 * s), x1 = *reinterpret_cast<const float4*>(xr[rb] + 16 * s + 4);
+                const float4 c0 = *reinterpret_cast<const float4*>(cr[rb] + 16 * s), c1 = *reinterpret_cast<const float4*>(cr[rb] + 16 * s + 4);
+                const float v[8] = {x0.x - c0.x, x0.y - c0.y, x0.z - c0.z, x0.w - c0.w, x1.x - c1.x, x1.y - c1.y, x1.z - c1.z, x1.w - c1.w};
+#pragma unroll
+                for (int x = 0; x < 8; ++x) { rr[rb] = fmaf(v[x], v[x], rr[rb]); amax = fmaxf(amax, fabsf(v[x])); }
+            }
+            rr[rb] += __shfl_xor(rr[rb], 32);
+        }
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+        int ae = 0;
+        if (amax > 0.f) (void)frexpf(2.f * amax, &ae);
+        const float s_a = amax > 0.f ? ldexpf(1.f, 9 - ae) : 1.f;   // largest |2 r s_a| in [256, 512)
+        const float S = s_a * s_c;
+        half8 a[2][KSTEPS];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const float f = -2.f * s_a;
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const float4 x0 = *reinterpret_cast<const float4*>(xr[rb] + 16 * s), x1 = *reinterpret_cast<const float4*>(xr[rb] + 16 * s + 4);
+                const float4 c0 = *reinterpret_cast<const float4*>(cr[rb] + 16 * s), c1 = *reinterpret_cast<const float4*>(cr[rb] + 16 * s + 4);
+                half8 hv;
+                hv[0] = (_Float16)((x0.x - c0.x) * f); hv[1] = (_Float16)((x0.y - c0.y) * f);
+                hv[2] = (_Float16)((x0.z - c0.z) * f); hv[3] = (_Float16)((x0.w - c0.w) * f);
+                hv[4] = (_Float16)((x1.x - c1.x) * f); hv[5] = (_Float16)((x1.y - c1.y) * f);
+                hv[6] = (_Float16)((x1.z - c1.z) * f); hv[7] = (_Float16)((x1.w - c1.w) * f);
+                a[rb][s] = hv;
+            }
+            const float t = tau[(int)(pidx[rb] / (uint32_t)w)];
+            const float ub = 60000.f / lut_scale[pidx[rb]];
+            // unscaled margin: fp16 rounding of both operands + the tables' own fp32 round-off
+            const float mg = 1.05f * 9.765625e-4f * fmaxf(ub - rr[rb] - nmax, 0.f) + 7.62939453125e-6f * ub;
+            const float c0v = real[rb] ? S * (rr[rb] - t) - S * mg - 5.f : INFINITY;
+            if (h == 0) {
+                s_pid[rb * 32 + row] = pidx[rb];
+                s_tau[rb * 32 + row] = real[rb] ? t : -1.f;
+                s_c0[rb * 32 + row] = c0v;
+            }
+        }
+        floatx16 c0[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c0[rb][i] = s_c0[rb * 32 + 8 * (i >> 2) + 4 * h + (i & 3)];
+        start = pair_start[pidx[0]];
+        start = __builtin_amdgcn_readfirstlane(start);
+        const uint32_t len = __builtin_amdgcn_readfirstlane(pair_len[pidx[0]]);
+
+        // ---- tiles of 32 entries ----
+        const uint32_t t0 = (b - pb0) * (IVFR_BLOCK / 32);
+        uint32_t t1 = (stop - pb0) * (IVFR_BLOCK / 32);
+        const uint32_t tl = (len + 31) / 32;
+        if (t1 > tl) t1 = tl;
+        uint32_t wn[M / 4];   // code words of the next tile
+        {
+            const uint32_t e = t0 * 32 + row;
+            const bool in = t0 < t1 && e < len;
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + (in ? e : 0u)) * M);
+#pragma unroll
+            for (int t2 = 0; t2 < M / 4; ++t2) wn[t2] = in ? src[t2] : 0u;
+        }
+        for (uint32_t tile = t0; tile < t1; ++tile) {
+            uint32_t wc[M / 4];
+#pragma unroll
+            for (int t2 = 0; t2 < M / 4; ++t2) wc[t2] = wn[t2];
+            const uint32_t e = tile * 32 + row;
+            const bool valid = e < len;
+            {
+                const uint32_t en = e + 32;
+                const bool in = tile + 1 < t1 && en < len;
+                const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + (in ? en : 0u)) * M);
+#pragma unroll
+                for (int t2 = 0; t2 < M / 4; ++t2) wn[t2] = in ? src[t2] : 0u;
+            }
+            // decoded operand: 8 dimensions of this lane's entry per step
+            half8 bv[KSTEPS];
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                uint32_t byte, off;
+                if (DSUB == 8) {
+                    const uint32_t wsel = wc[(2 * s) / 4] >> (8 * ((2 * s) % 4) + 8 * h);   // sub-quantizer 2s + h
+                    byte = wsel & 0xffu;
+                    off = (uint32_t)(2 * s) * (IVFR_KS * 16) + byte * 16;
+                } else {
+                    const int j = (16 * s) / DSUB;
+                    byte = (wc[j / 4] >> (8 * (j % 4))) & 0xffu;
+                    off = (uint32_t)j * (IVFR_KS * DSUB * 2) + byte * (DSUB * 2) + (uint32_t)((16 * s) % DSUB) * 2;
+                }
+                bv[s] = *reinterpret_cast<const half8*>(s_cent + cent_lane + off);
+            }
+            floatx16 acc[2];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[rb][0], bv[0], c0[rb], 0, 0, 0);
+#pragma unroll
+                for (int s = 1; s < KSTEPS; ++s) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[rb][s], bv[s], acc[rb], 0, 0, 0);
+            }
+            // ||y||^2: each lane half sums half of the sub-quantizers
+            float ns = 0.f;
+#pragma unroll
+            for (int jj = 0; jj < M / 2; ++jj) {
+                uint32_t byte;
+                if (M == 4) byte = (wc[0] >> (8 * jj + 16 * h)) & 0xffu;
+                else byte = ((h ? wc[M / 8 + jj / 4] : wc[jj / 4]) >> (8 * (jj % 4))) & 0xffu;
+                ns += *reinterpret_cast<const float*>(reinterpret_cast<const char*>(s_norm) + norm_lane + jj * (IVFR_KS * 4) + byte * 4);
+            }
+            ns += __shfl_xor(ns, 32);
+            const float lim = -S * ns;
+            float mn = acc[0][0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mn = fminf(mn, acc[0][i]);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mn = fminf(mn, acc[1][i]);
+            const bool pass = valid && mn <= lim;
+            const uint64_t bal = __ballot(pass);
+            if (bal == 0) continue;
+            if (pass) {
+                uint32_t mask = 0;
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) mask |= (acc[rb][i] <= lim ? 1u : 0u) << (rb * 16 + i);
+                const uint32_t slot = qn + __popcll(bal & ((1ull << lane) - 1ull));
+                q_entry[slot] = e | ((uint32_t)h << 31);
+                q_mask[slot] = mask;
+            }
+            qn += __popcll(bal);
+            if (qn > MFQ_CAP - 64) drain();
+        }
+        drain();   // the queue refers to this unit's rows
+        b = stop;
+    }
+}
+
+template <int M, int DSUB>
+static int launch_mfma64_md(const ivfr_index* ix, const float* queries, const int32_t* probe, const float* lut,
+                            const float* lut_scale, const uint32_t* pair_start, const uint32_t* pair_len,
+                            const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits, int w, const float* tau,
+                            uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
+    const size_t lds = (size_t)IVFR_KS * M * DSUB * 2 + (size_t)M * IVFR_KS * 4 +
+                       (size_t)(MF_T / 64) * (2 * MFQ_CAP + 3 * MF_ROWS) * sizeof(uint32_t);
+    static bool attr_done = false;
+    if (!attr_done && lds > 48 * 1024) {
+        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_mfma64_kernel<M, DSUB>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((adc_scan_mfma64_kernel<M, DSUB>), dim3(groups), dim3(MF_T), lds, st, ix->codes, queries, probe,
+                       ix->coarse, ix->pq, ix->pq_norm, ix->pq_maxnorm, lut, lut_scale, pair_start, pair_len, blkpre,
+                       unit_pairs, nunits, w, tau, cand, cand_cnt, lay);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+// sub-vectors of 8, 16 or 32 dimensions, at most 128 dimensions (the fp16 codebook takes 512 d bytes of LDS)
+bool ivfr_mfma_scan_supported(const ivfr_index* ix) {
+    const int m = ix->p.m, ds = ix->dsub;
+    return (m == 4 || m == 8 || m == 16) && (ds == 8 || ds == 16 || ds == 32) && m * ds <= 128;
+}
+
+int ivfr_launch_scan_mfma64(const ivfr_index* ix, const float* queries, const int32_t* probe, const float* lut,
+                            const float* lut_scale, const uint32_t* pair_start, const uint32_t* pair_len,
+                            const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits, int w, const float* tau,
+                            uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
+    if (nunits <= 0) return IVFR_OK;
+#define IVFR_MF_ARGS ix, queries, probe, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st
+    const int key = ix->p.m * 100 + ix->dsub;
+    switch (key) {
+        case 408: return launch_mfma64_md<4, 8>(IVFR_MF_ARGS);
+        case 416: return launch_mfma64_md<4, 16>(IVFR_MF_ARGS);
+        case 432: return launch_mfma64_md<4, 32>(IVFR_MF_ARGS);
+        case 808: return launch_mfma64_md<8, 8>(IVFR_MF_ARGS);
+        case 816: return launch_mfma64_md<8, 16>(IVFR_MF_ARGS);
+        case 1608: return launch_mfma64_md<16, 8>(IVFR_MF_ARGS);
+        default:
+            ivfr_set_error("matrix-core scan does not support m = %d with %d-dimensional sub-vectors", ix->p.m, ix->dsub);
+            return IVFR_ERR_INVALID_ARG;
+    }
+#undef IVFR_MF_ARGS
 }

@@ -83,18 +83,18 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     IVFR_REQUIRE((int64_t)kprime * ix->cap_mult < (1ll << 31), "kprime * cap_mult too large");
     IVFR_HIP(hipSetDevice(p.device));
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    ix->st_codes = ix->st_pairs = ix->st_dense = ix->st_streamed = ix->st_shared_codes = ix->st_shared2_codes = ix->st_shared8_codes = ix->st_retries = 0;
+    ix->st_codes = ix->st_pairs = ix->st_dense = ix->st_streamed = ix->st_shared_codes = ix->st_shared2_codes = ix->st_shared8_codes = ix->st_retries = ix->st_shared64_codes = 0;
     for (int i = 0; i < IVFR_N_STAGES; ++i) ix->prof_ms[i] = 0;
     ix->prof_scan_launches = 0;
     if (nq == 0) return IVFR_OK;
 
     const int d = p.d, c = p.c, m = p.m;
-    // queries per internal batch: the tuning value, lowered so that the per-batch tables (w m KB per query),
-    // the coarse keys (8 c bytes) and the short-list arrays (24 k' bytes) stay below 4 GiB each
+    // queries per internal batch: the tuning value, lowered so that the per-batch tables (w m KB per query) stay
+    // below 8 GiB, the coarse keys (8 c bytes) and the short-list arrays (24 k' bytes) below 4 GiB each
     int64_t B64 = std::min<int64_t>(nq, ix->batch);
     {
         const int64_t budget = 4ll << 30;
-        B64 = std::min<int64_t>(B64, std::max<int64_t>(1, budget / ((int64_t)w * p.m * IVFR_KS * 4)));
+        B64 = std::min<int64_t>(B64, std::max<int64_t>(1, 2 * budget / ((int64_t)w * p.m * IVFR_KS * 4)));
         B64 = std::min<int64_t>(B64, std::max<int64_t>(1, budget / ((int64_t)kprime * 24)));
         B64 = std::min<int64_t>(B64, std::max<int64_t>(1, budget / ((int64_t)p.c * 8)));
     }
@@ -150,9 +150,9 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_sids = cv.take<int32_t>((size_t)B * kprime);
     const size_t o_dpre = cv.take<uint32_t>((size_t)w + 1);
     const size_t o_lscale = cv.take<float>(P);
-    const size_t o_gpre = cv.take<uint32_t>(4 * (size_t)c);
+    const size_t o_gpre = cv.take<uint32_t>(5 * (size_t)c);
     const size_t o_gcur = cv.take<uint32_t>(2 * (size_t)c);
-    const size_t o_gcounts = cv.take<uint32_t>(4);
+    const size_t o_gcounts = cv.take<uint32_t>(8);
     // units of eight: at most P/8 + c (one more per list for a remainder of 5..7); units of four likewise
     const size_t n_u8 = ((size_t)P / 8 + c + 1) * 8, n_u4 = ((size_t)P / 4 + c + 1) * 4;
     const size_t o_gu8 = cv.take<uint32_t>(n_u8 + n_u4);
@@ -162,10 +162,12 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     const size_t o_gblk4 = cv.take<uint32_t>((size_t)P / 4 + c + 2);
     const size_t o_gblk2 = cv.take<uint32_t>((size_t)c + 2);
     const size_t o_gblklo = cv.take<uint32_t>((size_t)c + 2);
+    const size_t o_gu64 = cv.take<uint32_t>(((size_t)P / 64 + 1) * 64);   // units of 64 are always full
+    const size_t o_gblk64 = cv.take<uint32_t>((size_t)P / 64 + 2);
     // cleared by one kernel at the start of every batch: plan totals, unit work totals, failed-filter count,
     // candidate counters, pairs per list
     const size_t o_totals = cv.take<unsigned long long>(2);
-    const size_t o_gwork = cv.take<unsigned long long>(6);
+    const size_t o_gwork = cv.take<unsigned long long>(8);
     const size_t o_overtot = cv.take<int32_t>(4);
     const size_t o_cnt = cv.take<uint32_t>(B);
     const size_t o_gnp = cv.take<uint32_t>(2 * (size_t)c);
@@ -224,16 +226,20 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     gb.blk4 = reinterpret_cast<uint32_t*>(ws + o_gblk4);
     gb.blk2 = reinterpret_cast<uint32_t*>(ws + o_gblk2);
     gb.blklo = reinterpret_cast<uint32_t*>(ws + o_gblklo);
+    gb.unit64_pairs = reinterpret_cast<uint32_t*>(ws + o_gu64);
+    gb.blk64 = reinterpret_cast<uint32_t*>(ws + o_gblk64);
     gb.work = reinterpret_cast<unsigned long long*>(ws + o_gwork);
     const float half_frac = IVFR_HALF_UNIT_FRAC;
     const bool share = ix->share_lists >= 1 && ivfr_shared_scan_supported(ix);
     const bool share8 = share && ix->share_lists >= 2 && ivfr_shared8h_supported(ix);
+    const bool share64 = share8 && ix->share_lists >= 3 && ivfr_mfma_scan_supported(ix);
 
     std::vector<EventPair> events;
     size_t ev_used = 0;   // events of the index's pool taken by this call
     auto mark_on = [&](int kind, bool begin, hipStream_t s) -> int {
         const bool is_scan = kind == IVFR_STAGE_SCAN || kind == IVFR_STAGE_SCAN_SHARED ||
-                             kind == IVFR_STAGE_SCAN_SHARED2 || kind == IVFR_STAGE_SCAN_SHARED8;
+                             kind == IVFR_STAGE_SCAN_SHARED2 || kind == IVFR_STAGE_SCAN_SHARED8 ||
+                             kind == IVFR_STAGE_SCAN_SHARED64;
         if (ix->profiling == 0 || (ix->profiling == 1 && !is_scan)) return IVFR_OK;
         if (begin) {
             while (ix->prof_events.size() < ev_used + 2) {
@@ -274,13 +280,13 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         }
         IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, min_cap, IVFR_MAX_SAMPLE, kprime, half_frac, pb, st));
         if (share) {
-            IVFR_TRY(ivfr_launch_group_plan(probe, Pb, w, c, pb.exact_only, share8, pb.len, gb, st));
-            IVFR_HIP(hipMemcpyAsync(ix->h_status + 8, gb.counts, 4 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-            IVFR_HIP(hipMemcpyAsync(ix->h_status + 12, gb.work, 5 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+            IVFR_TRY(ivfr_launch_group_plan(probe, Pb, w, c, pb.exact_only, share8, share64, pb.len, gb, st));
+            IVFR_HIP(hipMemcpyAsync(ix->h_status + 8, gb.counts, 5 * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+            IVFR_HIP(hipMemcpyAsync(ix->h_status + 14, gb.work, 6 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         }
         // the candidate pool is sized by the plan: one small read-back
         IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
-        IVFR_HIP(hipMemcpyAsync(ix->h_status + 24, pb.blkpre_s + Pb, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        IVFR_HIP(hipMemcpyAsync(ix->h_status + 28, pb.blkpre_s + Pb, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
         IVFR_TRY(mark(IVFR_STAGE_PROBE, false));
         IVFR_TRY(mark(IVFR_STAGE_LUT, true));
         IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, lut_scale, st));
@@ -288,18 +294,27 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         IVFR_HIP(hipStreamSynchronize(st));
         unsigned long long tot2[2];
         memcpy(tot2, ix->h_status + 2, sizeof(tot2));
-        const uint32_t n_sample_chunks = (uint32_t)ix->h_status[24];
+        const uint32_t n_sample_chunks = (uint32_t)ix->h_status[28];
         ix->st_codes += (int64_t)tot2[0];
         ix->st_pairs += Pb;
-        int n_unit8 = 0, n_unit4 = 0, n_unit2 = 0, n_lo = 0;
-        int g8 = groups, g4 = groups, g2 = groups, g1 = pick_groups((double)tot2[0], 64);
+        int n_unit8 = 0, n_unit4 = 0, n_unit2 = 0, n_lo = 0, n_unit64 = 0;
+        int g8 = groups, g4 = groups, g2 = groups, g1 = pick_groups((double)tot2[0], 64), g64 = 8;
         if (share) {
-            unsigned long long gw[5];
-            memcpy(gw, ix->h_status + 12, sizeof(gw));
+            unsigned long long gw[6];
+            memcpy(gw, ix->h_status + 14, sizeof(gw));
             n_unit8 = ix->h_status[8];
             n_unit4 = ix->h_status[9];
             n_unit2 = ix->h_status[10];
             n_lo = ix->h_status[11];
+            n_unit64 = ix->h_status[12];
+            // one workgroup of eight wavefronts per compute unit at most; at least four blocks per wavefront
+            {
+                const double blocks64 = (double)gw[5] / 64.0 / (double)IVFR_BLOCK;
+                int g = (int)(blocks64 / 32.0) + 1;
+                if (ix->scan_groups > 0) g = ix->scan_groups;
+                g64 = std::min(ix->n_cu, (std::max(g, 8) + 7) & ~7);
+            }
+            ix->st_shared64_codes += (int64_t)gw[5];
             g8 = pick_groups((double)gw[1] / 8.0, 256);
             g4 = pick_groups((double)gw[2] / 4.0, 128);
             g2 = pick_groups((double)gw[3] / 2.0, 64);
@@ -329,8 +344,15 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
             // lists visited by several queries: eight, four or two queries per pass over the list; the rest pair
             // by pair.  The four launches are independent (they append to the same buffers through atomics), so
             // the three small ones go to side streams and fill the large one's tail.
+            const int n_side = n_unit64 > 0 ? 4 : 3;
             IVFR_HIP(hipEventRecord(ix->ev_fork, st));
-            for (int i = 0; i < 3; ++i) IVFR_HIP(hipStreamWaitEvent(ix->side[i], ix->ev_fork, 0));
+            for (int i = 0; i < n_side; ++i) IVFR_HIP(hipStreamWaitEvent(ix->side[i], ix->ev_fork, 0));
+            if (n_unit64 > 0) {
+                IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED64, true, ix->side[3]));
+                IVFR_TRY(ivfr_launch_scan_mfma64(ix, X, probe, lut, lut_scale, pb.pair_start, pb.len, gb.blk64,
+                                                 gb.unit64_pairs, n_unit64, w, tau, cand, cnt, lay, g64, ix->side[3]));
+                IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED64, false, ix->side[3]));
+            }
             IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED8, true));
             IVFR_TRY(ivfr_launch_scan_shared8h(ix, lut, lut_scale, pb.pair_start, pb.len, gb.blk8, gb.unit8_pairs, n_unit8,
                                                w, tau, cand, cnt, lay, g8, st));
@@ -348,7 +370,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
             IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, gb.blklo, gb.lo_pairs, n_lo, w, tau, cand, cnt,
                                       lay, g1, ix->side[2]));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN, false, ix->side[2]));
-            for (int i = 0; i < 3; ++i) {
+            for (int i = 0; i < n_side; ++i) {
                 IVFR_HIP(hipEventRecord(ix->ev_join[i], ix->side[i]));
                 IVFR_HIP(hipStreamWaitEvent(st, ix->ev_join[i], 0));
             }
@@ -469,7 +491,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         if (hipEventElapsedTime(&ms, ep.a, ep.b) == hipSuccess) {
             ix->prof_ms[ep.kind] += ms;
             if (ep.kind == IVFR_STAGE_SCAN || ep.kind == IVFR_STAGE_SCAN_SHARED || ep.kind == IVFR_STAGE_SCAN_SHARED2 ||
-                ep.kind == IVFR_STAGE_SCAN_SHARED8)
+                ep.kind == IVFR_STAGE_SCAN_SHARED8 || ep.kind == IVFR_STAGE_SCAN_SHARED64)
                 ix->prof_scan_launches += 1;
         }
     }

@@ -487,6 +487,36 @@ def test_list_sharing_modes_give_identical_bits(m):
     ix.close()
 
 
+@pytest.mark.parametrize("d,m", [(128, 8), (64, 8), (128, 4), (64, 4), (32, 4), (128, 16)])
+def test_matrix_core_units_give_identical_bits(d, m):
+    """Lists visited by 64 or more queries of the batch: the matrix-core scan (fp16 contraction against the
+    decoded entries as a filter, exact fp32 table sums for what passes) must record the same estimates as the
+    table look-up scans, so sharing mode 3 returns the bits of modes 2 and 0; checked against the oracle too."""
+    wl = tiny_workload(d=d, G=16, N=200000, n_train=3000, n_query=230, c=4, m=m, m_refine=8, iters=4)
+    index, X = wl["index"], wl["X"]
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    w, kp, k = 2, 16, 5   # k' small against the ~100000 visited entries: the bound passes a tiny share of them
+    outs = {}
+    for mode in (3, 2, 0):
+        ix.set_list_sharing(mode)
+        ids, dist, t = ix.search(xq, w, kp, k, trace=True)
+        st = ix.search_stats()
+        log("sharing mode", mode, st)
+        outs[mode] = (ids.cpu().numpy(), dist.cpu().numpy(),
+                      np.sort(t["short_ids"].cpu().numpy(), axis=1), np.sort(t["short_est"].cpu().numpy(), axis=1))
+        assert st["dense_fallbacks"] == 0
+        assert (st["codes_scanned_shared64"] > 0) == (mode == 3)
+        if mode == 3:
+            assert st["codes_scanned_shared64"] > st["codes_scanned"] // 2
+    for mode in (2, 0):
+        for a, b in zip(outs[3], outs[mode]):
+            assert np.array_equal(a, b)
+    sel = list(range(0, 230, 9))
+    compare_results(outs[3][0][sel], outs[3][1][sel], X[sel], index, w, kp, k)
+    ix.close()
+
+
 def test_papers_own_shortlist_setting():
     """Section 4.3 runs k = 10000 with k' = 20000 (k'/k = 2): the largest result lists the library sorts."""
     wl = tiny_workload(d=32, G=16, N=60000, n_train=2000, n_query=3, c=8, m=4, m_refine=8, iters=4)
