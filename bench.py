@@ -125,6 +125,8 @@ def sweep(args):
     from synthdata.gpu import DeviceMixture
 
     base = sd.CONFIGS[args.config]
+    if args.batch:
+        base = dataclasses.replace(base, batch=args.batch)
     if args.N:
         base = dataclasses.replace(base, N=args.N)
     if args.kprime:
@@ -151,6 +153,7 @@ def sweep(args):
             gt_cache[cfg.N] = gt
         gt = gt_cache[cfg.N]
         B = min(cfg.batch, cfg.n_query)
+        ix.set_tuning(batch=min(B, 65535))
         batches = [xq[i * B:(i + 1) * B].contiguous() for i in range(max(1, cfg.n_query // B))]
         ix.search(batches[-1], cfg.w, cfg.kprime, cfg.k)
         torch.cuda.synchronize()
@@ -190,15 +193,16 @@ def main():
     ap.add_argument("--c", type=int, default=0, help="override the number of coarse centroids (1 = exhaustive ADC+R)")
     ap.add_argument("--w", type=int, default=0, help="override the number of lists visited")
     ap.add_argument("--batch", type=int, default=0,
-                    help="queries per step (default: the workload's 1000); the library's internal batch follows it")
+                    help="queries per step (default: the workload's: 10000 for cfg4, else 1000); the library's "
+                         "internal batch follows it")
     ap.add_argument("--train-iters", type=int, default=10)
     ap.add_argument("--gt-queries", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scan-groups", type=int, default=0)
     ap.add_argument("--per-pair", action="store_true",
                     help="scan every (query, list) pair on its own (no sharing of a list between queries)")
-    ap.add_argument("--sharing", type=int, default=2, choices=(0, 1, 2),
-                    help="list sharing mode: 0 per pair, 1 fp32 units of four/two, 2 also fp16 units of eight")
+    ap.add_argument("--sharing", type=int, default=2, choices=(0, 1, 2, 3),
+                    help="list sharing mode: 0 per pair, 1 fp32 units of four/two, 2 also fp16 units of eight, 3 also matrix-core units of 64")
     ap.add_argument("--sweep-groups", default="",
                     help="comma-separated scan workgroup counts: time a few steps with each (to stderr) before the run")
     ap.add_argument("--sweep", default="", choices=("", "table1", "table2", "fig3"),
@@ -248,9 +252,9 @@ def main():
     ix.set_list_sharing(args.sharing)
     if args.batch:
         cfg = dataclasses.replace(cfg, batch=args.batch)
-        ix.set_tuning(batch=min(args.batch, 65535))
 
     B = min(cfg.batch, cfg.n_query)
+    ix.set_tuning(batch=min(B, 65535))
     n_batches = max(1, cfg.n_query // B)
     batches = [xq[i * B:(i + 1) * B].contiguous() for i in range(n_batches)]
 
@@ -280,6 +284,7 @@ def main():
     codes_shared = 0
     codes_shared2 = 0
     codes_shared8 = 0
+    codes_shared64 = 0
     codes_streamed = 0
     dense_total = 0
     retries_total = 0
@@ -294,6 +299,7 @@ def main():
         codes_shared += st["codes_scanned_shared"]
         codes_shared2 += st["codes_scanned_shared2"]
         codes_shared8 += st["codes_scanned_shared8"]
+        codes_shared64 += st["codes_scanned_shared64"]
         codes_streamed += st["codes_streamed"]
         scan_launches += pr.pop("scan_launches")
         for name, ms in pr.items():
@@ -336,9 +342,10 @@ def main():
     # Dominant kernel: the shared-list scan when it does most of the work, else the per-pair scan.
     # Algorithmic bytes = m bytes per (query, visited entry) estimate the kernel computes.
     kernels = [("adc_scan_kernel", stage_ms.get("scan", 0.0) / steps,
-                (codes - codes_shared - codes_shared2 - codes_shared8) / steps),
+                (codes - codes_shared - codes_shared2 - codes_shared8 - codes_shared64) / steps),
                ("adc_scan_shared_kernel", stage_ms.get("scan_shared", 0.0) / steps, codes_shared / steps),
-               ("adc_scan_shared8h_kernel", stage_ms.get("scan_shared8", 0.0) / steps, codes_shared8 / steps)]
+               ("adc_scan_shared8h_kernel", stage_ms.get("scan_shared8", 0.0) / steps, codes_shared8 / steps),
+               ("adc_scan_mfma64_kernel", stage_ms.get("scan_shared64", 0.0) / steps, codes_shared64 / steps)]
     kname, k_ms, k_codes = max(kernels, key=lambda k: k[1])
     code_bytes = cfg.m * k_codes
     lds_b = 2.0 if kname == "adc_scan_shared8h_kernel" else 4.0
@@ -359,6 +366,7 @@ def main():
         "codes_scanned_shared_per_step": codes_shared / steps,
         "codes_scanned_shared2_per_step": codes_shared2 / steps,
         "codes_scanned_shared8_per_step": codes_shared8 / steps,
+        "codes_scanned_shared64_per_step": codes_shared64 / steps,
         "stage_ms_per_step": {name: ms / args.steps for name, ms in stage_ms.items()},
         "dense_fallbacks_total": dense_total,
         "bound_retries_total": retries_total,

@@ -113,7 +113,7 @@ struct ivfr_index {
     std::vector<uint32_t> h_start;   // padded starts [c+1] (host)
 
     // tuning
-    int full_mult = 8, cap_mult = 16, batch = 1024, scan_groups = 0;
+    int full_mult = 8, cap_mult = 16, batch = 16384, scan_groups = 0;
     int share_lists = 2;             // 0 = every pair on its own; 1 = fp32 units of four / two; 2 = also fp16 units of eight; 3 = also matrix-core units of 64
     int min_cap = 8192;
 

@@ -1480,6 +1480,7 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
     // per-lane parts of the LDS addresses
     const uint32_t cent_lane = DSUB == 8 ? (uint32_t)h * (IVFR_KS * 16) : (uint32_t)h * 16;
     const uint32_t norm_lane = (uint32_t)h * (M / 2) * (IVFR_KS * 4);
+    const uint32_t hmask = h ? 0xffffffffu : 0u;
 
     auto drain = [&]() {
         for (uint32_t base = 0; base < qn; base += 64) {
@@ -1625,14 +1626,21 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
 #pragma unroll
                 for (int s = 1; s < KSTEPS; ++s) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[rb][s], bv[s], acc[rb], 0, 0, 0);
             }
-            // ||y||^2: each lane half sums half of the sub-quantizers
+            // ||y||^2: each lane half sums half of the sub-quantizers (its words picked without indexing by h)
             float ns = 0.f;
+            {
+                constexpr int NWH = M >= 8 ? M / 8 : 1;
+                uint32_t wh[NWH];
+                if (M == 4) wh[0] = wc[0] >> (16 * h);
+                else {
 #pragma unroll
-            for (int jj = 0; jj < M / 2; ++jj) {
-                uint32_t byte;
-                if (M == 4) byte = (wc[0] >> (8 * jj + 16 * h)) & 0xffu;
-                else byte = ((h ? wc[M / 8 + jj / 4] : wc[jj / 4]) >> (8 * (jj % 4))) & 0xffu;
-                ns += *reinterpret_cast<const float*>(reinterpret_cast<const char*>(s_norm) + norm_lane + jj * (IVFR_KS * 4) + byte * 4);
+                    for (int t2 = 0; t2 < NWH; ++t2) wh[t2] = wc[t2] ^ ((wc[t2] ^ wc[M / 8 + t2]) & hmask);
+                }
+#pragma unroll
+                for (int jj = 0; jj < M / 2; ++jj) {
+                    const uint32_t byte = (wh[jj / 4] >> (8 * (jj % 4))) & 0xffu;
+                    ns += *reinterpret_cast<const float*>(reinterpret_cast<const char*>(s_norm) + norm_lane + jj * (IVFR_KS * 4) + byte * 4);
+                }
             }
             ns += __shfl_xor(ns, 32);
             const float lim = -S * ns;
@@ -1645,13 +1653,15 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
             const uint64_t bal = __ballot(pass);
             if (bal == 0) continue;
             if (pass) {
+                // bit rb*16 + i = sign of lim - acc (clear: the row may keep the entry), shifted in from the top down
                 uint32_t mask = 0;
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) mask |= (acc[rb][i] <= lim ? 1u : 0u) << (rb * 16 + i);
-                const uint32_t slot = qn + __popcll(bal & ((1ull << lane) - 1ull));
-                q_entry[slot] = e | ((uint32_t)h << 31);
+                for (int x = 31; x >= 0; --x)
+                    mask = __builtin_amdgcn_alignbit(mask, __float_as_uint(lim - acc[x >> 4][x & 15]), 31);
+                mask = ~mask;
+                // passing lanes below this one: counted in place (no 64-bit lane mask kept in registers)
+                const uint32_t slot = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+                q_entry[slot] = e | (hmask & 0x80000000u);
                 q_mask[slot] = mask;
             }
             qn += __popcll(bal);
