@@ -23,13 +23,13 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 
 # HBM bytes moved per scan launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy
 # of known size (profiles/search_cfg4_hbm_traffic.txt), stored as a ratio to the algorithmic bytes of the
-# launch (m bytes per (query, entry) estimate); other workloads: null.
-#   per-pair scan (--per-pair):  101.37 GB read + 0.06 GB written for 101.14 GB of code bytes
-#   fp32 units of four (--sharing 1): 24.89 GB read + 0.16 GB written for 96.14 GB (one read serves four queries)
-#   fp16 units of eight (default):    14.07 GB read + 0.12 GB written for 92.97 GB (one read serves eight queries)
-MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 101.425 / 101.141,
-                          ("cfg4", "adc_scan_shared_kernel"): 25.051 / 96.142,
-                          ("cfg4", "adc_scan_shared8h_kernel"): 14.197 / 92.966}
+# launch (m bytes per (query, entry) estimate), for the default run of cfg4 (10000 queries per step); other
+# workloads and settings: null.
+#   per-pair scan (sharing mode 0): 1013.51 GB read + 0.54 GB written for 1011.41 GB of code bytes
+#   fp16 units of eight (default):  92.3 GB read + 1.80 GB written for 1001.31 GB (one read serves eight queries,
+#                                   and units of the same list that run side by side share it in L2)
+MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 1014.05 / 1011.41,
+                          ("cfg4", "adc_scan_shared8h_kernel"): 94.10 / 1001.31}
 LDS_PEAK_GBS = 256 * 128 * 2.4    # 256 CUs x 128 B/clk x 2.4 GHz
 
 
@@ -351,7 +351,7 @@ def main():
     lds_b = 2.0 if kname == "adc_scan_shared8h_kernel" else 4.0
     achieved = code_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
     traffic_key = (cfg.name, kname)
-    plain = not (args.N or args.kprime or args.k or args.m_refine >= 0 or args.c or args.w)
+    plain = not (args.N or args.kprime or args.k or args.m_refine >= 0 or args.c or args.w or args.batch)
     out = {
         "metric": "queries/s", "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,

@@ -142,8 +142,10 @@ int ivfr_set_list_sharing(ivfr_index* index, int32_t mode);
  *   cap_mult    (16)   such a query's candidate buffer holds max(cap_mult*k', min_cap) records, or its
  *   min_cap     (8192) sample, or the survivors expected from the bound plus six deviations, whichever
  *                      is largest; overflowing it triggers a rescan of that query with a tighter bound
- *   batch       (1024) queries processed per internal batch (fewer when w, k' or c are so large that
- *                      a batch's tables, short-lists or coarse keys would exceed 4 GiB)
+ *   batch       (16384) queries processed per internal batch (fewer when w, k' or c are so large that
+ *                      a batch's tables would exceed 8 GiB, its short-lists or coarse keys 4 GiB; a call
+ *                      that needs several batches is split into equal ones).  Queries of one batch share
+ *                      list reads, so larger batches are faster per query.
  *   scan_groups (0 = chosen from the amount of work) workgroups launched by the list-scan kernels          */
 int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int32_t min_cap, int32_t batch,
                     int32_t scan_groups);

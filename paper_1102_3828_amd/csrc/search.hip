@@ -89,13 +89,13 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
     if (nq == 0) return IVFR_OK;
 
     const int d = p.d, c = p.c, m = p.m;
-    // queries per internal batch: the tuning value, lowered so that the per-batch tables (w m KB per query),
-    // the coarse keys (8 c bytes) and the short-list arrays (24 k' bytes) stay below 4 GiB each; a call that
+    // queries per internal batch: the tuning value, lowered so that the per-batch tables (w m KB per query) stay
+    // below 8 GiB, the coarse keys (8 c bytes) and the short-list arrays (24 k' bytes) below 4 GiB each; a call that
     // needs several batches gets equal ones (the more queries share a batch, the more they share list reads)
     int64_t B64 = std::min<int64_t>(nq, ix->batch);
     {
         const int64_t budget = 4ll << 30;
-        B64 = std::min<int64_t>(B64, std::max<int64_t>(1, budget / ((int64_t)w * p.m * IVFR_KS * 4)));
+        B64 = std::min<int64_t>(B64, std::max<int64_t>(1, 2 * budget / ((int64_t)w * p.m * IVFR_KS * 4)));
         B64 = std::min<int64_t>(B64, std::max<int64_t>(1, budget / ((int64_t)kprime * 24)));
         B64 = std::min<int64_t>(B64, std::max<int64_t>(1, budget / ((int64_t)p.c * 8)));
     }

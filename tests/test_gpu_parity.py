@@ -616,8 +616,8 @@ def test_empty_lists_and_short_results():
 
 
 def test_visiting_thousands_of_lists_splits_the_batch():
-    """w = c = 8192: the look-up tables of one query take 32 MB, so the 150 queries cannot share one internal
-    batch (the library keeps a batch's tables under 4 GiB and splits the call into two batches of 75); results
+    """w = c = 8192: the look-up tables of one query take 32 MB, so the 300 queries cannot share one internal
+    batch (the library keeps a batch's tables under 8 GiB and splits the call into two batches of 150); results
     must not depend on the split."""
     rng = np.random.default_rng(23)
     d, c, m, mr, N = 32, 8192, 4, 4, 6000
@@ -626,11 +626,11 @@ def test_visiting_thousands_of_lists_splits_the_batch():
                           (rng.normal(size=(mr, 256, d // mr))).astype(np.float32))
     Y = np.clip(rng.normal(128, 40, size=(N, d)), 0, 255).round()
     index = orc.build_index(Y, np.arange(N), books)
-    X = np.clip(rng.normal(128, 40, size=(150, d)), 0, 255).astype(np.float32)
+    X = np.clip(rng.normal(128, 40, size=(300, d)), 0, 255).astype(np.float32)
     ix = gpu_index_from_oracle(index)
     ids, dist = ix.search(queries_dev(X), c, 300, 10)
-    assert ix.search_stats()["pairs"] == 150 * c
-    sel = [0, 1, 73, 74, 75, 76, 148, 149]   # both sides of the split (the oracle builds 8192 tables per query)
+    assert ix.search_stats()["pairs"] == 300 * c
+    sel = [0, 1, 148, 149, 150, 151, 298, 299]   # both sides of the split (the oracle builds 8192 tables per query)
     compare_results(ids.cpu().numpy()[sel], dist.cpu().numpy()[sel], X[sel], index, c, 300, 10)
     ix.close()
 
