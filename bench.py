@@ -23,13 +23,14 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 
 # HBM bytes moved per scan launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy
 # of known size (profiles/search_cfg4_hbm_traffic.txt), stored as a ratio to the algorithmic bytes of the
-# launch (m bytes per (query, entry) estimate), for the default run of cfg4 (10000 queries per step); other
-# workloads and settings: null.
-#   per-pair scan (sharing mode 0): 1013.51 GB read + 0.54 GB written for 1011.41 GB of code bytes
-#   fp16 units of eight (default):  92.3 GB read + 1.80 GB written for 1001.31 GB (one read serves eight queries,
-#                                   and units of the same list that run side by side share it in L2)
-MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 1014.05 / 1011.41,
-                          ("cfg4", "adc_scan_shared8h_kernel"): 94.10 / 1001.31}
+# launch (m bytes per (query, entry) estimate), for the default run of cfg4; other workloads and settings: null.
+#   per-pair scan (sharing mode 0):   101.45 GB read + 0.05 GB written for 101.14 GB of code bytes
+#   fp32 units of four (--sharing 1): 24.89 GB read + 0.16 GB written for 96.14 GB (one read serves four queries)
+#   fp16 units of eight (default):    11.26 GB read + 0.12 GB written for 92.97 GB (one read serves eight queries,
+#                                     and units of one list that run side by side on an XCD share it in L2)
+MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 101.500 / 101.141,
+                          ("cfg4", "adc_scan_shared_kernel"): 25.051 / 96.142,
+                          ("cfg4", "adc_scan_shared8h_kernel"): 11.381 / 92.966}
 LDS_PEAK_GBS = 256 * 128 * 2.4    # 256 CUs x 128 B/clk x 2.4 GHz
 
 
@@ -193,11 +194,12 @@ def main():
     ap.add_argument("--c", type=int, default=0, help="override the number of coarse centroids (1 = exhaustive ADC+R)")
     ap.add_argument("--w", type=int, default=0, help="override the number of lists visited")
     ap.add_argument("--batch", type=int, default=0,
-                    help="queries per step (default: the workload's: 10000 for cfg4, else 1000); the library's "
-                         "internal batch follows it")
+                    help="queries per step (default: the workload's 1000); the library's internal batch follows it")
     ap.add_argument("--train-iters", type=int, default=10)
     ap.add_argument("--gt-queries", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-whole-set", action="store_true",
+                    help="skip the extra calls that hand the workload's whole query set to one search call")
     ap.add_argument("--scan-groups", type=int, default=0)
     ap.add_argument("--per-pair", action="store_true",
                     help="scan every (query, list) pair on its own (no sharing of a list between queries)")
@@ -409,6 +411,20 @@ def main():
                                                 if key in MEASURED_TRAFFIC_RATIO and plain else None),
                                     "algorithmic_bytes_per_launch": pp_bytes, "avg_launch_ms": pp_ms / 3.0,
                                     "ms_per_step": 1e3 * pp_wall / 3.0, "list_sharing_mode": 0}
+    if cfg.n_query > B and not args.batch and not args.no_whole_set:
+        # The workload's whole query set in one call (outside the timed region): more queries share every list read.
+        ix.set_tuning(batch=min(cfg.n_query, 65535))
+        ix.search(xq, cfg.w, cfg.kprime, cfg.k)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            a_ids, _ = ix.search(xq, cfg.w, cfg.kprime, cfg.k)
+        torch.cuda.synchronize()
+        el = (time.perf_counter() - t0) / 3.0
+        out["whole_query_set_per_call"] = {"queries_per_call": cfg.n_query, "ms_per_call": 1e3 * el,
+                                           "queries_per_s": cfg.n_query / el,
+                                           "first_batch_ids_identical": bool((a_ids[:B].cpu().numpy() == g_ids).all())}
+        ix.set_tuning(batch=min(B, 65535))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ix, cfg, queries_u8, g_ids)
     ix.close()

@@ -180,5 +180,5 @@ CONFIGS = {
     "cfg1": Config("cfg1", 1_000_000, 100_000, 1000, 1024, None, 1024, 8, 16, 8, 1000, 100),
     "cfg2": Config("cfg2", 10_000_000, 1_000_000, 1000, 4096, None, 8192, 8, 32, 16, 1000, 100),
     "cfg3": Config("cfg3", 100_000_000, 1_000_000, 10_000, 16384, 1.1, 8192, 8, 16, 64, 10_000, 100),
-    "cfg4": Config("cfg4", 1_000_000_000, 2_000_000, 10_000, 16384, 1.1, 8192, 8, 8, 64, 1000, 100, batch=10_000),
+    "cfg4": Config("cfg4", 1_000_000_000, 2_000_000, 10_000, 16384, 1.1, 8192, 8, 8, 64, 1000, 100),
 }

@@ -274,6 +274,21 @@ def _full_size_case(name, n_check, **override):
         log(name, "sharing mode", mode, ix.search_stats())
         assert np.array_equal(p_ids.cpu().numpy(), gi) and np.array_equal(p_dist.cpu().numpy(), gd)
     ix.set_list_sharing(2)
+    if cfg.n_query > B:
+        # the workload's whole query set in one call (more queries share every list): same bits for the first
+        # B queries as when they are searched on their own, and the same bits with the matrix-core units
+        qa = dm.generate(sd.STREAM_QUERY, 0, cfg.n_query).float().contiguous()
+        ix.set_tuning(batch=cfg.n_query)
+        outs = []
+        for mode in (2, 3):
+            ix.set_list_sharing(mode)
+            a_ids, a_dist = ix.search(qa, cfg.w, cfg.kprime, cfg.k)
+            log(name, "whole query set, sharing mode", mode, ix.search_stats())
+            outs.append((a_ids.cpu().numpy(), a_dist.cpu().numpy()))
+        assert np.array_equal(outs[0][0][:B], gi) and np.array_equal(outs[0][1][:B], gd)
+        assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+        ix.set_list_sharing(2)
+        del qa
     log(name, "export")
     coarse, pq, rq = ix.get_codebooks()
     offsets, ids, codes, rcodes = ix.export()
