@@ -691,6 +691,59 @@ def test_random_shapes(seed):
     ix.close()
 
 
+def _crowded_case(seed):
+    """Seeded pick of a shape where many queries of the batch visit the same few lists."""
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([32, 64, 128]))
+    ms = [m for m in (4, 8, 16, 32) if d % m == 0 and d // m in (2, 4, 8, 16, 32)]
+    m = int(rng.choice(ms))
+    mr = int(rng.choice([0, 8]))
+    if seed % 2 == 0:   # long lists and a tiny k': the bound passes so few estimates that the filtered units are used
+        c = int(rng.choice([1, 2]))
+        N = int(rng.integers(200000, 400000))
+        kp = int(rng.choice([1, 4, 16]))
+    else:
+        c = int(rng.choice([1, 2, 3, 5]))
+        N = int(rng.integers(2000, 120000))
+        kp = int(rng.choice([1, 8, 40, 300]))
+    w = int(rng.integers(1, c + 1))
+    k = int(rng.integers(1, min(kp, 50) + 1))
+    nq = int(rng.integers(70, 400))
+    scale = float(rng.choice([1e-3, 1.0, 50.0]))
+    return dict(d=d, m=m, mr=mr, c=c, N=N, w=w, kp=kp, k=k, nq=nq, scale=scale)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_with_crowded_lists(seed):
+    """Seeded random shapes with 70-400 queries on one to five lists and codebooks / queries scaled by 0.001, 1
+    or 50: units of 64, eight, four and two all occur.  Every sharing mode must return the bits of the per-pair
+    scan; a few queries are checked against the oracle."""
+    cs = _crowded_case(seed)
+    log("crowded case", seed, cs)
+    rng = np.random.default_rng(6000 + seed)
+    d, c, m, mr, sc = cs["d"], cs["c"], cs["m"], cs["mr"], cs["scale"]
+    books = orc.Codebooks(((rng.normal(size=(c, d)) * 10 + 128) * sc).astype(np.float32),
+                          (rng.normal(size=(m, 256, d // m)) * 12 * sc).astype(np.float32),
+                          (rng.normal(size=(mr, 256, d // mr)) * 2 * sc).astype(np.float32) if mr else None)
+    Y = np.clip(rng.normal(128, 35, size=(cs["N"], d)), 0, 255).round() * sc
+    index = orc.build_index(Y, np.arange(cs["N"]), books)
+    X = (np.clip(rng.normal(128, 35, size=(cs["nq"], d)), 0, 255) * sc).astype(np.float32)
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    outs = {}
+    for mode in (0, 3, 2, 1):
+        ix.set_list_sharing(mode)
+        ids, dist = ix.search(xq, cs["w"], cs["kp"], cs["k"])
+        st = ix.search_stats()
+        log("  mode", mode, {a: b for a, b in st.items() if b})
+        outs[mode] = (ids.cpu().numpy(), dist.cpu().numpy())
+        assert np.array_equal(outs[mode][0], outs[0][0]) and np.array_equal(outs[mode][1], outs[0][1])
+    sel = list(range(0, cs["nq"], max(1, cs["nq"] // 5)))
+    exact, excused = compare_results(outs[0][0][sel], outs[0][1][sel], X[sel], index, cs["w"], cs["kp"], cs["k"])
+    assert excused <= max(2, exact // 50)
+    ix.close()
+
+
 def test_search_on_a_callers_stream():
     """The library enqueues on the stream it is given (here a non-default torch stream) and returns when that
     stream has drained: same bits as on the default stream."""
