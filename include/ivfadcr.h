@@ -86,7 +86,13 @@ int ivfr_import(ivfr_index* index, int64_t N, const int64_t* list_offsets, const
  * ids_out int32 [nq, k], dist_out fp32 [nq, k], device: per query ascending by (refined squared
  * distance, id); when fewer than k entries were scanned the tail is id -1, distance +inf.
  * stream: a hipStream_t (NULL = default stream).  Work is enqueued on it; the call also waits
- * for it to finish (it reads back a small status word), so outputs are valid on return. */
+ * for it to finish (it reads back a small status word), so outputs are valid on return.
+ * Query components must be finite: a query with a NaN or infinite component (or a squared norm
+ * beyond fp32) makes the call fail with IVFR_ERR_INVALID_ARG, naming the query.  The workspace of
+ * a call grows with nq (about w * m KB of tables per query) and is kept by the index for later calls.
+ * Errors: IVFR_ERR_INVALID_ARG for null pointers, parameters outside the ranges above or queries
+ * that are not finite, IVFR_ERR_STATE before ivfr_finalize / ivfr_import, IVFR_ERR_OOM /
+ * IVFR_ERR_HIP from the runtime; outputs are then undefined. */
 int ivfr_search(ivfr_index* index, const float* queries, int64_t nq, int32_t w, int32_t kprime, int32_t k,
                 int32_t* ids_out, float* dist_out, void* stream);
 

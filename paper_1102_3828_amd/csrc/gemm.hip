@@ -22,14 +22,16 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 #define KT 32
 #define LDS_STRIDE (KT + 4)
 
+// bad (optional, zero on entry): raised to row + 1 for a row whose squared norm is not a finite number
 __global__ __launch_bounds__(256) void row_norms_kernel(const float* __restrict__ X, int64_t n, int dim,
-                                                        float* __restrict__ out) {
+                                                        float* __restrict__ out, uint32_t* __restrict__ bad) {
     int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (row >= n) return;
     const float* x = X + row * dim;
     float s = 0.f;
     for (int e = 0; e < dim; ++e) s = fmaf(x[e], x[e], s);
     out[row] = s;
+    if (bad && !(s <= 3.0e38f)) atomicMax(bad, (uint32_t)row + 1u);
 }
 
 // out[j] = max over the `per` rows of group j of sqrt(norm2[j * per + k])
@@ -53,9 +55,9 @@ int ivfr_launch_group_max_norm(const float* norm2, int groups, int per, float* o
     return IVFR_OK;
 }
 
-int ivfr_launch_row_norms(const float* X, int64_t n, int dim, float* out, hipStream_t st) {
+int ivfr_launch_row_norms(const float* X, int64_t n, int dim, float* out, hipStream_t st, uint32_t* bad) {
     if (n <= 0) return IVFR_OK;
-    hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, X, n, dim, out);
+    hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, X, n, dim, out, bad);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }

@@ -135,7 +135,8 @@ struct ivfr_index {
 // ---- kernels' host launchers (each enqueues on `st` and returns a status) -------------------
 
 // squared norms of the rows of X [n, dim]
-int ivfr_launch_row_norms(const float* X, int64_t n, int dim, float* out, hipStream_t st);
+// bad (optional, zero on entry) is raised to row + 1 for a row whose squared norm is NaN, infinite or overflows
+int ivfr_launch_row_norms(const float* X, int64_t n, int dim, float* out, hipStream_t st, uint32_t* bad = nullptr);
 int ivfr_launch_group_max_norm(const float* norm2, int groups, int per, float* out, hipStream_t st);
 // uint8 [n, d] -> fp32
 int ivfr_launch_u8_to_f32(const uint8_t* x, int64_t count, float* out, hipStream_t st);

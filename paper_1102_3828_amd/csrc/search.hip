@@ -274,7 +274,7 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
                            zero_words, gb.unit8_pairs, share ? gb.unit_bytes / 4 : (size_t)0, tau, nb);
         // visited lists: the w nearest coarse centroids
         IVFR_TRY(mark(IVFR_STAGE_COARSE, true));
-        IVFR_TRY(ivfr_launch_row_norms(X, nb, d, xnorm, st));
+        IVFR_TRY(ivfr_launch_row_norms(X, nb, d, xnorm, st, reinterpret_cast<uint32_t*>(overtot + 1)));
         IVFR_TRY(ivfr_launch_dist_keys(X, xnorm, nb, ix->coarse, ix->coarse_norm, c, d, ckeys, st));
         IVFR_TRY(mark(IVFR_STAGE_COARSE, false));
         IVFR_TRY(mark(IVFR_STAGE_PROBE, true));
@@ -291,12 +291,18 @@ extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t n
         }
         // the candidate pool is sized by the plan: one small read-back
         IVFR_HIP(hipMemcpyAsync(ix->h_status + 2, pb.totals, 2 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+        IVFR_HIP(hipMemcpyAsync(ix->h_status + 6, overtot + 1, sizeof(int32_t), hipMemcpyDeviceToHost, st));
         IVFR_HIP(hipMemcpyAsync(ix->h_status + 28, pb.blkpre_s + Pb, sizeof(uint32_t), hipMemcpyDeviceToHost, st));
         IVFR_TRY(mark(IVFR_STAGE_PROBE, false));
         IVFR_TRY(mark(IVFR_STAGE_LUT, true));
         IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, lut_scale, st));
         IVFR_TRY(mark(IVFR_STAGE_LUT, false));
         IVFR_HIP(hipStreamSynchronize(st));
+        if (ix->h_status[6] != 0) {   // nothing after the tables has been enqueued for this batch
+            ivfr_set_error("query %lld has a component that is not finite (or a squared norm beyond fp32)",
+                           (long long)(q0 + ix->h_status[6] - 1));
+            return IVFR_ERR_INVALID_ARG;
+        }
         unsigned long long tot2[2];
         memcpy(tot2, ix->h_status + 2, sizeof(tot2));
         const uint32_t n_sample_chunks = (uint32_t)ix->h_status[28];

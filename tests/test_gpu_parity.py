@@ -795,4 +795,13 @@ def test_error_paths():
         assert e.value.code == pkg.binding.ERR_INVALID_ARG
     ids, _ = ix.search(xq, 2, 10, 5)    # still usable after errors
     assert ids.shape == (len(X), 5)
+    # a query with a NaN or an infinite component is refused, and named
+    for row, col, val in ((3, 7, float("nan")), (len(X) - 1, 0, float("inf")), (0, 31, float("-inf"))):
+        bad = xq.clone()
+        bad[row, col] = val
+        with pytest.raises(pkg.IvfrError) as e:
+            ix.search(bad, 2, 10, 5)
+        assert e.value.code == pkg.binding.ERR_INVALID_ARG and f"query {row} " in str(e.value)
+    ids2, _ = ix.search(xq, 2, 10, 5)
+    assert torch.equal(ids, ids2)
     ix.close()
