@@ -5,8 +5,10 @@
 //   units of queries that share a pass -> look-up tables (MFMA) -> sample of the visited entries
 //   (the same leading fraction of every visited list) -> per-query bound tau on the k'-th smallest
 //   estimate -> scan of every visited entry keeping estimates <= tau (four launches side by side:
-//   units of eight, four, two queries and single pairs) -> exact k' smallest of the survivors ->
-//   re-rank -> k smallest.
+//   units of eight, four, two queries and single pairs; in sharing mode 3 a fifth for units of 64 on
+//   the matrix cores) -> exact k' smallest of the survivors -> re-rank -> k smallest.
+// Queries with a component that is not finite are refused after the tables are built (their norms
+// are checked on the device; the flag comes back with the plan's sizes).
 // The host waits twice per batch: for the plan's sizes (candidate pool, launch shapes) and at the end.
 // tau is a statistical bound (the r-th smallest sampled estimate, r chosen five standard
 // deviations above the expected number of true k'-best entries in the sample), so the scan
