@@ -117,52 +117,90 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
     const int t = threadIdx.x & 7, g = threadIdx.x >> 3;
     const int per_q = (kprime + 127) / 128;
     const int64_t n_items = (int64_t)nq * per_q;
-    for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
-        const int q = q_base + (int)(item / per_q);
-        const int slot = (int)(item % per_q) * 128 + g;
-        const int n = short_n[q];
-        const bool live = slot < n;   // uniform over the 8 lanes of an entry
+    const int nit = d / 32;   // 16-byte pieces of a vector per lane (d is a multiple of 32 here, at most 128)
+    // Three items are in flight per workgroup: the position of item i + 2 is being read, the entry's id and code
+    // bytes of item i + 1 are being gathered (three random lines from HBM per entry, the latency that bounds
+    // this kernel), item i is decoded.  Loads return in issue order, so waiting for the oldest leaves the
+    // younger ones in flight.
+    struct Pos { int q, slot, n; uint32_t pos; };
+    struct Gather { int32_t id; uint32_t cb[4], rb[4]; };
+    auto read_pos = [&](int64_t item) -> Pos {
+        Pos r;
+        r.q = 0; r.slot = 0; r.n = 0; r.pos = 0;
+        if (item < n_items) {
+            r.q = q_base + (int)(item / per_q);
+            r.slot = (int)(item % per_q) * 128 + g;
+            r.n = short_n[r.q];
+            if (r.slot < kprime) r.pos = short_pos[(int64_t)r.q * kprime + r.slot];
+        }
+        return r;
+    };
+    auto gather = [&](const Pos& p) -> Gather {
+        Gather r;
+        r.id = -1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { r.cb[k] = 0; r.rb[k] = 0; }
+        if (p.slot < p.n) {   // uniform over the 8 lanes of an entry
+            r.id = ids[p.pos];
+            const uint8_t* code = codes + (uint64_t)p.pos * m;
+            const uint8_t* rcode = rcodes + (uint64_t)p.pos * mr;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int e = 4 * t + 32 * k;
+                if (k < nit) { r.cb[k] = code[e / dsub]; r.rb[k] = rcode[e / dsub_r]; }
+            }
+        }
+        return r;
+    };
+    int64_t item = blockIdx.x;
+    Pos p0 = read_pos(item), p1 = read_pos(item + gridDim.x);
+    Gather g0 = gather(p0);
+    for (; item < n_items; item += gridDim.x) {
+        const Pos p2 = read_pos(item + 2 * (int64_t)gridDim.x);
+        const Gather g1 = gather(p1);
+        const bool live = p0.slot < p0.n;
         float acc = 0.f;
-        int32_t id = -1;
         if (live) {
-            const uint32_t pos = short_pos[(int64_t)q * kprime + slot];
+            const uint32_t pos = p0.pos;
             int lo = (int)chunk_list[pos >> chunk_shift], hi = (int)chunk_list[(pos >> chunk_shift) + 1] + 1;
             while (hi - lo > 1) {
                 int mid = (lo + hi) >> 1;
                 if (list_start[mid] <= pos) lo = mid; else hi = mid;
             }
-            id = ids[pos];
-            const uint8_t* code = codes + (uint64_t)pos * m;
-            const uint8_t* rcode = rcodes + (uint64_t)pos * mr;
-            const float* x = queries + (int64_t)q * d;
+            const float* x = queries + (int64_t)p0.q * d;
             const float* cl = coarse + (int64_t)lo * d;
-            for (int e = 4 * t; e < d; e += 32) {
-                const int j = e / dsub, jr = e / dsub_r;
-                float4 y = *reinterpret_cast<const float4*>(cl + e);
-                const float4 pv = *reinterpret_cast<const float4*>(pq + ((int64_t)j * IVFR_KS + code[j]) * dsub + (e - j * dsub));
-                y.x += pv.x; y.y += pv.y; y.z += pv.z; y.w += pv.w;
-                const float4 rv = *reinterpret_cast<const float4*>(s_rq + (jr * IVFR_KS + rcode[jr]) * dsub_r + (e - jr * dsub_r));
-                y.x += rv.x; y.y += rv.y; y.z += rv.z; y.w += rv.w;
-                const float4 xv = *reinterpret_cast<const float4*>(x + e);
-                const float a = xv.x - y.x, b = xv.y - y.y, cc = xv.z - y.z, dd = xv.w - y.w;
-                acc = fmaf(a, a, acc); acc = fmaf(b, b, acc); acc = fmaf(cc, cc, acc); acc = fmaf(dd, dd, acc);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (k < nit) {
+                    const int e = 4 * t + 32 * k;
+                    const int j = e / dsub, jr = e / dsub_r;
+                    float4 y = *reinterpret_cast<const float4*>(cl + e);
+                    const float4 pv = *reinterpret_cast<const float4*>(pq + ((int64_t)j * IVFR_KS + g0.cb[k]) * dsub + (e - j * dsub));
+                    y.x += pv.x; y.y += pv.y; y.z += pv.z; y.w += pv.w;
+                    const float4 rv = *reinterpret_cast<const float4*>(s_rq + (jr * IVFR_KS + g0.rb[k]) * dsub_r + (e - jr * dsub_r));
+                    y.x += rv.x; y.y += rv.y; y.z += rv.z; y.w += rv.w;
+                    const float4 xv = *reinterpret_cast<const float4*>(x + e);
+                    const float a = xv.x - y.x, b = xv.y - y.y, cc = xv.z - y.z, dd = xv.w - y.w;
+                    acc = fmaf(a, a, acc); acc = fmaf(b, b, acc); acc = fmaf(cc, cc, acc); acc = fmaf(dd, dd, acc);
+                }
             }
         }
         acc += __shfl_xor(acc, 4, 64);
         acc += __shfl_xor(acc, 2, 64);
         acc += __shfl_xor(acc, 1, 64);
-        if (t == 0 && slot < kprime) {
-            const int64_t o = (int64_t)q * kprime + slot;
+        if (t == 0 && p0.slot < kprime) {
+            const int64_t o = (int64_t)p0.q * kprime + p0.slot;
             if (live) {
-                keys[o] = ((uint64_t)__float_as_uint(acc) << 32) | (uint32_t)id;
+                keys[o] = ((uint64_t)__float_as_uint(acc) << 32) | (uint32_t)g0.id;
                 if (refined_out) refined_out[o] = acc;
-                if (ids_out) ids_out[o] = id;
+                if (ids_out) ids_out[o] = g0.id;
             } else {
                 keys[o] = ~0ull;
                 if (refined_out) refined_out[o] = INFINITY;
                 if (ids_out) ids_out[o] = -1;
             }
         }
+        p0 = p1; p1 = p2; g0 = g1;
     }
 }
 
