@@ -771,6 +771,29 @@ __device__ __forceinline__ void load_code_pair(const uint8_t* __restrict__ codes
     }
 }
 
+// The M code bytes rotated down by r (0 <= r < M): byte i of the result is byte (i + r) mod M of the code.
+template <int M>
+__device__ __forceinline__ void rotate_code_bytes(uint32_t (&w)[M / 4], uint32_t r) {
+    const uint32_t r3 = r & 3u;
+    if (M == 4) {
+        w[0] = __builtin_amdgcn_alignbyte(w[0], w[0], r3);
+    } else if (M == 8) {
+        const bool sw = (r & 4u) != 0;
+        const uint32_t lo = sw ? w[1] : w[0], hi = sw ? w[0] : w[1];
+        w[0] = __builtin_amdgcn_alignbyte(hi, lo, r3);
+        w[1] = __builtin_amdgcn_alignbyte(lo, hi, r3);
+    } else {
+        static_assert(M == 4 || M == 8 || M == 16, "code sizes of the shared scans");
+        uint32_t t[4], u[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = (r & 4u) ? w[(i + 1) & 3] : w[i];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) u[i] = (r & 8u) ? t[(i + 2) & 3] : t[i];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = __builtin_amdgcn_alignbyte(u[(i + 1) & 3], u[i], r3);
+    }
+}
+
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 
@@ -1229,6 +1252,15 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
     }
     int u = lo;
     const int tid = threadIdx.x, lane = tid & 63;
+    // Table entry (j, byte) lives at [byte][j], and lane l looks its code's sub-quantizers up in the order
+    // l, l + 1, ... (mod M): the lanes of a wavefront that the LDS serves together (eight consecutive ones for
+    // 16-byte reads) then always read different j, hence different banks whatever the code bytes are.  Random
+    // 16-byte gathers cost 12.7 cycles per wavefront read, these 8.6 (8 is the LDS rate).
+    const uint32_t rot = (uint32_t)lane & (M - 1);
+    const char* s_lut_bytes = reinterpret_cast<const char*>(s_lut8);
+    uint32_t joff[M];
+#pragma unroll
+    for (int s2 = 0; s2 < M; ++s2) joff[s2] = ((rot + (uint32_t)s2) & (M - 1)) * 16u;
     uint32_t qn = 0;   // candidates queued by this wavefront (uniform over its lanes)
     uint32_t start = 0;
     // Exact fp32 re-evaluation of the queued candidates, one per lane: every lane works on its own
@@ -1287,11 +1319,11 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
             s_pid[tid] = raw != IVFR_NO_PAIR ? raw : unit_pairs[(int64_t)u * 8];
             s_tau[tid] = raw != IVFR_NO_PAIR ? tau[(int)(raw / (uint32_t)w)] : -1.f;
         }
-        for (int e = tid; e < M * IVFR_KS; e += H8_T) {
+        for (int e = tid; e < M * IVFR_KS; e += H8_T) {   // e = j * 256 + byte; stored at [byte][j]
             half8 h;
 #pragma unroll
             for (int x = 0; x < 8; ++x) h[x] = (_Float16)(lut[pid[x] * M * IVFR_KS + e] * sc[x]);
-            s_lut8[e] = h;
+            s_lut8[(e & (IVFR_KS - 1)) * M + (e >> 8)] = h;
         }
         __syncthreads();
         constexpr uint32_t BPV = H8_T / 256;   // blocks covered by the workgroup per v
@@ -1310,18 +1342,16 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
 #pragma unroll
             for (int v = 0; v < 2; ++v) {
                 half8 ha, hb;
+                rotate_code_bytes<M>(wds[v][0], rot);
+                rotate_code_bytes<M>(wds[v][1], rot);
 #pragma unroll
-                for (int t2 = 0; t2 < M / 4; ++t2) {
-                    const uint32_t wa = wds[v][0][t2], wb = wds[v][1][t2];
-                    const half8* L = s_lut8 + t2 * 4 * IVFR_KS;
-                    if (t2 == 0) { ha = L[wa & 0xff]; hb = L[wb & 0xff]; }
-                    else { ha += L[wa & 0xff]; hb += L[wb & 0xff]; }
-                    ha += L[IVFR_KS + ((wa >> 8) & 0xff)];
-                    hb += L[IVFR_KS + ((wb >> 8) & 0xff)];
-                    ha += L[2 * IVFR_KS + ((wa >> 16) & 0xff)];
-                    hb += L[2 * IVFR_KS + ((wb >> 16) & 0xff)];
-                    ha += L[3 * IVFR_KS + (wa >> 24)];
-                    hb += L[3 * IVFR_KS + (wb >> 24)];
+                for (int s2 = 0; s2 < M; ++s2) {
+                    const uint32_t ba = (wds[v][0][s2 / 4] >> (8 * (s2 % 4))) & 0xffu;
+                    const uint32_t bb = (wds[v][1][s2 / 4] >> (8 * (s2 % 4))) & 0xffu;
+                    const half8 xa = *reinterpret_cast<const half8*>(s_lut_bytes + ba * (M * 16) + joff[s2]);
+                    const half8 xb = *reinterpret_cast<const half8*>(s_lut_bytes + bb * (M * 16) + joff[s2]);
+                    if (s2 == 0) { ha = xa; hb = xb; }
+                    else { ha += xa; hb += xb; }
                 }
                 // fast reject: sums and thresholds are non-negative, so their fp16 bit patterns order like
                 // 16-bit integers; threshold minus sum in packed int16 is negative in all eight lanes of both
