@@ -846,24 +846,41 @@ __device__ __forceinline__ void half_unit_pass(const uint8_t* __restrict__ codes
         s_lut4[e] = h;
     }
     __syncthreads();
+    // exact re-evaluation of the queued candidates, one per lane; one append atomic per query and round
     auto drain = [&]() {
         for (uint32_t base = 0; base < wq.n; base += 64) {
             const uint32_t i = base + lane;
+            uint32_t e = 0, mask = 0;
+            uint32_t wd[M / 4];
+#pragma unroll
+            for (int t2 = 0; t2 < M / 4; ++t2) wd[t2] = 0;
             if (i < wq.n) {
-                const uint32_t e = wq.est[i], mask = wq.pos[i];
-                uint32_t wd[M / 4];
+                e = wq.est[i];
+                mask = wq.pos[i];
                 const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e) * M);
 #pragma unroll
                 for (int t2 = 0; t2 < M / 4; ++t2) wd[t2] = src[t2];
+            }
 #pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    if ((mask >> x) & 1u) {
-                        const float est = adc_sum<M>(lut + pid[x] * M * IVFR_KS, wd);
-                        if (est <= t[x]) {
-                            const uint32_t slot = atomicAdd(cnt[x], 1u);
-                            if (slot < cap[x]) qc[x][slot] = make_uint2(__float_as_uint(est), start + e);
-                        }
-                    }
+            for (int x = 0; x < 4; ++x) {
+                const bool mine = ((mask >> x) & 1u) != 0;
+                if (__ballot(mine) == 0) continue;
+                float est = 0.f;
+                bool keep = false;
+                if (mine) {
+                    est = adc_sum<M>(lut + pid[x] * M * IVFR_KS, wd);
+                    keep = est <= t[x];
+                }
+                const uint64_t kb = __ballot(keep);
+                if (kb == 0) continue;
+                const int leader = __ffsll((long long)kb) - 1;
+                uint32_t first = 0;
+                if (lane == leader) first = atomicAdd(cnt[x], (uint32_t)__popcll(kb));
+                first = __builtin_amdgcn_readlane(first, leader);
+                if (keep) {
+                    const uint32_t slot = first + __builtin_amdgcn_mbcnt_hi((uint32_t)(kb >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)kb, 0u));
+                    if (slot < cap[x]) qc[x][slot] = make_uint2(__float_as_uint(est), start + e);
+                }
             }
         }
         wq.n = 0;
@@ -1264,27 +1281,47 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
     uint32_t qn = 0;   // candidates queued by this wavefront (uniform over its lanes)
     uint32_t start = 0;
     // Exact fp32 re-evaluation of the queued candidates, one per lane: every lane works on its own
-    // (entry, query) combinations, so the table reads and the appends of a whole queue overlap.
+    // (entry, query) combinations, so the table reads of a whole queue overlap.  What is kept is appended with
+    // one atomic per query and round (the lanes that keep something for the same query share it): the counters
+    // of a batch sit in a few cache lines, and an atomic per record would queue up behind them.
     auto drain = [&]() {
         for (uint32_t base = 0; base < qn; base += 64) {
             const uint32_t i = base + lane;
+            uint32_t e = 0, mask = 0;
+            uint32_t wd[M / 4];
+#pragma unroll
+            for (int t2 = 0; t2 < M / 4; ++t2) wd[t2] = 0;
             if (i < qn) {
-                const uint32_t e = q_entry[i];
-                uint32_t mask = q_mask[i];
-                uint32_t wd[M / 4];
+                e = q_entry[i];
+                mask = q_mask[i];
                 const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e) * M);
 #pragma unroll
                 for (int t2 = 0; t2 < M / 4; ++t2) wd[t2] = src[t2];
-                while (mask) {
-                    const int x = __ffs(mask) - 1;
+            }
+            while (__ballot(mask != 0) != 0) {   // one query per lane and round
+                int x = -1;
+                float est = 0.f;
+                bool keep = false;
+                if (mask) {
+                    x = __ffs(mask) - 1;
                     mask &= mask - 1;
-                    const uint32_t pidx = s_pid[x];
-                    const float est = adc_sum<M>(lut + (int64_t)pidx * M * IVFR_KS, wd);
-                    if (est <= s_tau[x]) {
-                        const int q = (int)(pidx / (uint32_t)w);
-                        const uint32_t slot = atomicAdd(cand_cnt + q, 1u);
+                    est = adc_sum<M>(lut + (int64_t)s_pid[x] * M * IVFR_KS, wd);
+                    keep = est <= s_tau[x];
+                }
+                uint64_t todo = __ballot(keep);
+                while (todo) {   // one round per query that has records in this wavefront
+                    const int leader = __ffsll((long long)todo) - 1;
+                    const int xl = __builtin_amdgcn_readlane(x, leader);
+                    const uint64_t same = __ballot(keep && x == xl);
+                    const int q = (int)(s_pid[xl] / (uint32_t)w);
+                    uint32_t first = 0;
+                    if (lane == leader) first = atomicAdd(cand_cnt + q, (uint32_t)__popcll(same));
+                    first = __builtin_amdgcn_readlane(first, leader);
+                    if (keep && x == xl) {
+                        const uint32_t slot = first + __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
                         if (slot < lay.cap(q)) cand[lay.base(q) + slot] = make_uint2(__float_as_uint(est), start + e);
                     }
+                    todo &= ~same;
                 }
             }
         }

@@ -66,9 +66,11 @@ struct EventPair {
 // Upper limit of a query's sample (entries); beyond it the stride widens and the bound loosens.
 #define IVFR_MAX_SAMPLE 131072u
 // Queries whose bound is expected to pass more than this share of their estimates stay out of the
-// half-precision units of eight (the fp32 re-evaluation of what passes would dominate: measured on the
-// 10^9-vector workload, 0.04 % passing runs 2x faster than the fp32 units of four, 0.4 % runs 1.3x slower).
-#define IVFR_HALF_UNIT_FRAC 0.002f
+// half-precision units (the fp32 re-evaluation of what passes would dominate).  Measured: at 10^9 vectors a
+// query set passing 0.04 % runs twice as fast as in the fp32 units of four; the paper's k' = 20000 (0.5-0.8 %)
+// runs 11 % faster with 0.01 than with 0.002; at 10^8 vectors and k' = 10000 (about 1 %, half of the queries
+// on either side) 0.01 is 4 % faster than 0.002 and 0.02 is 2 % slower.
+#define IVFR_HALF_UNIT_FRAC 0.01f
 
 extern "C" int ivfr_search_trace(ivfr_index* ix, const float* queries, int64_t nq, int32_t w, int32_t kprime,
                                  int32_t k, int32_t* ids_out, float* dist_out, int32_t* probe_out,
