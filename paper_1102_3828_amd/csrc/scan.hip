@@ -1549,27 +1549,47 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
     const uint32_t norm_lane = (uint32_t)h * (M / 2) * (IVFR_KS * 4);
     const uint32_t hmask = h ? 0xffffffffu : 0u;
 
+    // exact re-evaluation of the queued candidates, one per lane; one append atomic per query and round
     auto drain = [&]() {
         for (uint32_t base = 0; base < qn; base += 64) {
             const uint32_t i = base + lane;
+            uint32_t e = 0, hh = 0, mask = 0;
+            uint32_t wd[M / 4];
+#pragma unroll
+            for (int t2 = 0; t2 < M / 4; ++t2) wd[t2] = 0;
             if (i < qn) {
-                const uint32_t e = q_entry[i] & 0x7fffffffu, hh = q_entry[i] >> 31;
-                uint32_t mask = q_mask[i];
-                uint32_t wd[M / 4];
+                e = q_entry[i] & 0x7fffffffu;
+                hh = q_entry[i] >> 31;
+                mask = q_mask[i];
                 const uint32_t* src = reinterpret_cast<const uint32_t*>(codes + ((uint64_t)start + e) * M);
 #pragma unroll
                 for (int t2 = 0; t2 < M / 4; ++t2) wd[t2] = src[t2];
-                while (mask) {
+            }
+            while (__ballot(mask != 0) != 0) {   // one row per lane and round
+                int r64 = -1;
+                float est = 0.f;
+                bool keep = false;
+                if (mask) {
                     const int x = __ffs(mask) - 1;
                     mask &= mask - 1;
-                    const int r64 = (x >> 4) * 32 + 8 * ((x & 15) >> 2) + 4 * (int)hh + (x & 3);
-                    const uint32_t pidx = s_pid[r64];
-                    const float est = adc_sum<M>(lut + (int64_t)pidx * M * IVFR_KS, wd);
-                    if (est <= s_tau[r64]) {
-                        const int q = (int)(pidx / (uint32_t)w);
-                        const uint32_t slot = atomicAdd(cand_cnt + q, 1u);
+                    r64 = (x >> 4) * 32 + 8 * ((x & 15) >> 2) + 4 * (int)hh + (x & 3);
+                    est = adc_sum<M>(lut + (int64_t)s_pid[r64] * M * IVFR_KS, wd);
+                    keep = est <= s_tau[r64];
+                }
+                uint64_t todo = __ballot(keep);
+                while (todo) {   // one round per row that has records in this wavefront
+                    const int leader = __ffsll((long long)todo) - 1;
+                    const int rl = __builtin_amdgcn_readlane(r64, leader);
+                    const uint64_t same = __ballot(keep && r64 == rl);
+                    const int q = (int)(s_pid[rl] / (uint32_t)w);
+                    uint32_t first = 0;
+                    if (lane == leader) first = atomicAdd(cand_cnt + q, (uint32_t)__popcll(same));
+                    first = __builtin_amdgcn_readlane(first, leader);
+                    if (keep && r64 == rl) {
+                        const uint32_t slot = first + __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
                         if (slot < lay.cap(q)) cand[lay.base(q) + slot] = make_uint2(__float_as_uint(est), start + e);
                     }
+                    todo &= ~same;
                 }
             }
         }
