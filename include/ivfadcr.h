@@ -142,7 +142,7 @@ int ivfr_set_list_sharing(ivfr_index* index, int32_t mode);
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
  *   full_mult   (8)    a query that visits at most full_mult*k' entries keeps every estimate; a
  *                      larger one first scores a sample of its entries (the same leading fraction of
- *                      every visited list, at least 4/k', about 16 (k' S)^(1/3) entries of the S visited)
+ *                      every visited list, at least 2/k', about 16 (k' S)^(1/3) entries of the S visited)
  *                      to bound the k'-th smallest estimate, and the scan keeps only estimates below
  *                      the bound
  *   cap_mult    (16)   such a query's candidate buffer holds max(cap_mult*k', min_cap) records, or its

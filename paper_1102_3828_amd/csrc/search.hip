@@ -62,7 +62,7 @@ struct EventPair {
 
 // Smallest Poisson mean of true k'-best entries wanted inside the sample: the sample stride (one entry in
 // `stride` is sampled) never exceeds k' / mu; the plan narrows it when a larger sample pays off.
-#define IVFR_SAMPLE_MU 4
+#define IVFR_SAMPLE_MU 2
 // Upper limit of a query's sample (entries); beyond it the stride widens and the bound loosens.
 #define IVFR_MAX_SAMPLE 131072u
 // Queries whose bound is expected to pass more than this share of their estimates stay out of the
