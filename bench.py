@@ -26,11 +26,11 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 # launch (m bytes per (query, entry) estimate), for the default run of cfg4; other workloads and settings: null.
 #   per-pair scan (sharing mode 0):   101.45 GB read + 0.05 GB written for 101.14 GB of code bytes
 #   fp32 units of four (--sharing 1): 24.89 GB read + 0.16 GB written for 96.14 GB (one read serves four queries)
-#   fp16 units of eight (default):    11.12 GB read + 0.12 GB written for 92.97 GB (one read serves eight queries,
+#   fp16 units of eight (default):    11.13 GB read + 0.05 GB written for 92.97 GB (one read serves eight queries,
 #                                     and units of one list that run side by side on an XCD share it in L2)
 MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 101.500 / 101.141,
                           ("cfg4", "adc_scan_shared_kernel"): 25.051 / 96.142,
-                          ("cfg4", "adc_scan_shared8h_kernel"): 11.243 / 92.966}
+                          ("cfg4", "adc_scan_shared8h_kernel"): 11.185 / 92.966}
 LDS_PEAK_GBS = 256 * 128 * 2.4    # 256 CUs x 128 B/clk x 2.4 GHz
 
 
