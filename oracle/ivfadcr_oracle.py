@@ -29,7 +29,11 @@ Eq. (5)); m' = 0 reduces to plain IVFADC (Table 1 rows with m' = 0); v = c and k
 the exact ordering over reconstructions (search steps 1-3 of section 3.2); data on the
 quantizer lattice gives exact distances; encoders are brute-force argmins (Eq. (8)); the
 distance routine is checked against hand loops; k-means against a library Lloyd and its
-monotone objective.  Absolute recall values of Table 1 need the BIGANN data: parity
+monotone objective; the truncated query stage (v < c lists visited, k' below what is scanned)
+against explicit loops and sorted() over (distance, index) tuples, with constructed exact ties
+at the v-th list, the k'-th estimate and the k-th refined distance; train() against a
+training set planted on a three-level lattice that the coarse quantizer, q_c and q_r must
+recover level by level (Eq. (7)).  Absolute recall values of Table 1 need the BIGANN data: parity
 unpinned for those (only the table's ordering in m' is checked).
 """
 from __future__ import annotations
