@@ -6,10 +6,17 @@ is already resident in HBM.  The index is built on the GPU from the seeded synth
 generator before the timed region.  Prints one JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg4]
+
+Two timed loops of K steps each run on the same index: the library's default setting (queries
+of a batch that visit the same list share one pass over it; the shared passes pre-filter in
+half precision and record exact fp32 estimates), which gives `value`, and list-sharing mode 0
+(every (query, list) pair streams its list from HBM on its own, fp32 throughout), which gives
+`value_f32_per_pair` and the HBM `roofline` of the per-pair ADC scan kernel.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -19,26 +26,49 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
-
-# HBM bytes moved per scan launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy
-# of known size (profiles/search_cfg4_hbm_traffic.txt), stored as a ratio to the algorithmic bytes of the
-# launch (m bytes per (query, entry) estimate), for the default run of cfg4; other workloads and settings: null.
-#   per-pair scan (sharing mode 0):   101.45 GB read + 0.05 GB written for 101.14 GB of code bytes
-#   fp32 units of four (--sharing 1): 24.89 GB read + 0.16 GB written for 96.14 GB (one read serves four queries)
-#   fp16 units of eight (default):    11.13 GB read + 0.05 GB written for 92.97 GB (one read serves eight queries,
-#                                     and units of one list that run side by side on an XCD share it in L2)
-MEASURED_TRAFFIC_RATIO = {("cfg4", "adc_scan_kernel"): 101.500 / 101.141,
-                          ("cfg4", "adc_scan_shared_kernel"): 25.051 / 96.142,
-                          ("cfg4", "adc_scan_shared8h_kernel"): 11.185 / 92.966}
-LDS_PEAK_GBS = 256 * 128 * 2.4    # 256 CUs x 128 B/clk x 2.4 GHz
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
+MFMA_F32_PEAK_TFLOPS = 157.3     # dense fp32 matrix peak
+# LDS read peak used for the shared-list scans: 256 compute units x 128 bytes per clock x 2.4 GHz.  The 128 B/clk
+# is the rate at which a compute unit's LDS returns data to a wavefront's 16-byte reads (eight lanes per clock);
+# profiles/lds_gather_microbenchmark.txt holds the measurement behind it.
+LDS_PEAK_GBS = 256 * 128 * 2.4
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "search_cfg4_hbm_traffic.txt")
+SCAN_SOURCES = ("paper_1102_3828_amd/csrc/scan.hip", "paper_1102_3828_amd/csrc/search.hip")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_index(cfg, dm, n_gt, args):
+def scan_source_hash():
+    h = hashlib.sha256()
+    for rel in SCAN_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic():
+    """HBM bytes per launch from the committed rocprofv3 counter summary, as ratios to the algorithmic bytes of the
+    same launches: {kernel: ratio}.  Used only when the summary was made from the scan sources this run uses
+    (its header records their hash) and the run is the plain cfg4 workload the summary covers; else {}."""
+    out = {}
+    try:
+        with open(TRAFFIC_PROFILE) as f:
+            lines = f.read().splitlines()
+    except OSError:
+        return out
+    recorded = [ln.split()[-1] for ln in lines if ln.startswith("scan_source_sha256:")]
+    if not recorded or recorded[0] != scan_source_hash():
+        return out
+    for ln in lines:
+        if ln.startswith("traffic_ratio "):
+            _, kernel, ratio = ln.split()
+            out[kernel] = float(ratio)
+    return out
+
+
+def build_index(cfg, dm, n_gt, train_iters):
     """Train, encode and finalize on the GPU; brute-force ground truth of the first n_gt queries
     is accumulated from the same generated chunks (exact: integer data, fp32 products < 2^24)."""
     import torch
@@ -49,11 +79,11 @@ def build_index(cfg, dm, n_gt, args):
     t0 = time.time()
     ix = pkg.Index(cfg.d, cfg.c, cfg.m, cfg.m_refine)
     train = dm.generate(sd.STREAM_TRAIN, 0, cfg.n_train)
-    ix.train(train, iters=args.train_iters, seed=1)
+    ix.train(train, iters=train_iters, seed=1)
     del train
     torch.cuda.synchronize()
     t_train = time.time() - t0
-    log(f"[bench] trained quantizers on {cfg.n_train} vectors in {t_train:.1f}s")
+    log(f"[bench] {cfg.name}: trained quantizers on {cfg.n_train} vectors in {t_train:.1f}s")
 
     queries_u8 = dm.generate(sd.STREAM_QUERY, 0, cfg.n_query)
     xq = queries_u8.float().contiguous()
@@ -78,39 +108,203 @@ def build_index(cfg, dm, n_gt, args):
                 gt_i = torch.where(better, imin + a + s, gt_i)
         if j % 10 == 9 or a + n >= cfg.N:
             torch.cuda.synchronize()
-            log(f"[bench] added {a + n} / {cfg.N} vectors ({time.time() - t0:.1f}s)")
+            log(f"[bench] {cfg.name}: added {a + n} / {cfg.N} vectors ({time.time() - t0:.1f}s)")
     del buf
     ix.finalize()
     torch.cuda.synchronize()
     t_add = time.time() - t0
-    log(f"[bench] encoded + finalized {cfg.N} vectors in {t_add:.1f}s")
     return ix, xq, queries_u8, gt_i[:, 0].cpu().numpy(), dict(train_s=t_train, add_s=t_add)
 
 
-def cpu_baseline(ix, cfg, queries_u8, gpu_ids, budget_s=15.0, max_q=64):
-    """The CPU oracle's search on the exported index, timed on this host for a bounded sample."""
+# ---------------------------------------------------------------------------------------------------------------
+# CPU baseline: the oracle, as it stands, on the host cores.  Worker processes are started with `spawn`, import
+# numpy and the oracle only (never the GPU runtime), and map the exported index from files in /dev/shm.
+
+def _oracle_worker(job):
+    """Searches queries job['rows'] (indices into the saved query array) one at a time until done or out of time."""
     import numpy as np
+    from threadpoolctl import threadpool_limits
     from oracle import ivfadcr_oracle as orc
+    d = job["dir"]
+    ld = lambda name: np.load(os.path.join(d, name + ".npy"), mmap_mode="r")
+    rq = ld("rq") if job["has_rq"] else None
+    index = orc.Index(orc.Codebooks(np.asarray(ld("coarse")), np.asarray(ld("pq")), None if rq is None else np.asarray(rq)),
+                      np.asarray(ld("offsets")), ld("ids"), ld("codes"), ld("rcodes"))
+    X = np.asarray(ld("queries"))
+    out = []
+    t_start = time.time()
+    with threadpool_limits(limits=1):
+        for qi in job["rows"]:
+            t0 = time.time()
+            ids, _, tr = orc.search_one(X[qi], index, job["w"], job["kprime"], job["k"])
+            out.append((int(qi), time.time() - t0, int(tr.scanned), ids.tolist()))
+            if time.time() - t_start > job["budget_s"]:
+                break
+    return out
+
+
+def start_oracle_pool():
+    """Worker processes for the CPU baseline, started (spawn) before this process touches the GPU."""
+    import multiprocessing as mp
+    workers = max(1, min(16, os.cpu_count() or 1))
+    pool = mp.get_context("spawn").Pool(workers)
+    pool.map(_noop, range(4 * workers))                    # processes up, numpy and the oracle imported
+    return pool, workers
+
+
+def cpu_baseline(pool, workers, ix, cfg, queries_u8, gpu_ids, budget_s=20.0, per_worker=4):
+    """The CPU oracle's search on the exported index: one worker process per host core (at most 16, this box's
+    share), every worker searching its queries one at a time in a single thread, for a bounded sample."""
+    import shutil
+    import tempfile
+    import numpy as np
+    n_sample = min(len(gpu_ids), cfg.n_query, workers * per_worker)
     coarse, pq, rq = ix.get_codebooks()
     t0 = time.time()
     offsets, ids, codes, rcodes = ix.export()
-    log(f"[bench] exported index to host in {time.time() - t0:.1f}s")
-    index = orc.Index(orc.Codebooks(coarse, pq, rq), offsets, ids, codes, rcodes)
-    X = queries_u8[:max_q].cpu().numpy()
-    done, same, scanned = 0, 0, 0
-    t0 = time.time()
-    for qi in range(len(X)):
-        o_ids, _, tr = orc.search_one(X[qi], index, cfg.w, cfg.kprime, cfg.k)
-        done += 1
-        scanned += tr.scanned
-        same += int((o_ids == gpu_ids[qi]).sum())
-        if time.time() - t0 > budget_s:
-            break
-    el = time.time() - t0
-    return {"value": done / el, "unit": "queries/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {done} queries of the same workload, one at a time (numpy float64, single thread)",
-            "adc_codes_per_s": scanned / el,
-            "ids_identical_to_gpu": same / float(done * cfg.k)}
+    base = "/dev/shm" if os.path.isdir("/dev/shm") else None
+    tmp = tempfile.mkdtemp(prefix="ivfr_oracle_", dir=base)
+    try:
+        for name, arr in (("offsets", offsets), ("ids", ids), ("codes", codes), ("rcodes", rcodes), ("coarse", coarse),
+                          ("pq", pq), ("queries", queries_u8[:n_sample].cpu().numpy())):
+            np.save(os.path.join(tmp, name + ".npy"), arr)
+        if rq is not None:
+            np.save(os.path.join(tmp, "rq.npy"), rq)
+        del offsets, ids, codes, rcodes
+        log(f"[bench] exported index to {tmp} in {time.time() - t0:.1f}s; oracle on {n_sample} queries, {workers} processes")
+        jobs = [dict(dir=tmp, has_rq=rq is not None, rows=list(range(r, n_sample, workers)), w=cfg.w, kprime=cfg.kprime,
+                     k=cfg.k, budget_s=budget_s) for r in range(workers)]
+        jobs = [j for j in jobs if j["rows"]]
+        t0 = time.time()
+        parts = pool.map(_oracle_worker, jobs, chunksize=1)
+        wall = time.time() - t0
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
+    res = [r for p in parts for r in p]
+    done = len(res)
+    scanned = sum(r[2] for r in res)
+    same = sum(int((np.asarray(r[3]) == gpu_ids[r[0]]).sum()) for r in res)
+    per_query = sum(r[1] for r in res) / max(done, 1)
+    return {"value": done / wall, "unit": "queries/s", "cores": len(jobs), "kind": "oracle",
+            "sample": f"{done} of the first {n_sample} queries of the same workload on the exported index, "
+                      f"{len(jobs)} worker processes (spawn, one thread each, index mapped from /dev/shm), "
+                      "each searching its queries one at a time (numpy float64)",
+            "adc_codes_per_s": scanned / wall,
+            "single_core_queries_per_s": 1.0 / per_query if per_query > 0 else None,
+            "single_core_note": "1 / mean seconds per query inside a worker while the other workers run",
+            "host_cpu_count": os.cpu_count(),
+            "ids_identical_to_gpu": same / float(max(done, 1) * cfg.k)}
+
+
+def _noop(_):
+    import numpy  # noqa: F401
+    from oracle import ivfadcr_oracle  # noqa: F401
+    return 0
+
+
+# ---------------------------------------------------------------------------------------------------------------
+
+def timed_loop(ix, batches, cfg, steps, warmup, label):
+    """W untimed + K timed search calls; HIP events around the list-scan launches only (profiling level 1).
+    Returns wall seconds, summed statistics and summed stage times."""
+    import torch
+    n_batches = len(batches)
+    for s in range(warmup):
+        t0 = time.perf_counter()
+        ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
+        log(f"[bench] {cfg.name} {label} warmup step {s}: {1e3 * (time.perf_counter() - t0):.2f} ms, {ix.search_stats()}")
+    ix.set_profiling(1)
+    acc = {}
+    stage_ms = {}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
+        for name, v in ix.search_stats().items():
+            acc[name] = acc.get(name, 0) + v
+        acc["batch_reruns"] = acc.get("batch_reruns", 0) + ix.workspace_info()["batch_reruns"]
+        for name, ms in ix.stage_times().items():
+            stage_ms[name] = stage_ms.get(name, 0.0) + ms
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ix.set_profiling(0)
+    return elapsed, acc, stage_ms
+
+
+def other_stage_times(ix, batches, cfg, steps, reps=3):
+    """Per-stage HIP-event times of the stages that are not list scans, from `reps` extra calls with events around
+    every stage (they cost the host about 0.1 ms per call, so they stay out of the timed loops); scaled to `steps`."""
+    ix.set_profiling(2)
+    out = {}
+    for s in range(reps):
+        ix.search(batches[s % len(batches)], cfg.w, cfg.kprime, cfg.k)
+        for name, ms in ix.stage_times().items():
+            if not name.startswith("scan") and not name.startswith("host"):
+                out[name] = out.get(name, 0.0) + ms * steps / reps
+    ix.set_profiling(0)
+    return out
+
+
+def recall_of(ids, gt, n_gt, k):
+    return {f"recall@{r}": float((ids[:n_gt, :r] == gt[:n_gt, None]).any(axis=1).mean())
+            for r in (1, 10, 100) if r <= k and n_gt}
+
+
+def derived_rates(cfg, B, stage_ms_per_step, codes_per_step):
+    """MFMA utilisation of the two dense contractions and the re-rank's data rates, from the stage timers."""
+    out = {}
+    co, lu, rr = (stage_ms_per_step.get(n, 0.0) for n in ("coarse", "lut", "rerank"))
+    if co > 0:
+        fl = 2.0 * B * cfg.c * cfg.d
+        out["coarse_gemm"] = {"flop_per_step": fl, "ms": co, "tflops": fl / co / 1e9,
+                              "mfma_util": fl / co / 1e9 / MFMA_F32_PEAK_TFLOPS}
+    if lu > 0:
+        fl = 2.0 * B * cfg.w * 256 * cfg.d
+        out["lut_gemm"] = {"flop_per_step": fl, "ms": lu, "tflops": fl / lu / 1e9,
+                           "mfma_util": fl / lu / 1e9 / MFMA_F32_PEAK_TFLOPS}
+    if rr > 0:
+        cand = float(B) * min(cfg.kprime, codes_per_step / max(B, 1))
+        useful = cand * (cfg.m + cfg.m_refine + 4)
+        out["rerank"] = {"candidates_per_step": cand, "ms": rr, "useful_bytes": useful,
+                         "useful_gbs": useful / rr / 1e6, "candidates_per_s": cand / rr * 1e3}
+    return out
+
+
+def small_config_entry(name, args):
+    """One of the smaller workloads end to end: build, default-setting timed loop, recall."""
+    import torch
+    import synthdata as sd
+    from synthdata.gpu import DeviceMixture
+    cfg = sd.CONFIGS[name]
+    dm = DeviceMixture(cfg.mixture(), "cuda:0")
+    n_gt = min(args.gt_queries, cfg.n_query)
+    ix, xq, _, gt, build_t = build_index(cfg, dm, n_gt, args.train_iters)
+    B = min(cfg.batch, cfg.n_query)
+    ix.set_tuning(batch=min(B, 65535))
+    batches = [xq[i * B:(i + 1) * B].contiguous() for i in range(max(1, cfg.n_query // B))]
+    elapsed, acc, _ = timed_loop(ix, batches, cfg, args.steps, args.warmup, "default")
+    stage = other_stage_times(ix, batches, cfg, 1)
+    ix.set_list_sharing(0)
+    el0, acc0, st0 = timed_loop(ix, batches, cfg, args.steps, 1, "per-pair")
+    ix.set_list_sharing(2)
+    ids, _ = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
+    scan0 = st0.get("scan", 0.0) / args.steps
+    bytes0 = cfg.m * acc0["codes_scanned"] / args.steps
+    entry = {"workload": f"{cfg.name}: N={cfg.N} c={cfg.c} m={cfg.m} m'={cfg.m_refine} w={cfg.w} k'={cfg.kprime} k={cfg.k}, "
+                         f"{B} queries per step",
+             "queries_per_s": args.steps * B / elapsed, "ms_per_step": 1e3 * elapsed / args.steps,
+             "adc_codes_per_s": acc["codes_scanned"] / elapsed,
+             "recall": recall_of(ids.cpu().numpy(), gt, n_gt, cfg.k),
+             "per_pair_f32": {"queries_per_s": args.steps * B / el0, "ms_per_step": 1e3 * el0 / args.steps,
+                              "scan_ms": scan0, "scan_gbs": bytes0 / scan0 / 1e6 if scan0 > 0 else None,
+                              "scan_hbm_frac": bytes0 / scan0 / 1e6 / HBM_PEAK_GBS if scan0 > 0 else None},
+             "stage_ms": {k: round(v, 4) for k, v in stage.items()},
+             **derived_rates(cfg, B, stage, acc["codes_scanned"] / args.steps),
+             "build_seconds": build_t}
+    ix.close()
+    del ix
+    torch.cuda.empty_cache()
+    return entry
 
 
 def sweep(args):
@@ -120,7 +314,6 @@ def sweep(args):
       table2: equal-memory pairs (m, m') without inverted file
       fig3:   recall@10 against the database size, IVFADC+R, m' in {0, 8, 32}"""
     import dataclasses
-    import numpy as np
     import torch
     import synthdata as sd
     from synthdata.gpu import DeviceMixture
@@ -149,7 +342,7 @@ def sweep(args):
         cfg = dataclasses.replace(base, **st)
         n_gt = min(args.gt_queries, cfg.n_query)
         have = gt_cache.get(cfg.N)
-        ix, xq, _, gt, build_t = build_index(cfg, dm, 0 if have is not None else n_gt, args)
+        ix, xq, _, gt, build_t = build_index(cfg, dm, 0 if have is not None else n_gt, args.train_iters)
         if have is None:
             gt_cache[cfg.N] = gt
         gt = gt_cache[cfg.N]
@@ -169,8 +362,7 @@ def sweep(args):
         el = time.perf_counter() - t0
         ids, _ = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
         ids = ids.cpu().numpy()
-        rec = {f"recall@{r}": float((ids[:n_gt, :r] == gt[:n_gt, None]).any(axis=1).mean())
-               for r in (1, 10, 100) if r <= cfg.k}
+        rec = recall_of(ids, gt, n_gt, cfg.k)
         row = {"sweep": args.sweep, "N": cfg.N, "c": cfg.c, "w": cfg.w, "m": cfg.m, "m_refine": cfg.m_refine,
                "kprime": cfg.kprime, "k": cfg.k, "bytes_per_vector": cfg.m + cfg.m_refine + 4,
                "ms_per_query": 1e3 * el / (args.steps * B), "queries_per_s": args.steps * B / el,
@@ -200,13 +392,14 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-whole-set", action="store_true",
                     help="skip the extra calls that hand the workload's whole query set to one search call")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the per_config entries of the smaller workloads (cfg0, cfg1, cfg2)")
     ap.add_argument("--scan-groups", type=int, default=0)
     ap.add_argument("--per-pair", action="store_true",
-                    help="scan every (query, list) pair on its own (no sharing of a list between queries)")
+                    help="default loop in sharing mode 0 as well (every (query, list) pair on its own)")
     ap.add_argument("--sharing", type=int, default=2, choices=(0, 1, 2, 3),
-                    help="list sharing mode: 0 per pair, 1 fp32 units of four/two, 2 also fp16 units of eight, 3 also matrix-core units of 64")
-    ap.add_argument("--sweep-groups", default="",
-                    help="comma-separated scan workgroup counts: time a few steps with each (to stderr) before the run")
+                    help="list sharing mode of the default loop: 0 per pair, 1 fp32 units of four/two, 2 also fp16 units "
+                         "of eight, 3 also matrix-core units of 64")
     ap.add_argument("--sweep", default="", choices=("", "table1", "table2", "fig3"),
                     help="run a parameter sweep in the shape of the paper's Table 1, Table 2 or Figure 3 on the "
                          "synthetic generator (one JSON line per setting) instead of the benchmark")
@@ -223,8 +416,9 @@ def main():
         sweep(args)
         return
 
+    oracle_pool = None if args.no_cpu_baseline else start_oracle_pool()
+
     import dataclasses
-    import numpy as np
     import torch
     import synthdata as sd
     from synthdata.gpu import DeviceMixture
@@ -244,84 +438,50 @@ def main():
         cfg = dataclasses.replace(cfg, w=args.w)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    plain = not (args.N or args.kprime or args.k or args.m_refine >= 0 or args.c or args.w or args.batch)
+
+    # the smaller workloads first (their indexes are freed again before the large one is built)
+    per_config = {}
+    if not args.no_per_config and plain and args.config == "cfg4":
+        for name in ("cfg0", "cfg1", "cfg2"):
+            per_config[name] = small_config_entry(name, args)
+            log(f"[bench] {name}: {per_config[name]['queries_per_s']:.0f} queries/s")
+
     dm = DeviceMixture(cfg.mixture(), "cuda:0")
     n_gt = min(args.gt_queries, cfg.n_query)
-    ix, xq, queries_u8, gt, build_t = build_index(cfg, dm, n_gt, args)
+    ix, xq, queries_u8, gt, build_t = build_index(cfg, dm, n_gt, args.train_iters)
+    log(f"[bench] {cfg.name}: encoded + finalized {cfg.N} vectors in {build_t['add_s']:.1f}s")
     if args.scan_groups:
         ix.set_tuning(scan_groups=args.scan_groups)
     if args.per_pair:
         args.sharing = 0
-    ix.set_list_sharing(args.sharing)
     if args.batch:
         cfg = dataclasses.replace(cfg, batch=args.batch)
-
     B = min(cfg.batch, cfg.n_query)
-    ix.set_tuning(batch=min(B, 65535))
+    ix.set_tuning(batch=min(B, 65535), scan_groups=args.scan_groups)
     n_batches = max(1, cfg.n_query // B)
     batches = [xq[i * B:(i + 1) * B].contiguous() for i in range(n_batches)]
+    steps = max(args.steps, 1)
 
-    if args.sweep_groups:
-        ix.set_profiling(True)
-        for gcount in [int(x) for x in args.sweep_groups.split(",")]:
-            ix.set_tuning(scan_groups=gcount)
-            acc = {}
-            for s in range(4):
-                ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
-                if s:
-                    for name, ms in ix.stage_times().items():
-                        acc[name] = acc.get(name, 0.0) + ms / 3.0
-            log(f"[bench] scan_groups={gcount}: " + ", ".join(f"{k} {v:.3f}" for k, v in acc.items() if k.startswith("scan") or k == "sample"))
-        ix.set_profiling(False)
-        ix.set_tuning(scan_groups=args.scan_groups)
-    for s in range(args.warmup):
-        t0 = time.perf_counter()
-        ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
-        log(f"[bench] warmup step {s}: {1e3 * (time.perf_counter() - t0):.1f} ms, {ix.search_stats()}")
-    # The timed steps record HIP events around the list-scan launches only (the roofline's kernel time);
-    # the other stages are timed in three extra steps after the timed region (events around every stage
-    # cost the host about 0.1 ms per step).
-    ix.set_profiling(1)
-    torch.cuda.synchronize()
-    codes = 0
-    codes_shared = 0
-    codes_shared2 = 0
-    codes_shared8 = 0
-    codes_shared64 = 0
-    codes_streamed = 0
-    dense_total = 0
-    retries_total = 0
-    stage_ms = {}
-    scan_launches = 0
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
-        st = ix.search_stats()
-        pr = ix.stage_times()
-        codes += st["codes_scanned"]
-        codes_shared += st["codes_scanned_shared"]
-        codes_shared2 += st["codes_scanned_shared2"]
-        codes_shared8 += st["codes_scanned_shared8"]
-        codes_shared64 += st["codes_scanned_shared64"]
-        codes_streamed += st["codes_streamed"]
-        scan_launches += pr.pop("scan_launches")
-        for name, ms in pr.items():
-            stage_ms[name] = stage_ms.get(name, 0.0) + ms
-        dense_total += st["dense_fallbacks"]
-        retries_total += st["bound_retries"]
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    log(f"[bench] timed {args.steps} steps in {elapsed:.3f}s")
-    ix.set_profiling(2)
-    other_ms = {}
-    for s in range(3):
-        ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
-        pr = ix.stage_times()
-        pr.pop("scan_launches")
-        for name, ms in pr.items():
-            if not name.startswith("scan"):
-                other_ms[name] = other_ms.get(name, 0.0) + ms * args.steps / 3.0
-    stage_ms.update(other_ms)
-    ix.set_profiling(False)
+    # ---- timed loop 1: the library's default setting -> value
+    ix.set_list_sharing(args.sharing)
+    elapsed, acc, stage_ms = timed_loop(ix, batches, cfg, steps, args.warmup, f"sharing {args.sharing}")
+    log(f"[bench] timed {steps} steps in {elapsed:.3f}s (sharing mode {args.sharing})")
+    stage_ms.update(other_stage_times(ix, batches, cfg, steps))
+    g_ids, _ = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
+    g_ids = g_ids.cpu().numpy()
+    recall = recall_of(g_ids, gt, n_gt, cfg.k)
+
+    # ---- timed loop 2: every (query, list) pair on its own, fp32 throughout -> the per-pair scan's HBM roofline
+    if args.sharing != 0:
+        ix.set_list_sharing(0)
+        el0, acc0, st0 = timed_loop(ix, batches, cfg, steps, 1, "sharing 0")
+        p_ids, _ = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
+        same_bits = bool((p_ids.cpu().numpy() == g_ids).all())
+        ix.set_list_sharing(args.sharing)
+    else:
+        el0, acc0, st0, same_bits = elapsed, acc, stage_ms, True
+    log(f"[bench] timed {steps} steps in {el0:.3f}s (sharing mode 0)")
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
@@ -331,89 +491,68 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # accuracy on the ground-truth subset (first batch holds the first n_gt queries)
-    g_ids, g_dist = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
-    g_ids = g_ids.cpu().numpy()
-    recall = {}
-    for r in (1, 10, 100):
-        if r <= cfg.k and n_gt:
-            recall[f"recall@{r}"] = float((g_ids[:n_gt, :r] == gt[:n_gt, None]).any(axis=1).mean())
-
-    qps = args.steps * B / elapsed
-    steps = max(args.steps, 1)
-    # Dominant kernel: the shared-list scan when it does most of the work, else the per-pair scan.
-    # Algorithmic bytes = m bytes per (query, visited entry) estimate the kernel computes.
-    kernels = [("adc_scan_kernel", stage_ms.get("scan", 0.0) / steps,
-                (codes - codes_shared - codes_shared2 - codes_shared8 - codes_shared64) / steps),
-               ("adc_scan_shared_kernel", stage_ms.get("scan_shared", 0.0) / steps, codes_shared / steps),
-               ("adc_scan_shared8h_kernel", stage_ms.get("scan_shared8", 0.0) / steps, codes_shared8 / steps),
-               ("adc_scan_mfma64_kernel", stage_ms.get("scan_shared64", 0.0) / steps, codes_shared64 / steps)]
-    kname, k_ms, k_codes = max(kernels, key=lambda k: k[1])
-    code_bytes = cfg.m * k_codes
-    lds_b = 2.0 if kname == "adc_scan_shared8h_kernel" else 4.0
-    achieved = code_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
-    traffic_key = (cfg.name, kname)
-    plain = not (args.N or args.kprime or args.k or args.m_refine >= 0 or args.c or args.w or args.batch)
+    traffic = measured_traffic() if (plain and cfg.name == "cfg4") else {}
+    qps = steps * B / elapsed
+    # per-pair scan: algorithmic bytes = m per (query, visited entry); one launch per step
+    pp_ms = st0.get("scan", 0.0) / steps
+    pp_bytes = cfg.m * acc0["codes_scanned"] / steps
+    pp_gbs = pp_bytes / pp_ms / 1e6 if pp_ms > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": f"adc_scan_kernel<{cfg.m}>", "list_sharing_mode": 0,
+                "achieved": pp_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pp_gbs / HBM_PEAK_GBS,
+                "traffic": pp_bytes * traffic["adc_scan_kernel_mode0"] if "adc_scan_kernel_mode0" in traffic else None,
+                "algorithmic_bytes_per_launch": pp_bytes, "avg_launch_ms": pp_ms, "launches_timed": steps,
+                "timing": "HIP events on the kernel's stream around each launch of the second timed loop"}
     out = {
-        "metric": "queries/s", "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "metric": "queries/s", "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if args.sharing < 2 else "f32 recorded estimates and distances; the shared-list scans pre-filter in f16",
+        "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N} d={cfg.d} c={cfg.c} m={cfg.m} m'={cfg.m_refine} "
                                f"w={cfg.w} k'={cfg.kprime} k={cfg.k}, {B} queries per step",
                    "generator": f"uint8 Gaussian mixture G={cfg.G} zipf={cfg.zipf} seed={sd.BASE_SEED}",
                    "list_sharing_mode": args.sharing},
-        "adc_codes_per_s": codes / elapsed,
-        "codes_scanned_per_step": codes / steps,
-        "codes_streamed_per_step": codes_streamed / steps,
-        "codes_scanned_shared_per_step": codes_shared / steps,
-        "codes_scanned_shared2_per_step": codes_shared2 / steps,
-        "codes_scanned_shared8_per_step": codes_shared8 / steps,
-        "codes_scanned_shared64_per_step": codes_shared64 / steps,
-        "stage_ms_per_step": {name: ms / args.steps for name, ms in stage_ms.items()},
-        "dense_fallbacks_total": dense_total,
-        "bound_retries_total": retries_total,
+        "adc_codes_per_s": acc["codes_scanned"] / elapsed,
+        "value_f32_per_pair": steps * B / el0, "ms_per_step_f32_per_pair": 1e3 * el0 / steps,
+        "adc_codes_per_s_f32_per_pair": acc0["codes_scanned"] / el0, "dtype_f32_per_pair": "f32",
+        "per_pair_ids_identical_to_default": same_bits,
+        "codes_scanned_per_step": acc["codes_scanned"] / steps,
+        "codes_streamed_per_step": acc["codes_streamed"] / steps,
+        "codes_scanned_shared_per_step": acc["codes_scanned_shared"] / steps,
+        "codes_scanned_shared2_per_step": acc["codes_scanned_shared2"] / steps,
+        "codes_scanned_shared8_per_step": acc["codes_scanned_shared8"] / steps,
+        "codes_scanned_shared64_per_step": acc["codes_scanned_shared64"] / steps,
+        "stage_ms_per_step": {name: ms / steps for name, ms in stage_ms.items()},
+        "dense_fallbacks_total": acc["dense_fallbacks"], "bound_retries_total": acc["bound_retries"],
+        "batch_reruns_total": acc["batch_reruns"],
         "recall": recall, "recall_queries": n_gt,
         "build_seconds": build_t,
-        "roofline": {"bound": "hbm", "kernel": kname, "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (code_bytes * MEASURED_TRAFFIC_RATIO[traffic_key]
-                                 if traffic_key in MEASURED_TRAFFIC_RATIO and plain else None),
-                     "algorithmic_bytes_per_launch": code_bytes,
-                     "avg_launch_ms": k_ms,
-                     # every estimate is m random LDS reads of 4 bytes (2 with fp16 tables): the scan's other limiter
-                     "lds": {"achieved": lds_b * code_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0,
-                             "peak": LDS_PEAK_GBS, "unit": "GB/s",
-                             "frac": (lds_b * code_bytes / (k_ms * 1e-3) / 1e9 / LDS_PEAK_GBS) if k_ms > 0 else 0.0}},
+        "roofline": roofline,
+        **derived_rates(cfg, B, {n: ms / steps for n, ms in stage_ms.items()}, acc["codes_scanned"] / steps),
     }
+    # the dominant kernel of the default setting: bound by LDS reads (16 bytes of fp16 table entries per estimate in
+    # the units of eight, 4 bytes per fp32 entry elsewhere), not by HBM, because one code read serves several queries
+    kernels = [("adc_scan_shared8h_kernel", "scan_shared8", "codes_scanned_shared8", 2.0),
+               ("adc_scan_shared_kernel<4>", "scan_shared", "codes_scanned_shared", 4.0),
+               ("adc_scan_mfma64_kernel", "scan_shared64", "codes_scanned_shared64", 0.0)]
     if args.sharing != 0:
-        # The same workload with every (query, list) pair scanned on its own (no reuse of a code read between
-        # queries): the HBM-bound form of the scan, three steps outside the timed region.
-        ix.set_list_sharing(0)
-        ix.set_profiling(True)
-        ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
-        pp_ms, pp_codes, pp_wall = 0.0, 0, 0.0
-        for s in range(3):
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            ix.search(batches[s % n_batches], cfg.w, cfg.kprime, cfg.k)
-            torch.cuda.synchronize()
-            pp_wall += time.perf_counter() - t0
-            pp_ms += ix.stage_times()["scan"]
-            pp_codes += ix.search_stats()["codes_scanned"]
-        ix.set_profiling(False)
-        ix.set_list_sharing(args.sharing)
-        pp_bytes = cfg.m * pp_codes / 3.0
-        pp_gbs = pp_bytes / (pp_ms / 3.0 * 1e-3) / 1e9 if pp_ms > 0 else 0.0
-        key = (cfg.name, "adc_scan_kernel")
-        out["roofline_per_pair"] = {"bound": "hbm", "kernel": "adc_scan_kernel", "achieved": pp_gbs, "peak": HBM_PEAK_GBS,
-                                    "unit": "GB/s", "frac": pp_gbs / HBM_PEAK_GBS,
-                                    "traffic": (pp_bytes * MEASURED_TRAFFIC_RATIO[key]
-                                                if key in MEASURED_TRAFFIC_RATIO and plain else None),
-                                    "algorithmic_bytes_per_launch": pp_bytes, "avg_launch_ms": pp_ms / 3.0,
-                                    "ms_per_step": 1e3 * pp_wall / 3.0, "list_sharing_mode": 0}
+        kname, stage, key, lds_b = max(kernels, key=lambda t: stage_ms.get(t[1], 0.0))
+        k_ms = stage_ms.get(stage, 0.0) / steps
+        k_est = acc[key] / steps
+        if k_ms > 0 and lds_b > 0:
+            lds_gbs = lds_b * cfg.m * k_est / k_ms / 1e6
+            tkey = {"adc_scan_shared8h_kernel": "adc_scan_shared8h_kernel"}.get(kname)
+            hbm = cfg.m * k_est * traffic[tkey] if tkey in traffic else None
+            out["roofline_shared"] = {
+                "bound": "lds", "kernel": kname, "achieved": lds_gbs, "peak": LDS_PEAK_GBS, "unit": "GB/s",
+                "frac": lds_gbs / LDS_PEAK_GBS, "lds_bytes_per_estimate": lds_b * cfg.m,
+                "estimates_per_launch": k_est, "avg_launch_ms": k_ms,
+                "peak_derivation": "256 CUs x 128 B/clk x 2.4 GHz; see profiles/lds_gather_microbenchmark.txt",
+                "traffic": hbm, "hbm_frac_of_traffic": (hbm / k_ms / 1e6 / HBM_PEAK_GBS) if hbm else None,
+                "note": "launches of the default setting overlap on side streams, so this duration is an upper bound"}
     if cfg.n_query > B and not args.batch and not args.no_whole_set:
         # The workload's whole query set in one call (outside the timed region): more queries share every list read.
-        ix.set_tuning(batch=min(cfg.n_query, 65535))
+        ix.set_tuning(batch=min(cfg.n_query, 65535), scan_groups=args.scan_groups)
         ix.search(xq, cfg.w, cfg.kprime, cfg.k)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -424,9 +563,15 @@ def main():
         out["whole_query_set_per_call"] = {"queries_per_call": cfg.n_query, "ms_per_call": 1e3 * el,
                                            "queries_per_s": cfg.n_query / el,
                                            "first_batch_ids_identical": bool((a_ids[:B].cpu().numpy() == g_ids).all())}
-        ix.set_tuning(batch=min(B, 65535))
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(ix, cfg, queries_u8, g_ids)
+        ix.set_tuning(batch=min(B, 65535), scan_groups=args.scan_groups)
+    if per_config:
+        out["per_config"] = per_config
+    if oracle_pool is not None:
+        try:
+            out["cpu_baseline"] = cpu_baseline(oracle_pool[0], oracle_pool[1], ix, cfg, queries_u8, g_ids)
+        finally:
+            oracle_pool[0].terminate()
+            oracle_pool[0].join()
     ix.close()
     print(json.dumps(out))
 

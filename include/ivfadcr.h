@@ -76,7 +76,9 @@ int64_t ivfr_ntotal(const ivfr_index* index);   /* vectors added so far (negativ
 /* The finished index as flat host arrays: list l holds entries list_offsets[l] ..
  * list_offsets[l+1]-1.  list_offsets int64 [c+1]; ids int32 [N]; codes uint8 [N, m]; rcodes
  * uint8 [N, m'] (may be NULL when m' = 0).  ivfr_import installs such arrays (codebooks must
- * be set first) and leaves the index finalized. */
+ * be set first) and leaves the index finalized.  Imported ids must be >= 0 (checked) and
+ * distinct (not checked: ties between equal distances are broken by id, and the selections rely
+ * on every (distance, id) key being unique). */
 int ivfr_export(const ivfr_index* index, int64_t* list_offsets, int32_t* ids, uint8_t* codes, uint8_t* rcodes);
 int ivfr_import(ivfr_index* index, int64_t N, const int64_t* list_offsets, const int32_t* ids,
                 const uint8_t* codes, const uint8_t* rcodes);
@@ -85,11 +87,19 @@ int ivfr_import(ivfr_index* index, int64_t N, const int64_t* list_offsets, const
  * queries: fp32 [nq, d], device.  1 <= w <= c, 1 <= k <= kprime.
  * ids_out int32 [nq, k], dist_out fp32 [nq, k], device: per query ascending by (refined squared
  * distance, id); when fewer than k entries were scanned the tail is id -1, distance +inf.
- * stream: a hipStream_t (NULL = default stream).  Work is enqueued on it; the call also waits
- * for it to finish (it reads back a small status word), so outputs are valid on return.
+ * stream: a hipStream_t (NULL = default stream).  The whole query stage is enqueued on it without
+ * a host round trip (unit counts, launch shapes and buffer checks are read by the kernels from
+ * device memory); the call then waits for the stream once, reads the status words the kernels left
+ * (failed buffer checks, queries that are not finite, work counters) and returns, so outputs are
+ * valid on return.  Further waits happen only on the rare redo paths: a candidate pool that turned
+ * out too small (the pool grows and the batch runs again; it keeps its size for later calls), or
+ * queries whose sampled bound failed its check (each is rescanned at most eight times with a
+ * tightened bound and at most once without any filter: bound_retries / dense_fallbacks of
+ * ivfr_search_stats).
  * Query components must be finite: a query with a NaN or infinite component (or a squared norm
  * beyond fp32) makes the call fail with IVFR_ERR_INVALID_ARG, naming the query.  The workspace of
- * a call grows with nq (about w * m KB of tables per query) and is kept by the index for later calls.
+ * a call grows with nq (about w * m KB of tables per query) and is kept by the index for later calls;
+ * IVFR_ERR_OOM is returned before anything is allocated when it cannot fit.
  * Errors: IVFR_ERR_INVALID_ARG for null pointers, parameters outside the ranges above or queries
  * that are not finite, IVFR_ERR_STATE before ivfr_finalize / ivfr_import, IVFR_ERR_OOM /
  * IVFR_ERR_HIP from the runtime; outputs are then undefined. */
@@ -156,6 +166,25 @@ int ivfr_set_list_sharing(ivfr_index* index, int32_t mode);
 int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int32_t min_cap, int32_t batch,
                     int32_t scan_groups);
 
+/* Device memory.  ivfr_memory_required is pure host arithmetic (no GPU call): the bytes an index of N
+ * vectors with these parameters holds on the device (index_bytes: codes, refinement codes, ids, list
+ * directory, codebooks) and the workspace a search call with nq queries, w and kprime adds
+ * (search_bytes: per-batch arrays plus the candidate pool expected for lists of equal length; a
+ * skewed index can want more).  Either output may be NULL.  With available_bytes > 0 it returns
+ * IVFR_ERR_OOM when the sum exceeds it.  ivfr_set_memory_limit caps what this index may hold in
+ * total (0 = no cap beyond the device's free memory): ivfr_finalize, ivfr_import and ivfr_search
+ * check the cap and the free device memory before allocating and fail with IVFR_ERR_OOM, leaving the
+ * index as it was. */
+int ivfr_memory_required(const ivfr_params* params, int64_t N, int64_t nq, int32_t w, int32_t kprime,
+                         int64_t available_bytes, int64_t* index_bytes, int64_t* search_bytes);
+int ivfr_set_memory_limit(ivfr_index* index, int64_t bytes);
+/* What the index holds on the device now (any pointer may be NULL): the finished inverted file, the
+ * search workspace (per-batch arrays, plus the buffer of the unfiltered redo when one was needed), the
+ * candidate pool; and how many internal batches of the most recent search call ran twice (the
+ * candidate pool had to grow, or a batch of a multi-batch call was brought back for a redo). */
+int ivfr_workspace_info(const ivfr_index* index, int64_t* index_bytes, int64_t* workspace_bytes,
+                        int64_t* pool_bytes, int64_t* batch_reruns);
+
 /* Per-stage GPU time of the most recent search call, in milliseconds, measured with HIP events
  * on the streams the kernels run on.  ivfr_set_profiling(index, level): 0 = off (default), 1 = only the
  * list-scan launches are timed (the IVFR_STAGE_SCAN* stages; about 0.03 ms of host time per batch), 2 = every
@@ -174,7 +203,9 @@ int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int3
 #define IVFR_STAGE_SCAN_SHARED2 9 /* ADC list scan, two queries per pass over a shared list   */
 #define IVFR_STAGE_SCAN_SHARED8 10 /* ADC list scan, eight queries per pass, fp16 tables      */
 #define IVFR_STAGE_SCAN_SHARED64 11 /* ADC list scan, 64 queries per pass on the matrix cores */
-#define IVFR_N_STAGES        12
+#define IVFR_STAGE_HOST_ENQUEUE 12 /* host time spent enqueuing the call's work (always measured) */
+#define IVFR_STAGE_HOST_WAIT 13  /* host time spent waiting for the stream (always measured)  */
+#define IVFR_N_STAGES        14
 int ivfr_set_profiling(ivfr_index* index, int32_t enable);
 int ivfr_stage_times(const ivfr_index* index, double* ms, int32_t* scan_launches);
 

@@ -4,7 +4,7 @@ The binding is loaded on first use, so that `paper_1102_3828_amd.build` can be i
 before the library exists.  Using the package without a built library raises ImportError."""
 import importlib
 
-_BINDING_NAMES = ("Index", "IvfrError", "EXPORTED", "LIB_PATH", "lib")
+_BINDING_NAMES = ("Index", "IvfrError", "EXPORTED", "LIB_PATH", "lib", "memory_required")
 
 
 def __getattr__(name):

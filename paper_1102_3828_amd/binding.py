@@ -53,6 +53,10 @@ def _load():
         "ivfr_set_list_sharing": (ctypes.c_int, [vp, i32]),
         "ivfr_set_tuning": (ctypes.c_int, [vp, i32, i32, i32, i32, i32]),
         "ivfr_set_profiling": (ctypes.c_int, [vp, i32]),
+        "ivfr_memory_required": (ctypes.c_int, [ctypes.POINTER(Params), i64, i64, i32, i32, i64,
+                                                ctypes.POINTER(i64), ctypes.POINTER(i64)]),
+        "ivfr_set_memory_limit": (ctypes.c_int, [vp, i64]),
+        "ivfr_workspace_info": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 4),
         "ivfr_stage_times": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]),
         "ivfr_last_error": (ctypes.c_char_p, []),
     }
@@ -65,7 +69,8 @@ def _load():
 lib = _load()
 EXPORTED = ["ivfr_create", "ivfr_destroy", "ivfr_train", "ivfr_set_codebooks", "ivfr_get_codebooks", "ivfr_add",
             "ivfr_finalize", "ivfr_ntotal", "ivfr_export", "ivfr_import", "ivfr_search", "ivfr_search_trace",
-            "ivfr_search_stats", "ivfr_set_list_sharing", "ivfr_set_tuning", "ivfr_set_profiling", "ivfr_stage_times", "ivfr_last_error"]
+            "ivfr_search_stats", "ivfr_set_list_sharing", "ivfr_set_tuning", "ivfr_set_profiling", "ivfr_stage_times", "ivfr_last_error",
+            "ivfr_memory_required", "ivfr_set_memory_limit", "ivfr_workspace_info"]
 
 
 def _check(rc):
@@ -87,6 +92,14 @@ def _ptr(x):
         return ctypes.c_void_p(x.ctypes.data)
     assert x.is_contiguous()
     return ctypes.c_void_p(x.data_ptr())
+
+
+def memory_required(d, c, m, m_refine, N, nq=0, w=1, kprime=1, available=0):
+    """(index_bytes, search_bytes) by ivfr_memory_required; raises IvfrError(ERR_OOM) beyond `available`."""
+    p = Params(d, c, m, m_refine, 0)
+    ib, sb = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib.ivfr_memory_required(ctypes.byref(p), N, nq, w, kprime, available, ctypes.byref(ib), ctypes.byref(sb)))
+    return ib.value, sb.value
 
 
 class Index:
@@ -208,12 +221,21 @@ class Index:
     def set_tuning(self, full_mult=0, cap_mult=0, min_cap=0, batch=0, scan_groups=0):
         _check(lib.ivfr_set_tuning(self._h, full_mult, cap_mult, min_cap, batch, scan_groups))
 
+    def set_memory_limit(self, nbytes):
+        """Cap on the device bytes this index may hold in total (0 = none)."""
+        _check(lib.ivfr_set_memory_limit(self._h, int(nbytes)))
+
+    def workspace_info(self):
+        v = [ctypes.c_int64() for _ in range(4)]
+        _check(lib.ivfr_workspace_info(self._h, *[ctypes.byref(x) for x in v]))
+        return dict(zip(("index_bytes", "workspace_bytes", "pool_bytes", "batch_reruns"), [x.value for x in v]))
+
     def set_profiling(self, level=2):
         """0 / False = off, 1 = time the list-scan launches only, 2 / True = time every stage."""
         level = 2 if level is True else (0 if level is False else int(level))
         _check(lib.ivfr_set_profiling(self._h, level))
 
-    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared", "scan_shared2", "scan_shared8", "scan_shared64")
+    STAGES = ("coarse", "probe", "lut", "sample", "scan", "shortlist", "rerank", "final", "scan_shared", "scan_shared2", "scan_shared8", "scan_shared64", "host_enqueue", "host_wait")
 
     def stage_times(self):
         """Per-stage milliseconds of the last search (after set_profiling) and scan launch count."""

@@ -89,22 +89,29 @@ extern "C" int ivfr_create(const ivfr_params* params, ivfr_index** out) {
     if (r == IVFR_OK) {
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, p.device) == hipSuccess) ix->n_cu = prop.multiProcessorCount;
+        // function attributes are per device: set with this index's device current, every time
         r = ivfr_select_init();
+        if (r == IVFR_OK) r = ivfr_scan_init();
+        if (r == IVFR_OK) r = ivfr_rerank_init();
     }
     if (r == IVFR_OK) {
-        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ix->h_status), 64 * sizeof(int), hipHostMallocDefault);
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ix->h_slots), IVFR_STATUS_SLOTS * sizeof(DevStatus),
+                                     hipHostMallocDefault);
+        if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ix->h_redo), 8 * sizeof(uint32_t), hipHostMallocDefault);
         if (e != hipSuccess) { ivfr_set_error("pinned host allocation failed"); r = IVFR_ERR_OOM; }
+        else memset(ix->h_slots, 0, IVFR_STATUS_SLOTS * sizeof(DevStatus));
     }
     for (int i = 0; i < 4 && r == IVFR_OK; ++i) {
-        if (hipStreamCreateWithFlags(&ix->side[i], hipStreamNonBlocking) != hipSuccess ||
-            hipEventCreateWithFlags(&ix->ev_join[i], hipEventDisableTiming) != hipSuccess) {
-            ivfr_set_error("stream / event creation failed");
+        if (hipStreamCreateWithFlags(&ix->side[i], hipStreamNonBlocking) != hipSuccess) {
+            ivfr_set_error("stream creation failed");
             r = IVFR_ERR_HIP;
         }
     }
-    if (r == IVFR_OK && hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming) != hipSuccess) {
-        ivfr_set_error("event creation failed");
-        r = IVFR_ERR_HIP;
+    for (int sl = 0; sl < IVFR_STATUS_SLOTS && r == IVFR_OK; ++sl) {
+        bool ok = hipEventCreateWithFlags(&ix->ev_fork[sl], hipEventDisableTiming) == hipSuccess;
+        for (int i = 0; i < 4 && ok; ++i)
+            ok = hipEventCreateWithFlags(&ix->ev_join[sl][i], hipEventDisableTiming) == hipSuccess;
+        if (!ok) { ivfr_set_error("event creation failed"); r = IVFR_ERR_HIP; }
     }
     if (r != IVFR_OK) { ivfr_destroy(ix); return r; }
     *out = ix;
@@ -127,12 +134,15 @@ extern "C" int ivfr_destroy(ivfr_index* ix) {
     dev_free(ix->list_fill); dev_free(ix->list_start); dev_free(ix->list_len); dev_free(ix->chunk_list);
     dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
     ix->search_ws.release(); ix->cand_ws.release(); ix->encode_ws.release(); ix->dense_ws.release();
-    if (ix->h_status) (void)hipHostFree(ix->h_status);
-    for (int i = 0; i < 4; ++i) {
+    if (ix->h_slots) (void)hipHostFree(ix->h_slots);
+    if (ix->h_redo) (void)hipHostFree(ix->h_redo);
+    for (int i = 0; i < 4; ++i)
         if (ix->side[i]) (void)hipStreamDestroy(ix->side[i]);
-        if (ix->ev_join[i]) (void)hipEventDestroy(ix->ev_join[i]);
+    for (int sl = 0; sl < IVFR_STATUS_SLOTS; ++sl) {
+        if (ix->ev_fork[sl]) (void)hipEventDestroy(ix->ev_fork[sl]);
+        for (int i = 0; i < 4; ++i)
+            if (ix->ev_join[sl][i]) (void)hipEventDestroy(ix->ev_join[sl][i]);
     }
-    if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
     for (hipEvent_t e : ix->prof_events) (void)hipEventDestroy(e);
     ix->prof_events.clear();
     delete ix;
@@ -388,8 +398,45 @@ extern "C" int ivfr_add(ivfr_index* ix, const uint8_t* x, int64_t n, int64_t id_
     return IVFR_OK;
 }
 
-// logical offsets -> padded layout on the device
+int ivfr_check_room(const ivfr_index* ix, size_t more) {
+    if (more == 0) return IVFR_OK;
+    if (ix->mem_limit > 0) {
+        const size_t held = ix->index_bytes + ix->search_ws.bytes + ix->cand_ws.bytes + ix->dense_ws.bytes + ix->encode_ws.bytes;
+        if (held + more > (size_t)ix->mem_limit) {
+            ivfr_set_error("%zu more device bytes on top of the %zu held exceed the index's memory limit of %lld",
+                           more, held, (long long)ix->mem_limit);
+            return IVFR_ERR_OOM;
+        }
+    }
+    size_t free_b = 0, total_b = 0;
+    if (hipMemGetInfo(&free_b, &total_b) == hipSuccess) {
+        if (more > free_b) {
+            ivfr_set_error("%zu more device bytes needed, %zu free of %zu", more, free_b, total_b);
+            return IVFR_ERR_OOM;
+        }
+    } else {
+        (void)hipGetLastError();
+    }
+    return IVFR_OK;
+}
+
+static void free_layout(ivfr_index* ix) {
+    dev_free(ix->list_start); dev_free(ix->list_len); dev_free(ix->chunk_list);
+    dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
+    ix->index_bytes = 0;
+}
+
+static int install_layout_inner(ivfr_index* ix, const std::vector<int64_t>& offsets);
+
+// logical offsets -> padded layout on the device; a failure leaves nothing allocated, so the call can be repeated
 static int install_layout(ivfr_index* ix, const std::vector<int64_t>& offsets) {
+    free_layout(ix);
+    const int r = install_layout_inner(ix, offsets);
+    if (r != IVFR_OK) free_layout(ix);
+    return r;
+}
+
+static int install_layout_inner(ivfr_index* ix, const std::vector<int64_t>& offsets) {
     const int c = ix->p.c;
     ix->h_offsets = offsets;
     ix->h_start.assign((size_t)c + 1, 0);
@@ -405,6 +452,14 @@ static int install_layout(ivfr_index* ix, const std::vector<int64_t>& offsets) {
     ix->h_start[(size_t)c] = (uint32_t)pos;
     ix->n_slots = pos + IVFR_TAIL_PAD;
     ix->N = offsets[(size_t)c];
+    {
+        // a query lands in a list with a probability proportional to its size: expected visited-list length
+        double s2 = 0.0;
+        for (int l = 0; l < c; ++l) s2 += (double)len[(size_t)l] * (double)len[(size_t)l];
+        ix->wmean_len = ix->N > 0 ? s2 / (double)ix->N : 0.0;
+    }
+    IVFR_TRY(ivfr_check_room(ix, ivfr_index_bytes(ix->p, ix->n_slots)));
+    ix->index_bytes = ivfr_index_bytes(ix->p, ix->n_slots);
     IVFR_TRY(dev_alloc(&ix->list_start, (size_t)c + 1));
     IVFR_TRY(dev_alloc(&ix->list_len, (size_t)c));
     IVFR_HIP(hipMemcpy(ix->list_start, ix->h_start.data(), ((size_t)c + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
@@ -486,6 +541,8 @@ extern "C" int ivfr_import(ivfr_index* ix, int64_t N, const int64_t* list_offset
     IVFR_REQUIRE(list_offsets[0] == 0 && list_offsets[c] == N, "list_offsets must run from 0 to N");
     for (int l = 0; l < c; ++l)
         IVFR_REQUIRE(list_offsets[l + 1] >= list_offsets[l], "list_offsets must be non-decreasing (list %d)", l);
+    for (int64_t i = 0; i < N; ++i)
+        IVFR_REQUIRE(ids[i] >= 0, "ids must be >= 0 (entry %lld has id %d)", (long long)i, (int)ids[i]);
     IVFR_TRY(use_device(ix));
     std::vector<int64_t> offsets(list_offsets, list_offsets + c + 1);
     IVFR_TRY(install_layout(ix, offsets));
@@ -514,6 +571,23 @@ extern "C" int ivfr_set_tuning(ivfr_index* ix, int32_t full_mult, int32_t cap_mu
     if (min_cap) ix->min_cap = min_cap;
     if (batch) ix->batch = batch;
     ix->scan_groups = scan_groups;
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_set_memory_limit(ivfr_index* ix, int64_t bytes) {
+    IVFR_REQUIRE(ix, "ivfr_set_memory_limit: null index");
+    IVFR_REQUIRE(bytes >= 0, "memory limit %lld must be >= 0", (long long)bytes);
+    ix->mem_limit = bytes;
+    return IVFR_OK;
+}
+
+extern "C" int ivfr_workspace_info(const ivfr_index* ix, int64_t* index_bytes, int64_t* workspace_bytes,
+                                   int64_t* pool_bytes, int64_t* batch_reruns) {
+    IVFR_REQUIRE(ix, "ivfr_workspace_info: null index");
+    if (index_bytes) *index_bytes = (int64_t)ix->index_bytes;
+    if (workspace_bytes) *workspace_bytes = (int64_t)(ix->search_ws.bytes + ix->dense_ws.bytes);
+    if (pool_bytes) *pool_bytes = (int64_t)ix->cand_ws.bytes;
+    if (batch_reruns) *batch_reruns = ix->st_reruns;
     return IVFR_OK;
 }
 

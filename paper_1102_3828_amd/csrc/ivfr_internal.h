@@ -68,6 +68,20 @@ struct DevBuf {
     template <class T> T* as() const { return reinterpret_cast<T*>(p); }
 };
 
+// Status words of one internal batch of a search call.  They live in device memory, are cleared by the batch's
+// first kernel, filled by the plan / scan / select kernels, and copied to a pinned host slot by one asynchronous
+// copy at the end of the batch: the host reads them once, after the stream has drained.
+struct DevStatus {
+    unsigned long long totals[2];   // [0] sum over queries of the visited lists' lengths, [1] candidate-pool records the plan wants
+    unsigned long long work[8];     // [0] list entries streamed; [1..5] estimates by units of eight, four, two, single pairs, units of 64
+    int32_t over_total;             // queries whose filter failed its check (too many or too few survivors)
+    uint32_t bad_query;             // row + 1 of a query with a component that is not finite (0: none)
+    uint32_t pool_short;            // 1: the candidate pool is smaller than totals[1]; the batch did no list work
+    uint32_t n_sample_chunks;       // chunks of the sample pass
+    uint32_t counts[8];             // units of eight, four, two, single pairs, units of 64
+};
+#define IVFR_STATUS_SLOTS 16        // batches of one call in flight between two host waits
+
 // One staged (encoded, not yet list-sorted) batch of database vectors.
 struct StagedChunk {
     int64_t n = 0;
@@ -119,18 +133,36 @@ struct ivfr_index {
 
     // scratch
     DevBuf search_ws, cand_ws, encode_ws, dense_ws;
-    int* h_status = nullptr;         // pinned host word(s) for status read-back
+    DevStatus* h_slots = nullptr;    // pinned host copies of the batches' status words [IVFR_STATUS_SLOTS]
+    uint32_t* h_redo = nullptr;      // pinned scratch of the (rare) per-query redo path [8]
     hipStream_t side[4] = {nullptr, nullptr, nullptr, nullptr};   // the smaller scan launches overlap the large one
-    hipEvent_t ev_fork = nullptr, ev_join[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ev_fork[IVFR_STATUS_SLOTS] = {nullptr};            // one set of fork / join events per batch in flight
+    hipEvent_t ev_join[IVFR_STATUS_SLOTS][4] = {{nullptr}};
 
     // stats of the last search
+    int64_t st_reruns = 0;           // batches of the last search that ran twice (pool grown, or brought back for a redo)
     int64_t st_codes = 0, st_pairs = 0, st_dense = 0, st_streamed = 0, st_shared_codes = 0, st_shared2_codes = 0, st_shared8_codes = 0, st_retries = 0, st_shared64_codes = 0;
     int profiling = 0;   // 0 off, 1 list-scan launches only, 2 every stage
     std::vector<hipEvent_t> prof_events;   // timing events, created once and reused by every search call
     double prof_ms[IVFR_N_STAGES] = {0};
     int prof_scan_launches = 0;
     int n_cu = 256;
+    // share of a batch's estimates that each scan launch computed in the previous call (units of eight, four, two,
+    // single pairs, units of 64), relative to pairs x mean visited-list length: sizes the next call's launches
+    double work_ratio[5] = {1.0, 1.0, 1.0, 1.0, 1.0};
+    double wmean_len = 0.0;          // expected length of a visited list: sum of len^2 / N (lists are hit in proportion to their size)
+    int64_t mem_limit = 0;           // > 0: device bytes the index may use in total (capacity checks refuse beyond it)
+    size_t index_bytes = 0;          // device bytes held by the finished inverted file
 };
+
+// Device bytes of the finished inverted file with n_slots padded entry slots.
+inline size_t ivfr_index_bytes(const ivfr_params& p, uint64_t n_slots) {
+    return (size_t)n_slots * ((size_t)p.m + (size_t)p.m_refine + sizeof(int32_t)) + ((size_t)p.c * 2 + 1) * sizeof(uint32_t) +
+           ((size_t)1 << 18) * sizeof(uint32_t);
+}
+// IVFR_ERR_OOM (before anything is allocated) when `more` further device bytes do not fit: beyond the index's
+// memory limit, when one is set, or beyond what the device reports as free.
+int ivfr_check_room(const ivfr_index* ix, size_t more);
 
 // ---- kernels' host launchers (each enqueues on `st` and returns a status) -------------------
 
@@ -186,6 +218,58 @@ int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, in
                            bool values_only = false);
 int ivfr_select_init();   // one-time function attributes
 
+// Per-query part of the search plan, shared by the plan kernel and by the host's estimate of the candidate
+// pool.  A query that visits `total` entries keeps every estimate when total <= full_limit (or when its sample
+// would be half of them or more); otherwise one entry in `stride` is sampled (the same leading fraction of
+// every visited list) to bound the k'-th smallest estimate.  Scoring a sampled entry and handling a surviving
+// one cost about the same order, and the survivors fall as k' (1 + 5/sqrt(mu) + 6/mu) with mu = k' n_s / total,
+// so the cheapest sample grows as the cube root of k' * total (the factor 16 is measured).  The stride is at
+// most stride_k (= k' / mu_min) and at least what keeps the sample below max_sample.
+struct QueryPlan {
+    bool fully;
+    uint32_t stride;
+};
+__host__ __device__ inline QueryPlan ivfr_plan_query(unsigned long long total, uint32_t full_limit, uint32_t stride_k,
+                                                     uint32_t max_sample, int kprime) {
+    QueryPlan r;
+    r.fully = total <= full_limit;
+    unsigned long long stride64 = 1;
+    {
+        const double ns = 16.0 * cbrt((double)kprime * (double)total);
+        const double st_d = (double)total / (ns > 1.0 ? ns : 1.0);
+        stride64 = st_d > 4.0e9 ? 4000000000ull : (unsigned long long)st_d;
+    }
+    if (stride64 > (stride_k < 1 ? 1ull : stride_k)) stride64 = stride_k < 1 ? 1ull : stride_k;
+    const unsigned long long widen = (total + max_sample - 1) / max_sample;
+    if (widen > stride64) stride64 = widen;
+    if (stride64 < 1) stride64 = 1;
+    if (stride64 <= 2) r.fully = true;
+    r.stride = (uint32_t)(stride64 > 0xFFFFFFFFull ? 0xFFFFFFFFull : stride64);
+    return r;
+}
+// Records of the query's candidate buffer: everything (no filter), or the largest of the sample, min_cap and the
+// survivors expected from the bound (rank r of the sample, one sampled entry standing for `stride`) plus six
+// deviations.  exact_only: so large a share of the estimates will pass the bound that the half-precision units
+// do not pay off.
+__host__ __device__ inline unsigned long long ivfr_plan_capacity(unsigned long long total, unsigned long long sampled,
+                                                                 QueryPlan qp, uint32_t min_cap, int kprime,
+                                                                 float half_frac, bool* exact_only) {
+    unsigned long long capv = total;
+    *exact_only = true;
+    if (!qp.fully) {
+        const double mu = (double)kprime / (double)qp.stride;
+        const double rank = mu + 5.0 * sqrt(mu) + 6.0;
+        const double expect = rank * (double)qp.stride;
+        capv = sampled > min_cap ? sampled : (unsigned long long)min_cap;
+        // the number of visited entries below the rank-th sampled one scatters by ~1/sqrt(rank): six deviations
+        const double roomy = expect * (1.0 + 6.0 / sqrt(rank));
+        if ((double)capv < roomy) capv = (unsigned long long)roomy;
+        *exact_only = expect > (double)half_frac * (double)total;
+    }
+    if (capv > 0xFFFFFFF0ull) capv = 0xFFFFFFF0ull;
+    return capv;
+}
+
 // Search plan, look-up tables, sample and list scan (scan.hip)
 struct PlanBuffers {
     uint32_t* pair_start;  // [P] first padded entry of the pair's list
@@ -204,6 +288,8 @@ struct PlanBuffers {
     uint8_t* fully;              // [nq] 1 = few enough entries to keep them all (no sample, tau = +inf)
     uint8_t* exact_only;         // [nq] 1 = too large a share of the estimates will pass the bound for fp16 units
     unsigned long long* totals;  // [2]: [0] = sum of sq, [1] = records in the candidate pool
+    DevStatus* status;           // the batch's status words (totals points into it)
+    unsigned long long pool_cap; // records the candidate pool holds; a plan that wants more voids the batch
 };
 // pb.totals must be zero on entry.
 int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, uint32_t full_limit,
@@ -211,19 +297,33 @@ int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, 
                      const PlanBuffers& pb, hipStream_t st);
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
                     float* lut, float* lut_scale, hipStream_t st);
+// Geometry of a list-scan launch.  The number of units (pairs, or units of several pairs) is either known on
+// the host or read by the kernel from a device word; the kernel spreads the launch's blocks over
+// min(groups, max(g_min, blocks / bpg)) workgroups (a multiple of eight: one contiguous share of the block
+// stream per XCD) and the remaining workgroups exit at once, so the host can launch from an estimate.
+struct ScanShape {
+    int n_host = 0;                  // units when n_dev is null
+    const uint32_t* n_dev = nullptr; // device word with the number of units
+    int groups = 8;                  // workgroups launched
+    uint32_t bpg = 0;                // blocks of IVFR_BLOCK entries wanted per workgroup; 0 = use every launched workgroup
+    uint32_t g_min = 8;
+};
 // unit_pairs == nullptr: unit u of the launch is pair u; otherwise pair unit_pairs[u].  An entry is kept
 // when its estimate is <= tau[q]; with tau_id, when its key (estimate, id) is <= (tau[q], tau_id[q]).
+// blkpre may be a slice of a longer prefix array: the launch's blocks are blkpre[0] .. blkpre[units].
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
-                     const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau, uint2* cand,
-                     uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st,
+                     const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape shape, int w, const float* tau,
+                     uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st,
                      const uint32_t* tau_id = nullptr);
 
 // Sample pass: the estimate of entry e < len_s[p] of pair p is written as a bare float at index soff[p] + e of
 // the query's buffer (no counters involved; only the values are needed to bound the k'-th smallest).  One wavefront per chunk of IVFR_SAMPLE_CHUNK entries; items[i] is the
 // pair of chunk i, chunk_pre the pairs' chunk prefix.
+// n_items: device word with the number of chunks; max_items: a host-side upper bound (sizes the grid, whose
+// wavefronts walk over the chunks).
 int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
-                            const uint32_t* chunk_pre, const uint32_t* items, uint32_t n_items, const uint32_t* soff,
-                            int w, uint2* cand, CandLayout lay, hipStream_t st);
+                            const uint32_t* chunk_pre, const uint32_t* items, const uint32_t* n_items, size_t max_items,
+                            const uint32_t* soff, int w, uint2* cand, CandLayout lay, hipStream_t st);
 
 // Shared scan: pairs of one batch grouped by list into units of eight, four, two and single pairs
 struct GroupBuffers {
@@ -252,20 +352,23 @@ int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint
 bool ivfr_shared_scan_supported(const ivfr_index* ix);
 bool ivfr_shared8h_supported(const ivfr_index* ix);
 int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const uint32_t* pair_start,
-                            const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
-                            int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
+                            const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs,
+                            ScanShape shape, int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay,
                             hipStream_t st, const float* lut_scale = nullptr, const uint8_t* exact_only = nullptr);
 int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const float* lut_scale,
                               const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
-                              const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,
-                              uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st);
+                              const uint32_t* unit_pairs, ScanShape shape, int w, const float* tau, uint2* cand,
+                              uint32_t* cand_cnt, CandLayout lay, hipStream_t st);
 // Units of 64 queries on the matrix cores (fp16 decode x query contraction as the filter, exact fp32 sums for
 // what passes).  queries: the batch's [nq][d] floats; probe: the list of every pair.
 bool ivfr_mfma_scan_supported(const ivfr_index* ix);
 int ivfr_launch_scan_mfma64(const ivfr_index* ix, const float* queries, const int32_t* probe, const float* lut,
                             const float* lut_scale, const uint32_t* pair_start, const uint32_t* pair_len,
-                            const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits, int w, const float* tau,
-                            uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st);
+                            const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape shape, int w, const float* tau,
+                            uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st);
+// One-time function attributes (dynamic LDS beyond 48 KB) of every kernel of a translation unit, for the current device.
+int ivfr_scan_init();
+int ivfr_rerank_init();
 
 // Encoding (encode.hip)
 int ivfr_launch_residual(float* X, int64_t n, int d, const float* C, const int32_t* assign, hipStream_t st);

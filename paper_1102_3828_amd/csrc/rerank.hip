@@ -204,6 +204,12 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
     }
 }
 
+int ivfr_rerank_init() {
+    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    return IVFR_OK;
+}
+
 int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, int nq, int kprime,
                        const uint32_t* short_pos, const int32_t* short_n, uint64_t* keys, float* refined_out,
                        int32_t* ids_out, hipStream_t st) {
@@ -212,12 +218,6 @@ int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, i
     const bool vec0 = (ix->dsub % 4 == 0) && (ix->p.m_refine == 0 || ix->dsub_r % 4 == 0) && ((ix->p.d / 8) % 4 == 0);
     const size_t rq_bytes = (size_t)IVFR_KS * ix->p.d * sizeof(float);
     if (vec0 && ix->p.m_refine > 0 && rq_bytes <= 128 * 1024 && (int64_t)nq * kprime >= (int64_t)ix->n_cu * 1024) {
-        static bool attr_done = false;
-        if (!attr_done) {
-            IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-            attr_done = true;
-        }
         const int64_t n_items = (int64_t)nq * ((kprime + 127) / 128);
         const int groups = (int)std::min<int64_t>(n_items, ix->n_cu);
         hipLaunchKernelGGL(rerank_lds_kernel, dim3(groups), dim3(1024), rq_bytes, st, queries, ix->p.d, ix->p.c, ix->p.m,

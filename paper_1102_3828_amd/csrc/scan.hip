@@ -2,6 +2,8 @@
 // visited (query, list) pairs, per-pair look-up tables of Eq. (5), and the ADC list scan.
 #include "ivfr_internal.h"
 
+#include <algorithm>
+
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // ------------------------------------------------------------------------------------------
@@ -41,24 +43,9 @@ __global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restri
     for (int r = lane; r < w; r += 64) total += list_len[probe[(int64_t)q * w + r]];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) total += __shfl_xor(total, off, 64);
-    bool fully = total <= full_limit;
-    // Sample size: scoring a sampled entry and handling a surviving one cost about the same order, and the
-    // survivors fall as k' (1 + 5/sqrt(mu) + 6/mu) with mu = k' n_s / total, so the cheapest sample grows as
-    // the cube root of k' * total (the factor 16 is measured).  Stride = total / n_s, at most k' / mu_min
-    // (stride_k), at least what keeps the sample below max_sample; a sample of half the entries or more is
-    // pointless: such a query keeps everything instead.
-    unsigned long long stride64 = 1;
-    {
-        const double ns = 16.0 * cbrt((double)kprime * (double)total);
-        const double st_d = (double)total / (ns > 1.0 ? ns : 1.0);
-        stride64 = st_d > 4.0e9 ? 4000000000ull : (unsigned long long)st_d;
-    }
-    if (stride64 > (stride_k < 1 ? 1ull : stride_k)) stride64 = stride_k < 1 ? 1ull : stride_k;
-    const unsigned long long widen = (total + max_sample - 1) / max_sample;
-    if (widen > stride64) stride64 = widen;
-    if (stride64 < 1) stride64 = 1;
-    if (stride64 <= 2) fully = true;
-    const uint32_t stride = (uint32_t)(stride64 > 0xFFFFFFFFull ? 0xFFFFFFFFull : stride64);
+    const QueryPlan qp = ivfr_plan_query(total, full_limit, stride_k, max_sample, kprime);
+    const bool fully = qp.fully;
+    const uint32_t stride = qp.stride;
     unsigned long long sampled = 0;
     uint32_t carry = 0, carry_s = 0, carry_e = 0;
     for (int r0 = 0; r0 < w; r0 += 64) {
@@ -95,22 +82,9 @@ __global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restri
     pb.sq[q] = total;
     pb.nsample[q] = (uint32_t)(sampled > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : sampled);
     pb.fully[q] = fully ? 1 : 0;
-    // buffer: everything (no filter), or the largest of the sample, min_cap and the survivors expected
-    // from the bound (rank r of the sample, one sampled entry standing for `stride`) plus six deviations
-    unsigned long long capv = total;
-    bool exact_only = true;   // the half-precision units of eight pay off only when very few estimates pass the bound
-    if (!fully) {
-        const double mu = (double)kprime / (double)stride;
-        const double rank = mu + 5.0 * sqrt(mu) + 6.0;
-        const double expect = rank * (double)stride;
-        capv = sampled > min_cap ? sampled : (unsigned long long)min_cap;
-        // the number of visited entries below the rank-th sampled one scatters by ~1/sqrt(rank): six deviations
-        const double roomy = expect * (1.0 + 6.0 / sqrt(rank));
-        if ((double)capv < roomy) capv = (unsigned long long)roomy;
-        exact_only = expect > (double)half_frac * (double)total;
-    }
+    bool exact_only = true;
+    const unsigned long long capv = ivfr_plan_capacity(total, sampled, qp, min_cap, kprime, half_frac, &exact_only);
     pb.exact_only[q] = exact_only ? 1 : 0;
-    if (capv > 0xFFFFFFF0ull) capv = 0xFFFFFFF0ull;
     pb.capq[q] = (uint32_t)capv;
     atomicAdd(pb.totals, total);
 }
@@ -150,7 +124,16 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(int nq, int w, PlanBuff
         if (tid == 1023) { carry64 = inc64; carry[0] = inc[0]; carry[1] = inc[1]; }
         __syncthreads();
     }
-    if (tid == 0) { pb.totals[1] = carry64; pb.blkpre[nq * w] = carry[0]; pb.blkpre_s[nq * w] = carry[1]; }
+    if (tid == 0) {
+        // A candidate pool smaller than the plan wants voids the batch: no block of any pair is scanned (the host
+        // reads the flag after the call's only wait, grows the pool and runs the batch again).
+        const bool dead = carry64 > pb.pool_cap;
+        pb.totals[1] = carry64;
+        pb.status->pool_short = dead ? 1u : 0u;
+        pb.blkpre[nq * w] = dead ? 0u : carry[0];
+        pb.blkpre_s[nq * w] = dead ? 0u : carry[1];
+        pb.status->n_sample_chunks = dead ? 0u : carry[1];
+    }
 }
 
 // The per-query block offsets are added to the query-relative prefixes of the P pairs, and the pair of
@@ -159,6 +142,11 @@ __global__ __launch_bounds__(256) void plan_expand_kernel(int P, int w, PlanBuff
     const int p = blockIdx.x * 256 + threadIdx.x;
     if (p >= P) return;
     const int q = p / w;
+    if (pb.status->pool_short) {   // void batch: every pair is empty, no query has a sample
+        pb.len[p] = 0; pb.len_s[p] = 0; pb.blkpre[p] = 0; pb.blkpre_s[p] = 0;
+        if (p == q * w) pb.nsample[q] = 0;
+        return;
+    }
     pb.blkpre[p] += pb.qblk[q];
     const uint32_t first = pb.blkpre_s[p] + pb.qblk_s[q];
     pb.blkpre_s[p] = first;
@@ -323,6 +311,27 @@ __device__ __forceinline__ uint32_t xcd_share_index(uint32_t block, uint32_t gro
     return (groups & 7u) ? block : (block & 7u) * (groups >> 3) + (block >> 3);
 }
 
+// The share [b, b_end) of the launch's block stream that this workgroup (or, with `parts` > 1, this one of the
+// workgroup's `parts` wavefronts) takes.  The stream is blkpre[0] .. blkpre[n] (blkpre may be a slice of a longer
+// prefix array, so positions are absolute).  With bpg > 0 only min(gridDim.x, max(g_min, blocks / bpg))
+// workgroups, rounded up to a multiple of eight, take part; the others return false at once.
+__device__ __forceinline__ bool scan_share(const uint32_t* __restrict__ blkpre, int n, uint32_t bpg, uint32_t g_min,
+                                           uint32_t parts, uint32_t part, uint32_t& b, uint32_t& b_end) {
+    const uint32_t base = blkpre[0], total = blkpre[n] - base;
+    uint32_t G = gridDim.x;
+    if (bpg) {
+        uint32_t want = total / bpg;
+        want = want < g_min ? g_min : want;
+        want = (want + 7u) & ~7u;
+        if (want < G) G = want;
+    }
+    if (blockIdx.x >= G) return false;
+    const uint32_t g = xcd_share_index(blockIdx.x, G) * parts + part, NG = G * parts;
+    b = base + (uint32_t)(((uint64_t)total * g) / NG);
+    b_end = base + (uint32_t)(((uint64_t)total * (g + 1)) / NG);
+    return b < b_end;
+}
+
 template <int M>
 __device__ __forceinline__ float adc_sum(const float* lut, const uint32_t* wds) {
     float s0 = 0.f, s1 = 0.f;
@@ -430,7 +439,9 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                                                        const uint32_t* __restrict__ pair_start,
                                                        const uint32_t* __restrict__ pair_len,
                                                        const uint32_t* __restrict__ blkpre,
-                                                       const uint32_t* __restrict__ unit_pairs, int P, int w,
+                                                       const uint32_t* __restrict__ unit_pairs, int n_host,
+                                                       const uint32_t* __restrict__ n_dev, uint32_t bpg,
+                                                       uint32_t g_min, int w,
                                                        const float* __restrict__ tau, uint2* __restrict__ cand,
                                                        uint32_t* __restrict__ cand_cnt, CandLayout lay,
                                                        const uint32_t* __restrict__ tau_id,
@@ -441,11 +452,9 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
     wq.pos = wq.est + WQ_CAP;
     wq.tag = wq.pos + WQ_CAP;
     wq.n = 0;
-    const uint32_t total = blkpre[P];
-    const uint32_t G = gridDim.x, g = xcd_share_index(blockIdx.x, gridDim.x);
-    uint32_t b = (uint32_t)(((uint64_t)total * g) / G);
-    const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / G);
-    if (b >= b_end) return;
+    const int P = n_dev ? (int)*n_dev : n_host;
+    uint32_t b, b_end;
+    if (P <= 0 || !scan_share(blkpre, P, bpg, g_min, 1u, 0u, b, b_end)) return;
     // last pair p with blkpre[p] <= b
     int lo = 0, hi = P;
     while (hi - lo > 1) {
@@ -522,31 +531,28 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
 }
 
 template <int M>
+static size_t scan_lds_bytes() { return (size_t)(M * IVFR_KS + 4 * WQ_WORDS) * sizeof(float); }
+
+template <int M>
 static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
-                         const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau,
-                         uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st,
+                         const uint32_t* blkpre, const uint32_t* unit_pairs, const ScanShape& sh, int w,
+                         const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st,
                          const uint32_t* tau_id) {
-    size_t lds = (size_t)(M * IVFR_KS + 4 * WQ_WORDS) * sizeof(float);
-    static bool attr_done = false;
-    if (!attr_done && lds > 48 * 1024) {
-        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_kernel<M>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_done = true;
-    }
-    hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start, pair_len,
-                       blkpre, unit_pairs, P, w, tau, cand, cand_cnt, lay, tau_id, ix->ids);
+    hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(sh.groups), dim3(256), scan_lds_bytes<M>(), st, ix->codes, lut,
+                       pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min, w, tau, cand,
+                       cand_cnt, lay, tau_id, ix->ids);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
 int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
-                     const uint32_t* blkpre, const uint32_t* unit_pairs, int P, int w, const float* tau, uint2* cand,
-                     uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st, const uint32_t* tau_id) {
-    if (P <= 0) return IVFR_OK;
+                     const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape sh, int w, const float* tau,
+                     uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st, const uint32_t* tau_id) {
+    if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
 #define IVFR_SCAN_CASE(MM)                                                                                     \
     case MM:                                                                                                   \
-        return launch_scan_m<MM>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, P, w, tau, cand, cand_cnt, \
-                                 lay, groups, st, tau_id)
+        return launch_scan_m<MM>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, \
+                                 lay, st, tau_id)
     switch (ix->p.m) {
         IVFR_SCAN_CASE(4);
         IVFR_SCAN_CASE(8);
@@ -946,7 +952,9 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
                                                               const uint32_t* __restrict__ pair_start,
                                                               const uint32_t* __restrict__ pair_len,
                                                               const uint32_t* __restrict__ blkpre,
-                                                              const uint32_t* __restrict__ unit_pairs, int nunits,
+                                                              const uint32_t* __restrict__ unit_pairs, int n_host,
+                                                              const uint32_t* __restrict__ n_dev, uint32_t bpg,
+                                                              uint32_t g_min,
                                                               int w, const float* __restrict__ tau,
                                                               uint2* __restrict__ cand,
                                                               uint32_t* __restrict__ cand_cnt, CandLayout lay,
@@ -960,11 +968,9 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
     wq.pos = wq.est + WQ_CAP;
     wq.tag = wq.pos + WQ_CAP;
     wq.n = 0;
-    const uint32_t total = blkpre[nunits];
-    const uint32_t NG = gridDim.x, g = xcd_share_index(blockIdx.x, gridDim.x);
-    uint32_t b = (uint32_t)(((uint64_t)total * g) / NG);
-    const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / NG);
-    if (b >= b_end) return;
+    const int nunits = n_dev ? (int)*n_dev : n_host;
+    uint32_t b, b_end;
+    if (nunits <= 0 || !scan_share(blkpre, nunits, bpg, g_min, 1u, 0u, b, b_end)) return;
     int lo = 0, hi = nunits;   // last unit u with blkpre[u] <= b
     while (hi - lo > 1) {
         int mid = (lo + hi) >> 1;
@@ -1080,19 +1086,16 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
 }
 
 template <int M, int G>
+static size_t shared_lds_bytes() { return (size_t)(M * IVFR_KS * G + 4 * WQ_WORDS) * sizeof(float); }
+
+template <int M, int G>
 static int launch_shared_mg(const ivfr_index* ix, const float* lut, const uint32_t* pair_start,
-                            const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
-                            int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
-                            hipStream_t st, const float* lut_scale, const uint8_t* exact_only) {
-    size_t lds = (size_t)(M * IVFR_KS * G + 4 * WQ_WORDS) * sizeof(float);
-    static bool attr_done = false;
-    if (!attr_done && lds > 48 * 1024) {
-        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared_kernel<M, G>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_done = true;
-    }
-    hipLaunchKernelGGL((adc_scan_shared_kernel<M, G>), dim3(groups), dim3(256), lds, st, ix->codes, lut, pair_start,
-                       pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, lut_scale, exact_only);
+                            const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs,
+                            const ScanShape& sh, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
+                            CandLayout lay, hipStream_t st, const float* lut_scale, const uint8_t* exact_only) {
+    hipLaunchKernelGGL((adc_scan_shared_kernel<M, G>), dim3(sh.groups), dim3(256), (shared_lds_bytes<M, G>()), st,
+                       ix->codes, lut, pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min,
+                       w, tau, cand, cand_cnt, lay, lut_scale, exact_only);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -1100,12 +1103,12 @@ static int launch_shared_mg(const ivfr_index* ix, const float* lut, const uint32
 bool ivfr_shared_scan_supported(const ivfr_index* ix) { return ix->p.m <= 16; }
 
 int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const uint32_t* pair_start,
-                            const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits,
-                            int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups,
+                            const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs,
+                            ScanShape sh, int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay,
                             hipStream_t st, const float* lut_scale, const uint8_t* exact_only) {
-    if (nunits <= 0) return IVFR_OK;
+    if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
 #define IVFR_SH_ARGS \
-    ix, lut, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st, lut_scale, exact_only
+    ix, lut, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st, lut_scale, exact_only
     if (G == 4) {
         switch (ix->p.m) {
             case 4: return launch_shared_mg<4, 4>(IVFR_SH_ARGS);
@@ -1161,59 +1164,63 @@ __global__ __launch_bounds__(64 * WAVES) void adc_sample_kernel(const uint8_t* _
                                                                 const uint32_t* __restrict__ pair_start,
                                                                 const uint32_t* __restrict__ len_s,
                                                                 const uint32_t* __restrict__ chunk_pre,
-                                                                const uint32_t* __restrict__ items, uint32_t n_items,
+                                                                const uint32_t* __restrict__ items,
+                                                                const uint32_t* __restrict__ n_items_dev,
                                                                 const uint32_t* __restrict__ soff, int w,
                                                                 uint2* __restrict__ cand, CandLayout lay) {
     extern __shared__ float s_lut[];   // WAVES wavefronts x M * 256 floats
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t item = blockIdx.x * WAVES + wave;   // uniform over the wavefront
-    if (item >= n_items) return;
-    const uint32_t p = items[item];
-    const uint32_t first = (item - chunk_pre[p]) * IVFR_SAMPLE_CHUNK;
-    const uint32_t n = len_s[p];
-    const uint32_t last = n - first < IVFR_SAMPLE_CHUNK ? n : first + IVFR_SAMPLE_CHUNK;   // exclusive
+    const uint32_t n_items = *n_items_dev;
     float* T = s_lut + wave * M * IVFR_KS;
-    {
-        const float4* src = reinterpret_cast<const float4*>(lut + (int64_t)p * M * IVFR_KS);
-        float4* dst = reinterpret_cast<float4*>(T);
+    // every wavefront walks over the chunks on its own (item is uniform over the wavefront)
+    for (uint32_t item = blockIdx.x * WAVES + wave; item < n_items; item += gridDim.x * WAVES) {
+        const uint32_t p = items[item];
+        const uint32_t first = (item - chunk_pre[p]) * IVFR_SAMPLE_CHUNK;
+        const uint32_t n = len_s[p];
+        const uint32_t last = n - first < IVFR_SAMPLE_CHUNK ? n : first + IVFR_SAMPLE_CHUNK;   // exclusive
+        {
+            const float4* src = reinterpret_cast<const float4*>(lut + (int64_t)p * M * IVFR_KS);
+            float4* dst = reinterpret_cast<float4*>(T);
 #pragma unroll
-        for (int i = 0; i < M; ++i) dst[i * 64 + lane] = src[i * 64 + lane];
-    }
-    // the wavefront's own writes are visible to its later reads: LDS operations of one wavefront complete in order
-    const uint32_t start = pair_start[p];
-    const int q = (int)(p / (uint32_t)w);
-    // bare estimates: the buffer (records of 8 bytes) holds at least the query's whole sample
-    float* out = reinterpret_cast<float*>(cand + lay.base(q)) + soff[p];
-    for (uint32_t e = first + 2u * lane; e < last; e += 128u) {
-        uint32_t w0[M / 4], w1[M / 4];
-        load_code_pair<M>(codes, start, e, true, last, w0, w1);
-        out[e] = adc_sum<M>(T, w0);
-        if (e + 1 < last) out[e + 1] = adc_sum<M>(T, w1);
+            for (int i = 0; i < M; ++i) dst[i * 64 + lane] = src[i * 64 + lane];
+        }
+        // the wavefront's own writes are visible to its later reads, and its reads of the previous chunk's table
+        // are done before these writes: LDS operations of one wavefront complete in order
+        const uint32_t start = pair_start[p];
+        const int q = (int)(p / (uint32_t)w);
+        // bare estimates: the buffer (records of 8 bytes) holds at least the query's whole sample
+        float* out = reinterpret_cast<float*>(cand + lay.base(q)) + soff[p];
+        for (uint32_t e = first + 2u * lane; e < last; e += 128u) {
+            uint32_t w0[M / 4], w1[M / 4];
+            load_code_pair<M>(codes, start, e, true, last, w0, w1);
+            out[e] = adc_sum<M>(T, w0);
+            if (e + 1 < last) out[e + 1] = adc_sum<M>(T, w1);
+        }
     }
 }
 
 template <int M, int WAVES>
+static size_t sample_lds_bytes() { return (size_t)WAVES * M * IVFR_KS * sizeof(float); }
+
+template <int M, int WAVES>
 static int launch_sample_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
-                           const uint32_t* chunk_pre, const uint32_t* items, uint32_t n_items, const uint32_t* soff,
-                           int w, uint2* cand, CandLayout lay, hipStream_t st) {
-    size_t lds = (size_t)WAVES * M * IVFR_KS * sizeof(float);
-    static bool attr_done = false;
-    if (!attr_done && lds > 48 * 1024) {
-        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_sample_kernel<M, WAVES>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_done = true;
-    }
-    hipLaunchKernelGGL((adc_sample_kernel<M, WAVES>), dim3((n_items + WAVES - 1) / WAVES), dim3(64 * WAVES), lds, st,
-                       ix->codes, lut, pair_start, len_s, chunk_pre, items, n_items, soff, w, cand, lay);
+                           const uint32_t* chunk_pre, const uint32_t* items, const uint32_t* n_items, size_t max_items,
+                           const uint32_t* soff, int w, uint2* cand, CandLayout lay, hipStream_t st) {
+    const size_t lds = sample_lds_bytes<M, WAVES>();
+    // as many workgroups as fit the compute units' LDS twice over, or one wavefront per chunk when there are fewer
+    const size_t per_cu = std::max<size_t>(1, (size_t)(160 * 1024) / lds);
+    const size_t grid = std::max<size_t>(1, std::min((max_items + WAVES - 1) / WAVES, (size_t)ix->n_cu * per_cu * 2));
+    hipLaunchKernelGGL((adc_sample_kernel<M, WAVES>), dim3((unsigned)grid), dim3(64 * WAVES), lds, st, ix->codes, lut,
+                       pair_start, len_s, chunk_pre, items, n_items, soff, w, cand, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
 int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
-                            const uint32_t* chunk_pre, const uint32_t* items, uint32_t n_items, const uint32_t* soff,
-                            int w, uint2* cand, CandLayout lay, hipStream_t st) {
-    if (n_items == 0) return IVFR_OK;
-#define IVFR_SAMPLE_ARGS ix, lut, pair_start, len_s, chunk_pre, items, n_items, soff, w, cand, lay, st
+                            const uint32_t* chunk_pre, const uint32_t* items, const uint32_t* n_items, size_t max_items,
+                            const uint32_t* soff, int w, uint2* cand, CandLayout lay, hipStream_t st) {
+    if (max_items == 0) return IVFR_OK;
+#define IVFR_SAMPLE_ARGS ix, lut, pair_start, len_s, chunk_pre, items, n_items, max_items, soff, w, cand, lay, st
     switch (ix->p.m) {
         case 4: return launch_sample_m<4, 4>(IVFR_SAMPLE_ARGS);
         case 8: return launch_sample_m<8, 4>(IVFR_SAMPLE_ARGS);
@@ -1246,7 +1253,9 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
                                                                 const uint32_t* __restrict__ pair_start,
                                                                 const uint32_t* __restrict__ pair_len,
                                                                 const uint32_t* __restrict__ blkpre,
-                                                                const uint32_t* __restrict__ unit_pairs, int nunits,
+                                                                const uint32_t* __restrict__ unit_pairs, int n_host,
+                                                                const uint32_t* __restrict__ n_dev, uint32_t bpg,
+                                                                uint32_t g_min,
                                                                 int w, const float* __restrict__ tau,
                                                                 uint2* __restrict__ cand,
                                                                 uint32_t* __restrict__ cand_cnt, CandLayout lay) {
@@ -1257,11 +1266,9 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
     uint32_t* q_mask = q_entry + Q8H_CAP;
     uint32_t* s_pid = reinterpret_cast<uint32_t*>(s_raw) + M * IVFR_KS * 4 + (H8_T / 64) * (2 * Q8H_CAP);
     float* s_tau = reinterpret_cast<float*>(s_pid + 8);
-    const uint32_t total = blkpre[nunits];
-    const uint32_t NG = gridDim.x, g = xcd_share_index(blockIdx.x, gridDim.x);
-    uint32_t b = (uint32_t)(((uint64_t)total * g) / NG);
-    const uint32_t b_end = (uint32_t)(((uint64_t)total * (g + 1)) / NG);
-    if (b >= b_end) return;
+    const int nunits = n_dev ? (int)*n_dev : n_host;
+    uint32_t b, b_end;
+    if (nunits <= 0 || !scan_share(blkpre, nunits, bpg, g_min, 1u, 0u, b, b_end)) return;
     int lo = 0, hi = nunits;
     while (hi - lo > 1) {
         int mid = (lo + hi) >> 1;
@@ -1423,19 +1430,18 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
 }
 
 template <int M>
+static size_t shared8h_lds_bytes() {
+    return (size_t)M * IVFR_KS * 16 + (H8_T / 64) * 2 * Q8H_CAP * sizeof(uint32_t) + 16 * sizeof(uint32_t);
+}
+
+template <int M>
 static int launch_shared8h_m(const ivfr_index* ix, const float* lut, const float* lut_scale,
                              const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
-                             const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,
-                             uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
-    size_t lds = (size_t)M * IVFR_KS * 16 + (H8_T / 64) * 2 * Q8H_CAP * sizeof(uint32_t) + 16 * sizeof(uint32_t);
-    static bool attr_done = false;
-    if (!attr_done && lds > 48 * 1024) {
-        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_shared8h_kernel<M>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_done = true;
-    }
-    hipLaunchKernelGGL(adc_scan_shared8h_kernel<M>, dim3(groups), dim3(H8_T), lds, st, ix->codes, lut, lut_scale,
-                       pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay);
+                             const uint32_t* unit_pairs, const ScanShape& sh, int w, const float* tau, uint2* cand,
+                             uint32_t* cand_cnt, CandLayout lay, hipStream_t st) {
+    hipLaunchKernelGGL(adc_scan_shared8h_kernel<M>, dim3(sh.groups), dim3(H8_T), shared8h_lds_bytes<M>(), st, ix->codes,
+                       lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min,
+                       w, tau, cand, cand_cnt, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -1444,13 +1450,13 @@ bool ivfr_shared8h_supported(const ivfr_index* ix) { return ix->p.m <= 16; }
 
 int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const float* lut_scale,
                               const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
-                              const uint32_t* unit_pairs, int nunits, int w, const float* tau, uint2* cand,
-                              uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
-    if (nunits <= 0) return IVFR_OK;
+                              const uint32_t* unit_pairs, ScanShape sh, int w, const float* tau, uint2* cand,
+                              uint32_t* cand_cnt, CandLayout lay, hipStream_t st) {
+    if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
     switch (ix->p.m) {
-        case 4: return launch_shared8h_m<4>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
-        case 8: return launch_shared8h_m<8>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
-        case 16: return launch_shared8h_m<16>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st);
+        case 4: return launch_shared8h_m<4>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st);
+        case 8: return launch_shared8h_m<8>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st);
+        case 16: return launch_shared8h_m<16>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st);
         default:
             ivfr_set_error("half-precision shared scan supports m <= 16; got %d", ix->p.m);
             return IVFR_ERR_INVALID_ARG;
@@ -1494,7 +1500,9 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
                                                               const uint32_t* __restrict__ pair_start,
                                                               const uint32_t* __restrict__ pair_len,
                                                               const uint32_t* __restrict__ blkpre,
-                                                              const uint32_t* __restrict__ unit_pairs, int nunits,
+                                                              const uint32_t* __restrict__ unit_pairs, int n_host,
+                                                              const uint32_t* __restrict__ n_dev, uint32_t bpg,
+                                                              uint32_t g_min,
                                                               int w, const float* __restrict__ tau,
                                                               uint2* __restrict__ cand,
                                                               uint32_t* __restrict__ cand_cnt, CandLayout lay) {
@@ -1513,6 +1521,8 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
     float* s_c0 = s_tau + MF_ROWS;
     const int tid = threadIdx.x, lane = tid & 63, row = lane & 31, h = lane >> 5;
 
+    const int nunits = n_dev ? (int)*n_dev : n_host;   // uniform over the workgroup: no unit, no work, no barrier
+    if (nunits <= 0 || blkpre[nunits] == blkpre[0]) return;
     // codebook scale: a power of two that brings the largest component below 128
     float cmax = 0.f, nmax = 0.f;
 #pragma unroll
@@ -1531,12 +1541,8 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
     for (int i = tid; i < M * IVFR_KS; i += MF_T) s_norm[i] = pq_norm[i];
     __syncthreads();   // the only barrier: from here on every wavefront works alone
 
-    const uint32_t total = blkpre[nunits];
-    const uint32_t NW = gridDim.x * (MF_T / 64);
-    const uint32_t gw = xcd_share_index(blockIdx.x, gridDim.x) * (MF_T / 64) + (uint32_t)(tid >> 6);
-    uint32_t b = (uint32_t)(((uint64_t)total * gw) / NW);
-    const uint32_t b_end = (uint32_t)(((uint64_t)total * (gw + 1)) / NW);
-    if (b >= b_end) return;
+    uint32_t b, b_end;
+    if (!scan_share(blkpre, nunits, bpg, g_min, MF_T / 64, (uint32_t)(tid >> 6), b, b_end)) return;
     int lo = 0, hi = nunits;
     while (hi - lo > 1) {
         int mid = (lo + hi) >> 1;
@@ -1760,21 +1766,20 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
 }
 
 template <int M, int DSUB>
+static size_t mfma64_lds_bytes() {
+    return (size_t)IVFR_KS * M * DSUB * 2 + (size_t)M * IVFR_KS * 4 +
+           (size_t)(MF_T / 64) * (2 * MFQ_CAP + 3 * MF_ROWS) * sizeof(uint32_t);
+}
+
+template <int M, int DSUB>
 static int launch_mfma64_md(const ivfr_index* ix, const float* queries, const int32_t* probe, const float* lut,
                             const float* lut_scale, const uint32_t* pair_start, const uint32_t* pair_len,
-                            const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits, int w, const float* tau,
-                            uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
-    const size_t lds = (size_t)IVFR_KS * M * DSUB * 2 + (size_t)M * IVFR_KS * 4 +
-                       (size_t)(MF_T / 64) * (2 * MFQ_CAP + 3 * MF_ROWS) * sizeof(uint32_t);
-    static bool attr_done = false;
-    if (!attr_done && lds > 48 * 1024) {
-        IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(adc_scan_mfma64_kernel<M, DSUB>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_done = true;
-    }
-    hipLaunchKernelGGL((adc_scan_mfma64_kernel<M, DSUB>), dim3(groups), dim3(MF_T), lds, st, ix->codes, queries, probe,
-                       ix->coarse, ix->pq, ix->pq_norm, ix->pq_maxnorm, lut, lut_scale, pair_start, pair_len, blkpre,
-                       unit_pairs, nunits, w, tau, cand, cand_cnt, lay);
+                            const uint32_t* blkpre, const uint32_t* unit_pairs, const ScanShape& sh, int w,
+                            const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st) {
+    hipLaunchKernelGGL((adc_scan_mfma64_kernel<M, DSUB>), dim3(sh.groups), dim3(MF_T), (mfma64_lds_bytes<M, DSUB>()), st,
+                       ix->codes, queries, probe, ix->coarse, ix->pq, ix->pq_norm, ix->pq_maxnorm, lut, lut_scale,
+                       pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min, w, tau, cand,
+                       cand_cnt, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -1787,10 +1792,10 @@ bool ivfr_mfma_scan_supported(const ivfr_index* ix) {
 
 int ivfr_launch_scan_mfma64(const ivfr_index* ix, const float* queries, const int32_t* probe, const float* lut,
                             const float* lut_scale, const uint32_t* pair_start, const uint32_t* pair_len,
-                            const uint32_t* blkpre, const uint32_t* unit_pairs, int nunits, int w, const float* tau,
-                            uint2* cand, uint32_t* cand_cnt, CandLayout lay, int groups, hipStream_t st) {
-    if (nunits <= 0) return IVFR_OK;
-#define IVFR_MF_ARGS ix, queries, probe, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, nunits, w, tau, cand, cand_cnt, lay, groups, st
+                            const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape sh, int w, const float* tau,
+                            uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st) {
+    if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
+#define IVFR_MF_ARGS ix, queries, probe, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st
     const int key = ix->p.m * 100 + ix->dsub;
     switch (key) {
         case 408: return launch_mfma64_md<4, 8>(IVFR_MF_ARGS);
@@ -1804,4 +1809,45 @@ int ivfr_launch_scan_mfma64(const ivfr_index* ix, const float* queries, const in
             return IVFR_ERR_INVALID_ARG;
     }
 #undef IVFR_MF_ARGS
+}
+
+// ------------------------------------------------------------------------------------------
+// Dynamic LDS beyond 48 KB has to be allowed per kernel and device.  Called by ivfr_create with the
+// index's device current, for every instantiation the launchers above can pick.
+// ------------------------------------------------------------------------------------------
+template <class K>
+static int allow_lds(K kernel, size_t bytes) {
+    if (bytes <= 48 * 1024) return IVFR_OK;
+    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)bytes));
+    return IVFR_OK;
+}
+
+int ivfr_scan_init() {
+    IVFR_TRY(allow_lds(adc_scan_kernel<4>, scan_lds_bytes<4>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<8>, scan_lds_bytes<8>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<16>, scan_lds_bytes<16>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<32>, scan_lds_bytes<32>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<64>, scan_lds_bytes<64>()));
+    IVFR_TRY(allow_lds(adc_scan_shared_kernel<4, 4>, shared_lds_bytes<4, 4>()));
+    IVFR_TRY(allow_lds(adc_scan_shared_kernel<8, 4>, shared_lds_bytes<8, 4>()));
+    IVFR_TRY(allow_lds(adc_scan_shared_kernel<16, 4>, shared_lds_bytes<16, 4>()));
+    IVFR_TRY(allow_lds(adc_scan_shared_kernel<4, 2>, shared_lds_bytes<4, 2>()));
+    IVFR_TRY(allow_lds(adc_scan_shared_kernel<8, 2>, shared_lds_bytes<8, 2>()));
+    IVFR_TRY(allow_lds(adc_scan_shared_kernel<16, 2>, shared_lds_bytes<16, 2>()));
+    IVFR_TRY(allow_lds(adc_scan_shared8h_kernel<4>, shared8h_lds_bytes<4>()));
+    IVFR_TRY(allow_lds(adc_scan_shared8h_kernel<8>, shared8h_lds_bytes<8>()));
+    IVFR_TRY(allow_lds(adc_scan_shared8h_kernel<16>, shared8h_lds_bytes<16>()));
+    IVFR_TRY(allow_lds(adc_sample_kernel<4, 4>, sample_lds_bytes<4, 4>()));
+    IVFR_TRY(allow_lds(adc_sample_kernel<8, 4>, sample_lds_bytes<8, 4>()));
+    IVFR_TRY(allow_lds(adc_sample_kernel<16, 4>, sample_lds_bytes<16, 4>()));
+    IVFR_TRY(allow_lds(adc_sample_kernel<32, 4>, sample_lds_bytes<32, 4>()));
+    IVFR_TRY(allow_lds(adc_sample_kernel<64, 2>, sample_lds_bytes<64, 2>()));
+    IVFR_TRY(allow_lds(adc_scan_mfma64_kernel<4, 8>, mfma64_lds_bytes<4, 8>()));
+    IVFR_TRY(allow_lds(adc_scan_mfma64_kernel<4, 16>, mfma64_lds_bytes<4, 16>()));
+    IVFR_TRY(allow_lds(adc_scan_mfma64_kernel<4, 32>, mfma64_lds_bytes<4, 32>()));
+    IVFR_TRY(allow_lds(adc_scan_mfma64_kernel<8, 8>, mfma64_lds_bytes<8, 8>()));
+    IVFR_TRY(allow_lds(adc_scan_mfma64_kernel<8, 16>, mfma64_lds_bytes<8, 16>()));
+    IVFR_TRY(allow_lds(adc_scan_mfma64_kernel<16, 8>, mfma64_lds_bytes<16, 8>()));
+    return IVFR_OK;
 }

@@ -39,3 +39,23 @@ def test_argument_errors_need_no_gpu():
     assert pkg.lib.ivfr_create(ctypes.byref(p), ctypes.byref(h)) == pkg.binding.ERR_INVALID_ARG
     assert pkg.lib.ivfr_create(None, ctypes.byref(h)) == pkg.binding.ERR_INVALID_ARG
     assert pkg.lib.ivfr_ntotal(None) == pkg.binding.ERR_INVALID_ARG
+
+
+def test_capacity_check_is_host_arithmetic():
+    """The byte accounting of section 3.3 (m + m' + 4 per vector) and the refusal to plan beyond the
+    memory that is available, without touching a GPU."""
+    import pytest
+    import paper_1102_3828_amd as pkg
+    ib, sb = pkg.memory_required(128, 8192, 8, 8, 10 ** 9)
+    assert sb == 0 and 20 * 10 ** 9 < ib < 20.2 * 10 ** 9           # 20 bytes per vector, ~20 GB
+    ib32, _ = pkg.memory_required(128, 8192, 8, 32, 10 ** 9)
+    assert 44 * 10 ** 9 < ib32 < 44.2 * 10 ** 9                     # 44 bytes per vector
+    ib, sb = pkg.memory_required(128, 8192, 8, 8, 10 ** 9, nq=1000, w=64, kprime=1000)
+    assert 0.5e9 < sb < 2e9                                         # 512 MB of tables + keys + candidate pool
+    pkg.memory_required(128, 8192, 8, 8, 10 ** 9, nq=1000, w=64, kprime=1000, available=288 * 10 ** 9)
+    with pytest.raises(pkg.IvfrError) as e:
+        pkg.memory_required(128, 8192, 8, 32, 10 ** 9, nq=1000, w=64, kprime=1000, available=40 * 10 ** 9)
+    assert e.value.code == pkg.binding.ERR_OOM and "exceed" in str(e.value)
+    with pytest.raises(pkg.IvfrError) as e:
+        pkg.memory_required(128, 16, 8, 8, 1000, nq=10, w=17, kprime=5)     # w > c
+    assert e.value.code == pkg.binding.ERR_INVALID_ARG

@@ -229,10 +229,11 @@ def test_config0_end_to_end_gpu_built_index():
     ix.close()
 
 
-def _full_size_case(name, n_check, **override):
+def _full_size_case(name, n_check, also=(), **override):
     """One of the five benchmark workloads at its full size, in the launch configuration the benchmark times
     (index built on the GPU from the HIP generator, first batch of 1000 queries searched in one
-    call); n_check of those queries are verified one by one against the oracle on the exported index."""
+    call); n_check of those queries are verified one by one against the oracle on the exported index.
+    also: further settings (dicts with kprime / k / n_check) searched on the same index and verified the same way."""
     import dataclasses
     import paper_1102_3828_amd as pkg
     from synthdata.gpu import DeviceMixture
@@ -255,51 +256,63 @@ def _full_size_case(name, n_check, **override):
     ix.finalize()
     B = min(cfg.batch, cfg.n_query)
     q_u8 = dm.generate(sd.STREAM_QUERY, 0, B)
-    log(name, "search")
-    g_ids, g_dist = ix.search(q_u8.float().contiguous(), cfg.w, cfg.kprime, cfg.k)
-    st = ix.search_stats()
-    log(name, st)
-    # closed form of section 3.3: a fraction of the order of w/c of the database is visited
-    frac = st["codes_scanned"] / float(B) / cfg.N
-    assert 0.3 * cfg.w / cfg.c < frac < (30.0 if cfg.zipf else 4.0) * cfg.w / cfg.c
-    # properties that hold at any size: ascending distances, distinct valid ids
-    gi, gd = g_ids.cpu().numpy(), g_dist.cpu().numpy()
-    assert (np.diff(gd, axis=1) >= 0).all() and (gi >= 0).all() and (gi < cfg.N).all()
-    assert all(len(set(r.tolist())) == cfg.k for r in gi[:50])
-    # every (query, list) pair scanned on its own, and the matrix-core units, must give the same bits for the
-    # whole batch
-    for mode in (0, 3):
-        ix.set_list_sharing(mode)
-        p_ids, p_dist = ix.search(q_u8.float().contiguous(), cfg.w, cfg.kprime, cfg.k)
-        log(name, "sharing mode", mode, ix.search_stats())
-        assert np.array_equal(p_ids.cpu().numpy(), gi) and np.array_equal(p_dist.cpu().numpy(), gd)
-    ix.set_list_sharing(2)
-    if cfg.n_query > B:
-        # the workload's whole query set in one call (more queries share every list): same bits for the first
-        # B queries as when they are searched on their own, and the same bits with the matrix-core units
-        qa = dm.generate(sd.STREAM_QUERY, 0, cfg.n_query).float().contiguous()
-        ix.set_tuning(batch=cfg.n_query)
-        outs = []
-        for mode in (2, 3):
-            ix.set_list_sharing(mode)
-            a_ids, a_dist = ix.search(qa, cfg.w, cfg.kprime, cfg.k)
-            log(name, "whole query set, sharing mode", mode, ix.search_stats())
-            outs.append((a_ids.cpu().numpy(), a_dist.cpu().numpy()))
-        assert np.array_equal(outs[0][0][:B], gi) and np.array_equal(outs[0][1][:B], gd)
-        assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    xq = q_u8.float().contiguous()
+    settings = [dict(kprime=cfg.kprime, k=cfg.k, n_check=n_check, whole=True)]
+    settings += [dict(kprime=a.get("kprime", cfg.kprime), k=a.get("k", cfg.k), n_check=a.get("n_check", n_check),
+                      whole=False) for a in also]
+    results = []
+    for s in settings:
+        kp, k = s["kprime"], s["k"]
+        log(name, "search k' =", kp, "k =", k)
         ix.set_list_sharing(2)
-        del qa
+        g_ids, g_dist = ix.search(xq, cfg.w, kp, k)
+        st = ix.search_stats()
+        log(name, st, ix.workspace_info())
+        # closed form of section 3.3: a fraction of the order of w/c of the database is visited
+        frac = st["codes_scanned"] / float(B) / cfg.N
+        assert 0.3 * cfg.w / cfg.c < frac < (30.0 if cfg.zipf else 4.0) * cfg.w / cfg.c
+        # properties that hold at any size: ascending distances, distinct valid ids
+        gi, gd = g_ids.cpu().numpy(), g_dist.cpu().numpy()
+        assert (np.diff(gd, axis=1) >= 0).all() and (gi >= 0).all() and (gi < cfg.N).all()
+        assert all(len(set(r.tolist())) == k for r in gi[:50])
+        # every (query, list) pair scanned on its own, and the matrix-core units, must give the same bits for the
+        # whole batch
+        for mode in (0, 3):
+            ix.set_list_sharing(mode)
+            p_ids, p_dist = ix.search(xq, cfg.w, kp, k)
+            log(name, "sharing mode", mode, ix.search_stats())
+            assert np.array_equal(p_ids.cpu().numpy(), gi) and np.array_equal(p_dist.cpu().numpy(), gd)
+        ix.set_list_sharing(2)
+        if s["whole"] and cfg.n_query > B:
+            # the workload's whole query set in one call (more queries share every list): same bits for the first
+            # B queries as when they are searched on their own, and the same bits with the matrix-core units
+            qa = dm.generate(sd.STREAM_QUERY, 0, cfg.n_query).float().contiguous()
+            ix.set_tuning(batch=cfg.n_query)
+            outs = []
+            for mode in (2, 3):
+                ix.set_list_sharing(mode)
+                a_ids, a_dist = ix.search(qa, cfg.w, kp, k)
+                log(name, "whole query set, sharing mode", mode, ix.search_stats())
+                outs.append((a_ids.cpu().numpy(), a_dist.cpu().numpy()))
+            assert np.array_equal(outs[0][0][:B], gi) and np.array_equal(outs[0][1][:B], gd)
+            assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+            ix.set_list_sharing(2)
+            ix.set_tuning(batch=B)
+            del qa
+        results.append((s, gi, gd))
     log(name, "export")
     coarse, pq, rq = ix.get_codebooks()
     offsets, ids, codes, rcodes = ix.export()
     ix.close()
     index = orc.Index(orc.Codebooks(coarse, pq, rq), offsets, ids, codes, rcodes)
     assert index.bytes_per_vector() == cfg.m + cfg.m_refine + 4
-    X = q_u8[:n_check].cpu().numpy()
-    log(name, "oracle on", n_check, "queries")
-    exact, excused = compare_results(gi[:n_check], gd[:n_check], X, index, cfg.w, cfg.kprime, cfg.k)
-    log(name, "exact", exact, "excused", excused)
-    assert exact >= 0.98 * n_check * cfg.k
+    for s, gi, gd in results:
+        n = s["n_check"]
+        X = q_u8[:n].cpu().numpy()
+        log(name, "oracle on", n, "queries, k' =", s["kprime"])
+        exact, excused = compare_results(gi[:n], gd[:n], X, index, cfg.w, s["kprime"], s["k"])
+        log(name, "exact", exact, "excused", excused)
+        assert exact >= 0.98 * n * s["k"]
 
 
 @pytest.mark.timeout(300)
@@ -317,9 +330,16 @@ def test_full_size_config3():
     _full_size_case("cfg3", 4)
 
 
-@pytest.mark.timeout(900)
+@pytest.mark.timeout(1200)
 def test_full_size_config4_one_billion():
-    _full_size_case("cfg4", 3)
+    """N = 10^9 with m' = 8: the short-list lengths the workload names, k' = 1000 and k' = 10000, on one index."""
+    _full_size_case("cfg4", 16, also=[dict(kprime=10000, n_check=16)])
+
+
+@pytest.mark.timeout(1200)
+def test_full_size_config4_one_billion_32_refinement_bytes():
+    """N = 10^9 with m' = 32 (44 bytes per vector resident)."""
+    _full_size_case("cfg4", 16, m_refine=32)
 
 
 def test_gpu_training_quality_matches_oracle():
@@ -604,6 +624,114 @@ def test_unrepresentative_sample(order):
         assert st["dense_fallbacks"] >= 6
     compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, index, 1, 100, 20)
     ix.close()
+
+
+def test_redo_paths_on_a_callers_stream_and_across_batches():
+    """Several queries of one call fail the filter's check (the few nearest entries lead the list): they are
+    redone without a filter.  On a non-default stream, and with the call split into internal batches so that
+    failing queries sit in batches whose arrays a later batch has overwritten, the results stay exact."""
+    torch = _torch()
+    rng = np.random.default_rng(17)
+    d, c, m, mr = 32, 1, 4, 4
+    parts = [rng.normal(180, 4, size=(4000, d)), rng.normal(60, 12, size=(116000, d))]
+    Y = np.clip(np.concatenate(parts), 0, 255).round()
+    T = Y[rng.permutation(len(Y))[:4000]]
+    ic, ip, ir = init_draws(len(T), c, m, mr)
+    books = orc.train(T, c, m, mr, 4, ic, ip, ir)
+    index = orc.build_index(Y, np.arange(len(Y)), books)
+    X = np.concatenate([rng.normal(180, 12, size=(6, d)), rng.normal(60, 12, size=(3, d))]).astype(np.float32)
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    ref_ids, ref_dist = ix.search(xq, 1, 100, 20)
+    assert ix.search_stats()["dense_fallbacks"] >= 6
+    compare_results(ref_ids.cpu().numpy(), ref_dist.cpu().numpy(), X, index, 1, 100, 20)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        s_ids, s_dist = ix.search(xq, 1, 100, 20)
+    log("caller's stream", ix.search_stats())
+    assert ix.search_stats()["dense_fallbacks"] >= 6
+    assert torch.equal(ref_ids, s_ids) and torch.equal(ref_dist, s_dist)
+    for batch in (2, 4):
+        ix.set_tuning(batch=batch)
+        with torch.cuda.stream(side):
+            b_ids, b_dist = ix.search(xq, 1, 100, 20)
+        info = ix.workspace_info()
+        log("batch", batch, ix.search_stats(), info)
+        assert info["batch_reruns"] >= 1 and ix.search_stats()["dense_fallbacks"] >= 6
+        assert torch.equal(ref_ids, b_ids) and torch.equal(ref_dist, b_dist)
+    ix.close()
+
+
+def test_candidate_pool_grows_when_the_estimate_is_low():
+    """The host sizes the candidate pool from the expected visited-list length.  Queries that all fall into one
+    list far longer than that want more: the plan kernel notices, the batch does no list work, the pool grows
+    and the batch runs again.  Later calls find the pool large enough."""
+    rng = np.random.default_rng(29)
+    d, c, m, mr = 32, 201, 4, 4
+    coarse = (rng.normal(size=(c, d)) * 60 + 128).astype(np.float32)
+    books = orc.Codebooks(coarse, (rng.normal(size=(m, 256, d // m)) * 8).astype(np.float32),
+                          (rng.normal(size=(mr, 256, d // mr)) * 2).astype(np.float32))
+    # list 0 holds 20000 vectors, every other list 1000: the expected visited-list length (sum of len^2 / N, about
+    # 2700) is below the 8 k' = 4000 entries up to which a query keeps everything, the real one far above
+    Y = np.concatenate([coarse[0][None] + rng.normal(size=(20000, d)) * 9] +
+                       [coarse[l][None] + rng.normal(size=(1000, d)) * 3 for l in range(1, c)])
+    index = orc.build_index(Y, np.arange(len(Y)), books)
+    assert index.list_offsets[1] - index.list_offsets[0] >= 19000
+    X = (coarse[0][None] + rng.normal(size=(40, d)) * 9).astype(np.float32)
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    ids, dist = ix.search(xq, 1, 500, 20)
+    info = ix.workspace_info()
+    log("first call", info, ix.search_stats())
+    assert info["batch_reruns"] == 1
+    compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, index, 1, 500, 20)
+    ids2, dist2 = ix.search(xq, 1, 500, 20)
+    info2 = ix.workspace_info()
+    assert info2["batch_reruns"] == 0 and info2["pool_bytes"] == info["pool_bytes"]
+    assert np.array_equal(ids.cpu().numpy(), ids2.cpu().numpy()) and np.array_equal(dist.cpu().numpy(), dist2.cpu().numpy())
+    ix.close()
+
+
+def test_memory_limit_refuses_before_allocating():
+    """Capacity checks on the host: with a cap below what finalize / search need the call fails with
+    IVFR_ERR_OOM and leaves the index as it was; with the cap lifted the same call succeeds."""
+    import paper_1102_3828_amd as pkg
+    wl = tiny_workload(d=64, m=8, m_refine=16, c=24, N=5000, n_train=3000)
+    index, X, Y, b = wl["index"], wl["X"], wl["Y"], wl["books"]
+    ix = pkg.Index(64, 24, 8, 16)
+    ix.set_codebooks(b.coarse, b.pq, b.rq)
+    ix.add(Y, 0)
+    ix.set_memory_limit(50_000)                       # the 5000 x 28 bytes of the lists alone are more
+    with pytest.raises(pkg.IvfrError) as e:
+        ix.finalize()
+    assert e.value.code == pkg.binding.ERR_OOM
+    ix.set_memory_limit(0)
+    ix.finalize()
+    xq = queries_dev(X)
+    held = ix.workspace_info()["index_bytes"]
+    ix.set_memory_limit(held + 100_000)               # the tables of 12 x 6 pairs alone take 590 KB
+    with pytest.raises(pkg.IvfrError) as e:
+        ix.search(xq, 6, 300, 20)
+    assert e.value.code == pkg.binding.ERR_OOM and "memory limit" in str(e.value)
+    assert ix.workspace_info()["workspace_bytes"] == 0
+    ix.set_memory_limit(0)
+    ids, dist = ix.search(xq, 6, 300, 20)
+    offsets, i2, codes, rcodes = ix.export()
+    gi = orc.Index(b, offsets, i2, codes, rcodes)
+    compare_results(ids.cpu().numpy(), dist.cpu().numpy(), X, gi, 6, 300, 20)
+    # import refuses negative ids
+    ix2 = pkg.Index(64, 24, 8, 16)
+    ix2.set_codebooks(b.coarse, b.pq, b.rq)
+    bad = i2.copy()
+    bad[7] = -3
+    with pytest.raises(pkg.IvfrError) as e:
+        ix2.import_(offsets, bad, codes, rcodes)
+    assert e.value.code == pkg.binding.ERR_INVALID_ARG
+    ix2.import_(offsets, i2, codes, rcodes)           # the refused call left nothing behind
+    ids3, dist3 = ix2.search(xq, 6, 300, 20)
+    assert np.array_equal(ids.cpu().numpy(), ids3.cpu().numpy())
+    ix.close()
+    ix2.close()
 
 
 def test_empty_lists_and_short_results():
