@@ -281,6 +281,8 @@ def small_config_entry(name, args):
     ix, xq, _, gt, build_t = build_index(cfg, dm, n_gt, args.train_iters)
     B = min(cfg.batch, cfg.n_query)
     ix.set_tuning(batch=min(B, 65535))
+    if args.table_mode >= 0:
+        ix.set_table_mode(args.table_mode)
     batches = [xq[i * B:(i + 1) * B].contiguous() for i in range(max(1, cfg.n_query // B))]
     elapsed, acc, _ = timed_loop(ix, batches, cfg, args.steps, args.warmup, "default")
     stage = other_stage_times(ix, batches, cfg, 1)
@@ -400,6 +402,9 @@ def main():
     ap.add_argument("--sharing", type=int, default=2, choices=(0, 1, 2, 3),
                     help="list sharing mode of the default loop: 0 per pair, 1 fp32 units of four/two, 2 also fp16 units "
                          "of eight, 3 also matrix-core units of 64")
+    ap.add_argument("--table-mode", type=int, default=-1, choices=(-1, 0, 1),
+                    help="look-up tables: 0 one per (query, list) pair in the workspace, 1 split into per-list and "
+                         "per-query terms summed in the scan (-1: the library's default)")
     ap.add_argument("--sweep", default="", choices=("", "table1", "table2", "fig3"),
                     help="run a parameter sweep in the shape of the paper's Table 1, Table 2 or Figure 3 on the "
                          "synthetic generator (one JSON line per setting) instead of the benchmark")
@@ -451,6 +456,8 @@ def main():
     n_gt = min(args.gt_queries, cfg.n_query)
     ix, xq, queries_u8, gt, build_t = build_index(cfg, dm, n_gt, args.train_iters)
     log(f"[bench] {cfg.name}: encoded + finalized {cfg.N} vectors in {build_t['add_s']:.1f}s")
+    if args.table_mode >= 0:
+        ix.set_table_mode(args.table_mode)
     if args.scan_groups:
         ix.set_tuning(scan_groups=args.scan_groups)
     if args.per_pair:
@@ -511,7 +518,7 @@ def main():
         "config": {"workload": f"{cfg.name}: N={cfg.N} d={cfg.d} c={cfg.c} m={cfg.m} m'={cfg.m_refine} "
                                f"w={cfg.w} k'={cfg.kprime} k={cfg.k}, {B} queries per step",
                    "generator": f"uint8 Gaussian mixture G={cfg.G} zipf={cfg.zipf} seed={sd.BASE_SEED}",
-                   "list_sharing_mode": args.sharing},
+                   "list_sharing_mode": args.sharing, "table_mode": args.table_mode},
         "adc_codes_per_s": acc["codes_scanned"] / elapsed,
         "value_f32_per_pair": steps * B / el0, "ms_per_step_f32_per_pair": 1e3 * el0 / steps,
         "adc_codes_per_s_f32_per_pair": acc0["codes_scanned"] / el0, "dtype_f32_per_pair": "f32",

@@ -149,6 +149,18 @@ int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* 
  * that filters with a rigorous error margin, followed by the same exact fp32 re-evaluation. */
 int ivfr_set_list_sharing(ivfr_index* index, int32_t mode);
 
+/* Look-up tables of Eq. (5).  mode 0: one m x 256 table per (query, visited list) pair is computed on
+ * the matrix cores and written to the workspace (w * m KB per query), from where the scan kernels
+ * load it.  mode 1 (split tables): the entry ||(x - c_l)^j - p_jk||^2 is expanded into
+ * ||(x - c_l)^j||^2 + (||p_jk||^2 + 2 c_l^j . p_jk) - 2 x^j . p_jk; the bracket is a c x m x 256 table kept
+ * with the index (built by the first search call in this mode, c * m KB), the last term one table per
+ * query, the first m scalars per pair, and the scan kernels add the three when a pair's table enters
+ * LDS: no per-pair table is written or read back.  Entries then carry the rounding of the larger
+ * intermediate terms (about 1e-6 of an estimate instead of 1e-7); all scan kernels evaluate an entry by
+ * the same expression, so the list-sharing modes stay bit-identical to one another within a table
+ * mode.  With split tables list-sharing mode 3 acts as mode 2. */
+int ivfr_set_table_mode(ivfr_index* index, int32_t mode);
+
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
  *   full_mult   (8)    a query that visits at most full_mult*k' entries keeps every estimate; a
  *                      larger one first scores a sample of its entries (the same leading fraction of
@@ -167,8 +179,10 @@ int ivfr_set_tuning(ivfr_index* index, int32_t full_mult, int32_t cap_mult, int3
                     int32_t scan_groups);
 
 /* Device memory.  ivfr_memory_required is pure host arithmetic (no GPU call): the bytes an index of N
- * vectors with these parameters holds on the device (index_bytes: codes, refinement codes, ids, list
- * directory, codebooks) and the workspace a search call with nq queries, w and kprime adds
+ * vectors with these parameters holds on the device (index_bytes: per vector the m-byte code that the
+ * list scan streams plus one record of id, list, code and refinement code - m + m' + 8 bytes rounded
+ * up to 32, 64 or 128 - that the re-rank gathers with a single memory access; list table; codebooks)
+ * and the workspace a search call with nq queries, w and kprime adds
  * (search_bytes: per-batch arrays plus the candidate pool expected for lists of equal length; a
  * skewed index can want more).  Either output may be NULL.  With available_bytes > 0 it returns
  * IVFR_ERR_OOM when the sum exceeds it.  ivfr_set_memory_limit caps what this index may hold in

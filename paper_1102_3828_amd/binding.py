@@ -52,6 +52,7 @@ def _load():
         "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 9),
         "ivfr_set_list_sharing": (ctypes.c_int, [vp, i32]),
         "ivfr_set_tuning": (ctypes.c_int, [vp, i32, i32, i32, i32, i32]),
+        "ivfr_set_table_mode": (ctypes.c_int, [vp, i32]),
         "ivfr_set_profiling": (ctypes.c_int, [vp, i32]),
         "ivfr_memory_required": (ctypes.c_int, [ctypes.POINTER(Params), i64, i64, i32, i32, i64,
                                                 ctypes.POINTER(i64), ctypes.POINTER(i64)]),
@@ -70,7 +71,7 @@ lib = _load()
 EXPORTED = ["ivfr_create", "ivfr_destroy", "ivfr_train", "ivfr_set_codebooks", "ivfr_get_codebooks", "ivfr_add",
             "ivfr_finalize", "ivfr_ntotal", "ivfr_export", "ivfr_import", "ivfr_search", "ivfr_search_trace",
             "ivfr_search_stats", "ivfr_set_list_sharing", "ivfr_set_tuning", "ivfr_set_profiling", "ivfr_stage_times", "ivfr_last_error",
-            "ivfr_memory_required", "ivfr_set_memory_limit", "ivfr_workspace_info"]
+            "ivfr_memory_required", "ivfr_set_memory_limit", "ivfr_workspace_info", "ivfr_set_table_mode"]
 
 
 def _check(rc):
@@ -217,6 +218,11 @@ class Index:
         """0 = per pair; 1 = fp32 units of four / two; 2 = also fp16 units of eight (default); 3 = also
         matrix-core units of 64."""
         _check(lib.ivfr_set_list_sharing(self._h, int(mode)))
+
+    def set_table_mode(self, mode):
+        """0 = one look-up table per (query, list) pair in the workspace; 1 = split tables (per-list and per-query
+        terms summed in the scan's prologue)."""
+        _check(lib.ivfr_set_table_mode(self._h, int(mode)))
 
     def set_tuning(self, full_mult=0, cap_mult=0, min_cap=0, batch=0, scan_groups=0):
         _check(lib.ivfr_set_tuning(self._h, full_mult, cap_mult, min_cap, batch, scan_groups))

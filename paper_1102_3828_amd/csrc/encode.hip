@@ -131,34 +131,96 @@ int ivfr_launch_list_ranks(const int32_t* list, int64_t n, int c, unsigned long 
     return IVFR_OK;
 }
 
-// Move one staged batch into the finished, list-sorted arrays.
+// Move one staged batch into the finished, list-sorted arrays: the dense code stream of the list scan and the
+// per-entry record (id, list, code, refinement code) that the re-rank and the tie-breaks by id read.
 __global__ __launch_bounds__(256) void scatter_kernel(const int32_t* __restrict__ list,
                                                       const uint32_t* __restrict__ rank,
                                                       const int32_t* __restrict__ ids_in,
                                                       const uint8_t* __restrict__ codes_in,
                                                       const uint8_t* __restrict__ rcodes_in, int64_t n, int m, int mr,
                                                       const uint32_t* __restrict__ list_start,
-                                                      int32_t* __restrict__ ids, uint8_t* __restrict__ codes,
-                                                      uint8_t* __restrict__ rcodes) {
+                                                      uint8_t* __restrict__ codes, uint8_t* __restrict__ rec,
+                                                      int rec_stride) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    uint64_t dst = (uint64_t)list_start[list[i]] + rank[i];
-    ids[dst] = ids_in[i];
+    const int l = list[i];
+    uint64_t dst = (uint64_t)list_start[l] + rank[i];
     const uint32_t* s = reinterpret_cast<const uint32_t*>(codes_in + i * m);
     uint32_t* o = reinterpret_cast<uint32_t*>(codes + dst * m);
-    for (int t = 0; t < m / 4; ++t) o[t] = s[t];
+    uint32_t* r = reinterpret_cast<uint32_t*>(rec + dst * rec_stride);
+    r[0] = (uint32_t)ids_in[i];
+    r[1] = (uint32_t)l;
+    for (int t = 0; t < m / 4; ++t) { o[t] = s[t]; r[2 + t] = s[t]; }
     if (mr > 0) {
         const uint32_t* sr = reinterpret_cast<const uint32_t*>(rcodes_in + i * mr);
-        uint32_t* orr = reinterpret_cast<uint32_t*>(rcodes + dst * mr);
-        for (int t = 0; t < mr / 4; ++t) orr[t] = sr[t];
+        for (int t = 0; t < mr / 4; ++t) r[2 + m / 4 + t] = sr[t];
     }
 }
 
-int ivfr_launch_scatter(const StagedChunk& ch, int m, int mr, const uint32_t* list_start, int32_t* ids,
-                        uint8_t* codes, uint8_t* rcodes, hipStream_t st) {
+int ivfr_launch_scatter(const StagedChunk& ch, int m, int mr, const uint32_t* list_start, uint8_t* codes,
+                        uint8_t* rec, int rec_stride, hipStream_t st) {
     if (ch.n <= 0) return IVFR_OK;
     hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)((ch.n + 255) / 256)), dim3(256), 0, st, ch.list, ch.rank,
-                       ch.ids, ch.codes, ch.rcodes, ch.n, m, mr, list_start, ids, codes, rcodes);
+                       ch.ids, ch.codes, ch.rcodes, ch.n, m, mr, list_start, codes, rec, rec_stride);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+// Records <-> dense per-slot arrays, for import and export.  Slots [slot0, slot0 + n) of the padded layout;
+// ids_st [n], rcodes_st [n, mr] are indexed by slot - slot0.  pack: the list of a slot is the last one that
+// starts at or before it (binary search); slots past the end of their list are padding and are left alone.
+__global__ __launch_bounds__(256) void pack_records_kernel(uint64_t slot0, int64_t n, int m, int mr, int c,
+                                                           const uint32_t* __restrict__ list_start,
+                                                           const uint32_t* __restrict__ list_len,
+                                                           const int32_t* __restrict__ ids_st,
+                                                           const uint8_t* __restrict__ rcodes_st,
+                                                           const uint8_t* __restrict__ codes,
+                                                           uint8_t* __restrict__ rec, int rec_stride) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t slot = slot0 + (uint64_t)i;
+    int lo = 0, hi = c;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if ((uint64_t)list_start[mid] <= slot) lo = mid; else hi = mid;
+    }
+    if (slot - list_start[lo] >= list_len[lo]) return;
+    uint32_t* r = reinterpret_cast<uint32_t*>(rec + slot * rec_stride);
+    r[0] = (uint32_t)ids_st[i];
+    r[1] = (uint32_t)lo;
+    const uint32_t* s = reinterpret_cast<const uint32_t*>(codes + slot * m);
+    for (int t = 0; t < m / 4; ++t) r[2 + t] = s[t];
+    const uint32_t* sr = reinterpret_cast<const uint32_t*>(rcodes_st + i * mr);
+    for (int t = 0; t < mr / 4; ++t) r[2 + m / 4 + t] = sr[t];
+}
+
+__global__ __launch_bounds__(256) void unpack_records_kernel(uint64_t slot0, int64_t n, int m, int mr,
+                                                             const uint8_t* __restrict__ rec, int rec_stride,
+                                                             int32_t* __restrict__ ids_st,
+                                                             uint8_t* __restrict__ rcodes_st) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t* r = reinterpret_cast<const uint32_t*>(rec + (slot0 + (uint64_t)i) * rec_stride);
+    ids_st[i] = (int32_t)r[0];
+    uint32_t* o = reinterpret_cast<uint32_t*>(rcodes_st + i * mr);
+    for (int t = 0; t < mr / 4; ++t) o[t] = r[2 + m / 4 + t];
+}
+
+int ivfr_launch_pack_records(const ivfr_index* ix, uint64_t slot0, int64_t n, const int32_t* ids_st,
+                             const uint8_t* rcodes_st, hipStream_t st) {
+    if (n <= 0) return IVFR_OK;
+    hipLaunchKernelGGL(pack_records_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, slot0, n, ix->p.m,
+                       ix->p.m_refine, ix->p.c, ix->list_start, ix->list_len, ids_st, rcodes_st, ix->codes, ix->rec,
+                       ix->rec_stride);
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+int ivfr_launch_unpack_records(const ivfr_index* ix, uint64_t slot0, int64_t n, int32_t* ids_st, uint8_t* rcodes_st,
+                               hipStream_t st) {
+    if (n <= 0) return IVFR_OK;
+    hipLaunchKernelGGL(unpack_records_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, slot0, n, ix->p.m,
+                       ix->p.m_refine, ix->rec, ix->rec_stride, ids_st, rcodes_st);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }

@@ -8,8 +8,12 @@
 // launchers defined in encode.hip
 int ivfr_launch_list_ranks(const int32_t* list, int64_t n, int c, unsigned long long* list_fill, uint32_t* cnt,
                            int T, uint32_t* rank, hipStream_t st);
-int ivfr_launch_scatter(const StagedChunk& ch, int m, int mr, const uint32_t* list_start, int32_t* ids,
-                        uint8_t* codes, uint8_t* rcodes, hipStream_t st);
+int ivfr_launch_scatter(const StagedChunk& ch, int m, int mr, const uint32_t* list_start, uint8_t* codes,
+                        uint8_t* rec, int rec_stride, hipStream_t st);
+int ivfr_launch_pack_records(const ivfr_index* ix, uint64_t slot0, int64_t n, const int32_t* ids_st,
+                             const uint8_t* rcodes_st, hipStream_t st);
+int ivfr_launch_unpack_records(const ivfr_index* ix, uint64_t slot0, int64_t n, int32_t* ids_st, uint8_t* rcodes_st,
+                               hipStream_t st);
 int ivfr_launch_iota(int32_t* ids, int64_t n, int64_t base, hipStream_t st);
 int ivfr_launch_km_accum_rows(const float* X, int64_t n, int d, const int32_t* assign, unsigned long long* sums,
                               unsigned long long* counts, hipStream_t st);
@@ -131,8 +135,9 @@ extern "C" int ivfr_destroy(ivfr_index* ix) {
     (void)hipDeviceSynchronize();
     free_staged(ix);
     dev_free(ix->coarse); dev_free(ix->coarse_norm); dev_free(ix->pq); dev_free(ix->pq_norm); dev_free(ix->pq_maxnorm); dev_free(ix->rq);
-    dev_free(ix->list_fill); dev_free(ix->list_start); dev_free(ix->list_len); dev_free(ix->chunk_list);
-    dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
+    dev_free(ix->list_term);
+    dev_free(ix->list_fill); dev_free(ix->list_start); dev_free(ix->list_len);
+    dev_free(ix->codes); dev_free(ix->rec);
     ix->search_ws.release(); ix->cand_ws.release(); ix->encode_ws.release(); ix->dense_ws.release();
     if (ix->h_slots) (void)hipHostFree(ix->h_slots);
     if (ix->h_redo) (void)hipHostFree(ix->h_redo);
@@ -181,6 +186,7 @@ extern "C" int ivfr_set_codebooks(ivfr_index* ix, const float* coarse, const flo
         IVFR_HIP(hipMemcpy(ix->rq, rq, (size_t)p.m_refine * IVFR_KS * ix->dsub_r * sizeof(float), hipMemcpyHostToDevice));
     IVFR_TRY(refresh_norms(ix, nullptr));
     IVFR_HIP(hipDeviceSynchronize());
+    dev_free(ix->list_term);   // belongs to the previous codebooks
     ix->has_books = true;
     return IVFR_OK;
 }
@@ -320,6 +326,7 @@ extern "C" int ivfr_train(ivfr_index* ix, const uint8_t* train, int64_t n, int32
     }
     TR(refresh_norms(ix, st));
     TRH(hipStreamSynchronize(st));
+    dev_free(ix->list_term);   // belongs to the previous codebooks
 #undef TR
 #undef TRH
     cleanup();
@@ -421,8 +428,8 @@ int ivfr_check_room(const ivfr_index* ix, size_t more) {
 }
 
 static void free_layout(ivfr_index* ix) {
-    dev_free(ix->list_start); dev_free(ix->list_len); dev_free(ix->chunk_list);
-    dev_free(ix->codes); dev_free(ix->rcodes); dev_free(ix->ids);
+    dev_free(ix->list_start); dev_free(ix->list_len);
+    dev_free(ix->codes); dev_free(ix->rec);
     ix->index_bytes = 0;
 }
 
@@ -464,29 +471,11 @@ static int install_layout_inner(ivfr_index* ix, const std::vector<int64_t>& offs
     IVFR_TRY(dev_alloc(&ix->list_len, (size_t)c));
     IVFR_HIP(hipMemcpy(ix->list_start, ix->h_start.data(), ((size_t)c + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
     IVFR_HIP(hipMemcpy(ix->list_len, len.data(), (size_t)c * sizeof(uint32_t), hipMemcpyHostToDevice));
-    // position -> list directory: for every 2^shift slots the last list that starts at or before the
-    // chunk's first slot (about 2^18 chunks); an entry's list is then found between two neighbours
-    int shift = 6;
-    while ((ix->n_slots >> shift) > (1ull << 18)) ++shift;
-    const size_t n_chunks = (size_t)(ix->n_slots >> shift) + 2;
-    std::vector<uint32_t> dir(n_chunks);
-    {
-        int l = 0;
-        for (size_t i = 0; i < n_chunks; ++i) {
-            const uint64_t first = (uint64_t)i << shift;
-            while (l + 1 < c && (uint64_t)ix->h_start[(size_t)l + 1] <= first) ++l;
-            dir[i] = (uint32_t)l;
-        }
-    }
-    ix->chunk_shift = shift;
-    IVFR_TRY(dev_alloc(&ix->chunk_list, n_chunks));
-    IVFR_HIP(hipMemcpy(ix->chunk_list, dir.data(), n_chunks * sizeof(uint32_t), hipMemcpyHostToDevice));
+    ix->rec_stride = ivfr_record_stride(ix->p);
     IVFR_TRY(dev_alloc(&ix->codes, (size_t)ix->n_slots * ix->p.m));
-    IVFR_TRY(dev_alloc(&ix->rcodes, (size_t)ix->n_slots * ix->p.m_refine));
-    IVFR_TRY(dev_alloc(&ix->ids, (size_t)ix->n_slots));
+    IVFR_TRY(dev_alloc(&ix->rec, (size_t)ix->n_slots * ix->rec_stride));
     IVFR_HIP(hipMemset(ix->codes, 0, (size_t)ix->n_slots * ix->p.m));
-    if (ix->p.m_refine) IVFR_HIP(hipMemset(ix->rcodes, 0, (size_t)ix->n_slots * ix->p.m_refine));
-    IVFR_HIP(hipMemset(ix->ids, 0xff, (size_t)ix->n_slots * sizeof(int32_t)));
+    IVFR_HIP(hipMemset(ix->rec, 0xff, (size_t)ix->n_slots * ix->rec_stride));   // padding slots: id -1
     return IVFR_OK;
 }
 
@@ -504,7 +493,7 @@ extern "C" int ivfr_finalize(ivfr_index* ix) {
     if (offsets[(size_t)c] != ix->n_added) { ivfr_set_error("internal: list fill %lld != added %lld", (long long)offsets[(size_t)c], (long long)ix->n_added); return IVFR_ERR_STATE; }
     IVFR_TRY(install_layout(ix, offsets));
     for (auto& ch : ix->staged)
-        IVFR_TRY(ivfr_launch_scatter(ch, ix->p.m, ix->p.m_refine, ix->list_start, ix->ids, ix->codes, ix->rcodes, nullptr));
+        IVFR_TRY(ivfr_launch_scatter(ch, ix->p.m, ix->p.m_refine, ix->list_start, ix->codes, ix->rec, ix->rec_stride, nullptr));
     IVFR_HIP(hipDeviceSynchronize());
     free_staged(ix);
     ix->encode_ws.release();
@@ -519,14 +508,35 @@ extern "C" int ivfr_export(const ivfr_index* ix, int64_t* list_offsets, int32_t*
     IVFR_TRY(use_device(ix));
     const int c = ix->p.c, m = ix->p.m, mr = ix->p.m_refine;
     memcpy(list_offsets, ix->h_offsets.data(), ((size_t)c + 1) * sizeof(int64_t));
-    for (int l = 0; l < c; ++l) {
-        const int64_t a = ix->h_offsets[(size_t)l], n = ix->h_offsets[(size_t)l + 1] - a;
-        if (n == 0) continue;
-        const uint64_t s = ix->h_start[(size_t)l];
-        IVFR_HIP(hipMemcpy(ids + a, ix->ids + s, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost));
-        IVFR_HIP(hipMemcpy(codes + a * m, ix->codes + s * m, (size_t)n * m, hipMemcpyDeviceToHost));
-        if (mr) IVFR_HIP(hipMemcpy(rcodes + a * mr, ix->rcodes + s * mr, (size_t)n * mr, hipMemcpyDeviceToHost));
+    // ids and refinement codes are unpacked from the per-entry records into dense per-slot staging arrays, a run of
+    // whole lists at a time; every list is then one contiguous copy per array
+    ivfr_index* mix = const_cast<ivfr_index*>(ix);
+    const uint64_t chunk_slots = 1ull << 24;
+    int l = 0;
+    while (l < c) {
+        const uint64_t s0 = ix->h_start[(size_t)l];
+        int l1 = l + 1;
+        while (l1 < c && (uint64_t)ix->h_start[(size_t)l1 + 1] - s0 <= chunk_slots) ++l1;
+        const uint64_t ns = (uint64_t)ix->h_start[(size_t)l1] - s0;   // slots of lists l .. l1-1 (at least one list)
+        if (ns > 0) {
+            IVFR_TRY(ivfr_check_room(ix, ns * (4 + (size_t)mr) > ix->encode_ws.bytes ? ns * (4 + (size_t)mr) + 512 : 0));
+            IVFR_TRY(mix->encode_ws.reserve(ns * (4 + (size_t)mr) + 512));
+            int32_t* ids_st = mix->encode_ws.as<int32_t>();
+            uint8_t* rc_st = mix->encode_ws.as<uint8_t>() + ((ns * 4 + 255) / 256 * 256);
+            IVFR_TRY(ivfr_launch_unpack_records(ix, s0, (int64_t)ns, ids_st, rc_st, nullptr));
+            IVFR_HIP(hipDeviceSynchronize());
+            for (int j = l; j < l1; ++j) {
+                const int64_t a = ix->h_offsets[(size_t)j], n = ix->h_offsets[(size_t)j + 1] - a;
+                if (n == 0) continue;
+                const uint64_t s = ix->h_start[(size_t)j], rel = s - s0;
+                IVFR_HIP(hipMemcpy(ids + a, ids_st + rel, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost));
+                IVFR_HIP(hipMemcpy(codes + a * m, ix->codes + s * m, (size_t)n * m, hipMemcpyDeviceToHost));
+                if (mr) IVFR_HIP(hipMemcpy(rcodes + a * mr, rc_st + rel * mr, (size_t)n * mr, hipMemcpyDeviceToHost));
+            }
+        }
+        l = l1;
     }
+    mix->encode_ws.release();
     return IVFR_OK;
 }
 
@@ -546,14 +556,34 @@ extern "C" int ivfr_import(ivfr_index* ix, int64_t N, const int64_t* list_offset
     IVFR_TRY(use_device(ix));
     std::vector<int64_t> offsets(list_offsets, list_offsets + c + 1);
     IVFR_TRY(install_layout(ix, offsets));
-    for (int l = 0; l < c; ++l) {
-        const int64_t a = offsets[(size_t)l], n = offsets[(size_t)l + 1] - a;
-        if (n == 0) continue;
-        const uint64_t s = ix->h_start[(size_t)l];
-        IVFR_HIP(hipMemcpy(ix->ids + s, ids + a, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice));
-        IVFR_HIP(hipMemcpy(ix->codes + s * m, codes + a * m, (size_t)n * m, hipMemcpyHostToDevice));
-        if (mr) IVFR_HIP(hipMemcpy(ix->rcodes + s * mr, rcodes + a * mr, (size_t)n * mr, hipMemcpyHostToDevice));
+    // codes go straight to the scan's dense stream; ids and refinement codes through dense per-slot staging arrays,
+    // a run of whole lists at a time, from which the per-entry records are packed on the device
+    const uint64_t chunk_slots = 1ull << 24;
+    int l = 0;
+    while (l < c) {
+        const uint64_t s0 = ix->h_start[(size_t)l];
+        int l1 = l + 1;
+        while (l1 < c && (uint64_t)ix->h_start[(size_t)l1 + 1] - s0 <= chunk_slots) ++l1;
+        const uint64_t ns = (uint64_t)ix->h_start[(size_t)l1] - s0;
+        if (ns > 0) {
+            IVFR_TRY(ivfr_check_room(ix, ns * (4 + (size_t)mr) > ix->encode_ws.bytes ? ns * (4 + (size_t)mr) + 512 : 0));
+            IVFR_TRY(ix->encode_ws.reserve(ns * (4 + (size_t)mr) + 512));
+            int32_t* ids_st = ix->encode_ws.as<int32_t>();
+            uint8_t* rc_st = ix->encode_ws.as<uint8_t>() + ((ns * 4 + 255) / 256 * 256);
+            for (int j = l; j < l1; ++j) {
+                const int64_t a = offsets[(size_t)j], n = offsets[(size_t)j + 1] - a;
+                if (n == 0) continue;
+                const uint64_t s = ix->h_start[(size_t)j], rel = s - s0;
+                IVFR_HIP(hipMemcpy(ids_st + rel, ids + a, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice));
+                IVFR_HIP(hipMemcpy(ix->codes + s * m, codes + a * m, (size_t)n * m, hipMemcpyHostToDevice));
+                if (mr) IVFR_HIP(hipMemcpy(rc_st + rel * mr, rcodes + a * mr, (size_t)n * mr, hipMemcpyHostToDevice));
+            }
+            IVFR_TRY(ivfr_launch_pack_records(ix, s0, (int64_t)ns, ids_st, rc_st, nullptr));
+            IVFR_HIP(hipDeviceSynchronize());
+        }
+        l = l1;
     }
+    ix->encode_ws.release();
     IVFR_HIP(hipDeviceSynchronize());
     ix->n_added = N;
     ix->finalized = true;
@@ -571,6 +601,24 @@ extern "C" int ivfr_set_tuning(ivfr_index* ix, int32_t full_mult, int32_t cap_mu
     if (min_cap) ix->min_cap = min_cap;
     if (batch) ix->batch = batch;
     ix->scan_groups = scan_groups;
+    return IVFR_OK;
+}
+
+int ivfr_ensure_list_terms(ivfr_index* ix, hipStream_t st) {
+    if (ix->list_term) return IVFR_OK;
+    const size_t count = (size_t)ix->p.c * ix->p.m * IVFR_KS;
+    IVFR_TRY(ivfr_check_room(ix, count * sizeof(float)));
+    IVFR_TRY(dev_alloc(&ix->list_term, count));
+    ix->index_bytes += count * sizeof(float);
+    const int r = ivfr_launch_list_terms(ix, ix->list_term, st);
+    if (r != IVFR_OK) { dev_free(ix->list_term); ix->index_bytes -= count * sizeof(float); }
+    return r;
+}
+
+extern "C" int ivfr_set_table_mode(ivfr_index* ix, int32_t mode) {
+    IVFR_REQUIRE(ix, "ivfr_set_table_mode: null index");
+    IVFR_REQUIRE(mode == 0 || mode == 1, "table mode %d must be 0 (one table per pair) or 1 (split tables)", mode);
+    ix->split_tables = mode;
     return IVFR_OK;
 }
 

@@ -103,6 +103,8 @@ struct ivfr_index {
     float* pq_norm = nullptr;      // [m, 256]
     float* pq_maxnorm = nullptr;   // [m] largest centroid norm of each sub-quantizer
     float* rq = nullptr;           // [m', 256, dsub_r]
+    float* list_term = nullptr;    // [c, m, 256] per-list part of the look-up tables (split tables), built on demand
+    int split_tables = 0;          // 1: look-up tables are summed in the scan's prologue from list and query terms
     bool has_books = false;
 
     // staging
@@ -118,11 +120,13 @@ struct ivfr_index {
     uint64_t n_slots = 0;            // padded entry count incl. tail pad
     uint32_t* list_start = nullptr;  // [c+1]
     uint32_t* list_len = nullptr;    // [c]
-    uint32_t* chunk_list = nullptr;  // [(n_slots >> chunk_shift) + 2]: last list starting at or before slot i << chunk_shift
-    int chunk_shift = 0;
-    uint8_t* codes = nullptr;        // [n_slots, m]
-    uint8_t* rcodes = nullptr;       // [n_slots, m']
-    int32_t* ids = nullptr;          // [n_slots]
+    uint8_t* codes = nullptr;        // [n_slots, m]: the dense stream the list scan reads
+    // One record per entry slot for everything that is fetched per candidate (re-rank, tie-breaks by id):
+    //   int32 id | uint32 list | m code bytes | m' refinement code bytes | padding to rec_stride
+    // rec_stride is a power of two up to 128 (a multiple of 64 beyond), so a record never straddles a 128-byte
+    // line: a short-list candidate costs one line instead of three from separate id / code / refinement arrays.
+    uint8_t* rec = nullptr;          // [n_slots, rec_stride]
+    int rec_stride = 0;
     std::vector<int64_t> h_offsets;  // logical CSR offsets [c+1] (host)
     std::vector<uint32_t> h_start;   // padded starts [c+1] (host)
 
@@ -156,13 +160,22 @@ struct ivfr_index {
 };
 
 // Device bytes of the finished inverted file with n_slots padded entry slots.
+// Bytes between two records of the per-entry record array (see ivfr_index::rec).
+inline int ivfr_record_stride(const ivfr_params& p) {
+    const int need = 8 + p.m + p.m_refine;
+    int r = 32;
+    while (r < need && r < 128) r <<= 1;
+    if (r < need) r = (need + 63) / 64 * 64;
+    return r;
+}
 inline size_t ivfr_index_bytes(const ivfr_params& p, uint64_t n_slots) {
-    return (size_t)n_slots * ((size_t)p.m + (size_t)p.m_refine + sizeof(int32_t)) + ((size_t)p.c * 2 + 1) * sizeof(uint32_t) +
-           ((size_t)1 << 18) * sizeof(uint32_t);
+    return (size_t)n_slots * ((size_t)p.m + (size_t)ivfr_record_stride(p)) + ((size_t)p.c * 2 + 1) * sizeof(uint32_t);
 }
 // IVFR_ERR_OOM (before anything is allocated) when `more` further device bytes do not fit: beyond the index's
 // memory limit, when one is set, or beyond what the device reports as free.
 int ivfr_check_room(const ivfr_index* ix, size_t more);
+// Allocates and fills the per-list term table of the split look-up tables if the index does not hold it yet.
+int ivfr_ensure_list_terms(ivfr_index* ix, hipStream_t st);
 
 // ---- kernels' host launchers (each enqueues on `st` and returns a status) -------------------
 
@@ -203,7 +216,8 @@ struct SelectArgs {
     // source B: records (estimate bits, entry position) with key = (estimate bits << 32) | ids[position];
     // segment q holds min(counts[q], lay.cap(q)) records from lay.base(q)
     const uint2* recs = nullptr;
-    const int32_t* ids = nullptr;
+    const int32_t* ids = nullptr;      // id of the entry at position pos is ids[pos * id_stride]
+    uint32_t id_stride = 1;            // in 32-bit words (the ids sit at the start of the per-entry records)
     const uint32_t* counts = nullptr;
     CandLayout lay;
 };
@@ -270,6 +284,63 @@ __host__ __device__ inline unsigned long long ivfr_plan_capacity(unsigned long l
     return capv;
 }
 
+// Where the scan kernels get the look-up table of a (query, list) pair from (Eq. (5)).
+//  materialised: lut[pair][j][k], written per batch by the table kernel;
+//  split:        ||(x - c_l)^j - p_jk||^2 = ||(x - c_l)^j||^2 + (||p_jk||^2 + 2 c_l^j . p_jk) - 2 x^j . p_jk:
+//                the bracket is a per-list table kept with the index (list_term[l][j][k]), the last term a
+//                per-query table (lut[query][j][k]), the first a per-pair scalar (pbase[pair][j]); the entry is
+//                max(0, (list_term + query term) + pbase), evaluated by the same expression wherever it is needed
+//                (table prologues and exact re-evaluations alike), so every kernel sees the same bits.
+struct PairTable {
+    const float* a;      // the pair's materialised table, or its list's term table   [m][256]
+    const float* b;      // nullptr, or the query's term table                         [m][256]
+    const float* base;   // split: ||(x - c_l)^j||^2, j < m
+    __device__ __forceinline__ float get(int e) const {   // e = j * 256 + k
+        return b ? fmaxf(0.f, (a[e] + b[e]) + base[e >> 8]) : a[e];
+    }
+    __device__ __forceinline__ float4 get4(int e) const {   // e a multiple of 4
+        const float4 va = *reinterpret_cast<const float4*>(a + e);
+        if (!b) return va;
+        const float4 vb = *reinterpret_cast<const float4*>(b + e);
+        const float s = base[e >> 8];
+        return make_float4(fmaxf(0.f, (va.x + vb.x) + s), fmaxf(0.f, (va.y + vb.y) + s), fmaxf(0.f, (va.z + vb.z) + s),
+                           fmaxf(0.f, (va.w + vb.w) + s));
+    }
+};
+struct TableSrc {
+    const float* lut = nullptr;        // [pairs][m][256], or in split mode [queries][m][256]
+    const float* list_term = nullptr;  // split mode: [c][m][256]
+    const float* pbase = nullptr;      // split mode: [pairs][m]
+    const int32_t* probe = nullptr;    // split mode: list of every pair
+    int w = 1, table_words = 0;        // pairs per query; m * 256
+    int m = 0;
+    __device__ __forceinline__ PairTable pair(int64_t pid) const {
+        PairTable t;
+        if (list_term) {
+            t.a = list_term + (int64_t)probe[pid] * table_words;
+            t.b = lut + (pid / w) * table_words;
+            t.base = pbase + pid * m;
+        } else {
+            t.a = lut + pid * table_words;
+            t.b = nullptr;
+            t.base = nullptr;
+        }
+        return t;
+    }
+    // the same tables seen from a query's pair range [first, first + n): for launches over a slice of the batch
+    TableSrc slice(int64_t first_pair) const {
+        TableSrc s = *this;
+        if (list_term) {
+            s.lut = lut + (first_pair / w) * table_words;
+            s.pbase = pbase + first_pair * m;
+            s.probe = probe + first_pair;
+        } else {
+            s.lut = lut + first_pair * table_words;
+        }
+        return s;
+    }
+};
+
 // Search plan, look-up tables, sample and list scan (scan.hip)
 struct PlanBuffers {
     uint32_t* pair_start;  // [P] first padded entry of the pair's list
@@ -297,6 +368,11 @@ int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, 
                      const PlanBuffers& pb, hipStream_t st);
 int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
                     float* lut, float* lut_scale, hipStream_t st);
+// Split tables.  list terms [c][m][256] = ||p_jk||^2 + 2 c_l^j . p_jk (once per index); per batch the query terms
+// [nq][m][256] = -2 x^j . p_jk and, per pair, pbase [P][m] = ||(x - c_l)^j||^2 with the fp16 scale of the pair's table.
+int ivfr_launch_list_terms(const ivfr_index* ix, float* list_term, hipStream_t st);
+int ivfr_launch_query_terms(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
+                            float* qterm, float* pbase, float* lut_scale, hipStream_t st);
 // Geometry of a list-scan launch.  The number of units (pairs, or units of several pairs) is either known on
 // the host or read by the kernel from a device word; the kernel spreads the launch's blocks over
 // min(groups, max(g_min, blocks / bpg)) workgroups (a multiple of eight: one contiguous share of the block
@@ -311,7 +387,7 @@ struct ScanShape {
 // unit_pairs == nullptr: unit u of the launch is pair u; otherwise pair unit_pairs[u].  An entry is kept
 // when its estimate is <= tau[q]; with tau_id, when its key (estimate, id) is <= (tau[q], tau_id[q]).
 // blkpre may be a slice of a longer prefix array: the launch's blocks are blkpre[0] .. blkpre[units].
-int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
+int ivfr_launch_scan(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape shape, int w, const float* tau,
                      uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st,
                      const uint32_t* tau_id = nullptr);
@@ -321,7 +397,7 @@ int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pai
 // pair of chunk i, chunk_pre the pairs' chunk prefix.
 // n_items: device word with the number of chunks; max_items: a host-side upper bound (sizes the grid, whose
 // wavefronts walk over the chunks).
-int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
+int ivfr_launch_sample_scan(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* len_s,
                             const uint32_t* chunk_pre, const uint32_t* items, const uint32_t* n_items, size_t max_items,
                             const uint32_t* soff, int w, uint2* cand, CandLayout lay, hipStream_t st);
 
@@ -351,18 +427,18 @@ int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint
 // half-precision tables with an exact re-evaluation, like the units of eight.
 bool ivfr_shared_scan_supported(const ivfr_index* ix);
 bool ivfr_shared8h_supported(const ivfr_index* ix);
-int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const uint32_t* pair_start,
+int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const TableSrc& ts, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs,
                             ScanShape shape, int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay,
                             hipStream_t st, const float* lut_scale = nullptr, const uint8_t* exact_only = nullptr);
-int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const float* lut_scale,
+int ivfr_launch_scan_shared8h(const ivfr_index* ix, const TableSrc& ts, const float* lut_scale,
                               const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
                               const uint32_t* unit_pairs, ScanShape shape, int w, const float* tau, uint2* cand,
                               uint32_t* cand_cnt, CandLayout lay, hipStream_t st);
 // Units of 64 queries on the matrix cores (fp16 decode x query contraction as the filter, exact fp32 sums for
 // what passes).  queries: the batch's [nq][d] floats; probe: the list of every pair.
 bool ivfr_mfma_scan_supported(const ivfr_index* ix);
-int ivfr_launch_scan_mfma64(const ivfr_index* ix, const float* queries, const int32_t* probe, const float* lut,
+int ivfr_launch_scan_mfma64(const ivfr_index* ix, const float* queries, const int32_t* probe, const TableSrc& ts,
                             const float* lut_scale, const uint32_t* pair_start, const uint32_t* pair_len,
                             const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape shape, int w, const float* tau,
                             uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st);

@@ -7,10 +7,11 @@
 // Eight lanes share one entry and interleave its dimensions in 16-byte pieces (lane t takes
 // dimensions 4t..4t+3 of every group of 32), so that one load instruction of the eight lanes
 // covers 128 contiguous bytes of the query and the coarse centroid and whole codebook rows (few
-// cache lines per instruction); the partial sums are combined with three xor-shuffles.  The entry's list is found from its position through a
-// directory (one list index per 2^shift slots) followed by a binary search between two
-// neighbouring directory entries, usually zero to two steps.  Output per entry: the 64-bit key
-// (distance bits << 32 | id) consumed by the final top-k selection.
+// cache lines per instruction); the partial sums are combined with three xor-shuffles.
+// Everything that is fetched per candidate - id, list, code and refinement code - sits in one
+// record that never straddles a 128-byte line, so the random gather from HBM costs one line per
+// candidate.  Output per entry: the 64-bit key (distance bits << 32 | id) consumed by the final
+// top-k selection.
 #include "ivfr_internal.h"
 #include <algorithm>
 
@@ -18,11 +19,8 @@ template <int VEC>
 __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ queries, int d, int c, int m, int mr,
                                                      int dsub, int dsub_r, const float* __restrict__ coarse,
                                                      const float* __restrict__ pq, const float* __restrict__ rq,
-                                                     const uint32_t* __restrict__ list_start,
-                                                     const uint32_t* __restrict__ chunk_list, int chunk_shift,
-                                                     const uint8_t* __restrict__ codes,
-                                                     const uint8_t* __restrict__ rcodes,
-                                                     const int32_t* __restrict__ ids, int kprime, int q_base,
+                                                     const uint8_t* __restrict__ rec, int rec_stride,
+                                                     int kprime, int q_base,
                                                      const uint32_t* __restrict__ short_pos,
                                                      const int32_t* __restrict__ short_n, uint64_t* __restrict__ keys,
                                                      float* __restrict__ refined_out, int32_t* __restrict__ ids_out) {
@@ -35,16 +33,11 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
     int32_t id = -1;
     if (live) {
         const uint32_t pos = short_pos[(int64_t)q * kprime + slot];
-        // last list with list_start <= pos
-        int lo = (int)chunk_list[pos >> chunk_shift], hi = (int)chunk_list[(pos >> chunk_shift) + 1] + 1;
-        while (hi - lo > 1) {
-            int mid = (lo + hi) >> 1;
-            if (list_start[mid] <= pos) lo = mid; else hi = mid;
-        }
-        const int l = lo;
-        id = ids[pos];
-        const uint8_t* code = codes + (uint64_t)pos * m;
-        const uint8_t* rcode = rcodes + (uint64_t)pos * mr;
+        const uint8_t* r = rec + (uint64_t)pos * rec_stride;
+        id = *reinterpret_cast<const int32_t*>(r);
+        const uint32_t l = *reinterpret_cast<const uint32_t*>(r + 4);
+        const uint8_t* code = r + 8;
+        const uint8_t* rcode = r + 8 + m;
         const float* x = queries + (int64_t)q * d;
         const float* cl = coarse + (int64_t)l * d;
         if (VEC == 4) {
@@ -101,11 +94,8 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
 __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restrict__ queries, int d, int c, int m, int mr,
                                                           int dsub, int dsub_r, const float* __restrict__ coarse,
                                                           const float* __restrict__ pq, const float* __restrict__ rq,
-                                                          const uint32_t* __restrict__ list_start,
-                                                          const uint32_t* __restrict__ chunk_list, int chunk_shift,
-                                                          const uint8_t* __restrict__ codes,
-                                                          const uint8_t* __restrict__ rcodes,
-                                                          const int32_t* __restrict__ ids, int kprime, int q_base,
+                                                          const uint8_t* __restrict__ rec, int rec_stride,
+                                                          int kprime, int q_base,
                                                           int nq, const uint32_t* __restrict__ short_pos,
                                                           const int32_t* __restrict__ short_n,
                                                           uint64_t* __restrict__ keys, float* __restrict__ refined_out,
@@ -118,12 +108,12 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
     const int per_q = (kprime + 127) / 128;
     const int64_t n_items = (int64_t)nq * per_q;
     const int nit = d / 32;   // 16-byte pieces of a vector per lane (d is a multiple of 32 here, at most 128)
-    // Three items are in flight per workgroup: the position of item i + 2 is being read, the entry's id and code
-    // bytes of item i + 1 are being gathered (three random lines from HBM per entry, the latency that bounds
-    // this kernel), item i is decoded.  Loads return in issue order, so waiting for the oldest leaves the
+    // Three items are in flight per workgroup: the position of item i + 2 is being read, the record of item
+    // i + 1 (id, list, code bytes: one random line from HBM per entry, the latency that bounds this kernel) is
+    // being gathered, item i is decoded.  Loads return in issue order, so waiting for the oldest leaves the
     // younger ones in flight.
     struct Pos { int q, slot, n; uint32_t pos; };
-    struct Gather { int32_t id; uint32_t cb[4], rb[4]; };
+    struct Gather { int32_t id; uint32_t list; uint32_t cb[4], rb[4]; };
     auto read_pos = [&](int64_t item) -> Pos {
         Pos r;
         r.q = 0; r.slot = 0; r.n = 0; r.pos = 0;
@@ -138,12 +128,15 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
     auto gather = [&](const Pos& p) -> Gather {
         Gather r;
         r.id = -1;
+        r.list = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) { r.cb[k] = 0; r.rb[k] = 0; }
         if (p.slot < p.n) {   // uniform over the 8 lanes of an entry
-            r.id = ids[p.pos];
-            const uint8_t* code = codes + (uint64_t)p.pos * m;
-            const uint8_t* rcode = rcodes + (uint64_t)p.pos * mr;
+            const uint8_t* e = rec + (uint64_t)p.pos * rec_stride;
+            r.id = *reinterpret_cast<const int32_t*>(e);
+            r.list = *reinterpret_cast<const uint32_t*>(e + 4);
+            const uint8_t* code = e + 8;
+            const uint8_t* rcode = e + 8 + m;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int e = 4 * t + 32 * k;
@@ -161,14 +154,8 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
         const bool live = p0.slot < p0.n;
         float acc = 0.f;
         if (live) {
-            const uint32_t pos = p0.pos;
-            int lo = (int)chunk_list[pos >> chunk_shift], hi = (int)chunk_list[(pos >> chunk_shift) + 1] + 1;
-            while (hi - lo > 1) {
-                int mid = (lo + hi) >> 1;
-                if (list_start[mid] <= pos) lo = mid; else hi = mid;
-            }
             const float* x = queries + (int64_t)p0.q * d;
-            const float* cl = coarse + (int64_t)lo * d;
+            const float* cl = coarse + (int64_t)g0.list * d;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 if (k < nit) {
@@ -221,17 +208,15 @@ int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, i
         const int64_t n_items = (int64_t)nq * ((kprime + 127) / 128);
         const int groups = (int)std::min<int64_t>(n_items, ix->n_cu);
         hipLaunchKernelGGL(rerank_lds_kernel, dim3(groups), dim3(1024), rq_bytes, st, queries, ix->p.d, ix->p.c, ix->p.m,
-                           ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq, ix->list_start,
-                           ix->chunk_list, ix->chunk_shift, ix->codes, ix->rcodes, ix->ids, kprime, q_base, nq, short_pos,
-                           short_n, keys, refined_out, ids_out);
+                           ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq, ix->rec, ix->rec_stride,
+                           kprime, q_base, nq, short_pos, short_n, keys, refined_out, ids_out);
         IVFR_HIP(hipGetLastError());
         return IVFR_OK;
     }
     const bool vec = (ix->dsub % 4 == 0) && (ix->p.m_refine == 0 || ix->dsub_r % 4 == 0) && ((ix->p.d / 8) % 4 == 0);
 #define IVFR_RERANK_ARGS                                                                                       \
     queries, ix->p.d, ix->p.c, ix->p.m, ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq,      \
-        ix->list_start, ix->chunk_list, ix->chunk_shift, ix->codes, ix->rcodes, ix->ids, kprime, q_base,       \
-        short_pos, short_n, keys, refined_out, ids_out
+        ix->rec, ix->rec_stride, kprime, q_base, short_pos, short_n, keys, refined_out, ids_out
     if (vec) hipLaunchKernelGGL(rerank_kernel<4>, grid, dim3(256), 0, st, IVFR_RERANK_ARGS);
     else hipLaunchKernelGGL(rerank_kernel<1>, grid, dim3(256), 0, st, IVFR_RERANK_ARGS);
 #undef IVFR_RERANK_ARGS

@@ -291,6 +291,130 @@ int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* p
 }
 
 // ------------------------------------------------------------------------------------------
+// Split tables.  The table entry of Eq. (5) for query x, list l (centroid c_l), sub-quantizer j, value k is
+//   ||(x - c_l)^j - p_jk||^2 = ||(x - c_l)^j||^2 + (||p_jk||^2 + 2 c_l^j . p_jk) - 2 x^j . p_jk .
+// The bracket depends on the list only and is computed once per index (c tables), the last term on the query
+// only (one table per query instead of one per (query, list) pair), and the first is m scalars per pair; the
+// scan kernels add the three when a pair's table enters LDS, so no per-pair table is ever written to memory.
+// Both term tables are rows V [n, d] against the PQ codebook:  out[row][j][k] = beta ||p_jk||^2 + alpha V[row]^j . p_jk
+// (list terms: V = coarse centroids, alpha = 2, beta = 1; query terms: V = queries, alpha = -2, beta = 0), the
+// dot products on the matrix cores exactly as in the per-pair table kernel above.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void term_mfma_kernel(const float* __restrict__ V, int n, int d, int m, int dsub,
+                                                        const float* __restrict__ pq, const float* __restrict__ pq_norm,
+                                                        float alpha, float beta, float* __restrict__ out) {
+    extern __shared__ float smem[];
+    const int stride = d + 4;
+    float* R = smem;                   // [32][d + 4]
+    const int p0 = blockIdx.x * 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < 32 * (d / 4); i += 256) {
+        int pr = i / (d / 4), e = (i % (d / 4)) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (p0 + pr < n) v = *reinterpret_cast<const float4*>(V + (int64_t)(p0 + pr) * d + e);
+        *reinterpret_cast<float4*>(R + pr * stride + e) = v;
+    }
+    __syncthreads();
+    const int r = lane & 31, h = lane >> 5;
+    const int ntile = m * 8;   // (j, 32-centroid tile) units
+    for (int u = wave; u < ntile; u += 4) {
+        const int j = u >> 3, nt = u & 7;
+        floatx16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        const float* brow = pq + ((int64_t)j * IVFR_KS + nt * 32 + r) * dsub;
+        for (int kk = 0; kk < dsub; kk += 8) {
+            float4 a = *reinterpret_cast<const float4*>(R + r * stride + j * dsub + kk + 4 * h);
+            float4 b = *reinterpret_cast<const float4*>(brow + kk + 4 * h);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+        }
+        const float pn = beta * pq_norm[j * IVFR_KS + nt * 32 + r];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int pr = 8 * (v >> 2) + 4 * h + (v & 3);
+            if (p0 + pr < n) out[((int64_t)(p0 + pr) * m + j) * IVFR_KS + nt * 32 + r] = fmaf(alpha, acc[v], pn);
+        }
+    }
+}
+
+// the same for sub-vector widths the MFMA path does not cover (dsub % 8 != 0): one thread per output
+__global__ __launch_bounds__(256) void term_direct_kernel(const float* __restrict__ V, int64_t n, int d, int m, int dsub,
+                                                          const float* __restrict__ pq,
+                                                          const float* __restrict__ pq_norm, float alpha, float beta,
+                                                          float* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;   // row * m * 256 + j * 256 + k
+    if (i >= n * m * IVFR_KS) return;
+    const int64_t row = i / (m * IVFR_KS);
+    const int e = (int)(i % (m * IVFR_KS)), j = e >> 8;
+    const float* v = V + row * d + j * dsub;
+    const float* cb = pq + (int64_t)e * dsub;
+    float s = 0.f;
+    for (int t = 0; t < dsub; ++t) s = fmaf(v[t], cb[t], s);
+    out[i] = fmaf(alpha, s, beta * pq_norm[e]);
+}
+
+static int launch_terms(const ivfr_index* ix, const float* V, int64_t n, float alpha, float beta, float* out,
+                        hipStream_t st) {
+    if (n <= 0) return IVFR_OK;
+    const int d = ix->p.d, m = ix->p.m;
+    if (ix->dsub % 8 == 0) {
+        const size_t lds = (size_t)(32 * (d + 4)) * sizeof(float);
+        hipLaunchKernelGGL(term_mfma_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), lds, st, V, (int)n, d, m, ix->dsub,
+                           ix->pq, ix->pq_norm, alpha, beta, out);
+    } else {
+        const int64_t total = n * m * IVFR_KS;
+        hipLaunchKernelGGL(term_direct_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, V, n, d, m,
+                           ix->dsub, ix->pq, ix->pq_norm, alpha, beta, out);
+    }
+    IVFR_HIP(hipGetLastError());
+    return IVFR_OK;
+}
+
+// Per pair: pbase[p][j] = ||(x_q - c_l)^j||^2 (the same fused multiply-add chain as in the per-pair table kernel) and
+// the fp16 scale of the pair's table.  The m lanes of a pair sit side by side.
+__global__ __launch_bounds__(256) void pair_base_kernel(const float* __restrict__ queries,
+                                                        const int32_t* __restrict__ probe, int P, int w, int d, int m,
+                                                        int dsub, const float* __restrict__ coarse,
+                                                        const float* __restrict__ pq_maxnorm,
+                                                        float* __restrict__ pbase, float* __restrict__ lut_scale) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t p = i / m;
+    const int j = (int)(i % m);
+    float a2 = 0.f;
+    if (p < P) {
+        const float* x = queries + (p / w) * d + j * dsub;
+        const float* cc = coarse + (int64_t)probe[p] * d + j * dsub;
+        float s = 0.f;
+        for (int e = 0; e < dsub; ++e) { const float v = x[e] - cc[e]; s = fmaf(v, v, s); }
+        pbase[p * m + j] = s;
+        const float a = sqrtf(s) + pq_maxnorm[j];
+        a2 = a * a;
+    }
+    // upper bound of the table's entries: sum over the pair's m lanes (m is a power of two, at most 64)
+    for (int off = m >> 1; off >= 1; off >>= 1) a2 += __shfl_xor(a2, off, 64);
+    if (p < P && j == 0) lut_scale[p] = a2 > 0.f ? 60000.f / a2 : 1.f;
+}
+
+int ivfr_launch_list_terms(const ivfr_index* ix, float* list_term, hipStream_t st) {
+    return launch_terms(ix, ix->coarse, ix->p.c, 2.f, 1.f, list_term, st);
+}
+
+int ivfr_launch_query_terms(const ivfr_index* ix, const float* queries, const int32_t* probe, int nq, int w,
+                            float* qterm, float* pbase, float* lut_scale, hipStream_t st) {
+    IVFR_TRY(launch_terms(ix, queries, nq, -2.f, 0.f, qterm, st));
+    const int64_t total = (int64_t)nq * w * ix->p.m;
+    if (total > 0) {
+        hipLaunchKernelGGL(pair_base_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, queries, probe,
+                           nq * w, w, ix->p.d, ix->p.m, ix->dsub, ix->coarse, ix->pq_maxnorm, pbase, lut_scale);
+        IVFR_HIP(hipGetLastError());
+    }
+    return IVFR_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // ADC list scan (Eq. (5)): estimate = sum over the m code bytes of T[j][byte_j].
 //
 // The visited (pair, block) work of a pass is one virtual stream of blocks of IVFR_BLOCK entries;
@@ -343,6 +467,23 @@ __device__ __forceinline__ float adc_sum(const float* lut, const uint32_t* wds) 
         s1 += L[IVFR_KS + ((v >> 8) & 0xff)];
         s0 += L[2 * IVFR_KS + ((v >> 16) & 0xff)];
         s1 += L[3 * IVFR_KS + (v >> 24)];
+    }
+    return s0 + s1;
+}
+
+// The same sum, in the same order, read entry by entry from the pair's table in global memory (exact
+// re-evaluation of candidates that a reduced-precision filter let through).
+template <int M>
+__device__ __forceinline__ float adc_sum_pair(const PairTable& pt, const uint32_t* wds) {
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int t = 0; t < M / 4; ++t) {
+        uint32_t v = wds[t];
+        const int o = t * 4 * IVFR_KS;
+        s0 += pt.get(o + (int)(v & 0xff));
+        s1 += pt.get(o + IVFR_KS + (int)((v >> 8) & 0xff));
+        s0 += pt.get(o + 2 * IVFR_KS + (int)((v >> 16) & 0xff));
+        s1 += pt.get(o + 3 * IVFR_KS + (int)(v >> 24));
     }
     return s0 + s1;
 }
@@ -435,7 +576,7 @@ __device__ __forceinline__ void wq_flush(WaveQueue& wq, uint2* const (&qc)[G], u
 
 template <int M>
 __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict__ codes,
-                                                       const float* __restrict__ lut,
+                                                       TableSrc ts,
                                                        const uint32_t* __restrict__ pair_start,
                                                        const uint32_t* __restrict__ pair_len,
                                                        const uint32_t* __restrict__ blkpre,
@@ -445,7 +586,7 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                                                        const float* __restrict__ tau, uint2* __restrict__ cand,
                                                        uint32_t* __restrict__ cand_cnt, CandLayout lay,
                                                        const uint32_t* __restrict__ tau_id,
-                                                       const int32_t* __restrict__ ids) {
+                                                       const int32_t* __restrict__ ids, uint32_t id_stride) {
     extern __shared__ float s_lut[];   // M * 256 floats, then the wavefronts' append queues
     WaveQueue wq;
     wq.est = reinterpret_cast<uint32_t*>(s_lut) + M * IVFR_KS + (threadIdx.x >> 6) * WQ_WORDS;
@@ -479,9 +620,9 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
         uint32_t* const cnt[1] = {cand_cnt + q};
         __syncthreads();   // previous pair's table no longer in use
         {
-            const float4* src = reinterpret_cast<const float4*>(lut + pid * M * IVFR_KS);
+            const PairTable pt = ts.pair(pid);
             float4* dst = reinterpret_cast<float4*>(s_lut);
-            for (int i = tid; i < M * IVFR_KS / 4; i += 256) dst[i] = src[i];
+            for (int i = tid; i < M * IVFR_KS / 4; i += 256) dst[i] = pt.get4(4 * i);
         }
         __syncthreads();
         // two blocks per iteration: both loads are issued before the first table look-up
@@ -514,8 +655,8 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                 const float est1 = adc_sum<M>(s_lut, wds[u][1]);
                 bool k0 = in0[u] && est0 <= t, k1 = in1[u] && est1 <= t;
                 if (tau_id) {
-                    if (k0 && est0 == t) k0 = (uint32_t)ids[start + e0[u]] <= t_id;
-                    if (k1 && est1 == t) k1 = (uint32_t)ids[start + e0[u] + 1] <= t_id;
+                    if (k0 && est0 == t) k0 = (uint32_t)ids[(size_t)(start + e0[u]) * id_stride] <= t_id;
+                    if (k1 && est1 == t) k1 = (uint32_t)ids[(size_t)(start + e0[u] + 1) * id_stride] <= t_id;
                 }
                 if (keep_all) {   // nothing is filtered: a full wavefront of records per pass, one atomic for all of them
                     append_records(k0, est0, start + e0[u], k1, est1, start + e0[u] + 1, qc[0], cnt[0], cap[0]);
@@ -534,24 +675,24 @@ template <int M>
 static size_t scan_lds_bytes() { return (size_t)(M * IVFR_KS + 4 * WQ_WORDS) * sizeof(float); }
 
 template <int M>
-static int launch_scan_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
+static int launch_scan_m(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* pair_len,
                          const uint32_t* blkpre, const uint32_t* unit_pairs, const ScanShape& sh, int w,
                          const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st,
                          const uint32_t* tau_id) {
-    hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(sh.groups), dim3(256), scan_lds_bytes<M>(), st, ix->codes, lut,
+    hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(sh.groups), dim3(256), scan_lds_bytes<M>(), st, ix->codes, ts,
                        pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min, w, tau, cand,
-                       cand_cnt, lay, tau_id, ix->ids);
+                       cand_cnt, lay, tau_id, reinterpret_cast<const int32_t*>(ix->rec), (uint32_t)(ix->rec_stride / 4));
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
-int ivfr_launch_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* pair_len,
+int ivfr_launch_scan(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape sh, int w, const float* tau,
                      uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st, const uint32_t* tau_id) {
     if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
 #define IVFR_SCAN_CASE(MM)                                                                                     \
     case MM:                                                                                                   \
-        return launch_scan_m<MM>(ix, lut, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, \
+        return launch_scan_m<MM>(ix, ts, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, \
                                  lay, st, tau_id)
     switch (ix->p.m) {
         IVFR_SCAN_CASE(4);
@@ -823,7 +964,7 @@ __device__ __forceinline__ void vload(float2& a, const float* v) { a = make_floa
 // Called by all 256 threads after the barrier that retires the previous unit's tables; blocks [b, stop)
 // of the unit whose first block is pb0.  wq's arrays serve as the candidate queue (entry, query mask).
 template <int M>
-__device__ __forceinline__ void half_unit_pass(const uint8_t* __restrict__ codes, const float* __restrict__ lut,
+__device__ __forceinline__ void half_unit_pass(const uint8_t* __restrict__ codes, const PairTable (&pt)[4],
                                                const float* __restrict__ lut_scale,
                                                const uint32_t* __restrict__ unit, const int64_t (&pid)[4],
                                                const float (&t)[4], uint2* const (&qc)[4], uint32_t* const (&cnt)[4],
@@ -848,7 +989,7 @@ __device__ __forceinline__ void half_unit_pass(const uint8_t* __restrict__ codes
     for (int e = tid; e < M * IVFR_KS; e += 256) {
         half4 h;
 #pragma unroll
-        for (int x = 0; x < 4; ++x) h[x] = (_Float16)(lut[pid[x] * M * IVFR_KS + e] * sc[x]);
+        for (int x = 0; x < 4; ++x) h[x] = (_Float16)(pt[x].get(e) * sc[x]);
         s_lut4[e] = h;
     }
     __syncthreads();
@@ -874,7 +1015,7 @@ __device__ __forceinline__ void half_unit_pass(const uint8_t* __restrict__ codes
                 float est = 0.f;
                 bool keep = false;
                 if (mine) {
-                    est = adc_sum<M>(lut + pid[x] * M * IVFR_KS, wd);
+                    est = adc_sum_pair<M>(pt[x], wd);
                     keep = est <= t[x];
                 }
                 const uint64_t kb = __ballot(keep);
@@ -948,7 +1089,7 @@ __device__ __forceinline__ void half_unit_pass(const uint8_t* __restrict__ codes
 
 template <int M, int G>
 __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __restrict__ codes,
-                                                              const float* __restrict__ lut,
+                                                              TableSrc ts,
                                                               const uint32_t* __restrict__ pair_start,
                                                               const uint32_t* __restrict__ pair_len,
                                                               const uint32_t* __restrict__ blkpre,
@@ -983,6 +1124,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
         const uint32_t pb0 = blkpre[u], pb1 = blkpre[u + 1];
         const uint32_t stop = pb1 < b_end ? pb1 : b_end;
         int64_t pid[G];
+        PairTable pt[G];
         float t[G];
         uint2* qc[G];
         uint32_t* cnt[G];
@@ -992,6 +1134,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
             const uint32_t raw = unit_pairs[(int64_t)u * G + x];
             const bool real = raw != IVFR_NO_PAIR;
             pid[x] = real ? (int64_t)raw : (int64_t)unit_pairs[(int64_t)u * G];   // an empty slot reads slot 0's table
+            pt[x] = ts.pair(pid[x]);
             const int q = (int)(pid[x] / w);
             t[x] = real ? tau[q] : -1.f;                                         // ... and never keeps anything
             qc[x] = cand + lay.base(q);
@@ -1011,7 +1154,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
         __syncthreads();   // previous unit's tables no longer in use
         if constexpr (G == 4) {
             if (half_unit) {
-                half_unit_pass<M>(codes, lut, lut_scale, unit_pairs + (int64_t)u * G, pid, t, qc, cnt, cap, start, len, b,
+                half_unit_pass<M>(codes, pt, lut_scale, unit_pairs + (int64_t)u * G, pid, t, qc, cnt, cap, start, len, b,
                                   stop, pb0, s_raw, wq);
                 b = stop;
                 continue;
@@ -1020,7 +1163,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
         for (int e = tid; e < M * IVFR_KS; e += 256) {
             float v[G];
 #pragma unroll
-            for (int x = 0; x < G; ++x) v[x] = lut[pid[x] * M * IVFR_KS + e];
+            for (int x = 0; x < G; ++x) v[x] = pt[x].get(e);
             vec_t packed;
             vload(packed, v);
             s_lutv[e] = packed;
@@ -1089,12 +1232,12 @@ template <int M, int G>
 static size_t shared_lds_bytes() { return (size_t)(M * IVFR_KS * G + 4 * WQ_WORDS) * sizeof(float); }
 
 template <int M, int G>
-static int launch_shared_mg(const ivfr_index* ix, const float* lut, const uint32_t* pair_start,
+static int launch_shared_mg(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs,
                             const ScanShape& sh, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
                             CandLayout lay, hipStream_t st, const float* lut_scale, const uint8_t* exact_only) {
     hipLaunchKernelGGL((adc_scan_shared_kernel<M, G>), dim3(sh.groups), dim3(256), (shared_lds_bytes<M, G>()), st,
-                       ix->codes, lut, pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min,
+                       ix->codes, ts, pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min,
                        w, tau, cand, cand_cnt, lay, lut_scale, exact_only);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
@@ -1102,13 +1245,13 @@ static int launch_shared_mg(const ivfr_index* ix, const float* lut, const uint32
 
 bool ivfr_shared_scan_supported(const ivfr_index* ix) { return ix->p.m <= 16; }
 
-int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const float* lut, const uint32_t* pair_start,
+int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const TableSrc& ts, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs,
                             ScanShape sh, int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay,
                             hipStream_t st, const float* lut_scale, const uint8_t* exact_only) {
     if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
 #define IVFR_SH_ARGS \
-    ix, lut, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st, lut_scale, exact_only
+    ix, ts, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st, lut_scale, exact_only
     if (G == 4) {
         switch (ix->p.m) {
             case 4: return launch_shared_mg<4, 4>(IVFR_SH_ARGS);
@@ -1160,7 +1303,7 @@ typedef short short8 __attribute__((ext_vector_type(8)));
 // ------------------------------------------------------------------------------------------
 template <int M, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void adc_sample_kernel(const uint8_t* __restrict__ codes,
-                                                                const float* __restrict__ lut,
+                                                                TableSrc ts,
                                                                 const uint32_t* __restrict__ pair_start,
                                                                 const uint32_t* __restrict__ len_s,
                                                                 const uint32_t* __restrict__ chunk_pre,
@@ -1179,10 +1322,10 @@ __global__ __launch_bounds__(64 * WAVES) void adc_sample_kernel(const uint8_t* _
         const uint32_t n = len_s[p];
         const uint32_t last = n - first < IVFR_SAMPLE_CHUNK ? n : first + IVFR_SAMPLE_CHUNK;   // exclusive
         {
-            const float4* src = reinterpret_cast<const float4*>(lut + (int64_t)p * M * IVFR_KS);
+            const PairTable pt = ts.pair((int64_t)p);
             float4* dst = reinterpret_cast<float4*>(T);
 #pragma unroll
-            for (int i = 0; i < M; ++i) dst[i * 64 + lane] = src[i * 64 + lane];
+            for (int i = 0; i < M; ++i) dst[i * 64 + lane] = pt.get4(4 * (i * 64 + lane));
         }
         // the wavefront's own writes are visible to its later reads, and its reads of the previous chunk's table
         // are done before these writes: LDS operations of one wavefront complete in order
@@ -1203,24 +1346,24 @@ template <int M, int WAVES>
 static size_t sample_lds_bytes() { return (size_t)WAVES * M * IVFR_KS * sizeof(float); }
 
 template <int M, int WAVES>
-static int launch_sample_m(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
+static int launch_sample_m(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* len_s,
                            const uint32_t* chunk_pre, const uint32_t* items, const uint32_t* n_items, size_t max_items,
                            const uint32_t* soff, int w, uint2* cand, CandLayout lay, hipStream_t st) {
     const size_t lds = sample_lds_bytes<M, WAVES>();
     // as many workgroups as fit the compute units' LDS twice over, or one wavefront per chunk when there are fewer
     const size_t per_cu = std::max<size_t>(1, (size_t)(160 * 1024) / lds);
     const size_t grid = std::max<size_t>(1, std::min((max_items + WAVES - 1) / WAVES, (size_t)ix->n_cu * per_cu * 2));
-    hipLaunchKernelGGL((adc_sample_kernel<M, WAVES>), dim3((unsigned)grid), dim3(64 * WAVES), lds, st, ix->codes, lut,
+    hipLaunchKernelGGL((adc_sample_kernel<M, WAVES>), dim3((unsigned)grid), dim3(64 * WAVES), lds, st, ix->codes, ts,
                        pair_start, len_s, chunk_pre, items, n_items, soff, w, cand, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
-int ivfr_launch_sample_scan(const ivfr_index* ix, const float* lut, const uint32_t* pair_start, const uint32_t* len_s,
+int ivfr_launch_sample_scan(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* len_s,
                             const uint32_t* chunk_pre, const uint32_t* items, const uint32_t* n_items, size_t max_items,
                             const uint32_t* soff, int w, uint2* cand, CandLayout lay, hipStream_t st) {
     if (max_items == 0) return IVFR_OK;
-#define IVFR_SAMPLE_ARGS ix, lut, pair_start, len_s, chunk_pre, items, n_items, max_items, soff, w, cand, lay, st
+#define IVFR_SAMPLE_ARGS ix, ts, pair_start, len_s, chunk_pre, items, n_items, max_items, soff, w, cand, lay, st
     switch (ix->p.m) {
         case 4: return launch_sample_m<4, 4>(IVFR_SAMPLE_ARGS);
         case 8: return launch_sample_m<8, 4>(IVFR_SAMPLE_ARGS);
@@ -1248,7 +1391,7 @@ __device__ __forceinline__ uint32_t sign_free_mask(uint4 u) {
 
 template <int M>
 __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* __restrict__ codes,
-                                                                const float* __restrict__ lut,
+                                                                TableSrc ts,
                                                                 const float* __restrict__ lut_scale,
                                                                 const uint32_t* __restrict__ pair_start,
                                                                 const uint32_t* __restrict__ pair_len,
@@ -1312,7 +1455,7 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
                 if (mask) {
                     x = __ffs(mask) - 1;
                     mask &= mask - 1;
-                    est = adc_sum<M>(lut + (int64_t)s_pid[x] * M * IVFR_KS, wd);
+                    est = adc_sum_pair<M>(ts.pair((int64_t)s_pid[x]), wd);
                     keep = est <= s_tau[x];
                 }
                 uint64_t todo = __ballot(keep);
@@ -1339,17 +1482,19 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
         const uint32_t pb0 = blkpre[u], pb1 = blkpre[u + 1];
         const uint32_t stop = pb1 < b_end ? pb1 : b_end;
         int64_t pid[8];
-        float t[8], ts[8], sc[8];
+        PairTable pt[8];
+        float t[8], tsc[8], sc[8];
         half8 tsh;   // the thresholds in half precision, rounded up (bit pattern 0xFFFF for an empty slot)
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
             const uint32_t raw = unit_pairs[(int64_t)u * 8 + x];
             const bool real = raw != IVFR_NO_PAIR;
             pid[x] = real ? (int64_t)raw : (int64_t)unit_pairs[(int64_t)u * 8];
+            pt[x] = ts.pair(pid[x]);
             sc[x] = lut_scale[pid[x]];
             t[x] = real ? tau[(int)(pid[x] / w)] : -1.f;
-            ts[x] = real ? t[x] * sc[x] * (1.f + (M + 1.2f) * 4.8828125e-4f) + 4e-3f : -1.f;
-            tsh[x] = (_Float16)(real ? ts[x] * 1.001f + 1e-4f : 0.f);   // 2^-10 > the 2^-11 of the conversion
+            tsc[x] = real ? t[x] * sc[x] * (1.f + (M + 1.2f) * 4.8828125e-4f) + 4e-3f : -1.f;
+            tsh[x] = (_Float16)(real ? tsc[x] * 1.001f + 1e-4f : 0.f);   // 2^-10 > the 2^-11 of the conversion
         }
         short8 tshi = __builtin_bit_cast(short8, tsh);
 #pragma unroll
@@ -1366,7 +1511,7 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
         for (int e = tid; e < M * IVFR_KS; e += H8_T) {   // e = j * 256 + byte; stored at [byte][j]
             half8 h;
 #pragma unroll
-            for (int x = 0; x < 8; ++x) h[x] = (_Float16)(lut[pid[x] * M * IVFR_KS + e] * sc[x]);
+            for (int x = 0; x < 8; ++x) h[x] = (_Float16)(pt[x].get(e) * sc[x]);
             s_lut8[(e & (IVFR_KS - 1)) * M + (e >> 8)] = h;
         }
         __syncthreads();
@@ -1435,12 +1580,12 @@ static size_t shared8h_lds_bytes() {
 }
 
 template <int M>
-static int launch_shared8h_m(const ivfr_index* ix, const float* lut, const float* lut_scale,
+static int launch_shared8h_m(const ivfr_index* ix, const TableSrc& ts, const float* lut_scale,
                              const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
                              const uint32_t* unit_pairs, const ScanShape& sh, int w, const float* tau, uint2* cand,
                              uint32_t* cand_cnt, CandLayout lay, hipStream_t st) {
     hipLaunchKernelGGL(adc_scan_shared8h_kernel<M>, dim3(sh.groups), dim3(H8_T), shared8h_lds_bytes<M>(), st, ix->codes,
-                       lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min,
+                       ts, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min,
                        w, tau, cand, cand_cnt, lay);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
@@ -1448,15 +1593,15 @@ static int launch_shared8h_m(const ivfr_index* ix, const float* lut, const float
 
 bool ivfr_shared8h_supported(const ivfr_index* ix) { return ix->p.m <= 16; }
 
-int ivfr_launch_scan_shared8h(const ivfr_index* ix, const float* lut, const float* lut_scale,
+int ivfr_launch_scan_shared8h(const ivfr_index* ix, const TableSrc& ts, const float* lut_scale,
                               const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
                               const uint32_t* unit_pairs, ScanShape sh, int w, const float* tau, uint2* cand,
                               uint32_t* cand_cnt, CandLayout lay, hipStream_t st) {
     if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
     switch (ix->p.m) {
-        case 4: return launch_shared8h_m<4>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st);
-        case 8: return launch_shared8h_m<8>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st);
-        case 16: return launch_shared8h_m<16>(ix, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st);
+        case 4: return launch_shared8h_m<4>(ix, ts, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st);
+        case 8: return launch_shared8h_m<8>(ix, ts, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st);
+        case 16: return launch_shared8h_m<16>(ix, ts, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st);
         default:
             ivfr_set_error("half-precision shared scan supports m <= 16; got %d", ix->p.m);
             return IVFR_ERR_INVALID_ARG;
@@ -1495,7 +1640,7 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
                                                               const float* __restrict__ pq,
                                                               const float* __restrict__ pq_norm,
                                                               const float* __restrict__ pq_maxnorm,
-                                                              const float* __restrict__ lut,
+                                                              TableSrc ts,
                                                               const float* __restrict__ lut_scale,
                                                               const uint32_t* __restrict__ pair_start,
                                                               const uint32_t* __restrict__ pair_len,
@@ -1579,7 +1724,7 @@ __global__ __launch_bounds__(MF_T) void adc_scan_mfma64_kernel(const uint8_t* __
                     const int x = __ffs(mask) - 1;
                     mask &= mask - 1;
                     r64 = (x >> 4) * 32 + 8 * ((x & 15) >> 2) + 4 * (int)hh + (x & 3);
-                    est = adc_sum<M>(lut + (int64_t)s_pid[r64] * M * IVFR_KS, wd);
+                    est = adc_sum_pair<M>(ts.pair((int64_t)s_pid[r64]), wd);
                     keep = est <= s_tau[r64];
                 }
                 uint64_t todo = __ballot(keep);
@@ -1772,12 +1917,12 @@ static size_t mfma64_lds_bytes() {
 }
 
 template <int M, int DSUB>
-static int launch_mfma64_md(const ivfr_index* ix, const float* queries, const int32_t* probe, const float* lut,
+static int launch_mfma64_md(const ivfr_index* ix, const float* queries, const int32_t* probe, const TableSrc& ts,
                             const float* lut_scale, const uint32_t* pair_start, const uint32_t* pair_len,
                             const uint32_t* blkpre, const uint32_t* unit_pairs, const ScanShape& sh, int w,
                             const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st) {
     hipLaunchKernelGGL((adc_scan_mfma64_kernel<M, DSUB>), dim3(sh.groups), dim3(MF_T), (mfma64_lds_bytes<M, DSUB>()), st,
-                       ix->codes, queries, probe, ix->coarse, ix->pq, ix->pq_norm, ix->pq_maxnorm, lut, lut_scale,
+                       ix->codes, queries, probe, ix->coarse, ix->pq, ix->pq_norm, ix->pq_maxnorm, ts, lut_scale,
                        pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min, w, tau, cand,
                        cand_cnt, lay);
     IVFR_HIP(hipGetLastError());
@@ -1790,12 +1935,12 @@ bool ivfr_mfma_scan_supported(const ivfr_index* ix) {
     return (m == 4 || m == 8 || m == 16) && (ds == 8 || ds == 16 || ds == 32) && m * ds <= 128;
 }
 
-int ivfr_launch_scan_mfma64(const ivfr_index* ix, const float* queries, const int32_t* probe, const float* lut,
+int ivfr_launch_scan_mfma64(const ivfr_index* ix, const float* queries, const int32_t* probe, const TableSrc& ts,
                             const float* lut_scale, const uint32_t* pair_start, const uint32_t* pair_len,
                             const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape sh, int w, const float* tau,
                             uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st) {
     if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
-#define IVFR_MF_ARGS ix, queries, probe, lut, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st
+#define IVFR_MF_ARGS ix, queries, probe, ts, lut_scale, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st
     const int key = ix->p.m * 100 + ix->dsub;
     switch (key) {
         case 408: return launch_mfma64_md<4, 8>(IVFR_MF_ARGS);

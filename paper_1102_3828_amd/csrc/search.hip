@@ -81,12 +81,12 @@ struct Carver {
 // Byte offsets of one batch's arrays inside the search workspace.
 struct SearchLayout {
     size_t xnorm, ckeys, probe, probed, pstart, len, pre, lens, pres, items, soff, nsample, qblk, sq, fully, exonly,
-        capq, coff, lut, tau, tauid, spos, sest, sn, over, rkeys, sref, sids, lscale, gpre, gcur, gu8, gu2, glop, gblk8,
+        capq, coff, lut, pbase, tau, tauid, spos, sest, sn, over, rkeys, sref, sids, lscale, gpre, gcur, gu8, gu2, glop, gblk8,
         gblk4, gblk2, gblklo, gu64, gblk64, status, cnt, gnp;
     size_t n_items_max, n_u8, n_u4, zero_words, bytes;
 };
 
-static SearchLayout layout_search(const ivfr_params& p, int B, int w, int kprime) {
+static SearchLayout layout_search(const ivfr_params& p, int B, int w, int kprime, bool split) {
     SearchLayout L;
     const size_t P = (size_t)B * w, c = (size_t)p.c;
     Carver cv;
@@ -110,7 +110,9 @@ static SearchLayout layout_search(const ivfr_params& p, int B, int w, int kprime
     L.exonly = cv.take<uint8_t>(B);
     L.capq = cv.take<uint32_t>(B);
     L.coff = cv.take<unsigned long long>(B);
-    L.lut = cv.take<float>(P * p.m * IVFR_KS);
+    // look-up tables: one per (query, list) pair, or with split tables one term table per query and m scalars per pair
+    L.lut = cv.take<float>((split ? (size_t)B : P) * p.m * IVFR_KS);
+    L.pbase = cv.take<float>(split ? P * p.m : 1);
     L.tau = cv.take<float>(B);
     L.tauid = cv.take<uint32_t>(B);
     L.spos = cv.take<uint32_t>((size_t)B * kprime);
@@ -151,7 +153,7 @@ static int64_t batch_size(const ivfr_index* ix, int64_t nq, int w, int kprime) {
     const ivfr_params& p = ix->p;
     int64_t B = std::min<int64_t>(nq, ix->batch);
     const int64_t budget = 4ll << 30;
-    B = std::min<int64_t>(B, std::max<int64_t>(1, 2 * budget / ((int64_t)w * p.m * IVFR_KS * 4)));
+    if (!ix->split_tables) B = std::min<int64_t>(B, std::max<int64_t>(1, 2 * budget / ((int64_t)w * p.m * IVFR_KS * 4)));
     B = std::min<int64_t>(B, std::max<int64_t>(1, budget / ((int64_t)kprime * 24)));
     B = std::min<int64_t>(B, std::max<int64_t>(1, budget / ((int64_t)p.c * 8)));
     return std::max<int64_t>(B, 1);
@@ -187,7 +189,7 @@ extern "C" int ivfr_memory_required(const ivfr_params* params, int64_t N, int64_
         const int64_t B0 = batch_size(&tmp, nq, w, kprime);
         const int64_t nb = (nq + B0 - 1) / B0;
         const int B = (int)((nq + nb - 1) / nb);
-        sb = (int64_t)layout_search(p, B, w, kprime).bytes;
+        sb = (int64_t)layout_search(p, B, w, kprime, false).bytes;
         const double per_query = (double)w * ((double)N / (double)p.c);
         sb += (int64_t)(pool_estimate(&tmp, B, w, kprime, per_query) * sizeof(uint2));
     }
@@ -240,7 +242,16 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
         return (nq + n_batches - 1) / n_batches;
     };
     B64 = even_batches(B64);
-    SearchLayout L = layout_search(p, (int)B64, w, kprime);
+    const bool split = ix->split_tables != 0;
+    if (split) {
+        if (fixed_ws && !ix->list_term) {
+            ivfr_set_error("split tables: the per-list table is built by the first ivfr_search call in this mode; "
+                           "the fixed-workspace entry point cannot allocate it");
+            return IVFR_ERR_STATE;
+        }
+        IVFR_TRY(ivfr_ensure_list_terms(ix, reinterpret_cast<hipStream_t>(stream)));
+    }
+    SearchLayout L = layout_search(p, (int)B64, w, kprime, split);
     unsigned long long pool_cap = 0;
     if (fixed) {
         // the largest batch whose arrays and expected candidate pool (with a quarter in reserve) fit the buffer
@@ -254,7 +265,7 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
                 return IVFR_ERR_OOM;
             }
             B64 = even_batches((B64 + 1) / 2);
-            L = layout_search(p, (int)B64, w, kprime);
+            L = layout_search(p, (int)B64, w, kprime, split);
         }
         pool_cap = (fixed_bytes - L.bytes) / sizeof(uint2) - 64;
     }
@@ -307,6 +318,17 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
     pb.capq = reinterpret_cast<uint32_t*>(ws + L.capq);
     pb.coff = reinterpret_cast<unsigned long long*>(ws + L.coff);
     float* lut = reinterpret_cast<float*>(ws + L.lut);
+    float* pbase = reinterpret_cast<float*>(ws + L.pbase);
+    TableSrc tsrc;
+    tsrc.lut = lut;
+    tsrc.w = w;
+    tsrc.m = m;
+    tsrc.table_words = m * IVFR_KS;
+    if (split) {
+        tsrc.list_term = ix->list_term;
+        tsrc.pbase = pbase;
+        tsrc.probe = probe;
+    }
     CandLayout lay;
     lay.off = pb.coff;
     lay.capq = pb.capq;
@@ -342,7 +364,8 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
     const float half_frac = IVFR_HALF_UNIT_FRAC;
     const bool share = ix->share_lists >= 1 && ivfr_shared_scan_supported(ix);
     const bool share8 = share && ix->share_lists >= 2 && ivfr_shared8h_supported(ix);
-    const bool share64 = share8 && ix->share_lists >= 3 && ivfr_mfma_scan_supported(ix);
+    // the matrix-core filter's error margin is derived for materialised tables: with split tables mode 3 acts as mode 2
+    const bool share64 = share8 && ix->share_lists >= 3 && ivfr_mfma_scan_supported(ix) && !split;
 
     // Launch shapes.  Every workgroup of a scan takes an equal share of the launch's 512-entry blocks; about 128
     // blocks per group of 256 threads (256 for the 512-thread scan of eight, 64 for the narrower kernels) balances
@@ -440,18 +463,19 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
         if (share) IVFR_TRY(ivfr_launch_group_plan(probe, Pb, w, c, pb.exact_only, share8, share64, pb.len, gb, st));
         IVFR_TRY(mark(IVFR_STAGE_PROBE, false));
         IVFR_TRY(mark(IVFR_STAGE_LUT, true));
-        IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, lut_scale, st));
+        if (split) IVFR_TRY(ivfr_launch_query_terms(ix, X, probe, nb, w, lut, pbase, lut_scale, st));
+        else IVFR_TRY(ivfr_launch_lut(ix, X, probe, nb, w, lut, lut_scale, st));
         IVFR_TRY(mark(IVFR_STAGE_LUT, false));
         // uniform sample of the visited entries -> bound tau on the k'-th smallest estimate (a query without a
         // sample keeps tau = +inf)
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, true));
         {
             const size_t max_items = (size_t)Pb + (size_t)nb * ((IVFR_MAX_SAMPLE + (size_t)w) / IVFR_SAMPLE_CHUNK + 1);
-            IVFR_TRY(ivfr_launch_sample_scan(ix, lut, pb.pair_start, pb.len_s, pb.blkpre_s, pb.items_s,
+            IVFR_TRY(ivfr_launch_sample_scan(ix, tsrc, pb.pair_start, pb.len_s, pb.blkpre_s, pb.items_s,
                                              &dstat->n_sample_chunks, max_items, pb.soff, w, cand, lay, st));
             // the sample of query q is nsample[q] bare estimates at the start of its buffer
             SelectArgs a;
-            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = pb.nsample; a.lay = lay;
+            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = reinterpret_cast<const int32_t*>(ix->rec); a.id_stride = (uint32_t)(ix->rec_stride / 4); a.counts = pb.nsample; a.lay = lay;
             IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, 0, pb.fully, tau, nullptr, st, true));
         }
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
@@ -477,27 +501,27 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             for (int i = 0; i < n_side; ++i) IVFR_HIP(hipStreamWaitEvent(ix->side[i], ix->ev_fork[slot], 0));
             if (share64) {
                 IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED64, true, ix->side[3]));
-                IVFR_TRY(ivfr_launch_scan_mfma64(ix, X, probe, lut, lut_scale, pb.pair_start, pb.len, gb.blk64,
+                IVFR_TRY(ivfr_launch_scan_mfma64(ix, X, probe, tsrc, lut_scale, pb.pair_start, pb.len, gb.blk64,
                                                  gb.unit64_pairs, s64, w, tau, cand, cnt, lay, ix->side[3]));
                 IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED64, false, ix->side[3]));
             }
             if (share8) {
                 IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED8, true));
-                IVFR_TRY(ivfr_launch_scan_shared8h(ix, lut, lut_scale, pb.pair_start, pb.len, gb.blk8, gb.unit8_pairs, s8,
+                IVFR_TRY(ivfr_launch_scan_shared8h(ix, tsrc, lut_scale, pb.pair_start, pb.len, gb.blk8, gb.unit8_pairs, s8,
                                                    w, tau, cand, cnt, lay, st));
                 IVFR_TRY(mark(IVFR_STAGE_SCAN_SHARED8, false));
             }
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED, true, ix->side[0]));
-            IVFR_TRY(ivfr_launch_scan_shared(ix, 4, lut, pb.pair_start, pb.len, gb.blk4, gb.unit4_pairs, s4, w,
+            IVFR_TRY(ivfr_launch_scan_shared(ix, 4, tsrc, pb.pair_start, pb.len, gb.blk4, gb.unit4_pairs, s4, w,
                                              tau, cand, cnt, lay, ix->side[0], share8 ? lut_scale : nullptr,
                                              share8 ? pb.exact_only : nullptr));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED, false, ix->side[0]));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED2, true, ix->side[1]));
-            IVFR_TRY(ivfr_launch_scan_shared(ix, 2, lut, pb.pair_start, pb.len, gb.blk2, gb.unit2_pairs, s2, w,
+            IVFR_TRY(ivfr_launch_scan_shared(ix, 2, tsrc, pb.pair_start, pb.len, gb.blk2, gb.unit2_pairs, s2, w,
                                              tau, cand, cnt, lay, ix->side[1]));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED2, false, ix->side[1]));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN, true, ix->side[2]));
-            IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, gb.blklo, gb.lo_pairs, s1, w, tau, cand, cnt,
+            IVFR_TRY(ivfr_launch_scan(ix, tsrc, pb.pair_start, pb.len, gb.blklo, gb.lo_pairs, s1, w, tau, cand, cnt,
                                       lay, ix->side[2]));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN, false, ix->side[2]));
             for (int i = 0; i < n_side; ++i) {
@@ -507,13 +531,13 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
         } else {
             const ScanShape s1 = shape_for(est_codes / IVFR_BLOCK + Pb, 64, nullptr, Pb);
             IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
-            IVFR_TRY(ivfr_launch_scan(ix, lut, pb.pair_start, pb.len, pb.blkpre, nullptr, s1, w, tau, cand, cnt, lay, st));
+            IVFR_TRY(ivfr_launch_scan(ix, tsrc, pb.pair_start, pb.len, pb.blkpre, nullptr, s1, w, tau, cand, cnt, lay, st));
             IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
         }
         IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, true));
         {
             SelectArgs a;
-            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = cnt; a.lay = lay;
+            a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = reinterpret_cast<const int32_t*>(ix->rec); a.id_stride = (uint32_t)(ix->rec_stride / 4); a.counts = cnt; a.lay = lay;
             IVFR_TRY(ivfr_launch_select_records(a, 0, pb.sq, spos, sest, sn, over, overtot, st));
         }
         IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, false));
@@ -546,7 +570,7 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
                 g = g < (double)g_lo ? (double)g_lo : (g > 32768.0 ? 32768.0 : g);
                 sq_shape.groups = ((int)g + 7) & ~7;
             }
-            const float* q_lut = lut + (size_t)q * w * m * IVFR_KS;
+            const TableSrc q_lut = tsrc.slice((int64_t)q * w);
             const uint32_t* q_start = pb.pair_start + (size_t)q * w;
             const uint32_t* q_len = pb.len + (size_t)q * w;
             const uint32_t* q_pre = pb.blkpre + (size_t)q * w;   // w + 1 values of the batch-wide block prefix
@@ -565,7 +589,7 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             for (int tries = 0; tries < 8 && h_cnt > h_cap && h_cap >= (uint32_t)kprime; ++tries) {
                 ix->st_retries += 1;
                 SelectArgs a;
-                a.nseg = 1; a.K = kprime; a.recs = cand; a.ids = ix->ids; a.counts = cnt + q; a.lay = qlay;
+                a.nseg = 1; a.K = kprime; a.recs = cand; a.ids = reinterpret_cast<const int32_t*>(ix->rec); a.id_stride = (uint32_t)(ix->rec_stride / 4); a.counts = cnt + q; a.lay = qlay;
                 IVFR_TRY(ivfr_launch_select_tau(a, pb.sq + q, kprime, kprime, nullptr, tau + q, tau_id + q, st));
                 hipLaunchKernelGGL(clear_u32_kernel, dim3(1), dim3(64), 0, st, cnt + q);
                 IVFR_TRY(ivfr_launch_scan(ix, q_lut, q_start, q_len, q_pre, nullptr, sq_shape, w, tau + q, cand, cnt + q,
@@ -606,7 +630,7 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             dlay.ucap = (uint32_t)(sqv + 1);
             IVFR_TRY(ivfr_launch_scan(ix, q_lut, q_start, q_len, q_pre, nullptr, sq_shape, w, dtau, dcand, dcnt, dlay, st));
             SelectArgs a;
-            a.nseg = 1; a.K = kprime; a.recs = dcand; a.ids = ix->ids; a.counts = dcnt; a.lay = dlay;
+            a.nseg = 1; a.K = kprime; a.recs = dcand; a.ids = reinterpret_cast<const int32_t*>(ix->rec); a.id_stride = (uint32_t)(ix->rec_stride / 4); a.counts = dcnt; a.lay = dlay;
             IVFR_TRY(ivfr_launch_select_records(a, q, nullptr, spos, sest, sn, nullptr, nullptr, st));
         }
         IVFR_TRY(finish(q0, nb));

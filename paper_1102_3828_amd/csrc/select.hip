@@ -27,6 +27,7 @@ struct SegView {
     int64_t base;
     int64_t n;
     const uint32_t* vals = nullptr;   // source C: bare distance words; the element index is the low half of the key
+    uint32_t id_stride = 1;           // ids[pos * id_stride] is the id of the entry at position pos
 };
 
 __device__ __forceinline__ uint32_t seg_hi(const SegView& s, int64_t i, uint32_t* pos) {
@@ -45,7 +46,7 @@ __device__ __forceinline__ uint32_t seg_hi(const SegView& s, int64_t i, uint32_t
 }
 
 __device__ __forceinline__ uint32_t seg_lo(const SegView& s, uint32_t pos) {
-    return (s.keys || s.vals) ? pos : (uint32_t)s.ids[pos];
+    return (s.keys || s.vals) ? pos : (uint32_t)s.ids[(size_t)pos * s.id_stride];
 }
 
 // Returns the K-th smallest key of the segment (1 <= K <= n).  All threads must call.
@@ -218,8 +219,8 @@ __device__ __forceinline__ int64_t seg_count(const uint32_t* counts, uint32_t ca
 // best are in it (Poisson-like).  Taking the r-th smallest sampled estimate with r = mu + 5
 // sqrt(mu) + 6 makes it all but certain (beyond five standard deviations) that at least k'
 // visited entries lie at or below it; the filtered scan verifies that by counting.
-__global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, const int32_t* ids, CandLayout lay,
-                                                           const uint32_t* counts,
+__global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, const int32_t* ids, uint32_t id_stride,
+                                                           CandLayout lay, const uint32_t* counts,
                                                            const unsigned long long* sq, int kprime,
                                                            int fixed_rank, const uint8_t* skip, float* tau,
                                                            uint32_t* tau_id, int values_only) {
@@ -238,6 +239,7 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
         return;
     }
     SegView s{nullptr, recs, ids, (int64_t)lay.base(seg), n};
+    s.id_stride = id_stride;
     if (values_only) {   // the segment holds n bare estimates (4 bytes each) at the start of its record buffer
         s.recs = nullptr;
         s.vals = reinterpret_cast<const uint32_t*>(recs);
@@ -253,7 +255,7 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
 int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, int fixed_rank,
                            const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st, bool values_only) {
     if (a.nseg <= 0) return IVFR_OK;
-    hipLaunchKernelGGL(select_tau_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.lay, a.counts, sq,
+    hipLaunchKernelGGL(select_tau_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.id_stride, a.lay, a.counts, sq,
                        kprime, fixed_rank, skip, tau, tau_id, values_only ? 1 : 0);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
@@ -261,6 +263,7 @@ int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, in
 
 // ---- unordered compaction of the K smallest records -----------------------------------------
 __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs, const int32_t* ids,
+                                                               uint32_t id_stride,
                                                                CandLayout lay, const uint32_t* counts, int K,
                                                                int out_base,
                                                                const unsigned long long* sq, uint32_t* out_pos,
@@ -284,6 +287,7 @@ __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs
         return;
     }
     SegView s{nullptr, recs, ids, (int64_t)lay.base(seg), n};
+    s.id_stride = id_stride;
     uint32_t* op = out_pos + (int64_t)q * K;
     float* oe = out_est + (int64_t)q * K;
     if (n <= K) {
@@ -299,7 +303,7 @@ __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs
     const uint32_t p_hi = (uint32_t)(pivot >> 32), p_lo = (uint32_t)pivot;
     for (int64_t i = threadIdx.x; i < n; i += SEL_T) {
         uint2 r = recs[s.base + i];
-        bool take = r.x < p_hi || (r.x == p_hi && (uint32_t)ids[r.y] <= p_lo);
+        bool take = r.x < p_hi || (r.x == p_hi && (uint32_t)ids[(size_t)r.y * id_stride] <= p_lo);
         if (take) {
             uint32_t slot = atomicAdd(&s_slot, 1u);
             if (slot < (uint32_t)K) { op[slot] = r.y; oe[slot] = __uint_as_float(r.x); }
@@ -312,7 +316,7 @@ int ivfr_launch_select_records(const SelectArgs& a, int out_base, const unsigned
                                float* out_est, int32_t* out_n, int32_t* overflow, int32_t* overflow_total,
                                hipStream_t st) {
     if (a.nseg <= 0) return IVFR_OK;
-    hipLaunchKernelGGL(select_records_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.lay, a.counts, a.K,
+    hipLaunchKernelGGL(select_records_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.id_stride, a.lay, a.counts, a.K,
                        out_base, sq, out_pos, out_est, out_n, overflow, overflow_total);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;

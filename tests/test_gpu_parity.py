@@ -51,12 +51,15 @@ def test_hip_generator_matches_numpy():
 
 # ------------------------------------------------------------------ stage-level parity
 
+@pytest.mark.parametrize("table_mode", [0, 1])
 @pytest.mark.parametrize("kw", [dict(), dict(m_refine=0), dict(d=64, m=8, m_refine=16, c=24, N=5000, n_train=3000)])
-def test_stages_against_oracle_trace(kw):
-    """Visited lists, short-list (ids, ADC estimates) and refined distances of every query."""
+def test_stages_against_oracle_trace(kw, table_mode):
+    """Visited lists, short-list (ids, ADC estimates) and refined distances of every query; with one look-up table
+    per pair and with split tables (per-list and per-query terms summed in the scan)."""
     wl = tiny_workload(**kw)
     index, X = wl["index"], wl["X"]
     ix = gpu_index_from_oracle(index)
+    ix.set_table_mode(table_mode)
     c = len(index.books.coarse)
     for w, kp, k in ((3, 50, 10), (c, 200, 20), (1, 10 ** 4, 5), (2, 7, 7)):
         log("stages", kw, w, kp, k)
@@ -93,13 +96,15 @@ def test_stages_against_oracle_trace(kw):
     ix.close()
 
 
+@pytest.mark.parametrize("table_mode", [0, 1])
 @pytest.mark.parametrize("m,m_refine", [(4, 0), (4, 64), (16, 8), (32, 32), (64, 4)])
-def test_other_code_sizes(m, m_refine):
+def test_other_code_sizes(m, m_refine, table_mode):
     """Code sizes other than the workloads' m = 8 (the paper's Table 2 varies m and m'): every
     sub-vector width from 16 down to 1 dimension, with and without list sharing."""
     wl = tiny_workload(d=64, G=16, N=4000, n_train=2500, n_query=16, c=12, m=m, m_refine=m_refine, iters=3)
     index, X = wl["index"], wl["X"]
     ix = gpu_index_from_oracle(index)
+    ix.set_table_mode(table_mode)
     xq = queries_dev(X)
     for share in (2, 1, 0):
         ix.set_list_sharing(share)
@@ -226,6 +231,11 @@ def test_config0_end_to_end_gpu_built_index():
     assert r10 > 0.5
     st = ix.search_stats()
     assert st["pairs"] == cfg.n_query * cfg.w and st["dense_fallbacks"] == 0
+    ix.set_table_mode(1)
+    t_ids, t_dist = ix.search(queries_dev(X), cfg.w, cfg.kprime, cfg.k)
+    exact, excused = compare_results(t_ids.cpu().numpy(), t_dist.cpu().numpy(), X, index, cfg.w, cfg.kprime, cfg.k)
+    log("split tables: exact", exact, "excused", excused)
+    assert exact >= 0.99 * cfg.n_query * cfg.k
     ix.close()
 
 
@@ -299,17 +309,31 @@ def _full_size_case(name, n_check, also=(), **override):
             ix.set_list_sharing(2)
             ix.set_tuning(batch=B)
             del qa
-        results.append((s, gi, gd))
+        results.append((s, gi, gd, 0))
+        # split look-up tables (per-list and per-query terms summed in the scan's prologue): per-pair and shared scans
+        # must agree bit for bit with one another; the oracle comparison below covers the different rounding
+        ix.set_table_mode(1)
+        t_ids, t_dist = ix.search(xq, cfg.w, kp, k)
+        log(name, "split tables", ix.search_stats(), ix.workspace_info())
+        ti, td = t_ids.cpu().numpy(), t_dist.cpu().numpy()
+        ix.set_list_sharing(0)
+        p_ids, p_dist = ix.search(xq, cfg.w, kp, k)
+        assert np.array_equal(p_ids.cpu().numpy(), ti) and np.array_equal(p_dist.cpu().numpy(), td)
+        ix.set_list_sharing(2)
+        ix.set_table_mode(0)
+        log(name, "split tables: ids identical to materialised tables", float((ti == gi).mean()))
+        assert (ti == gi).mean() > 0.98
+        results.append((dict(s, n_check=max(2, s["n_check"] // 2)), ti, td, 1))
     log(name, "export")
     coarse, pq, rq = ix.get_codebooks()
     offsets, ids, codes, rcodes = ix.export()
     ix.close()
     index = orc.Index(orc.Codebooks(coarse, pq, rq), offsets, ids, codes, rcodes)
     assert index.bytes_per_vector() == cfg.m + cfg.m_refine + 4
-    for s, gi, gd in results:
+    for s, gi, gd, table_mode in results:
         n = s["n_check"]
         X = q_u8[:n].cpu().numpy()
-        log(name, "oracle on", n, "queries, k' =", s["kprime"])
+        log(name, "oracle on", n, "queries, k' =", s["kprime"], "table mode", table_mode)
         exact, excused = compare_results(gi[:n], gd[:n], X, index, cfg.w, s["kprime"], s["k"])
         log(name, "exact", exact, "excused", excused)
         assert exact >= 0.98 * n * s["k"]
@@ -485,14 +509,16 @@ def test_edge_cases_and_internal_paths():
     ix.close()
 
 
+@pytest.mark.parametrize("table_mode", [0, 1])
 @pytest.mark.parametrize("m", [8, 16, 4])
-def test_list_sharing_modes_give_identical_bits(m):
+def test_list_sharing_modes_give_identical_bits(m, table_mode):
     """Many queries on few lists: units of eight (half-precision tables + exact re-evaluation), of
     four and of two (fp32 tables) and single pairs must all record the same fp32 estimates, so the
     three sharing modes return identical bits; the trace is checked against the oracle as well."""
     wl = tiny_workload(d=32, G=16, N=600000, n_train=3000, n_query=75, c=4, m=m, m_refine=16, iters=4)
     index, X = wl["index"], wl["X"]
     ix = gpu_index_from_oracle(index)
+    ix.set_table_mode(table_mode)
     xq = queries_dev(X)
     # sampled bound + filter, as the large workloads run; k' is small against the ~300000 visited entries, so
     # the bound passes well under 1 % of the estimates and the half-precision units are used
@@ -795,8 +821,9 @@ def _random_case(seed):
     return dict(d=d, m=m, mr=mr, c=c, N=N, w=w, kp=kp, k=k, nq=nq)
 
 
+@pytest.mark.parametrize("table_mode", [0, 1])
 @pytest.mark.parametrize("seed", range(40))
-def test_random_shapes(seed):
+def test_random_shapes(seed, table_mode):
     """Seeded random shapes: odd dimensions and code sizes, more lists than vectors, k' above and below what is
     visited, every list-sharing mode and both the filtered and the keep-everything paths."""
     cs = _random_case(seed)
@@ -810,6 +837,7 @@ def test_random_shapes(seed):
     index = orc.build_index(Y, np.arange(cs["N"]), books)
     X = np.clip(rng.normal(128, 35, size=(cs["nq"], d)), 0, 255).astype(np.float32)
     ix = gpu_index_from_oracle(index)
+    ix.set_table_mode(table_mode)
     xq = queries_dev(X)
     for mode, full_mult in ((2, 8), (1, 1), (0, 1)):
         ix.set_list_sharing(mode)
@@ -842,8 +870,9 @@ def _crowded_case(seed):
     return dict(d=d, m=m, mr=mr, c=c, N=N, w=w, kp=kp, k=k, nq=nq, scale=scale)
 
 
+@pytest.mark.parametrize("table_mode", [0, 1])
 @pytest.mark.parametrize("seed", range(16))
-def test_random_shapes_with_crowded_lists(seed):
+def test_random_shapes_with_crowded_lists(seed, table_mode):
     """Seeded random shapes with 70-400 queries on one to five lists and codebooks / queries scaled by 0.001, 1
     or 50: units of 64, eight, four and two all occur.  Every sharing mode must return the bits of the per-pair
     scan; a few queries are checked against the oracle."""
@@ -858,6 +887,7 @@ def test_random_shapes_with_crowded_lists(seed):
     index = orc.build_index(Y, np.arange(cs["N"]), books)
     X = (np.clip(rng.normal(128, 35, size=(cs["nq"], d)), 0, 255) * sc).astype(np.float32)
     ix = gpu_index_from_oracle(index)
+    ix.set_table_mode(table_mode)
     xq = queries_dev(X)
     outs = {}
     for mode in (0, 3, 2, 1):
