@@ -101,7 +101,7 @@ extern "C" int ivfr_create(const ivfr_params* params, ivfr_index** out) {
     if (r == IVFR_OK) {
         hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&ix->h_slots), IVFR_STATUS_SLOTS * sizeof(DevStatus),
                                      hipHostMallocDefault);
-        if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ix->h_redo), 8 * sizeof(uint32_t), hipHostMallocDefault);
+        if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ix->h_redo), (16 + IVFR_REDO_CHUNK) * sizeof(uint32_t), hipHostMallocDefault);
         if (e != hipSuccess) { ivfr_set_error("pinned host allocation failed"); r = IVFR_ERR_OOM; }
         else memset(ix->h_slots, 0, IVFR_STATUS_SLOTS * sizeof(DevStatus));
     }

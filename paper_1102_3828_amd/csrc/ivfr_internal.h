@@ -81,6 +81,7 @@ struct DevStatus {
     uint32_t counts[8];             // units of eight, four, two, single pairs, units of 64
 };
 #define IVFR_STATUS_SLOTS 16        // batches of one call in flight between two host waits
+#define IVFR_REDO_CHUNK 4096        // failed-check flags read back per copy by the redo path
 
 // One staged (encoded, not yet list-sorted) batch of database vectors.
 struct StagedChunk {
@@ -138,7 +139,7 @@ struct ivfr_index {
     // scratch
     DevBuf search_ws, cand_ws, encode_ws, dense_ws;
     DevStatus* h_slots = nullptr;    // pinned host copies of the batches' status words [IVFR_STATUS_SLOTS]
-    uint32_t* h_redo = nullptr;      // pinned scratch of the (rare) per-query redo path [8]
+    uint32_t* h_redo = nullptr;      // pinned scratch of the (rare) per-query redo path [16 + IVFR_REDO_CHUNK]
     hipStream_t side[4] = {nullptr, nullptr, nullptr, nullptr};   // the smaller scan launches overlap the large one
     hipEvent_t ev_fork[IVFR_STATUS_SLOTS] = {nullptr};            // one set of fork / join events per batch in flight
     hipEvent_t ev_join[IVFR_STATUS_SLOTS][4] = {{nullptr}};

@@ -142,7 +142,7 @@ static SearchLayout layout_search(const ivfr_params& p, int B, int w, int kprime
     L.cnt = cv.take<uint32_t>(B);
     L.gnp = cv.take<uint32_t>(2 * c);
     L.zero_words = (cv.off - L.status + 3) / 4;
-    L.bytes = cv.off + 256;
+    L.bytes = (cv.off + 511) / 256 * 256;
     return L;
 }
 
@@ -552,21 +552,27 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
     // one at a time.  The launches take slices of the batch's arrays: the query's w pairs, their block prefix, its
     // counter, bound and buffer.
     auto redo_failed = [&](int64_t q0, int nb) -> int {
-        std::vector<int32_t> h_over((size_t)nb);
-        std::vector<unsigned long long> h_sq((size_t)nb);
-        IVFR_HIP(hipMemcpyAsync(h_over.data(), over, (size_t)nb * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-        IVFR_HIP(hipMemcpyAsync(h_sq.data(), pb.sq, (size_t)nb * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
-        IVFR_HIP(hipStreamSynchronize(st));
-        uint32_t* h = ix->h_redo;   // pinned: [0] count, [1] capacity, [2] still over
+        // pinned read-back area: [0] count, [1] capacity, [2] still over, [4..5] entries visited, [16..] a run of flags
+        uint32_t* h = ix->h_redo;
+        const int32_t* h_flags = reinterpret_cast<const int32_t*>(h + 16);
         for (int q = 0; q < nb; ++q) {
-            if (!h_over[(size_t)q]) continue;
+            if (q % IVFR_REDO_CHUNK == 0) {   // the failed-check flags of the next run of queries
+                const int n_run = std::min(IVFR_REDO_CHUNK, nb - q);
+                IVFR_HIP(hipMemcpyAsync(h + 16, over + q, (size_t)n_run * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                IVFR_HIP(hipStreamSynchronize(st));
+            }
+            if (!h_flags[q % IVFR_REDO_CHUNK]) continue;
+            IVFR_HIP(hipMemcpyAsync(h + 4, pb.sq + q, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+            IVFR_HIP(hipStreamSynchronize(st));
+            unsigned long long sq_q = 0;
+            memcpy(&sq_q, h + 4, sizeof(sq_q));
             ScanShape sq_shape;
             sq_shape.n_host = w;
             sq_shape.g_min = g_lo;
             if (ix->scan_groups > 0) {
                 sq_shape.groups = ix->scan_groups;
             } else {
-                double g = (double)h_sq[(size_t)q] / (double)IVFR_BLOCK / 64.0;
+                double g = (double)sq_q / (double)IVFR_BLOCK / 64.0;
                 g = g < (double)g_lo ? (double)g_lo : (g > 32768.0 ? 32768.0 : g);
                 sq_shape.groups = ((int)g + 7) & ~7;
             }
@@ -606,7 +612,7 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             if (settled) continue;
             // last resort: a buffer for every visited entry, no filter
             ix->st_dense += 1;
-            const uint64_t sqv = h_sq[(size_t)q];
+            const uint64_t sqv = sq_q;
             IVFR_REQUIRE(sqv < 0xFFFFFFF0ull, "a query visits more than 2^32 entries");
             const size_t bytes = (size_t)(sqv + 64) * sizeof(uint2) + 1024;
             if (fixed && bytes > ix->dense_ws.bytes) {
