@@ -106,6 +106,21 @@ int ivfr_import(ivfr_index* index, int64_t N, const int64_t* list_offsets, const
 int ivfr_search(ivfr_index* index, const float* queries, int64_t nq, int32_t w, int32_t kprime, int32_t k,
                 int32_t* ids_out, float* dist_out, void* stream);
 
+/* ivfr_search for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same results (bit for bit) as ivfr_search, but the
+ * per-batch arrays and the candidate pool are carved from a fixed array of 128 MiB that the library keeps
+ * in device memory (one per GPU it runs on, held until the process ends) instead of from buffers that grow
+ * on demand; the call allocates and frees nothing on the device.  Queries are processed in as many internal
+ * batches as it takes to fit (look-up tables of w * m KB per query with table mode 0, c * 8 bytes of coarse
+ * keys and 24 * kprime bytes of short-list per query, plus the candidate pool).  It fails with IVFR_ERR_OOM,
+ * saying what was needed, when one query alone does not fit, when a batch's candidate pool turns out to want
+ * more than the array holds, or when a query needs the unfiltered redo pass; with IVFR_ERR_STATE in table
+ * mode 1 before a first ivfr_search call has built the per-list table.  Nothing is timed
+ * (ivfr_stage_times reports host times only).  All calls on one GPU share that GPU's array, whichever index
+ * they search: calls that overlap in time on one GPU race, also on different streams and different indexes. */
+int ivfr_search_static(ivfr_index* index, const float* queries, int64_t nq, int32_t w, int32_t kprime, int32_t k,
+                       int32_t* ids_out, float* dist_out, void* stream);
+
 /* Same search, additionally exposing intermediate results for verification (any of the extra
  * pointers may be NULL).  All device memory.
  *   probe_out       int32 [nq, w]   visited lists, nearest first (ties: lower list index)

@@ -48,6 +48,7 @@ def _load():
         "ivfr_export": (ctypes.c_int, [vp, vp, vp, vp, vp]),
         "ivfr_import": (ctypes.c_int, [vp, i64, vp, vp, vp, vp]),
         "ivfr_search": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp]),
+        "ivfr_search_static": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp]),
         "ivfr_search_trace": (ctypes.c_int, [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "ivfr_search_stats": (ctypes.c_int, [vp] + [ctypes.POINTER(i64)] * 9),
         "ivfr_set_list_sharing": (ctypes.c_int, [vp, i32]),
@@ -69,7 +70,7 @@ def _load():
 
 lib = _load()
 EXPORTED = ["ivfr_create", "ivfr_destroy", "ivfr_train", "ivfr_set_codebooks", "ivfr_get_codebooks", "ivfr_add",
-            "ivfr_finalize", "ivfr_ntotal", "ivfr_export", "ivfr_import", "ivfr_search", "ivfr_search_trace",
+            "ivfr_finalize", "ivfr_ntotal", "ivfr_export", "ivfr_import", "ivfr_search", "ivfr_search_static", "ivfr_search_trace",
             "ivfr_search_stats", "ivfr_set_list_sharing", "ivfr_set_tuning", "ivfr_set_profiling", "ivfr_stage_times", "ivfr_last_error",
             "ivfr_memory_required", "ivfr_set_memory_limit", "ivfr_workspace_info", "ivfr_set_table_mode"]
 
@@ -206,6 +207,17 @@ class Index:
                                      _ptr(t["probe"]), _ptr(t["probe_dist"]), _ptr(t["short_ids"]),
                                      _ptr(t["short_est"]), _ptr(t["short_ref"]), _ptr(t["short_count"]), st))
         return ids, dist, t
+
+    def search_static(self, queries, w, kprime, k, ids, dist, stream=None):
+        """ivfr_search_static: the caller passes the output tensors (int32 [nq, k], fp32 [nq, k]); nothing is
+        allocated on the device by this method or by the library."""
+        import torch
+        assert queries.dtype == torch.float32 and queries.is_cuda and queries.is_contiguous()
+        nq = queries.shape[0]
+        assert ids.dtype == torch.int32 and dist.dtype == torch.float32 and ids.shape == (nq, k) and dist.shape == (nq, k)
+        assert ids.is_contiguous() and dist.is_contiguous()
+        st = ctypes.c_void_p(stream if stream is not None else torch.cuda.current_stream(queries.device).cuda_stream)
+        _check(lib.ivfr_search_static(self._h, _ptr(queries), nq, w, kprime, k, _ptr(ids), _ptr(dist), st))
 
     def search_stats(self):
         v = [ctypes.c_int64() for _ in range(9)]

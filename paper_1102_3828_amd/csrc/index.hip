@@ -105,6 +105,7 @@ extern "C" int ivfr_create(const ivfr_params* params, ivfr_index** out) {
         if (e != hipSuccess) { ivfr_set_error("pinned host allocation failed"); r = IVFR_ERR_OOM; }
         else memset(ix->h_slots, 0, IVFR_STATUS_SLOTS * sizeof(DevStatus));
     }
+    if (r == IVFR_OK) r = ivfr_static_scratch_address(p.device, &ix->static_ws);
     for (int i = 0; i < 4 && r == IVFR_OK; ++i) {
         if (hipStreamCreateWithFlags(&ix->side[i], hipStreamNonBlocking) != hipSuccess) {
             ivfr_set_error("stream creation failed");

@@ -82,6 +82,7 @@ struct DevStatus {
 };
 #define IVFR_STATUS_SLOTS 16        // batches of one call in flight between two host waits
 #define IVFR_REDO_CHUNK 4096        // failed-check flags read back per copy by the redo path
+#define IVFR_STATIC_SCRATCH_BYTES (128u << 20)   // workspace of ivfr_search_static: one such array per device
 
 // One staged (encoded, not yet list-sorted) batch of database vectors.
 struct StagedChunk {
@@ -138,6 +139,7 @@ struct ivfr_index {
 
     // scratch
     DevBuf search_ws, cand_ws, encode_ws, dense_ws;
+    char* static_ws = nullptr;       // this device's copy of the static workspace array (address from the runtime)
     DevStatus* h_slots = nullptr;    // pinned host copies of the batches' status words [IVFR_STATUS_SLOTS]
     uint32_t* h_redo = nullptr;      // pinned scratch of the (rare) per-query redo path [16 + IVFR_REDO_CHUNK]
     hipStream_t side[4] = {nullptr, nullptr, nullptr, nullptr};   // the smaller scan launches overlap the large one
@@ -175,6 +177,8 @@ inline size_t ivfr_index_bytes(const ivfr_params& p, uint64_t n_slots) {
 // IVFR_ERR_OOM (before anything is allocated) when `more` further device bytes do not fit: beyond the index's
 // memory limit, when one is set, or beyond what the device reports as free.
 int ivfr_check_room(const ivfr_index* ix, size_t more);
+// Address of the current device's copy of the static workspace array (search.hip).
+int ivfr_static_scratch_address(int device, char** out);
 // Allocates and fills the per-list term table of the split look-up tables if the index does not hold it yet.
 int ivfr_ensure_list_terms(ivfr_index* ix, hipStream_t st);
 

@@ -28,6 +28,7 @@
 
 #include <algorithm>
 #include <chrono>
+#include <mutex>
 #include <string.h>
 
 int ivfr_launch_select_records(const SelectArgs& a, int out_base, const unsigned long long* sq, uint32_t* out_pos,
@@ -38,6 +39,33 @@ int ivfr_launch_select_sorted(const SelectArgs& a, const int32_t* counts_i32, in
 int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, int nq, int kprime,
                        const uint32_t* short_pos, const int32_t* short_n, uint64_t* keys, float* refined_out,
                        int32_t* ids_out, hipStream_t st);
+
+// Workspace of ivfr_search_static, for callers that cannot allocate.  Every device holds its own copy of the
+// array, at its own address, until the process ends.  In host code the array's name is only a handle: the
+// address of a device's copy is asked from the runtime once, with that device current, and that address is
+// what host code passes to kernels and copies from then on.
+static __device__ __align__(256) unsigned char ivfr_static_scratch[IVFR_STATIC_SCRATCH_BYTES];
+
+#define IVFR_MAX_DEVICES 64
+static char* g_static_addr[IVFR_MAX_DEVICES];
+static std::mutex g_static_mutex;
+
+int ivfr_static_scratch_address(int device, char** out) {
+    *out = nullptr;
+    if (device < 0 || device >= IVFR_MAX_DEVICES) {
+        ivfr_set_error("device %d: the static workspace covers device ordinals below %d", device, IVFR_MAX_DEVICES);
+        return IVFR_ERR_INVALID_ARG;
+    }
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_addr[device]) {
+        IVFR_HIP(hipSetDevice(device));
+        void* p = nullptr;
+        IVFR_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(ivfr_static_scratch)));
+        g_static_addr[device] = static_cast<char*>(p);
+    }
+    *out = g_static_addr[device];
+    return IVFR_OK;
+}
 
 // Start of a batch: clear the counters (one contiguous block), mark every unit slot empty, tau = +inf.
 __global__ __launch_bounds__(256) void batch_reset_kernel(uint32_t* zero, size_t zero_words, uint32_t* ones,
@@ -750,4 +778,12 @@ extern "C" int ivfr_search(ivfr_index* ix, const float* queries, int64_t nq, int
                            int32_t* ids_out, float* dist_out, void* stream) {
     return run_search(ix, queries, nq, w, kprime, k, ids_out, dist_out, nullptr, nullptr, nullptr, nullptr, nullptr,
                       nullptr, stream, nullptr, 0);
+}
+
+extern "C" int ivfr_search_static(ivfr_index* ix, const float* queries, int64_t nq, int32_t w, int32_t kprime,
+                                  int32_t k, int32_t* ids_out, float* dist_out, void* stream) {
+    IVFR_REQUIRE(ix, "ivfr_search_static: null index");
+    if (!ix->static_ws) { ivfr_set_error("ivfr_search_static: the static workspace is not available on this device"); return IVFR_ERR_STATE; }
+    return run_search(ix, queries, nq, w, kprime, k, ids_out, dist_out, nullptr, nullptr, nullptr, nullptr, nullptr,
+                      nullptr, stream, ix->static_ws, (size_t)IVFR_STATIC_SCRATCH_BYTES);
 }
