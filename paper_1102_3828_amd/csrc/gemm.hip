@@ -55,8 +55,36 @@ int ivfr_launch_group_max_norm(const float* norm2, int groups, int per, float* o
     return IVFR_OK;
 }
 
+// Rows of at least 32 floats: eight lanes per row, 16 bytes per lane and step (coalesced), partial sums combined
+// with three xor-shuffles.
+__global__ __launch_bounds__(256) void row_norms8_kernel(const float* __restrict__ X, int64_t n, int dim,
+                                                         float* __restrict__ out, uint32_t* __restrict__ bad) {
+    const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);
+    const int t = threadIdx.x & 7;
+    float s = 0.f;
+    if (row < n) {
+        const float* x = X + row * dim;
+        for (int e = 4 * t; e < dim; e += 32) {
+            const float4 v = *reinterpret_cast<const float4*>(x + e);
+            s = fmaf(v.x, v.x, s); s = fmaf(v.y, v.y, s); s = fmaf(v.z, v.z, s); s = fmaf(v.w, v.w, s);
+        }
+    }
+    s += __shfl_xor(s, 4, 64);
+    s += __shfl_xor(s, 2, 64);
+    s += __shfl_xor(s, 1, 64);
+    if (row < n && t == 0) {
+        out[row] = s;
+        if (bad && !(s <= 3.0e38f)) atomicMax(bad, (uint32_t)row + 1u);
+    }
+}
+
 int ivfr_launch_row_norms(const float* X, int64_t n, int dim, float* out, hipStream_t st, uint32_t* bad) {
     if (n <= 0) return IVFR_OK;
+    if (dim >= 32 && dim % 4 == 0) {
+        hipLaunchKernelGGL(row_norms8_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, st, X, n, dim, out, bad);
+        IVFR_HIP(hipGetLastError());
+        return IVFR_OK;
+    }
     hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, X, n, dim, out, bad);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;

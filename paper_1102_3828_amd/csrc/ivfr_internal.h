@@ -312,6 +312,20 @@ struct PairTable {
                            fmaxf(0.f, (va.w + vb.w) + s));
     }
 };
+// Entry e of the tables of G pairs that visit the same list (a unit of the shared scans): with split tables the
+// list's term is loaded once for all of them.  Same expression, hence the same bits, as PairTable::get.
+template <int G>
+__device__ __forceinline__ void unit_table_entries(const PairTable (&pt)[G], int e, float (&v)[G]) {
+    if (pt[0].b) {
+        const float ae = pt[0].a[e];
+#pragma unroll
+        for (int x = 0; x < G; ++x) v[x] = fmaxf(0.f, (ae + pt[x].b[e]) + pt[x].base[e >> 8]);
+    } else {
+#pragma unroll
+        for (int x = 0; x < G; ++x) v[x] = pt[x].a[e];
+    }
+}
+
 struct TableSrc {
     const float* lut = nullptr;        // [pairs][m][256], or in split mode [queries][m][256]
     const float* list_term = nullptr;  // split mode: [c][m][256]

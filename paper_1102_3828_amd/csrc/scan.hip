@@ -988,8 +988,10 @@ __device__ __forceinline__ void half_unit_pass(const uint8_t* __restrict__ codes
         if (unit[x] == IVFR_NO_PAIR) tshi[x] = (short)-1;
     for (int e = tid; e < M * IVFR_KS; e += 256) {
         half4 h;
+        float v[4];
+        unit_table_entries<4>(pt, e, v);
 #pragma unroll
-        for (int x = 0; x < 4; ++x) h[x] = (_Float16)(pt[x].get(e) * sc[x]);
+        for (int x = 0; x < 4; ++x) h[x] = (_Float16)(v[x] * sc[x]);
         s_lut4[e] = h;
     }
     __syncthreads();
@@ -1162,8 +1164,7 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
         }
         for (int e = tid; e < M * IVFR_KS; e += 256) {
             float v[G];
-#pragma unroll
-            for (int x = 0; x < G; ++x) v[x] = pt[x].get(e);
+            unit_table_entries<G>(pt, e, v);
             vec_t packed;
             vload(packed, v);
             s_lutv[e] = packed;
@@ -1350,9 +1351,10 @@ static int launch_sample_m(const ivfr_index* ix, const TableSrc& ts, const uint3
                            const uint32_t* chunk_pre, const uint32_t* items, const uint32_t* n_items, size_t max_items,
                            const uint32_t* soff, int w, uint2* cand, CandLayout lay, hipStream_t st) {
     const size_t lds = sample_lds_bytes<M, WAVES>();
-    // as many workgroups as fit the compute units' LDS twice over, or one wavefront per chunk when there are fewer
+    // four times the workgroups that the compute units' LDS holds at once (measured best against one, two and one
+    // workgroup per chunk), or one wavefront per chunk when there are fewer
     const size_t per_cu = std::max<size_t>(1, (size_t)(160 * 1024) / lds);
-    const size_t grid = std::max<size_t>(1, std::min((max_items + WAVES - 1) / WAVES, (size_t)ix->n_cu * per_cu * 2));
+    const size_t grid = std::max<size_t>(1, std::min((max_items + WAVES - 1) / WAVES, (size_t)ix->n_cu * per_cu * 4));
     hipLaunchKernelGGL((adc_sample_kernel<M, WAVES>), dim3((unsigned)grid), dim3(64 * WAVES), lds, st, ix->codes, ts,
                        pair_start, len_s, chunk_pre, items, n_items, soff, w, cand, lay);
     IVFR_HIP(hipGetLastError());
@@ -1510,8 +1512,10 @@ __global__ __launch_bounds__(H8_T) void adc_scan_shared8h_kernel(const uint8_t* 
         }
         for (int e = tid; e < M * IVFR_KS; e += H8_T) {   // e = j * 256 + byte; stored at [byte][j]
             half8 h;
+            float v[8];
+            unit_table_entries<8>(pt, e, v);
 #pragma unroll
-            for (int x = 0; x < 8; ++x) h[x] = (_Float16)(pt[x].get(e) * sc[x]);
+            for (int x = 0; x < 8; ++x) h[x] = (_Float16)(v[x] * sc[x]);
             s_lut8[(e & (IVFR_KS - 1)) * M + (e >> 8)] = h;
         }
         __syncthreads();

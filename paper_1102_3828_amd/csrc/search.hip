@@ -438,8 +438,9 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             ev_used += 2;
             IVFR_HIP(hipEventRecord(ep.a, s));
             events.push_back(ep);
-        } else {
-            IVFR_HIP(hipEventRecord(events.back().b, s));
+        } else {   // closes the most recent pair of this kind (stages on different streams interleave)
+            for (size_t i = events.size(); i-- > 0;)
+                if (events[i].kind == kind) { IVFR_HIP(hipEventRecord(events[i].b, s)); break; }
         }
         return IVFR_OK;
     };
@@ -498,7 +499,11 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
         // sample keeps tau = +inf)
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, true));
         {
-            const size_t max_items = (size_t)Pb + (size_t)nb * ((IVFR_MAX_SAMPLE + (size_t)w) / IVFR_SAMPLE_CHUNK + 1);
+            // chunks the sample can have at most; a batch whose queries are expected to keep everything (no sample)
+            // gets a small grid, whose wavefronts would still walk over whatever chunks there are
+            const bool expect_sample = 1.5 * visit_est > (double)full_limit;
+            const size_t max_items = expect_sample
+                ? (size_t)Pb + (size_t)nb * ((IVFR_MAX_SAMPLE + (size_t)w) / IVFR_SAMPLE_CHUNK + 1) : (size_t)ix->n_cu * 4;
             IVFR_TRY(ivfr_launch_sample_scan(ix, tsrc, pb.pair_start, pb.len_s, pb.blkpre_s, pb.items_s,
                                              &dstat->n_sample_chunks, max_items, pb.soff, w, cand, lay, st));
             // the sample of query q is nsample[q] bare estimates at the start of its buffer

@@ -16,6 +16,8 @@
 // the id array only in passes 4-7 and only for records whose estimate equals the pivot's.
 #include "ivfr_internal.h"
 
+#include <algorithm>
+
 #define SEL_T 512
 #define SEL_LCAP 2048
 #define SORT_MAX 16384
@@ -223,40 +225,43 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
                                                            CandLayout lay, const uint32_t* counts,
                                                            const unsigned long long* sq, int kprime,
                                                            int fixed_rank, const uint8_t* skip, float* tau,
-                                                           uint32_t* tau_id, int values_only) {
-    const int seg = blockIdx.x;
-    if (skip && skip[seg]) return;
-    bool over;
-    int64_t n = seg_count(counts, values_only ? 0xFFFFFFFFu : lay.cap(seg), seg, &over);
-    const double mu = (double)kprime * (double)n / (double)(sq[seg] ? sq[seg] : 1ull);
-    // fixed_rank > 0: the records are a subset of the visited entries and their fixed_rank-th smallest is wanted
-    const int64_t r = fixed_rank > 0 ? (int64_t)fixed_rank : (int64_t)ceil(mu + 5.0 * sqrt(mu) + 6.0);
-    if (n < r || n == 0) {
-        if (threadIdx.x == 0) {
-            tau[seg] = INFINITY;
-            if (tau_id) tau_id[seg] = 0xFFFFFFFFu;
+                                                           uint32_t* tau_id, int values_only, int nseg) {
+    // the workgroups walk over the segments: a batch whose queries all skip the bound costs a few hundred
+    // workgroup launches, not one per query (seg is uniform over the workgroup, so every barrier is reached by all)
+    for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
+        if (skip && skip[seg]) continue;
+        bool over;
+        int64_t n = seg_count(counts, values_only ? 0xFFFFFFFFu : lay.cap(seg), seg, &over);
+        const double mu = (double)kprime * (double)n / (double)(sq[seg] ? sq[seg] : 1ull);
+        // fixed_rank > 0: the records are a subset of the visited entries and their fixed_rank-th smallest is wanted
+        const int64_t r = fixed_rank > 0 ? (int64_t)fixed_rank : (int64_t)ceil(mu + 5.0 * sqrt(mu) + 6.0);
+        if (n < r || n == 0) {
+            if (threadIdx.x == 0) {
+                tau[seg] = INFINITY;
+                if (tau_id) tau_id[seg] = 0xFFFFFFFFu;
+            }
+            continue;
         }
-        return;
-    }
-    SegView s{nullptr, recs, ids, (int64_t)lay.base(seg), n};
-    s.id_stride = id_stride;
-    if (values_only) {   // the segment holds n bare estimates (4 bytes each) at the start of its record buffer
-        s.recs = nullptr;
-        s.vals = reinterpret_cast<const uint32_t*>(recs);
-        s.base = 2 * (int64_t)lay.base(seg);
-    }
-    uint64_t pivot = radix_pivot(s, (uint32_t)r);
-    if (threadIdx.x == 0) {
-        tau[seg] = __uint_as_float((uint32_t)(pivot >> 32));
-        if (tau_id) tau_id[seg] = (uint32_t)pivot;
+        SegView s{nullptr, recs, ids, (int64_t)lay.base(seg), n};
+        s.id_stride = id_stride;
+        if (values_only) {   // the segment holds n bare estimates (4 bytes each) at the start of its record buffer
+            s.recs = nullptr;
+            s.vals = reinterpret_cast<const uint32_t*>(recs);
+            s.base = 2 * (int64_t)lay.base(seg);
+        }
+        uint64_t pivot = radix_pivot(s, (uint32_t)r);   // ends with a barrier: its LDS state is free for the next segment
+        if (threadIdx.x == 0) {
+            tau[seg] = __uint_as_float((uint32_t)(pivot >> 32));
+            if (tau_id) tau_id[seg] = (uint32_t)pivot;
+        }
     }
 }
 
 int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, int fixed_rank,
                            const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st, bool values_only) {
     if (a.nseg <= 0) return IVFR_OK;
-    hipLaunchKernelGGL(select_tau_kernel, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.id_stride, a.lay, a.counts, sq,
-                       kprime, fixed_rank, skip, tau, tau_id, values_only ? 1 : 0);
+    hipLaunchKernelGGL(select_tau_kernel, dim3(std::min(a.nseg, 1024)), dim3(SEL_T), 0, st, a.recs, a.ids, a.id_stride,
+                       a.lay, a.counts, sq, kprime, fixed_rank, skip, tau, tau_id, values_only ? 1 : 0, a.nseg);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
