@@ -232,9 +232,10 @@ struct SelectArgs {
 // sample holds fewer than r).  fixed_rank > 0 takes that rank instead.  skip[seg] != 0 leaves tau alone.
 // tau_id (optional) receives the id of the record taken, i.e. the low half of its key.  values_only: segment
 // q holds counts[q] bare estimates (4 bytes each) from the start of its record buffer instead of records.
+// mostly_skipped: the caller expects nearly every segment to be skipped (a few workgroups then walk over them).
 int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, int fixed_rank,
                            const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st,
-                           bool values_only = false);
+                           bool values_only = false, bool mostly_skipped = false);
 int ivfr_select_init();   // one-time function attributes
 
 // Per-query part of the search plan, shared by the plan kernel and by the host's estimate of the candidate

@@ -509,7 +509,7 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             // the sample of query q is nsample[q] bare estimates at the start of its buffer
             SelectArgs a;
             a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = reinterpret_cast<const int32_t*>(ix->rec); a.id_stride = (uint32_t)(ix->rec_stride / 4); a.counts = pb.nsample; a.lay = lay;
-            IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, 0, pb.fully, tau, nullptr, st, true));
+            IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, 0, pb.fully, tau, nullptr, st, true, !expect_sample));
         }
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
         // scan of every visited entry, keeping estimates <= tau

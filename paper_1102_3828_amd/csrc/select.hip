@@ -221,14 +221,17 @@ __device__ __forceinline__ int64_t seg_count(const uint32_t* counts, uint32_t ca
 // best are in it (Poisson-like).  Taking the r-th smallest sampled estimate with r = mu + 5
 // sqrt(mu) + 6 makes it all but certain (beyond five standard deviations) that at least k'
 // visited entries lie at or below it; the filtered scan verifies that by counting.
+// WALK: few workgroups walk over the segments (for batches in which hardly any query has a sample: launching a
+// workgroup per query only to find its skip flag set costs more than the whole selection); otherwise one
+// workgroup per segment.
+template <bool WALK>
 __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, const int32_t* ids, uint32_t id_stride,
                                                            CandLayout lay, const uint32_t* counts,
                                                            const unsigned long long* sq, int kprime,
                                                            int fixed_rank, const uint8_t* skip, float* tau,
                                                            uint32_t* tau_id, int values_only, int nseg) {
-    // the workgroups walk over the segments: a batch whose queries all skip the bound costs a few hundred
-    // workgroup launches, not one per query (seg is uniform over the workgroup, so every barrier is reached by all)
-    for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
+    // seg is uniform over the workgroup, so every barrier is reached by all its threads
+    for (int seg = blockIdx.x; seg < nseg; seg += WALK ? (int)gridDim.x : nseg) {
         if (skip && skip[seg]) continue;
         bool over;
         int64_t n = seg_count(counts, values_only ? 0xFFFFFFFFu : lay.cap(seg), seg, &over);
@@ -258,10 +261,15 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
 }
 
 int ivfr_launch_select_tau(const SelectArgs& a, const unsigned long long* sq, int kprime, int fixed_rank,
-                           const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st, bool values_only) {
+                           const uint8_t* skip, float* tau, uint32_t* tau_id, hipStream_t st, bool values_only,
+                           bool mostly_skipped) {
     if (a.nseg <= 0) return IVFR_OK;
-    hipLaunchKernelGGL(select_tau_kernel, dim3(std::min(a.nseg, 1024)), dim3(SEL_T), 0, st, a.recs, a.ids, a.id_stride,
-                       a.lay, a.counts, sq, kprime, fixed_rank, skip, tau, tau_id, values_only ? 1 : 0, a.nseg);
+    if (mostly_skipped)
+        hipLaunchKernelGGL(select_tau_kernel<true>, dim3(std::min(a.nseg, 256)), dim3(SEL_T), 0, st, a.recs, a.ids,
+                           a.id_stride, a.lay, a.counts, sq, kprime, fixed_rank, skip, tau, tau_id, values_only ? 1 : 0, a.nseg);
+    else
+        hipLaunchKernelGGL(select_tau_kernel<false>, dim3(a.nseg), dim3(SEL_T), 0, st, a.recs, a.ids, a.id_stride,
+                           a.lay, a.counts, sq, kprime, fixed_rank, skip, tau, tau_id, values_only ? 1 : 0, a.nseg);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
