@@ -716,6 +716,16 @@ def test_candidate_pool_grows_when_the_estimate_is_low():
     assert info2["batch_reruns"] == 0 and info2["pool_bytes"] == info["pool_bytes"]
     assert np.array_equal(ids.cpu().numpy(), ids2.cpu().numpy()) and np.array_equal(dist.cpu().numpy(), dist2.cpu().numpy())
     ix.close()
+    # the same in a call of several internal batches, all enqueued before the first status is read: every batch finds
+    # the pool too small and is run again, one after the other
+    ix = gpu_index_from_oracle(index)
+    ix.set_tuning(batch=10)
+    ids3, dist3 = ix.search(xq, 1, 500, 20)
+    info3 = ix.workspace_info()
+    log("four batches", info3, ix.search_stats())
+    assert info3["batch_reruns"] >= 1
+    assert np.array_equal(ids.cpu().numpy(), ids3.cpu().numpy()) and np.array_equal(dist.cpu().numpy(), dist3.cpu().numpy())
+    ix.close()
 
 
 def test_memory_limit_refuses_before_allocating():

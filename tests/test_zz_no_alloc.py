@@ -41,6 +41,19 @@ def test_static_workspace_search_matches_the_allocating_entry_point():
     with torch.cuda.stream(side):
         ix.search_static(xq, w, kp, k, ids, dist)
     assert torch.equal(ids, ref_ids) and torch.equal(dist, ref_dist)
+    # more queries than fit the fixed array at once (96 KB of tables per query at w = 12): the call splits them into
+    # internal batches by itself, same bits as the allocating entry point
+    big = xq.repeat(80, 1).contiguous()                                # 3840 queries
+    ix.set_list_sharing(2)
+    ref_ids, ref_dist = ix.search(big, 12, kp, k)
+    ids_b = torch.empty((len(big), k), dtype=torch.int32, device="cuda")
+    dist_b = torch.empty((len(big), k), dtype=torch.float32, device="cuda")
+    ix.search_static(big, 12, kp, k, ids_b, dist_b)
+    assert ix.search_stats()["pairs"] == len(big) * 12
+    assert torch.equal(ids_b, ref_ids) and torch.equal(dist_b, ref_dist)
+    ref_ids, ref_dist = ix.search(xq, w, kp, k)
+    ix.search_static(xq, w, kp, k, ids, dist)
+    assert torch.equal(ids, ref_ids) and torch.equal(dist, ref_dist)
     # a request whose workspace cannot fit the fixed array even for one query: clear error, nothing done
     with pytest.raises(pkg.IvfrError) as e:
         ix.search_static(xq, 12, 6_000_000, 12, ids, dist)            # 24 k' bytes of short-list per query = 144 MB
