@@ -288,7 +288,7 @@ def small_config_entry(name, args):
     stage = other_stage_times(ix, batches, cfg, 1)
     ix.set_list_sharing(0)
     el0, acc0, st0 = timed_loop(ix, batches, cfg, args.steps, 1, "per-pair")
-    ix.set_list_sharing(2)
+    ix.set_list_sharing(-1)
     ids, _ = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
     scan0 = st0.get("scan", 0.0) / args.steps
     bytes0 = cfg.m * acc0["codes_scanned"] / args.steps
@@ -399,8 +399,9 @@ def main():
     ap.add_argument("--scan-groups", type=int, default=0)
     ap.add_argument("--per-pair", action="store_true",
                     help="default loop in sharing mode 0 as well (every (query, list) pair on its own)")
-    ap.add_argument("--sharing", type=int, default=2, choices=(0, 1, 2, 3),
-                    help="list sharing mode of the default loop: 0 per pair, 1 fp32 units of four/two, 2 also fp16 units "
+    ap.add_argument("--sharing", type=int, default=-1, choices=(-1, 0, 1, 2, 3),
+                    help="list sharing mode of the default loop: -1 the library's choice (2 for batches that stream "
+                         "3e8 codes or more, else 0), 0 per pair, 1 fp32 units of four/two, 2 also fp16 units "
                          "of eight, 3 also matrix-core units of 64")
     ap.add_argument("--table-mode", type=int, default=-1, choices=(-1, 0, 1),
                     help="look-up tables: 0 one per (query, list) pair in the workspace, 1 split into per-list and "
@@ -479,8 +480,13 @@ def main():
     g_ids = g_ids.cpu().numpy()
     recall = recall_of(g_ids, gt, n_gt, cfg.k)
 
+    # the mode the library ran in: shared units were counted or not
+    shared_codes = sum(acc[k] for k in ("codes_scanned_shared", "codes_scanned_shared2", "codes_scanned_shared8",
+                                        "codes_scanned_shared64"))
+    sharing_eff = args.sharing if args.sharing >= 0 else (2 if shared_codes > 0 else 0)
+
     # ---- timed loop 2: every (query, list) pair on its own, fp32 throughout -> the per-pair scan's HBM roofline
-    if args.sharing != 0:
+    if sharing_eff != 0:
         ix.set_list_sharing(0)
         el0, acc0, st0 = timed_loop(ix, batches, cfg, steps, 1, "sharing 0")
         p_ids, _ = ix.search(batches[0], cfg.w, cfg.kprime, cfg.k)
@@ -513,12 +519,13 @@ def main():
         "metric": "queries/s", "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / steps, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if args.sharing < 2 else "f32 recorded estimates and distances; the shared-list scans pre-filter in f16",
+        "dtype": "f32" if sharing_eff < 2 else "f32 recorded estimates and distances; the shared-list scans pre-filter in f16",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N} d={cfg.d} c={cfg.c} m={cfg.m} m'={cfg.m_refine} "
                                f"w={cfg.w} k'={cfg.kprime} k={cfg.k}, {B} queries per step",
                    "generator": f"uint8 Gaussian mixture G={cfg.G} zipf={cfg.zipf} seed={sd.BASE_SEED}",
-                   "list_sharing_mode": args.sharing, "table_mode": args.table_mode},
+                   "list_sharing_mode": args.sharing, "list_sharing_mode_in_effect": sharing_eff,
+                   "table_mode": args.table_mode},
         "adc_codes_per_s": acc["codes_scanned"] / elapsed,
         "value_f32_per_pair": steps * B / el0, "ms_per_step_f32_per_pair": 1e3 * el0 / steps,
         "adc_codes_per_s_f32_per_pair": acc0["codes_scanned"] / el0, "dtype_f32_per_pair": "f32",
@@ -542,7 +549,7 @@ def main():
     kernels = [("adc_scan_shared8h_kernel", "scan_shared8", "codes_scanned_shared8", 2.0),
                ("adc_scan_shared_kernel<4>", "scan_shared", "codes_scanned_shared", 4.0),
                ("adc_scan_mfma64_kernel", "scan_shared64", "codes_scanned_shared64", 0.0)]
-    if args.sharing != 0:
+    if sharing_eff != 0:
         kname, stage, key, lds_b = max(kernels, key=lambda t: stage_ms.get(t[1], 0.0))
         k_ms = stage_ms.get(stage, 0.0) / steps
         k_est = acc[key] / steps

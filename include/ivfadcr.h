@@ -153,8 +153,11 @@ int ivfr_search_stats(const ivfr_index* index, int64_t* codes_scanned, int64_t* 
 
 /* List sharing.  Queries of one internal batch that visit the same list are scanned together: the
  * list's codes are read once and each code byte fetches all the queries' table entries with one
- * LDS read.  mode 0: every (query, list) pair is scanned on its own.  mode 1 (needs m <= 16): units
- * of four and of two queries with fp32 tables (16- and 8-byte LDS reads).  mode 2 (default; m <= 16):
+ * LDS read.  mode -1 (default): mode 2 for batches expected to stream 3e8 codes or more (queries of the
+ * batch x entries a query visits, estimated from the list lengths), mode 0 for smaller ones, where the
+ * grouping costs more than it saves.  mode 0: every (query, list) pair is scanned on its own.  mode 1
+ * (needs m <= 16): units
+ * of four and of two queries with fp32 tables (16- and 8-byte LDS reads).  mode 2 (m <= 16):
  * in addition units of eight queries with half-precision tables; an entry whose half-precision
  * estimate could be within the bound is re-evaluated in fp32 before it is kept, so the recorded
  * estimates, and therefore the results, are bit-identical in all modes.  mode 3 (m in {4, 8, 16},

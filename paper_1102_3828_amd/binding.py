@@ -226,9 +226,9 @@ class Index:
                  "codes_scanned_shared2", "codes_scanned_shared8", "bound_retries", "codes_scanned_shared64")
         return dict(zip(names, [x.value for x in v]))
 
-    def set_list_sharing(self, mode=2):
-        """0 = per pair; 1 = fp32 units of four / two; 2 = also fp16 units of eight (default); 3 = also
-        matrix-core units of 64."""
+    def set_list_sharing(self, mode=-1):
+        """-1 = 2 for large batches, 0 for small ones (default); 0 = per pair; 1 = fp32 units of four / two;
+        2 = also fp16 units of eight; 3 = also matrix-core units of 64."""
         _check(lib.ivfr_set_list_sharing(self._h, int(mode)))
 
     def set_table_mode(self, mode):

@@ -155,39 +155,82 @@ __device__ __forceinline__ void mma_slab(const float* As, const float* Bs, int w
 // Accumulator element v of a 32x32 MFMA tile sits at row 8*(v/4) + 4*(lane/32) + v%4, col lane%32.
 __device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
+// The same staging and accumulation for a workgroup tile of (64 T) x (64 T) outputs, T = 1 or 2: each of the
+// 2x2 wavefronts owns T x T MFMA tiles.  The k order per output element does not depend on T, so both tile sizes
+// give the same bits.
+template <int T>
+__device__ __forceinline__ void stage_rows(const float* __restrict__ M, int64_t rows, int d, int64_t row0, int k0,
+                                           float* lds) {
+    const int tid = threadIdx.x;
+    const int kc = (tid & 7) * 4;
+#pragma unroll
+    for (int i = 0; i < 2 * T; ++i) {
+        int r = (tid >> 3) + 32 * i;
+        int64_t gr = row0 + r;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gr < rows && k0 + kc < d) v = *reinterpret_cast<const float4*>(M + gr * d + k0 + kc);
+        *reinterpret_cast<float4*>(lds + r * LDS_STRIDE + kc) = v;
+    }
+}
+
+template <int T>
+__device__ __forceinline__ void mma_tiles(const float* As, const float* Bs, int wm, int wn, floatx16 (&acc)[T][T]) {
+    const int lane = threadIdx.x & 63;
+    const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int kk = 0; kk < KT / 8; ++kk) {
+        float4 a[T], b[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            a[t] = *reinterpret_cast<const float4*>(As + (32 * T * wm + 32 * t + r) * LDS_STRIDE + kk * 8 + 4 * h);
+            b[t] = *reinterpret_cast<const float4*>(Bs + (32 * T * wn + 32 * t + r) * LDS_STRIDE + kk * 8 + 4 * h);
+        }
+#pragma unroll
+        for (int ta = 0; ta < T; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < T; ++tb) {
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta].x, b[tb].x, acc[ta][tb], 0, 0, 0);
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta].y, b[tb].y, acc[ta][tb], 0, 0, 0);
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta].z, b[tb].z, acc[ta][tb], 0, 0, 0);
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta].w, b[tb].w, acc[ta][tb], 0, 0, 0);
+            }
+    }
+}
+
+template <int T>
 __global__ __launch_bounds__(256) void dist_keys_kernel(const float* __restrict__ X, const float* __restrict__ xnorm,
                                                         int64_t n, const float* __restrict__ C,
                                                         const float* __restrict__ cnorm, int c, int d,
                                                         uint64_t* __restrict__ keys) {
-    __shared__ float As[TM * LDS_STRIDE];
-    __shared__ float Bs[TN * LDS_STRIDE];
-    const int64_t row0 = (int64_t)blockIdx.x * TM;
-    const int64_t col0 = (int64_t)blockIdx.y * TN;
+    __shared__ float As[64 * T * LDS_STRIDE];
+    __shared__ float Bs[64 * T * LDS_STRIDE];
+    const int64_t row0 = (int64_t)blockIdx.x * (64 * T);
+    const int64_t col0 = (int64_t)blockIdx.y * (64 * T);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wm = wave >> 1, wn = wave & 1;
-    floatx16 acc[2][2];
+    floatx16 acc[T][T];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < T; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < T; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
     for (int k0 = 0; k0 < d; k0 += KT) {
         __syncthreads();
-        stage_slab(X, n, d, row0, k0, As);
-        stage_slab(C, c, d, col0, k0, Bs);
+        stage_rows<T>(X, n, d, row0, k0, As);
+        stage_rows<T>(C, c, d, col0, k0, Bs);
         __syncthreads();
-        mma_slab(As, Bs, wm, wn, acc);
+        mma_tiles<T>(As, Bs, wm, wn, acc);
     }
 #pragma unroll
-    for (int ta = 0; ta < 2; ++ta)
+    for (int ta = 0; ta < T; ++ta)
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            int64_t col = col0 + 64 * wn + 32 * tb + (lane & 31);
+        for (int tb = 0; tb < T; ++tb) {
+            int64_t col = col0 + 32 * T * wn + 32 * tb + (lane & 31);
             float cn = (col < c) ? cnorm[col] : 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                int64_t row = row0 + 64 * wm + 32 * ta + acc_row(v, lane);
+                int64_t row = row0 + 32 * T * wm + 32 * ta + acc_row(v, lane);
                 if (row < n && col < c) {
                     float dist = fmaxf(0.f, fmaf(-2.f, acc[ta][tb][v], xnorm[row] + cn));
                     keys[row * c + col] = ((uint64_t)__float_as_uint(dist) << 32) | (uint32_t)col;
@@ -199,8 +242,15 @@ __global__ __launch_bounds__(256) void dist_keys_kernel(const float* __restrict_
 int ivfr_launch_dist_keys(const float* X, const float* xnorm, int64_t n, const float* C, const float* cnorm,
                           int c, int d, uint64_t* keys, hipStream_t st) {
     if (n <= 0) return IVFR_OK;
-    dim3 grid((unsigned)((n + TM - 1) / TM), (unsigned)((c + TN - 1) / TN));
-    hipLaunchKernelGGL(dist_keys_kernel, grid, dim3(256), 0, st, X, xnorm, n, C, cnorm, c, d, keys);
+    // 128 x 128 tiles unless they would leave most compute units without a workgroup
+    const int64_t big = ((n + TM - 1) / TM) * ((c + TN - 1) / TN);
+    if (big >= 256) {
+        dim3 grid((unsigned)((n + TM - 1) / TM), (unsigned)((c + TN - 1) / TN));
+        hipLaunchKernelGGL(dist_keys_kernel<2>, grid, dim3(256), 0, st, X, xnorm, n, C, cnorm, c, d, keys);
+    } else {
+        dim3 grid((unsigned)((n + 63) / 64), (unsigned)((c + 63) / 64));
+        hipLaunchKernelGGL(dist_keys_kernel<1>, grid, dim3(256), 0, st, X, xnorm, n, C, cnorm, c, d, keys);
+    }
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }

@@ -673,7 +673,7 @@ extern "C" int ivfr_search_stats(const ivfr_index* ix, int64_t* codes_scanned, i
 
 extern "C" int ivfr_set_list_sharing(ivfr_index* ix, int32_t mode) {
     IVFR_REQUIRE(ix, "ivfr_set_list_sharing: null index");
-    IVFR_REQUIRE(mode >= 0 && mode <= 3, "list sharing mode %d must be 0, 1, 2 or 3", mode);
+    IVFR_REQUIRE(mode >= -1 && mode <= 3, "list sharing mode %d must be -1 (automatic), 0, 1, 2 or 3", mode);
     ix->share_lists = mode;
     return IVFR_OK;
 }

@@ -134,7 +134,8 @@ struct ivfr_index {
 
     // tuning
     int full_mult = 8, cap_mult = 16, batch = 16384, scan_groups = 0;
-    int share_lists = 2;             // 0 = every pair on its own; 1 = fp32 units of four / two; 2 = also fp16 units of eight; 3 = also matrix-core units of 64
+    int share_lists = -1;            // -1 = 2 or 0 by the size of the batch's scan; 0 = every pair on its own; 1 = fp32 units of four / two;
+                                     // 2 = also fp16 units of eight; 3 = also matrix-core units of 64
     int min_cap = 8192;
 
     // scratch
@@ -240,7 +241,7 @@ int ivfr_select_init();   // one-time function attributes
 
 // Per-query part of the search plan, shared by the plan kernel and by the host's estimate of the candidate
 // pool.  A query that visits `total` entries keeps every estimate when total <= full_limit (or when its sample
-// would be half of them or more); otherwise one entry in `stride` is sampled (the same leading fraction of
+// would be a third of them or more); otherwise one entry in `stride` is sampled (the same leading fraction of
 // every visited list) to bound the k'-th smallest estimate.  Scoring a sampled entry and handling a surviving
 // one cost about the same order, and the survivors fall as k' (1 + 5/sqrt(mu) + 6/mu) with mu = k' n_s / total,
 // so the cheapest sample grows as the cube root of k' * total (the factor 16 is measured).  The stride is at
@@ -263,7 +264,7 @@ __host__ __device__ inline QueryPlan ivfr_plan_query(unsigned long long total, u
     const unsigned long long widen = (total + max_sample - 1) / max_sample;
     if (widen > stride64) stride64 = widen;
     if (stride64 < 1) stride64 = 1;
-    if (stride64 <= 2) r.fully = true;
+    if (stride64 <= 3) r.fully = true;   // a sample of a third or more of the entries saves nothing
     r.stride = (uint32_t)(stride64 > 0xFFFFFFFFull ? 0xFFFFFFFFull : stride64);
     return r;
 }
@@ -369,11 +370,13 @@ struct PlanBuffers {
     uint32_t* blkpre;      // [P+1] exclusive prefix of scan blocks over the pairs
     uint32_t* blkpre_s;    // [P+1] exclusive prefix of the sample's chunks (IVFR_SAMPLE_CHUNK entries) over the pairs
     uint32_t* items_s;     // [blkpre_s[P]] pair of every sample chunk
-    uint32_t* soff;        // [P] first record of the pair's sample inside the query's candidate buffer
+    uint32_t* soff;        // [P] first record of the pair's sample inside the query's candidate buffer; for a query that
+                           //     keeps everything (no sample) the place of the pair's first entry in that buffer
     uint32_t* qblk;        // [nq] scan blocks of the query, then (after the plan's scan) its first block
     uint32_t* qblk_s;      // [nq] same for the sample
     uint32_t* nsample;     // [nq] sampled entries of the query
     uint32_t* capq;        // [nq] records in the query's candidate buffer
+    uint32_t* cnt;         // [nq] record counters of the scan (zero on entry; preset for queries that keep everything)
     unsigned long long* coff;    // [nq] first record of the query's candidate buffer in the pool
     unsigned long long* sq;      // [nq] entries in the query's visited lists
     uint8_t* fully;              // [nq] 1 = few enough entries to keep them all (no sample, tau = +inf)
@@ -407,10 +410,16 @@ struct ScanShape {
 // unit_pairs == nullptr: unit u of the launch is pair u; otherwise pair unit_pairs[u].  An entry is kept
 // when its estimate is <= tau[q]; with tau_id, when its key (estimate, id) is <= (tau[q], tau_id[q]).
 // blkpre may be a slice of a longer prefix array: the launch's blocks are blkpre[0] .. blkpre[units].
+// Queries that keep every estimate need no counter: entry e of pair p is record off[p] + e of the query's buffer
+// (the plan presets the query's counter to its number of visited entries).  fully == nullptr: nobody is placed so.
+struct DirectPlace {
+    const uint8_t* fully = nullptr;   // [nq]
+    const uint32_t* off = nullptr;    // [P]
+};
 int ivfr_launch_scan(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape shape, int w, const float* tau,
                      uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st,
-                     const uint32_t* tau_id = nullptr);
+                     const uint32_t* tau_id = nullptr, DirectPlace direct = DirectPlace());
 
 // Sample pass: the estimate of entry e < len_s[p] of pair p is written as a bare float at index soff[p] + e of
 // the query's buffer (no counters involved; only the values are needed to bound the k'-th smallest).  One wavefront per chunk of IVFR_SAMPLE_CHUNK entries; items[i] is the
@@ -450,7 +459,8 @@ bool ivfr_shared8h_supported(const ivfr_index* ix);
 int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const TableSrc& ts, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs,
                             ScanShape shape, int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay,
-                            hipStream_t st, const float* lut_scale = nullptr, const uint8_t* exact_only = nullptr);
+                            hipStream_t st, const float* lut_scale = nullptr, const uint8_t* exact_only = nullptr,
+                            DirectPlace direct = DirectPlace());
 int ivfr_launch_scan_shared8h(const ivfr_index* ix, const TableSrc& ts, const float* lut_scale,
                               const uint32_t* pair_start, const uint32_t* pair_len, const uint32_t* blkpre,
                               const uint32_t* unit_pairs, ScanShape shape, int w, const float* tau, uint2* cand,

@@ -88,7 +88,8 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
 
 // Variant for many short-list entries: the refinement codebook (256 d floats, 128 KB at d = 128) is
 // copied into LDS once per workgroup and the workgroups (one per compute unit, 1024 threads) walk over
-// blocks of 128 entries.  The codebook rows are short (d/m' floats), so gathering them through the
+// blocks of 128 entries, each workgroup over one contiguous range of blocks, so that consecutive blocks belong to
+// the same query and its vector stays in registers.  The codebook rows are short (d/m' floats), so gathering them through the
 // vector cache fetches whole 128-byte lines for 32 or 64 useful bytes, and that fill traffic from L2 is
 // what bounds the plain kernel when k' is large.  Arithmetic and summation order are the same.
 __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restrict__ queries, int d, int c, int m, int mr,
@@ -114,10 +115,11 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
     // younger ones in flight.
     struct Pos { int q, slot, n; uint32_t pos; };
     struct Gather { int32_t id; uint32_t list; uint32_t cb[4], rb[4]; };
+    const int64_t item_end = n_items * (int64_t)(blockIdx.x + 1) / (int64_t)gridDim.x;
     auto read_pos = [&](int64_t item) -> Pos {
         Pos r;
         r.q = 0; r.slot = 0; r.n = 0; r.pos = 0;
-        if (item < n_items) {
+        if (item < item_end) {
             r.q = q_base + (int)(item / per_q);
             r.slot = (int)(item % per_q) * 128 + g;
             r.n = short_n[r.q];
@@ -145,16 +147,26 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
         }
         return r;
     };
-    int64_t item = blockIdx.x;
-    Pos p0 = read_pos(item), p1 = read_pos(item + gridDim.x);
+    int64_t item = n_items * (int64_t)blockIdx.x / (int64_t)gridDim.x;
+    Pos p0 = read_pos(item), p1 = read_pos(item + 1);
     Gather g0 = gather(p0);
-    for (; item < n_items; item += gridDim.x) {
-        const Pos p2 = read_pos(item + 2 * (int64_t)gridDim.x);
+    float4 xr[4];   // this lane's pieces of the current query
+    int xq = -1;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) xr[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (; item < item_end; ++item) {
+        const Pos p2 = read_pos(item + 2);
         const Gather g1 = gather(p1);
+        if (p0.q != xq) {   // uniform over the workgroup
+            xq = p0.q;
+            const float* x = queries + (int64_t)xq * d;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (k < nit) xr[k] = *reinterpret_cast<const float4*>(x + 4 * t + 32 * k);
+        }
         const bool live = p0.slot < p0.n;
         float acc = 0.f;
         if (live) {
-            const float* x = queries + (int64_t)p0.q * d;
             const float* cl = coarse + (int64_t)g0.list * d;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -166,7 +178,7 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
                     y.x += pv.x; y.y += pv.y; y.z += pv.z; y.w += pv.w;
                     const float4 rv = *reinterpret_cast<const float4*>(s_rq + (jr * IVFR_KS + g0.rb[k]) * dsub_r + (e - jr * dsub_r));
                     y.x += rv.x; y.y += rv.y; y.z += rv.z; y.w += rv.w;
-                    const float4 xv = *reinterpret_cast<const float4*>(x + e);
+                    const float4 xv = xr[k];
                     const float a = xv.x - y.x, b = xv.y - y.y, cc = xv.z - y.z, dd = xv.w - y.w;
                     acc = fmaf(a, a, acc); acc = fmaf(b, b, acc); acc = fmaf(cc, cc, acc); acc = fmaf(dd, dd, acc);
                 }

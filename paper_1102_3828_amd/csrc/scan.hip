@@ -62,12 +62,15 @@ __global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restri
         }
         const uint32_t nb = (len + IVFR_BLOCK - 1) / IVFR_BLOCK, nbs = (ls + IVFR_SAMPLE_CHUNK - 1) / IVFR_SAMPLE_CHUNK;
         const uint32_t inc = wave_incl_scan(nb, lane), inc_s = wave_incl_scan(nbs, lane);
-        const uint32_t inc_e = wave_incl_scan(ls, lane);   // a query's sample stays below 2^32 entries (max_sample + w)
+        // entries before the pair in the query's buffer: of the sample (below 2^32: max_sample + w), or, for a
+        // query that keeps everything, of the lists themselves (at most full_limit)
+        const uint32_t le = fully ? len : ls;
+        const uint32_t inc_e = wave_incl_scan(le, lane);
         if (r < w) {
             const int64_t p = (int64_t)q * w + r;
             pb.blkpre[p] = carry + inc - nb;
             pb.blkpre_s[p] = carry_s + inc_s - nbs;
-            pb.soff[p] = carry_e + inc_e - ls;
+            pb.soff[p] = carry_e + inc_e - le;
         }
         carry += __shfl(inc, 63, 64);
         carry_s += __shfl(inc_s, 63, 64);
@@ -82,6 +85,7 @@ __global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restri
     pb.sq[q] = total;
     pb.nsample[q] = (uint32_t)(sampled > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : sampled);
     pb.fully[q] = fully ? 1 : 0;
+    if (fully) pb.cnt[q] = (uint32_t)total;   // its records are placed by position, not counted
     bool exact_only = true;
     const unsigned long long capv = ivfr_plan_capacity(total, sampled, qp, min_cap, kprime, half_frac, &exact_only);
     pb.exact_only[q] = exact_only ? 1 : 0;
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(256) void plan_expand_kernel(int P, int w, PlanBuff
     const int q = p / w;
     if (pb.status->pool_short) {   // void batch: every pair is empty, no query has a sample
         pb.len[p] = 0; pb.len_s[p] = 0; pb.blkpre[p] = 0; pb.blkpre_s[p] = 0;
-        if (p == q * w) pb.nsample[q] = 0;
+        if (p == q * w) { pb.nsample[q] = 0; pb.cnt[q] = 0; }
         return;
     }
     pb.blkpre[p] += pb.qblk[q];
@@ -174,7 +178,10 @@ int ivfr_launch_plan(const ivfr_index* ix, const int32_t* probe, int nq, int w, 
 // residuals in LDS, and each wavefront walks its share of the (j, 32-centroid tile) grid.
 // Negative round-off is clamped to zero (the quantity is a squared norm).
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void lut_mfma_kernel(const float* __restrict__ queries,
+// Sixteen wavefronts per workgroup: a wavefront's (j, tile) units are chains of dependent loads (codebook rows from
+// L2, then the matrix instructions, then the stores), so the latency is hidden by the number of wavefronts.
+#define LUT_T 1024
+__global__ __launch_bounds__(LUT_T) void lut_mfma_kernel(const float* __restrict__ queries,
                                                        const int32_t* __restrict__ probe, int P, int w, int d, int m,
                                                        int dsub, const float* __restrict__ coarse,
                                                        const float* __restrict__ pq, const float* __restrict__ pq_norm,
@@ -186,7 +193,7 @@ __global__ __launch_bounds__(256) void lut_mfma_kernel(const float* __restrict__
     float* rn = smem + 32 * stride;    // [32][m]
     const int p0 = blockIdx.x * 32;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < 32 * (d / 4); i += 256) {
+    for (int i = tid; i < 32 * (d / 4); i += LUT_T) {
         int pr = i / (d / 4), e = (i % (d / 4)) * 4;
         int p = p0 + pr;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -200,7 +207,7 @@ __global__ __launch_bounds__(256) void lut_mfma_kernel(const float* __restrict__
         *reinterpret_cast<float4*>(R + pr * stride + e) = v;
     }
     __syncthreads();
-    for (int i = tid; i < 32 * m; i += 256) {
+    for (int i = tid; i < 32 * m; i += LUT_T) {
         int pr = i / m, j = i % m;
         float s = 0.f;
         for (int e = 0; e < dsub; ++e) { float v = R[pr * stride + j * dsub + e]; s = fmaf(v, v, s); }
@@ -216,7 +223,7 @@ __global__ __launch_bounds__(256) void lut_mfma_kernel(const float* __restrict__
     }
     const int r = lane & 31, h = lane >> 5;
     const int ntile = m * 8;   // (j, 32-centroid tile) units
-    for (int u = wave; u < ntile; u += 4) {
+    for (int u = wave; u < ntile; u += LUT_T / 64) {
         const int j = u >> 3, nt = u & 7;
         floatx16 acc;
 #pragma unroll
@@ -280,7 +287,7 @@ int ivfr_launch_lut(const ivfr_index* ix, const float* queries, const int32_t* p
     if (P <= 0) return IVFR_OK;
     if (ix->dsub % 8 == 0) {
         size_t lds = (size_t)(32 * (d + 4) + 32 * m) * sizeof(float);
-        hipLaunchKernelGGL(lut_mfma_kernel, dim3((P + 31) / 32), dim3(256), lds, st, queries, probe, P, w, d, m,
+        hipLaunchKernelGGL(lut_mfma_kernel, dim3((P + 31) / 32), dim3(LUT_T), lds, st, queries, probe, P, w, d, m,
                            ix->dsub, ix->coarse, ix->pq, ix->pq_norm, ix->pq_maxnorm, lut, lut_scale);
     } else {
         hipLaunchKernelGGL(lut_direct_kernel, dim3(P), dim3(256), (size_t)d * sizeof(float), st, queries, probe, P, w,
@@ -586,7 +593,8 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                                                        const float* __restrict__ tau, uint2* __restrict__ cand,
                                                        uint32_t* __restrict__ cand_cnt, CandLayout lay,
                                                        const uint32_t* __restrict__ tau_id,
-                                                       const int32_t* __restrict__ ids, uint32_t id_stride) {
+                                                       const int32_t* __restrict__ ids, uint32_t id_stride,
+                                                       DirectPlace direct) {
     extern __shared__ float s_lut[];   // M * 256 floats, then the wavefronts' append queues
     WaveQueue wq;
     wq.est = reinterpret_cast<uint32_t*>(s_lut) + M * IVFR_KS + (threadIdx.x >> 6) * WQ_WORDS;
@@ -615,6 +623,8 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
         // with tau_id the bound is the 64-bit key (estimate, id): an estimate equal to tau passes only up to that id
         const uint32_t t_id = tau_id ? tau_id[q] : 0xFFFFFFFFu;
         const bool keep_all = t == INFINITY;
+        const bool placed = direct.fully && direct.fully[q];   // implies keep_all
+        const uint32_t place0 = placed ? direct.off[pid] : 0u;
         uint2* const qc[1] = {cand + lay.base(q)};
         const uint32_t cap[1] = {lay.cap(q)};
         uint32_t* const cnt[1] = {cand_cnt + q};
@@ -658,7 +668,11 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                     if (k0 && est0 == t) k0 = (uint32_t)ids[(size_t)(start + e0[u]) * id_stride] <= t_id;
                     if (k1 && est1 == t) k1 = (uint32_t)ids[(size_t)(start + e0[u] + 1) * id_stride] <= t_id;
                 }
-                if (keep_all) {   // nothing is filtered: a full wavefront of records per pass, one atomic for all of them
+                if (placed) {   // every entry has its own place: no counter
+                    const uint32_t s0 = place0 + e0[u];
+                    if (in0[u] && s0 < cap[0]) qc[0][s0] = make_uint2(__float_as_uint(est0), start + e0[u]);
+                    if (in1[u] && s0 + 1 < cap[0]) qc[0][s0 + 1] = make_uint2(__float_as_uint(est1), start + e0[u] + 1);
+                } else if (keep_all) {   // nothing is filtered: a full wavefront of records per pass, one atomic for all of them
                     append_records(k0, est0, start + e0[u], k1, est1, start + e0[u] + 1, qc[0], cnt[0], cap[0]);
                 } else {
                     if (wq.n > WQ_CAP - 128) wq_flush<1>(wq, qc, cnt, cap);
@@ -678,22 +692,24 @@ template <int M>
 static int launch_scan_m(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* pair_len,
                          const uint32_t* blkpre, const uint32_t* unit_pairs, const ScanShape& sh, int w,
                          const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st,
-                         const uint32_t* tau_id) {
+                         const uint32_t* tau_id, DirectPlace direct) {
     hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(sh.groups), dim3(256), scan_lds_bytes<M>(), st, ix->codes, ts,
                        pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min, w, tau, cand,
-                       cand_cnt, lay, tau_id, reinterpret_cast<const int32_t*>(ix->rec), (uint32_t)(ix->rec_stride / 4));
+                       cand_cnt, lay, tau_id, reinterpret_cast<const int32_t*>(ix->rec), (uint32_t)(ix->rec_stride / 4),
+                       direct);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
 
 int ivfr_launch_scan(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* pair_len,
                      const uint32_t* blkpre, const uint32_t* unit_pairs, ScanShape sh, int w, const float* tau,
-                     uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st, const uint32_t* tau_id) {
+                     uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st, const uint32_t* tau_id,
+                     DirectPlace direct) {
     if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
 #define IVFR_SCAN_CASE(MM)                                                                                     \
     case MM:                                                                                                   \
         return launch_scan_m<MM>(ix, ts, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, \
-                                 lay, st, tau_id)
+                                 lay, st, tau_id, direct)
     switch (ix->p.m) {
         IVFR_SCAN_CASE(4);
         IVFR_SCAN_CASE(8);
@@ -1102,7 +1118,8 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
                                                               uint2* __restrict__ cand,
                                                               uint32_t* __restrict__ cand_cnt, CandLayout lay,
                                                               const float* __restrict__ lut_scale,
-                                                              const uint8_t* __restrict__ exact_only) {
+                                                              const uint8_t* __restrict__ exact_only,
+                                                              DirectPlace direct) {
     typedef typename LutVec<G>::type vec_t;
     extern __shared__ float s_raw[];
     vec_t* s_lutv = reinterpret_cast<vec_t*>(s_raw);   // [M * 256] vectors: component x = query x of the unit
@@ -1131,6 +1148,8 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
         uint2* qc[G];
         uint32_t* cnt[G];
         uint32_t cap[G];
+        bool placed[G];      // the query keeps everything and every entry has its own place in its buffer
+        uint32_t place0[G];
 #pragma unroll
         for (int x = 0; x < G; ++x) {
             const uint32_t raw = unit_pairs[(int64_t)u * G + x];
@@ -1139,6 +1158,8 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
             pt[x] = ts.pair(pid[x]);
             const int q = (int)(pid[x] / w);
             t[x] = real ? tau[q] : -1.f;                                         // ... and never keeps anything
+            placed[x] = real && direct.fully && direct.fully[q];
+            place0[x] = placed[x] ? direct.off[pid[x]] : 0u;
             qc[x] = cand + lay.base(q);
             cap[x] = lay.cap(q);
             cnt[x] = cand_cnt + q;
@@ -1214,7 +1235,11 @@ __global__ __launch_bounds__(256) void adc_scan_shared_kernel(const uint8_t* __r
 #pragma unroll
                 for (int x = 0; x < G; ++x) {
                     const float ea = vget(a0, x) + vget(a1, x), eb = vget(b0, x) + vget(b1, x);
-                    if (t[x] == INFINITY) {   // nothing is filtered for this query: direct, one atomic per pass
+                    if (placed[x]) {
+                        const uint32_t s0 = place0[x] + e0[v];
+                        if (in0[v] && s0 < cap[x]) qc[x][s0] = make_uint2(__float_as_uint(ea), start + e0[v]);
+                        if (in1[v] && s0 + 1 < cap[x]) qc[x][s0 + 1] = make_uint2(__float_as_uint(eb), start + e0[v] + 1);
+                    } else if (t[x] == INFINITY) {   // nothing is filtered for this query: one atomic per pass
                         append_records(in0[v], ea, start + e0[v], in1[v], eb, start + e0[v] + 1, qc[x], cnt[x], cap[x]);
                     } else {
                         if (wq.n > WQ_CAP - 128) wq_flush<G>(wq, qc, cnt, cap);
@@ -1236,10 +1261,11 @@ template <int M, int G>
 static int launch_shared_mg(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs,
                             const ScanShape& sh, int w, const float* tau, uint2* cand, uint32_t* cand_cnt,
-                            CandLayout lay, hipStream_t st, const float* lut_scale, const uint8_t* exact_only) {
+                            CandLayout lay, hipStream_t st, const float* lut_scale, const uint8_t* exact_only,
+                            DirectPlace direct) {
     hipLaunchKernelGGL((adc_scan_shared_kernel<M, G>), dim3(sh.groups), dim3(256), (shared_lds_bytes<M, G>()), st,
                        ix->codes, ts, pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min,
-                       w, tau, cand, cand_cnt, lay, lut_scale, exact_only);
+                       w, tau, cand, cand_cnt, lay, lut_scale, exact_only, direct);
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -1249,10 +1275,10 @@ bool ivfr_shared_scan_supported(const ivfr_index* ix) { return ix->p.m <= 16; }
 int ivfr_launch_scan_shared(const ivfr_index* ix, int G, const TableSrc& ts, const uint32_t* pair_start,
                             const uint32_t* pair_len, const uint32_t* blkpre, const uint32_t* unit_pairs,
                             ScanShape sh, int w, const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay,
-                            hipStream_t st, const float* lut_scale, const uint8_t* exact_only) {
+                            hipStream_t st, const float* lut_scale, const uint8_t* exact_only, DirectPlace direct) {
     if (!sh.n_dev && sh.n_host <= 0) return IVFR_OK;
 #define IVFR_SH_ARGS \
-    ix, ts, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st, lut_scale, exact_only
+    ix, ts, pair_start, pair_len, blkpre, unit_pairs, sh, w, tau, cand, cand_cnt, lay, st, lut_scale, exact_only, direct
     if (G == 4) {
         switch (ix->p.m) {
             case 4: return launch_shared_mg<4, 4>(IVFR_SH_ARGS);

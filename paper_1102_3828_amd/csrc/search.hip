@@ -361,6 +361,10 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
     lay.off = pb.coff;
     lay.capq = pb.capq;
     uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + L.cnt);
+    pb.cnt = cnt;
+    DirectPlace direct;   // queries that keep everything: records by position
+    direct.fully = pb.fully;
+    direct.off = pb.soff;
     float* tau = reinterpret_cast<float*>(ws + L.tau);
     uint32_t* tau_id = reinterpret_cast<uint32_t*>(ws + L.tauid);
     uint32_t* spos = reinterpret_cast<uint32_t*>(ws + L.spos);
@@ -390,10 +394,15 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
     gb.blk64 = reinterpret_cast<uint32_t*>(ws + L.gblk64);
     gb.work = dstat->work;
     const float half_frac = IVFR_HALF_UNIT_FRAC;
-    const bool share = ix->share_lists >= 1 && ivfr_shared_scan_supported(ix);
-    const bool share8 = share && ix->share_lists >= 2 && ivfr_shared8h_supported(ix);
+    // Grouping the pairs by list and running four scans side by side costs about 0.15 ms per batch, which the
+    // shared scans only win back when the batch streams some 10^8 codes or more (measured: even at 3.8e8 codes per
+    // 1000 queries, ahead by a third at 1.3e9).  Left to itself the call shares lists from 3e8 expected codes.
+    int share_mode = ix->share_lists;
+    if (share_mode < 0) share_mode = (double)std::min<int64_t>(nq, B) * visit_est >= 3.0e8 ? 2 : 0;
+    const bool share = share_mode >= 1 && ivfr_shared_scan_supported(ix);
+    const bool share8 = share && share_mode >= 2 && ivfr_shared8h_supported(ix);
     // the matrix-core filter's error margin is derived for materialised tables: with split tables mode 3 acts as mode 2
-    const bool share64 = share8 && ix->share_lists >= 3 && ivfr_mfma_scan_supported(ix) && !split;
+    const bool share64 = share8 && share_mode >= 3 && ivfr_mfma_scan_supported(ix) && !split;
 
     // Launch shapes.  Every workgroup of a scan takes an equal share of the launch's 512-entry blocks; about 128
     // blocks per group of 256 threads (256 for the 512-thread scan of eight, 64 for the narrower kernels) balances
@@ -547,15 +556,15 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED, true, ix->side[0]));
             IVFR_TRY(ivfr_launch_scan_shared(ix, 4, tsrc, pb.pair_start, pb.len, gb.blk4, gb.unit4_pairs, s4, w,
                                              tau, cand, cnt, lay, ix->side[0], share8 ? lut_scale : nullptr,
-                                             share8 ? pb.exact_only : nullptr));
+                                             share8 ? pb.exact_only : nullptr, direct));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED, false, ix->side[0]));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED2, true, ix->side[1]));
             IVFR_TRY(ivfr_launch_scan_shared(ix, 2, tsrc, pb.pair_start, pb.len, gb.blk2, gb.unit2_pairs, s2, w,
-                                             tau, cand, cnt, lay, ix->side[1]));
+                                             tau, cand, cnt, lay, ix->side[1], nullptr, nullptr, direct));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN_SHARED2, false, ix->side[1]));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN, true, ix->side[2]));
             IVFR_TRY(ivfr_launch_scan(ix, tsrc, pb.pair_start, pb.len, gb.blklo, gb.lo_pairs, s1, w, tau, cand, cnt,
-                                      lay, ix->side[2]));
+                                      lay, ix->side[2], nullptr, direct));
             IVFR_TRY(mark_on(IVFR_STAGE_SCAN, false, ix->side[2]));
             for (int i = 0; i < n_side; ++i) {
                 IVFR_HIP(hipEventRecord(ix->ev_join[slot][i], ix->side[i]));
@@ -564,7 +573,8 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
         } else {
             const ScanShape s1 = shape_for(est_codes / IVFR_BLOCK + Pb, 64, nullptr, Pb);
             IVFR_TRY(mark(IVFR_STAGE_SCAN, true));
-            IVFR_TRY(ivfr_launch_scan(ix, tsrc, pb.pair_start, pb.len, pb.blkpre, nullptr, s1, w, tau, cand, cnt, lay, st));
+            IVFR_TRY(ivfr_launch_scan(ix, tsrc, pb.pair_start, pb.len, pb.blkpre, nullptr, s1, w, tau, cand, cnt, lay, st,
+                                      nullptr, direct));
             IVFR_TRY(mark(IVFR_STAGE_SCAN, false));
         }
         IVFR_TRY(mark(IVFR_STAGE_SHORTLIST, true));

@@ -7,19 +7,23 @@
 // every key distinct, so "the K smallest keys" is the K smallest distances with ties broken
 // towards the lowest index, exactly.
 //
-// Method: most-significant-digit radix select, 8 passes of 8 bits.  Each pass histograms the
-// digit of the keys that still match the prefix found so far (LDS atomics), a workgroup scan
-// finds the digit bucket that holds the K-th smallest, and the prefix grows by one byte.
-// After 8 passes the prefix is the K-th smallest key itself (the pivot); a last sweep emits
-// every key <= pivot.  (As soon as few keys still match the prefix they are sorted in LDS
-// instead, which ends the passes early.)  For short-list records the low half (the vector id) is fetched from
-// the id array only in passes 4-7 and only for records whose estimate equals the pivot's.
+// Method: the K-th smallest key (the pivot) is found by narrowing a range of distance words.  One sweep takes the
+// minimum and maximum word of the segment; each further sweep histograms the words inside the current range
+// into up to 1024 equal power-of-two bins (LDS atomics), a workgroup scan finds the bin that holds the K-th
+// smallest, and the range shrinks to that bin.  Starting at the minimum and maximum skips the leading bits that
+// all estimates of a query share, so one histogram sweep usually leaves a handful of keys; at most four are ever
+// needed for 32 bits.  The few keys left in the range are gathered into LDS with their index words and ranked by
+// counting.  Only if more than 512 keys share one distance word does the same narrowing go on over their index
+// words.  A last sweep by the caller emits every key <= pivot.  For short-list records the index word (the
+// vector id) is fetched from the record array only for the gathered keys.
 #include "ivfr_internal.h"
 
 #include <algorithm>
 
 #define SEL_T 512
-#define SEL_LCAP 2048
+#define SEL_BINS (2 * SEL_T)
+#define SEL_RC 512        // keys ranked by counting
+#define SEL_RANK_SORT 256 // results sorted by counting rather than by a bitonic network
 #define SORT_MAX 16384
 
 struct SegView {
@@ -51,160 +55,136 @@ __device__ __forceinline__ uint32_t seg_lo(const SegView& s, uint32_t pos) {
     return (s.keys || s.vals) ? pos : (uint32_t)s.ids[(size_t)pos * s.id_stride];
 }
 
-// Returns the K-th smallest key of the segment (1 <= K <= n).  All threads must call.
-// Radix passes run only while more than SEL_LCAP keys still match the prefix; the remaining
-// candidates are then gathered into LDS, sorted there, and the pivot is read off directly.
-__device__ uint64_t radix_pivot(const SegView& s, uint32_t K) {
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t wsum[SEL_T / 64];
-    __shared__ uint32_t s_bin, s_need, s_match, s_fill;
-    __shared__ uint64_t lbuf[SEL_LCAP];
-    const int tid = threadIdx.x;
-    uint64_t prefix = 0;
-    uint32_t need = K;
-    uint64_t nmatch = (uint64_t)s.n;
-    if (K <= SEL_T / 2 && s.n > SEL_LCAP) {
-        // Small K: every thread takes the minimum distance word of its strided share; the K-th
-        // smallest of those SEL_T minima bounds the K-th smallest key from above, and at least K
-        // keys lie at or below it.  Those few keys are gathered and sorted in LDS: two sweeps.
-        uint32_t mn = 0xFFFFFFFFu;
-        for (int64_t i = tid; i < s.n; i += SEL_T) {
-            uint32_t pos;
-            uint32_t hi = seg_hi(s, i, &pos);
-            mn = hi < mn ? hi : mn;
-        }
-        lbuf[tid] = mn;
-        __syncthreads();
-        for (uint32_t k = 2; k <= SEL_T; k <<= 1)
-            for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-                uint32_t i = tid, ixj = i ^ j;
-                if (ixj > i) {
-                    uint64_t a = lbuf[i], b = lbuf[ixj];
-                    bool asc = (i & k) == 0;
-                    if ((a > b) == asc) { lbuf[i] = b; lbuf[ixj] = a; }
-                }
-                __syncthreads();
-            }
-        const uint32_t bound = (uint32_t)lbuf[K - 1];
-        __syncthreads();
-        if (tid == 0) s_fill = 0;
-        __syncthreads();
-        for (int64_t i = tid; i < s.n; i += SEL_T) {
-            uint32_t pos;
-            uint32_t hi = seg_hi(s, i, &pos);
-            if (hi <= bound) {
-                uint32_t slot = atomicAdd(&s_fill, 1u);
-                if (slot < SEL_LCAP) lbuf[slot] = ((uint64_t)hi << 32) | seg_lo(s, pos);
-            }
-        }
-        __syncthreads();
-        const uint32_t got = s_fill;
-        __syncthreads();
-        if (got <= SEL_LCAP) {
-            uint32_t n2 = 2;
-            while (n2 < got) n2 <<= 1;
-            for (uint32_t i = got + tid; i < n2; i += SEL_T) lbuf[i] = ~0ull;
-            __syncthreads();
-            for (uint32_t k = 2; k <= n2; k <<= 1)
-                for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-                    for (uint32_t i = tid; i < n2; i += SEL_T) {
-                        uint32_t ixj = i ^ j;
-                        if (ixj > i) {
-                            uint64_t a = lbuf[i], b = lbuf[ixj];
-                            bool asc = (i & k) == 0;
-                            if ((a > b) == asc) { lbuf[i] = b; lbuf[ixj] = a; }
-                        }
-                    }
-                    __syncthreads();
-                }
-            const uint64_t pivot = lbuf[K - 1];
-            __syncthreads();
-            return pivot;
-        }
-        // too many equal distance words: fall through to the radix passes
+struct SelShared {
+    uint32_t hist[SEL_BINS];
+    uint64_t cand[SEL_RC];
+    uint32_t wa[SEL_T / 64], wb[SEL_T / 64];
+    uint32_t bin, need, cnt, fill;
+    uint64_t pivot;
+};
+
+// Narrows [lo, hi] around the need-th smallest of the words word(i, &v) yields (false = element not taken part),
+// until at most SEL_RC words are left in the range or the range is a single value.  count is the number of words
+// on entry and in the final range on return; need becomes the rank inside the final range.  All threads call.
+template <class F>
+__device__ void narrow_range(SelShared& sh, F word, int64_t n, uint32_t& lo, uint32_t& hi, uint32_t& need,
+                             uint64_t& count) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    uint32_t mn = 0xFFFFFFFFu, mx = 0u;
+    for (int64_t i = tid; i < n; i += SEL_T) {
+        uint32_t v;
+        if (word(i, &v)) { mn = v < mn ? v : mn; mx = v > mx ? v : mx; }
     }
-    int pass = 0;
-    for (; pass < 8 && nmatch > SEL_LCAP; ++pass) {
-        const int shift = 56 - 8 * pass;
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
-        const uint32_t pre_hi = (pass >= 4) ? (uint32_t)(prefix >> (8 * (pass - 4))) : 0u;
-        for (int64_t i = tid; i < s.n; i += SEL_T) {
-            uint32_t pos;
-            uint32_t hi = seg_hi(s, i, &pos);
-            if (pass < 4) {
-                uint64_t key = (uint64_t)hi << 32;
-                if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1u);
-            } else if (hi == pre_hi) {
-                uint64_t key = ((uint64_t)hi << 32) | seg_lo(s, pos);
-                if ((key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1u);
-            }
-        }
-        __syncthreads();
-        // inclusive scan of the 256 buckets by the first 256 threads
-        uint32_t h = 0, inc = 0;
-        if (tid < 256) {
-            h = hist[tid];
-            inc = h;
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                uint32_t o = __shfl_up(inc, off, 64);
-                if ((tid & 63) >= off) inc += o;
-            }
-            if ((tid & 63) == 63) wsum[tid >> 6] = inc;
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t a = __shfl_xor(mn, off, 64), b = __shfl_xor(mx, off, 64);
+        mn = a < mn ? a : mn;
+        mx = b > mx ? b : mx;
+    }
+    if (lane == 0) { sh.wa[wv] = mn; sh.wb[wv] = mx; }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < SEL_T / 64; ++i) {
+        mn = sh.wa[i] < mn ? sh.wa[i] : mn;
+        mx = sh.wb[i] > mx ? sh.wb[i] : mx;
+    }
+    __syncthreads();   // wa is used again below
+    lo = mn;
+    hi = mx;
+    // each pass leaves a span below 2^shift <= span / 512: four passes reach a single value from any 32-bit span
+    for (int pass = 0; pass < 4 && count > SEL_RC && hi > lo; ++pass) {
+        const uint32_t span = hi - lo;
+        int shift = 0;
+        while ((span >> shift) >= SEL_BINS) ++shift;
+        for (int i = tid; i < SEL_BINS; i += SEL_T) sh.hist[i] = 0;
+        __syncthreads();
+        for (int64_t i = tid; i < n; i += SEL_T) {
+            uint32_t v;
+            if (word(i, &v) && v >= lo && v <= hi) atomicAdd(&sh.hist[(v - lo) >> shift], 1u);
         }
         __syncthreads();
-        if (tid < 256) {
-            uint32_t add = 0;
-            for (int wv = 0; wv < (tid >> 6); ++wv) add += wsum[wv];
-            inc += add;
-            uint32_t exc = inc - h;
-            if (exc < need && need <= inc) { s_bin = (uint32_t)tid; s_need = need - exc; s_match = h; }
+        // two bins per thread; inclusive scan over the workgroup
+        const uint32_t a = sh.hist[2 * tid], b = sh.hist[2 * tid + 1];
+        uint32_t inc = a + b;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t o = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += o;
+        }
+        if (lane == 63) sh.wa[wv] = inc;
+        __syncthreads();
+        uint32_t exc = inc - (a + b);
+        for (int i = 0; i < wv; ++i) exc += sh.wa[i];
+        if (exc < need && need <= exc + a) {
+            sh.bin = 2u * tid; sh.need = need - exc; sh.cnt = a;
+        } else if (exc + a < need && need <= exc + a + b) {
+            sh.bin = 2u * tid + 1u; sh.need = need - exc - a; sh.cnt = b;
         }
         __syncthreads();
-        prefix = (prefix << 8) | s_bin;
-        need = s_need;
-        nmatch = s_match;
+        const uint32_t nlo = lo + (sh.bin << shift);
+        const uint64_t nhi = (uint64_t)nlo + ((1ull << shift) - 1ull);
+        hi = nhi < (uint64_t)hi ? (uint32_t)nhi : hi;
+        lo = nlo;
+        need = sh.need;
+        count = sh.cnt;
         __syncthreads();
     }
-    if (pass == 8) return prefix;
-    // gather the keys whose top `pass` bytes equal the prefix
-    if (tid == 0) s_fill = 0;
+}
+
+// Returns the K-th smallest key of the segment (1 <= K <= n).  All threads must call; ends with a barrier.
+__device__ uint64_t kth_key(const SegView& s, uint32_t K) {
+    __shared__ SelShared sh;
+    const int tid = threadIdx.x;
+    uint32_t need = K;
+    uint64_t count = (uint64_t)s.n;
+    uint32_t lo = 0u, hi = 0xFFFFFFFFu, lo2 = 0u, hi2 = 0xFFFFFFFFu;
+    bool by_index = false;
+    if (count > SEL_RC) {
+        auto dist_word = [&](int64_t i, uint32_t* v) {
+            uint32_t pos;
+            *v = seg_hi(s, i, &pos);
+            return true;
+        };
+        narrow_range(sh, dist_word, s.n, lo, hi, need, count);
+        if (count > SEL_RC) {   // lo == hi: that many keys share the distance word, their index words decide
+            by_index = true;
+            const uint32_t fixed = lo;
+            auto index_word = [&](int64_t i, uint32_t* v) {
+                uint32_t pos;
+                if (seg_hi(s, i, &pos) != fixed) return false;
+                *v = seg_lo(s, pos);
+                return true;
+            };
+            narrow_range(sh, index_word, s.n, lo2, hi2, need, count);
+            if (count > SEL_RC) return ((uint64_t)fixed << 32) | lo2;   // equal keys throughout
+        }
+    }
+    if (tid == 0) sh.fill = 0;
     __syncthreads();
     for (int64_t i = tid; i < s.n; i += SEL_T) {
         uint32_t pos;
-        uint32_t hi = seg_hi(s, i, &pos);
-        bool match;
-        if (pass == 0) match = true;
-        else if (pass <= 4) match = (hi >> (32 - 8 * pass)) == (uint32_t)prefix;
-        else match = hi == (uint32_t)(prefix >> (8 * (pass - 4)));
-        if (match) {
-            uint64_t key = ((uint64_t)hi << 32) | seg_lo(s, pos);
-            if (pass > 4 && (key >> (64 - 8 * pass)) != prefix) continue;
-            uint32_t slot = atomicAdd(&s_fill, 1u);
-            if (slot < SEL_LCAP) lbuf[slot] = key;
-        }
+        const uint32_t h = seg_hi(s, i, &pos);
+        if (h < lo || h > hi) continue;
+        const uint32_t l = seg_lo(s, pos);
+        if (by_index && (l < lo2 || l > hi2)) continue;
+        const uint32_t slot = atomicAdd(&sh.fill, 1u);
+        if (slot < SEL_RC) sh.cand[slot] = ((uint64_t)h << 32) | l;
     }
     __syncthreads();
-    const uint32_t mcount = s_fill < SEL_LCAP ? s_fill : SEL_LCAP;
-    uint32_t n2 = 2;
-    while (n2 < mcount) n2 <<= 1;
-    for (uint32_t i = mcount + tid; i < n2; i += SEL_T) lbuf[i] = ~0ull;
-    __syncthreads();
-    for (uint32_t k = 2; k <= n2; k <<= 1) {
-        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            for (uint32_t i = tid; i < n2; i += SEL_T) {
-                uint32_t ixj = i ^ j;
-                if (ixj > i) {
-                    uint64_t a = lbuf[i], b = lbuf[ixj];
-                    bool asc = (i & k) == 0;
-                    if ((a > b) == asc) { lbuf[i] = b; lbuf[ixj] = a; }
-                }
-            }
-            __syncthreads();
+    const uint32_t got = sh.fill < SEL_RC ? sh.fill : SEL_RC;
+    if ((uint32_t)tid < got) {
+        // the key with fewer than `need` keys below it and at least `need` at or below it (equal keys agree)
+        const uint64_t key = sh.cand[tid];
+        uint32_t lt = 0, le = 0;
+        for (uint32_t j = 0; j < got; ++j) {
+            const uint64_t kj = sh.cand[j];
+            lt += kj < key ? 1u : 0u;
+            le += kj <= key ? 1u : 0u;
         }
+        if (lt < need && need <= le) sh.pivot = key;
     }
-    const uint64_t pivot = lbuf[need - 1];
+    __syncthreads();
+    const uint64_t pivot = sh.pivot;
     __syncthreads();
     return pivot;
 }
@@ -252,7 +232,7 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
             s.vals = reinterpret_cast<const uint32_t*>(recs);
             s.base = 2 * (int64_t)lay.base(seg);
         }
-        uint64_t pivot = radix_pivot(s, (uint32_t)r);   // ends with a barrier: its LDS state is free for the next segment
+        uint64_t pivot = kth_key(s, (uint32_t)r);   // ends with a barrier: its LDS state is free for the next segment
         if (threadIdx.x == 0) {
             tau[seg] = __uint_as_float((uint32_t)(pivot >> 32));
             if (tau_id) tau_id[seg] = (uint32_t)pivot;
@@ -312,7 +292,7 @@ __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs
         if (threadIdx.x == 0) out_n[q] = (int32_t)n;
         return;
     }
-    const uint64_t pivot = radix_pivot(s, (uint32_t)K);
+    const uint64_t pivot = kth_key(s, (uint32_t)K);
     const uint32_t p_hi = (uint32_t)(pivot >> 32), p_lo = (uint32_t)pivot;
     for (int64_t i = threadIdx.x; i < n; i += SEL_T) {
         uint2 r = recs[s.base + i];
@@ -354,7 +334,7 @@ __global__ __launch_bounds__(SEL_T) void select_sorted_kernel(const uint64_t* ke
         for (int64_t i = threadIdx.x; i < n; i += SEL_T) sk[i] = keys[s.base + i];
         m_out = (int)n;
     } else {
-        const uint64_t pivot = radix_pivot(s, (uint32_t)K);
+        const uint64_t pivot = kth_key(s, (uint32_t)K);
         for (int64_t i = threadIdx.x; i < n; i += SEL_T) {
             uint64_t k = keys[s.base + i];
             if (k <= pivot) {
@@ -365,6 +345,29 @@ __global__ __launch_bounds__(SEL_T) void select_sorted_kernel(const uint64_t* ke
         m_out = K;
     }
     __syncthreads();
+    if (n2 <= SEL_RANK_SORT) {
+        // few results: every key counts the keys before it and goes straight to its place
+        const int m_have = n <= K ? m_out : (int)(s_slot < (uint32_t)n2 ? s_slot : (uint32_t)n2);
+        for (int i = threadIdx.x; i < m_have; i += SEL_T) {
+            const uint64_t key = sk[i];
+            int r = 0;
+            for (int j = 0; j < m_have; ++j) {
+                const uint64_t kj = sk[j];
+                r += (kj < key || (kj == key && j < i)) ? 1 : 0;
+            }
+            if (r < m_out) {
+                const int64_t o = (int64_t)q * K + r;
+                out_lo[o] = (int32_t)(uint32_t)key;
+                out_hi[o] = __uint_as_float((uint32_t)(key >> 32));
+            }
+        }
+        for (int i = m_out + threadIdx.x; i < K; i += SEL_T) {
+            const int64_t o = (int64_t)q * K + i;
+            out_lo[o] = -1;
+            out_hi[o] = INFINITY;
+        }
+        return;
+    }
     for (int k = 2; k <= n2; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
             for (int i = threadIdx.x; i < n2; i += SEL_T) {

@@ -23,6 +23,9 @@ def gpu_index_from_oracle(index, d=None):
     ix = pkg.Index(dd, c, b.pq.shape[0], b.m_refine)
     ix.set_codebooks(b.coarse, b.pq, b.rq)
     ix.import_(index.list_offsets, index.ids, index.codes, index.rcodes)
+    # Left to itself the library scans batches this small pair by pair; the tests want the shared-list scans
+    # (units of eight, four, two) exercised on every small case as well, so they ask for them.
+    ix.set_list_sharing(2)
     return ix
 
 
@@ -287,11 +290,14 @@ def _full_size_case(name, n_check, also=(), **override):
         assert all(len(set(r.tolist())) == k for r in gi[:50])
         # every (query, list) pair scanned on its own, and the matrix-core units, must give the same bits for the
         # whole batch
-        for mode in (0, 3):
+        for mode in (0, 3, -1):
             ix.set_list_sharing(mode)
             p_ids, p_dist = ix.search(xq, cfg.w, kp, k)
             log(name, "sharing mode", mode, ix.search_stats())
             assert np.array_equal(p_ids.cpu().numpy(), gi) and np.array_equal(p_dist.cpu().numpy(), gd)
+            if mode == -1:   # left to itself the library shares lists when it expects the batch to stream 3e8 codes
+                if st["codes_scanned"] >= 1.0e9: assert ix.search_stats()["codes_scanned_shared8"] > 0
+                if st["codes_scanned"] <= 1.0e8: assert ix.search_stats()["codes_scanned_shared8"] == 0
         ix.set_list_sharing(2)
         if s["whole"] and cfg.n_query > B:
             # the workload's whole query set in one call (more queries share every list): same bits for the first
@@ -448,6 +454,23 @@ def test_encode_parity_with_oracle_codebooks():
 
 
 # ------------------------------------------------------------------ edge cases and host logic
+
+def test_automatic_sharing_scans_small_batches_pair_by_pair():
+    wl = tiny_workload(d=64, m=8, m_refine=16, c=24, N=5000, n_train=3000)
+    index, X = wl["index"], wl["X"]
+    ix = gpu_index_from_oracle(index)
+    xq = queries_dev(X)
+    shared = ix.search(xq, 6, 300, 20)
+    assert ix.search_stats()["codes_scanned_shared"] > 0
+    ix.set_list_sharing(-1)   # the library's default
+    auto = ix.search(xq, 6, 300, 20)
+    st = ix.search_stats()
+    assert st["codes_scanned_shared"] == 0 and st["codes_scanned_shared8"] == 0
+    assert st["codes_streamed"] == st["codes_scanned"]
+    assert np.array_equal(shared[0].cpu().numpy(), auto[0].cpu().numpy())
+    assert np.array_equal(shared[1].cpu().numpy(), auto[1].cpu().numpy())
+    ix.close()
+
 
 def test_edge_cases_and_internal_paths():
     wl = tiny_workload(d=64, m=8, m_refine=16, c=24, N=5000, n_train=3000)
