@@ -15,7 +15,9 @@
 // needed for 32 bits.  The few keys left in the range are gathered into LDS with their index words and ranked by
 // counting.  Only if more than 512 keys share one distance word does the same narrowing go on over their index
 // words.  A last sweep by the caller emits every key <= pivot.  For short-list records the index word (the
-// vector id) is fetched from the record array only for the gathered keys.
+// vector id) is fetched from the record array only for the gathered keys.  When few keys are wanted out of many
+// (K <= 256 of more than 4096: the bound from the sample, the visited lists, the final top-k) the range comes from
+// one sweep instead of two: the K-th smallest of the 512 per-thread minima is an upper bound with few keys below it.
 #include "ivfr_internal.h"
 
 #include <algorithm>
@@ -64,11 +66,11 @@ struct SelShared {
 };
 
 // Narrows [lo, hi] around the need-th smallest of the words word(i, &v) yields (false = element not taken part),
-// until at most SEL_RC words are left in the range or the range is a single value.  count is the number of words
+// until at most `stop` words are left in the range or the range is a single value.  count is the number of words
 // on entry and in the final range on return; need becomes the rank inside the final range.  All threads call.
 template <class F>
 __device__ void narrow_range(SelShared& sh, F word, int64_t n, uint32_t& lo, uint32_t& hi, uint32_t& need,
-                             uint64_t& count) {
+                             uint64_t& count, uint32_t stop = SEL_RC) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     uint32_t mn = 0xFFFFFFFFu, mx = 0u;
     for (int64_t i = tid; i < n; i += SEL_T) {
@@ -92,7 +94,7 @@ __device__ void narrow_range(SelShared& sh, F word, int64_t n, uint32_t& lo, uin
     lo = mn;
     hi = mx;
     // each pass leaves a span below 2^shift <= span / 512: four passes reach a single value from any 32-bit span
-    for (int pass = 0; pass < 4 && count > SEL_RC && hi > lo; ++pass) {
+    for (int pass = 0; pass < 4 && count > stop && hi > lo; ++pass) {
         const uint32_t span = hi - lo;
         int shift = 0;
         while ((span >> shift) >= SEL_BINS) ++shift;
@@ -135,6 +137,68 @@ __device__ void narrow_range(SelShared& sh, F word, int64_t n, uint32_t& lo, uin
 __device__ uint64_t kth_key(const SegView& s, uint32_t K) {
     __shared__ SelShared sh;
     const int tid = threadIdx.x;
+    // keys with distance word in [lo, hi] (and, with by_index, index word in [lo2, hi2]) go to LDS; returns how many
+    // there were (only the first SEL_RC are kept)
+    auto gather = [&](uint32_t lo, uint32_t hi, bool by_index, uint32_t lo2, uint32_t hi2) -> uint32_t {
+        if (tid == 0) sh.fill = 0;
+        __syncthreads();
+        for (int64_t i = tid; i < s.n; i += SEL_T) {
+            uint32_t pos;
+            const uint32_t h = seg_hi(s, i, &pos);
+            if (h < lo || h > hi) continue;
+            const uint32_t l = seg_lo(s, pos);
+            if (by_index && (l < lo2 || l > hi2)) continue;
+            const uint32_t slot = atomicAdd(&sh.fill, 1u);
+            if (slot < SEL_RC) sh.cand[slot] = ((uint64_t)h << 32) | l;
+        }
+        __syncthreads();
+        const uint32_t got = sh.fill;
+        __syncthreads();
+        return got;
+    };
+    // the need-th smallest of the got <= SEL_RC gathered keys, by counting: the key with fewer than `need` keys below
+    // it and at least `need` at or below it (equal keys agree)
+    auto ranked = [&](uint32_t got, uint32_t need) -> uint64_t {
+        if ((uint32_t)tid < got) {
+            const uint64_t key = sh.cand[tid];
+            uint32_t lt = 0, le = 0;
+            for (uint32_t j = 0; j < got; ++j) {
+                const uint64_t kj = sh.cand[j];
+                lt += kj < key ? 1u : 0u;
+                le += kj <= key ? 1u : 0u;
+            }
+            if (lt < need && need <= le) sh.pivot = key;
+        }
+        __syncthreads();
+        const uint64_t pivot = sh.pivot;
+        __syncthreads();
+        return pivot;
+    };
+    if (K <= SEL_T / 2 && s.n > 8 * SEL_T) {
+        // Few of many: every thread takes the minimum distance word of its strided share; the K-th smallest of those
+        // SEL_T minima bounds the K-th smallest key from above, and at least K keys (a few more as a rule) lie at or
+        // below it.  One sweep for the minima, one to gather those keys; the bound itself is found by narrowing over
+        // the minima in LDS.
+        uint32_t* mins = reinterpret_cast<uint32_t*>(sh.cand);
+        uint32_t mn = 0xFFFFFFFFu;
+        for (int64_t i = tid; i < s.n; i += SEL_T) {
+            uint32_t pos;
+            const uint32_t h = seg_hi(s, i, &pos);
+            mn = h < mn ? h : mn;
+        }
+        mins[tid] = mn;
+        __syncthreads();
+        auto min_word = [&](int64_t i, uint32_t* v) {
+            *v = mins[i];
+            return true;
+        };
+        uint32_t mlo = 0u, bound = 0xFFFFFFFFu, mneed = K;
+        uint64_t mcount = SEL_T;
+        narrow_range(sh, min_word, SEL_T, mlo, bound, mneed, mcount, 1u);   // ends with a barrier: mins may be overwritten
+        const uint32_t got = gather(0u, bound, false, 0u, 0u);
+        if (got <= SEL_RC) return ranked(got, K);
+        // a crowd of equal distance words at the bound: the general way
+    }
     uint32_t need = K;
     uint64_t count = (uint64_t)s.n;
     uint32_t lo = 0u, hi = 0xFFFFFFFFu, lo2 = 0u, hi2 = 0xFFFFFFFFu;
@@ -159,34 +223,9 @@ __device__ uint64_t kth_key(const SegView& s, uint32_t K) {
             if (count > SEL_RC) return ((uint64_t)fixed << 32) | lo2;   // equal keys throughout
         }
     }
-    if (tid == 0) sh.fill = 0;
-    __syncthreads();
-    for (int64_t i = tid; i < s.n; i += SEL_T) {
-        uint32_t pos;
-        const uint32_t h = seg_hi(s, i, &pos);
-        if (h < lo || h > hi) continue;
-        const uint32_t l = seg_lo(s, pos);
-        if (by_index && (l < lo2 || l > hi2)) continue;
-        const uint32_t slot = atomicAdd(&sh.fill, 1u);
-        if (slot < SEL_RC) sh.cand[slot] = ((uint64_t)h << 32) | l;
-    }
-    __syncthreads();
-    const uint32_t got = sh.fill < SEL_RC ? sh.fill : SEL_RC;
-    if ((uint32_t)tid < got) {
-        // the key with fewer than `need` keys below it and at least `need` at or below it (equal keys agree)
-        const uint64_t key = sh.cand[tid];
-        uint32_t lt = 0, le = 0;
-        for (uint32_t j = 0; j < got; ++j) {
-            const uint64_t kj = sh.cand[j];
-            lt += kj < key ? 1u : 0u;
-            le += kj <= key ? 1u : 0u;
-        }
-        if (lt < need && need <= le) sh.pivot = key;
-    }
-    __syncthreads();
-    const uint64_t pivot = sh.pivot;
-    __syncthreads();
-    return pivot;
+    uint32_t got = gather(lo, hi, by_index, lo2, hi2);
+    got = got < SEL_RC ? got : SEL_RC;
+    return ranked(got, need);
 }
 
 __device__ __forceinline__ int64_t seg_count(const uint32_t* counts, uint32_t cap, int seg, bool* over) {
