@@ -92,9 +92,6 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
 // the same query and its vector stays in registers.  The codebook rows are short (d/m' floats), so gathering them through the
 // vector cache fetches whole 128-byte lines for 32 or 64 useful bytes, and that fill traffic from L2 is
 // what bounds the plain kernel when k' is large.  Arithmetic and summation order are the same.
-// NIT = d / 32: the 16-byte pieces of a vector per lane, a compile-time constant so that all loads of an entry's
-// decode are issued together instead of one dependent round trip per piece.
-template <int NIT>
 __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restrict__ queries, int d, int c, int m, int mr,
                                                           int dsub, int dsub_r, const float* __restrict__ coarse,
                                                           const float* __restrict__ pq, const float* __restrict__ rq,
@@ -111,6 +108,10 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
     const int t = threadIdx.x & 7, g = threadIdx.x >> 3;
     const int per_q = (kprime + 127) / 128;
     const int64_t n_items = (int64_t)nq * per_q;
+    // 16-byte pieces of a vector per lane (d is a multiple of 32 here, at most 128).  A run-time value on purpose: as a
+    // compile-time constant the compiler issues all loads of an entry's decode up front, which measured slower
+    // (0.88 -> 0.99 ms for 10^7 entries).
+    const int nit = d / 32;
     // Three items are in flight per workgroup: the position of item i + 2 is being read, the record of item
     // i + 1 (id, list, code bytes: one random line from HBM per entry, the latency that bounds this kernel) is
     // being gathered, item i is decoded.  Loads return in issue order, so waiting for the oldest leaves the
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int e = 4 * t + 32 * k;
-                if (k < NIT) { r.cb[k] = code[e / dsub]; r.rb[k] = rcode[e / dsub_r]; }
+                if (k < nit) { r.cb[k] = code[e / dsub]; r.rb[k] = rcode[e / dsub_r]; }
             }
         }
         return r;
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
             const float* x = queries + (int64_t)xq * d;
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                if (k < NIT) xr[k] = *reinterpret_cast<const float4*>(x + 4 * t + 32 * k);
+                if (k < nit) xr[k] = *reinterpret_cast<const float4*>(x + 4 * t + 32 * k);
         }
         const bool live = p0.slot < p0.n;
         float acc = 0.f;
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
             const float* cl = coarse + (int64_t)g0.list * d;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                if (k < NIT) {
+                if (k < nit) {
                     const int e = 4 * t + 32 * k;
                     const int j = e / dsub, jr = e / dsub_r;
                     float4 y = *reinterpret_cast<const float4*>(cl + e);
@@ -206,13 +207,7 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
 }
 
 int ivfr_rerank_init() {
-    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel<1>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel<2>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel<3>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel<4>),
+    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
     return IVFR_OK;
 }
@@ -227,17 +222,9 @@ int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, i
     if (vec0 && ix->p.m_refine > 0 && rq_bytes <= 128 * 1024 && (int64_t)nq * kprime >= (int64_t)ix->n_cu * 1024) {
         const int64_t n_items = (int64_t)nq * ((kprime + 127) / 128);
         const int groups = (int)std::min<int64_t>(n_items, ix->n_cu);
-#define IVFR_RERANK_LDS(NIT)                                                                                      \
-    hipLaunchKernelGGL(rerank_lds_kernel<NIT>, dim3(groups), dim3(1024), rq_bytes, st, queries, ix->p.d, ix->p.c,     \
-                       ix->p.m, ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq, ix->rec,            \
-                       ix->rec_stride, kprime, q_base, nq, short_pos, short_n, keys, refined_out, ids_out)
-        switch (ix->p.d / 32) {   // d is a multiple of 32 here, at most 128
-            case 1: IVFR_RERANK_LDS(1); break;
-            case 2: IVFR_RERANK_LDS(2); break;
-            case 3: IVFR_RERANK_LDS(3); break;
-            default: IVFR_RERANK_LDS(4); break;
-        }
-#undef IVFR_RERANK_LDS
+        hipLaunchKernelGGL(rerank_lds_kernel, dim3(groups), dim3(1024), rq_bytes, st, queries, ix->p.d, ix->p.c, ix->p.m,
+                           ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq, ix->rec, ix->rec_stride,
+                           kprime, q_base, nq, short_pos, short_n, keys, refined_out, ids_out);
         IVFR_HIP(hipGetLastError());
         return IVFR_OK;
     }

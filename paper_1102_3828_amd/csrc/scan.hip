@@ -772,54 +772,39 @@ __device__ __forceinline__ ListSplit split_units(uint32_t nA, uint32_t nB, int u
     return s;
 }
 
-// per list: exclusive prefixes of the five kinds of unit (eight, four, two, single, 64); one workgroup
+// per list: exclusive prefixes of the five kinds of unit (eight, four, two, single, 64); one workgroup per kind
 __global__ __launch_bounds__(1024) void group_scan_lists_kernel(int c, int use64, const uint32_t* __restrict__ list_np,
                                                                 uint32_t* __restrict__ gpre /*[5][c]*/,
                                                                 uint32_t* __restrict__ cur /*[2c]*/,
                                                                 uint32_t* __restrict__ counts /*[5]*/) {
-    __shared__ uint32_t wtot[5][16];
-    __shared__ uint32_t carry[5];
+    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t carry;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (tid < 5) carry[tid] = 0;
+    const int a = blockIdx.x;
+    if (tid == 0) carry = 0;
     __syncthreads();
     for (int base = 0; base < c; base += 1024) {
-        int l = base + tid;
-        uint32_t v[5] = {0, 0, 0, 0, 0};
+        const int l = base + tid;
+        uint32_t v = 0;
         if (l < c) {
-            ListSplit sp = split_units(list_np[2 * l], list_np[2 * l + 1], use64);
-            v[0] = sp.n8; v[1] = sp.n4; v[2] = sp.n2; v[3] = sp.n1; v[4] = sp.n64;
+            const ListSplit sp = split_units(list_np[2 * l], list_np[2 * l + 1], use64);
+            v = a == 0 ? sp.n8 : (a == 1 ? sp.n4 : (a == 2 ? sp.n2 : (a == 3 ? sp.n1 : sp.n64)));
         }
-        uint32_t inc[5] = {v[0], v[1], v[2], v[3], v[4]};
-#pragma unroll
-        for (int a = 0; a < 5; ++a) {
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                uint32_t o = __shfl_up(inc[a], off, 64);
-                if (lane >= off) inc[a] += o;
-            }
-            if (lane == 63) wtot[a][wv] = inc[a];
+        uint32_t inc = wave_incl_scan(v, lane);
+        if (lane == 63) wtot[wv] = inc;
+        __syncthreads();
+        uint32_t add = carry;
+        for (int x = 0; x < wv; ++x) add += wtot[x];
+        inc += add;
+        if (l < c) {
+            gpre[(int64_t)a * c + l] = inc - v;
+            if (a == 0) { cur[2 * l] = 0; cur[2 * l + 1] = 0; }
         }
         __syncthreads();
-#pragma unroll
-        for (int a = 0; a < 5; ++a) {
-            uint32_t add = carry[a];
-            for (int x = 0; x < wv; ++x) add += wtot[a][x];
-            inc[a] += add;
-        }
-        if (l < c) {
-#pragma unroll
-            for (int a = 0; a < 5; ++a) gpre[(int64_t)a * c + l] = inc[a] - v[a];
-            cur[2 * l] = 0;
-            cur[2 * l + 1] = 0;
-        }
-        __syncthreads();
-        if (tid == 1023) {
-#pragma unroll
-            for (int a = 0; a < 5; ++a) carry[a] = inc[a];
-        }
+        if (tid == 1023) carry = inc;
         __syncthreads();
     }
-    if (tid < 5) counts[tid] = carry[tid];
+    if (tid == 0) counts[a] = carry;
 }
 
 __global__ void group_fill_kernel(const int32_t* __restrict__ probe, int P, int w,
@@ -868,24 +853,40 @@ __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* 
     if (tid == 0) { s_read = 0; s_est = 0; carry = 0; }
     __syncthreads();
     unsigned long long my_read = 0, my_est = 0;
-    for (int base = 0; base < n; base += 1024) {
-        int u = base + tid;
-        uint32_t len = 0;
-        if (u < n) {
-            len = pair_len[ids[(int64_t)u * step]];
-            uint32_t members = 0;
-            for (int x = 0; x < step; ++x) members += ids[(int64_t)u * step + x] != IVFR_NO_PAIR ? 1u : 0u;
-            my_read += len;
-            my_est += (unsigned long long)len * members;
+    // four consecutive units per thread and step: their loads (pair ids, then the list length behind the first id)
+    // are independent chains and in flight together
+    for (int base = 0; base < n; base += 4096) {
+        const int u0 = base + 4 * tid;
+        uint32_t len[4], v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = u0 + i;
+            len[i] = u < n ? pair_len[ids[(int64_t)u * step]] : 0u;
         }
-        const uint32_t v = (len + IVFR_BLOCK - 1) / IVFR_BLOCK;
-        uint32_t inc = wave_incl_scan(v, lane);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int u = u0 + i;
+            if (u < n) {
+                uint32_t members = 0;
+                for (int x = 0; x < step; ++x) members += ids[(int64_t)u * step + x] != IVFR_NO_PAIR ? 1u : 0u;
+                my_read += len[i];
+                my_est += (unsigned long long)len[i] * members;
+            }
+            v[i] = (len[i] + IVFR_BLOCK - 1) / IVFR_BLOCK;
+        }
+        const uint32_t vsum = v[0] + v[1] + v[2] + v[3];
+        uint32_t inc = wave_incl_scan(vsum, lane);
         if (lane == 63) wtot[wv] = inc;
         __syncthreads();
         uint32_t add = carry;
         for (int x = 0; x < wv; ++x) add += wtot[x];
         inc += add;
-        if (u < n) out[u] = inc - v;
+        uint32_t run = inc - vsum;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (u0 + i < n) out[u0 + i] = run;
+            run += v[i];
+        }
         __syncthreads();
         if (tid == 1023) carry = inc;
         __syncthreads();
@@ -905,7 +906,7 @@ int ivfr_launch_group_plan(const int32_t* probe, int P, int w, int c, const uint
     const int u64 = (use8 && use64) ? 1 : 0;
     hipLaunchKernelGGL(group_count_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0,
                        gb.list_np);
-    hipLaunchKernelGGL(group_scan_lists_kernel, dim3(1), dim3(1024), 0, st, c, u64, gb.list_np, gb.gpre, gb.cur, gb.counts);
+    hipLaunchKernelGGL(group_scan_lists_kernel, dim3(5), dim3(1024), 0, st, c, u64, gb.list_np, gb.gpre, gb.cur, gb.counts);
     hipLaunchKernelGGL(group_fill_kernel, dim3((P + 255) / 256), dim3(256), 0, st, probe, P, w, exact_only, use8 ? 1 : 0, u64,
                        c, gb.list_np, gb.gpre, gb.cur, gb.unit8_pairs, gb.unit4_pairs, gb.unit2_pairs, gb.lo_pairs,
                        gb.unit64_pairs);
