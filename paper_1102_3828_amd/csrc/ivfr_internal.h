@@ -377,6 +377,7 @@ struct PlanBuffers {
     uint32_t* nsample;     // [nq] sampled entries of the query
     uint32_t* capq;        // [nq] records in the query's candidate buffer
     uint32_t* cnt;         // [nq] record counters of the scan (zero on entry; preset for queries that keep everything)
+    int place;             // 1 = the scans place the records of such queries by position (DirectPlace); 0 = they count them
     unsigned long long* coff;    // [nq] first record of the query's candidate buffer in the pool
     unsigned long long* sq;      // [nq] entries in the query's visited lists
     uint8_t* fully;              // [nq] 1 = few enough entries to keep them all (no sample, tau = +inf)

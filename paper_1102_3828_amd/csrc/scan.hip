@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restri
     pb.sq[q] = total;
     pb.nsample[q] = (uint32_t)(sampled > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : sampled);
     pb.fully[q] = fully ? 1 : 0;
-    if (fully) pb.cnt[q] = (uint32_t)total;   // its records are placed by position, not counted
+    if (fully && pb.place) pb.cnt[q] = (uint32_t)total;   // its records are placed by position, not counted
     bool exact_only = true;
     const unsigned long long capv = ivfr_plan_capacity(total, sampled, qp, min_cap, kprime, half_frac, &exact_only);
     pb.exact_only[q] = exact_only ? 1 : 0;
@@ -581,7 +581,9 @@ __device__ __forceinline__ void wq_flush(WaveQueue& wq, uint2* const (&qc)[G], u
     wq.n = 0;
 }
 
-template <int M>
+// PLACE: some queries of the launch may keep everything with their records placed by position (`direct`); without it
+// the argument is never read.
+template <int M, bool PLACE>
 __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict__ codes,
                                                        TableSrc ts,
                                                        const uint32_t* __restrict__ pair_start,
@@ -623,7 +625,7 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
         // with tau_id the bound is the 64-bit key (estimate, id): an estimate equal to tau passes only up to that id
         const uint32_t t_id = tau_id ? tau_id[q] : 0xFFFFFFFFu;
         const bool keep_all = t == INFINITY;
-        const bool placed = direct.fully && direct.fully[q];   // implies keep_all
+        const bool placed = PLACE && direct.fully[q];   // implies keep_all
         const uint32_t place0 = placed ? direct.off[pid] : 0u;
         uint2* const qc[1] = {cand + lay.base(q)};
         const uint32_t cap[1] = {lay.cap(q)};
@@ -668,7 +670,7 @@ __global__ __launch_bounds__(256) void adc_scan_kernel(const uint8_t* __restrict
                     if (k0 && est0 == t) k0 = (uint32_t)ids[(size_t)(start + e0[u]) * id_stride] <= t_id;
                     if (k1 && est1 == t) k1 = (uint32_t)ids[(size_t)(start + e0[u] + 1) * id_stride] <= t_id;
                 }
-                if (placed) {   // every entry has its own place: no counter
+                if (PLACE && placed) {   // every entry has its own place: no counter
                     const uint32_t s0 = place0 + e0[u];
                     if (in0[u] && s0 < cap[0]) qc[0][s0] = make_uint2(__float_as_uint(est0), start + e0[u]);
                     if (in1[u] && s0 + 1 < cap[0]) qc[0][s0 + 1] = make_uint2(__float_as_uint(est1), start + e0[u] + 1);
@@ -693,10 +695,14 @@ static int launch_scan_m(const ivfr_index* ix, const TableSrc& ts, const uint32_
                          const uint32_t* blkpre, const uint32_t* unit_pairs, const ScanShape& sh, int w,
                          const float* tau, uint2* cand, uint32_t* cand_cnt, CandLayout lay, hipStream_t st,
                          const uint32_t* tau_id, DirectPlace direct) {
-    hipLaunchKernelGGL(adc_scan_kernel<M>, dim3(sh.groups), dim3(256), scan_lds_bytes<M>(), st, ix->codes, ts,
-                       pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min, w, tau, cand,
-                       cand_cnt, lay, tau_id, reinterpret_cast<const int32_t*>(ix->rec), (uint32_t)(ix->rec_stride / 4),
-                       direct);
+#define IVFR_SCAN_LAUNCH(PL)                                                                                      \
+    hipLaunchKernelGGL((adc_scan_kernel<M, PL>), dim3(sh.groups), dim3(256), scan_lds_bytes<M>(), st, ix->codes, ts,  \
+                       pair_start, pair_len, blkpre, unit_pairs, sh.n_host, sh.n_dev, sh.bpg, sh.g_min, w, tau, cand, \
+                       cand_cnt, lay, tau_id, reinterpret_cast<const int32_t*>(ix->rec),                              \
+                       (uint32_t)(ix->rec_stride / 4), direct)
+    if (direct.fully) IVFR_SCAN_LAUNCH(true);
+    else IVFR_SCAN_LAUNCH(false);
+#undef IVFR_SCAN_LAUNCH
     IVFR_HIP(hipGetLastError());
     return IVFR_OK;
 }
@@ -2000,11 +2006,16 @@ static int allow_lds(K kernel, size_t bytes) {
 }
 
 int ivfr_scan_init() {
-    IVFR_TRY(allow_lds(adc_scan_kernel<4>, scan_lds_bytes<4>()));
-    IVFR_TRY(allow_lds(adc_scan_kernel<8>, scan_lds_bytes<8>()));
-    IVFR_TRY(allow_lds(adc_scan_kernel<16>, scan_lds_bytes<16>()));
-    IVFR_TRY(allow_lds(adc_scan_kernel<32>, scan_lds_bytes<32>()));
-    IVFR_TRY(allow_lds(adc_scan_kernel<64>, scan_lds_bytes<64>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<4, false>, scan_lds_bytes<4>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<4, true>, scan_lds_bytes<4>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<8, false>, scan_lds_bytes<8>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<8, true>, scan_lds_bytes<8>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<16, false>, scan_lds_bytes<16>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<16, true>, scan_lds_bytes<16>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<32, false>, scan_lds_bytes<32>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<32, true>, scan_lds_bytes<32>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<64, false>, scan_lds_bytes<64>()));
+    IVFR_TRY(allow_lds(adc_scan_kernel<64, true>, scan_lds_bytes<64>()));
     IVFR_TRY(allow_lds(adc_scan_shared_kernel<4, 4>, shared_lds_bytes<4, 4>()));
     IVFR_TRY(allow_lds(adc_scan_shared_kernel<8, 4>, shared_lds_bytes<8, 4>()));
     IVFR_TRY(allow_lds(adc_scan_shared_kernel<16, 4>, shared_lds_bytes<16, 4>()));

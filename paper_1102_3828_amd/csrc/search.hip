@@ -362,9 +362,15 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
     lay.capq = pb.capq;
     uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + L.cnt);
     pb.cnt = cnt;
-    DirectPlace direct;   // queries that keep everything: records by position
-    direct.fully = pb.fully;
-    direct.off = pb.soff;
+    // Queries that keep everything get their records placed by position.  Where no such query is to be expected
+    // (queries visit far more entries than the limit for keeping everything) the scans run without that path; a
+    // query that keeps everything all the same then appends through its counter.
+    pb.place = visit_est <= 64.0 * (double)full_limit ? 1 : 0;
+    DirectPlace direct;
+    if (pb.place) {
+        direct.fully = pb.fully;
+        direct.off = pb.soff;
+    }
     float* tau = reinterpret_cast<float*>(ws + L.tau);
     uint32_t* tau_id = reinterpret_cast<uint32_t*>(ws + L.tauid);
     uint32_t* spos = reinterpret_cast<uint32_t*>(ws + L.spos);

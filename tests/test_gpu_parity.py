@@ -643,6 +643,27 @@ def test_duplicate_vectors_are_cut_by_id():
     assert np.array_equal(ids.cpu().numpy(), o_ids)
     assert np.allclose(dist.cpu().numpy(), o_dist, rtol=REL_TOL)
     ix.close()
+    # The same with every estimate kept (no bound): the short-list selection then takes 50 of 15000 records of
+    # which thousands share one estimate, so the few-of-many shortcut finds a crowd at its bound, the general
+    # narrowing takes over and goes on over the ids.
+    Y = np.repeat(distinct, 5000, axis=0)
+    Y = Y[rng.permutation(len(Y))]
+    index = orc.build_index(Y, np.arange(len(Y)), books)
+    ix = gpu_index_from_oracle(index)
+    for mode in (2, 0):
+        ix.set_list_sharing(mode)
+        ix.set_tuning(full_mult=1000)
+        ids, dist = ix.search(queries_dev(X), 8, 50, 20)
+        st = ix.search_stats()
+        assert st["bound_retries"] == 0 and st["dense_fallbacks"] == 0
+        o_ids, o_dist, _ = orc.search(X, index, 8, 50, 20)
+        assert np.array_equal(ids.cpu().numpy(), o_ids)
+        assert np.allclose(dist.cpu().numpy(), o_dist, rtol=REL_TOL)
+        # and with a bound: the sample's selection meets the same crowd
+        ix.set_tuning(full_mult=1)
+        ids, dist = ix.search(queries_dev(X), 8, 50, 20)
+        assert np.array_equal(ids.cpu().numpy(), o_ids)
+    ix.close()
 
 
 @pytest.mark.parametrize("order", ["far_first", "near_first"])
