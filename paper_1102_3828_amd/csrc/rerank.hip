@@ -92,6 +92,10 @@ __global__ __launch_bounds__(256) void rerank_kernel(const float* __restrict__ q
 // the same query and its vector stays in registers.  The codebook rows are short (d/m' floats), so gathering them through the
 // vector cache fetches whole 128-byte lines for 32 or 64 useful bytes, and that fill traffic from L2 is
 // what bounds the plain kernel when k' is large.  Arithmetic and summation order are the same.
+// FM = m' (8, 16 or 32) for the common shape d = 128, m = 8: the record is then read with two or three 16-byte loads
+// (id, list and the eight code bytes in the first) and this lane's code bytes are shifted out of registers, instead
+// of ten narrow loads of the same line.  FM = 0: any shape.
+template <int FM>
 __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restrict__ queries, int d, int c, int m, int mr,
                                                           int dsub, int dsub_r, const float* __restrict__ coarse,
                                                           const float* __restrict__ pq, const float* __restrict__ rq,
@@ -136,7 +140,33 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
         r.list = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) { r.cb[k] = 0; r.rb[k] = 0; }
-        if (p.slot < p.n) {   // uniform over the 8 lanes of an entry
+        if (FM > 0 && p.slot < p.n) {
+            // d = 128, m = 8: piece k of lane t lies in sub-quantizer 2k + t/4 of the first stage (16 dimensions each)
+            const uint8_t* e = rec + (uint64_t)p.pos * rec_stride;
+            const uint4 h = *reinterpret_cast<const uint4*>(e);
+            r.id = (int32_t)h.x;
+            r.list = h.y;
+            const uint32_t cw[2] = {h.z, h.w};
+            const uint32_t hi4 = (uint32_t)t >> 2;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) r.cb[k] = (cw[k >> 1] >> (8u * (2u * (k & 1) + hi4))) & 0xffu;
+            if (FM == 8) {          // 16 dimensions per refinement sub-quantizer: the same byte pattern
+                const uint2 rw2 = *reinterpret_cast<const uint2*>(e + 16);
+                const uint32_t rw[2] = {rw2.x, rw2.y};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) r.rb[k] = (rw[k >> 1] >> (8u * (2u * (k & 1) + hi4))) & 0xffu;
+            } else if (FM == 16) {  // 8 dimensions each: byte 4k + t/2
+                const uint4 rw4 = *reinterpret_cast<const uint4*>(e + 16);
+                const uint32_t rw[4] = {rw4.x, rw4.y, rw4.z, rw4.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) r.rb[k] = (rw[k] >> (8u * ((uint32_t)t >> 1))) & 0xffu;
+            } else {                // 4 dimensions each: byte 8k + t
+                const uint4 ra = *reinterpret_cast<const uint4*>(e + 16), rb4 = *reinterpret_cast<const uint4*>(e + 32);
+                const uint32_t rw[8] = {ra.x, ra.y, ra.z, ra.w, rb4.x, rb4.y, rb4.z, rb4.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) r.rb[k] = ((hi4 ? rw[2 * k + 1] : rw[2 * k]) >> (8u * ((uint32_t)t & 3u))) & 0xffu;
+            }
+        } else if (p.slot < p.n) {   // uniform over the 8 lanes of an entry
             const uint8_t* e = rec + (uint64_t)p.pos * rec_stride;
             r.id = *reinterpret_cast<const int32_t*>(e);
             r.list = *reinterpret_cast<const uint32_t*>(e + 4);
@@ -207,7 +237,13 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
 }
 
 int ivfr_rerank_init() {
-    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel),
+    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel<0>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel<8>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel<16>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    IVFR_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_lds_kernel<32>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
     return IVFR_OK;
 }
@@ -222,9 +258,17 @@ int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, i
     if (vec0 && ix->p.m_refine > 0 && rq_bytes <= 128 * 1024 && (int64_t)nq * kprime >= (int64_t)ix->n_cu * 1024) {
         const int64_t n_items = (int64_t)nq * ((kprime + 127) / 128);
         const int groups = (int)std::min<int64_t>(n_items, ix->n_cu);
-        hipLaunchKernelGGL(rerank_lds_kernel, dim3(groups), dim3(1024), rq_bytes, st, queries, ix->p.d, ix->p.c, ix->p.m,
-                           ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq, ix->rec, ix->rec_stride,
-                           kprime, q_base, nq, short_pos, short_n, keys, refined_out, ids_out);
+#define IVFR_RERANK_LDS(FM)                                                                                       \
+    hipLaunchKernelGGL(rerank_lds_kernel<FM>, dim3(groups), dim3(1024), rq_bytes, st, queries, ix->p.d, ix->p.c,      \
+                       ix->p.m, ix->p.m_refine, ix->dsub, ix->dsub_r, ix->coarse, ix->pq, ix->rq, ix->rec,            \
+                       ix->rec_stride, kprime, q_base, nq, short_pos, short_n, keys, refined_out, ids_out)
+        const int mr = ix->p.m_refine;
+        const bool common = ix->p.d == 128 && ix->p.m == 8 && ix->rec_stride % 16 == 0;
+        if (common && mr == 8) IVFR_RERANK_LDS(8);
+        else if (common && mr == 16) IVFR_RERANK_LDS(16);
+        else if (common && mr == 32) IVFR_RERANK_LDS(32);
+        else IVFR_RERANK_LDS(0);
+#undef IVFR_RERANK_LDS
         IVFR_HIP(hipGetLastError());
         return IVFR_OK;
     }
