@@ -205,11 +205,13 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
             for (int k = 0; k < 4; ++k) {
                 if (k < nit) {
                     const int e = 4 * t + 32 * k;
-                    const int j = e / dsub, jr = e / dsub_r;
+                    // sub-vector widths: compile-time for the common shape (shifts instead of multiplications)
+                    const int ds = FM > 0 ? 16 : dsub, dr = FM > 0 ? 128 / (FM > 0 ? FM : 1) : dsub_r;
+                    const int j = e / ds, jr = e / dr;
                     float4 y = *reinterpret_cast<const float4*>(cl + e);
-                    const float4 pv = *reinterpret_cast<const float4*>(pq + ((int64_t)j * IVFR_KS + g0.cb[k]) * dsub + (e - j * dsub));
+                    const float4 pv = *reinterpret_cast<const float4*>(pq + (j * IVFR_KS + (int)g0.cb[k]) * ds + (e - j * ds));
                     y.x += pv.x; y.y += pv.y; y.z += pv.z; y.w += pv.w;
-                    const float4 rv = *reinterpret_cast<const float4*>(s_rq + (jr * IVFR_KS + g0.rb[k]) * dsub_r + (e - jr * dsub_r));
+                    const float4 rv = *reinterpret_cast<const float4*>(s_rq + (jr * IVFR_KS + (int)g0.rb[k]) * dr + (e - jr * dr));
                     y.x += rv.x; y.y += rv.y; y.z += rv.z; y.w += rv.w;
                     const float4 xv = xr[k];
                     const float a = xv.x - y.x, b = xv.y - y.y, cc = xv.z - y.z, dd = xv.w - y.w;
