@@ -897,8 +897,16 @@ __global__ __launch_bounds__(1024) void group_scan_units_kernel(const uint32_t* 
         if (tid == 1023) carry = inc;
         __syncthreads();
     }
-    atomicAdd(&s_read, my_read);
-    atomicAdd(&s_est, my_est);
+    // one LDS atomic per wavefront (1024 threads adding 64-bit words to one address would queue up behind one another)
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        my_read += __shfl_xor(my_read, off, 64);
+        my_est += __shfl_xor(my_est, off, 64);
+    }
+    if (lane == 0) {
+        atomicAdd(&s_read, my_read);
+        atomicAdd(&s_est, my_est);
+    }
     __syncthreads();
     if (tid == 0) {
         out[n] = carry;

@@ -38,23 +38,43 @@ struct SegView {
     uint32_t id_stride = 1;           // ids[pos * id_stride] is the id of the entry at position pos
 };
 
-__device__ __forceinline__ uint32_t seg_hi(const SegView& s, int64_t i, uint32_t* pos) {
-    if (s.vals) {
-        *pos = (uint32_t)i;
-        return s.vals[s.base + i];
-    }
-    if (s.keys) {
-        uint64_t k = s.keys[s.base + i];
-        *pos = (uint32_t)k;
-        return (uint32_t)(k >> 32);
-    }
-    uint2 r = s.recs[s.base + i];
-    *pos = r.y;
-    return r.x;
+enum { SRC_VALS = 0, SRC_KEYS = 1, SRC_RECS = 2 };   // which of the three sources a segment uses (compile-time in the kernels)
+
+template <int SRC>
+__device__ __forceinline__ uint32_t seg_lo(const SegView& s, uint32_t pos) {
+    return SRC != SRC_RECS ? pos : (uint32_t)s.ids[(size_t)pos * s.id_stride];
 }
 
-__device__ __forceinline__ uint32_t seg_lo(const SegView& s, uint32_t pos) {
-    return (s.keys || s.vals) ? pos : (uint32_t)s.ids[(size_t)pos * s.id_stride];
+// One sweep of the workgroup over the segment: body(distance word, pos) for every element, thread tid taking
+// elements tid, tid + SEL_T, ...  Four loads are issued before the first is used (a sweep is a chain of load
+// latencies otherwise: a segment of 50000 sampled estimates is 98 elements per thread).
+template <int SRC, class B>
+__device__ __forceinline__ void sweep(const SegView& s, B body) {
+    const int64_t n = s.n;
+    int64_t i = threadIdx.x;
+    if (SRC == SRC_VALS) {
+        const uint32_t* v = s.vals + s.base;
+        for (; i + 3 * SEL_T < n; i += 4 * SEL_T) {
+            const uint32_t a = v[i], b = v[i + SEL_T], c = v[i + 2 * SEL_T], d = v[i + 3 * SEL_T];
+            body(a, (uint32_t)i); body(b, (uint32_t)(i + SEL_T)); body(c, (uint32_t)(i + 2 * SEL_T)); body(d, (uint32_t)(i + 3 * SEL_T));
+        }
+        for (; i < n; i += SEL_T) body(v[i], (uint32_t)i);
+    } else if (SRC == SRC_KEYS) {
+        const uint64_t* v = s.keys + s.base;
+        for (; i + 3 * SEL_T < n; i += 4 * SEL_T) {
+            const uint64_t a = v[i], b = v[i + SEL_T], c = v[i + 2 * SEL_T], d = v[i + 3 * SEL_T];
+            body((uint32_t)(a >> 32), (uint32_t)a); body((uint32_t)(b >> 32), (uint32_t)b);
+            body((uint32_t)(c >> 32), (uint32_t)c); body((uint32_t)(d >> 32), (uint32_t)d);
+        }
+        for (; i < n; i += SEL_T) { const uint64_t a = v[i]; body((uint32_t)(a >> 32), (uint32_t)a); }
+    } else {
+        const uint2* v = s.recs + s.base;
+        for (; i + 3 * SEL_T < n; i += 4 * SEL_T) {
+            const uint2 a = v[i], b = v[i + SEL_T], c = v[i + 2 * SEL_T], d = v[i + 3 * SEL_T];
+            body(a.x, a.y); body(b.x, b.y); body(c.x, c.y); body(d.x, d.y);
+        }
+        for (; i < n; i += SEL_T) { const uint2 a = v[i]; body(a.x, a.y); }
+    }
 }
 
 struct SelShared {
@@ -65,18 +85,15 @@ struct SelShared {
     uint64_t pivot;
 };
 
-// Narrows [lo, hi] around the need-th smallest of the words word(i, &v) yields (false = element not taken part),
-// until at most `stop` words are left in the range or the range is a single value.  count is the number of words
+// Narrows [lo, hi] around the need-th smallest of the words that word(f) feeds to f (one call sweeps this thread's
+// share of them), until at most `stop` words are left in the range or the range is a single value.  count is the number of words
 // on entry and in the final range on return; need becomes the rank inside the final range.  All threads call.
 template <class F>
-__device__ void narrow_range(SelShared& sh, F word, int64_t n, uint32_t& lo, uint32_t& hi, uint32_t& need,
+__device__ void narrow_range(SelShared& sh, F word, uint32_t& lo, uint32_t& hi, uint32_t& need,
                              uint64_t& count, uint32_t stop = SEL_RC) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     uint32_t mn = 0xFFFFFFFFu, mx = 0u;
-    for (int64_t i = tid; i < n; i += SEL_T) {
-        uint32_t v;
-        if (word(i, &v)) { mn = v < mn ? v : mn; mx = v > mx ? v : mx; }
-    }
+    word([&](uint32_t v) { mn = v < mn ? v : mn; mx = v > mx ? v : mx; });
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         const uint32_t a = __shfl_xor(mn, off, 64), b = __shfl_xor(mx, off, 64);
@@ -100,10 +117,9 @@ __device__ void narrow_range(SelShared& sh, F word, int64_t n, uint32_t& lo, uin
         while ((span >> shift) >= SEL_BINS) ++shift;
         for (int i = tid; i < SEL_BINS; i += SEL_T) sh.hist[i] = 0;
         __syncthreads();
-        for (int64_t i = tid; i < n; i += SEL_T) {
-            uint32_t v;
-            if (word(i, &v) && v >= lo && v <= hi) atomicAdd(&sh.hist[(v - lo) >> shift], 1u);
-        }
+        word([&](uint32_t v) {
+            if (v >= lo && v <= hi) atomicAdd(&sh.hist[(v - lo) >> shift], 1u);
+        });
         __syncthreads();
         // two bins per thread; inclusive scan over the workgroup
         const uint32_t a = sh.hist[2 * tid], b = sh.hist[2 * tid + 1];
@@ -134,6 +150,7 @@ __device__ void narrow_range(SelShared& sh, F word, int64_t n, uint32_t& lo, uin
 }
 
 // Returns the K-th smallest key of the segment (1 <= K <= n).  All threads must call; ends with a barrier.
+template <int SRC>
 __device__ uint64_t kth_key(const SegView& s, uint32_t K) {
     __shared__ SelShared sh;
     const int tid = threadIdx.x;
@@ -142,15 +159,13 @@ __device__ uint64_t kth_key(const SegView& s, uint32_t K) {
     auto gather = [&](uint32_t lo, uint32_t hi, bool by_index, uint32_t lo2, uint32_t hi2) -> uint32_t {
         if (tid == 0) sh.fill = 0;
         __syncthreads();
-        for (int64_t i = tid; i < s.n; i += SEL_T) {
-            uint32_t pos;
-            const uint32_t h = seg_hi(s, i, &pos);
-            if (h < lo || h > hi) continue;
-            const uint32_t l = seg_lo(s, pos);
-            if (by_index && (l < lo2 || l > hi2)) continue;
+        sweep<SRC>(s, [&](uint32_t h, uint32_t pos) {
+            if (h < lo || h > hi) return;
+            const uint32_t l = seg_lo<SRC>(s, pos);
+            if (by_index && (l < lo2 || l > hi2)) return;
             const uint32_t slot = atomicAdd(&sh.fill, 1u);
             if (slot < SEL_RC) sh.cand[slot] = ((uint64_t)h << 32) | l;
-        }
+        });
         __syncthreads();
         const uint32_t got = sh.fill;
         __syncthreads();
@@ -181,20 +196,13 @@ __device__ uint64_t kth_key(const SegView& s, uint32_t K) {
         // the minima in LDS.
         uint32_t* mins = reinterpret_cast<uint32_t*>(sh.cand);
         uint32_t mn = 0xFFFFFFFFu;
-        for (int64_t i = tid; i < s.n; i += SEL_T) {
-            uint32_t pos;
-            const uint32_t h = seg_hi(s, i, &pos);
-            mn = h < mn ? h : mn;
-        }
+        sweep<SRC>(s, [&](uint32_t h, uint32_t) { mn = h < mn ? h : mn; });
         mins[tid] = mn;
         __syncthreads();
-        auto min_word = [&](int64_t i, uint32_t* v) {
-            *v = mins[i];
-            return true;
-        };
+        auto min_words = [&](auto f) { f(mins[tid]); };   // one minimum per thread
         uint32_t mlo = 0u, bound = 0xFFFFFFFFu, mneed = K;
         uint64_t mcount = SEL_T;
-        narrow_range(sh, min_word, SEL_T, mlo, bound, mneed, mcount, 1u);   // ends with a barrier: mins may be overwritten
+        narrow_range(sh, min_words, mlo, bound, mneed, mcount, 1u);   // ends with a barrier: mins may be overwritten
         const uint32_t got = gather(0u, bound, false, 0u, 0u);
         if (got <= SEL_RC) return ranked(got, K);
         // a crowd of equal distance words at the bound: the general way
@@ -204,22 +212,15 @@ __device__ uint64_t kth_key(const SegView& s, uint32_t K) {
     uint32_t lo = 0u, hi = 0xFFFFFFFFu, lo2 = 0u, hi2 = 0xFFFFFFFFu;
     bool by_index = false;
     if (count > SEL_RC) {
-        auto dist_word = [&](int64_t i, uint32_t* v) {
-            uint32_t pos;
-            *v = seg_hi(s, i, &pos);
-            return true;
-        };
-        narrow_range(sh, dist_word, s.n, lo, hi, need, count);
+        auto dist_words = [&](auto f) { sweep<SRC>(s, [&](uint32_t h, uint32_t) { f(h); }); };
+        narrow_range(sh, dist_words, lo, hi, need, count);
         if (count > SEL_RC) {   // lo == hi: that many keys share the distance word, their index words decide
             by_index = true;
             const uint32_t fixed = lo;
-            auto index_word = [&](int64_t i, uint32_t* v) {
-                uint32_t pos;
-                if (seg_hi(s, i, &pos) != fixed) return false;
-                *v = seg_lo(s, pos);
-                return true;
+            auto index_words = [&](auto f) {
+                sweep<SRC>(s, [&](uint32_t h, uint32_t pos) { if (h == fixed) f(seg_lo<SRC>(s, pos)); });
             };
-            narrow_range(sh, index_word, s.n, lo2, hi2, need, count);
+            narrow_range(sh, index_words, lo2, hi2, need, count);
             if (count > SEL_RC) return ((uint64_t)fixed << 32) | lo2;   // equal keys throughout
         }
     }
@@ -271,7 +272,8 @@ __global__ __launch_bounds__(SEL_T) void select_tau_kernel(const uint2* recs, co
             s.vals = reinterpret_cast<const uint32_t*>(recs);
             s.base = 2 * (int64_t)lay.base(seg);
         }
-        uint64_t pivot = kth_key(s, (uint32_t)r);   // ends with a barrier: its LDS state is free for the next segment
+        // ends with a barrier: its LDS state is free for the next segment
+        const uint64_t pivot = values_only ? kth_key<SRC_VALS>(s, (uint32_t)r) : kth_key<SRC_RECS>(s, (uint32_t)r);
         if (threadIdx.x == 0) {
             tau[seg] = __uint_as_float((uint32_t)(pivot >> 32));
             if (tau_id) tau_id[seg] = (uint32_t)pivot;
@@ -331,16 +333,15 @@ __global__ __launch_bounds__(SEL_T) void select_records_kernel(const uint2* recs
         if (threadIdx.x == 0) out_n[q] = (int32_t)n;
         return;
     }
-    const uint64_t pivot = kth_key(s, (uint32_t)K);
+    const uint64_t pivot = kth_key<SRC_RECS>(s, (uint32_t)K);
     const uint32_t p_hi = (uint32_t)(pivot >> 32), p_lo = (uint32_t)pivot;
-    for (int64_t i = threadIdx.x; i < n; i += SEL_T) {
-        uint2 r = recs[s.base + i];
-        bool take = r.x < p_hi || (r.x == p_hi && (uint32_t)ids[(size_t)r.y * id_stride] <= p_lo);
+    sweep<SRC_RECS>(s, [&](uint32_t est, uint32_t pos) {
+        const bool take = est < p_hi || (est == p_hi && (uint32_t)ids[(size_t)pos * id_stride] <= p_lo);
         if (take) {
-            uint32_t slot = atomicAdd(&s_slot, 1u);
-            if (slot < (uint32_t)K) { op[slot] = r.y; oe[slot] = __uint_as_float(r.x); }
+            const uint32_t slot = atomicAdd(&s_slot, 1u);
+            if (slot < (uint32_t)K) { op[slot] = pos; oe[slot] = __uint_as_float(est); }
         }
-    }
+    });
     if (threadIdx.x == 0) out_n[q] = K;
 }
 
@@ -373,14 +374,14 @@ __global__ __launch_bounds__(SEL_T) void select_sorted_kernel(const uint64_t* ke
         for (int64_t i = threadIdx.x; i < n; i += SEL_T) sk[i] = keys[s.base + i];
         m_out = (int)n;
     } else {
-        const uint64_t pivot = kth_key(s, (uint32_t)K);
-        for (int64_t i = threadIdx.x; i < n; i += SEL_T) {
-            uint64_t k = keys[s.base + i];
+        const uint64_t pivot = kth_key<SRC_KEYS>(s, (uint32_t)K);
+        sweep<SRC_KEYS>(s, [&](uint32_t h, uint32_t l) {
+            const uint64_t k = ((uint64_t)h << 32) | l;
             if (k <= pivot) {
-                uint32_t slot = atomicAdd(&s_slot, 1u);
+                const uint32_t slot = atomicAdd(&s_slot, 1u);
                 if (slot < (uint32_t)n2) sk[slot] = k;
             }
-        }
+        });
         m_out = K;
     }
     __syncthreads();
