@@ -86,8 +86,9 @@ struct SelShared {
 };
 
 // Narrows [lo, hi] around the need-th smallest of the words that word(f) feeds to f (one call sweeps this thread's
-// share of them), until at most `stop` words are left in the range or the range is a single value.  count is the number of words
-// on entry and in the final range on return; need becomes the rank inside the final range.  All threads call.
+// share of them), until at most `stop` words are left in the range or the range is a single value.  count is the
+// number of words on entry and in the final range on return; need becomes the rank inside the final range.  All
+// threads call.
 template <class F>
 __device__ void narrow_range(SelShared& sh, F word, uint32_t& lo, uint32_t& hi, uint32_t& need,
                              uint64_t& count, uint32_t stop = SEL_RC) {
