@@ -116,6 +116,8 @@ extern "C" int ivfr_create(const ivfr_params* params, ivfr_index** out) {
         bool ok = hipEventCreateWithFlags(&ix->ev_fork[sl], hipEventDisableTiming) == hipSuccess;
         for (int i = 0; i < 4 && ok; ++i)
             ok = hipEventCreateWithFlags(&ix->ev_join[sl][i], hipEventDisableTiming) == hipSuccess;
+        for (int i = 0; i < 2 && ok; ++i)
+            ok = hipEventCreateWithFlags(&ix->ev_group[sl][i], hipEventDisableTiming) == hipSuccess;
         if (!ok) { ivfr_set_error("event creation failed"); r = IVFR_ERR_HIP; }
     }
     if (r != IVFR_OK) { ivfr_destroy(ix); return r; }
@@ -148,6 +150,8 @@ extern "C" int ivfr_destroy(ivfr_index* ix) {
         if (ix->ev_fork[sl]) (void)hipEventDestroy(ix->ev_fork[sl]);
         for (int i = 0; i < 4; ++i)
             if (ix->ev_join[sl][i]) (void)hipEventDestroy(ix->ev_join[sl][i]);
+        for (int i = 0; i < 2; ++i)
+            if (ix->ev_group[sl][i]) (void)hipEventDestroy(ix->ev_group[sl][i]);
     }
     for (hipEvent_t e : ix->prof_events) (void)hipEventDestroy(e);
     ix->prof_events.clear();

@@ -146,6 +146,7 @@ struct ivfr_index {
     hipStream_t side[4] = {nullptr, nullptr, nullptr, nullptr};   // the smaller scan launches overlap the large one
     hipEvent_t ev_fork[IVFR_STATUS_SLOTS] = {nullptr};            // one set of fork / join events per batch in flight
     hipEvent_t ev_join[IVFR_STATUS_SLOTS][4] = {{nullptr}};
+    hipEvent_t ev_group[IVFR_STATUS_SLOTS][2] = {{nullptr}};      // the pair grouping of a batch runs beside its table kernel
 
     // stats of the last search
     int64_t st_reruns = 0;           // batches of the last search that ran twice (pool grown, or brought back for a redo)

@@ -504,7 +504,14 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             IVFR_TRY(ivfr_launch_select_sorted(a, nullptr, 0, probe, probed, st));
         }
         IVFR_TRY(ivfr_launch_plan(ix, probe, nb, w, full_limit, stride_k, min_cap, IVFR_MAX_SAMPLE, kprime, half_frac, pb, st));
-        if (share) IVFR_TRY(ivfr_launch_group_plan(probe, Pb, w, c, pb.exact_only, share8, share64, pb.len, gb, st));
+        if (share) {
+            // The grouping of the pairs by list (four small kernels, mostly latency) is needed by the shared scans
+            // only: it runs on a side stream beside the table kernel, the sample and the bound.
+            IVFR_HIP(hipEventRecord(ix->ev_group[slot][0], st));
+            IVFR_HIP(hipStreamWaitEvent(ix->side[0], ix->ev_group[slot][0], 0));
+            IVFR_TRY(ivfr_launch_group_plan(probe, Pb, w, c, pb.exact_only, share8, share64, pb.len, gb, ix->side[0]));
+            IVFR_HIP(hipEventRecord(ix->ev_group[slot][1], ix->side[0]));
+        }
         IVFR_TRY(mark(IVFR_STAGE_PROBE, false));
         IVFR_TRY(mark(IVFR_STAGE_LUT, true));
         if (split) IVFR_TRY(ivfr_launch_query_terms(ix, X, probe, nb, w, lut, pbase, lut_scale, st));
@@ -545,6 +552,7 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             s64.bpg = ix->scan_groups > 0 ? 0u : 32u;
             s64.g_min = 8;
             const int n_side = share64 ? 4 : 3;
+            IVFR_HIP(hipStreamWaitEvent(st, ix->ev_group[slot][1], 0));   // the units are in place
             IVFR_HIP(hipEventRecord(ix->ev_fork[slot], st));
             for (int i = 0; i < n_side; ++i) IVFR_HIP(hipStreamWaitEvent(ix->side[i], ix->ev_fork[slot], 0));
             if (share64) {
