@@ -242,51 +242,76 @@ int ivfr_select_init();   // one-time function attributes
 
 // Per-query part of the search plan, shared by the plan kernel and by the host's estimate of the candidate
 // pool.  A query that visits `total` entries keeps every estimate when total <= full_limit (or when its sample
-// would be a third of them or more); otherwise one entry in `stride` is sampled (the same leading fraction of
-// every visited list) to bound the k'-th smallest estimate.  Scoring a sampled entry and handling a surviving
-// one cost about the same order, and the survivors fall as k' (1 + 5/sqrt(mu) + 6/mu) with mu = k' n_s / total,
-// so the cheapest sample grows as the cube root of k' * total (the factor 16 is measured).  The stride is at
-// most stride_k (= k' / mu_min) and at least what keeps the sample below max_sample.
+// would be a third of them or more); otherwise a sample bounds the k'-th smallest estimate.  Scoring a sampled
+// entry and handling a surviving one cost about the same order, and the survivors fall as k' (1 + 5/sqrt(mu) + 6/mu)
+// with mu = k' n_s / (entries sampled from), so the cheapest sample size n_s grows as the cube root of k' * total
+// (the factor 16 is measured).  Where that leaves mu small (a short-list that is tiny against the visit: mu = 3 at
+// 10^7 visited entries and k' = 1000) the sample is drawn from the nearest visited lists only: the lists in probe
+// order up to the first that brings their entries to `total_u` = k' n_s / 16 (mu = 16), but not fewer than
+// total / IVFR_SAMPLE_NEAR_DIV or 8 k'.  Any subset of the visited entries with k' members at or below a bound makes
+// the bound valid for the whole visit; the nearest lists hold most of the short-list, their tables are a fraction
+// of the tables the sample has to load, and the larger mu means a tighter rank.  One entry in `stride` of the
+// sampled lists is taken (the same leading fraction of each); the stride is at most stride_k (= k' / mu_min) and
+// at least what keeps the sample below max_sample.
+#define IVFR_SAMPLE_NEAR_DIV 4
 struct QueryPlan {
     bool fully;
     uint32_t stride;
 };
-__host__ __device__ inline QueryPlan ivfr_plan_query(unsigned long long total, uint32_t full_limit, uint32_t stride_k,
-                                                     uint32_t max_sample, int kprime) {
+// entries of the nearest lists that the sample is drawn from, given the whole visit (the plan kernel walks the
+// lists up to this threshold; the host's estimate takes the threshold itself)
+__host__ __device__ inline unsigned long long ivfr_sample_threshold(unsigned long long total, int kprime) {
+    const double kp = (double)(kprime > 0 ? kprime : 1);
+    const double want = kp * cbrt(kp * (double)total);   // k' n_s / 16 with n_s = 16 (k' total)^(1/3)
+    unsigned long long t = want >= (double)total ? total : (unsigned long long)want;
+    if (t < total / IVFR_SAMPLE_NEAR_DIV) t = total / IVFR_SAMPLE_NEAR_DIV;
+    if (t < 8ull * (unsigned long long)kp) t = 8ull * (unsigned long long)kp;
+    return t < total ? t : total;
+}
+__host__ __device__ inline QueryPlan ivfr_plan_query(unsigned long long total, unsigned long long total_u,
+                                                     uint32_t full_limit, uint32_t stride_k, uint32_t max_sample,
+                                                     int kprime) {
     QueryPlan r;
     r.fully = total <= full_limit;
-    unsigned long long stride64 = 1;
-    {
-        const double ns = 16.0 * cbrt((double)kprime * (double)total);
-        const double st_d = (double)total / (ns > 1.0 ? ns : 1.0);
-        stride64 = st_d > 4.0e9 ? 4000000000ull : (unsigned long long)st_d;
+    const double ns = 16.0 * cbrt((double)kprime * (double)total);
+    unsigned long long strides[2];   // one entry in strides[0] of the whole visit, in strides[1] of the nearest lists
+    const unsigned long long sizes[2] = {total, total_u};
+    for (int i = 0; i < 2; ++i) {
+        const double st_d = (double)sizes[i] / (ns > 1.0 ? ns : 1.0);
+        unsigned long long st = st_d > 4.0e9 ? 4000000000ull : (unsigned long long)st_d;
+        if (st > (stride_k < 1 ? 1ull : stride_k)) st = stride_k < 1 ? 1ull : stride_k;
+        const unsigned long long widen = (sizes[i] + max_sample - 1) / max_sample;
+        if (widen > st) st = widen;
+        if (st < 1) st = 1;
+        strides[i] = st;
     }
-    if (stride64 > (stride_k < 1 ? 1ull : stride_k)) stride64 = stride_k < 1 ? 1ull : stride_k;
-    const unsigned long long widen = (total + max_sample - 1) / max_sample;
-    if (widen > stride64) stride64 = widen;
-    if (stride64 < 1) stride64 = 1;
-    if (stride64 <= 3) r.fully = true;   // a sample of a third or more of the entries saves nothing
-    r.stride = (uint32_t)(stride64 > 0xFFFFFFFFull ? 0xFFFFFFFFull : stride64);
+    if (strides[0] <= 3) r.fully = true;   // a sample of a third or more of the entries saves nothing
+    r.stride = (uint32_t)(strides[1] > 0xFFFFFFFFull ? 0xFFFFFFFFull : strides[1]);
     return r;
 }
 // Records of the query's candidate buffer: everything (no filter), or the largest of the sample, min_cap and the
-// survivors expected from the bound (rank r of the sample, one sampled entry standing for `stride`) plus six
-// deviations.  exact_only: so large a share of the estimates will pass the bound that the half-precision units
-// do not pay off.
-__host__ __device__ inline unsigned long long ivfr_plan_capacity(unsigned long long total, unsigned long long sampled,
-                                                                 QueryPlan qp, uint32_t min_cap, int kprime,
-                                                                 float half_frac, bool* exact_only) {
+// survivors expected from the bound plus six deviations.  The bound is the rank-th smallest of the sample, one
+// sampled entry standing for `stride` entries of the sampled lists; how many entries of the other lists lie below
+// it is not known beforehand, so the buffer allows for the case that they are as dense there as in the sampled
+// lists (total / total_u times as many).  exact_only: so large a share of the estimates will pass the bound that
+// the half-precision units do not pay off.
+__host__ __device__ inline unsigned long long ivfr_plan_capacity(unsigned long long total, unsigned long long total_u,
+                                                                 unsigned long long sampled, QueryPlan qp,
+                                                                 uint32_t min_cap, int kprime, float half_frac,
+                                                                 bool* exact_only) {
     unsigned long long capv = total;
     *exact_only = true;
     if (!qp.fully) {
         const double mu = (double)kprime / (double)qp.stride;
         const double rank = mu + 5.0 * sqrt(mu) + 6.0;
-        const double expect = rank * (double)qp.stride;
+        const double spread = (double)total / (double)(total_u > 0 ? total_u : 1ull);
+        const double expect_u = rank * (double)qp.stride;   // entries of the sampled lists below the bound
         capv = sampled > min_cap ? sampled : (unsigned long long)min_cap;
         // the number of visited entries below the rank-th sampled one scatters by ~1/sqrt(rank): six deviations
-        const double roomy = expect * (1.0 + 6.0 / sqrt(rank));
+        const double roomy = expect_u * spread * (1.0 + 6.0 / sqrt(rank));
         if ((double)capv < roomy) capv = (unsigned long long)roomy;
-        *exact_only = expect > (double)half_frac * (double)total;
+        // what is likely rather than what is possible: the other lists add a quarter
+        *exact_only = expect_u * (spread < 1.25 ? spread : 1.25) > (double)half_frac * (double)total;
     }
     if (capv > 0xFFFFFFF0ull) capv = 0xFFFFFFF0ull;
     return capv;
@@ -381,6 +406,7 @@ struct PlanBuffers {
     int place;             // 1 = the scans place the records of such queries by position (DirectPlace); 0 = they count them
     unsigned long long* coff;    // [nq] first record of the query's candidate buffer in the pool
     unsigned long long* sq;      // [nq] entries in the query's visited lists
+    unsigned long long* su;      // [nq] entries in the nearest visited lists, which the query's sample is drawn from
     uint8_t* fully;              // [nq] 1 = few enough entries to keep them all (no sample, tau = +inf)
     uint8_t* exact_only;         // [nq] 1 = too large a share of the estimates will pass the bound for fp16 units
     unsigned long long* totals;  // [2]: [0] = sum of sq, [1] = records in the candidate pool

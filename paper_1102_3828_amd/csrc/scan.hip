@@ -43,19 +43,49 @@ __global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restri
     for (int r = lane; r < w; r += 64) total += list_len[probe[(int64_t)q * w + r]];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) total += __shfl_xor(total, off, 64);
-    const QueryPlan qp = ivfr_plan_query(total, full_limit, stride_k, max_sample, kprime);
+    // the sample comes from the nearest lists: those whose predecessors in probe order hold fewer than `thresh` entries
+    const unsigned long long thresh = ivfr_sample_threshold(total, kprime);
+    unsigned long long total_u = 0, before = 0;
+    for (int r0 = 0; r0 < w; r0 += 64) {
+        const int r = r0 + lane;
+        const unsigned long long len = r < w ? (unsigned long long)list_len[probe[(int64_t)q * w + r]] : 0ull;
+        unsigned long long inc = len;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned long long o = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += o;
+        }
+        if (before + inc - len < thresh) total_u += len;
+        before += __shfl(inc, 63, 64);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) total_u += __shfl_xor(total_u, off, 64);
+    const QueryPlan qp = ivfr_plan_query(total, total_u, full_limit, stride_k, max_sample, kprime);
     const bool fully = qp.fully;
     const uint32_t stride = qp.stride;
     unsigned long long sampled = 0;
     uint32_t carry = 0, carry_s = 0, carry_e = 0;
+    before = 0;
     for (int r0 = 0; r0 < w; r0 += 64) {
         const int r = r0 + lane;
         uint32_t len = 0, ls = 0;
+        {
+            // the same walk as above: is this pair one of the sampled lists?
+            const unsigned long long l64 = r < w ? (unsigned long long)list_len[probe[(int64_t)q * w + r]] : 0ull;
+            unsigned long long inc = l64;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const unsigned long long o = __shfl_up(inc, off, 64);
+                if (lane >= off) inc += o;
+            }
+            const bool in_u = before + inc - l64 < thresh;
+            before += __shfl(inc, 63, 64);
+            if (r < w) ls = (fully || !in_u) ? 0u : ((uint32_t)l64 + stride - 1) / stride;
+        }
         if (r < w) {
             const int64_t p = (int64_t)q * w + r;
             const int l = probe[p];
             len = list_len[l];
-            ls = fully ? 0u : (len + stride - 1) / stride;
             pb.pair_start[p] = list_start[l];
             pb.len[p] = len;
             pb.len_s[p] = ls;
@@ -83,11 +113,12 @@ __global__ __launch_bounds__(256) void plan_pairs_kernel(const int32_t* __restri
     pb.qblk[q] = carry;
     pb.qblk_s[q] = carry_s;
     pb.sq[q] = total;
+    pb.su[q] = total_u;
     pb.nsample[q] = (uint32_t)(sampled > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : sampled);
     pb.fully[q] = fully ? 1 : 0;
     if (fully && pb.place) pb.cnt[q] = (uint32_t)total;   // its records are placed by position, not counted
     bool exact_only = true;
-    const unsigned long long capv = ivfr_plan_capacity(total, sampled, qp, min_cap, kprime, half_frac, &exact_only);
+    const unsigned long long capv = ivfr_plan_capacity(total, total_u, sampled, qp, min_cap, kprime, half_frac, &exact_only);
     pb.exact_only[q] = exact_only ? 1 : 0;
     pb.capq[q] = (uint32_t)capv;
     atomicAdd(pb.totals, total);

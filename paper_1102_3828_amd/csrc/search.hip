@@ -108,7 +108,7 @@ struct Carver {
 
 // Byte offsets of one batch's arrays inside the search workspace.
 struct SearchLayout {
-    size_t xnorm, ckeys, probe, probed, pstart, len, pre, lens, pres, items, soff, nsample, qblk, sq, fully, exonly,
+    size_t xnorm, ckeys, probe, probed, pstart, len, pre, lens, pres, items, soff, nsample, qblk, sq, su, fully, exonly,
         capq, coff, lut, pbase, tau, tauid, spos, sest, sn, over, rkeys, sref, sids, lscale, gpre, gcur, gu8, gu2, glop, gblk8,
         gblk4, gblk2, gblklo, gu64, gblk64, status, cnt, gnp;
     size_t n_items_max, n_u8, n_u4, zero_words, bytes;
@@ -134,6 +134,7 @@ static SearchLayout layout_search(const ivfr_params& p, int B, int w, int kprime
     L.nsample = cv.take<uint32_t>(B);
     L.qblk = cv.take<uint32_t>(2 * (size_t)B);
     L.sq = cv.take<unsigned long long>(B);
+    L.su = cv.take<unsigned long long>(B);
     L.fully = cv.take<uint8_t>(B);
     L.exonly = cv.take<uint8_t>(B);
     L.capq = cv.take<uint32_t>(B);
@@ -193,10 +194,11 @@ static unsigned long long pool_estimate(const ivfr_index* ix, int nb, int w, int
     const uint32_t full_limit = (uint32_t)std::min<int64_t>((int64_t)ix->full_mult * kprime, 1ll << 30);
     const uint32_t stride_k = (uint32_t)std::max(1, kprime / IVFR_SAMPLE_MU);
     const unsigned long long total = (unsigned long long)std::max(per_query, 1.0);
-    const QueryPlan qp = ivfr_plan_query(total, full_limit, stride_k, IVFR_MAX_SAMPLE, kprime);
-    const unsigned long long sampled = qp.fully ? 0ull : total / qp.stride + (unsigned long long)w;
+    const unsigned long long total_u = ivfr_sample_threshold(total, kprime);
+    const QueryPlan qp = ivfr_plan_query(total, total_u, full_limit, stride_k, IVFR_MAX_SAMPLE, kprime);
+    const unsigned long long sampled = qp.fully ? 0ull : total_u / qp.stride + (unsigned long long)w;
     bool eo;
-    const unsigned long long cap = ivfr_plan_capacity(total, sampled, qp, min_cap, kprime, IVFR_HALF_UNIT_FRAC, &eo);
+    const unsigned long long cap = ivfr_plan_capacity(total, total_u, sampled, qp, min_cap, kprime, IVFR_HALF_UNIT_FRAC, &eo);
     return (unsigned long long)nb * ((cap + 31ull) & ~31ull);
 }
 
@@ -338,6 +340,7 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
     pb.qblk = reinterpret_cast<uint32_t*>(ws + L.qblk);
     pb.qblk_s = pb.qblk + B;
     pb.sq = reinterpret_cast<unsigned long long*>(ws + L.sq);
+    pb.su = reinterpret_cast<unsigned long long*>(ws + L.su);
     pb.fully = reinterpret_cast<uint8_t*>(ws + L.fully);
     pb.exact_only = reinterpret_cast<uint8_t*>(ws + L.exonly);
     pb.totals = dstat->totals;
@@ -531,7 +534,7 @@ static int run_search(ivfr_index* ix, const float* queries, int64_t nq, int32_t 
             // the sample of query q is nsample[q] bare estimates at the start of its buffer
             SelectArgs a;
             a.nseg = nb; a.K = kprime; a.recs = cand; a.ids = reinterpret_cast<const int32_t*>(ix->rec); a.id_stride = (uint32_t)(ix->rec_stride / 4); a.counts = pb.nsample; a.lay = lay;
-            IVFR_TRY(ivfr_launch_select_tau(a, pb.sq, kprime, 0, pb.fully, tau, nullptr, st, true, !expect_sample));
+            IVFR_TRY(ivfr_launch_select_tau(a, pb.su, kprime, 0, pb.fully, tau, nullptr, st, true, !expect_sample));
         }
         IVFR_TRY(mark(IVFR_STAGE_SAMPLE, false));
         // scan of every visited entry, keeping estimates <= tau
