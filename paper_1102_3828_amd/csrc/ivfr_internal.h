@@ -254,6 +254,9 @@ int ivfr_select_init();   // one-time function attributes
 // sampled lists is taken (the same leading fraction of each); the stride is at most stride_k (= k' / mu_min) and
 // at least what keeps the sample below max_sample.
 #define IVFR_SAMPLE_NEAR_DIV 4
+#ifndef IVFR_SAMPLE_FACTOR
+#define IVFR_SAMPLE_FACTOR 16.0   // n_s = factor * (k' total)^(1/3)
+#endif
 struct QueryPlan {
     bool fully;
     uint32_t stride;
@@ -262,7 +265,7 @@ struct QueryPlan {
 // lists up to this threshold; the host's estimate takes the threshold itself)
 __host__ __device__ inline unsigned long long ivfr_sample_threshold(unsigned long long total, int kprime) {
     const double kp = (double)(kprime > 0 ? kprime : 1);
-    const double want = kp * cbrt(kp * (double)total);   // k' n_s / 16 with n_s = 16 (k' total)^(1/3)
+    const double want = kp * (IVFR_SAMPLE_FACTOR / 16.0) * cbrt(kp * (double)total);   // k' n_s / 16: mu = 16
     unsigned long long t = want >= (double)total ? total : (unsigned long long)want;
     if (t < total / IVFR_SAMPLE_NEAR_DIV) t = total / IVFR_SAMPLE_NEAR_DIV;
     if (t < 8ull * (unsigned long long)kp) t = 8ull * (unsigned long long)kp;
@@ -273,7 +276,7 @@ __host__ __device__ inline QueryPlan ivfr_plan_query(unsigned long long total, u
                                                      int kprime) {
     QueryPlan r;
     r.fully = total <= full_limit;
-    const double ns = 16.0 * cbrt((double)kprime * (double)total);
+    const double ns = IVFR_SAMPLE_FACTOR * cbrt((double)kprime * (double)total);
     unsigned long long strides[2];   // one entry in strides[0] of the whole visit, in strides[1] of the nearest lists
     const unsigned long long sizes[2] = {total, total_u};
     for (int i = 0; i < 2; ++i) {
