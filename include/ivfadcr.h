@@ -181,10 +181,10 @@ int ivfr_set_table_mode(ivfr_index* index, int32_t mode);
 
 /* Internal sizing knobs (defaults in parentheses); 0 keeps the current value.
  *   full_mult   (8)    a query that visits at most full_mult*k' entries keeps every estimate; a
- *                      larger one first scores a sample of its entries (the same leading fraction of
- *                      every visited list, at least 2/k', about 16 (k' S)^(1/3) entries of the S visited)
- *                      to bound the k'-th smallest estimate, and the scan keeps only estimates below
- *                      the bound
+ *                      larger one first scores a sample of its entries (about 16 (k' S)^(1/3) of the S
+ *                      visited, at least a fraction 2/k'; the same leading fraction of every visited list,
+ *                      or of the nearest ones only when k' is tiny against S) to bound the k'-th smallest
+ *                      estimate, and the scan keeps only estimates below the bound
  *   cap_mult    (16)   such a query's candidate buffer holds max(cap_mult*k', min_cap) records, or its
  *   min_cap     (8192) sample, or the survivors expected from the bound plus six deviations, whichever
  *                      is largest; overflowing it triggers a rescan of that query with a tighter bound
