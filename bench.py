@@ -563,7 +563,9 @@ def main():
                 "estimates_per_launch": k_est, "avg_launch_ms": k_ms,
                 "peak_derivation": "256 CUs x 128 B/clk x 2.4 GHz; see profiles/lds_gather_microbenchmark.txt",
                 "traffic": hbm, "hbm_frac_of_traffic": (hbm / k_ms / 1e6 / HBM_PEAK_GBS) if hbm else None,
-                "note": "launches of the default setting overlap on side streams, so this duration is an upper bound"}
+                "note": "launches of the default setting overlap on side streams, so this duration is an upper bound; the peak "
+                        "assumes 2.4 GHz, the chip sustains about 1.9 GHz under this kernel "
+                        "(profiles/scan_cfg4_counters.txt: LDS active in 86 % and vector ALU in 94 % of the cycles)"}
     if cfg.n_query > B and not args.batch and not args.no_whole_set:
         # The workload's whole query set in one call (outside the timed region): more queries share every list read.
         ix.set_tuning(batch=min(cfg.n_query, 65535), scan_groups=args.scan_groups)
