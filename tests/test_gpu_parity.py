@@ -666,6 +666,43 @@ def test_duplicate_vectors_are_cut_by_id():
     ix.close()
 
 
+@pytest.mark.parametrize("mode", [0, 2])
+def test_bound_from_a_sample_of_the_nearest_lists(mode):
+    """A short-list that is tiny against the visit (k' = 10 of ~30000 visited entries): the bound's sample is drawn
+    from the nearest visited lists only.  Also with the nearest lists empty, so that the walk over the lists has to
+    go on past them."""
+    wl = tiny_workload(d=32, G=64, N=60000, n_train=4000, n_query=16, c=64, m=4, m_refine=4, iters=4)
+    index, X = wl["index"], wl["X"]
+    w, kp, k = 32, 10, 5
+    ix = gpu_index_from_oracle(index)
+    ix.set_list_sharing(mode)
+    ids, dist = ix.search(queries_dev(X), w, kp, k)
+    st = ix.search_stats()
+    log("nearest-list sample", st)
+    assert st["dense_fallbacks"] == 0
+    o_ids, o_dist, traces = orc.search(X, index, w, kp, k)
+    assert np.array_equal(ids.cpu().numpy(), o_ids)
+    assert np.allclose(dist.cpu().numpy(), o_dist, rtol=REL_TOL)
+    ix.close()
+    # the same database with every query's three nearest lists emptied
+    drop = set()
+    for t in traces:
+        drop.update(int(l) for l in t.probe[:3])
+    keep = np.ones(index.N, dtype=bool)
+    for l in drop:
+        keep[index.list_offsets[l]:index.list_offsets[l + 1]] = False
+    lens = np.array([int(keep[index.list_offsets[l]:index.list_offsets[l + 1]].sum()) for l in range(64)])
+    offsets = np.concatenate([[0], np.cumsum(lens)])
+    sparse = orc.Index(index.books, offsets, index.ids[keep], index.codes[keep], index.rcodes[keep])
+    ix = gpu_index_from_oracle(sparse)
+    ix.set_list_sharing(mode)
+    ids, dist = ix.search(queries_dev(X), w, kp, k)
+    o_ids, o_dist, _ = orc.search(X, sparse, w, kp, k)
+    assert np.array_equal(ids.cpu().numpy(), o_ids)
+    assert np.allclose(dist.cpu().numpy(), o_dist, rtol=REL_TOL)
+    ix.close()
+
+
 @pytest.mark.parametrize("order", ["far_first", "near_first"])
 def test_unrepresentative_sample(order):
     """One list whose sampled prefix misrepresents it.  Far entries first: the bound drawn from the
