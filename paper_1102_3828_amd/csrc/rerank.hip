@@ -110,7 +110,10 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
         reinterpret_cast<float4*>(s_rq)[i] = reinterpret_cast<const float4*>(rq)[i];
     __syncthreads();
     const int t = threadIdx.x & 7, g = threadIdx.x >> 3;
-    const int per_q = (kprime + 127) / 128;
+    // C entries per group of eight lanes and block (slots g, g + 128, ... of a block of 128 C slots): their decode
+    // chains are independent, so C of each load are in flight per lane
+    constexpr int C = FM > 0 ? 2 : 1;
+    const int per_q = (kprime + 128 * C - 1) / (128 * C);
     const int64_t n_items = (int64_t)nq * per_q;
     // 16-byte pieces of a vector per lane (d is a multiple of 32 here, at most 128).  A run-time value on purpose: as a
     // compile-time constant the compiler issues all loads of an entry's decode up front, which measured slower
@@ -120,62 +123,71 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
     // i + 1 (id, list, code bytes: one random line from HBM per entry, the latency that bounds this kernel) is
     // being gathered, item i is decoded.  Loads return in issue order, so waiting for the oldest leaves the
     // younger ones in flight.
-    struct Pos { int q, slot, n; uint32_t pos; };
-    struct Gather { int32_t id; uint32_t list; uint32_t cb[4], rb[4]; };
+    struct Pos { int q, slot, n; uint32_t pos[C]; };   // slot: the first of the group's C slots
+    struct Gather { int32_t id[C]; uint32_t list[C]; uint32_t cb[C][4], rb[C][4]; };
     const int64_t item_end = n_items * (int64_t)(blockIdx.x + 1) / (int64_t)gridDim.x;
     auto read_pos = [&](int64_t item) -> Pos {
         Pos r;
-        r.q = 0; r.slot = 0; r.n = 0; r.pos = 0;
+        r.q = 0; r.slot = 0; r.n = 0;
+#pragma unroll
+        for (int cc = 0; cc < C; ++cc) r.pos[cc] = 0;
         if (item < item_end) {
             r.q = q_base + (int)(item / per_q);
-            r.slot = (int)(item % per_q) * 128 + g;
+            r.slot = (int)(item % per_q) * (128 * C) + g;
             r.n = short_n[r.q];
-            if (r.slot < kprime) r.pos = short_pos[(int64_t)r.q * kprime + r.slot];
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc)
+                if (r.slot + 128 * cc < kprime) r.pos[cc] = short_pos[(int64_t)r.q * kprime + r.slot + 128 * cc];
         }
         return r;
     };
     auto gather = [&](const Pos& p) -> Gather {
         Gather r;
-        r.id = -1;
-        r.list = 0;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) { r.cb[k] = 0; r.rb[k] = 0; }
-        if (FM > 0 && p.slot < p.n) {
-            // d = 128, m = 8: piece k of lane t lies in sub-quantizer 2k + t/4 of the first stage (16 dimensions each)
-            const uint8_t* e = rec + (uint64_t)p.pos * rec_stride;
-            const uint4 h = *reinterpret_cast<const uint4*>(e);
-            r.id = (int32_t)h.x;
-            r.list = h.y;
-            const uint32_t cw[2] = {h.z, h.w};
-            const uint32_t hi4 = (uint32_t)t >> 2;
+        for (int cc = 0; cc < C; ++cc) {
+            r.id[cc] = -1;
+            r.list[cc] = 0;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) r.cb[k] = (cw[k >> 1] >> (8u * (2u * (k & 1) + hi4))) & 0xffu;
-            if (FM == 8) {          // 16 dimensions per refinement sub-quantizer: the same byte pattern
-                const uint2 rw2 = *reinterpret_cast<const uint2*>(e + 16);
-                const uint32_t rw[2] = {rw2.x, rw2.y};
+            for (int k = 0; k < 4; ++k) { r.cb[cc][k] = 0; r.rb[cc][k] = 0; }
+            const bool live = p.slot + 128 * cc < p.n;   // uniform over the 8 lanes of an entry
+            if (FM > 0 && live) {
+                // d = 128, m = 8: piece k of lane t lies in sub-quantizer 2k + t/4 of the first stage (16 dimensions each)
+                const uint8_t* e = rec + (uint64_t)p.pos[cc] * rec_stride;
+                const uint4 h = *reinterpret_cast<const uint4*>(e);
+                r.id[cc] = (int32_t)h.x;
+                r.list[cc] = h.y;
+                const uint32_t cw[2] = {h.z, h.w};
+                const uint32_t hi4 = (uint32_t)t >> 2;
 #pragma unroll
-                for (int k = 0; k < 4; ++k) r.rb[k] = (rw[k >> 1] >> (8u * (2u * (k & 1) + hi4))) & 0xffu;
-            } else if (FM == 16) {  // 8 dimensions each: byte 4k + t/2
-                const uint4 rw4 = *reinterpret_cast<const uint4*>(e + 16);
-                const uint32_t rw[4] = {rw4.x, rw4.y, rw4.z, rw4.w};
+                for (int k = 0; k < 4; ++k) r.cb[cc][k] = (cw[k >> 1] >> (8u * (2u * (k & 1) + hi4))) & 0xffu;
+                if (FM == 8) {          // 16 dimensions per refinement sub-quantizer: the same byte pattern
+                    const uint2 rw2 = *reinterpret_cast<const uint2*>(e + 16);
+                    const uint32_t rw[2] = {rw2.x, rw2.y};
 #pragma unroll
-                for (int k = 0; k < 4; ++k) r.rb[k] = (rw[k] >> (8u * ((uint32_t)t >> 1))) & 0xffu;
-            } else {                // 4 dimensions each: byte 8k + t
-                const uint4 ra = *reinterpret_cast<const uint4*>(e + 16), rb4 = *reinterpret_cast<const uint4*>(e + 32);
-                const uint32_t rw[8] = {ra.x, ra.y, ra.z, ra.w, rb4.x, rb4.y, rb4.z, rb4.w};
+                    for (int k = 0; k < 4; ++k) r.rb[cc][k] = (rw[k >> 1] >> (8u * (2u * (k & 1) + hi4))) & 0xffu;
+                } else if (FM == 16) {  // 8 dimensions each: byte 4k + t/2
+                    const uint4 rw4 = *reinterpret_cast<const uint4*>(e + 16);
+                    const uint32_t rw[4] = {rw4.x, rw4.y, rw4.z, rw4.w};
 #pragma unroll
-                for (int k = 0; k < 4; ++k) r.rb[k] = ((hi4 ? rw[2 * k + 1] : rw[2 * k]) >> (8u * ((uint32_t)t & 3u))) & 0xffu;
-            }
-        } else if (p.slot < p.n) {   // uniform over the 8 lanes of an entry
-            const uint8_t* e = rec + (uint64_t)p.pos * rec_stride;
-            r.id = *reinterpret_cast<const int32_t*>(e);
-            r.list = *reinterpret_cast<const uint32_t*>(e + 4);
-            const uint8_t* code = e + 8;
-            const uint8_t* rcode = e + 8 + m;
+                    for (int k = 0; k < 4; ++k) r.rb[cc][k] = (rw[k] >> (8u * ((uint32_t)t >> 1))) & 0xffu;
+                } else {                // 4 dimensions each: byte 8k + t
+                    const uint4 ra = *reinterpret_cast<const uint4*>(e + 16), rb4 = *reinterpret_cast<const uint4*>(e + 32);
+                    const uint32_t rw[8] = {ra.x, ra.y, ra.z, ra.w, rb4.x, rb4.y, rb4.z, rb4.w};
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int e = 4 * t + 32 * k;
-                if (k < nit) { r.cb[k] = code[e / dsub]; r.rb[k] = rcode[e / dsub_r]; }
+                    for (int k = 0; k < 4; ++k)
+                        r.rb[cc][k] = ((hi4 ? rw[2 * k + 1] : rw[2 * k]) >> (8u * ((uint32_t)t & 3u))) & 0xffu;
+                }
+            } else if (live) {
+                const uint8_t* e = rec + (uint64_t)p.pos[cc] * rec_stride;
+                r.id[cc] = *reinterpret_cast<const int32_t*>(e);
+                r.list[cc] = *reinterpret_cast<const uint32_t*>(e + 4);
+                const uint8_t* code = e + 8;
+                const uint8_t* rcode = e + 8 + m;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int e2 = 4 * t + 32 * k;
+                    if (k < nit) { r.cb[cc][k] = code[e2 / dsub]; r.rb[cc][k] = rcode[e2 / dsub_r]; }
+                }
             }
         }
         return r;
@@ -187,6 +199,8 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
     int xq = -1;
 #pragma unroll
     for (int k = 0; k < 4; ++k) xr[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    // sub-vector widths: compile-time for the common shape (shifts instead of multiplications)
+    const int ds = FM > 0 ? 16 : dsub, dr = FM > 0 ? 128 / (FM > 0 ? FM : 1) : dsub_r;
     for (; item < item_end; ++item) {
         const Pos p2 = read_pos(item + 2);
         const Gather g1 = gather(p1);
@@ -197,41 +211,57 @@ __global__ __launch_bounds__(1024) void rerank_lds_kernel(const float* __restric
             for (int k = 0; k < 4; ++k)
                 if (k < nit) xr[k] = *reinterpret_cast<const float4*>(x + 4 * t + 32 * k);
         }
-        const bool live = p0.slot < p0.n;
-        float acc = 0.f;
-        if (live) {
-            const float* cl = coarse + (int64_t)g0.list * d;
+        float acc[C];
+        bool live[C];
+        const float* cl[C];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                if (k < nit) {
-                    const int e = 4 * t + 32 * k;
-                    // sub-vector widths: compile-time for the common shape (shifts instead of multiplications)
-                    const int ds = FM > 0 ? 16 : dsub, dr = FM > 0 ? 128 / (FM > 0 ? FM : 1) : dsub_r;
-                    const int j = e / ds, jr = e / dr;
-                    float4 y = *reinterpret_cast<const float4*>(cl + e);
-                    const float4 pv = *reinterpret_cast<const float4*>(pq + (j * IVFR_KS + (int)g0.cb[k]) * ds + (e - j * ds));
-                    y.x += pv.x; y.y += pv.y; y.z += pv.z; y.w += pv.w;
-                    const float4 rv = *reinterpret_cast<const float4*>(s_rq + (jr * IVFR_KS + (int)g0.rb[k]) * dr + (e - jr * dr));
-                    y.x += rv.x; y.y += rv.y; y.z += rv.z; y.w += rv.w;
-                    const float4 xv = xr[k];
-                    const float a = xv.x - y.x, b = xv.y - y.y, cc = xv.z - y.z, dd = xv.w - y.w;
-                    acc = fmaf(a, a, acc); acc = fmaf(b, b, acc); acc = fmaf(cc, cc, acc); acc = fmaf(dd, dd, acc);
+        for (int cc = 0; cc < C; ++cc) {
+            acc[cc] = 0.f;
+            live[cc] = p0.slot + 128 * cc < p0.n;
+            cl[cc] = coarse + (int64_t)g0.list[cc] * d;   // list 0 for an entry that is not there: a valid row, unused
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (k < nit) {
+                const int e = 4 * t + 32 * k;
+                const int j = e / ds, jr = e / dr;
+                float4 y[C], pv[C], rv[C];
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) {
+                    y[cc] = *reinterpret_cast<const float4*>(cl[cc] + e);
+                    pv[cc] = *reinterpret_cast<const float4*>(pq + (j * IVFR_KS + (int)g0.cb[cc][k]) * ds + (e - j * ds));
+                    rv[cc] = *reinterpret_cast<const float4*>(s_rq + (jr * IVFR_KS + (int)g0.rb[cc][k]) * dr + (e - jr * dr));
+                }
+                const float4 xv = xr[k];
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) {
+                    float4 yy = y[cc];
+                    yy.x += pv[cc].x; yy.y += pv[cc].y; yy.z += pv[cc].z; yy.w += pv[cc].w;
+                    yy.x += rv[cc].x; yy.y += rv[cc].y; yy.z += rv[cc].z; yy.w += rv[cc].w;
+                    const float a = xv.x - yy.x, b = xv.y - yy.y, c2 = xv.z - yy.z, dd = xv.w - yy.w;
+                    acc[cc] = fmaf(a, a, acc[cc]); acc[cc] = fmaf(b, b, acc[cc]);
+                    acc[cc] = fmaf(c2, c2, acc[cc]); acc[cc] = fmaf(dd, dd, acc[cc]);
                 }
             }
         }
-        acc += __shfl_xor(acc, 4, 64);
-        acc += __shfl_xor(acc, 2, 64);
-        acc += __shfl_xor(acc, 1, 64);
-        if (t == 0 && p0.slot < kprime) {
-            const int64_t o = (int64_t)p0.q * kprime + p0.slot;
-            if (live) {
-                keys[o] = ((uint64_t)__float_as_uint(acc) << 32) | (uint32_t)g0.id;
-                if (refined_out) refined_out[o] = acc;
-                if (ids_out) ids_out[o] = g0.id;
-            } else {
-                keys[o] = ~0ull;
-                if (refined_out) refined_out[o] = INFINITY;
-                if (ids_out) ids_out[o] = -1;
+#pragma unroll
+        for (int cc = 0; cc < C; ++cc) {
+            float a = acc[cc];
+            a += __shfl_xor(a, 4, 64);
+            a += __shfl_xor(a, 2, 64);
+            a += __shfl_xor(a, 1, 64);
+            const int slot = p0.slot + 128 * cc;
+            if (t == 0 && slot < kprime) {
+                const int64_t o = (int64_t)p0.q * kprime + slot;
+                if (live[cc]) {
+                    keys[o] = ((uint64_t)__float_as_uint(a) << 32) | (uint32_t)g0.id[cc];
+                    if (refined_out) refined_out[o] = a;
+                    if (ids_out) ids_out[o] = g0.id[cc];
+                } else {
+                    keys[o] = ~0ull;
+                    if (refined_out) refined_out[o] = INFINITY;
+                    if (ids_out) ids_out[o] = -1;
+                }
             }
         }
         p0 = p1; p1 = p2; g0 = g1;
@@ -258,7 +288,7 @@ int ivfr_launch_rerank(const ivfr_index* ix, const float* queries, int q_base, i
     const bool vec0 = (ix->dsub % 4 == 0) && (ix->p.m_refine == 0 || ix->dsub_r % 4 == 0) && ((ix->p.d / 8) % 4 == 0);
     const size_t rq_bytes = (size_t)IVFR_KS * ix->p.d * sizeof(float);
     if (vec0 && ix->p.m_refine > 0 && rq_bytes <= 128 * 1024 && (int64_t)nq * kprime >= (int64_t)ix->n_cu * 1024) {
-        const int64_t n_items = (int64_t)nq * ((kprime + 127) / 128);
+        const int64_t n_items = (int64_t)nq * ((kprime + 127) / 128);   // an upper bound of the kernel's own count
         const int groups = (int)std::min<int64_t>(n_items, ix->n_cu);
 #define IVFR_RERANK_LDS(FM)                                                                                       \
     hipLaunchKernelGGL(rerank_lds_kernel<FM>, dim3(groups), dim3(1024), rq_bytes, st, queries, ix->p.d, ix->p.c,      \
