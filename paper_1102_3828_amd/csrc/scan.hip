@@ -1370,9 +1370,9 @@ typedef short short8 __attribute__((ext_vector_type(8)));
 // Sample pass: the first len_s[p] entries of every pair, all estimates kept (the values only), each at its own place
 // in the query's buffer (the plan's prefix sums give the place, no counter is touched).  The prefixes are
 // short (a few hundred entries, a few chunks of IVFR_SAMPLE_CHUNK for the longest lists) and there
-// are tens of thousands of pairs, so the work is table loads and latency: one wavefront per chunk,
-// each with its own LDS slice for the table and no workgroup barrier, keeps many independent
-// chunks in flight per compute unit.
+// are tens of thousands of pairs, so the work is table loads and latency: a small workgroup (two wavefronts
+// at m <= 16) per chunk shares one table, so that a compute unit keeps sixteen independent chunks and all of its
+// 32 wavefronts in flight, and a chunk is half as many steps long as with one wavefront.
 // ------------------------------------------------------------------------------------------
 template <int M, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void adc_sample_kernel(const uint8_t* __restrict__ codes,
@@ -1384,29 +1384,28 @@ __global__ __launch_bounds__(64 * WAVES) void adc_sample_kernel(const uint8_t* _
                                                                 const uint32_t* __restrict__ n_items_dev,
                                                                 const uint32_t* __restrict__ soff, int w,
                                                                 uint2* __restrict__ cand, CandLayout lay) {
-    extern __shared__ float s_lut[];   // WAVES wavefronts x M * 256 floats
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    extern __shared__ float s_lut[];   // one table of M * 256 floats, shared by the workgroup's WAVES wavefronts
+    const int tid = threadIdx.x;
     const uint32_t n_items = *n_items_dev;
-    float* T = s_lut + wave * M * IVFR_KS;
-    // every wavefront walks over the chunks on its own (item is uniform over the wavefront)
-    for (uint32_t item = blockIdx.x * WAVES + wave; item < n_items; item += gridDim.x * WAVES) {
+    float* T = s_lut;
+    // the workgroup walks over the chunks (item is uniform over it: every barrier is reached by all its threads)
+    for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
         const uint32_t p = items[item];
         const uint32_t first = (item - chunk_pre[p]) * IVFR_SAMPLE_CHUNK;
         const uint32_t n = len_s[p];
         const uint32_t last = n - first < IVFR_SAMPLE_CHUNK ? n : first + IVFR_SAMPLE_CHUNK;   // exclusive
+        __syncthreads();   // the previous chunk's table is no longer read
         {
             const PairTable pt = ts.pair((int64_t)p);
             float4* dst = reinterpret_cast<float4*>(T);
-#pragma unroll
-            for (int i = 0; i < M; ++i) dst[i * 64 + lane] = pt.get4(4 * (i * 64 + lane));
+            for (int i = tid; i < M * IVFR_KS / 4; i += 64 * WAVES) dst[i] = pt.get4(4 * i);
         }
-        // the wavefront's own writes are visible to its later reads, and its reads of the previous chunk's table
-        // are done before these writes: LDS operations of one wavefront complete in order
+        __syncthreads();
         const uint32_t start = pair_start[p];
         const int q = (int)(p / (uint32_t)w);
         // bare estimates: the buffer (records of 8 bytes) holds at least the query's whole sample
         float* out = reinterpret_cast<float*>(cand + lay.base(q)) + soff[p];
-        for (uint32_t e = first + 2u * lane; e < last; e += 128u) {
+        for (uint32_t e = first + 2u * tid; e < last; e += 128u * WAVES) {
             uint32_t w0[M / 4], w1[M / 4];
             load_code_pair<M>(codes, start, e, true, last, w0, w1);
             out[e] = adc_sum<M>(T, w0);
@@ -1416,17 +1415,17 @@ __global__ __launch_bounds__(64 * WAVES) void adc_sample_kernel(const uint8_t* _
 }
 
 template <int M, int WAVES>
-static size_t sample_lds_bytes() { return (size_t)WAVES * M * IVFR_KS * sizeof(float); }
+static size_t sample_lds_bytes() { return (size_t)M * IVFR_KS * sizeof(float); }
 
 template <int M, int WAVES>
 static int launch_sample_m(const ivfr_index* ix, const TableSrc& ts, const uint32_t* pair_start, const uint32_t* len_s,
                            const uint32_t* chunk_pre, const uint32_t* items, const uint32_t* n_items, size_t max_items,
                            const uint32_t* soff, int w, uint2* cand, CandLayout lay, hipStream_t st) {
     const size_t lds = sample_lds_bytes<M, WAVES>();
-    // four times the workgroups that the compute units' LDS holds at once (measured best against one, two and one
-    // workgroup per chunk), or one wavefront per chunk when there are fewer
-    const size_t per_cu = std::max<size_t>(1, (size_t)(160 * 1024) / lds);
-    const size_t grid = std::max<size_t>(1, std::min((max_items + WAVES - 1) / WAVES, (size_t)ix->n_cu * per_cu * 4));
+    // four times the workgroups that a compute unit holds at once (its LDS or its 32 wavefronts), or one workgroup per
+    // chunk when there are fewer
+    const size_t per_cu = std::max<size_t>(1, std::min<size_t>((size_t)(160 * 1024) / lds, (size_t)32 / WAVES));
+    const size_t grid = std::max<size_t>(1, std::min(max_items, (size_t)ix->n_cu * per_cu * 4));
     hipLaunchKernelGGL((adc_sample_kernel<M, WAVES>), dim3((unsigned)grid), dim3(64 * WAVES), lds, st, ix->codes, ts,
                        pair_start, len_s, chunk_pre, items, n_items, soff, w, cand, lay);
     IVFR_HIP(hipGetLastError());
@@ -1439,11 +1438,11 @@ int ivfr_launch_sample_scan(const ivfr_index* ix, const TableSrc& ts, const uint
     if (max_items == 0) return IVFR_OK;
 #define IVFR_SAMPLE_ARGS ix, ts, pair_start, len_s, chunk_pre, items, n_items, max_items, soff, w, cand, lay, st
     switch (ix->p.m) {
-        case 4: return launch_sample_m<4, 4>(IVFR_SAMPLE_ARGS);
-        case 8: return launch_sample_m<8, 4>(IVFR_SAMPLE_ARGS);
-        case 16: return launch_sample_m<16, 4>(IVFR_SAMPLE_ARGS);
+        case 4: return launch_sample_m<4, 2>(IVFR_SAMPLE_ARGS);
+        case 8: return launch_sample_m<8, 2>(IVFR_SAMPLE_ARGS);
+        case 16: return launch_sample_m<16, 2>(IVFR_SAMPLE_ARGS);
         case 32: return launch_sample_m<32, 4>(IVFR_SAMPLE_ARGS);
-        case 64: return launch_sample_m<64, 2>(IVFR_SAMPLE_ARGS);
+        case 64: return launch_sample_m<64, 4>(IVFR_SAMPLE_ARGS);
         default:
             ivfr_set_error("list scan supports m in {4, 8, 16, 32, 64}; got %d", ix->p.m);
             return IVFR_ERR_INVALID_ARG;
@@ -2064,11 +2063,11 @@ int ivfr_scan_init() {
     IVFR_TRY(allow_lds(adc_scan_shared8h_kernel<4>, shared8h_lds_bytes<4>()));
     IVFR_TRY(allow_lds(adc_scan_shared8h_kernel<8>, shared8h_lds_bytes<8>()));
     IVFR_TRY(allow_lds(adc_scan_shared8h_kernel<16>, shared8h_lds_bytes<16>()));
-    IVFR_TRY(allow_lds(adc_sample_kernel<4, 4>, sample_lds_bytes<4, 4>()));
-    IVFR_TRY(allow_lds(adc_sample_kernel<8, 4>, sample_lds_bytes<8, 4>()));
-    IVFR_TRY(allow_lds(adc_sample_kernel<16, 4>, sample_lds_bytes<16, 4>()));
+    IVFR_TRY(allow_lds(adc_sample_kernel<4, 2>, sample_lds_bytes<4, 2>()));
+    IVFR_TRY(allow_lds(adc_sample_kernel<8, 2>, sample_lds_bytes<8, 2>()));
+    IVFR_TRY(allow_lds(adc_sample_kernel<16, 2>, sample_lds_bytes<16, 2>()));
     IVFR_TRY(allow_lds(adc_sample_kernel<32, 4>, sample_lds_bytes<32, 4>()));
-    IVFR_TRY(allow_lds(adc_sample_kernel<64, 2>, sample_lds_bytes<64, 2>()));
+    IVFR_TRY(allow_lds(adc_sample_kernel<64, 4>, sample_lds_bytes<64, 4>()));
     IVFR_TRY(allow_lds(adc_scan_mfma64_kernel<4, 8>, mfma64_lds_bytes<4, 8>()));
     IVFR_TRY(allow_lds(adc_scan_mfma64_kernel<4, 16>, mfma64_lds_bytes<4, 16>()));
     IVFR_TRY(allow_lds(adc_scan_mfma64_kernel<4, 32>, mfma64_lds_bytes<4, 32>()));
